@@ -1,0 +1,389 @@
+"""Plain CPU CKKS for the encrypted ternary matmul path -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import
+this package; the GPU library never does and shares no code with it.
+
+What is computed, and from where:
+  * column-wise SIMD encoding, Enc, Dec, Add, Rot: the paper's Preliminaries
+    (Homomorphic Encryption and RNS-CKKS; SIMD Encoding; Rotation);
+  * the multiplication-free plaintext-ciphertext product: Alg. 1 (PCMM) and the
+    worked toy example before it, which fixes the index order Y = X W;
+  * everything the paper leaves to its CKKS library (transform, hybrid key
+    switching, rescale): the standard published definitions, in the order
+    decompose -> ModUp -> automorphism -> key inner product -> ModDown.
+
+Steps are taken one at a time, each a call into the plain C routines of
+orc_kernels.c or a numpy expression; no fusion, no lazy reduction.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from .params import Params
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+_u64p = ctypes.POINTER(ctypes.c_uint64)
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        path = os.path.join(_HERE, "liborc.so")
+        if not os.path.exists(path):
+            from .build import build
+            build()
+        _LIB = ctypes.CDLL(path)
+        _LIB.orc_powmod.restype = ctypes.c_uint64
+        _LIB.orc_powmod.argtypes = [ctypes.c_uint64] * 3
+    return _LIB
+
+
+def _p(a):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _u64(x):
+    return np.ascontiguousarray(np.array(x, dtype=np.uint64))
+
+
+GK_STREAM_TAG = 2 << 56
+PK_STREAM = 1
+
+
+class Ciphertext:
+    """(c0, c1), each [l1][N] uint64 coefficient-form residues in [0, q_i)."""
+
+    def __init__(self, c0, c1, scale):
+        self.c0, self.c1, self.scale = c0, c1, scale
+
+    @property
+    def l1(self):
+        return self.c0.shape[0]
+
+    def limbs(self):
+        return np.stack([self.c0, self.c1])
+
+
+class Oracle:
+    def __init__(self, params: Params):
+        self.pr = params
+        self.lib = _lib()
+        pr = params
+        self.N = pr.N
+        self.n = pr.n_slots
+        self.ext_primes_full = pr.q + pr.p
+        # slot j <-> root exponent 5^j mod 2N
+        e = np.empty(self.n, dtype=np.int64)
+        x = 1
+        for j in range(self.n):
+            e[j] = x
+            x = x * 5 % (2 * self.N)
+        self.rot_exp = e
+
+    # ------------------------------------------------------------------ ring
+    def _primes_psi(self, primes):
+        return _u64(primes), _u64([self.pr.psi[m] for m in primes])
+
+    def ntt(self, a, primes, inverse=False):
+        """a: [len(primes)][N] -> transformed copy (negacyclic, natural order)."""
+        a = np.ascontiguousarray(a, dtype=np.uint64).copy()
+        q, psi = self._primes_psi(primes)
+        self.lib.orc_ntt(_p(a), len(primes), self.pr.log_n, _p(q), _p(psi), int(inverse))
+        return a
+
+    def polymul(self, a, b, primes):
+        """Product in prod_i Z_{q_i}[X]/(X^N+1), limb-wise."""
+        fa, fb = self.ntt(a, primes), self.ntt(b, primes)
+        q = _u64(primes)
+        c = np.empty_like(fa)
+        self.lib.orc_pointwise_mul(_p(c), _p(fa), _p(fb), len(primes), self.N, _p(q))
+        return self.ntt(c, primes, inverse=True)
+
+    def polymul_naive(self, a, b, q):
+        a = np.ascontiguousarray(a, dtype=np.uint64)
+        b = np.ascontiguousarray(b, dtype=np.uint64)
+        c = np.empty_like(a)
+        self.lib.orc_negacyclic_naive(_p(c), _p(a), _p(b), len(a), ctypes.c_uint64(q))
+        return c
+
+    def add(self, a, b, primes):
+        c = np.empty_like(a)
+        self.lib.orc_add(_p(c), _p(np.ascontiguousarray(a)), _p(np.ascontiguousarray(b)), len(primes), self.N, _p(_u64(primes)))
+        return c
+
+    def sub(self, a, b, primes):
+        c = np.empty_like(a)
+        self.lib.orc_sub(_p(c), _p(np.ascontiguousarray(a)), _p(np.ascontiguousarray(b)), len(primes), self.N, _p(_u64(primes)))
+        return c
+
+    def mul_scalar(self, a, scalars, primes):
+        c = np.empty_like(a)
+        self.lib.orc_mul_scalar(_p(c), _p(np.ascontiguousarray(a)), _p(_u64(scalars)), len(primes), self.N, _p(_u64(primes)))
+        return c
+
+    def automorphism(self, a, g, primes):
+        out = np.empty_like(a)
+        self.lib.orc_automorphism(_p(out), _p(np.ascontiguousarray(a)), len(primes), self.N, ctypes.c_uint64(g), _p(_u64(primes)))
+        return out
+
+    def small_to_rns(self, v, primes):
+        v = np.ascontiguousarray(v, dtype=np.int8)
+        out = np.empty((len(primes), self.N), dtype=np.uint64)
+        self.lib.orc_small_to_rns(_p(out), _p(v), len(primes), self.N, _p(_u64(primes)))
+        return out
+
+    def i64_to_rns(self, v, primes):
+        v = np.ascontiguousarray(v, dtype=np.int64)
+        out = np.empty((len(primes), self.N), dtype=np.uint64)
+        self.lib.orc_i64_to_rns(_p(out), _p(v), len(primes), self.N, _p(_u64(primes)))
+        return out
+
+    def uniform(self, seed, stream, prime_ids, primes):
+        out = np.empty((len(primes), self.N), dtype=np.uint64)
+        for r, (pid, q) in enumerate(zip(prime_ids, primes)):
+            self.lib.orc_uniform(_p(out[r]), self.N, ctypes.c_uint64(seed), ctypes.c_uint64(stream),
+                                 ctypes.c_uint64(pid), ctypes.c_uint64(q))
+        return out
+
+    # -------------------------------------------------------------- encoding
+    def encode_coeffs(self, z):
+        """pi: real slot vector (zero-padded to N/2) -> signed integer coefficients.
+        m_k = round((2 Delta/N) Re sum_j z_j conj(zeta_j^k)), zeta_j = exp(i pi 5^j / N),
+        rounding half away from zero.  Evaluated with one length-2N FFT."""
+        N = self.N
+        zz = np.zeros(self.n, dtype=np.float64)
+        zz[: len(z)] = np.asarray(z, dtype=np.float64)
+        A = np.zeros(2 * N, dtype=np.complex128)
+        A[self.rot_exp] = zz
+        A[2 * N - self.rot_exp] = zz  # conjugate positions (real input)
+        m = np.fft.fft(A)[:N].real * (self.pr.scale / N)
+        return (np.sign(m) * np.floor(np.abs(m) + 0.5)).astype(np.int64)
+
+    def encode_coeffs_direct(self, z):
+        """Same map by the defining O(N * N/2) sum (small N only)."""
+        N = self.N
+        zz = np.zeros(self.n, dtype=np.float64)
+        zz[: len(z)] = np.asarray(z, dtype=np.float64)
+        k = np.arange(N, dtype=np.float64)[:, None]
+        ang = np.pi * self.rot_exp[None, :].astype(np.float64) * k / N
+        m = (2.0 * self.pr.scale / N) * (np.cos(ang) @ zz)
+        return (np.sign(m) * np.floor(np.abs(m) + 0.5)).astype(np.int64)
+
+    def decode_coeffs(self, m, scale=None):
+        """z_j = m(zeta_j) / Delta for real-valued coefficient vector m (float64)."""
+        N = self.N
+        B = np.zeros(2 * N, dtype=np.complex128)
+        B[:N] = m
+        F = np.fft.ifft(B) * (2 * N)
+        return F[self.rot_exp] / (scale if scale is not None else self.pr.scale)
+
+    def encode(self, z, l1):
+        return self.i64_to_rns(self.encode_coeffs(z), self.pr.q[:l1])
+
+    # ------------------------------------------------------------------ keys
+    def keygen(self, s, e, seed):
+        """KeyGen (paper, Preliminaries).  s: ternary secret, e: rounded-Gaussian
+        error, both int8[N] supplied by the caller; a is the counter-based uniform
+        stream PK_STREAM.  pk = (-a s + e, a) over Q_L."""
+        pr = self.pr
+        sk = np.ascontiguousarray(s, dtype=np.int8)
+        a = self.uniform(seed, PK_STREAM, range(pr.L), pr.q)
+        s_rns = self.small_to_rns(sk, pr.q)
+        e_rns = self.small_to_rns(e, pr.q)
+        b = self.add(self.sub(np.zeros_like(a), self.polymul(a, s_rns, pr.q), pr.q), e_rns, pr.q)
+        return sk, (b, a)
+
+    def galois_keygen(self, sk, step, e, seed):
+        """Key for Rot(.; step): for every digit j of the full chain,
+        (b_j, a_j) over Q_L * P with b_j = -a_j s + e_j + [P]_{q_i} phi_g(s) on the
+        limbs i of digit j only.  e: int8[beta][N]."""
+        pr = self.pr
+        g = pr.galois_element(step)
+        ext = pr.q + pr.p
+        ids = list(range(pr.L + pr.K))
+        s_ext = self.small_to_rns(sk, ext)
+        s_g = self.automorphism(s_ext, g, ext)
+        beta = pr.beta(pr.L)
+        bs, as_ = [], []
+        for j in range(beta):
+            a = self.uniform(seed, GK_STREAM_TAG | (g << 8) | j, ids, ext)
+            e_rns = self.small_to_rns(e[j], ext)
+            b = self.add(self.sub(np.zeros_like(a), self.polymul(a, s_ext, ext), ext), e_rns, ext)
+            factor = [(pr.P % ext[i]) if i in pr.digit_limbs(j, pr.L) else 0 for i in ids]
+            b = self.add(b, self.mul_scalar(s_g, factor, ext), ext)
+            bs.append(b)
+            as_.append(a)
+        return {"g": g, "step": step, "b": np.stack(bs), "a": np.stack(as_), "ntt": {}}
+
+    # ------------------------------------------------------- encrypt/decrypt
+    def encrypt(self, pt_rns, pk, v, e0, e1):
+        """Enc_pk (paper, Preliminaries): ct = v pk + (m + e0, e1) at the level of pt."""
+        l1 = pt_rns.shape[0]
+        pr = self.pr
+        q = pr.q[:l1]
+        v_rns = self.small_to_rns(v, q)
+        c0 = self.add(self.add(self.polymul(v_rns, pk[0][:l1], q), pt_rns, q), self.small_to_rns(e0, q), q)
+        c1 = self.add(self.polymul(v_rns, pk[1][:l1], q), self.small_to_rns(e1, q), q)
+        return Ciphertext(c0, c1, pr.scale)
+
+    def decrypt_coeffs(self, ct, sk):
+        """c0 + c1 s, CRT of limbs 0 and 1, centred; float64 coefficients."""
+        pr = self.pr
+        l1 = ct.l1
+        use = min(l1, 2)
+        q = pr.q[:use]
+        s_rns = self.small_to_rns(sk, q)
+        m = self.add(ct.c0[:use], self.polymul(np.ascontiguousarray(ct.c1[:use]), s_rns, q), q)
+        out = np.empty(self.N, dtype=np.float64)
+        if use == 2:
+            self.lib.orc_crt2_center(_p(out), _p(np.ascontiguousarray(m[0])), _p(np.ascontiguousarray(m[1])),
+                                     ctypes.c_uint64(q[0]), ctypes.c_uint64(q[1]), self.N)
+        else:
+            self.lib.orc_center1(_p(out), _p(np.ascontiguousarray(m[0])), ctypes.c_uint64(q[0]), self.N)
+        return out
+
+    def decrypt(self, ct, sk):
+        """Dec_sk followed by decoding; returns the real parts of all N/2 slots."""
+        return self.decode_coeffs(self.decrypt_coeffs(ct, sk), ct.scale).real
+
+    # ---------------------------------------------------------- key switching
+    def bconv(self, src, qs, inv, tgt, hat):
+        out = np.empty((len(tgt), self.N), dtype=np.uint64)
+        self.lib.orc_bconv(_p(out), _p(np.ascontiguousarray(src)), len(qs), len(tgt), self.N, _p(_u64(qs)), _p(_u64(inv)),
+                           _p(_u64(hat)), _p(_u64(tgt)))
+        return out
+
+    def mod_up(self, c1):
+        """Digit decomposition + ModUp: [l1][N] -> [beta][l1+K][N], coefficient form.
+        Limbs inside a digit are copied; every other limb of Q_l and all of P gets
+        the fast basis conversion of the digit (no overflow correction)."""
+        pr = self.pr
+        l1 = c1.shape[0]
+        out = np.empty((pr.beta(l1), l1 + pr.K, self.N), dtype=np.uint64)
+        for j in range(pr.beta(l1)):
+            src, qs, inv, tgt_idx, tgt, hat = pr.modup_constants(j, l1)
+            out[j, src] = c1[src]
+            out[j, tgt_idx] = self.bconv(c1[src], qs, inv, tgt, hat)
+        return out
+
+    def mod_down(self, u, l1):
+        """[l1+K][N] -> [l1][N]: (u - BConv_{P->Q}([u]_P)) * P^{-1} mod q_i, no rounding offset."""
+        pr = self.pr
+        inv, tgt, hat, p_inv = pr.moddown_constants(l1)
+        r = self.bconv(u[l1:], pr.p, inv, tgt, hat)
+        return self.mul_scalar(self.sub(np.ascontiguousarray(u[:l1]), r, tgt), p_inv, tgt)
+
+    def _key_at_level(self, gk, l1):
+        pr = self.pr
+        if l1 not in gk["ntt"]:
+            sel = list(range(l1)) + list(range(pr.L, pr.L + pr.K))
+            primes = [(pr.q + pr.p)[i] for i in sel]
+            beta = pr.beta(l1)
+            kb = np.stack([self.ntt(gk["b"][j][sel], primes) for j in range(beta)])
+            ka = np.stack([self.ntt(gk["a"][j][sel], primes) for j in range(beta)])
+            gk["ntt"] = {l1: (primes, kb, ka)}
+        return gk["ntt"][l1]
+
+    def rotate_from_digits(self, c0, digits, gk, scale):
+        """Steps c-f of the rotation: automorphism of every raised digit and of c0,
+        key inner product over the extended basis, ModDown, add phi_g(c0)."""
+        pr = self.pr
+        l1 = c0.shape[0]
+        g = gk["g"]
+        primes, kb, ka = self._key_at_level(gk, l1)
+        qv = _u64(primes)
+        u0 = np.zeros((l1 + pr.K, self.N), dtype=np.uint64)
+        u1 = np.zeros_like(u0)
+        for j in range(digits.shape[0]):
+            dg = self.ntt(self.automorphism(digits[j], g, primes), primes)
+            self.lib.orc_pointwise_mac(_p(u0), _p(dg), _p(np.ascontiguousarray(kb[j])), len(primes), self.N, _p(qv))
+            self.lib.orc_pointwise_mac(_p(u1), _p(dg), _p(np.ascontiguousarray(ka[j])), len(primes), self.N, _p(qv))
+        u0 = self.ntt(u0, primes, inverse=True)
+        u1 = self.ntt(u1, primes, inverse=True)
+        q = pr.q[:l1]
+        out0 = self.add(self.automorphism(np.ascontiguousarray(c0), g, q), self.mod_down(u0, l1), q)
+        out1 = self.mod_down(u1, l1)
+        return Ciphertext(out0, out1, scale)
+
+    def rotate(self, ct, gk):
+        """Rot(ct; k) for the step the key was generated for (paper, Rotation)."""
+        return self.rotate_from_digits(ct.c0, self.mod_up(ct.c1), gk, ct.scale)
+
+    # ------------------------------------------------------------------ PCMM
+    @staticmethod
+    def placement_block(i, c_tot, placement):
+        return 0 if placement == "zero" else i % c_tot
+
+    def plan(self, W, c_tot, placement):
+        """For output i: list of (packed input G, rotation amount rho, sign) with
+        virtual column j = G*c_tot + b needed at rho = (b - p_i) mod c_tot."""
+        d, m = W.shape
+        plan = []
+        for i in range(m):
+            p_i = self.placement_block(i, c_tot, placement)
+            terms = []
+            for j in range(d):
+                w = int(W[j, i])
+                if w:
+                    terms.append((j // c_tot, (j % c_tot - p_i) % c_tot, w))
+            plan.append(terms)
+        return plan
+
+    def accumulate(self, terms, l1, scale):
+        """Alg. 1 for one output: y starts as the all-zero ciphertext; add the
+        operand where the weight is +1, subtract where it is -1, skip zeros.
+        terms: list of (Ciphertext, sign)."""
+        q = _u64(self.pr.q[:l1])
+        outs = []
+        for poly in (0, 1):
+            y = np.empty((l1, self.N), dtype=np.uint64)
+            keep = [np.ascontiguousarray(t.c0 if poly == 0 else t.c1) for t, _ in terms]
+            ptrs = (ctypes.c_void_p * max(1, len(keep)))(*[a.ctypes.data for a in keep])
+            signs = np.array([sg for _, sg in terms], dtype=np.int8)
+            self.lib.orc_signed_accumulate(_p(y), ptrs, _p(np.ascontiguousarray(signs)), len(keep), l1, self.N, _p(q))
+            outs.append(y)
+        return Ciphertext(outs[0], outs[1], scale)
+
+    def ternary_matmul(self, cts, s, d, W, placement, gks):
+        """Y = X W on ciphertexts (Alg. 1).  cts: packed inputs, ciphertext G
+        holding column G*c_tot+b in slot block b; gks: {rho: key for step rho*s}.
+        Unpacks by rotations into column-aligned operands, then add/sub only."""
+        c_tot = self.n // s
+        W = np.asarray(W)
+        assert W.shape[0] == d and len(cts) == -(-d // c_tot)
+        plan = self.plan(W, c_tot, placement)
+        need = sorted({(G, rho) for terms in plan for (G, rho, _) in terms})
+        digits = {}
+        virt = {}
+        for G, rho in need:
+            if rho == 0:
+                virt[(G, rho)] = cts[G]
+                continue
+            if G not in digits:
+                digits[G] = self.mod_up(cts[G].c1)
+            virt[(G, rho)] = self.rotate_from_digits(cts[G].c0, digits[G], gks[rho], cts[G].scale)
+        l1, scale = cts[0].l1, cts[0].scale
+        return [self.accumulate([(virt[(G, rho)], w) for (G, rho, w) in terms], l1, scale) for terms in plan]
+
+    # --------------------------------------------------------------- rescale
+    def mul_scalar_rescale(self, ct, kappa):
+        """c <- c * round(kappa q_l) (negative constants as q_i - |.|), then drop limb l:
+        c'_i = (c_i - (c_l mod q_i)) q_l^{-1} mod q_i, no rounding offset."""
+        pr = self.pr
+        l1 = ct.l1
+        ql = pr.q[l1 - 1]
+        k = int(np.sign(kappa) * np.floor(abs(kappa) * ql + 0.5))
+        q = pr.q[:l1]
+        const = [k % m for m in q]
+        rest = q[: l1 - 1]
+        ql_inv = [pow(ql, -1, m) for m in rest]
+        out = []
+        for c in (ct.c0, ct.c1):
+            c = self.mul_scalar(np.ascontiguousarray(c), const, q)
+            last = np.stack([c[l1 - 1] % np.uint64(m) for m in rest])
+            out.append(self.mul_scalar(self.sub(np.ascontiguousarray(c[: l1 - 1]), last, rest), ql_inv, rest))
+        return Ciphertext(out[0], out[1], ct.scale * k / ql)

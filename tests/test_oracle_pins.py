@@ -1,0 +1,389 @@
+"""Pins for the CPU oracle: each part is checked against something other than
+itself -- the schoolbook product, Python big integers, closed forms, the
+paper's printed toy example, float64 linear algebra."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import Oracle, Params
+from oracle.params import is_prime
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def crt(residues, moduli):
+    M = 1
+    for m in moduli:
+        M *= m
+    x = 0
+    for r, m in zip(residues, moduli):
+        Mi = M // m
+        x += int(r) * Mi * pow(Mi, -1, m)
+    return x % M, M
+
+
+def small_params(wlcfg, log_n):
+    """The workload's own primes (found for its full ring) run at a small ring."""
+    full = Params(*wlcfg.param_tuple())
+    return Params(log_n, 0, 0, 0, 0, wlcfg.alpha, wlcfg.log_scale, q=full.q, p=full.p)
+
+
+@pytest.fixture(scope="module")
+def all_small():
+    return [small_params(w, 8) for w in wl.WORKLOADS]
+
+
+# ------------------------------------------------------------------ primes
+@pytest.mark.parametrize("w", wl.WORKLOADS, ids=lambda w: w.name)
+def test_prime_chains(w):
+    pr = Params(*w.param_tuple())
+    assert len(pr.q) == w.q_count and len(pr.p) == w.p_count
+    assert len(set(pr.q + pr.p)) == len(pr.q + pr.p)
+    for m, bits in [(x, w.q_bits) for x in pr.q] + [(x, w.p_bits) for x in pr.p]:
+        assert m.bit_length() == bits
+        assert m % (2 * pr.N) == 1
+        # Fermat + trial division, independent of the Miller-Rabin used to find them
+        assert pow(2, m - 1, m) == 1 and pow(3, m - 1, m) == 1
+        assert all(m % f for f in range(3, 2000, 2))
+        assert pow(pr.psi[m], pr.N, m) == m - 1
+    assert pr.q == sorted(pr.q, reverse=True)
+
+
+def test_is_prime_small_table():
+    known = [2, 3, 5, 7, 11, 13, 97, 65537, 2147483647, (1 << 61) - 1]
+    comp = [1, 4, 561, 6601, 2147483649, (1 << 61) + 1, 3215031751]
+    assert all(is_prime(x) for x in known) and not any(is_prime(x) for x in comp)
+
+
+# --------------------------------------------------------------------- NTT
+def test_ntt_is_the_defining_sum():
+    pr = Params(4, 30, 2, 31, 1, 1, 20)
+    o = Oracle(pr)
+    rng = np.random.default_rng(0)
+    for q in pr.q + pr.p:
+        a = rng.integers(0, q, size=o.N, dtype=np.uint64)
+        got = o.ntt(a[None, :], [q])[0]
+        psi = pr.psi[q]
+        for k in range(o.N):
+            want = sum(int(a[i]) * pow(psi, (2 * k + 1) * i, q) for i in range(o.N)) % q
+            assert int(got[k]) == want
+
+
+def test_ntt_product_matches_schoolbook_on_every_prime(all_small):
+    rng = np.random.default_rng(1)
+    for pr in all_small:
+        o = Oracle(pr)
+        for q in pr.q + pr.p:
+            a = rng.integers(0, q, size=o.N, dtype=np.uint64)
+            b = rng.integers(0, q, size=o.N, dtype=np.uint64)
+            got = o.polymul(a[None, :], b[None, :], [q])[0]
+            assert np.array_equal(got, o.polymul_naive(a, b, q))
+
+
+def test_schoolbook_against_python_ints():
+    q, n = 1000003 * 0 + 998244353, 16
+    pr = Params(4, 0, 0, 0, 0, 1, 20, q=[q], p=[])
+    o = Oracle(pr)
+    rng = np.random.default_rng(2)
+    a = rng.integers(0, q, size=n, dtype=np.uint64)
+    b = rng.integers(0, q, size=n, dtype=np.uint64)
+    want = [0] * n
+    for i in range(n):
+        for j in range(n):
+            k = i + j
+            if k < n:
+                want[k] += int(a[i]) * int(b[j])
+            else:
+                want[k - n] -= int(a[i]) * int(b[j])
+    assert [int(x) for x in o.polymul_naive(a, b, q)] == [w % q for w in want]
+
+
+def test_ntt_roundtrip_and_x_power(all_small):
+    rng = np.random.default_rng(3)
+    pr = all_small[3]
+    o = Oracle(pr)
+    primes = pr.q + pr.p
+    a = np.stack([rng.integers(0, q, size=o.N, dtype=np.uint64) for q in primes])
+    assert np.array_equal(o.ntt(o.ntt(a, primes), primes, inverse=True), a)
+    # X^(N-1) * X = -1
+    x1 = np.zeros((len(primes), o.N), dtype=np.uint64)
+    xn = np.zeros_like(x1)
+    x1[:, 1] = 1
+    xn[:, o.N - 1] = 1
+    prod = o.polymul(x1, xn, primes)
+    want = np.zeros_like(x1)
+    want[:, 0] = np.array([q - 1 for q in primes], dtype=np.uint64)
+    assert np.array_equal(prod, want)
+
+
+# ---------------------------------------------------------------- encoding
+def test_encode_fft_matches_direct_sum_and_roundtrip():
+    pr = Params(10, 36, 3, 37, 1, 1, 30)
+    o = Oracle(pr)
+    rng = np.random.default_rng(4)
+    z = rng.uniform(-1, 1, o.n)
+    m = o.encode_coeffs(z)
+    assert np.abs(m - o.encode_coeffs_direct(z)).max() <= 1
+    back = o.decode_coeffs(m.astype(np.float64))
+    assert np.abs(back.real - z).max() < 2.0 ** -20
+    assert np.abs(back.imag).max() < 2.0 ** -20
+
+
+def test_encode_is_ring_homomorphism_and_rotation_direction():
+    pr = Params(8, 50, 2, 60, 1, 1, 24)
+    o = Oracle(pr)
+    rng = np.random.default_rng(5)
+    z1, z2 = rng.uniform(-1, 1, o.n), rng.uniform(-1, 1, o.n)
+    q = pr.q
+    m1, m2 = o.i64_to_rns(o.encode_coeffs(z1), q), o.i64_to_rns(o.encode_coeffs(z2), q)
+    prod = o.polymul(m1, m2, q)
+    ct = type("C", (), {})()
+    from oracle.ckks import Ciphertext
+    c = Ciphertext(prod, np.zeros_like(prod), pr.scale ** 2)
+    coeffs = o.decrypt_coeffs(c, np.zeros(o.N, dtype=np.int8))
+    got = o.decode_coeffs(coeffs, pr.scale ** 2).real
+    assert np.abs(got - z1 * z2).max() < 1e-4
+    # Rot(c;k)[i] = c[i+k]  (paper, Rotation): phi_{5^k} of the encoding decodes to the left shift
+    for k in (1, 3, o.n - 1):
+        g = pr.galois_element(k)
+        rot = o.automorphism(m1, g, q)
+        cr = Ciphertext(rot, np.zeros_like(rot), pr.scale)
+        z = o.decode_coeffs(o.decrypt_coeffs(cr, np.zeros(o.N, dtype=np.int8))).real
+        assert np.abs(z - np.roll(z1, -k)).max() < 1e-5
+    assert pr.galois_element(-1) == pow(5, o.n - 1, 2 * o.N)
+
+
+def test_crt_center_against_python_ints():
+    pr = Params(4, 50, 2, 60, 1, 1, 20)
+    o = Oracle(pr)
+    from oracle.ckks import Ciphertext
+    rng = np.random.default_rng(6)
+    q0, q1 = pr.q
+    vals = [int(v) for v in rng.integers(-(1 << 62), 1 << 62, size=o.N)]
+    vals[0], vals[1], vals[2] = (q0 * q1) // 2, -((q0 * q1) // 2), 0
+    c0 = np.array([[v % q0 for v in vals], [v % q1 for v in vals]], dtype=np.uint64)
+    got = o.decrypt_coeffs(Ciphertext(c0, np.zeros_like(c0), 1.0), np.zeros(o.N, dtype=np.int8))
+    assert np.array_equal(got, np.array([float(v) for v in vals]))
+
+
+# ------------------------------------------------------ basis conversions
+@pytest.mark.parametrize("widx", [0, 1, 3])
+def test_modup_is_digit_plus_small_multiple_of_Qj(widx, all_small):
+    pr = all_small[widx]
+    o = Oracle(pr)
+    rng = np.random.default_rng(7)
+    for l1 in {pr.L, max(1, pr.L - 1)}:
+        c1 = np.stack([rng.integers(0, q, size=o.N, dtype=np.uint64) for q in pr.q[:l1]])
+        up = o.mod_up(c1)
+        ext = pr.q[:l1] + pr.p
+        assert up.shape == (pr.beta(l1), l1 + pr.K, o.N)
+        for j in range(pr.beta(l1)):
+            src = pr.digit_limbs(j, l1)
+            qs = [pr.q[i] for i in src]
+            for idx in range(0, o.N, 37):
+                dval, Qj = crt([c1[i, idx] for i in src], qs)
+                us = set()
+                for t_i, t in enumerate(ext):
+                    r = int(up[j, t_i, idx])
+                    if t_i in src:
+                        assert r == int(c1[t_i, idx])
+                        continue
+                    u = (r - dval) * pow(Qj, -1, t) % t
+                    us.add(u)
+                assert len(us) == 1 and 0 <= us.pop() < len(src)
+
+
+@pytest.mark.parametrize("widx", [0, 1, 3])
+def test_moddown_is_exact_division_up_to_small_integer(widx, all_small):
+    pr = all_small[widx]
+    o = Oracle(pr)
+    rng = np.random.default_rng(8)
+    l1 = pr.L
+    ext = pr.q[:l1] + pr.p
+    u = np.stack([rng.integers(0, q, size=o.N, dtype=np.uint64) for q in ext])
+    out = o.mod_down(u, l1)
+    for idx in range(0, o.N, 29):
+        full, _ = crt([u[i, idx] for i in range(len(ext))], ext)
+        up, P = crt([u[l1 + k, idx] for k in range(pr.K)], pr.p)
+        exact = (full - up) // P
+        assert (full - up) % P == 0
+        vs = {(exact - int(out[i, idx])) % pr.q[i] for i in range(l1)}
+        assert len(vs) == 1 and 0 <= vs.pop() < pr.K
+
+
+def test_rescale_is_exact_division(all_small):
+    pr = all_small[4]
+    o = Oracle(pr)
+    from oracle.ckks import Ciphertext
+    rng = np.random.default_rng(9)
+    l1 = pr.L
+    q = pr.q[:l1]
+    c0 = np.stack([rng.integers(0, m, size=o.N, dtype=np.uint64) for m in q])
+    c1 = np.stack([rng.integers(0, m, size=o.N, dtype=np.uint64) for m in q])
+    kappa = -(2.0 ** -5)
+    out = o.mul_scalar_rescale(Ciphertext(c0, c1, pr.scale), kappa)
+    ql = q[-1]
+    k = -int(math.floor(abs(kappa) * ql + 0.5))
+    assert out.l1 == l1 - 1 and out.scale == pr.scale * k / ql
+    for idx in range(0, o.N, 41):
+        for src, dst in ((c0, out.c0), (c1, out.c1)):
+            val, Q = crt([src[i, idx] for i in range(l1)], q)
+            val = val * k % Q
+            exact = (val - val % ql) // ql
+            assert [int(dst[i, idx]) for i in range(l1 - 1)] == [exact % m for m in q[:-1]]
+
+
+# --------------------------------------------------------- whole key switch
+def _keys(o, rng, seed=11):
+    sk, pk = o.keygen(wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), seed)
+    return sk, pk
+
+
+def _enc(o, rng, pk, z, l1):
+    return o.encrypt(o.encode(z, l1), pk, wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), wl.error_poly(rng, o.N))
+
+
+@pytest.mark.parametrize("widx,log_n", [(0, 10), (1, 10), (3, 10)])
+def test_key_switch_noise_and_rotation(widx, log_n):
+    w = wl.WORKLOADS[widx]
+    pr = small_params(w, log_n)
+    o = Oracle(pr)
+    rng = np.random.default_rng(10 + widx)
+    sk, pk = _keys(o, rng)
+    z = rng.uniform(-1, 1, o.n)
+    ct = _enc(o, rng, pk, z, pr.L)
+    assert np.abs(o.decrypt(ct, sk) - z).max() < 1e-3
+    for step in (1, 5, -1, o.n // 2):
+        gk = o.galois_keygen(sk, step, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 12)
+        rot = o.rotate(ct, gk)
+        assert rot.l1 == ct.l1 and rot.scale == ct.scale  # Rot consumes no level
+        assert np.abs(o.decrypt(rot, sk) - np.roll(z, -step)).max() < 1e-3
+        # (out0 + out1 s) - phi_g(c0 + c1 s) is a small polynomial
+        q = pr.q[:2]
+        s_rns = o.small_to_rns(sk, q)
+        lhs = o.add(rot.c0[:2], o.polymul(np.ascontiguousarray(rot.c1[:2]), s_rns, q), q)
+        inner = o.add(ct.c0[:2], o.polymul(np.ascontiguousarray(ct.c1[:2]), s_rns, q), q)
+        diff = o.sub(lhs, o.automorphism(inner, gk["g"], q), q)
+        from oracle.ckks import Ciphertext
+        noise = o.decrypt_coeffs(Ciphertext(diff, np.zeros_like(diff), 1.0), np.zeros(o.N, dtype=np.int8))
+        assert np.abs(noise).max() < pr.scale * 1e-3 / math.sqrt(o.N)
+
+
+def test_rotate_at_lower_level():
+    w = wl.WORKLOADS[4]
+    pr = small_params(w, 9)
+    o = Oracle(pr)
+    rng = np.random.default_rng(20)
+    sk, pk = _keys(o, rng)
+    z = rng.uniform(-1, 1, o.n)
+    ct = _enc(o, rng, pk, z, pr.L - 3)  # 13 limbs: last digit is partial
+    gk = o.galois_keygen(sk, 3, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 5)
+    rot = o.rotate(ct, gk)
+    assert rot.l1 == pr.L - 3
+    assert np.abs(o.decrypt(rot, sk) - np.roll(z, -3)).max() < 1e-3
+
+
+# -------------------------------------------------------------------- PCMM
+def _read_toy():
+    W, Y = [], {}
+    for line in open(os.path.join(HERE, "golden", "pcmm_toy.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "W":
+            W.append([int(x) for x in t[1:]])
+        else:
+            Y[int(t[1])] = [(int(x[1:]), 1 if x[0] == "+" else -1) for x in t[2:]]
+    return np.array(W, dtype=np.int8), Y
+
+
+def test_pcmm_toy_example_from_paper():
+    W, Y = _read_toy()
+    pr = Params(4, 36, 3, 37, 1, 1, 30)
+    o = Oracle(pr)
+    rng = np.random.default_rng(21)
+    sk, pk = _keys(o, rng)
+    s, d = 4, 4  # the example's s=d=4; ring with 8 slots, one column per ciphertext pair below
+    X = rng.uniform(-1, 1, (o.n, d))  # c_tot = 1: every ciphertext is one column (the paper's own packing)
+    cts = [_enc(o, rng, pk, X[:, j], pr.L) for j in range(d)]
+    out = o.ternary_matmul(cts, o.n, d, W, "zero", {})  # no Galois key needed
+    assert len(out) == 2
+    for i, terms in Y.items():
+        for poly in ("c0", "c1"):
+            for l, q in enumerate(pr.q):
+                want = [0] * o.N
+                for j, sg in terms:
+                    for k in range(o.N):
+                        want[k] += sg * int(getattr(cts[j], poly)[l, k])
+                assert [int(v) for v in getattr(out[i], poly)[l]] == [v % q for v in want]
+        assert out[i].l1 == pr.L and out[i].scale == pr.scale  # level and scale unchanged
+    got = np.stack([o.decrypt(c, sk) for c in out], axis=1)
+    assert np.abs(got - X @ W.astype(np.float64)).max() < 1e-3
+
+
+def test_pcmm_identity_and_zero_column():
+    pr = Params(6, 36, 3, 37, 1, 1, 30)
+    o = Oracle(pr)
+    rng = np.random.default_rng(22)
+    sk, pk = _keys(o, rng)
+    d = 3
+    cts = [_enc(o, rng, pk, rng.uniform(-1, 1, o.n), pr.L) for _ in range(d)]
+    W = np.eye(d, 4, dtype=np.int8)  # last output column is all zero
+    out = o.ternary_matmul(cts, o.n, d, W, "zero", {})
+    for j in range(d):
+        assert np.array_equal(out[j].c0, cts[j].c0) and np.array_equal(out[j].c1, cts[j].c1)
+    assert not out[3].c0.any() and not out[3].c1.any()  # transparent zero ciphertext
+
+
+@pytest.mark.parametrize("placement", ["diagonal", "zero"])
+def test_pcmm_tiny_workload_end_to_end(placement, tiny_oracle):
+    w = wl.WORKLOADS[0]
+    o = tiny_oracle
+    pr = o.pr
+    rng = wl.rng_for(w.index)
+    W = wl.ternary_weights(rng, w.d_in, w.d_out)
+    X = wl.activations(rng, w.tokens, w.d_in, w.act)
+    sk, pk = _keys(o, rng)
+    packed = wl.pack_columns(X, o.n)
+    assert packed.shape[0] == 1
+    cts = [_enc(o, rng, pk, packed[0], pr.L)]
+    c_tot = w.c_tot
+    plan = o.plan(W, c_tot, placement)
+    rhos = sorted({rho for t in plan for (_, rho, _) in t if rho})
+    assert len(rhos) <= c_tot - 1
+    gks = {rho: o.galois_keygen(sk, rho * w.tokens, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 33) for rho in rhos}
+    out = o.ternary_matmul(cts, w.tokens, w.d_in, W, placement, gks)
+    assert sum(len(t) for t in plan) == int(np.count_nonzero(W))  # one ciphertext add/sub per non-zero weight
+    ref = X @ W.astype(np.float64)
+    err = 0.0
+    for i, c in enumerate(out):
+        p_i = o.placement_block(i, c_tot, placement)
+        z = o.decrypt(c, sk)[p_i * w.tokens:(p_i + 1) * w.tokens]
+        err = max(err, np.abs(z - ref[:, i]).max())
+        assert c.l1 == pr.L and c.scale == pr.scale
+    assert err < 1e-3
+
+
+def test_uniform_stream_follows_its_specification():
+    """The sampler is this build's own format (no external pin): check the C
+    routine against the written specification evaluated with Python integers."""
+    M = (1 << 64) - 1
+
+    def mix(z):
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9 & M
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EB & M
+        return z ^ (z >> 31)
+
+    # SplitMix64 (Steele, Lea, Flood 2014) first output for seed 0, as widely tabulated
+    assert mix(0x9E3779B97F4A7C15) == 0xE220A8397B1DCDAF
+    pr = Params(4, 50, 1, 60, 1, 1, 20)
+    o = Oracle(pr)
+    seed, stream, pid, q = 12345, (2 << 56) | (5 << 8) | 1, 3, pr.p[0]
+    got = o.uniform(seed, stream, [pid], [q])[0]
+    G = 0x9E3779B97F4A7C15
+    key = mix((mix((mix(seed) + stream) & M) + pid) & M)
+    want = [((mix((key + G * (2 * i + 1)) & M) << 64) | mix((key + G * (2 * i + 2)) & M)) % q for i in range(o.N)]
+    assert [int(x) for x in got] == want

@@ -1,0 +1,108 @@
+"""Seeded synthetic inputs and the five workload shapes.
+
+This module serves both the GPU library's tests/benchmark and the CPU oracle.
+It holds none of the method's arithmetic: only shapes, parameter choices and
+numpy random draws (weights, activations, and the small secret/error/mask
+polynomials that key generation and encryption consume as inputs).
+
+The draws stand in for BitNet b1.58 weights and transformer activations, which
+the paper evaluates on but which are not available here: weights are iid
+ternary with P(-1)=P(+1)=0.3, P(0)=0.4; activations are uniform [-1,1] or
+N(0,1) clipped to [-4,4].
+"""
+from dataclasses import dataclass
+
+import numpy as np
+
+BASE_SEED = 250909424
+ERROR_SIGMA = 3.2
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    index: int
+    log_n: int
+    q_bits: int
+    q_count: int
+    p_bits: int
+    p_count: int
+    alpha: int
+    log_scale: int
+    tokens: int = 0  # s
+    d_in: int = 0  # d
+    d_out: int = 0  # m
+    d_mid: int = 0  # FFN hidden width (two-layer workloads only)
+    placement: str = "diagonal"
+    act: str = "uniform"  # "uniform" [-1,1] or "normal" N(0,1) clipped to [-4,4]
+    batch: int = 0  # key-switch microbench: number of ciphertexts
+    kappa: float = 0.0  # scalar applied before the rescale between two layers
+
+    @property
+    def N(self):
+        return 1 << self.log_n
+
+    @property
+    def n_slots(self):
+        return self.N // 2
+
+    @property
+    def c_tot(self):
+        return self.n_slots // self.tokens if self.tokens else 0
+
+    def param_tuple(self):
+        return (self.log_n, self.q_bits, self.q_count, self.p_bits, self.p_count, self.alpha, self.log_scale)
+
+
+WORKLOADS = [
+    Workload("tiny", 0, 12, 36, 3, 37, 1, 1, 30, tokens=32, d_in=64, d_out=64, placement="diagonal", act="uniform"),
+    Workload("keyswitch", 1, 16, 50, 10, 60, 3, 3, 40, batch=64, act="uniform"),
+    Workload("proj768", 2, 16, 50, 12, 60, 4, 4, 40, tokens=32, d_in=768, d_out=768, placement="diagonal", act="normal"),
+    Workload("attn2560", 3, 16, 50, 16, 60, 4, 4, 40, tokens=128, d_in=2560, d_out=2560, placement="diagonal", act="normal"),
+    Workload("ffn2560", 4, 16, 50, 16, 60, 4, 4, 40, tokens=128, d_in=2560, d_out=2560, d_mid=6912, placement="zero",
+             act="normal", kappa=2.0 ** -5),
+]
+BY_NAME = {w.name: w for w in WORKLOADS}
+
+# key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
+KEYSWITCH_STEPS = [1 << i for i in range(15)] + [-1]
+
+
+def rng_for(index, salt=0):
+    return np.random.default_rng(BASE_SEED + index + 1000 * salt)
+
+
+def ternary_weights(rng, d, m):
+    """Row-major d x m int8 in {-1,0,+1}, P(-1)=P(+1)=0.3, P(0)=0.4."""
+    u = rng.random((d, m))
+    return (np.where(u < 0.3, -1, 0) + np.where(u >= 0.7, 1, 0)).astype(np.int8)
+
+
+def activations(rng, tokens, d, kind):
+    if kind == "uniform":
+        return rng.uniform(-1.0, 1.0, size=(tokens, d))
+    return np.clip(rng.standard_normal((tokens, d)), -4.0, 4.0)
+
+
+def pack_columns(X, n_slots):
+    """Column-wise SIMD packing with several columns per ciphertext: packed vector
+    G holds column G*c_tot+b in slots [b*s,(b+1)*s).  Returns [n_ct][n_slots]."""
+    s, d = X.shape
+    c_tot = n_slots // s
+    n_ct = -(-d // c_tot)
+    out = np.zeros((n_ct, n_slots), dtype=np.float64)
+    for j in range(d):
+        G, b = divmod(j, c_tot)
+        out[G, b * s:(b + 1) * s] = X[:, j]
+    return out
+
+
+def ternary_poly(rng, n):
+    """Uniform ternary polynomial (secret key, encryption mask), int8[n]."""
+    return rng.integers(-1, 2, size=n, dtype=np.int8)
+
+
+def error_poly(rng, shape):
+    """Rounded Gaussian, sigma 3.2, clipped at +-19 (about 6 sigma), int8."""
+    e = np.rint(rng.normal(0.0, ERROR_SIGMA, size=shape))
+    return np.clip(e, -19, 19).astype(np.int8)
