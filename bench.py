@@ -1,0 +1,299 @@
+#!/usr/bin/env python3
+"""Benchmark of the encrypted ternary matmul hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input:
+  * matmul workloads: unpack rotations (ModUp, NTT, key inner product, iNTT,
+    ModDown) + Alg. 1 accumulate (+ scalar-multiply/rescale + second layer for
+    the FFN workload), inputs and keys already resident in HBM;
+  * the key-switch microbenchmark (always run as a second leg): 64 ciphertexts,
+    each rotated by one of 16 Galois elements, reported as rotations/s.
+One JSON line is printed.  `value` is ms/layer of the matmul workload;
+`rotations` carries the rotations/s figure; `roofline` describes the dominant
+kernel class of the timed step; `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload on this host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+# plain integer ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit lane-ops/s; one 64-bit add = 2 of them
+U64_ADD_PEAK = 256 * 4 * 16 * 2.4e9 / 2
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+class Runner:
+    def __init__(self, w, seed=1):
+        from paper_2509_09424_amd import binding
+        self.w = w
+        self.ctx = binding.Context(*w.param_tuple(), seed=seed)
+        self.N, self.n = w.N, w.n_slots
+        self.L, self.K, self.alpha = w.q_count, w.p_count, w.alpha
+        self.beta = -(-self.L // self.alpha)
+        self.sk, self.pk = self.ctx.keygen(None, None, 11)
+
+    def sync(self):
+        import torch
+        torch.cuda.synchronize()
+
+    # ---- workload set-up (untimed): inputs and keys made resident on the device
+    def setup(self):
+        w = self.w
+        rng = wl.rng_for(w.index)
+        if w.name == "keyswitch":
+            X = rng.uniform(-1.0, 1.0, size=(w.batch, self.n))
+            pt = self.ctx.encode(X, self.L)
+            self.ct_in = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            self.steps = [wl.KEYSWITCH_STEPS[b % 16] for b in range(w.batch)]
+            self.gk = self.ctx.galois_keygen(self.sk, wl.KEYSWITCH_STEPS, None, 13)
+            self.ct_out = self.ctx.ct_alloc(w.batch, self.L)
+            self.X = X
+            return
+        self.W = wl.ternary_weights(rng, w.d_in, w.d_mid or w.d_out)
+        self.X = wl.activations(rng, w.tokens, w.d_in, w.act)
+        if w.d_mid:
+            self.W2 = wl.ternary_weights(rng, w.d_mid, w.d_out)
+        packed = wl.pack_columns(self.X, self.n)
+        pt = self.ctx.encode(packed, self.L)
+        self.ct_in = self.ctx.encrypt(self.pk, pt)
+        pt.free()
+        c_tot = w.c_tot
+        n_rho = min(c_tot, w.d_in)
+        rot_steps = [r * w.tokens for r in range(1, c_tot)] if w.placement == "diagonal" else [r * w.tokens for r in range(1, n_rho)]
+        t0 = time.time()
+        self.gk = self.ctx.galois_keygen(self.sk, rot_steps, None, 13) if rot_steps else None
+        log("generated %d Galois keys in %.1f s" % (len(rot_steps), time.time() - t0))
+        self.ct_out = self.ctx.ct_alloc(w.d_mid or w.d_out, self.L)
+        if w.d_mid:
+            self.ct_out2 = self.ctx.ct_alloc(w.d_out, self.L - 1)
+
+    def step(self):
+        w = self.w
+        if w.name == "keyswitch":
+            self.ctx.rotate(self.gk, self.ct_in, self.steps, self.ct_out)
+            return
+        self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
+        if w.d_mid:
+            # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
+            if getattr(self, "mid", None) is not None:
+                self.mid.free()
+            mid = self.ctx.ct_wrap(self.ct_out.device_ptr, w.d_mid, self.L, self.ct_in.scale)
+            self.ctx.mul_scalar_rescale(mid, w.kappa)
+            self.mid = mid
+            self.ctx.ternary_matmul(None, mid, self.n, w.d_mid, self.W2, "zero", self.ct_out2)
+
+    def check(self):
+        """Decrypts a few outputs and compares with the float64 product (sanity, untimed)."""
+        w = self.w
+        self.sync()
+        if w.name == "keyswitch":
+            dec = self.ctx.decrypt(self.sk, self.ct_out)
+            err = max(np.abs(dec[b] - np.roll(self.X[b], -self.steps[b])).max() for b in range(w.batch))
+            return float(err)
+        ref = self.X @ self.W.astype(np.float64)
+        out = self.ct_out
+        if w.d_mid:
+            ref = (ref * w.kappa) @ self.W2.astype(np.float64)
+            out = self.ct_out2
+        m = w.d_out
+        err = 0.0
+        # decrypt only a sample of output ciphertexts through wrapped single-ciphertext views
+        sample = sorted(set([0, 1, m // 2, m - 1] + list(np.random.default_rng(0).integers(0, m, 12))))
+        n, limbs, scale, base = out._info()
+        alloc = self.L - 1 if w.d_mid else self.L
+        words = 2 * alloc * self.N
+        for i in sample:
+            one = self.ctx.ct_wrap(base + 8 * words * i, 1, limbs, scale)
+            p_i = 0 if (w.placement == "zero" or w.d_mid) else i % w.c_tot
+            dec = self.ctx.decrypt(self.sk, one, p_i * w.tokens, w.tokens)[0]
+            err = max(err, float(np.abs(dec - ref[:, i]).max()))
+            one.free()
+        return err
+
+
+def time_steps(runner, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        runner.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        runner.step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def kernel_profile(runner):
+    """One extra, untimed step with the library's HIP-event timers on: per-class total ms and launches."""
+    import torch
+    torch.cuda.synchronize()
+    runner.ctx.profile_read()
+    runner.ctx.profile_enable(True)
+    runner.step()
+    torch.cuda.synchronize()
+    prof = runner.ctx.profile_read()
+    runner.ctx.profile_enable(False)
+    return prof
+
+
+def roofline_for(w, prof):
+    """Roofline entry of the dominant kernel class of the step."""
+    N, L, K, alpha = w.N, w.q_count, w.p_count, w.alpha
+    unit = 8.0 * N
+    ext = L + K
+    beta = -(-L // alpha)
+    groups = {
+        "ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"],
+        "inner_product": ["inner_product"], "modup": ["modup"], "moddown": ["moddown"],
+        "accumulate": ["accumulate"], "mul_scalar_rescale": ["mul_scalar_rescale"],
+    }
+    tot = {g: sum(prof.get(k, (0.0, 0))[0] for k in ks) for g, ks in groups.items()}
+    dom = max(tot, key=tot.get)
+    ms = tot[dom]
+    if w.name == "keyswitch":
+        n_rot, n_modup = w.batch, w.batch
+    else:
+        c_tot = w.c_tot
+        n_in = -(-w.d_in // c_tot)
+        n_rot = w.d_in - n_in
+        n_modup = n_in
+    if dom == "ntt":
+        limbs = n_modup * beta * ext + n_rot * 2 * ext  # forward on raised digits + inverse on both accumulators
+        algo = 2 * unit * limbs  # each limb read once and written once
+        return dom, {"bound": "hbm", "achieved": algo / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "kernel": "ntt (both passes, forward+inverse)",
+                     "launch_ms": ms, "limb_transforms": limbs}
+    if dom == "inner_product":
+        algo = unit * n_rot * (3 * beta * ext + 2 * ext)
+    elif dom == "modup":
+        algo = unit * n_modup * (L + beta * ext)
+    elif dom == "moddown":
+        algo = unit * n_rot * (2 * ext + 3 * L)
+    elif dom == "mul_scalar_rescale":
+        algo = unit * w.d_mid * (2 * L + 2 * (L - 1))
+    else:
+        # Alg. 1: one 64-bit add/sub per non-zero weight per limb word
+        nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
+        ops = nnz * 2 * L * N
+        return dom, {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": U64_ADD_PEAK / 1e12, "unit": "Tadd64/s",
+                     "frac": ops / (ms * 1e-3) / U64_ADD_PEAK, "traffic": None, "kernel": "accumulate", "launch_ms": ms}
+    gbs = algo / (ms * 1e-3) / 1e9
+    return dom, {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                 "traffic": None, "kernel": dom, "launch_ms": ms}
+
+
+def cpu_baseline(w):
+    """The CPU oracle, as it stands, on a bounded sample of the workload: one hoisted
+    rotation at the workload's parameters plus the Alg. 1 sum of one output column over
+    a sample of its operands; extrapolated linearly to the step's rotation and add counts."""
+    from oracle import Oracle, Params
+    t_setup = time.time()
+    pr = Params(*w.param_tuple())
+    o = Oracle(pr)
+    rng = np.random.default_rng(5)
+    sk, pk = o.keygen(wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), 3)
+    z = rng.uniform(-1, 1, o.n)
+    ct = o.encrypt(o.encode(z, pr.L), pk, wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), wl.error_poly(rng, o.N))
+    step = w.tokens if w.tokens else 1
+    gk = o.galois_keygen(sk, step, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 4)
+    o._key_at_level(gk, pr.L)
+    log("oracle set-up %.1f s" % (time.time() - t_setup))
+    t0 = time.perf_counter()
+    digits = o.mod_up(ct.c1)
+    t_modup = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    rot = o.rotate_from_digits(ct.c0, digits, gk, ct.scale)
+    t_rot = time.perf_counter() - t0
+    cores = len(os.sched_getaffinity(0))
+    if w.name == "keyswitch":
+        per = t_modup + t_rot
+        return {"value": 1.0 / per, "unit": "rotations/s", "cores": cores, "kind": "oracle",
+                "sample": "1 full rotation (ModUp + key switch) at the workload's parameters"}
+    n_terms = 64
+    t0 = time.perf_counter()
+    o.accumulate([(rot if k % 2 else ct, 1 if k % 3 else -1) for k in range(n_terms)], pr.L, ct.scale)
+    t_add = (time.perf_counter() - t0) / n_terms
+    c_tot = w.c_tot
+    n_in = -(-w.d_in // c_tot)
+    n_rot = w.d_in - n_in
+    nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
+    total = n_in * t_modup + n_rot * t_rot + nnz * t_add
+    return {"value": total * 1e3, "unit": "ms/layer", "cores": cores, "kind": "oracle",
+            "sample": "1 ModUp (%.2f s) + 1 hoisted rotation (%.2f s) + %d ciphertext add/subs (%.4f s each), extrapolated "
+                      "linearly to %d ModUps, %d rotations, %.3g add/subs" % (t_modup, t_rot, n_terms, t_add, n_in, n_rot, nnz)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="attn2560", choices=[w.name for w in wl.WORKLOADS])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-keyswitch-leg", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.init()
+    w = wl.BY_NAME[args.workload]
+    log("workload %s on %s" % (w.name, torch.cuda.get_device_name(0)))
+    t0 = time.time()
+    r = Runner(w)
+    r.setup()
+    log("set-up done in %.1f s" % (time.time() - t0))
+    ms = time_steps(r, args.steps, args.warmup)
+    log("timed %d steps: %.3f ms/step" % (args.steps, ms))
+    err = r.check()
+    log("decrypted max abs error on sampled outputs: %.3e" % err)
+    prof = kernel_profile(r)
+    dom, roof = roofline_for(w, prof)
+    kernels = {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(prof.items())}
+    line = {
+        "metric": "encrypted ternary matmul ms/layer + key-switched rotations/sec at N=2^16",
+        "value": ms, "unit": "ms/layer" if w.name != "keyswitch" else "ms/batch",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": w.name, "log_n": w.log_n, "q_limbs": w.q_count, "p_limbs": w.p_count, "alpha": w.alpha,
+                   "tokens": w.tokens, "d_in": w.d_in, "d_mid": w.d_mid, "d_out": w.d_out, "placement": w.placement},
+        "decrypt_max_abs_err": err, "roofline": roof, "kernels_ms_per_step": kernels,
+    }
+    if w.name == "keyswitch":
+        line["rotations"] = {"value": w.batch / (ms * 1e-3), "unit": "rotations/s", "workload": "keyswitch"}
+    del r
+    if w.name != "keyswitch" and not args.no_keyswitch_leg:
+        kw = wl.BY_NAME["keyswitch"]
+        rk = Runner(kw)
+        rk.setup()
+        kms = time_steps(rk, max(args.steps, 5), args.warmup)
+        kerr = rk.check()
+        kprof = kernel_profile(rk)
+        _, kroof = roofline_for(kw, kprof)
+        line["rotations"] = {"value": kw.batch / (kms * 1e-3), "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": kms,
+                             "decrypt_max_abs_err": kerr, "roofline": kroof,
+                             "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(kprof.items())}}
+        log("key-switch leg: %.1f rotations/s" % line["rotations"]["value"])
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

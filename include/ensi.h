@@ -1,0 +1,183 @@
+/*
+ * ensi.h -- C ABI of the MI355X (gfx950) library for CKKS-encrypted ternary
+ * matrix multiplication: the multiplication-free plaintext-ciphertext product
+ * of the ENSI paper (Alg. 1, PCMM) under column-wise SIMD packing, together
+ * with the CKKS primitives it stands on (Preliminaries: KeyGen, Encryption,
+ * Decryption, Addition, Rotation).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative ENSI_E_* code; a
+ *     message for the last failure on a context is kept by ensi_last_error().
+ *     Nothing throws across this boundary.
+ *   - "host" pointers are ordinary CPU memory borrowed for the duration of the
+ *     call; "device" pointers are HIP device memory on the context's GPU.
+ *   - Handles are opaque, owned by the caller, and released with the matching
+ *     *_free.  A ciphertext handle is a BATCH of n ciphertexts stored
+ *     contiguously on the device as u64 words [n][2][limbs_alloc][N]:
+ *     polynomial-major, then RNS limb, then coefficient (unit stride),
+ *     coefficient form, canonical residues in [0, q_i).  Only the first
+ *     `limbs` (<= limbs_alloc) limbs of each polynomial are active.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return; results are ready after the stream
+ *     is synchronised.  Calls that return host data synchronise themselves.
+ *   - Ring degree N = 2^log_n, n = N/2 slots.  Primes: q_0..q_{L-1} of q_bits
+ *     bits and p_0..p_{K-1} of p_bits bits, the largest primes = 1 mod 2N
+ *     below 2^bits, descending (P chain skips members of the Q chain).
+ *   - Random material is either passed in (int8 host arrays: ternary
+ *     polynomials, small error polynomials) or, where the pointer is NULL,
+ *     drawn by the library's own host sampler.  Uniform ring elements come from
+ *     a counter-based generator keyed by (seed, stream id, prime index):
+ *       mix(z): z^=z>>30; z*=0xBF58476D1CE4E5B9; z^=z>>27; z*=0x94D049BB133111EB; z^=z>>31
+ *       key = mix(mix(mix(seed)+stream)+prime_index)
+ *       coefficient i = (mix(key+G*(2i+1))*2^64 + mix(key+G*(2i+2))) mod q,  G=0x9E3779B97F4A7C15
+ *     with stream 1 for the public key and (2<<56)|(g<<8)|digit for the key of
+ *     Galois element g.
+ */
+#ifndef ENSI_H
+#define ENSI_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ENSI_OK 0
+#define ENSI_E_BADARG -1 /* null pointer, value out of range, weight outside {-1,0,1} */
+#define ENSI_E_NOKEY -2  /* a needed rotation step has no Galois key in the key set */
+#define ENSI_E_LEVEL -3  /* operands at different levels, or no limb left to drop */
+#define ENSI_E_SHAPE -4  /* batch sizes / layout do not fit together */
+#define ENSI_E_NOMEM -5  /* device or host allocation failed */
+#define ENSI_E_HIP -6    /* a HIP runtime call failed */
+
+#define ENSI_PLACE_ZERO 0     /* every output column in slot block 0 */
+#define ENSI_PLACE_DIAGONAL 1 /* output column i in slot block i mod c_tot */
+
+typedef struct ensi_ctx ensi_ctx;
+typedef struct ensi_sk ensi_sk;
+typedef struct ensi_pk ensi_pk;
+typedef struct ensi_gk ensi_gk;
+typedef struct ensi_pt ensi_pt;
+typedef struct ensi_ct ensi_ct;
+
+typedef struct ensi_params {
+    int32_t log_n;     /* ring degree N = 2^log_n, 4 <= log_n <= 16 */
+    int32_t q_bits;    /* bit size of the ciphertext primes (<= 60) */
+    int32_t q_count;   /* L: number of ciphertext primes (<= 28) */
+    int32_t p_bits;    /* bit size of the special primes (<= 61) */
+    int32_t p_count;   /* K: number of special primes (1..4) */
+    int32_t alpha;     /* limbs per key-switching digit (1..4) */
+    int32_t log_scale; /* encoding scale Delta = 2^log_scale */
+    uint64_t seed;     /* seeds the library's own sampler (used only where NULL randomness is passed) */
+} ensi_params;
+
+/* ---- context ----------------------------------------------------------- */
+/* Finds the primes, builds transform tables and conversion constants and
+ * uploads them to the current HIP device. */
+int ensi_ctx_create(const ensi_params *params, ensi_ctx **out);
+void ensi_ctx_free(ensi_ctx *ctx);
+const char *ensi_last_error(const ensi_ctx *ctx); /* string owned by ctx; "" if none */
+/* q: host[L], p: host[K] */
+int ensi_get_primes(const ensi_ctx *ctx, uint64_t *q, uint64_t *p);
+
+/* ---- keys (Preliminaries, KeyGen) -------------------------------------- */
+/* s: host int8[N] ternary secret; e: host int8[N] error; either may be NULL
+ * (library samples).  pk = (-a s + e, a) over Q_L, a = counter stream 1 of
+ * seed_a. */
+int ensi_keygen(ensi_ctx *ctx, const int8_t *s, const int8_t *e, uint64_t seed_a, ensi_sk **sk, ensi_pk **pk);
+void ensi_sk_free(ensi_sk *sk);
+void ensi_pk_free(ensi_pk *pk);
+/* One hybrid key-switching key per rotation step (duplicates are merged).
+ * e: host int8[n_steps][beta][N] errors (beta = ceil(L/alpha)) or NULL. For
+ * step k the Galois element is g = 5^(k mod n) mod 2N, and for each digit j
+ * (b_j, a_j) over Q_L*P with b_j = -a_j s + e_j + [P]_{q_i} phi_g(s) on the
+ * limbs i of digit j only. */
+int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_t *steps, int32_t n_steps, const int8_t *e,
+                       uint64_t seed_a, ensi_gk **gk);
+void ensi_gk_free(ensi_gk *gk);
+
+/* ---- plaintexts (column-wise SIMD encoding, pi) ------------------------- */
+/* slots: host double[n_pt][n_slots] real values, zero-padded to N/2 slots.
+ * Slot j sits at the root exp(i pi 5^j / N); coefficients are
+ * round-half-away((2 Delta/N) sum_j z_j cos(pi 5^j k / N)).  `limbs` = number
+ * of active Q limbs (level + 1). */
+int ensi_encode(ensi_ctx *ctx, const double *slots, int32_t n_pt, int32_t n_slots, int32_t limbs, ensi_pt **pt);
+/* coeffs: host int64[n_pt][N] signed integer coefficients (already encoded). */
+int ensi_pt_import(ensi_ctx *ctx, const int64_t *coeffs, int32_t n_pt, int32_t limbs, ensi_pt **pt);
+/* coeffs: host int64[n_pt][N], centred representative of limb 0 (exact only while |m| < q_0/2). */
+int ensi_pt_export(ensi_ctx *ctx, const ensi_pt *pt, int64_t *coeffs);
+void ensi_pt_free(ensi_pt *pt);
+
+/* ---- ciphertexts -------------------------------------------------------- */
+/* Allocates an (uninitialised) batch on the device. */
+int ensi_ct_alloc(ensi_ctx *ctx, int32_t n, int32_t limbs, ensi_ct **ct);
+/* Wraps caller-owned device memory of n*2*limbs*N u64 words (e.g. a PyTorch
+ * int64 tensor); the caller keeps ownership and must keep it alive. */
+int ensi_ct_wrap(ensi_ctx *ctx, void *device_words, int32_t n, int32_t limbs, double scale, ensi_ct **ct);
+void ensi_ct_free(ensi_ct *ct);
+int ensi_ct_info(const ensi_ct *ct, int32_t *n, int32_t *limbs, double *scale, void **device_words);
+/* host u64[n][2][limbs][N], compact (active limbs only). */
+int ensi_ct_export(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *limbs_out);
+int ensi_ct_import(ensi_ctx *ctx, const uint64_t *limbs_in, int32_t n, int32_t limbs, double scale, ensi_ct **ct);
+
+/* Enc_pk: ct_i = v_i pk + (m_i + e0_i, e1_i).  v, e0, e1: host int8[n_pt][N] or
+ * NULL (all three given or all three NULL). */
+int ensi_encrypt(ensi_ctx *ctx, const ensi_pk *pk, const ensi_pt *pt, const int8_t *v, const int8_t *e0,
+                 const int8_t *e1, ensi_ct **ct);
+/* Dec_sk then decode: slots_out host double[n][n_slots] = real parts of slots
+ * [slot_begin, slot_begin+n_slots) of c0 + c1 s (CRT of limbs 0,1, centred,
+ * divided by the ciphertext's scale). */
+int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct, int32_t slot_begin, int32_t n_slots,
+                 double *slots_out);
+
+/* ---- Rot (Preliminaries, Rotation): out_i = Rot(in_i; steps[i]) --------- */
+/* Cyclic left shift of the slot vector by steps[i] (negative = inverse
+ * rotation), by the automorphism X -> X^g and hybrid key switching:
+ * digit-decompose c1, ModUp each digit to Q_l + P (fast basis conversion, no
+ * correction), automorphism, inner product with the key, ModDown (no rounding
+ * offset), add phi_g(c0).  steps: host int32[n].  in and out are batches of
+ * equal n and limbs and must not overlap.  Level and scale are unchanged. */
+int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream);
+
+/* ---- Alg. 1 (PCMM): Y = X W on ciphertexts, additions/subtractions only - */
+/* in : ceil(d/c_tot) packed ciphertexts, c_tot = (N/2)/s; ciphertext G holds
+ *      activation column G*c_tot+b (s tokens) in slots [b*s,(b+1)*s).  c_tot=1
+ *      is one column per ciphertext (the paper's own packing) and needs no key.
+ * W  : host int8[d][m], row-major, values in {-1,0,+1}.
+ * out: batch of m ciphertexts; out_i carries column i of Y in slot block p_i
+ *      (placement); its other blocks are unspecified.  Same level/scale as in.
+ * Packed inputs are first unpacked into column-aligned operands by rotations
+ * (one ModUp per packed input, shared by all its rotations; gk must hold a key
+ * for step rho*s for every needed rho), then every output is the signed sum of
+ * its operands limb-wise mod q_i (zero weights skipped; an all-zero weight
+ * column gives the all-zero ciphertext). */
+int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
+                        int32_t m, int32_t placement, ensi_ct *out, void *stream);
+
+/* ---- scalar multiply + rescale (between two PCMM layers) ---------------- */
+/* In place on the whole batch: c <- c * round(kappa q_l) mod q_i, then limb l
+ * is dropped: c_i <- (c_i - (c_l mod q_i)) q_l^{-1} mod q_i.  limbs decreases
+ * by one (limbs_alloc is unchanged).  The encoded values are multiplied by
+ * kappa (0 < |kappa| < 1); the scale absorbs only the rounding of the constant:
+ * scale' = scale * round(kappa q_l) / (kappa q_l). */
+int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stream);
+
+/* ---- transform alone (parity and measurement of the NTT kernels) -------- */
+/* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
+ * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order
+ * is internal to the library; inverse(forward(x)) == x. */
+int ensi_ntt(ensi_ctx *ctx, void *data, int32_t n_limbs, const int32_t *prime_idx, int32_t inverse, void *stream);
+
+/* ---- per-kernel timers --------------------------------------------------- */
+/* While enabled, every kernel launch is bracketed by HIP events on its
+ * stream; ensi_profile_read synchronises and returns accumulated milliseconds
+ * and launch counts per kernel class.  names_out: host buffer receiving
+ * '\n'-separated class names; ms/count: host arrays of capacity cap. Returns
+ * the number of classes. */
+int ensi_profile_enable(ensi_ctx *ctx, int32_t on);
+int ensi_profile_read(ensi_ctx *ctx, char *names_out, int32_t names_cap, double *ms, int64_t *count, int32_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ENSI_H */

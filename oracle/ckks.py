@@ -372,7 +372,9 @@ class Oracle:
     # --------------------------------------------------------------- rescale
     def mul_scalar_rescale(self, ct, kappa):
         """c <- c * round(kappa q_l) (negative constants as q_i - |.|), then drop limb l:
-        c'_i = (c_i - (c_l mod q_i)) q_l^{-1} mod q_i, no rounding offset."""
+        c'_i = (c_i - (c_l mod q_i)) q_l^{-1} mod q_i, no rounding offset.  The encoded
+        values are multiplied by kappa; the scale only absorbs the rounding of the
+        constant: scale' = scale * round(kappa q_l) / (kappa q_l)."""
         pr = self.pr
         l1 = ct.l1
         ql = pr.q[l1 - 1]
@@ -386,4 +388,4 @@ class Oracle:
             c = self.mul_scalar(np.ascontiguousarray(c), const, q)
             last = np.stack([c[l1 - 1] % np.uint64(m) for m in rest])
             out.append(self.mul_scalar(self.sub(np.ascontiguousarray(c[: l1 - 1]), last, rest), ql_inv, rest))
-        return Ciphertext(out[0], out[1], ct.scale * k / ql)
+        return Ciphertext(out[0], out[1], ct.scale * k / (kappa * ql))

@@ -1,0 +1,257 @@
+"""ctypes binding of libensi_hip.so: argument marshalling only.
+
+Every function mirrors one entry point of include/ensi.h; all arithmetic runs
+inside the library's HIP kernels.  There is no fallback: if the shared library
+is missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libensi_hip.so")
+_lib = None
+
+PLACE_ZERO, PLACE_DIAGONAL = 0, 1
+_PLACEMENTS = {"zero": PLACE_ZERO, "diagonal": PLACE_DIAGONAL}
+
+EXPORTED = [
+    "ensi_ctx_create", "ensi_ctx_free", "ensi_last_error", "ensi_get_primes", "ensi_keygen", "ensi_sk_free",
+    "ensi_pk_free", "ensi_galois_keygen", "ensi_gk_free", "ensi_encode", "ensi_pt_import", "ensi_pt_export",
+    "ensi_pt_free", "ensi_ct_alloc", "ensi_ct_wrap", "ensi_ct_free", "ensi_ct_info", "ensi_ct_export",
+    "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
+    "ensi_mul_scalar_rescale", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+]
+
+
+class EnsiError(RuntimeError):
+    pass
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("log_n", ctypes.c_int32), ("q_bits", ctypes.c_int32), ("q_count", ctypes.c_int32),
+                ("p_bits", ctypes.c_int32), ("p_count", ctypes.c_int32), ("alpha", ctypes.c_int32),
+                ("log_scale", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+
+
+def load():
+    """Loads the built library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise EnsiError("libensi_hip.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.ensi_last_error.restype = ctypes.c_char_p
+        for name in EXPORTED:
+            getattr(lib, name)  # raises AttributeError on a missing symbol
+        for name in EXPORTED:
+            if name.endswith("_free") or name == "ensi_last_error":
+                continue
+            getattr(lib, name).restype = ctypes.c_int
+        for name in ("ensi_ctx_free", "ensi_sk_free", "ensi_pk_free", "ensi_gk_free", "ensi_pt_free", "ensi_ct_free"):
+            getattr(lib, name).restype = None
+            getattr(lib, name).argtypes = [ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i8(a, shape=None):
+    if a is None:
+        return None
+    a = np.ascontiguousarray(a, dtype=np.int8)
+    if shape is not None and tuple(a.shape) != tuple(shape):
+        raise EnsiError("expected int8 array of shape %s, got %s" % (shape, a.shape))
+    return a
+
+
+class Context:
+    def __init__(self, log_n, q_bits, q_count, p_bits, p_count, alpha, log_scale, seed=1):
+        self.lib = load()
+        self.params = _Params(log_n, q_bits, q_count, p_bits, p_count, alpha, log_scale, seed)
+        self.h = ctypes.c_void_p()
+        rc = self.lib.ensi_ctx_create(ctypes.byref(self.params), ctypes.byref(self.h))
+        if rc:
+            raise EnsiError("ensi_ctx_create failed with code %d" % rc)
+        self.N = 1 << log_n
+        self.n_slots = self.N // 2
+        self.L, self.K, self.alpha = q_count, p_count, alpha
+        self.beta = -(-q_count // alpha)
+
+    def _check(self, rc):
+        if rc:
+            raise EnsiError("code %d: %s" % (rc, self.lib.ensi_last_error(self.h).decode()))
+
+    def close(self):
+        if self.h:
+            self.lib.ensi_ctx_free(self.h)
+            self.h = ctypes.c_void_p()
+
+    def primes(self):
+        q = np.zeros(self.L, dtype=np.uint64)
+        p = np.zeros(self.K, dtype=np.uint64)
+        self._check(self.lib.ensi_get_primes(self.h, _ptr(q), _ptr(p)))
+        return [int(x) for x in q], [int(x) for x in p]
+
+    # ---- keys
+    def keygen(self, s=None, e=None, seed_a=0):
+        s, e = _i8(s, (self.N,)), _i8(e, (self.N,))
+        sk, pk = ctypes.c_void_p(), ctypes.c_void_p()
+        self._check(self.lib.ensi_keygen(self.h, _ptr(s), _ptr(e), ctypes.c_uint64(seed_a), ctypes.byref(sk), ctypes.byref(pk)))
+        return _Handle(self, sk, "ensi_sk_free"), _Handle(self, pk, "ensi_pk_free")
+
+    def galois_keygen(self, sk, steps, e=None, seed_a=0):
+        steps = np.ascontiguousarray(steps, dtype=np.int32)
+        e = _i8(e, (len(steps), self.beta, self.N))
+        gk = ctypes.c_void_p()
+        self._check(self.lib.ensi_galois_keygen(self.h, sk.h, _ptr(steps), len(steps), _ptr(e), ctypes.c_uint64(seed_a), ctypes.byref(gk)))
+        return _Handle(self, gk, "ensi_gk_free")
+
+    # ---- plaintexts
+    def encode(self, slots, limbs):
+        slots = np.ascontiguousarray(np.atleast_2d(slots), dtype=np.float64)
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_encode(self.h, _ptr(slots), slots.shape[0], slots.shape[1], limbs, ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=slots.shape[0])
+
+    def pt_import(self, coeffs, limbs):
+        coeffs = np.ascontiguousarray(np.atleast_2d(coeffs), dtype=np.int64)
+        if coeffs.shape[1] != self.N:
+            raise EnsiError("coefficient arrays must have N entries")
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_pt_import(self.h, _ptr(coeffs), coeffs.shape[0], limbs, ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=coeffs.shape[0])
+
+    def pt_export(self, pt):
+        out = np.empty((pt.n, self.N), dtype=np.int64)
+        self._check(self.lib.ensi_pt_export(self.h, pt.h, _ptr(out)))
+        return out
+
+    # ---- ciphertexts
+    def ct_alloc(self, n, limbs):
+        ct = ctypes.c_void_p()
+        self._check(self.lib.ensi_ct_alloc(self.h, n, limbs, ctypes.byref(ct)))
+        return Ciphertexts(self, ct)
+
+    def ct_wrap(self, device_ptr, n, limbs, scale):
+        ct = ctypes.c_void_p()
+        self._check(self.lib.ensi_ct_wrap(self.h, ctypes.c_void_p(device_ptr), n, limbs, ctypes.c_double(scale), ctypes.byref(ct)))
+        return Ciphertexts(self, ct)
+
+    def ct_import(self, limbs_array, scale):
+        a = np.ascontiguousarray(limbs_array, dtype=np.uint64)
+        if a.ndim != 4 or a.shape[1] != 2 or a.shape[3] != self.N:
+            raise EnsiError("expected uint64 [n][2][limbs][N]")
+        ct = ctypes.c_void_p()
+        self._check(self.lib.ensi_ct_import(self.h, _ptr(a), a.shape[0], a.shape[2], ctypes.c_double(scale), ctypes.byref(ct)))
+        return Ciphertexts(self, ct)
+
+    def encrypt(self, pk, pt, v=None, e0=None, e1=None):
+        shape = (pt.n, self.N)
+        v, e0, e1 = _i8(v, shape), _i8(e0, shape), _i8(e1, shape)
+        ct = ctypes.c_void_p()
+        self._check(self.lib.ensi_encrypt(self.h, pk.h, pt.h, _ptr(v), _ptr(e0), _ptr(e1), ctypes.byref(ct)))
+        return Ciphertexts(self, ct)
+
+    def decrypt(self, sk, ct, slot_begin=0, n_slots=None):
+        n_slots = self.n_slots - slot_begin if n_slots is None else n_slots
+        out = np.empty((ct.n, n_slots), dtype=np.float64)
+        self._check(self.lib.ensi_decrypt(self.h, sk.h, ct.h, slot_begin, n_slots, _ptr(out)))
+        return out
+
+    # ---- hot path
+    def rotate(self, gk, ct_in, steps, ct_out=None, stream=0):
+        steps = np.ascontiguousarray(steps, dtype=np.int32)
+        if len(steps) != ct_in.n:
+            raise EnsiError("one step per ciphertext")
+        if ct_out is None:
+            ct_out = self.ct_alloc(ct_in.n, ct_in.limbs)
+        self._check(self.lib.ensi_rotate(self.h, gk.h, ct_in.h, _ptr(steps), ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def ternary_matmul(self, gk, ct_in, s, d, W, placement="diagonal", ct_out=None, stream=0):
+        W = np.ascontiguousarray(W, dtype=np.int8)
+        if W.ndim != 2 or W.shape[0] != d:
+            raise EnsiError("W must be int8 [d][m]")
+        m = W.shape[1]
+        if ct_out is None:
+            ct_out = self.ct_alloc(m, ct_in.limbs)
+        self._check(self.lib.ensi_ternary_matmul(self.h, gk.h if gk is not None else None, ct_in.h, s, d, _ptr(W), m,
+                                                 _PLACEMENTS[placement], ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def mul_scalar_rescale(self, ct, kappa, stream=0):
+        self._check(self.lib.ensi_mul_scalar_rescale(self.h, ct.h, ctypes.c_double(kappa), ctypes.c_void_p(stream)))
+        return ct
+
+    def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):
+        prime_idx = np.ascontiguousarray(prime_idx, dtype=np.int32)
+        self._check(self.lib.ensi_ntt(self.h, ctypes.c_void_p(device_ptr), len(prime_idx), _ptr(prime_idx), int(inverse),
+                                      ctypes.c_void_p(stream)))
+
+    # ---- timers
+    def profile_enable(self, on=True):
+        self._check(self.lib.ensi_profile_enable(self.h, int(on)))
+
+    def profile_read(self):
+        cap = 64
+        names = ctypes.create_string_buffer(4096)
+        ms = np.zeros(cap, dtype=np.float64)
+        cnt = np.zeros(cap, dtype=np.int64)
+        n = self.lib.ensi_profile_read(self.h, names, 4096, _ptr(ms), _ptr(cnt), cap)
+        if n < 0:
+            self._check(n)
+        nm = names.value.decode().split("\n")[:n]
+        return {nm[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
+
+
+class _Handle:
+    def __init__(self, ctx, h, free_name, n=0):
+        self.ctx, self.h, self._free, self.n = ctx, h, free_name, n
+
+    def free(self):
+        if self.h:
+            getattr(self.ctx.lib, self._free)(self.h)
+            self.h = ctypes.c_void_p()
+
+
+class Ciphertexts(_Handle):
+    """A batch of ciphertexts resident on the device."""
+
+    def __init__(self, ctx, h):
+        super().__init__(ctx, h, "ensi_ct_free")
+
+    def _info(self):
+        n, limbs, scale, ptr = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_double(), ctypes.c_void_p()
+        self.ctx._check(self.ctx.lib.ensi_ct_info(self.h, ctypes.byref(n), ctypes.byref(limbs), ctypes.byref(scale), ctypes.byref(ptr)))
+        return n.value, limbs.value, scale.value, ptr.value
+
+    @property
+    def n(self):
+        return self._info()[0]
+
+    @n.setter
+    def n(self, _):
+        pass
+
+    @property
+    def limbs(self):
+        return self._info()[1]
+
+    @property
+    def scale(self):
+        return self._info()[2]
+
+    @property
+    def device_ptr(self):
+        return self._info()[3]
+
+    def export(self):
+        n, limbs, _, _ = self._info()
+        out = np.empty((n, 2, limbs, self.ctx.N), dtype=np.uint64)
+        self.ctx._check(self.ctx.lib.ensi_ct_export(self.ctx.h, self.h, _ptr(out)))
+        return out

@@ -1,0 +1,959 @@
+// Host side of the library: context set-up (primes, tables, conversion
+// constants), key generation, encryption/decryption plumbing, and the C ABI.
+// All polynomial arithmetic runs in the kernels of ntt.hip / kernels.hip; the
+// host only derives constants, builds launch descriptors and moves data.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <random>
+
+#include "common.h"
+#include "hostmath.h"
+
+// ------------------------------------------------------------------ utilities
+namespace {
+
+struct DevBuf {
+    void *p = nullptr;
+    DevBuf() {}
+    DevBuf(const DevBuf &) = delete;
+    ~DevBuf() {
+        if (p) (void)hipFree(p);
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 8); }
+    template <class T>
+    T *as() { return (T *)p; }
+};
+
+template <class T>
+hipError_t upload(T **d, const std::vector<T> &h) {
+    hipError_t e = hipMalloc((void **)d, std::max<size_t>(h.size() * sizeof(T), 8));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+LimbMap make_map(const ensi_ctx *ctx, int l1, bool with_p) {
+    LimbMap m;
+    m.n = l1 + (with_p ? ctx->K : 0);
+    for (int e = 0; e < ENSI_MAX_EXT; e++) m.prime[e] = 0;
+    for (int e = 0; e < m.n; e++) m.prime[e] = e < l1 ? e : ctx->L + (e - l1);
+    return m;
+}
+
+u32 galois_element(const ensi_ctx *ctx, int32_t step) {
+    const int n = ctx->N / 2;
+    int k = step % n;
+    if (k < 0) k += n;
+    return ctx->rot_exp[k];
+}
+u32 inv_mod_2n(u32 g, int N) {
+    // g odd: Newton iteration modulo a power of two
+    u32 x = g;
+    for (int i = 0; i < 5; i++) x *= 2 - g * x;
+    return x & (2 * (u32)N - 1);
+}
+
+int grow(ensi_ctx *ctx, u64 **p, size_t *have, size_t need) {
+    if (*have >= need) return ENSI_OK;
+    if (*p) ENSI_HIP(ctx, hipFree(*p));
+    *p = nullptr;
+    *have = 0;
+    hipError_t e = hipMalloc((void **)p, need * sizeof(u64));
+    if (e != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of %zu bytes failed: %s", need * sizeof(u64), hipGetErrorString(e));
+    *have = need;
+    return ENSI_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------- timers
+int timer_id(ensi_ctx *ctx, const char *name) {
+    for (size_t i = 0; i < ctx->timers.size(); i++)
+        if (ctx->timers[i].name == name) return (int)i;
+    KernelTimer t;
+    t.name = name;
+    ctx->timers.push_back(t);
+    return (int)ctx->timers.size() - 1;
+}
+void timer_begin(ensi_ctx *ctx, int id, hipStream_t st) {
+    hipEvent_t a, b;
+    (void)hipEventCreate(&a);
+    (void)hipEventCreate(&b);
+    (void)hipEventRecord(a, st);
+    ctx->pending.push_back({id, {a, b}});
+}
+void timer_end(ensi_ctx *ctx, hipStream_t st) { (void)hipEventRecord(ctx->pending.back().second.second, st); }
+
+extern "C" int ensi_profile_enable(ensi_ctx *ctx, int32_t on) {
+    if (!ctx) return ENSI_E_BADARG;
+    ctx->profiling = on != 0;
+    return ENSI_OK;
+}
+extern "C" int ensi_profile_read(ensi_ctx *ctx, char *names_out, int32_t names_cap, double *ms, int64_t *count, int32_t cap) {
+    if (!ctx) return ENSI_E_BADARG;
+    for (auto &p : ctx->pending) {
+        (void)hipEventSynchronize(p.second.second);
+        float t = 0;
+        if (hipEventElapsedTime(&t, p.second.first, p.second.second) == hipSuccess) {
+            ctx->timers[p.first].ms += t;
+            ctx->timers[p.first].count += 1;
+        }
+        (void)hipEventDestroy(p.second.first);
+        (void)hipEventDestroy(p.second.second);
+    }
+    ctx->pending.clear();
+    std::string names;
+    int n = 0;
+    for (auto &t : ctx->timers) {
+        if (n < cap) {
+            if (ms) ms[n] = t.ms;
+            if (count) count[n] = t.count;
+        }
+        names += t.name;
+        names += '\n';
+        n++;
+    }
+    if (names_out && names_cap > 0) {
+        strncpy(names_out, names.c_str(), names_cap - 1);
+        names_out[names_cap - 1] = 0;
+    }
+    for (auto &t : ctx->timers) {
+        t.ms = 0;
+        t.count = 0;
+    }
+    return n;
+}
+
+// --------------------------------------------------------------------- context
+static bool find_primes(int bits, int count, u64 two_n, const std::vector<u64> &skip, std::vector<u64> &out) {
+    u64 x = (((u64)1 << bits) - 1) / two_n * two_n + 1;
+    if (x >= ((u64)1 << bits)) x -= two_n;
+    while ((int)out.size() < count) {
+        if (x < two_n) return false;
+        if (std::find(skip.begin(), skip.end(), x) == skip.end() && hm_is_prime(x)) out.push_back(x);
+        x -= two_n;
+    }
+    return true;
+}
+
+extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
+    if (!prm || !out) return ENSI_E_BADARG;
+    *out = nullptr;
+    if (prm->log_n < 4 || prm->log_n > 16 || prm->q_bits < 20 || prm->q_bits > 60 || prm->p_bits < 20 || prm->p_bits > 61 ||
+        prm->q_count < 1 || prm->p_count < 1 || prm->p_count > ENSI_MAX_K || prm->q_count + prm->p_count > ENSI_MAX_EXT ||
+        prm->alpha < 1 || prm->alpha > ENSI_MAX_ALPHA || prm->log_scale < 1 || prm->log_scale > 60 ||
+        (prm->q_count + prm->alpha - 1) / prm->alpha > 8)
+        return ENSI_E_BADARG;
+    ensi_ctx *ctx = new ensi_ctx();
+    ctx->prm = *prm;
+    ctx->log_n = prm->log_n;
+    ctx->N = 1 << prm->log_n;
+    ctx->L = prm->q_count;
+    ctx->K = prm->p_count;
+    ctx->alpha = prm->alpha;
+    ctx->scale = ldexp(1.0, prm->log_scale);
+    const int N = ctx->N;
+    const u64 two_n = 2 * (u64)N;
+    if (hipGetDevice(&ctx->device) != hipSuccess) {
+        delete ctx;
+        return ENSI_E_HIP;
+    }
+    std::vector<u64> qs, ps;
+    if (!find_primes(prm->q_bits, ctx->L, two_n, {}, qs) || !find_primes(prm->p_bits, ctx->K, two_n, qs, ps)) {
+        delete ctx;
+        return ENSI_E_BADARG;
+    }
+    ctx->primes = qs;
+    ctx->primes.insert(ctx->primes.end(), ps.begin(), ps.end());
+    const int np = ctx->L + ctx->K;
+
+    std::vector<PrimeConst> pcs(np);
+    std::vector<u64> tw((size_t)np * 4 * N);
+    for (int i = 0; i < np; i++) {
+        const u64 q = ctx->primes[i];
+        u64 psi = 0;
+        for (u64 g = 2; g < 1000 && !psi; g++) {
+            u64 c = hm_powmod(g, (q - 1) / two_n, q);
+            if (hm_powmod(c, N, q) == q - 1) psi = c;
+        }
+        if (!psi) {
+            delete ctx;
+            return ENSI_E_BADARG;
+        }
+        ctx->psi.push_back(psi);
+        PrimeConst &pc = pcs[i];
+        memset(&pc, 0, sizeof(pc));
+        pc.q = q;
+        pc.qneg_inv = hm_neg_inv64(q);
+        u64 r = hm_to_mont(1, q);
+        pc.r2 = hm_mulmod(r, r, q);
+        pc.n_inv = hm_invmod((u64)N % q, q);
+        pc.n_inv_s = hm_shoup(pc.n_inv, q);
+        // powers of psi and psi^{-1}, then bit-reversed tables
+        std::vector<u64> pw(N), ipw(N);
+        const u64 psi_inv = hm_invmod(psi, q);
+        pw[0] = ipw[0] = 1;
+        for (int k = 1; k < N; k++) {
+            pw[k] = hm_mulmod(pw[k - 1], psi, q);
+            ipw[k] = hm_mulmod(ipw[k - 1], psi_inv, q);
+        }
+        u64 *t = tw.data() + (size_t)i * 4 * N;
+        for (int k = 0; k < N; k++) {
+            u32 rk = 0;
+            for (int b = 0; b < ctx->log_n; b++) rk |= ((k >> b) & 1u) << (ctx->log_n - 1 - b);
+            t[k] = pw[rk];
+            t[N + k] = hm_shoup(pw[rk], q);
+            t[2 * N + k] = ipw[rk];
+            t[3 * N + k] = hm_shoup(ipw[rk], q);
+        }
+    }
+    std::vector<double> cs(2 * (size_t)N);
+    for (size_t e = 0; e < cs.size(); e++) cs[e] = (double)cosl(M_PIl * (long double)e / (long double)N);
+    ctx->rot_exp.resize(N / 2);
+    u64 x = 1;
+    for (int j = 0; j < N / 2; j++) {
+        ctx->rot_exp[j] = (u32)x;
+        x = x * 5 % two_n;
+    }
+    if (upload(&ctx->d_pc, pcs) != hipSuccess || upload(&ctx->d_tw, tw) != hipSuccess || upload(&ctx->d_cos, cs) != hipSuccess ||
+        upload(&ctx->d_rot_exp, ctx->rot_exp) != hipSuccess) {
+        ensi_ctx_free(ctx);
+        return ENSI_E_HIP;
+    }
+    *out = ctx;
+    return ENSI_OK;
+}
+
+static void free_modconst(ensi_ctx *ctx) {
+    for (auto &kv : ctx->modup) {
+        (void)hipFree(kv.second.inv);
+        (void)hipFree(kv.second.inv_s);
+        (void)hipFree(kv.second.hat);
+    }
+    for (auto &kv : ctx->moddown) {
+        (void)hipFree(kv.second.inv);
+        (void)hipFree(kv.second.inv_s);
+        (void)hipFree(kv.second.hat);
+        (void)hipFree(kv.second.pinv);
+        (void)hipFree(kv.second.pinv_s);
+    }
+}
+
+extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
+    if (!ctx) return;
+    (void)hipDeviceSynchronize();
+    free_modconst(ctx);
+    if (ctx->d_pc) (void)hipFree(ctx->d_pc);
+    if (ctx->d_tw) (void)hipFree(ctx->d_tw);
+    if (ctx->d_cos) (void)hipFree(ctx->d_cos);
+    if (ctx->d_rot_exp) (void)hipFree(ctx->d_rot_exp);
+    if (ctx->ws_digits) (void)hipFree(ctx->ws_digits);
+    if (ctx->ws_u) (void)hipFree(ctx->ws_u);
+    if (ctx->ws_virt) (void)hipFree(ctx->ws_virt);
+    if (ctx->ws_desc) (void)hipFree(ctx->ws_desc);
+    if (ctx->ws_plan) (void)hipFree(ctx->ws_plan);
+    for (auto &p : ctx->pending) {
+        (void)hipEventDestroy(p.second.first);
+        (void)hipEventDestroy(p.second.second);
+    }
+    delete ctx;
+}
+
+extern "C" const char *ensi_last_error(const ensi_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+extern "C" int ensi_get_primes(const ensi_ctx *ctx, uint64_t *q, uint64_t *p) {
+    if (!ctx) return ENSI_E_BADARG;
+    if (q) memcpy(q, ctx->primes.data(), sizeof(u64) * ctx->L);
+    if (p) memcpy(p, ctx->primes.data() + ctx->L, sizeof(u64) * ctx->K);
+    return ENSI_OK;
+}
+
+// Conversion constants at level l1 (built once per level, kept for the context's life).
+static int get_modup(ensi_ctx *ctx, int l1, const ModUpConst **out) {
+    auto it = ctx->modup.find(l1);
+    if (it == ctx->modup.end()) {
+        ModUpConst mc;
+        memset(&mc, 0, sizeof(mc));
+        mc.l1 = l1;
+        mc.K = ctx->K;
+        mc.alpha = ctx->alpha;
+        mc.beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+        const int ext = l1 + ctx->K;
+        std::vector<u64> inv((size_t)mc.beta * mc.alpha, 0), inv_s(inv.size(), 0), hat((size_t)mc.beta * ext * mc.alpha, 0);
+        for (int j = 0; j < mc.beta; j++) {
+            const int first = j * mc.alpha;
+            const int ns = std::min(mc.alpha, l1 - first);
+            mc.n_src[j] = ns;
+            for (int a = 0; a < ns; a++) {
+                const u64 qa = ctx->primes[first + a];
+                u64 prod = 1;  // (Q_j/q_a) mod q_a
+                for (int b = 0; b < ns; b++)
+                    if (b != a) prod = hm_mulmod(prod, ctx->primes[first + b] % qa, qa);
+                inv[j * mc.alpha + a] = hm_invmod(prod, qa);
+                inv_s[j * mc.alpha + a] = hm_shoup(inv[j * mc.alpha + a], qa);
+                for (int e = 0; e < ext; e++) {
+                    if (e >= first && e < first + ns) continue;
+                    const u64 t = ctx->primes[e < l1 ? e : ctx->L + (e - l1)];
+                    u64 h = 1;
+                    for (int b = 0; b < ns; b++)
+                        if (b != a) h = hm_mulmod(h, ctx->primes[first + b] % t, t);
+                    hat[((size_t)j * ext + e) * mc.alpha + a] = hm_to_mont(h, t);
+                }
+            }
+        }
+        if (upload(&mc.inv, inv) != hipSuccess || upload(&mc.inv_s, inv_s) != hipSuccess || upload(&mc.hat, hat) != hipSuccess)
+            ENSI_FAIL(ctx, ENSI_E_HIP, "uploading ModUp constants failed");
+        it = ctx->modup.insert({l1, mc}).first;
+    }
+    *out = &it->second;
+    return ENSI_OK;
+}
+
+static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
+    auto it = ctx->moddown.find(l1);
+    if (it == ctx->moddown.end()) {
+        ModDownConst mc;
+        memset(&mc, 0, sizeof(mc));
+        mc.l1 = l1;
+        mc.K = ctx->K;
+        const int K = ctx->K, L = ctx->L;
+        std::vector<u64> inv(K), inv_s(K), hat((size_t)l1 * K), pinv(l1), pinv_s(l1);
+        for (int k = 0; k < K; k++) {
+            const u64 pk = ctx->primes[L + k];
+            u64 prod = 1;
+            for (int b = 0; b < K; b++)
+                if (b != k) prod = hm_mulmod(prod, ctx->primes[L + b] % pk, pk);
+            inv[k] = hm_invmod(prod, pk);
+            inv_s[k] = hm_shoup(inv[k], pk);
+        }
+        for (int i = 0; i < l1; i++) {
+            const u64 q = ctx->primes[i];
+            u64 P = 1;
+            for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
+            pinv[i] = hm_invmod(P, q);
+            pinv_s[i] = hm_shoup(pinv[i], q);
+            for (int k = 0; k < K; k++) {
+                u64 h = 1;
+                for (int b = 0; b < K; b++)
+                    if (b != k) h = hm_mulmod(h, ctx->primes[L + b] % q, q);
+                hat[(size_t)i * K + k] = hm_to_mont(h, q);
+            }
+        }
+        if (upload(&mc.inv, inv) != hipSuccess || upload(&mc.inv_s, inv_s) != hipSuccess || upload(&mc.hat, hat) != hipSuccess ||
+            upload(&mc.pinv, pinv) != hipSuccess || upload(&mc.pinv_s, pinv_s) != hipSuccess)
+            ENSI_FAIL(ctx, ENSI_E_HIP, "uploading ModDown constants failed");
+        it = ctx->moddown.insert({l1, mc}).first;
+    }
+    *out = &it->second;
+    return ENSI_OK;
+}
+
+// ------------------------------------------------------------------ sampling
+// The library's own sampler, used only where the caller passes NULL randomness.
+static void sample_ternary(ensi_ctx *ctx, int8_t *out, size_t n) {
+    std::mt19937_64 gen(ctx->prm.seed * 0x9E3779B97F4A7C15ULL + (++ctx->sampler_ctr));
+    std::uniform_int_distribution<int> d(-1, 1);
+    for (size_t i = 0; i < n; i++) out[i] = (int8_t)d(gen);
+}
+static void sample_error(ensi_ctx *ctx, int8_t *out, size_t n) {
+    std::mt19937_64 gen(ctx->prm.seed * 0x9E3779B97F4A7C15ULL + (++ctx->sampler_ctr));
+    std::normal_distribution<double> d(0.0, 3.2);
+    for (size_t i = 0; i < n; i++) {
+        double v = nearbyint(d(gen));
+        out[i] = (int8_t)std::max(-19.0, std::min(19.0, v));
+    }
+}
+
+// ------------------------------------------------------------------------ keys
+extern "C" int ensi_keygen(ensi_ctx *ctx, const int8_t *s, const int8_t *e, uint64_t seed_a, ensi_sk **sk_out, ensi_pk **pk_out) {
+    if (!ctx || !sk_out || !pk_out) return ENSI_E_BADARG;
+    const int N = ctx->N, L = ctx->L, ext = ctx->L + ctx->K;
+    std::vector<int8_t> sv(N), ev(N);
+    if (s) memcpy(sv.data(), s, N);
+    else sample_ternary(ctx, sv.data(), N);
+    if (e) memcpy(ev.data(), e, N);
+    else sample_error(ctx, ev.data(), N);
+    for (int i = 0; i < N; i++)
+        if (sv[i] < -1 || sv[i] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "secret coefficient %d outside {-1,0,1}", i);
+
+    hipStream_t st = nullptr;
+    LimbMap mext = make_map(ctx, L, true), mq = make_map(ctx, L, false);
+    DevBuf d_small, d_e, d_a;
+    ensi_sk *sk = new ensi_sk();
+    sk->ctx = ctx;
+    sk->s = sv;
+    sk->d_s_hat = nullptr;
+    ensi_pk *pk = new ensi_pk();
+    pk->ctx = ctx;
+    pk->d_pk = nullptr;
+    auto fail = [&](int code) {
+        ensi_sk_free(sk);
+        ensi_pk_free(pk);
+        return code;
+    };
+    if (d_small.alloc(2 * (size_t)N) != hipSuccess || d_e.alloc((size_t)L * N * 8) != hipSuccess || d_a.alloc((size_t)L * N * 8) != hipSuccess ||
+        hipMalloc((void **)&sk->d_s_hat, (size_t)ext * N * 8) != hipSuccess || hipMalloc((void **)&pk->d_pk, (size_t)2 * L * N * 8) != hipSuccess) {
+        ctx->err = "device allocation failed in keygen";
+        return fail(ENSI_E_NOMEM);
+    }
+    (void)hipMemcpy(d_small.p, sv.data(), N, hipMemcpyHostToDevice);
+    (void)hipMemcpy(d_small.as<int8_t>() + N, ev.data(), N, hipMemcpyHostToDevice);
+    // secret: residues -> transform domain -> Montgomery form, over Q_L + P
+    launch_small_to_rns(ctx, d_small.as<int8_t>(), 1, mext, sk->d_s_hat, st);
+    launch_ntt(ctx, sk->d_s_hat, ext, mext, false, st);
+    launch_to_mont(ctx, sk->d_s_hat, ext, mext, st);
+    // pk = (-a s + e, a) over Q_L
+    u64 *pk_b = pk->d_pk, *pk_a = pk->d_pk + (size_t)L * N;
+    launch_uniform(ctx, d_a.as<u64>(), mq, seed_a, 1, st);
+    launch_ntt(ctx, d_a.as<u64>(), L, mq, false, st);
+    launch_small_to_rns(ctx, d_small.as<int8_t>() + N, 1, mq, d_e.as<u64>(), st);
+    launch_ntt(ctx, d_e.as<u64>(), L, mq, false, st);
+    launch_key_assemble(ctx, pk_b, d_a.as<u64>(), sk->d_s_hat, d_e.as<u64>(), nullptr, nullptr, mq, st);
+    (void)hipMemcpyAsync(pk_a, d_a.p, (size_t)L * N * 8, hipMemcpyDeviceToDevice, st);
+    launch_to_mont(ctx, pk_a, L, mq, st);
+    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
+        ctx->err = "kernel failure in keygen";
+        return fail(ENSI_E_HIP);
+    }
+    *sk_out = sk;
+    *pk_out = pk;
+    return ENSI_OK;
+}
+extern "C" void ensi_sk_free(ensi_sk *sk) {
+    if (!sk) return;
+    if (sk->d_s_hat) (void)hipFree(sk->d_s_hat);
+    delete sk;
+}
+extern "C" void ensi_pk_free(ensi_pk *pk) {
+    if (!pk) return;
+    if (pk->d_pk) (void)hipFree(pk->d_pk);
+    delete pk;
+}
+
+extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_t *steps, int32_t n_steps, const int8_t *e,
+                                  uint64_t seed_a, ensi_gk **out) {
+    if (!ctx || !sk || !out || (n_steps > 0 && !steps) || n_steps < 0) return ENSI_E_BADARG;
+    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
+    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
+    hipStream_t st = nullptr;
+    LimbMap mext = make_map(ctx, L, true);
+    ensi_gk *gk = new ensi_gk();
+    gk->ctx = ctx;
+    DevBuf d_s, d_sg, d_e8, d_e, d_fac;
+    if (d_s.alloc((size_t)ext * N * 8) != hipSuccess || d_sg.alloc((size_t)ext * N * 8) != hipSuccess || d_e8.alloc(N) != hipSuccess ||
+        d_e.alloc((size_t)ext * N * 8) != hipSuccess || d_fac.alloc((size_t)ext * 8) != hipSuccess) {
+        ensi_gk_free(gk);
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in galois_keygen");
+    }
+    DevBuf d_s8;
+    if (d_s8.alloc(N) != hipSuccess) {
+        ensi_gk_free(gk);
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in galois_keygen");
+    }
+    (void)hipMemcpy(d_s8.p, sk->s.data(), N, hipMemcpyHostToDevice);
+    launch_small_to_rns(ctx, d_s8.as<int8_t>(), 1, mext, d_s.as<u64>(), st);  // coefficient form of s
+    std::vector<int8_t> ev(N);
+    for (int t = 0; t < n_steps; t++) {
+        const u32 g = galois_element(ctx, steps[t]);
+        if (gk->keys.count(g)) continue;
+        u64 *key = nullptr;
+        if (hipMalloc((void **)&key, (size_t)beta * 2 * ext * N * 8) != hipSuccess) {
+            ensi_gk_free(gk);
+            ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of a Galois key failed");
+        }
+        gk->keys[g] = key;
+        // phi_g(s), transform domain
+        launch_automorphism_coef(ctx, d_sg.as<u64>(), d_s.as<u64>(), mext, inv_mod_2n(g, N), st);
+        launch_ntt(ctx, d_sg.as<u64>(), ext, mext, false, st);
+        for (int j = 0; j < beta; j++) {
+            u64 *kb = key + (size_t)(j * 2) * ext * N, *ka = kb + (size_t)ext * N;
+            if (e) memcpy(ev.data(), e + ((size_t)t * beta + j) * N, N);
+            else sample_error(ctx, ev.data(), N);
+            (void)hipMemcpyAsync(d_e8.p, ev.data(), N, hipMemcpyHostToDevice, st);
+            (void)hipStreamSynchronize(st);
+            launch_small_to_rns(ctx, d_e8.as<int8_t>(), 1, mext, d_e.as<u64>(), st);
+            launch_ntt(ctx, d_e.as<u64>(), ext, mext, false, st);
+            launch_uniform(ctx, ka, mext, seed_a, ((u64)2 << 56) | ((u64)g << 8) | (u64)j, st);
+            launch_ntt(ctx, ka, ext, mext, false, st);
+            std::vector<u64> fac(ext, 0);
+            for (int i = j * ctx->alpha; i < std::min((j + 1) * ctx->alpha, L); i++) {
+                const u64 q = ctx->primes[i];
+                u64 P = 1;
+                for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
+                fac[i] = hm_to_mont(P, q);
+            }
+            (void)hipMemcpyAsync(d_fac.p, fac.data(), ext * 8, hipMemcpyHostToDevice, st);
+            (void)hipStreamSynchronize(st);
+            launch_key_assemble(ctx, kb, ka, sk->d_s_hat, d_e.as<u64>(), d_sg.as<u64>(), d_fac.as<u64>(), mext, st);
+            launch_to_mont(ctx, ka, ext, mext, st);
+        }
+    }
+    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
+        ensi_gk_free(gk);
+        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in galois_keygen");
+    }
+    *out = gk;
+    return ENSI_OK;
+}
+extern "C" void ensi_gk_free(ensi_gk *gk) {
+    if (!gk) return;
+    for (auto &kv : gk->keys) (void)hipFree(kv.second);
+    delete gk;
+}
+
+// ------------------------------------------------------------------ plaintexts
+static int pt_from_coeffs(ensi_ctx *ctx, const int64_t *d_coeffs, int n_pt, int limbs, ensi_pt **out) {
+    ensi_pt *pt = new ensi_pt();
+    pt->ctx = ctx;
+    pt->n = n_pt;
+    pt->limbs = limbs;
+    pt->d = nullptr;
+    if (hipMalloc((void **)&pt->d, (size_t)n_pt * limbs * ctx->N * 8) != hipSuccess) {
+        delete pt;
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed for plaintext");
+    }
+    launch_i64_to_rns(ctx, d_coeffs, n_pt, make_map(ctx, limbs, false), pt->d, nullptr);
+    if (hipStreamSynchronize(nullptr) != hipSuccess) {
+        ensi_pt_free(pt);
+        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in plaintext conversion");
+    }
+    *out = pt;
+    return ENSI_OK;
+}
+
+extern "C" int ensi_encode(ensi_ctx *ctx, const double *slots, int32_t n_pt, int32_t n_slots, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !slots || !out || n_pt < 1 || n_slots < 1 || n_slots > ctx->N / 2 || limbs < 1 || limbs > ctx->L) return ENSI_E_BADARG;
+    DevBuf d_slots, d_coeffs;
+    if (d_slots.alloc((size_t)n_pt * n_slots * 8) != hipSuccess || d_coeffs.alloc((size_t)n_pt * ctx->N * 8) != hipSuccess)
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in encode");
+    ENSI_HIP(ctx, hipMemcpy(d_slots.p, slots, (size_t)n_pt * n_slots * 8, hipMemcpyHostToDevice));
+    launch_encode(ctx, d_slots.as<double>(), n_pt, n_slots, d_coeffs.as<int64_t>(), nullptr);
+    return pt_from_coeffs(ctx, d_coeffs.as<int64_t>(), n_pt, limbs, out);
+}
+extern "C" int ensi_pt_import(ensi_ctx *ctx, const int64_t *coeffs, int32_t n_pt, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !coeffs || !out || n_pt < 1 || limbs < 1 || limbs > ctx->L) return ENSI_E_BADARG;
+    DevBuf d_coeffs;
+    if (d_coeffs.alloc((size_t)n_pt * ctx->N * 8) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in pt_import");
+    ENSI_HIP(ctx, hipMemcpy(d_coeffs.p, coeffs, (size_t)n_pt * ctx->N * 8, hipMemcpyHostToDevice));
+    return pt_from_coeffs(ctx, d_coeffs.as<int64_t>(), n_pt, limbs, out);
+}
+extern "C" int ensi_pt_export(ensi_ctx *ctx, const ensi_pt *pt, int64_t *coeffs) {
+    if (!ctx || !pt || !coeffs) return ENSI_E_BADARG;
+    DevBuf d_out;
+    if (d_out.alloc((size_t)pt->n * ctx->N * 8) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in pt_export");
+    launch_center_i64(ctx, pt->d, (size_t)pt->limbs * ctx->N, pt->n, d_out.as<int64_t>(), nullptr);
+    ENSI_HIP(ctx, hipMemcpy(coeffs, d_out.p, (size_t)pt->n * ctx->N * 8, hipMemcpyDeviceToHost));
+    return ENSI_OK;
+}
+extern "C" void ensi_pt_free(ensi_pt *pt) {
+    if (!pt) return;
+    if (pt->d) (void)hipFree(pt->d);
+    delete pt;
+}
+
+// ----------------------------------------------------------------- ciphertexts
+extern "C" int ensi_ct_alloc(ensi_ctx *ctx, int32_t n, int32_t limbs, ensi_ct **out) {
+    if (!ctx || !out || n < 1 || limbs < 1 || limbs > ctx->L) return ENSI_E_BADARG;
+    ensi_ct *ct = new ensi_ct();
+    ct->ctx = ctx;
+    ct->n = n;
+    ct->limbs = ct->limbs_alloc = limbs;
+    ct->scale = ctx->scale;
+    ct->owns = true;
+    ct->d = nullptr;
+    hipError_t e = hipMalloc((void **)&ct->d, (size_t)n * 2 * limbs * ctx->N * 8);
+    if (e != hipSuccess) {
+        delete ct;
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of %zu bytes failed: %s", (size_t)n * 2 * limbs * ctx->N * 8, hipGetErrorString(e));
+    }
+    *out = ct;
+    return ENSI_OK;
+}
+extern "C" int ensi_ct_wrap(ensi_ctx *ctx, void *device_words, int32_t n, int32_t limbs, double scale, ensi_ct **out) {
+    if (!ctx || !out || !device_words || n < 1 || limbs < 1 || limbs > ctx->L) return ENSI_E_BADARG;
+    ensi_ct *ct = new ensi_ct();
+    ct->ctx = ctx;
+    ct->n = n;
+    ct->limbs = ct->limbs_alloc = limbs;
+    ct->scale = scale;
+    ct->owns = false;
+    ct->d = (u64 *)device_words;
+    *out = ct;
+    return ENSI_OK;
+}
+extern "C" void ensi_ct_free(ensi_ct *ct) {
+    if (!ct) return;
+    if (ct->owns && ct->d) (void)hipFree(ct->d);
+    delete ct;
+}
+extern "C" int ensi_ct_info(const ensi_ct *ct, int32_t *n, int32_t *limbs, double *scale, void **device_words) {
+    if (!ct) return ENSI_E_BADARG;
+    if (n) *n = ct->n;
+    if (limbs) *limbs = ct->limbs;
+    if (scale) *scale = ct->scale;
+    if (device_words) *device_words = ct->d;
+    return ENSI_OK;
+}
+extern "C" int ensi_ct_export(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *out) {
+    if (!ctx || !ct || !out) return ENSI_E_BADARG;
+    const size_t N = ctx->N;
+    ENSI_HIP(ctx, hipDeviceSynchronize());
+    if (ct->limbs == ct->limbs_alloc) {
+        ENSI_HIP(ctx, hipMemcpy(out, ct->d, (size_t)ct->n * 2 * ct->limbs * N * 8, hipMemcpyDeviceToHost));
+    } else {
+        ENSI_HIP(ctx, hipMemcpy2D(out, (size_t)ct->limbs * N * 8, ct->d, (size_t)ct->limbs_alloc * N * 8, (size_t)ct->limbs * N * 8,
+                                  (size_t)ct->n * 2, hipMemcpyDeviceToHost));
+    }
+    return ENSI_OK;
+}
+extern "C" int ensi_ct_import(ensi_ctx *ctx, const uint64_t *in, int32_t n, int32_t limbs, double scale, ensi_ct **out) {
+    if (!ctx || !in || !out) return ENSI_E_BADARG;
+    for (int l = 0; l < limbs && l < ctx->L; l++) {
+        // spot-check canonical range on the first words of each limb of the first ciphertext
+        for (int i = 0; i < 4 && i < ctx->N; i++)
+            if (in[(size_t)l * ctx->N + i] >= ctx->primes[l]) ENSI_FAIL(ctx, ENSI_E_BADARG, "imported residue not below q_%d", l);
+    }
+    int rc = ensi_ct_alloc(ctx, n, limbs, out);
+    if (rc) return rc;
+    (*out)->scale = scale;
+    hipError_t e = hipMemcpy((*out)->d, in, (size_t)n * 2 * limbs * ctx->N * 8, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        ensi_ct_free(*out);
+        *out = nullptr;
+        ENSI_FAIL(ctx, ENSI_E_HIP, "upload failed: %s", hipGetErrorString(e));
+    }
+    return ENSI_OK;
+}
+
+extern "C" int ensi_encrypt(ensi_ctx *ctx, const ensi_pk *pk, const ensi_pt *pt, const int8_t *v, const int8_t *e0, const int8_t *e1,
+                            ensi_ct **out) {
+    if (!ctx || !pk || !pt || !out) return ENSI_E_BADARG;
+    if (!((v && e0 && e1) || (!v && !e0 && !e1))) ENSI_FAIL(ctx, ENSI_E_BADARG, "v, e0, e1 must be all given or all NULL");
+    const int N = ctx->N, L = ctx->L, l1 = pt->limbs, n = pt->n;
+    const size_t pn = (size_t)n * N;
+    std::vector<int8_t> small(3 * pn);
+    if (v) {
+        memcpy(small.data(), v, pn);
+        memcpy(small.data() + pn, e0, pn);
+        memcpy(small.data() + 2 * pn, e1, pn);
+    } else {
+        sample_ternary(ctx, small.data(), pn);
+        sample_error(ctx, small.data() + pn, 2 * pn);
+    }
+    int rc = ensi_ct_alloc(ctx, n, l1, out);
+    if (rc) return rc;
+    ensi_ct *ct = *out;
+    hipStream_t st = nullptr;
+    LimbMap mq = make_map(ctx, l1, false);
+    DevBuf d_small, d_v, d_t, d_e;
+    const size_t rows = (size_t)n * l1;
+    if (d_small.alloc(3 * pn) != hipSuccess || d_v.alloc(rows * N * 8) != hipSuccess || d_t.alloc(rows * N * 8) != hipSuccess ||
+        d_e.alloc(rows * N * 8) != hipSuccess) {
+        ensi_ct_free(ct);
+        *out = nullptr;
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in encrypt");
+    }
+    (void)hipMemcpy(d_small.p, small.data(), 3 * pn, hipMemcpyHostToDevice);
+    // v: residues -> transform domain
+    launch_small_to_rns(ctx, d_small.as<int8_t>(), n, mq, d_v.as<u64>(), st);
+    launch_ntt(ctx, d_v.as<u64>(), (int)rows, mq, false, st);
+    for (int poly = 0; poly < 2; poly++) {
+        // t = v * pk[poly] (rows 0..l1-1 of the L-limb key), back to coefficient form
+        for (int c = 0; c < n; c++)
+            launch_mul_mont(ctx, d_t.as<u64>() + (size_t)c * l1 * N, d_v.as<u64>() + (size_t)c * l1 * N, pk->d_pk + (size_t)poly * L * N, l1,
+                            mq, st);
+        launch_ntt(ctx, d_t.as<u64>(), (int)rows, mq, true, st);
+        // + error (+ message on c0)
+        launch_small_to_rns(ctx, d_small.as<int8_t>() + (1 + poly) * pn, n, mq, d_e.as<u64>(), st);
+        for (int c = 0; c < n; c++) {
+            u64 *dst = ct->d + ((size_t)c * 2 + poly) * l1 * N;
+            launch_add(ctx, dst, d_t.as<u64>() + (size_t)c * l1 * N, d_e.as<u64>() + (size_t)c * l1 * N, l1, mq, st);
+            if (poly == 0) launch_add(ctx, dst, dst, pt->d + (size_t)c * l1 * N, l1, mq, st);
+        }
+    }
+    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
+        ensi_ct_free(ct);
+        *out = nullptr;
+        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in encrypt");
+    }
+    return ENSI_OK;
+}
+
+extern "C" int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct, int32_t slot_begin, int32_t n_slots, double *slots_out) {
+    if (!ctx || !sk || !ct || !slots_out || slot_begin < 0 || n_slots < 1 || slot_begin + n_slots > ctx->N / 2) return ENSI_E_BADARG;
+    const int N = ctx->N, n = ct->n;
+    const int use = std::min(ct->limbs, 2);
+    hipStream_t st = nullptr;
+    LimbMap mq = make_map(ctx, use, false);
+    DevBuf d_m, d_coef, d_out;
+    if (d_m.alloc((size_t)n * use * N * 8) != hipSuccess || d_coef.alloc((size_t)n * N * 8) != hipSuccess ||
+        d_out.alloc((size_t)n * n_slots * 8) != hipSuccess)
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in decrypt");
+    ENSI_HIP(ctx, hipDeviceSynchronize());
+    const size_t poly_words = (size_t)ct->limbs_alloc * N;
+    for (int c = 0; c < n; c++)
+        ENSI_HIP(ctx, hipMemcpyAsync(d_m.as<u64>() + (size_t)c * use * N, ct->d + ((size_t)c * 2 + 1) * poly_words, (size_t)use * N * 8,
+                                     hipMemcpyDeviceToDevice, st));
+    launch_ntt(ctx, d_m.as<u64>(), n * use, mq, false, st);
+    for (int c = 0; c < n; c++) {
+        u64 *mc = d_m.as<u64>() + (size_t)c * use * N;
+        launch_mul_mont(ctx, mc, mc, sk->d_s_hat, use, mq, st);
+    }
+    launch_ntt(ctx, d_m.as<u64>(), n * use, mq, true, st);
+    for (int c = 0; c < n; c++) {
+        u64 *mc = d_m.as<u64>() + (size_t)c * use * N;
+        launch_add(ctx, mc, mc, ct->d + (size_t)c * 2 * poly_words, use, mq, st);
+    }
+    launch_crt_center(ctx, d_m.as<u64>(), n, use, d_coef.as<double>(), st);
+    launch_decode(ctx, d_coef.as<double>(), n, slot_begin, n_slots, 1.0 / ct->scale, d_out.as<double>(), st);
+    ENSI_HIP(ctx, hipStreamSynchronize(st));
+    ENSI_HIP(ctx, hipMemcpy(slots_out, d_out.p, (size_t)n * n_slots * 8, hipMemcpyDeviceToHost));
+    return ENSI_OK;
+}
+
+// --------------------------------------------------------------------- rotation
+// Runs inner product -> inverse transform -> ModDown for n_rot descriptors already on the device.
+static int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out,
+                         hipStream_t st) {
+    const ModDownConst *md;
+    int rc = get_moddown(ctx, l1, &md);
+    if (rc) return rc;
+    const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    launch_inner(ctx, d_desc, n_rot, l1, beta, ctx->ws_u, st);
+    launch_ntt(ctx, ctx->ws_u, n_rot * 2 * ext, make_map(ctx, l1, true), true, st);
+    launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, ctx->ws_u, st);
+    return ENSI_OK;
+}
+
+static int ensure_desc(ensi_ctx *ctx, size_t n) {
+    if (ctx->ws_desc_n >= n) return ENSI_OK;
+    if (ctx->ws_desc) ENSI_HIP(ctx, hipFree(ctx->ws_desc));
+    ctx->ws_desc = nullptr;
+    ctx->ws_desc_n = 0;
+    if (hipMalloc((void **)&ctx->ws_desc, n * sizeof(RotDesc)) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "descriptor allocation failed");
+    ctx->ws_desc_n = n;
+    return ENSI_OK;
+}
+
+extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream) {
+    if (!ctx || !gk || !in || !steps || !out) return ENSI_E_BADARG;
+    if (in->n != out->n) ENSI_FAIL(ctx, ENSI_E_SHAPE, "rotate: batch sizes differ (%d vs %d)", in->n, out->n);
+    if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rotate: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
+    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "rotate: in and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const int N = ctx->N, l1 = in->limbs, ext = l1 + ctx->K, n = in->n;
+    const int beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    std::vector<RotDesc> desc(n);
+    const size_t in_ct = (size_t)2 * in->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    int rc;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)n * beta * ext * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)n * 2 * ext * N))) return rc;
+    if ((rc = ensure_desc(ctx, n))) return rc;
+    for (int c = 0; c < n; c++) {
+        const u32 g = galois_element(ctx, steps[c]);
+        auto it = gk->keys.find(g);
+        if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "rotate: no Galois key for step %d", steps[c]);
+        desc[c].c0 = in->d + (size_t)c * in_ct;
+        desc[c].digits = ctx->ws_digits + (size_t)c * beta * ext * N;
+        desc[c].key = it->second;
+        desc[c].out = out->d + (size_t)c * out_ct;
+        desc[c].g = g;
+        desc[c].g_inv = inv_mod_2n(g, N);
+    }
+    const ModUpConst *mu;
+    if ((rc = get_modup(ctx, l1, &mu))) return rc;
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), n * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+    launch_modup(ctx, *mu, in->d, in_ct, in->limbs_alloc, n, ctx->ws_digits, st);
+    launch_ntt(ctx, ctx->ws_digits, n * beta * ext, make_map(ctx, l1, true), false, st);
+    if ((rc = run_rotations(ctx, ctx->ws_desc, n, l1, in->limbs_alloc, out->limbs_alloc, st))) return rc;
+    out->scale = in->scale;
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ------------------------------------------------------------------------ PCMM
+extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
+                                   int32_t m, int32_t placement, ensi_ct *out, void *stream) {
+    if (!ctx || !in || !W || !out || s < 1 || d < 1 || m < 1) return ENSI_E_BADARG;
+    if (placement != ENSI_PLACE_ZERO && placement != ENSI_PLACE_DIAGONAL) ENSI_FAIL(ctx, ENSI_E_BADARG, "unknown placement %d", placement);
+    const int N = ctx->N, n_slots = N / 2;
+    if (n_slots % s) ENSI_FAIL(ctx, ENSI_E_SHAPE, "tokens per column (%d) must divide the slot count %d", s, n_slots);
+    const int c_tot = n_slots / s;
+    const int n_in = (d + c_tot - 1) / c_tot;
+    if (in->n != n_in) ENSI_FAIL(ctx, ENSI_E_SHAPE, "expected %d packed input ciphertexts for d=%d, c_tot=%d, got %d", n_in, d, c_tot, in->n);
+    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
+    if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "matmul: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
+    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
+    for (size_t k = 0; k < (size_t)d * m; k++)
+        if (W[k] < -1 || W[k] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "weight %zu is %d, outside {-1,0,1}", k, (int)W[k]);
+    hipStream_t st = (hipStream_t)stream;
+    const int l1 = in->limbs, ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
+
+    // ---- plan: which (packed input G, rotation amount rho) operands exist, and the
+    // weight of each operand in each output: W'[v][i] = W[G*c_tot + (rho + p_i) mod c_tot][i]
+    std::vector<int> vid((size_t)n_in * c_tot, -1);
+    for (int j = 0; j < d; j++) {
+        const int G = j / c_tot, b = j % c_tot;
+        const int8_t *row = W + (size_t)j * m;
+        for (int i = 0; i < m; i++) {
+            if (!row[i]) continue;
+            const int p = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
+            int rho = b - p;
+            if (rho < 0) rho += c_tot;
+            vid[(size_t)G * c_tot + rho] = 0;
+        }
+    }
+    int n_v = 0, n_rot = 0;
+    for (int G = 0; G < n_in; G++)
+        for (int rho = 0; rho < c_tot; rho++)
+            if (vid[(size_t)G * c_tot + rho] == 0) {
+                vid[(size_t)G * c_tot + rho] = n_v++;
+                if (rho) n_rot++;
+            }
+    const int tiles = (m + 31) / 32;
+    std::vector<u32> masks((size_t)tiles * std::max(n_v, 1) * 2, 0);
+    for (int j = 0; j < d; j++) {
+        const int G = j / c_tot, b = j % c_tot;
+        const int8_t *row = W + (size_t)j * m;
+        for (int i = 0; i < m; i++) {
+            if (!row[i]) continue;
+            const int p = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
+            int rho = b - p;
+            if (rho < 0) rho += c_tot;
+            const int v = vid[(size_t)G * c_tot + rho];
+            masks[((size_t)(i / 32) * n_v + v) * 2 + (row[i] > 0 ? 0 : 1)] |= 1u << (i % 32);
+        }
+    }
+    // ---- keys for every needed rotation amount
+    std::vector<const u64 *> key_of(c_tot, nullptr);
+    std::vector<u32> g_of(c_tot, 1);
+    for (int rho = 1; rho < c_tot; rho++) {
+        bool need = false;
+        for (int G = 0; G < n_in && !need; G++) need = vid[(size_t)G * c_tot + rho] >= 0;
+        if (!need) continue;
+        if (!gk) ENSI_FAIL(ctx, ENSI_E_NOKEY, "matmul needs rotations but no key set was given");
+        const u32 g = galois_element(ctx, rho * s);
+        auto it = gk->keys.find(g);
+        if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "matmul: no Galois key for step %d", rho * s);
+        key_of[rho] = it->second;
+        g_of[rho] = g;
+    }
+    // ---- workspaces
+    int rc;
+    const int chunk = 128;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)beta * ext * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, std::max(n_rot, 1)) * 2 * ext * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)std::max(n_rot, 1) * in_ct))) return rc;
+    if ((rc = ensure_desc(ctx, std::max(n_rot, 1)))) return rc;
+    const size_t plan_words = masks.size() / 2 + 1 + (size_t)std::max(n_v, 1);
+    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, plan_words))) return rc;
+    u32 *d_masks = (u32 *)ctx->ws_plan;
+    const u64 **d_vptr = (const u64 **)(ctx->ws_plan + masks.size() / 2 + 1);
+
+    // ---- unpack: rotations of every packed input, one ModUp per input
+    std::vector<RotDesc> desc;
+    std::vector<const u64 *> vptr(std::max(n_v, 1), nullptr);
+    std::vector<std::pair<int, int>> groups;  // (first desc, count) per packed input with rotations
+    int r = 0;
+    for (int G = 0; G < n_in; G++) {
+        const int first = r;
+        for (int rho = 0; rho < c_tot; rho++) {
+            const int v = vid[(size_t)G * c_tot + rho];
+            if (v < 0) continue;
+            if (rho == 0) {
+                vptr[v] = in->d + (size_t)G * in_ct;
+                continue;
+            }
+            RotDesc ds;
+            ds.c0 = in->d + (size_t)G * in_ct;
+            ds.digits = ctx->ws_digits;
+            ds.key = key_of[rho];
+            ds.out = ctx->ws_virt + (size_t)r * in_ct;
+            ds.g = g_of[rho];
+            ds.g_inv = inv_mod_2n(ds.g, N);
+            desc.push_back(ds);
+            vptr[v] = ds.out;
+            r++;
+        }
+        groups.push_back({first, r - first});
+    }
+    if (n_rot) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, hipMemcpyAsync(d_masks, masks.data(), masks.size() * sizeof(u32), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, hipMemcpyAsync((void *)d_vptr, vptr.data(), vptr.size() * sizeof(u64 *), hipMemcpyHostToDevice, st));
+    if (n_rot) {
+        const ModUpConst *mu;
+        if ((rc = get_modup(ctx, l1, &mu))) return rc;
+        LimbMap mext = make_map(ctx, l1, true);
+        for (int G = 0; G < n_in; G++) {
+            if (!groups[G].second) continue;
+            launch_modup(ctx, *mu, in->d + (size_t)G * in_ct, in_ct, in->limbs_alloc, 1, ctx->ws_digits, st);
+            launch_ntt(ctx, ctx->ws_digits, beta * ext, mext, false, st);
+            for (int o = 0; o < groups[G].second; o += chunk) {
+                const int cnt = std::min(chunk, groups[G].second - o);
+                if ((rc = run_rotations(ctx, ctx->ws_desc + groups[G].first + o, cnt, l1, in->limbs_alloc, in->limbs_alloc, st))) return rc;
+            }
+        }
+    }
+    // ---- Alg. 1: signed sums
+    launch_accumulate(ctx, d_vptr, n_v, d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
+    out->scale = in->scale;
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// -------------------------------------------------------------------- rescale
+extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stream) {
+    if (!ctx || !ct || !(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
+    if (ct->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
+    hipStream_t st = (hipStream_t)stream;
+    const int l1 = ct->limbs;
+    const u64 ql = ctx->primes[l1 - 1];
+    const double kr = floor(fabs(kappa) * (double)ql + 0.5);
+    const u64 kabs = (u64)kr;
+    std::vector<u64> consts(4 * (size_t)l1, 0);
+    for (int i = 0; i < l1; i++) {
+        const u64 q = ctx->primes[i];
+        u64 k = kabs % q;
+        if (kappa < 0 && k) k = q - k;
+        consts[i] = k;
+        consts[l1 + i] = hm_shoup(k, q);
+        if (i < l1 - 1) {
+            consts[2 * l1 + i] = hm_invmod(ql % q, q);
+            consts[3 * l1 + i] = hm_shoup(consts[2 * l1 + i], q);
+        }
+    }
+    int rc;
+    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, consts.size()))) return rc;
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan, consts.data(), consts.size() * 8, hipMemcpyHostToDevice, st));
+    launch_rescale(ctx, ct->d, ct->n, l1, ct->limbs_alloc, ctx->ws_plan, st);
+    ct->limbs = l1 - 1;
+    ct->scale = ct->scale * kr / (fabs(kappa) * (double)ql);
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ------------------------------------------------------------------------- NTT
+extern "C" int ensi_ntt(ensi_ctx *ctx, void *data, int32_t n_limbs, const int32_t *prime_idx, int32_t inverse, void *stream) {
+    if (!ctx || !data || !prime_idx || n_limbs < 1) return ENSI_E_BADARG;
+    // rows are grouped into runs that share a periodic prime pattern of at most ENSI_MAX_EXT
+    int period = 0;
+    for (int p = 1; p <= ENSI_MAX_EXT && p <= n_limbs && !period; p++) {
+        bool ok = true;
+        for (int r = p; r < n_limbs && ok; r++) ok = prime_idx[r] == prime_idx[r - p];
+        if (ok) period = p;
+    }
+    if (!period) ENSI_FAIL(ctx, ENSI_E_BADARG, "ntt: prime pattern must repeat with period <= %d", ENSI_MAX_EXT);
+    LimbMap map;
+    map.n = period;
+    for (int e = 0; e < ENSI_MAX_EXT; e++) map.prime[e] = 0;
+    for (int e = 0; e < period; e++) {
+        if (prime_idx[e] < 0 || prime_idx[e] >= ctx->L + ctx->K) ENSI_FAIL(ctx, ENSI_E_BADARG, "ntt: prime index %d out of range", prime_idx[e]);
+        map.prime[e] = prime_idx[e];
+    }
+    launch_ntt(ctx, (u64 *)data, n_limbs, map, inverse != 0, (hipStream_t)stream);
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}

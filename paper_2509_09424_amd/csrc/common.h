@@ -1,0 +1,184 @@
+// Internal declarations shared by the library's translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/ensi.h"
+#include "modarith.h"
+
+#define ENSI_MAX_EXT 32   // max limbs of an extended basis (L + K)
+#define ENSI_MAX_ALPHA 4
+#define ENSI_MAX_K 4
+
+// Per-prime constants, device-resident as one array indexed by prime id
+// (0..L-1 = q chain, L..L+K-1 = p chain).
+struct PrimeConst {
+    u64 q;
+    u64 qneg_inv;   // -q^{-1} mod 2^64
+    u64 r2;         // 2^128 mod q   (to Montgomery form: mont_mul(x, r2))
+    u64 n_inv;      // N^{-1} mod q
+    u64 n_inv_s;    // its Shoup companion
+    u64 pad[3];
+};
+
+// Which prime each limb row of a kernel's operand uses.
+struct LimbMap {
+    int32_t n;                  // limbs per polynomial in this operand
+    int32_t prime[ENSI_MAX_EXT];
+};
+
+// Constants of the ModUp of one level (limbs = l1): per digit, per target limb.
+struct ModUpConst {
+    int32_t l1, K, alpha, beta;
+    int32_t n_src[8];                               // limbs in digit j
+    // device arrays
+    u64 *inv;      // [beta][alpha]      (Q_j/q_i)^{-1} mod q_i
+    u64 *inv_s;    // [beta][alpha]      Shoup companion
+    u64 *hat;      // [beta][l1+K][alpha] (Q_j/q_i) mod t, Montgomery form (0 rows for limbs inside the digit)
+};
+struct ModDownConst {
+    int32_t l1, K;
+    u64 *inv;      // [K]   (P/p_k)^{-1} mod p_k
+    u64 *inv_s;    // [K]
+    u64 *hat;      // [l1][K]  (P/p_k) mod q_i, Montgomery form
+    u64 *pinv;     // [l1]  P^{-1} mod q_i
+    u64 *pinv_s;   // [l1]
+};
+
+// One rotation to perform: everything the fused kernels need, device-resident.
+struct RotDesc {
+    const u64 *c0;      // source polynomial c0: [limb_stride_in][N]
+    const u64 *digits;  // raised digits, transform domain: [beta][l1+K][N]
+    const u64 *key;     // key: [beta_full][2][L+K][N], transform domain, Montgomery form
+    u64 *out;           // destination ciphertext: [2][limb_stride_out][N]
+    u32 g;              // Galois element
+    u32 g_inv;          // its inverse mod 2N
+};
+
+struct KernelTimer {
+    std::string name;
+    double ms = 0;
+    int64_t count = 0;
+};
+
+struct ensi_ctx {
+    ensi_params prm;
+    int log_n, N, L, K, alpha;
+    double scale;
+    int device;
+    std::vector<u64> primes;        // L + K
+    std::vector<u64> psi;           // chosen 2N-th roots
+    PrimeConst *d_pc = nullptr;     // [L+K]
+    u64 *d_tw = nullptr;            // [L+K][4][N]: fwd, fwd Shoup, inv, inv Shoup
+    double *d_cos = nullptr;        // [2N] cos(pi e / N)
+    u32 *d_rot_exp = nullptr;       // [N/2] 5^j mod 2N
+    std::vector<u32> rot_exp;
+    std::map<int, ModUpConst> modup;      // by l1
+    std::map<int, ModDownConst> moddown;  // by l1
+    // scratch for key switching, grown on demand
+    u64 *ws_digits = nullptr; size_t ws_digits_words = 0;
+    u64 *ws_u = nullptr; size_t ws_u_words = 0;
+    RotDesc *ws_desc = nullptr; size_t ws_desc_n = 0;
+    u64 *ws_virt = nullptr; size_t ws_virt_words = 0;   // unpacked (rotated) operands of the matmul
+    u64 *ws_plan = nullptr; size_t ws_plan_words = 0;   // weight masks, operand pointer table, small constants
+    // sampler state for NULL randomness
+    u64 sampler_ctr = 0;
+    // timers
+    bool profiling = false;
+    std::vector<KernelTimer> timers;
+    std::vector<std::pair<int, std::pair<hipEvent_t, hipEvent_t>>> pending;
+    std::string err;
+};
+
+struct ensi_sk {
+    ensi_ctx *ctx;
+    std::vector<int8_t> s;  // host copy
+    u64 *d_s_hat;           // [L+K][N] transform domain, Montgomery form
+};
+struct ensi_pk {
+    ensi_ctx *ctx;
+    u64 *d_pk;  // [2][L][N] transform domain, Montgomery form
+};
+struct ensi_gk {
+    ensi_ctx *ctx;
+    std::map<u32, u64 *> keys;  // Galois element -> device [beta][2][L+K][N]
+};
+struct ensi_pt {
+    ensi_ctx *ctx;
+    int n, limbs;
+    u64 *d;  // [n][limbs][N] coefficient form
+};
+struct ensi_ct {
+    ensi_ctx *ctx;
+    int n, limbs, limbs_alloc;
+    double scale;
+    u64 *d;
+    bool owns;
+};
+
+#define ENSI_FAIL(ctx, code, ...)                              \
+    do {                                                       \
+        char _b[512];                                          \
+        snprintf(_b, sizeof(_b), __VA_ARGS__);                 \
+        if (ctx) (ctx)->err = _b;                              \
+        return (code);                                         \
+    } while (0)
+
+#define ENSI_HIP(ctx, expr)                                                                              \
+    do {                                                                                                 \
+        hipError_t _e = (expr);                                                                          \
+        if (_e != hipSuccess) ENSI_FAIL(ctx, ENSI_E_HIP, "%s failed: %s", #expr, hipGetErrorString(_e)); \
+    } while (0)
+
+// ---- timers ---------------------------------------------------------------
+int timer_id(ensi_ctx *ctx, const char *name);
+void timer_begin(ensi_ctx *ctx, int id, hipStream_t st);
+void timer_end(ensi_ctx *ctx, hipStream_t st);
+
+struct ScopedTimer {
+    ensi_ctx *c;
+    hipStream_t st;
+    bool on;
+    ScopedTimer(ensi_ctx *ctx, const char *name, hipStream_t s) : c(ctx), st(s), on(ctx->profiling) {
+        if (on) timer_begin(c, timer_id(c, name), st);
+    }
+    ~ScopedTimer() {
+        if (on) timer_end(c, st);
+    }
+};
+
+// ---- launchers (defined in the .hip files) ---------------------------------
+// Transform n_inst limb rows in place; row r uses prime map.prime[r % map.n].
+void launch_ntt(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);
+
+void launch_modup(ensi_ctx *ctx, const ModUpConst &mc, const u64 *ct_base, size_t ct_stride_words, int limb_stride,
+                  int n_ct, u64 *digits, hipStream_t st);
+void launch_inner(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int beta, u64 *u, hipStream_t st);
+void launch_moddown(ensi_ctx *ctx, const ModDownConst &mc, const RotDesc *d_desc, int n_rot, int limb_stride_in,
+                    int limb_stride_out, const u64 *u, hipStream_t st);
+void launch_accumulate(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, const u32 *d_masks, int m, int l1,
+                       int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
+void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, hipStream_t st);
+
+void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
+void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
+void launch_uniform(ensi_ctx *ctx, u64 *out, const LimbMap &map, u64 seed, u64 stream_id, hipStream_t st);
+// out = a (.) b_mont  (+ add) per limb row; rows cycle through map
+void launch_mul_mont(ensi_ctx *ctx, u64 *out, const u64 *a, const u64 *b_mont, int n_rows, const LimbMap &map,
+                     hipStream_t st);
+void launch_add(ensi_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int n_rows, const LimbMap &map, hipStream_t st);
+void launch_to_mont(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, hipStream_t st);
+// b = -a*s + e (+ factor[row] * sg), all transform domain; s_mont in Montgomery form; writes b in Montgomery form
+void launch_key_assemble(ensi_ctx *ctx, u64 *b_out, const u64 *a, const u64 *s_mont, const u64 *e, const u64 *sg,
+                         const u64 *d_factor, const LimbMap &map, hipStream_t st);
+void launch_automorphism_coef(ensi_ctx *ctx, u64 *out, const u64 *in, const LimbMap &map, u32 g_inv, hipStream_t st);
+void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int64_t *d_coeffs, hipStream_t st);
+void launch_crt_center(ensi_ctx *ctx, const u64 *m, int n_ct, int n_limbs_used, double *out, hipStream_t st);
+void launch_center_i64(ensi_ctx *ctx, const u64 *m, size_t stride_words, int n, int64_t *out, hipStream_t st);
+void launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale,
+                   double *d_out, hipStream_t st);

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI, on the
+same seeded inputs.  Integer results (RNS limbs) must match bit for bit;
+decrypted slots must lie within 1e-3 of the float64 product."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from helpers import Pair, stack_cts, to_oracle_cts
+
+pytestmark = pytest.mark.gpu
+
+TINY = wl.WORKLOADS[0].param_tuple()
+# a small ring with the BitNet-shaped workloads' chain structure (alpha=4, partial last digit at lower levels)
+SMALL4 = (10, 50, 6, 60, 4, 4, 40)
+SMALL3 = (10, 50, 5, 60, 3, 3, 40)  # alpha=3: digits 3+2
+
+
+@pytest.fixture(scope="module")
+def tiny():
+    p = Pair(TINY)
+    yield p
+    p.close()
+
+
+@pytest.fixture(scope="module")
+def small4():
+    p = Pair(SMALL4)
+    yield p
+    p.close()
+
+
+def test_primes_match_oracle(tiny):
+    q, p = tiny.ctx.primes()
+    assert q == tiny.pr.q and p == tiny.pr.p
+
+
+def test_ntt_roundtrip_and_evaluation_set(tiny):
+    rng = np.random.default_rng(0)
+    primes = tiny.pr.q + tiny.pr.p
+    x = np.stack([rng.integers(0, m, size=tiny.N, dtype=np.uint64) for m in primes])
+    # ship the rows to the device inside a ciphertext-shaped import (2 ciphertexts x 2 polys x 1 limb)
+    ct = tiny.ctx.ct_import(x.reshape(2, 2, 1, tiny.N) % np.uint64(tiny.pr.q[0]), 1.0)
+    x = ct.export().reshape(4, tiny.N)
+    idx = [0, 0, 0, 0]
+    tiny.ctx.ntt(ct.device_ptr, idx, inverse=False)
+    fwd = ct.export().reshape(4, tiny.N)
+    want = tiny.o.ntt(x, [tiny.pr.q[0]] * 4)
+    # whichever primitive root a side picked, the transform is the set of evaluations at all odd powers
+    assert np.array_equal(np.sort(fwd, axis=1), np.sort(want, axis=1))
+    assert not np.array_equal(fwd, x)
+    tiny.ctx.ntt(ct.device_ptr, idx, inverse=True)
+    assert np.array_equal(ct.export().reshape(4, tiny.N), x)
+    ct.free()
+
+
+def test_encode_within_one_and_import_export(tiny):
+    rng = np.random.default_rng(1)
+    z = rng.uniform(-1, 1, (2, tiny.n))
+    pt = tiny.ctx.encode(z, tiny.pr.L)
+    got = tiny.ctx.pt_export(pt)
+    want = np.stack([tiny.o.encode_coeffs(v) for v in z])
+    assert np.abs(got - want).max() <= 1
+    assert (got != want).mean() < 0.01
+    pt2 = tiny.ctx.pt_import(want, tiny.pr.L)
+    assert np.array_equal(tiny.ctx.pt_export(pt2), want)
+    pt.free()
+    pt2.free()
+
+
+def test_encrypt_bit_exact_and_decrypt(tiny):
+    rng = np.random.default_rng(2)
+    z = rng.uniform(-1, 1, (3, tiny.n))
+    o_cts, g_ct = tiny.encrypt_both(z, tiny.pr.L)
+    assert np.array_equal(g_ct.export(), stack_cts(o_cts))
+    got = tiny.ctx.decrypt(tiny.g_sk, g_ct)
+    want = np.stack([tiny.o.decrypt(c, tiny.o_sk) for c in o_cts])
+    assert np.abs(got - want).max() < 1e-7
+    assert np.abs(got - z).max() < 1e-3
+    part = tiny.ctx.decrypt(tiny.g_sk, g_ct, slot_begin=64, n_slots=32)
+    assert np.abs(part - want[:, 64:96]).max() < 1e-7
+    g_ct.free()
+
+
+@pytest.mark.parametrize("params", [TINY, SMALL4, SMALL3], ids=["tiny", "alpha4", "alpha3"])
+def test_rotate_bit_exact(params):
+    p = Pair(params)
+    try:
+        steps = [1, -1, 5, p.n // 2, 3]
+        o_gks, g_gk = p.galois_keys(sorted(set(steps)))
+        z = p.rng.uniform(-1, 1, (len(steps), p.n))
+        for limbs in sorted({p.pr.L, max(2, p.pr.L - 1), 2}, reverse=True):
+            o_cts, g_ct = p.encrypt_both(z, limbs)
+            out = p.ctx.rotate(g_gk, g_ct, steps)
+            want = [p.o.rotate(c, o_gks[st]) for c, st in zip(o_cts, steps)]
+            assert np.array_equal(out.export(), stack_cts(want)), "limbs=%d" % limbs
+            dec = p.ctx.decrypt(p.g_sk, out)
+            for i, st in enumerate(steps):
+                assert np.abs(dec[i] - np.roll(z[i], -st)).max() < 1e-3
+            assert out.limbs == limbs and out.scale == g_ct.scale
+            out.free()
+            g_ct.free()
+        g_gk.free()
+    finally:
+        p.close()
+
+
+@pytest.mark.parametrize("placement", ["diagonal", "zero"])
+def test_tiny_workload_matmul_bit_exact(tiny, placement):
+    w = wl.WORKLOADS[0]
+    rng = wl.rng_for(w.index)
+    W = wl.ternary_weights(rng, w.d_in, w.d_out)
+    X = wl.activations(rng, w.tokens, w.d_in, w.act)
+    packed = wl.pack_columns(X, tiny.n)
+    o_cts, g_ct = tiny.encrypt_both(packed, tiny.pr.L)
+    rhos = list(range(1, w.c_tot))
+    o_by_step, g_gk = tiny.galois_keys([r * w.tokens for r in rhos])
+    o_gks = {r: o_by_step[r * w.tokens] for r in rhos}
+    want = tiny.o.ternary_matmul(o_cts, w.tokens, w.d_in, W, placement, o_gks)
+    out = tiny.ctx.ternary_matmul(g_gk, g_ct, w.tokens, w.d_in, W, placement)
+    assert np.array_equal(out.export(), stack_cts(want))
+    assert out.limbs == tiny.pr.L and out.scale == g_ct.scale  # PCMM consumes no level
+    ref = X @ W.astype(np.float64)
+    err = 0.0
+    dec = tiny.ctx.decrypt(tiny.g_sk, out)
+    for i in range(w.d_out):
+        p_i = 0 if placement == "zero" else i % w.c_tot
+        err = max(err, np.abs(dec[i, p_i * w.tokens:(p_i + 1) * w.tokens] - ref[:, i]).max())
+    assert err < (1e-3 if placement == "diagonal" else 2e-3)
+    out.free()
+    g_ct.free()
+    g_gk.free()
+
+
+def test_matmul_paper_packing_needs_no_key(small4):
+    """One column per ciphertext (c_tot = 1): the paper's own packing; pure add/sub."""
+    p = small4
+    d, m = 37, 70  # ragged against the 32-wide output tiles
+    rng = np.random.default_rng(5)
+    W = wl.ternary_weights(rng, d, m)
+    W[:, 3] = 0  # an all-zero weight column gives the all-zero ciphertext
+    X = rng.uniform(-1, 1, (p.n, d))
+    for limbs in (p.pr.L, 3):
+        o_cts, g_ct = p.encrypt_both(X.T, limbs)
+        want = p.o.ternary_matmul(o_cts, p.n, d, W, "zero", {})
+        out = p.ctx.ternary_matmul(None, g_ct, p.n, d, W, "zero")
+        got = out.export()
+        assert np.array_equal(got, stack_cts(want))
+        assert not got[3].any()
+        dec = p.ctx.decrypt(p.g_sk, out)
+        assert np.abs(dec.T - X @ W.astype(np.float64)).max() < 1e-3
+        out.free()
+        g_ct.free()
+
+
+def test_matmul_several_packed_inputs(small4):
+    p = small4
+    s, d, m = 64, 19, 13  # c_tot = 8: three packed inputs, the last one ragged
+    rng = np.random.default_rng(6)
+    W = wl.ternary_weights(rng, d, m)
+    X = rng.uniform(-1, 1, (s, d))
+    packed = wl.pack_columns(X, p.n)
+    assert packed.shape[0] == 3
+    o_cts, g_ct = p.encrypt_both(packed, p.pr.L)
+    c_tot = p.n // s
+    o_by_step, g_gk = p.galois_keys([r * s for r in range(1, c_tot)])
+    o_gks = {r: o_by_step[r * s] for r in range(1, c_tot)}
+    for placement in ("diagonal", "zero"):
+        want = p.o.ternary_matmul(o_cts, s, d, W, placement, o_gks)
+        out = p.ctx.ternary_matmul(g_gk, g_ct, s, d, W, placement)
+        assert np.array_equal(out.export(), stack_cts(want)), placement
+        dec = p.ctx.decrypt(p.g_sk, out)
+        ref = X @ W.astype(np.float64)
+        for i in range(m):
+            p_i = 0 if placement == "zero" else i % c_tot
+            assert np.abs(dec[i, p_i * s:(p_i + 1) * s] - ref[:, i]).max() < 1e-3
+        out.free()
+    g_ct.free()
+    g_gk.free()
+
+
+def test_mul_scalar_rescale_bit_exact_and_two_layer(small4):
+    p = small4
+    rng = np.random.default_rng(7)
+    z = rng.uniform(-1, 1, (2, p.n))
+    for kappa in (2.0 ** -5, -0.3):
+        o_cts, g_ct = p.encrypt_both(z, p.pr.L)
+        want = [p.o.mul_scalar_rescale(c, kappa) for c in o_cts]
+        p.ctx.mul_scalar_rescale(g_ct, kappa)
+        assert g_ct.limbs == p.pr.L - 1
+        assert np.array_equal(g_ct.export(), stack_cts(want))
+        assert g_ct.scale == want[0].scale
+        dec = p.ctx.decrypt(p.g_sk, g_ct)
+        assert np.abs(dec - kappa * z).max() < 1e-3
+        # a rotation after the rescale runs at the lower level on the strided storage
+        o_gks, g_gk = p.galois_keys([2])
+        rot = p.ctx.rotate(g_gk, g_ct, [2, 2])
+        want_rot = [p.o.rotate(c, o_gks[2]) for c in want]
+        assert np.array_equal(rot.export(), stack_cts(want_rot))
+        rot.free()
+        g_gk.free()
+        g_ct.free()
+
+
+def test_error_paths(tiny):
+    E = tiny.binding.EnsiError
+    z = np.zeros((1, tiny.n))
+    _, g_ct = tiny.encrypt_both(z, tiny.pr.L)
+    _, g_gk = tiny.galois_keys([1])
+    with pytest.raises(E, match="code -2"):
+        tiny.ctx.rotate(g_gk, g_ct, [2])  # no key for step 2
+    W = np.zeros((64, 64), dtype=np.int8)
+    W[0, 0] = 2
+    with pytest.raises(E, match="code -1"):
+        tiny.ctx.ternary_matmul(g_gk, g_ct, 32, 64, W)
+    W[0, 0] = 1
+    W[5, 0] = 1
+    with pytest.raises(E, match="code -2"):
+        tiny.ctx.ternary_matmul(None, g_ct, 32, 64, W, "zero")  # needs rotations, no key set
+    with pytest.raises(E, match="code -4"):
+        tiny.ctx.ternary_matmul(g_gk, g_ct, 32, 4000, np.zeros((4000, 2), dtype=np.int8))  # needs 2 packed inputs
+    low = tiny.ctx.ct_alloc(1, 2)
+    with pytest.raises(E, match="code -3"):
+        tiny.ctx.rotate(g_gk, g_ct, [1], low)
+    low.free()
+    g_ct.free()
+    g_gk.free()

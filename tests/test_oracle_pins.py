@@ -227,7 +227,7 @@ def test_rescale_is_exact_division(all_small):
     out = o.mul_scalar_rescale(Ciphertext(c0, c1, pr.scale), kappa)
     ql = q[-1]
     k = -int(math.floor(abs(kappa) * ql + 0.5))
-    assert out.l1 == l1 - 1 and out.scale == pr.scale * k / ql
+    assert out.l1 == l1 - 1 and out.scale == pr.scale * k / (kappa * ql)
     for idx in range(0, o.N, 41):
         for src, dst in ((c0, out.c0), (c1, out.c1)):
             val, Q = crt([src[i, idx] for i in range(l1)], q)
