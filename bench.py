@@ -116,7 +116,7 @@ class Runner:
         alloc = self.L - 1 if w.d_mid else self.L
         words = 2 * alloc * self.N
         for i in sample:
-            one = self.ctx.ct_wrap(base + 8 * words * i, 1, limbs, scale)
+            one = self.ctx.ct_wrap(int(base) + 8 * words * int(i), 1, limbs, scale)
             p_i = 0 if (w.placement == "zero" or w.d_mid) else i % w.c_tot
             dec = self.ctx.decrypt(self.sk, one, p_i * w.tokens, w.tokens)[0]
             err = max(err, float(np.abs(dec - ref[:, i]).max()))

@@ -139,7 +139,7 @@ class Context:
 
     def ct_wrap(self, device_ptr, n, limbs, scale):
         ct = ctypes.c_void_p()
-        self._check(self.lib.ensi_ct_wrap(self.h, ctypes.c_void_p(device_ptr), n, limbs, ctypes.c_double(scale), ctypes.byref(ct)))
+        self._check(self.lib.ensi_ct_wrap(self.h, ctypes.c_void_p(int(device_ptr)), n, limbs, ctypes.c_double(scale), ctypes.byref(ct)))
         return Ciphertexts(self, ct)
 
     def ct_import(self, limbs_array, scale):
@@ -158,7 +158,8 @@ class Context:
         return Ciphertexts(self, ct)
 
     def decrypt(self, sk, ct, slot_begin=0, n_slots=None):
-        n_slots = self.n_slots - slot_begin if n_slots is None else n_slots
+        slot_begin = int(slot_begin)
+        n_slots = self.n_slots - slot_begin if n_slots is None else int(n_slots)
         out = np.empty((ct.n, n_slots), dtype=np.float64)
         self._check(self.lib.ensi_decrypt(self.h, sk.h, ct.h, slot_begin, n_slots, _ptr(out)))
         return out
@@ -190,7 +191,7 @@ class Context:
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):
         prime_idx = np.ascontiguousarray(prime_idx, dtype=np.int32)
-        self._check(self.lib.ensi_ntt(self.h, ctypes.c_void_p(device_ptr), len(prime_idx), _ptr(prime_idx), int(inverse),
+        self._check(self.lib.ensi_ntt(self.h, ctypes.c_void_p(int(device_ptr)), len(prime_idx), _ptr(prime_idx), int(inverse),
                                       ctypes.c_void_p(stream)))
 
     # ---- timers
