@@ -154,6 +154,12 @@ int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32
 int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
                         int32_t m, int32_t placement, ensi_ct *out, void *stream);
 
+/* Selects the kernel that forms the signed sums of Alg. 1: 0 = automatic (the
+ * int8 matrix-core contraction over byte planes whenever N >= 32 and the exact
+ * sum of the operands fits 62 bits, else the plain-ALU kernel), 1 = always the
+ * plain-ALU kernel, 2 = same as 0.  Both give identical residues. */
+int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode);
+
 /* ---- scalar multiply + rescale (between two PCMM layers) ---------------- */
 /* In place on the whole batch: c <- c * round(kappa q_l) mod q_i, then limb l
  * is dropped: c_i <- (c_i - (c_l mod q_i)) q_l^{-1} mod q_i.  limbs decreases

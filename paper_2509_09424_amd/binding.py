@@ -21,7 +21,7 @@ EXPORTED = [
     "ensi_pk_free", "ensi_galois_keygen", "ensi_gk_free", "ensi_encode", "ensi_pt_import", "ensi_pt_export",
     "ensi_pt_free", "ensi_ct_alloc", "ensi_ct_wrap", "ensi_ct_free", "ensi_ct_info", "ensi_ct_export",
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
-    "ensi_mul_scalar_rescale", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -184,6 +184,9 @@ class Context:
         self._check(self.lib.ensi_ternary_matmul(self.h, gk.h if gk is not None else None, ct_in.h, s, d, _ptr(W), m,
                                                  _PLACEMENTS[placement], ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
+
+    def set_accumulate_mode(self, mode):
+        self._check(self.lib.ensi_set_accumulate_mode(self.h, int(mode)))
 
     def mul_scalar_rescale(self, ct, kappa, stream=0):
         self._check(self.lib.ensi_mul_scalar_rescale(self.h, ct.h, ctypes.c_double(kappa), ctypes.c_void_p(stream)))

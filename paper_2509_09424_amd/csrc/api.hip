@@ -127,6 +127,7 @@ extern "C" int ensi_profile_read(ensi_ctx *ctx, char *names_out, int32_t names_c
 }
 
 // --------------------------------------------------------------------- context
+static void free_plan(MatmulPlan *p);
 static bool find_primes(int bits, int count, u64 two_n, const std::vector<u64> &skip, std::vector<u64> &out) {
     u64 x = (((u64)1 << bits) - 1) / two_n * two_n + 1;
     if (x >= ((u64)1 << bits)) x -= two_n;
@@ -254,6 +255,7 @@ extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
     if (ctx->ws_virt) (void)hipFree(ctx->ws_virt);
     if (ctx->ws_desc) (void)hipFree(ctx->ws_desc);
     if (ctx->ws_plan) (void)hipFree(ctx->ws_plan);
+    for (MatmulPlan *p : ctx->plans) free_plan(p);
     for (auto &p : ctx->pending) {
         (void)hipEventDestroy(p.second.first);
         (void)hipEventDestroy(p.second.second);
@@ -774,6 +776,131 @@ extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, 
 }
 
 // ------------------------------------------------------------------------ PCMM
+static u64 hash_weights(const int8_t *W, size_t n, u64 h) {
+    size_t i = 0;
+    for (; i + 8 <= n; i += 8) {
+        u64 w;
+        memcpy(&w, W + i, 8);
+        h = (h ^ w) * 0x100000001B3ULL;
+        h ^= h >> 29;
+    }
+    for (; i < n; i++) h = (h ^ (u64)(uint8_t)W[i]) * 0x100000001B3ULL;
+    return h;
+}
+
+static void free_plan(MatmulPlan *p) {
+    if (!p) return;
+    if (p->d_masks) (void)hipFree(p->d_masks);
+    if (p->d_wt) (void)hipFree(p->d_wt);
+    if (p->d_bias) (void)hipFree(p->d_bias);
+    delete p;
+}
+
+// Builds (or finds) the plan of Y = X W: which (packed input G, rotation amount rho)
+// operands exist, and the weight of each operand in each output,
+//   W'[v][i] = W[G*c_tot + (rho + p_i) mod c_tot][i],   p_i = placement block of output i.
+static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int placement, int c_tot, int n_in, int l1,
+                    MatmulPlan **out) {
+    u64 h = 0xCBF29CE484222325ULL ^ ((u64)s << 40) ^ ((u64)d << 20) ^ (u64)m ^ ((u64)placement << 60) ^ ((u64)l1 << 52);
+    h = hash_weights(W, (size_t)d * m, h);
+    for (size_t k = 0; k < ctx->plans.size(); k++) {
+        MatmulPlan *p = ctx->plans[k];
+        if (p->hash == h && p->s == s && p->d == d && p->m == m && p->placement == placement) {
+            *out = p;
+            return ENSI_OK;
+        }
+    }
+    for (size_t k = 0; k < (size_t)d * m; k++)
+        if (W[k] < -1 || W[k] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "weight %zu is %d, outside {-1,0,1}", k, (int)W[k]);
+    MatmulPlan *p = new MatmulPlan();
+    p->hash = h;
+    p->s = s; p->d = d; p->m = m; p->placement = placement; p->c_tot = c_tot; p->n_in = n_in;
+    p->vid.assign((size_t)n_in * c_tot, -1);
+    for (int j = 0; j < d; j++) {
+        const int G = j / c_tot, b = j % c_tot;
+        const int8_t *row = W + (size_t)j * m;
+        for (int i = 0; i < m; i++) {
+            if (!row[i]) continue;
+            const int pb = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
+            int rho = b - pb;
+            if (rho < 0) rho += c_tot;
+            p->vid[(size_t)G * c_tot + rho] = 0;
+        }
+    }
+    p->n_v = p->n_rot = 0;
+    for (int G = 0; G < n_in; G++)
+        for (int rho = 0; rho < c_tot; rho++)
+            if (p->vid[(size_t)G * c_tot + rho] == 0) {
+                p->vid[(size_t)G * c_tot + rho] = p->n_v++;
+                if (rho) p->n_rot++;
+            }
+    const int n_v = p->n_v;
+    // matrix-core layout is valid when a 32-word tile stays inside a limb and the exact
+    // signed sum of n_v residues fits 62 bits
+    int qbits = 0;
+    for (int i = 0; i < l1; i++) qbits = std::max(qbits, 64 - __builtin_clzll(ctx->primes[i]));
+    int log_nv = 0;
+    while ((1 << log_nv) < std::max(n_v, 1)) log_nv++;
+    const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && qbits + log_nv <= 62;
+    p->planes = 0;
+    p->n_kpad = (std::max(n_v, 1) + 31) / 32 * 32;
+    p->m_pad = (m + 255) / 256 * 256;
+    const int tiles = (m + 31) / 32;
+    std::vector<u32> masks((size_t)tiles * std::max(n_v, 1) * 2, 0);
+    std::vector<int8_t> wt;
+    std::vector<int64_t> bias;
+    if (mfma_ok) {
+        const int need = (qbits + 7) / 8;
+        p->planes = need <= 5 ? 5 : need <= 7 ? 7 : 8;
+        wt.assign((size_t)p->m_pad * p->n_kpad, 0);
+        bias.assign(p->m_pad, 0);
+    }
+    for (int j = 0; j < d; j++) {
+        const int G = j / c_tot, b = j % c_tot;
+        const int8_t *row = W + (size_t)j * m;
+        for (int i = 0; i < m; i++) {
+            if (!row[i]) continue;
+            const int pb = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
+            int rho = b - pb;
+            if (rho < 0) rho += c_tot;
+            const int v = p->vid[(size_t)G * c_tot + rho];
+            masks[((size_t)(i / 32) * n_v + v) * 2 + (row[i] > 0 ? 0 : 1)] |= 1u << (i % 32);
+            if (mfma_ok) {
+                wt[(size_t)i * p->n_kpad + v] = row[i];
+                bias[i] += row[i];
+            }
+        }
+    }
+    if (mfma_ok) {
+        u64 ones = 0;  // sum_b 256^b over the contracted planes
+        for (int b = 0; b < p->planes; b++) ones |= (u64)1 << (8 * b);
+        for (int i = 0; i < m; i++) bias[i] = (int64_t)((u64)(bias[i] * 128) * ones);
+    }
+    hipError_t e1 = upload(&p->d_masks, masks), e2 = hipSuccess, e3 = hipSuccess;
+    if (mfma_ok) {
+        e2 = upload(&p->d_wt, wt);
+        e3 = upload(&p->d_bias, bias);
+    }
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) {
+        free_plan(p);
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "uploading the matmul plan failed");
+    }
+    if (ctx->plans.size() >= 8) {
+        (void)hipDeviceSynchronize();
+        free_plan(ctx->plans.front());
+        ctx->plans.erase(ctx->plans.begin());
+    }
+    ctx->plans.push_back(p);
+    *out = p;
+    return ENSI_OK;
+}
+
+extern "C" int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode) {
+    if (!ctx || mode < 0 || mode > 2) return ENSI_E_BADARG;
+    ctx->accumulate_mode = mode;
+    return ENSI_OK;
+}
+
 extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
                                    int32_t m, int32_t placement, ensi_ct *out, void *stream) {
     if (!ctx || !in || !W || !out || s < 1 || d < 1 || m < 1) return ENSI_E_BADARG;
@@ -786,51 +913,19 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
     if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "matmul: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
-    for (size_t k = 0; k < (size_t)d * m; k++)
-        if (W[k] < -1 || W[k] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "weight %zu is %d, outside {-1,0,1}", k, (int)W[k]);
     hipStream_t st = (hipStream_t)stream;
     const int l1 = in->limbs, ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
+    int rc;
+    MatmulPlan *plan;
+    if ((rc = get_plan(ctx, W, s, d, m, placement, c_tot, n_in, l1, &plan))) return rc;
+    const int n_v = plan->n_v, n_rot = plan->n_rot;
+    const std::vector<int> &vid = plan->vid;
 
-    // ---- plan: which (packed input G, rotation amount rho) operands exist, and the
-    // weight of each operand in each output: W'[v][i] = W[G*c_tot + (rho + p_i) mod c_tot][i]
-    std::vector<int> vid((size_t)n_in * c_tot, -1);
-    for (int j = 0; j < d; j++) {
-        const int G = j / c_tot, b = j % c_tot;
-        const int8_t *row = W + (size_t)j * m;
-        for (int i = 0; i < m; i++) {
-            if (!row[i]) continue;
-            const int p = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
-            int rho = b - p;
-            if (rho < 0) rho += c_tot;
-            vid[(size_t)G * c_tot + rho] = 0;
-        }
-    }
-    int n_v = 0, n_rot = 0;
-    for (int G = 0; G < n_in; G++)
-        for (int rho = 0; rho < c_tot; rho++)
-            if (vid[(size_t)G * c_tot + rho] == 0) {
-                vid[(size_t)G * c_tot + rho] = n_v++;
-                if (rho) n_rot++;
-            }
-    const int tiles = (m + 31) / 32;
-    std::vector<u32> masks((size_t)tiles * std::max(n_v, 1) * 2, 0);
-    for (int j = 0; j < d; j++) {
-        const int G = j / c_tot, b = j % c_tot;
-        const int8_t *row = W + (size_t)j * m;
-        for (int i = 0; i < m; i++) {
-            if (!row[i]) continue;
-            const int p = placement == ENSI_PLACE_ZERO ? 0 : i % c_tot;
-            int rho = b - p;
-            if (rho < 0) rho += c_tot;
-            const int v = vid[(size_t)G * c_tot + rho];
-            masks[((size_t)(i / 32) * n_v + v) * 2 + (row[i] > 0 ? 0 : 1)] |= 1u << (i % 32);
-        }
-    }
     // ---- keys for every needed rotation amount
     std::vector<const u64 *> key_of(c_tot, nullptr);
     std::vector<u32> g_of(c_tot, 1);
-    for (int rho = 1; rho < c_tot; rho++) {
+    for (int rho = 1; rho < c_tot && n_rot; rho++) {
         bool need = false;
         for (int G = 0; G < n_in && !need; G++) need = vid[(size_t)G * c_tot + rho] >= 0;
         if (!need) continue;
@@ -842,21 +937,18 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
         g_of[rho] = g;
     }
     // ---- workspaces
-    int rc;
     const int chunk = 128;
     if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)beta * ext * N))) return rc;
     if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, std::max(n_rot, 1)) * 2 * ext * N))) return rc;
     if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)std::max(n_rot, 1) * in_ct))) return rc;
     if ((rc = ensure_desc(ctx, std::max(n_rot, 1)))) return rc;
-    const size_t plan_words = masks.size() / 2 + 1 + (size_t)std::max(n_v, 1);
-    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, plan_words))) return rc;
-    u32 *d_masks = (u32 *)ctx->ws_plan;
-    const u64 **d_vptr = (const u64 **)(ctx->ws_plan + masks.size() / 2 + 1);
+    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, (size_t)std::max(n_v, 1) + 4 * ENSI_MAX_EXT))) return rc;
+    const u64 **d_vptr = (const u64 **)ctx->ws_plan;
 
     // ---- unpack: rotations of every packed input, one ModUp per input
     std::vector<RotDesc> desc;
     std::vector<const u64 *> vptr(std::max(n_v, 1), nullptr);
-    std::vector<std::pair<int, int>> groups;  // (first desc, count) per packed input with rotations
+    std::vector<std::pair<int, int>> groups;  // (first descriptor, count) per packed input
     int r = 0;
     for (int G = 0; G < n_in; G++) {
         const int first = r;
@@ -881,7 +973,6 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
         groups.push_back({first, r - first});
     }
     if (n_rot) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync(d_masks, masks.data(), masks.size() * sizeof(u32), hipMemcpyHostToDevice, st));
     ENSI_HIP(ctx, hipMemcpyAsync((void *)d_vptr, vptr.data(), vptr.size() * sizeof(u64 *), hipMemcpyHostToDevice, st));
     if (n_rot) {
         const ModUpConst *mu;
@@ -898,7 +989,12 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
         }
     }
     // ---- Alg. 1: signed sums
-    launch_accumulate(ctx, d_vptr, n_v, d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
+    const bool use_mfma = plan->planes > 0 && ctx->accumulate_mode != 1;
+    if (use_mfma)
+        launch_accumulate_mfma(ctx, d_vptr, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc, out->d,
+                               out->limbs_alloc, st);
+    else
+        launch_accumulate(ctx, d_vptr, n_v, plan->d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
     out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;

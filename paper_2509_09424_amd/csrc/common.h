@@ -60,6 +60,18 @@ struct RotDesc {
     u32 g_inv;          // its inverse mod 2N
 };
 
+// Everything about one ternary_matmul that depends only on (W, s, d, m, placement).
+struct MatmulPlan {
+    u64 hash;
+    int s, d, m, placement, c_tot, n_in;
+    int n_v, n_rot;
+    std::vector<int> vid;        // [n_in][c_tot] -> operand index or -1
+    int n_kpad, m_pad, planes;   // matrix-core layout (planes = 0: not built, use the plain-ALU kernel)
+    u32 *d_masks = nullptr;      // [tiles32][n_v][2] (+1 bits, -1 bits)
+    int8_t *d_wt = nullptr;      // [m_pad][n_kpad] weights, operand index fastest
+    int64_t *d_bias = nullptr;   // [m_pad]
+};
+
 struct KernelTimer {
     std::string name;
     double ms = 0;
@@ -85,7 +97,9 @@ struct ensi_ctx {
     u64 *ws_u = nullptr; size_t ws_u_words = 0;
     RotDesc *ws_desc = nullptr; size_t ws_desc_n = 0;
     u64 *ws_virt = nullptr; size_t ws_virt_words = 0;   // unpacked (rotated) operands of the matmul
-    u64 *ws_plan = nullptr; size_t ws_plan_words = 0;   // weight masks, operand pointer table, small constants
+    u64 *ws_plan = nullptr; size_t ws_plan_words = 0;   // operand pointer table, small constants
+    std::vector<MatmulPlan *> plans;                    // cached per weight matrix (weights are static server-side)
+    int accumulate_mode = 0;                            // 0 auto, 1 plain-ALU kernel, 2 matrix-core kernel where valid
     // sampler state for NULL randomness
     u64 sampler_ctr = 0;
     // timers
@@ -164,6 +178,9 @@ void launch_moddown(ensi_ctx *ctx, const ModDownConst &mc, const RotDesc *d_desc
 void launch_accumulate(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, const u32 *d_masks, int m, int l1,
                        int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
 void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, hipStream_t st);
+// planes: 5, 7 or 8 (byte planes contracted); weights d_wt [m_pad][n_kpad], m_pad multiple of 256, n_kpad of 32
+void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, int n_kpad, const int8_t *d_wt, const int64_t *d_bias,
+                            int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
 
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);

@@ -116,8 +116,13 @@ def test_tiny_workload_matmul_bit_exact(tiny, placement):
     o_by_step, g_gk = tiny.galois_keys([r * w.tokens for r in rhos])
     o_gks = {r: o_by_step[r * w.tokens] for r in rhos}
     want = tiny.o.ternary_matmul(o_cts, w.tokens, w.d_in, W, placement, o_gks)
-    out = tiny.ctx.ternary_matmul(g_gk, g_ct, w.tokens, w.d_in, W, placement)
-    assert np.array_equal(out.export(), stack_cts(want))
+    for mode in (1, 2):  # plain-ALU kernel, then the matrix-core kernel
+        tiny.ctx.set_accumulate_mode(mode)
+        out = tiny.ctx.ternary_matmul(g_gk, g_ct, w.tokens, w.d_in, W, placement)
+        assert np.array_equal(out.export(), stack_cts(want)), "accumulate mode %d" % mode
+        if mode == 1:
+            out.free()
+    tiny.ctx.set_accumulate_mode(0)
     assert out.limbs == tiny.pr.L and out.scale == g_ct.scale  # PCMM consumes no level
     ref = X @ W.astype(np.float64)
     err = 0.0
@@ -142,9 +147,14 @@ def test_matmul_paper_packing_needs_no_key(small4):
     for limbs in (p.pr.L, 3):
         o_cts, g_ct = p.encrypt_both(X.T, limbs)
         want = p.o.ternary_matmul(o_cts, p.n, d, W, "zero", {})
-        out = p.ctx.ternary_matmul(None, g_ct, p.n, d, W, "zero")
-        got = out.export()
-        assert np.array_equal(got, stack_cts(want))
+        for mode in (1, 2):
+            p.ctx.set_accumulate_mode(mode)
+            out = p.ctx.ternary_matmul(None, g_ct, p.n, d, W, "zero")
+            got = out.export()
+            assert np.array_equal(got, stack_cts(want)), "accumulate mode %d, limbs %d" % (mode, limbs)
+            if mode == 1:
+                out.free()
+        p.ctx.set_accumulate_mode(0)
         assert not got[3].any()
         dec = p.ctx.decrypt(p.g_sk, out)
         assert np.abs(dec.T - X @ W.astype(np.float64)).max() < 1e-3
@@ -166,8 +176,13 @@ def test_matmul_several_packed_inputs(small4):
     o_gks = {r: o_by_step[r * s] for r in range(1, c_tot)}
     for placement in ("diagonal", "zero"):
         want = p.o.ternary_matmul(o_cts, s, d, W, placement, o_gks)
-        out = p.ctx.ternary_matmul(g_gk, g_ct, s, d, W, placement)
-        assert np.array_equal(out.export(), stack_cts(want)), placement
+        for mode in (1, 2):
+            p.ctx.set_accumulate_mode(mode)
+            out = p.ctx.ternary_matmul(g_gk, g_ct, s, d, W, placement)
+            assert np.array_equal(out.export(), stack_cts(want)), (placement, mode)
+            if mode == 1:
+                out.free()
+        p.ctx.set_accumulate_mode(0)
         dec = p.ctx.decrypt(p.g_sk, out)
         ref = X @ W.astype(np.float64)
         for i in range(m):
@@ -176,6 +191,28 @@ def test_matmul_several_packed_inputs(small4):
         out.free()
     g_ct.free()
     g_gk.free()
+
+
+def test_matmul_many_operands_and_wide_primes():
+    """Long sums: 300 operands on 50-bit primes (matrix-core kernel, several k-steps and two
+    256-output tiles) and 40 operands on 60-bit primes (plain-ALU kernel with mid-loop reductions,
+    the only valid one there)."""
+    for params, d, m in (((8, 50, 3, 60, 1, 3, 40), 300, 290), ((8, 60, 2, 61, 1, 2, 40), 40, 33)):
+        p = Pair(params)
+        try:
+            rng = np.random.default_rng(8)
+            W = wl.ternary_weights(rng, d, m)
+            X = rng.uniform(-1, 1, (p.n, d)) * 0.05
+            o_cts, g_ct = p.encrypt_both(X.T, p.pr.L)
+            want = stack_cts(p.o.ternary_matmul(o_cts, p.n, d, W, "zero", {}))
+            for mode in (1, 2):
+                p.ctx.set_accumulate_mode(mode)
+                out = p.ctx.ternary_matmul(None, g_ct, p.n, d, W, "zero")
+                assert np.array_equal(out.export(), want), (params, mode)
+                out.free()
+            g_ct.free()
+        finally:
+            p.close()
 
 
 def test_mul_scalar_rescale_bit_exact_and_two_layer(small4):
