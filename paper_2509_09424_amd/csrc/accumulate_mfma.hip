@@ -9,18 +9,29 @@
 // bit-identical to the sequence of modular additions and subtractions.
 //
 // Bytes are unsigned; the matrix pipe is signed, so each byte u is fed as u-128
-// (u xor 0x80) and the constant 128 * sum_v W'[v][i] * sum_b 256^b is added back per
-// output (`bias`, wrapped 64-bit).
+// (u xor 0x80) and 128 * sum_v W'[v][i] (`bias`) is added back to every plane of
+// output i when the planes are recombined.
 //
-// Work split: a workgroup (4 waves) owns 256 outputs x 32 consecutive words; each
-// wave owns 64 outputs (two 32x32 blocks) for all byte planes.  Per step of 32
-// operands the workgroup loads 32x32 words, transposes them into byte planes in
-// LDS (cell = 16 operands of one word of one plane), and every wave multiplies its
-// weight fragments (read straight from global memory, v-contiguous layout) with
-// the shared plane fragments.  Workgroups that share the same 32 words (different
-// output tiles) are given consecutive slots on one XCD so the operand words are
-// fetched from HBM once and served from that XCD's L2 afterwards.
+// Operand v is the ciphertext at xbase + v*xstride words (the unpack phase writes its
+// rotations straight into that array).
+//
+// Work split.  A work item is 256 outputs x 32 consecutive words; inside it each of
+// the 4 waves owns 64 outputs (two 32x32 blocks) for all byte planes and walks the
+// operands in steps of 32.  Per step:
+//   * the raw 32x32 operand words and the wave's two weight fragments arrive in LDS
+//     by asynchronous global->LDS copies issued AM_DEPTH steps earlier (rings of
+//     AM_DEPTH+1 slots; no registers are held while they are in flight);
+//   * the words of step k+1 are transposed into byte planes (cell = 16 operands of
+//     one word of one plane; one pad cell per 8 so dword writes hit distinct banks)
+//     in the shadow of the matrix instructions of step k;
+//   * one barrier.
+// The grid is persistent: one workgroup per CU, 32 per XCD.  Items that share their
+// 32 words (different output tiles) are consecutive in one XCD's list and the
+// workers of that XCD take the list round-robin, so they read the same operand words
+// at nearly the same time and all but the first read are served by that XCD's L2.
 #include "common.h"
+
+#include <ensi_dma.h>
 
 typedef int v4i __attribute__((vector_size(16)));
 typedef int v16i __attribute__((vector_size(64)));
@@ -29,6 +40,12 @@ typedef int v16i __attribute__((vector_size(64)));
 #define AM_TILE_M 256
 #define AM_TILE_N 32
 #define AM_TILE_K 32
+#define AM_DEPTH 7
+#define AM_RING (AM_DEPTH + 1)  // power of two; the step loop is unrolled by it so every LDS offset is a constant
+#define AM_PLANE_CELLS 72       // 64 cells of 16 bytes + 8 pad cells
+#define AM_XBLOCK 1040          // 4 operand rows of 32 words (one copy) + 16 bytes so that blocks start 4 banks apart
+#define AM_XSLOT (8 * AM_XBLOCK)  // raw operand words of one step
+#define AM_ASLOT 2048           // one wave's two weight fragments of one step
 
 // Byte b of four dwords gathered into one dword (4x4 byte transpose, two stages).
 __device__ __forceinline__ void transpose4(u32 a0, u32 a1, u32 a2, u32 a3, u32 *p) {
@@ -52,113 +69,235 @@ __device__ __forceinline__ u64 reduce_signed(int64_t t, u64 q, double q_inv) {
     return (u64)r;
 }
 
-template <int PLANES>
-__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *const *vptr, int n_v, int n_kpad, const int8_t *wt,
-                                                                const int64_t *bias, int m, const PrimeConst *pc, int N, int l1,
-                                                                int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n,
-                                                                int n_tiles_m) {
-    __shared__ v4i lds[2][PLANES * 64];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wv = tid >> 6, g = lane >> 5, nl = lane & 31;
-    // XCD-aware tile assignment: workgroup b runs on XCD b%8; consecutive local slots share the word tile
-    const int b = blockIdx.x, xcd = b & 7, loc = b >> 3;
-    const int m_tile = loc % n_tiles_m;
-    const int nt = (loc / n_tiles_m) * 8 + xcd;
-    if (nt >= n_tiles_n) return;
-    const size_t word0 = (size_t)nt * AM_TILE_N;
-    const size_t per_poly = (size_t)l1 * N;
-    const int poly = (int)(word0 / per_poly);
-    const size_t rem = word0 - (size_t)poly * per_poly;
-    const int limb = (int)(rem / N);
-    const size_t off_in = (size_t)poly * limb_stride_in * N + rem;
-    const size_t off_out = (size_t)poly * limb_stride_out * N + rem;
-    // loader role: word ln of the tile, operands 4*k4 .. 4*k4+3 of the step
-    const int ln = tid & 31, k4 = tid >> 5;
-    // weight fragments: rows (outputs) i0 + nl and i0 + 32 + nl, 16 consecutive operands starting at 16*g
-    const int i0 = m_tile * AM_TILE_M + wv * 64;
-    const int8_t *wa0 = wt + (size_t)(i0 + nl) * n_kpad + 16 * g;
-    const int8_t *wa1 = wa0 + (size_t)32 * n_kpad;
-
-    v16i acc[PLANES][2];
-#pragma unroll
-    for (int p = 0; p < PLANES; p++)
-#pragma unroll
-        for (int mb = 0; mb < 2; mb++)
-#pragma unroll
-            for (int r = 0; r < 16; r++) acc[p][mb][r] = 0;
-
-    const int nk = n_kpad / AM_TILE_K;
-    u64 x[4];
-#pragma unroll
-    for (int j = 0; j < 4; j++) {
-        int v = 4 * k4 + j;
-        v = v < n_v ? v : n_v - 1;
-        x[j] = vptr[v][off_in + ln];
-    }
-    v4i a0 = *(const v4i *)wa0, a1 = *(const v4i *)wa1;
-
-    for (int ks = 0; ks < nk; ks++) {
-        // byte planes of the four loaded words -> LDS
-        u32 pl[8];
-        transpose4((u32)x[0], (u32)x[1], (u32)x[2], (u32)x[3], pl);
-        transpose4((u32)(x[0] >> 32), (u32)(x[1] >> 32), (u32)(x[2] >> 32), (u32)(x[3] >> 32), pl + 4);
-        int *cells = (int *)lds[ks & 1];
-#pragma unroll
-        for (int p = 0; p < PLANES; p++) cells[(p * 64 + (k4 >> 2) * 32 + ln) * 4 + (k4 & 3)] = (int)(pl[p] ^ 0x80808080u);
-        __syncthreads();
-        v4i a0n = a0, a1n = a1;
-        if (ks + 1 < nk) {
-            const int kb = (ks + 1) * AM_TILE_K;
-#pragma unroll
-            for (int j = 0; j < 4; j++) {
-                int v = kb + 4 * k4 + j;
-                v = v < n_v ? v : n_v - 1;
-                x[j] = vptr[v][off_in + ln];
-            }
-            a0n = *(const v4i *)(wa0 + kb);
-            a1n = *(const v4i *)(wa1 + kb);
-        }
-#pragma unroll
-        for (int p = 0; p < PLANES; p++) {
-            const v4i bf = lds[ks & 1][p * 64 + g * 32 + nl];
-            acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, bf, acc[p][0], 0, 0, 0);
-            acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, bf, acc[p][1], 0, 0, 0);
-        }
-        a0 = a0n;
-        a1 = a1n;
-    }
-
-    // recombine planes, add the offset term, reduce mod q, store.  Accumulator register r of
-    // a lane holds output row 8*(r/4) + 4*(lane/32) + r%4 of the 32x32 block, column lane%32.
-    const u64 q = pc[limb].q;
-    const double q_inv = 1.0 / (double)q;
-    const size_t ct_words_out = (size_t)2 * limb_stride_out * N;
-#pragma unroll
-    for (int mb = 0; mb < 2; mb++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int i = i0 + mb * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
-            if (i < m) {
-                int64_t t = bias[i];
-#pragma unroll
-                for (int p = 0; p < PLANES; p++) t += (int64_t)((u64)(int64_t)acc[p][mb][r] << (8 * p));
-                out[(size_t)i * ct_words_out + off_out + nl] = reduce_signed(t, q, q_inv);
-            }
-        }
+__device__ __forceinline__ int am_cell(int g, int n) {
+    const int c = g * 32 + n;
+    return c + (c >> 3);
 }
 
-void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, int n_kpad, const int8_t *d_wt, const int64_t *d_bias,
+template <int PLANES>
+struct AmLayout {
+    static constexpr int plane_bytes = PLANES * AM_PLANE_CELLS * 16;
+    static constexpr int planes_off = 0;                              // [2][plane_bytes]
+    static constexpr int xring_off = 2 * plane_bytes;                 // [AM_RING][AM_XSLOT]
+    static constexpr int aring_off = xring_off + AM_RING * AM_XSLOT;  // [4 waves][AM_RING][AM_ASLOT]
+    static constexpr int total = aring_off + 4 * AM_RING * AM_ASLOT;
+};
+
+template <int PLANES>
+__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
+                                                                const int32_t *bias, int m, const PrimeConst *pc, int N, int l1,
+                                                                int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n,
+                                                                int n_tiles_m, int workers_per_xcd) {
+    HIP_DYNAMIC_SHARED(char, smem)
+    typedef AmLayout<PLANES> LY;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6, g = lane >> 5, nl = lane & 31;
+    // transposer role: operands 4*k4..4*k4+3 of the step (= copy block k4), word ln.  k4 varies fastest so
+    // that one wave's dword writes cover all banks.
+    const int k4 = tid & 7, ln = tid >> 3;
+    const int nk = n_kpad / AM_TILE_K;
+    const u32 smem0 = lds_addr(smem);
+    // wave-uniform LDS byte addresses of this wave's copy targets (slot 0)
+    const u32 x_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::xring_off + 2 * wv * AM_XBLOCK));
+    const u32 a_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::aring_off + wv * AM_RING * AM_ASLOT));
+    const char *a_rd = smem + LY::aring_off + wv * AM_RING * AM_ASLOT + lane * 16;
+    const char *x_rd = smem + LY::xring_off + k4 * AM_XBLOCK + ln * 8;
+    int *p_wr = (int *)(smem + LY::planes_off) + am_cell(k4 >> 2, ln) * 4 + (k4 & 3);
+    const v4i *p_rd = (const v4i *)(smem + LY::planes_off) + am_cell(g, nl);
+    const size_t per_poly = (size_t)l1 * N;
+    const size_t ct_words_out = (size_t)2 * limb_stride_out * N;
+    const int xcd = blockIdx.x & 7, worker = blockIdx.x >> 3;
+    const int items = ((n_tiles_n + 7) / 8) * n_tiles_m;
+    const u64 step_bytes = (u64)AM_TILE_K * xstride * sizeof(u64);
+
+    for (int item = worker; item < items; item += workers_per_xcd) {
+        const int m_tile = item % n_tiles_m;
+        const int nt = (item / n_tiles_m) * 8 + xcd;
+        if (nt >= n_tiles_n) continue;
+        const size_t word0 = (size_t)nt * AM_TILE_N;
+        const int poly = (int)(word0 / per_poly);
+        const size_t rem = word0 - (size_t)poly * per_poly;
+        const int limb = (int)(rem / N);
+        const size_t off_in = (size_t)poly * limb_stride_in * N + rem;
+        const size_t off_out = (size_t)poly * limb_stride_out * N + rem;
+        const int i0 = m_tile * AM_TILE_M + wv * 64;
+        // copy addressing: one copy moves 4 operand rows of 32 words; lane -> (row lane/16, words 2*(lane%16)..+1).
+        // Running per-lane pointers walk the operands in step order; they are only used (and advanced) for
+        // steps that lie wholly inside the n_v operands, the ragged remainder is clamped lane by lane.
+        const u64 *xlane = xbase + off_in + 2 * (lane & 15);
+        const int row0 = 8 * wv + (lane >> 4);
+        const char *px0 = (const char *)(xlane + (u64)(u32)row0 * (u64)xstride);
+        const char *px1 = px0 + 4 * (u64)xstride * sizeof(u64);
+        const char *pa = (const char *)(wfrag + ((size_t)m_tile * nk * 4 + wv) * 128 + lane);
+
+        auto issue_x = [&](int step, int slot) {  // raw words of `step` -> ring slot; 2 copies per wave
+            const u32 dst = x_lds + (u32)slot * AM_XSLOT;
+            if ((step + 1) * AM_TILE_K <= n_v) {
+                dma_load16(px0, dst);
+                dma_load16(px1, dst + AM_XBLOCK);
+                px0 += step_bytes;
+                px1 += step_bytes;
+            } else {
+                const int st = step < nk ? step : nk - 1;
+#pragma unroll
+                for (int c = 0; c < 2; c++) {
+                    int v = st * AM_TILE_K + row0 + 4 * c;
+                    v = v < n_v ? v : n_v - 1;
+                    dma_load16(xlane + (u64)(u32)v * (u64)xstride, dst + c * AM_XBLOCK);
+                }
+            }
+        };
+        auto issue_a = [&](int step, int slot) {  // this wave's fragments of `step` -> ring slot; 2 copies
+            const u32 dst = a_lds + (u32)slot * AM_ASLOT;
+            dma_load16(pa, dst);
+            dma_load16(pa + 1024, dst + 1024);
+            pa += step + 1 < nk ? 8192 : 0;
+        };
+        auto planes_of = [&](int slot, u32 *pl) {  // read the thread's 4 raw words, transpose
+            const char *src = x_rd + slot * AM_XSLOT;
+            u64 w[4];
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[j] = *(const u64 *)(src + j * 256);
+            transpose4((u32)w[0], (u32)w[1], (u32)w[2], (u32)w[3], pl);
+            transpose4((u32)(w[0] >> 32), (u32)(w[1] >> 32), (u32)(w[2] >> 32), (u32)(w[3] >> 32), pl + 4);
+        };
+        auto write_planes = [&](int parity, const u32 *pl) {
+            int *cells = p_wr + parity * (LY::plane_bytes / 4);
+#pragma unroll
+            for (int p = 0; p < PLANES; p++) cells[p * AM_PLANE_CELLS * 4] = (int)(pl[p] ^ 0x80808080u);
+        };
+
+        v16i acc[PLANES][2];
+#pragma unroll
+        for (int p = 0; p < PLANES; p++)
+#pragma unroll
+            for (int mb = 0; mb < 2; mb++)
+#pragma unroll
+                for (int r = 0; r < 16; r++) acc[p][mb][r] = 0;
+
+        // drain the previous item's loads and stores: inside the step loop only the copies are in flight
+        wait_vmcnt<0>();
+        __syncthreads();  // every wave is done with the LDS contents of the previous item
+        // prologue: X(0), then (X(t+1), A(t)) for t = 0..DEPTH-1  -- same order as the steady state
+        issue_x(0, 0);
+#pragma unroll
+        for (int t = 0; t < AM_DEPTH; t++) {
+            issue_x(t + 1, t + 1);
+            issue_a(t, t);
+        }
+        wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(0), X(1), A(0) have landed
+        __syncthreads();
+        {
+            u32 pl[8];
+            planes_of(0, pl);
+            write_planes(0, pl);
+        }
+        __syncthreads();
+
+        // nk is a multiple of AM_RING (the plan pads the operand count with zero weights)
+        for (int ks0 = 0; ks0 < nk; ks0 += AM_RING) {
+#pragma unroll
+            for (int s = 0; s < AM_RING; s++) {
+                const int ks = ks0 + s;
+                // fragments of this step: planes(ks) in buffer s&1, A(ks) in slot s
+                const char *ar = a_rd + s * AM_ASLOT;
+                const v4i a0 = *(const v4i *)ar, a1 = *(const v4i *)(ar + 1024);
+                const v4i *pb = p_rd + (s & 1) * (LY::plane_bytes / 16);
+                v4i bf[PLANES];
+#pragma unroll
+                for (int p = 0; p < PLANES; p++) bf[p] = pb[p * AM_PLANE_CELLS];
+                // planes of step ks+1 (slot (s+1) % RING), in the shadow of the products of step ks
+                u32 pl[8];
+                planes_of((s + 1) % AM_RING, pl);
+#pragma unroll
+                for (int p = 0; p < PLANES; p++) {
+                    acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, bf[p], acc[p][0], 0, 0, 0);
+                    acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, bf[p], acc[p][1], 0, 0, 0);
+                }
+                write_planes((s + 1) & 1, pl);
+                // refill: X(ks+RING) takes the slot of X(ks), A(ks+DEPTH) the slot of A(ks-1);
+                // both were last read before the previous barrier
+                issue_x(ks + AM_RING, s);
+                issue_a(ks + AM_DEPTH, (s + AM_DEPTH) % AM_RING);
+                wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(ks+2) and A(ks+1) have landed
+                __syncthreads();
+            }
+        }
+
+        // Recombine planes, add the offset term 128 * sum_v W'[v][i] * sum_p 256^p, reduce mod q, store.
+        // Accumulator register r of a lane holds output row 8*(r/4) + 4*(lane/32) + r%4 of the 32x32
+        // block, column lane%32.  The accumulators go through LDS (all rings and planes are dead by
+        // now) so that the recombination can be a rolled loop with few live registers.
+        wait_vmcnt<0>();
+        __syncthreads();
+        const u64 q = pc[limb].q;
+        const double q_inv = 1.0 / (double)q;
+        u64 ones = 0;
+#pragma unroll
+        for (int p = 0; p < PLANES; p++) ones |= (u64)1 << (8 * p);
+        v4i *scr = (v4i *)smem + tid;  // chunk (p, c) of this thread at scr[(p*4 + c) * 256]
+#pragma unroll
+        for (int mb = 0; mb < 2; mb++) {
+#pragma unroll
+            for (int p = 0; p < PLANES; p++)
+#pragma unroll
+                for (int c = 0; c < 4; c++) {
+                    v4i t4 = {acc[p][mb][4 * c], acc[p][mb][4 * c + 1], acc[p][mb][4 * c + 2], acc[p][mb][4 * c + 3]};
+                    scr[(p * 4 + c) * AM_THREADS] = t4;
+                }
+#pragma unroll 1
+            for (int c = 0; c < 4; c++) {
+                const int ib = i0 + mb * 32 + 8 * c + 4 * g;  // rows ib .. ib+3
+                int64_t t[4];
+#pragma unroll
+                for (int e = 0; e < 4; e++) t[e] = (int64_t)((u64)(int64_t)bias[ib + e] * ones);
+#pragma unroll
+                for (int p = 0; p < PLANES; p++) {
+                    const v4i t4 = scr[(p * 4 + c) * AM_THREADS];
+#pragma unroll
+                    for (int e = 0; e < 4; e++) t[e] += (int64_t)((u64)(int64_t)t4[e] << (8 * p));
+                }
+#pragma unroll
+                for (int e = 0; e < 4; e++)
+                    if (ib + e < m) out[(size_t)(ib + e) * ct_words_out + off_out + nl] = reduce_signed(t[e], q, q_inv);
+            }
+        }
+    }
+    wait_vmcnt<0>();  // no copy may still be in flight into LDS when the workgroup ends
+}
+
+template <int P>
+static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
+                      const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n, int n_tiles_m,
+                      int workers) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, xbase, xstride, n_v, n_kpad, wfrag, bias, m,
+                       ctx->d_pc, ctx->N, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+}
+
+void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
                             int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st) {
     ScopedTimer t(ctx, "accumulate_mfma", st);
     const size_t words = (size_t)2 * l1 * ctx->N;
     const int n_tiles_n = (int)(words / AM_TILE_N);
     const int n_tiles_m = (m + AM_TILE_M - 1) / AM_TILE_M;
-    const unsigned grid = 8u * (unsigned)((n_tiles_n + 7) / 8) * (unsigned)n_tiles_m;
-#define AM_LAUNCH(P)                                                                                                           \
-    hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), 0, st, d_vptr, n_v, n_kpad, d_wt, d_bias, m, ctx->d_pc, \
-                       ctx->N, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m)
-    if (planes <= 5) AM_LAUNCH(5);
-    else if (planes <= 7) AM_LAUNCH(7);
-    else AM_LAUNCH(8);
-#undef AM_LAUNCH
+    static int n_cu = 0;
+    if (!n_cu) {
+        hipDeviceProp_t prop;
+        n_cu = hipGetDeviceProperties(&prop, ctx->device) == hipSuccess ? prop.multiProcessorCount : 256;
+        if (n_cu < 8) n_cu = 8;
+    }
+    const int workers = n_cu / 8;  // one persistent workgroup per CU; workgroup b runs on XCD b % 8
+    const unsigned grid = 8u * (unsigned)workers;
+    const v4i *wf = (const v4i *)d_wt;
+    if (planes <= 5)
+        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+    else if (planes <= 7)
+        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+    else
+        am_launch<8>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
 }

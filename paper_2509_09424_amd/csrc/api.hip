@@ -829,11 +829,17 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
     }
     p->n_v = p->n_rot = 0;
     for (int G = 0; G < n_in; G++)
-        for (int rho = 0; rho < c_tot; rho++)
-            if (p->vid[(size_t)G * c_tot + rho] == 0) {
-                p->vid[(size_t)G * c_tot + rho] = p->n_v++;
-                if (rho) p->n_rot++;
-            }
+        for (int rho = 1; rho < c_tot; rho++)
+            if (p->vid[(size_t)G * c_tot + rho] == 0) p->n_rot++;
+    if (p->n_rot == 0) {
+        // no rotation anywhere: the operands are the inputs themselves, in place (operand G = input G)
+        for (int G = 0; G < n_in; G++) p->vid[(size_t)G * c_tot] = G;
+        p->n_v = n_in;
+    } else {
+        for (int G = 0; G < n_in; G++)
+            for (int rho = 0; rho < c_tot; rho++)
+                if (p->vid[(size_t)G * c_tot + rho] == 0) p->vid[(size_t)G * c_tot + rho] = p->n_v++;
+    }
     const int n_v = p->n_v;
     // matrix-core layout is valid when a 32-word tile stays inside a limb and the exact
     // signed sum of n_v residues fits 62 bits
@@ -843,12 +849,12 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
     while ((1 << log_nv) < std::max(n_v, 1)) log_nv++;
     const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && qbits + log_nv <= 62;
     p->planes = 0;
-    p->n_kpad = (std::max(n_v, 1) + 31) / 32 * 32;
+    p->n_kpad = (std::max(n_v, 1) + 255) / 256 * 256;  // whole groups of eight 32-operand steps
     p->m_pad = (m + 255) / 256 * 256;
     const int tiles = (m + 31) / 32;
     std::vector<u32> masks((size_t)tiles * std::max(n_v, 1) * 2, 0);
     std::vector<int8_t> wt;
-    std::vector<int64_t> bias;
+    std::vector<int32_t> bias;
     if (mfma_ok) {
         const int need = (qbits + 7) / 8;
         p->planes = need <= 5 ? 5 : need <= 7 ? 7 : 8;
@@ -866,16 +872,17 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
             const int v = p->vid[(size_t)G * c_tot + rho];
             masks[((size_t)(i / 32) * n_v + v) * 2 + (row[i] > 0 ? 0 : 1)] |= 1u << (i % 32);
             if (mfma_ok) {
-                wt[(size_t)i * p->n_kpad + v] = row[i];
+                // fragment order: [output tile of 256][step of 32 operands][wave][block of 32][lane][16 bytes],
+                // lane = 32*(operand half of the step) + output within the block
+                const size_t cell = ((((size_t)(i / 256) * (p->n_kpad / 32) + v / 32) * 4 + (i % 256) / 64) * 2 + (i % 64) / 32) * 64 +
+                                    ((v % 32) / 16) * 32 + i % 32;
+                wt[cell * 16 + v % 16] = row[i];
                 bias[i] += row[i];
             }
         }
     }
-    if (mfma_ok) {
-        u64 ones = 0;  // sum_b 256^b over the contracted planes
-        for (int b = 0; b < p->planes; b++) ones |= (u64)1 << (8 * b);
-        for (int i = 0; i < m; i++) bias[i] = (int64_t)((u64)(bias[i] * 128) * ones);
-    }
+    if (mfma_ok)
+        for (int i = 0; i < m; i++) bias[i] *= 128;  // every byte is fed to the matrix pipe as u - 128
     hipError_t e1 = upload(&p->d_masks, masks), e2 = hipSuccess, e3 = hipSuccess;
     if (mfma_ok) {
         e2 = upload(&p->d_wt, wt);
@@ -936,45 +943,41 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
         key_of[rho] = it->second;
         g_of[rho] = g;
     }
-    // ---- workspaces
+    // ---- workspaces.  With rotations, operand v is written to slot v of ws_virt (inputs used
+    // unrotated are copied there); without, the operands are the input batch itself.
     const int chunk = 128;
-    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)beta * ext * N))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, std::max(n_rot, 1)) * 2 * ext * N))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)std::max(n_rot, 1) * in_ct))) return rc;
-    if ((rc = ensure_desc(ctx, std::max(n_rot, 1)))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, (size_t)std::max(n_v, 1) + 4 * ENSI_MAX_EXT))) return rc;
-    const u64 **d_vptr = (const u64 **)ctx->ws_plan;
-
-    // ---- unpack: rotations of every packed input, one ModUp per input
-    std::vector<RotDesc> desc;
-    std::vector<const u64 *> vptr(std::max(n_v, 1), nullptr);
-    std::vector<std::pair<int, int>> groups;  // (first descriptor, count) per packed input
-    int r = 0;
-    for (int G = 0; G < n_in; G++) {
-        const int first = r;
-        for (int rho = 0; rho < c_tot; rho++) {
-            const int v = vid[(size_t)G * c_tot + rho];
-            if (v < 0) continue;
-            if (rho == 0) {
-                vptr[v] = in->d + (size_t)G * in_ct;
-                continue;
-            }
-            RotDesc ds;
-            ds.c0 = in->d + (size_t)G * in_ct;
-            ds.digits = ctx->ws_digits;
-            ds.key = key_of[rho];
-            ds.out = ctx->ws_virt + (size_t)r * in_ct;
-            ds.g = g_of[rho];
-            ds.g_inv = inv_mod_2n(ds.g, N);
-            desc.push_back(ds);
-            vptr[v] = ds.out;
-            r++;
-        }
-        groups.push_back({first, r - first});
-    }
-    if (n_rot) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync((void *)d_vptr, vptr.data(), vptr.size() * sizeof(u64 *), hipMemcpyHostToDevice, st));
+    const u64 *xbase = in->d;
     if (n_rot) {
+        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)beta * ext * N))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, n_rot) * 2 * ext * N))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)n_v * in_ct))) return rc;
+        if ((rc = ensure_desc(ctx, n_rot))) return rc;
+        xbase = ctx->ws_virt;
+        std::vector<RotDesc> desc;
+        std::vector<std::pair<int, int>> groups;  // (first descriptor, count) per packed input
+        for (int G = 0; G < n_in; G++) {
+            const int first = (int)desc.size();
+            for (int rho = 0; rho < c_tot; rho++) {
+                const int v = vid[(size_t)G * c_tot + rho];
+                if (v < 0) continue;
+                u64 *slot = ctx->ws_virt + (size_t)v * in_ct;
+                if (rho == 0) {
+                    ENSI_HIP(ctx, hipMemcpyAsync(slot, in->d + (size_t)G * in_ct, in_ct * sizeof(u64), hipMemcpyDeviceToDevice, st));
+                    continue;
+                }
+                RotDesc ds;
+                ds.c0 = in->d + (size_t)G * in_ct;
+                ds.digits = ctx->ws_digits;
+                ds.key = key_of[rho];
+                ds.out = slot;
+                ds.g = g_of[rho];
+                ds.g_inv = inv_mod_2n(ds.g, N);
+                desc.push_back(ds);
+            }
+            groups.push_back({first, (int)desc.size() - first});
+        }
+        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        // ---- unpack: one ModUp per packed input, shared by all its rotations
         const ModUpConst *mu;
         if ((rc = get_modup(ctx, l1, &mu))) return rc;
         LimbMap mext = make_map(ctx, l1, true);
@@ -991,10 +994,10 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     // ---- Alg. 1: signed sums
     const bool use_mfma = plan->planes > 0 && ctx->accumulate_mode != 1;
     if (use_mfma)
-        launch_accumulate_mfma(ctx, d_vptr, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc, out->d,
-                               out->limbs_alloc, st);
+        launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc,
+                               out->d, out->limbs_alloc, st);
     else
-        launch_accumulate(ctx, d_vptr, n_v, plan->d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
+        launch_accumulate(ctx, xbase, in_ct, n_v, plan->d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
     out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;

@@ -69,7 +69,7 @@ struct MatmulPlan {
     int n_kpad, m_pad, planes;   // matrix-core layout (planes = 0: not built, use the plain-ALU kernel)
     u32 *d_masks = nullptr;      // [tiles32][n_v][2] (+1 bits, -1 bits)
     int8_t *d_wt = nullptr;      // [m_pad][n_kpad] weights, operand index fastest
-    int64_t *d_bias = nullptr;   // [m_pad]
+    int32_t *d_bias = nullptr;   // [m_pad] 128 * column sum of the weights
 };
 
 struct KernelTimer {
@@ -175,11 +175,12 @@ void launch_modup(ensi_ctx *ctx, const ModUpConst &mc, const u64 *ct_base, size_
 void launch_inner(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int beta, u64 *u, hipStream_t st);
 void launch_moddown(ensi_ctx *ctx, const ModDownConst &mc, const RotDesc *d_desc, int n_rot, int limb_stride_in,
                     int limb_stride_out, const u64 *u, hipStream_t st);
-void launch_accumulate(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, const u32 *d_masks, int m, int l1,
+// operand v of the signed sums is the ciphertext at xbase + v*xstride words
+void launch_accumulate(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, const u32 *d_masks, int m, int l1,
                        int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
 void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, hipStream_t st);
 // planes: 5, 7 or 8 (byte planes contracted); weights d_wt [m_pad][n_kpad], m_pad multiple of 256, n_kpad of 32
-void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, int n_kpad, const int8_t *d_wt, const int64_t *d_bias,
+void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
                             int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
 
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);

@@ -152,7 +152,7 @@ void launch_moddown(ensi_ctx *ctx, const ModDownConst &mc, const RotDesc *d_desc
 // the block, so zero weights are skipped by uniform branches.  Sums are kept as
 // wrapping signed 64-bit integers and reduced every `red_every` operands.
 #define ACC_T 32
-__global__ __launch_bounds__(EW_THREADS) void k_accumulate(const u64 *const *vptr, int n_v, const u32 *masks, int m,
+__global__ __launch_bounds__(EW_THREADS) void k_accumulate(const u64 *xbase, size_t xstride, int n_v, const u32 *masks, int m,
                                                            const PrimeConst *pc, int N, int l1, int limb_stride_in, u64 *out,
                                                            int limb_stride_out, int red_every) {
     const size_t w = (size_t)blockIdx.y * EW_THREADS + threadIdx.x;  // word within the active limbs of one ciphertext
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_accumulate(const u64 *const *vpt
     for (int v = 0; v < n_v; v++) {
         const u32 pm = mk[2 * v], mm = mk[2 * v + 1];
         if ((pm | mm) == 0) continue;
-        const int64_t x = (int64_t)vptr[v][off_in];
+        const int64_t x = (int64_t)xbase[(size_t)v * xstride + off_in];
 #pragma unroll
         for (int t = 0; t < ACC_T; t++) {
             if (pm & (1u << t)) acc[t] += x;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_accumulate(const u64 *const *vpt
     }
 }
 
-void launch_accumulate(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, const u32 *d_masks, int m, int l1,
+void launch_accumulate(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, const u32 *d_masks, int m, int l1,
                        int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st) {
     ScopedTimer t(ctx, "accumulate", st);
     int qbits = 0;
@@ -213,7 +213,7 @@ void launch_accumulate(ensi_ctx *ctx, const u64 *const *d_vptr, int n_v, const u
     if (red_every > 1) red_every -= 1;  // the carried residue counts as one operand
     size_t words = (size_t)2 * l1 * ctx->N;
     dim3 grid((m + ACC_T - 1) / ACC_T, (unsigned)((words + EW_THREADS - 1) / EW_THREADS));
-    hipLaunchKernelGGL(k_accumulate, grid, dim3(EW_THREADS), 0, st, d_vptr, n_v, d_masks, m, ctx->d_pc, ctx->N, l1,
+    hipLaunchKernelGGL(k_accumulate, grid, dim3(EW_THREADS), 0, st, xbase, xstride, n_v, d_masks, m, ctx->d_pc, ctx->N, l1,
                        limb_stride_in, out, limb_stride_out, red_every);
 }
 
