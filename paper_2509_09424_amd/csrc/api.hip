@@ -192,6 +192,14 @@ extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
         pc.r2 = hm_mulmod(r, r, q);
         pc.n_inv = hm_invmod((u64)N % q, q);
         pc.n_inv_s = hm_shoup(pc.n_inv, q);
+        // N = 2^16 rings transform limbs with primes below 2^50 in fp64 (see ntt16.hip)
+        const bool fp = ctx->log_n == 16 && q < ((u64)1 << 50);
+        if (fp) {
+            const double qi = 1.0 / (double)q, nq = (double)pc.n_inv / (double)q;
+            pc.pad[0] = 1;
+            memcpy(&pc.pad[1], &qi, 8);
+            memcpy(&pc.pad[2], &nq, 8);
+        }
         // powers of psi and psi^{-1}, then bit-reversed tables
         std::vector<u64> pw(N), ipw(N);
         const u64 psi_inv = hm_invmod(psi, q);
@@ -204,10 +212,20 @@ extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
         for (int k = 0; k < N; k++) {
             u32 rk = 0;
             for (int b = 0; b < ctx->log_n; b++) rk |= ((k >> b) & 1u) << (ctx->log_n - 1 - b);
-            t[k] = pw[rk];
-            t[N + k] = hm_shoup(pw[rk], q);
-            t[2 * N + k] = ipw[rk];
-            t[3 * N + k] = hm_shoup(ipw[rk], q);
+            if (fp) {
+                // fp64 path: the table holds the twiddle and twiddle/q as doubles
+                const double w = (double)pw[rk], wi = (double)ipw[rk];
+                const double wq = w / (double)q, wiq = wi / (double)q;
+                memcpy(&t[k], &w, 8);
+                memcpy(&t[N + k], &wq, 8);
+                memcpy(&t[2 * N + k], &wi, 8);
+                memcpy(&t[3 * N + k], &wiq, 8);
+            } else {
+                t[k] = pw[rk];
+                t[N + k] = hm_shoup(pw[rk], q);
+                t[2 * N + k] = ipw[rk];
+                t[3 * N + k] = hm_shoup(ipw[rk], q);
+            }
         }
     }
     std::vector<double> cs(2 * (size_t)N);

@@ -23,7 +23,7 @@ struct PrimeConst {
     u64 r2;         // 2^128 mod q   (to Montgomery form: mont_mul(x, r2))
     u64 n_inv;      // N^{-1} mod q
     u64 n_inv_s;    // its Shoup companion
-    u64 pad[3];
+    u64 pad[3];     // [0] 1 if this prime's transform tables hold doubles (fp64 path), [1] bits of 1/q, [2] bits of n_inv/q
 };
 
 // Which prime each limb row of a kernel's operand uses.
@@ -169,6 +169,7 @@ struct ScopedTimer {
 // ---- launchers (defined in the .hip files) ---------------------------------
 // Transform n_inst limb rows in place; row r uses prime map.prime[r % map.n].
 void launch_ntt(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);
+void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);  // N = 2^16 only
 
 void launch_modup(ensi_ctx *ctx, const ModUpConst &mc, const u64 *ct_base, size_t ct_stride_words, int limb_stride,
                   int n_ct, u64 *digits, hipStream_t st);

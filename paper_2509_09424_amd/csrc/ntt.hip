@@ -183,6 +183,10 @@ static void launch_ntt_chunk(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap
 // Rows beyond the grid's y limit are transformed in several launches, each a whole
 // number of periods of the prime map.
 void launch_ntt(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st) {
+    if (ctx->log_n == 16) {
+        launch_ntt16(ctx, data, n_inst, map, inverse, st);
+        return;
+    }
     const int max_rows = (32768 / map.n) * map.n;
     for (int done = 0; done < n_inst; done += max_rows)
         launch_ntt_chunk(ctx, data + (size_t)done * ctx->N, std::min(max_rows, n_inst - done), map, inverse, st);

@@ -1,0 +1,266 @@
+// Negacyclic NTT for N = 2^16: two passes of 256-point transforms, each done as two
+// radix-16 steps held in registers with one exchange through LDS in between.
+//
+// Same transform, stage order, twiddle tables (psi^bitrev(k)) and output order as the
+// generic kernels in ntt.hip: the 16 stages of the Cooley-Tukey network (Gentleman-
+// Sande for the inverse) are cut 4 + 4 | 4 + 4.  Viewing a limb as 256 x 256 (row-
+// major), the column pass covers the stages whose butterflies span rows and the row
+// pass those inside a row.  In a 4-stage step a thread owns 16 elements whose
+// indices differ in the 4 bits the step works on; the twiddle of local stage k and
+// local butterfly group g is table[(Mbase << k) + g] with
+//   Mbase = 1 | 16 + j | 256 + r | (256 + r) * 16 + j
+// for column step 1 | column step 2 | row step 1 | row step 2 (j: the thread's slot
+// of 16, r: the row).
+//
+// Arithmetic.  64-bit integer multiplies are a quarter-rate, multi-instruction affair
+// on this chip while fp64 FMAs run at full rate, so limbs whose prime is below 2^50
+// are transformed in fp64: residues are held as exact integers in doubles and a
+// product x*w mod p is  h = x*w; l = fma(x,w,-h); q = rint(x*(w/p)); r = fma(-q,p,h)+l
+// (exact: h - q*p and l are integers below 2^53).  Values are kept lazily within
+// +-8p and brought back with x - rint(x/p)*p between steps.  The special primes
+// (60 bits) use the integer Shoup/Harvey butterflies.  Both produce canonical
+// residues, so results are bit-identical to the generic kernels.
+#include <algorithm>
+
+#include "common.h"
+
+#define N16_THREADS 256
+#define N16_LOG 16
+
+struct ArithInt {
+    typedef u64 T;
+    u64 q, two_q, ninv, ninv_s;
+    __device__ __forceinline__ void init(const PrimeConst &pc) {
+        q = pc.q;
+        two_q = 2 * pc.q;
+        ninv = pc.n_inv;
+        ninv_s = pc.n_inv_s;
+    }
+    __device__ __forceinline__ T load(u64 x) const { return x; }
+    __device__ __forceinline__ T center(T x) const { return x; }
+    __device__ __forceinline__ void ct(T &x, T &y, u64 w, u64 ws) const {  // in/out [0,4q)
+        const T xs = csub(x, two_q);
+        const T t = mul_shoup_lazy(y, w, ws, q);
+        x = xs + t;
+        y = xs - t + two_q;
+    }
+    __device__ __forceinline__ void gs(T &u, T &v, u64 w, u64 ws) const {  // in/out [0,2q)
+        const T s = csub(u + v, two_q);
+        v = mul_shoup_lazy(u - v + two_q, w, ws, q);
+        u = s;
+    }
+    __device__ __forceinline__ T mid(T x) const { return x; }
+    __device__ __forceinline__ u64 store_fwd(T x) const { return csub(csub(x, two_q), q); }
+    __device__ __forceinline__ u64 store_inv(T x) const { return csub(x, q); }
+    __device__ __forceinline__ u64 store_inv_scaled(T x) const { return mul_shoup(x, ninv, ninv_s, q); }
+};
+
+struct ArithFp {
+    typedef double T;
+    double p, pinv, ninv, ninv_p;
+    __device__ __forceinline__ void init(const PrimeConst &pc) {
+        p = (double)pc.q;
+        pinv = __longlong_as_double((long long)pc.pad[1]);
+        ninv = (double)pc.n_inv;
+        ninv_p = __longlong_as_double((long long)pc.pad[2]);
+    }
+    __device__ __forceinline__ T load(u64 x) const { return (double)x; }
+    __device__ __forceinline__ T mid(T x) const { return fma(-rint(x * pinv), p, x); }  // -> |x| <= p/2
+    __device__ __forceinline__ T center(T x) const { return mid(x); }
+    __device__ __forceinline__ T mulmod(T y, T w, T wp) const {  // |y| < 2^53 -> |result| < 2.5p, exact integer
+        const double h = y * w;
+        const double l = fma(y, w, -h);
+        const double q = rint(y * wp);
+        return fma(-q, p, h) + l;
+    }
+    __device__ __forceinline__ void ct(T &x, T &y, u64 w, u64 ws) const {
+        const T t = mulmod(y, __longlong_as_double((long long)w), __longlong_as_double((long long)ws));
+        y = x - t;
+        x = x + t;
+    }
+    __device__ __forceinline__ void gs(T &u, T &v, u64 w, u64 ws) const {
+        const T s = u + v;
+        v = mulmod(u - v, __longlong_as_double((long long)w), __longlong_as_double((long long)ws));
+        u = s;
+    }
+    __device__ __forceinline__ u64 canon(T x) const {
+        T r = mid(x);
+        r = r < 0.0 ? r + p : r;
+        return (u64)r;
+    }
+    __device__ __forceinline__ u64 store_fwd(T x) const { return canon(x); }
+    __device__ __forceinline__ u64 store_inv(T x) const { return canon(x); }
+    __device__ __forceinline__ u64 store_inv_scaled(T x) const { return canon(mulmod(mid(x), ninv, ninv_p)); }
+};
+
+// Four Cooley-Tukey stages on 16 elements whose local index i is the 4 index bits of the step
+// (bit 3 = largest distance).  tw/tws: the prime's forward table and its companion.
+template <class A>
+__device__ __forceinline__ void ct4(const A &ar, typename A::T *v, const u64 *tw, const u64 *tws, u32 mbase) {
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int d = 8 >> k;
+#pragma unroll
+        for (int g = 0; g < (1 << k); g++) {
+            const u64 w = tw[(mbase << k) + g], ws = tws[(mbase << k) + g];
+#pragma unroll
+            for (int o = 0; o < d; o++) {
+                const int i0 = g * 2 * d + o;
+                ar.ct(v[i0], v[i0 + d], w, ws);
+            }
+        }
+    }
+}
+// The inverse of ct4 up to the factor 16 (inverse table).
+template <class A>
+__device__ __forceinline__ void gs4(const A &ar, typename A::T *v, const u64 *tw, const u64 *tws, u32 mbase) {
+#pragma unroll
+    for (int k = 3; k >= 0; k--) {
+        const int d = 8 >> k;
+#pragma unroll
+        for (int g = 0; g < (1 << k); g++) {
+            const u64 w = tw[(mbase << k) + g], ws = tws[(mbase << k) + g];
+#pragma unroll
+            for (int o = 0; o < d; o++) {
+                const int i0 = g * 2 * d + o;
+                ar.gs(v[i0], v[i0 + d], w, ws);
+            }
+        }
+    }
+}
+
+// ---- column pass: tile = 256 rows x 16 columns; thread (c = tid%16, j = tid/16)
+template <bool FWD, class A>
+__device__ __forceinline__ void cols_body(u64 *g, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds) {
+    A ar;
+    ar.init(pc);
+    const int tid = threadIdx.x, c = tid & 15, j = tid >> 4;
+    typename A::T v[16];
+    if (FWD) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ar.load(g[(size_t)(j + 16 * i) * 256 + c]);
+        ct4(ar, v, tw, tws, 1u);
+#pragma unroll
+        for (int i = 0; i < 16; i++) ((typename A::T *)lds)[(j + 16 * i) * 16 + c] = ar.mid(v[i]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ((typename A::T *)lds)[(16 * j + i) * 16 + c];
+        ct4(ar, v, tw, tws, 16u + j);
+#pragma unroll
+        for (int i = 0; i < 16; i++) g[(size_t)(16 * j + i) * 256 + c] = ar.store_fwd(v[i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ar.center(ar.load(g[(size_t)(16 * j + i) * 256 + c]));
+        gs4(ar, v, tw, tws, 16u + j);
+#pragma unroll
+        for (int i = 0; i < 16; i++) ((typename A::T *)lds)[(16 * j + i) * 16 + c] = ar.mid(v[i]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ((typename A::T *)lds)[(j + 16 * i) * 16 + c];
+        gs4(ar, v, tw, tws, 1u);
+#pragma unroll
+        for (int i = 0; i < 16; i++) g[(size_t)(j + 16 * i) * 256 + c] = ar.store_inv_scaled(v[i]);
+    }
+}
+
+// ---- row pass: tile = 16 contiguous rows; thread (rho = tid/16, j = tid%16).  LDS positions are
+// padded by one word per 16 so that both the strided and the contiguous 16-element patterns are
+// conflict-free; global traffic is fully coalesced (the contiguous-per-thread layout only ever
+// touches LDS).
+__device__ __forceinline__ int rpad(int p) { return p + (p >> 4); }
+
+template <bool FWD, class A>
+__device__ __forceinline__ void rows_body(u64 *g, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds, int r0) {
+    A ar;
+    ar.init(pc);
+    const int tid = threadIdx.x, rho = tid >> 4, j = tid & 15;
+    const u32 r = (u32)(r0 + rho);
+    typename A::T v[16];
+    typename A::T *l = (typename A::T *)lds;
+    if (FWD) {
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ar.load(g[rho * 256 + j + 16 * i]);
+        ct4(ar, v, tw, tws, 256u + r);
+#pragma unroll
+        for (int i = 0; i < 16; i++) l[rpad(rho * 256 + j + 16 * i)] = ar.mid(v[i]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + 16 * j + i)];
+        ct4(ar, v, tw, tws, (256u + r) * 16u + j);
+#pragma unroll
+        for (int i = 0; i < 16; i++) lds[rpad(rho * 256 + 16 * j + i)] = ar.store_fwd(v[i]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) g[tid + 256 * i] = lds[rpad(tid + 256 * i)];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; i++) lds[rpad(tid + 256 * i)] = g[tid + 256 * i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = ar.center(ar.load(lds[rpad(rho * 256 + 16 * j + i)]));
+        gs4(ar, v, tw, tws, (256u + r) * 16u + j);
+#pragma unroll
+        for (int i = 0; i < 16; i++) l[rpad(rho * 256 + 16 * j + i)] = ar.mid(v[i]);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + j + 16 * i)];
+        gs4(ar, v, tw, tws, 256u + r);
+#pragma unroll
+        for (int i = 0; i < 16; i++) g[rho * 256 + j + 16 * i] = ar.store_inv(v[i]);
+    }
+}
+
+template <bool FWD>
+__global__ __launch_bounds__(N16_THREADS) void k_ntt16_cols(u64 *data, const u64 *tw_all, const PrimeConst *pcs, LimbMap map) {
+    __shared__ u64 lds[4096];
+    const int inst = blockIdx.y;
+    const int prime = map.prime[inst % map.n];
+    const PrimeConst pc = pcs[prime];
+    const size_t N = (size_t)1 << N16_LOG;
+    const u64 *tw = tw_all + (size_t)prime * 4 * N + (FWD ? 0 : 2 * N);
+    u64 *g = data + (size_t)inst * N + (size_t)blockIdx.x * 16;
+    if (pc.pad[0]) cols_body<FWD, ArithFp>(g, tw, tw + N, pc, lds);
+    else cols_body<FWD, ArithInt>(g, tw, tw + N, pc, lds);
+}
+
+template <bool FWD>
+__global__ __launch_bounds__(N16_THREADS) void k_ntt16_rows(u64 *data, const u64 *tw_all, const PrimeConst *pcs, LimbMap map) {
+    __shared__ u64 lds[4096 + 256];
+    const int inst = blockIdx.y;
+    const int prime = map.prime[inst % map.n];
+    const PrimeConst pc = pcs[prime];
+    const size_t N = (size_t)1 << N16_LOG;
+    const u64 *tw = tw_all + (size_t)prime * 4 * N + (FWD ? 0 : 2 * N);
+    const int r0 = blockIdx.x * 16;
+    u64 *g = data + (size_t)inst * N + (size_t)r0 * 256;
+    if (pc.pad[0]) rows_body<FWD, ArithFp>(g, tw, tw + N, pc, lds, r0);
+    else rows_body<FWD, ArithInt>(g, tw, tw + N, pc, lds, r0);
+}
+
+void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st) {
+    const int max_rows = (32768 / map.n) * map.n;
+    for (int done = 0; done < n_inst; done += max_rows) {
+        const int cnt = std::min(max_rows, n_inst - done);
+        u64 *d = data + (size_t)done * ctx->N;
+        dim3 grid(16, cnt);
+        if (!inverse) {
+            {
+                ScopedTimer t(ctx, "ntt_fwd_cols", st);
+                hipLaunchKernelGGL(k_ntt16_cols<true>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+            }
+            {
+                ScopedTimer t(ctx, "ntt_fwd_rows", st);
+                hipLaunchKernelGGL(k_ntt16_rows<true>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+            }
+        } else {
+            {
+                ScopedTimer t(ctx, "ntt_inv_rows", st);
+                hipLaunchKernelGGL(k_ntt16_rows<false>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+            }
+            {
+                ScopedTimer t(ctx, "ntt_inv_cols", st);
+                hipLaunchKernelGGL(k_ntt16_cols<false>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+            }
+        }
+    }
+}

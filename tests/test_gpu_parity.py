@@ -261,3 +261,82 @@ def test_error_paths(tiny):
     low.free()
     g_ct.free()
     g_gk.free()
+
+
+# ---------------------------------------------------------------- full ring (N = 2^16)
+KEYSWITCH = wl.WORKLOADS[1].param_tuple()  # 10 x 50-bit + 3 x 60-bit, alpha = 3
+
+
+@pytest.fixture(scope="module")
+def full():
+    p = Pair(KEYSWITCH)
+    yield p
+    p.close()
+
+
+def test_full_ring_ntt_roundtrip_and_evaluation_set(full):
+    """The N = 2^16 transform (register radix-16 steps; fp64 arithmetic on the 50-bit primes,
+    integer arithmetic on the 60-bit ones)."""
+    rng = np.random.default_rng(10)
+    L = full.pr.L
+    primes = full.pr.q + full.pr.p
+    idx = [0, L - 1, L, L + 2]  # two 50-bit primes, two 60-bit primes
+    x = np.stack([rng.integers(0, full.pr.q[-1], size=full.N, dtype=np.uint64) for _ in idx])
+    x[0, :4] = [0, 1, full.pr.q[0] - 1, full.pr.q[0] // 2]
+    x[0] %= np.uint64(full.pr.q[0])
+    ct = full.ctx.ct_import(x.reshape(2, 2, 1, full.N) % np.uint64(full.pr.q[0]), 1.0)
+    x = ct.export().reshape(4, full.N)
+    full.ctx.ntt(ct.device_ptr, idx, inverse=False)
+    fwd = ct.export().reshape(4, full.N)
+    want = full.o.ntt(x, [primes[i] for i in idx])
+    assert np.array_equal(np.sort(fwd, axis=1), np.sort(want, axis=1))
+    full.ctx.ntt(ct.device_ptr, idx, inverse=True)
+    assert np.array_equal(ct.export().reshape(4, full.N), x)
+    ct.free()
+
+
+def test_full_ring_rotate_bit_exact(full):
+    p = full
+    steps = [1, -1, 4096]
+    o_gks, g_gk = p.galois_keys(sorted(set(steps)))
+    z = p.rng.uniform(-1, 1, (len(steps), p.n))
+    for limbs in (p.pr.L, 4):
+        o_cts, g_ct = p.encrypt_both(z, limbs)
+        assert np.array_equal(g_ct.export(), stack_cts(o_cts))
+        out = p.ctx.rotate(g_gk, g_ct, steps)
+        want = [p.o.rotate(c, o_gks[st]) for c, st in zip(o_cts, steps)]
+        assert np.array_equal(out.export(), stack_cts(want)), "limbs=%d" % limbs
+        dec = p.ctx.decrypt(p.g_sk, out, 0, 256)
+        for i, st in enumerate(steps):
+            assert np.abs(dec[i] - np.roll(z[i], -st)[:256]).max() < 1e-3
+        out.free()
+        g_ct.free()
+    g_gk.free()
+
+
+def test_full_ring_matmul_bit_exact(full):
+    p = full
+    s, d, m = p.n // 4, 6, 5  # c_tot = 4: two packed inputs, rotations by 1..3 blocks
+    rng = np.random.default_rng(11)
+    W = wl.ternary_weights(rng, d, m)
+    W[0, 0], W[5, 4] = 1, -1
+    X = np.clip(rng.standard_normal((s, d)), -4, 4)
+    packed = wl.pack_columns(X, p.n)
+    o_cts, g_ct = p.encrypt_both(packed, p.pr.L)
+    o_by_step, g_gk = p.galois_keys([r * s for r in range(1, 4)])
+    o_gks = {r: o_by_step[r * s] for r in range(1, 4)}
+    want = stack_cts(p.o.ternary_matmul(o_cts, s, d, W, "diagonal", o_gks))
+    for mode in (1, 2):
+        p.ctx.set_accumulate_mode(mode)
+        out = p.ctx.ternary_matmul(g_gk, g_ct, s, d, W, "diagonal")
+        assert np.array_equal(out.export(), want), "accumulate mode %d" % mode
+        if mode == 1:
+            out.free()
+    p.ctx.set_accumulate_mode(0)
+    ref = X @ W.astype(np.float64)
+    for i in range(m):
+        one = p.ctx.decrypt(p.g_sk, out, (i % 4) * s, 512)
+        assert np.abs(one[i] - ref[:512, i]).max() < 1e-3
+    out.free()
+    g_ct.free()
+    g_gk.free()
