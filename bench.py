@@ -26,6 +26,7 @@ sys.path.insert(0, ROOT)
 import workloads as wl  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0
+INT8_MFMA_PEAK_TOPS = 5000.0  # dense int8 matrix-core peak, TOP/s
 # plain integer ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit lane-ops/s; one 64-bit add = 2 of them
 U64_ADD_PEAK = 256 * 4 * 16 * 2.4e9 / 2
 
@@ -158,7 +159,7 @@ def roofline_for(w, prof):
     groups = {
         "ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"],
         "inner_product": ["inner_product"], "modup": ["modup"], "moddown": ["moddown"],
-        "accumulate": ["accumulate"], "mul_scalar_rescale": ["mul_scalar_rescale"],
+        "accumulate": ["accumulate"], "accumulate_mfma": ["accumulate_mfma"], "mul_scalar_rescale": ["mul_scalar_rescale"],
     }
     tot = {g: sum(prof.get(k, (0.0, 0))[0] for k in ks) for g, ks in groups.items()}
     dom = max(tot, key=tot.get)
@@ -176,6 +177,15 @@ def roofline_for(w, prof):
         return dom, {"bound": "hbm", "achieved": algo / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "kernel": "ntt (both passes, forward+inverse)",
                      "launch_ms": ms, "limb_transforms": limbs}
+    if dom == "accumulate_mfma":
+        # Alg. 1 on the matrix cores: one int8 multiply-add per (output, operand, limb word, byte plane); 7 planes at 50 bits
+        planes = -(-w.q_bits // 8)
+        planes = 5 if planes <= 5 else 7 if planes <= 7 else 8
+        dm = w.d_in * (w.d_mid or w.d_out) + (w.d_mid * w.d_out if w.d_mid else 0)
+        ops = 2.0 * dm * 2 * L * N * planes
+        return dom, {"bound": "mfma", "achieved": ops / (ms * 1e-3) / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None, "kernel": "accumulate_mfma",
+                     "launch_ms": ms, "launches": prof.get("accumulate_mfma", (0, 1))[1]}
     if dom == "inner_product":
         algo = unit * n_rot * (3 * beta * ext + 2 * ext)
     elif dom == "modup":

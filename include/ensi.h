@@ -134,8 +134,9 @@ int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct, int32_t sl
 /* Cyclic left shift of the slot vector by steps[i] (negative = inverse
  * rotation), by the automorphism X -> X^g and hybrid key switching:
  * digit-decompose c1, ModUp each digit to Q_l + P (fast basis conversion, no
- * correction), automorphism, inner product with the key, ModDown (no rounding
- * offset), add phi_g(c0).  steps: host int32[n].  in and out are batches of
+ * correction), automorphism, inner product with the key, ModDown (basis
+ * conversion P -> Q_l on centred residues, so the division error is zero-mean),
+ * add phi_g(c0).  steps: host int32[n].  in and out are batches of
  * equal n and limbs and must not overlap.  Level and scale are unchanged. */
 int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream);
 
@@ -156,13 +157,14 @@ int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int
 
 /* Selects the kernel that forms the signed sums of Alg. 1: 0 = automatic (the
  * int8 matrix-core contraction over byte planes whenever N >= 32 and the exact
- * sum of the operands fits 62 bits, else the plain-ALU kernel), 1 = always the
+ * sum of the operands fits a signed 64-bit word, else the plain-ALU kernel), 1 = always the
  * plain-ALU kernel, 2 = same as 0.  Both give identical residues. */
 int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode);
 
 /* ---- scalar multiply + rescale (between two PCMM layers) ---------------- */
 /* In place on the whole batch: c <- c * round(kappa q_l) mod q_i, then limb l
- * is dropped: c_i <- (c_i - (c_l mod q_i)) q_l^{-1} mod q_i.  limbs decreases
+ * is dropped: c_i <- (c_i - [c_l]) q_l^{-1} mod q_i with [c_l] the centred
+ * representative of limb l (division with rounding to nearest).  limbs decreases
  * by one (limbs_alloc is unchanged).  The encoded values are multiplied by
  * kappa (0 < |kappa| < 1); the scale absorbs only the rounding of the constant:
  * scale' = scale * round(kappa q_l) / (kappa q_l). */

@@ -251,10 +251,10 @@ class Oracle:
         return self.decode_coeffs(self.decrypt_coeffs(ct, sk), ct.scale).real
 
     # ---------------------------------------------------------- key switching
-    def bconv(self, src, qs, inv, tgt, hat):
+    def bconv(self, src, qs, inv, tgt, hat, centered=False):
         out = np.empty((len(tgt), self.N), dtype=np.uint64)
         self.lib.orc_bconv(_p(out), _p(np.ascontiguousarray(src)), len(qs), len(tgt), self.N, _p(_u64(qs)), _p(_u64(inv)),
-                           _p(_u64(hat)), _p(_u64(tgt)))
+                           _p(_u64(hat)), _p(_u64(tgt)), int(centered))
         return out
 
     def mod_up(self, c1):
@@ -271,10 +271,14 @@ class Oracle:
         return out
 
     def mod_down(self, u, l1):
-        """[l1+K][N] -> [l1][N]: (u - BConv_{P->Q}([u]_P)) * P^{-1} mod q_i, no rounding offset."""
+        """[l1+K][N] -> [l1][N]: (u - BConv_{P->Q}([u]_P)) * P^{-1} mod q_i.  The conversion takes
+        the residues [u P_k^^-1]_{p_k} centred, so what is subtracted is [u]_P + v P with v
+        symmetric around zero: the division error then has no constant component (an uncentred
+        conversion leaves a mean of about (K-1)/2 per coefficient, which the decoding
+        concentrates on the few slots whose roots are nearest 1)."""
         pr = self.pr
         inv, tgt, hat, p_inv = pr.moddown_constants(l1)
-        r = self.bconv(u[l1:], pr.p, inv, tgt, hat)
+        r = self.bconv(u[l1:], pr.p, inv, tgt, hat, centered=True)
         return self.mul_scalar(self.sub(np.ascontiguousarray(u[:l1]), r, tgt), p_inv, tgt)
 
     def _key_at_level(self, gk, l1):
@@ -372,7 +376,8 @@ class Oracle:
     # --------------------------------------------------------------- rescale
     def mul_scalar_rescale(self, ct, kappa):
         """c <- c * round(kappa q_l) (negative constants as q_i - |.|), then drop limb l:
-        c'_i = (c_i - (c_l mod q_i)) q_l^{-1} mod q_i, no rounding offset.  The encoded
+        c'_i = (c_i - [c_l]) q_l^{-1} mod q_i with [c_l] the centred representative of limb l in
+        (-q_l/2, q_l/2] (division with rounding to nearest: zero-mean error).  The encoded
         values are multiplied by kappa; the scale only absorbs the rounding of the
         constant: scale' = scale * round(kappa q_l) / (kappa q_l)."""
         pr = self.pr
@@ -386,6 +391,8 @@ class Oracle:
         out = []
         for c in (ct.c0, ct.c1):
             c = self.mul_scalar(np.ascontiguousarray(c), const, q)
-            last = np.stack([c[l1 - 1] % np.uint64(m) for m in rest])
+            top = c[l1 - 1]
+            neg = top > np.uint64(ql // 2)  # centred representative is top - ql
+            last = np.stack([np.where(neg, (top % np.uint64(m) + np.uint64(m - ql % m)) % np.uint64(m), top % np.uint64(m)) for m in rest])
             out.append(self.mul_scalar(self.sub(np.ascontiguousarray(c[: l1 - 1]), last, rest), ql_inv, rest))
         return Ciphertext(out[0], out[1], ct.scale * k / (kappa * ql))

@@ -176,19 +176,26 @@ void orc_automorphism(uint64_t *out, const uint64_t *in, int n_limbs, int n, uin
         }
 }
 
-/* Fast basis conversion (no correction term).  Source limbs in[a][.] mod qs[a],
- * a < A.  For every target modulus t[k]:
- *   out[k][i] = sum_a ( in[a][i] * inv[a] mod qs[a] ) * hat_mod_t[k][a]   mod t[k]
- * where inv[a] = (Qs/qs[a])^{-1} mod qs[a], hat_mod_t[k][a] = (Qs/qs[a]) mod t[k]. */
+/* Fast basis conversion.  Source limbs in[a][.] mod qs[a], a < A.  For every target
+ * modulus t[k]:
+ *   out[k][i] = sum_a  y_a * hat_mod_t[k][a]   mod t[k],   y_a = in[a][i] * inv[a] mod qs[a]
+ * where inv[a] = (Qs/qs[a])^{-1} mod qs[a], hat_mod_t[k][a] = (Qs/qs[a]) mod t[k].
+ * centered = 0: y_a is taken in [0, qs[a])            (the sum is x + u*Qs, 0 <= u < A);
+ * centered = 1: y_a is taken in (-qs[a]/2, qs[a]/2]   (the sum is x + u*Qs, |u| <= A/2, zero mean).
+ * No floating-point correction of u in either case. */
 void orc_bconv(uint64_t *out, const uint64_t *in, int A, int T, int n, const uint64_t *qs, const uint64_t *inv,
-               const uint64_t *hat_mod_t, const uint64_t *t) {
+               const uint64_t *hat_mod_t, const uint64_t *t, int centered) {
 #pragma omp parallel for
     for (int k = 0; k < T; k++)
         for (int i = 0; i < n; i++) {
             uint64_t acc = 0;
             for (int a = 0; a < A; a++) {
                 uint64_t y = mulmod(in[(size_t)a * n + i], inv[a], qs[a]);
-                acc = addmod(acc, mulmod(y, hat_mod_t[(size_t)k * A + a], t[k]), t[k]);
+                uint64_t h = hat_mod_t[(size_t)k * A + a];
+                if (centered && y > qs[a] / 2)
+                    acc = submod(acc, mulmod(qs[a] - y, h, t[k]), t[k]); /* y - qs[a] is negative */
+                else
+                    acc = addmod(acc, mulmod(y, h, t[k]), t[k]);
             }
             out[(size_t)k * n + i] = acc;
         }

@@ -59,7 +59,7 @@ __device__ __forceinline__ void transpose4(u32 a0, u32 a1, u32 a2, u32 a3, u32 *
     p[3] = __builtin_amdgcn_perm(t3, t1, 0x07060302u);
 }
 
-// signed 64-bit T (|T| < 2^62, |T|/q < 2^31) to its canonical residue mod q
+// signed 64-bit T (|T| < 2^63, |T|/q < 2^31) to its canonical residue mod q
 __device__ __forceinline__ u64 reduce_signed(int64_t t, u64 q, double q_inv) {
     const int k = (int)rint((double)t * q_inv);
     int64_t r = t - (int64_t)k * (int64_t)q;

@@ -257,6 +257,7 @@ static void free_modconst(ensi_ctx *ctx) {
         (void)hipFree(kv.second.hat);
         (void)hipFree(kv.second.pinv);
         (void)hipFree(kv.second.pinv_s);
+        (void)hipFree(kv.second.negtab);
     }
 }
 
@@ -339,7 +340,7 @@ static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
         mc.l1 = l1;
         mc.K = ctx->K;
         const int K = ctx->K, L = ctx->L;
-        std::vector<u64> inv(K), inv_s(K), hat((size_t)l1 * K), pinv(l1), pinv_s(l1);
+        std::vector<u64> inv(K), inv_s(K), hat((size_t)l1 * K), pinv(l1), pinv_s(l1), negtab((size_t)l1 * (K + 1));
         for (int k = 0; k < K; k++) {
             const u64 pk = ctx->primes[L + k];
             u64 prod = 1;
@@ -354,6 +355,7 @@ static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
             for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
             pinv[i] = hm_invmod(P, q);
             pinv_s[i] = hm_shoup(pinv[i], q);
+            for (int j = 0; j <= K; j++) negtab[(size_t)i * (K + 1) + j] = hm_mulmod((u64)j, P, q);
             for (int k = 0; k < K; k++) {
                 u64 h = 1;
                 for (int b = 0; b < K; b++)
@@ -362,7 +364,7 @@ static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
             }
         }
         if (upload(&mc.inv, inv) != hipSuccess || upload(&mc.inv_s, inv_s) != hipSuccess || upload(&mc.hat, hat) != hipSuccess ||
-            upload(&mc.pinv, pinv) != hipSuccess || upload(&mc.pinv_s, pinv_s) != hipSuccess)
+            upload(&mc.pinv, pinv) != hipSuccess || upload(&mc.pinv_s, pinv_s) != hipSuccess || upload(&mc.negtab, negtab) != hipSuccess)
             ENSI_FAIL(ctx, ENSI_E_HIP, "uploading ModDown constants failed");
         it = ctx->moddown.insert({l1, mc}).first;
     }
@@ -860,12 +862,11 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
     }
     const int n_v = p->n_v;
     // matrix-core layout is valid when a 32-word tile stays inside a limb and the exact
-    // signed sum of n_v residues fits 62 bits
+    // signed sum of n_v residues fits a signed 64-bit word
     int qbits = 0;
     for (int i = 0; i < l1; i++) qbits = std::max(qbits, 64 - __builtin_clzll(ctx->primes[i]));
-    int log_nv = 0;
-    while ((1 << log_nv) < std::max(n_v, 1)) log_nv++;
-    const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && qbits + log_nv <= 62;
+    // |sum of n_v residues| <= n_v * (2^qbits - 1) must stay below 2^63
+    const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && qbits <= 56 && (u64)n_v <= ((u64)1 << (63 - qbits));
     p->planes = 0;
     p->n_kpad = (std::max(n_v, 1) + 255) / 256 * 256;  // whole groups of eight 32-operand steps
     p->m_pad = (m + 255) / 256 * 256;
@@ -1030,7 +1031,7 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
     const u64 ql = ctx->primes[l1 - 1];
     const double kr = floor(fabs(kappa) * (double)ql + 0.5);
     const u64 kabs = (u64)kr;
-    std::vector<u64> consts(4 * (size_t)l1, 0);
+    std::vector<u64> consts(5 * (size_t)l1, 0);
     for (int i = 0; i < l1; i++) {
         const u64 q = ctx->primes[i];
         u64 k = kabs % q;
@@ -1040,6 +1041,7 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
         if (i < l1 - 1) {
             consts[2 * l1 + i] = hm_invmod(ql % q, q);
             consts[3 * l1 + i] = hm_shoup(consts[2 * l1 + i], q);
+            consts[4 * l1 + i] = ql % q;
         }
     }
     int rc;

@@ -48,6 +48,7 @@ struct ModDownConst {
     u64 *hat;      // [l1][K]  (P/p_k) mod q_i, Montgomery form
     u64 *pinv;     // [l1]  P^{-1} mod q_i
     u64 *pinv_s;   // [l1]
+    u64 *negtab;   // [l1][K+1]  j * (P mod q_i) mod q_i: what j negative centred residues add to the conversion
 };
 
 // One rotation to perform: everything the fused kernels need, device-resident.

@@ -118,15 +118,22 @@ __global__ __launch_bounds__(EW_THREADS) void k_moddown(ModDownConst mc, const R
     const u32 isrc = neg ? i0 - N : i0;
     for (int poly = 0; poly < 2; poly++) {
         const u64 *up = u + ((size_t)blockIdx.y * 2 + poly) * ext * N;
+        // residues [u * (P/p_k)^-1]_{p_k}; the conversion takes them centred, i.e. every residue above
+        // p_k/2 stands for itself minus p_k, which changes the converted value by -(P mod q_i)
         u64 y[ENSI_MAX_K];
+        int n_neg = 0;
         for (int k = 0; k < ENSI_MAX_K; k++)
-            if (k < mc.K) y[k] = mul_shoup(up[(size_t)(mc.l1 + k) * N + idx], mc.inv[k], mc.inv_s[k], pc[L + k].q);
+            if (k < mc.K) {
+                const u64 pk = pc[L + k].q;
+                y[k] = mul_shoup(up[(size_t)(mc.l1 + k) * N + idx], mc.inv[k], mc.inv_s[k], pk);
+                n_neg += y[k] > pk / 2 ? 1 : 0;
+            }
         for (int i = 0; i < mc.l1; i++) {
             const PrimeConst p = pc[i];
             acc128 acc = {0, 0};
             for (int k = 0; k < ENSI_MAX_K; k++)
                 if (k < mc.K) mac128(acc, y[k], mc.hat[i * mc.K + k]);
-            u64 r = mont_reduce(acc, p.q, p.qneg_inv);
+            u64 r = sub_mod(mont_reduce(acc, p.q, p.qneg_inv), mc.negtab[i * (mc.K + 1) + n_neg], p.q);
             u64 v = mul_shoup(sub_mod(up[(size_t)i * N + idx], r, p.q), mc.pinv[i], mc.pinv_s[i], p.q);
             if (poly == 0) {
                 u64 c = d.c0[(size_t)i * N + isrc];
@@ -218,7 +225,7 @@ void launch_accumulate(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v,
 }
 
 // ------------------------------------------------------- scalar multiply + rescale
-// consts: [4][l1]: k mod q_i, Shoup(k), q_l^{-1} mod q_i, Shoup(.)  (row 2,3 unused at i = l1-1)
+// consts: [5][l1]: k mod q_i, Shoup(k), q_l^{-1} mod q_i, Shoup(.), q_l mod q_i  (rows 2..4 unused at i = l1-1)
 // grid (N/256, 2, n_ct)
 __global__ __launch_bounds__(EW_THREADS) void k_rescale(u64 *ct, int l1, int limb_stride, int N, const PrimeConst *pc,
                                                         const u64 *consts) {
@@ -228,6 +235,7 @@ __global__ __launch_bounds__(EW_THREADS) void k_rescale(u64 *ct, int l1, int lim
     const int last = l1 - 1;
     const u64 ql = pc[last].q;
     const u64 xl = mul_shoup(c[(size_t)last * N + idx], consts[last], consts[l1 + last], ql);
+    const bool neg = xl > ql / 2;
     for (int i = 0; i < last; i++) {
         const u64 q = pc[i].q;
         u64 v = mul_shoup(c[(size_t)i * N + idx], consts[i], consts[l1 + i], q);
@@ -236,6 +244,8 @@ __global__ __launch_bounds__(EW_THREADS) void k_rescale(u64 *ct, int l1, int lim
             r -= q;
             if (r >= q) r %= q;
         }
+        // centred representative of limb l: values above q_l/2 stand for themselves minus q_l
+        if (neg) r = sub_mod(r, consts[4 * l1 + i], q);
         c[(size_t)i * N + idx] = mul_shoup(sub_mod(v, r, q), consts[2 * l1 + i], consts[3 * l1 + i], q);
     }
 }

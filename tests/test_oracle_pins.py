@@ -197,7 +197,7 @@ def test_modup_is_digit_plus_small_multiple_of_Qj(widx, all_small):
 
 
 @pytest.mark.parametrize("widx", [0, 1, 3])
-def test_moddown_is_exact_division_up_to_small_integer(widx, all_small):
+def test_moddown_is_exact_division_up_to_small_symmetric_integer(widx, all_small):
     pr = all_small[widx]
     o = Oracle(pr)
     rng = np.random.default_rng(8)
@@ -208,10 +208,12 @@ def test_moddown_is_exact_division_up_to_small_integer(widx, all_small):
     for idx in range(0, o.N, 29):
         full, _ = crt([u[i, idx] for i in range(len(ext))], ext)
         up, P = crt([u[l1 + k, idx] for k in range(pr.K)], pr.p)
+        up = up - P if up > P // 2 else up  # centred representative of [u]_P
         exact = (full - up) // P
         assert (full - up) % P == 0
-        vs = {(exact - int(out[i, idx])) % pr.q[i] for i in range(l1)}
-        assert len(vs) == 1 and 0 <= vs.pop() < pr.K
+        # out = (u - [u]_P)/P - v ([u]_P centred) with one small integer v per coefficient, |v| <= K/2
+        vs = {(exact - int(out[i, idx]) + pr.K) % pr.q[i] - pr.K for i in range(l1)}
+        assert len(vs) == 1 and abs(vs.pop()) <= pr.K / 2
 
 
 def test_rescale_is_exact_division(all_small):
@@ -232,7 +234,10 @@ def test_rescale_is_exact_division(all_small):
         for src, dst in ((c0, out.c0), (c1, out.c1)):
             val, Q = crt([src[i, idx] for i in range(l1)], q)
             val = val * k % Q
-            exact = (val - val % ql) // ql
+            top = val % ql
+            top = top - ql if top > ql // 2 else top  # centred: division with rounding to nearest
+            exact = (val - top) // ql
+            assert (val - top) % ql == 0 and abs(exact * ql - val) <= ql // 2
             assert [int(dst[i, idx]) for i in range(l1 - 1)] == [exact % m for m in q[:-1]]
 
 
