@@ -251,7 +251,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="attn2560", choices=[w.name for w in wl.WORKLOADS])
+    ap.add_argument("--workload", default="ffn2560", choices=[w.name for w in wl.WORKLOADS])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-keyswitch-leg", action="store_true")
     args = ap.parse_args()
