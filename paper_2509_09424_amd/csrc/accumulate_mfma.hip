@@ -80,7 +80,8 @@ struct AmLayout {
     static constexpr int planes_off = 0;                              // [2][plane_bytes]
     static constexpr int xring_off = 2 * plane_bytes;                 // [AM_RING][AM_XSLOT]
     static constexpr int aring_off = xring_off + AM_RING * AM_XSLOT;  // [4 waves][AM_RING][AM_ASLOT]
-    static constexpr int total = aring_off + 4 * AM_RING * AM_ASLOT;
+    static constexpr int bias_off = aring_off + 4 * AM_RING * AM_ASLOT;  // [256] offset terms of the item's outputs
+    static constexpr int total = bias_off + AM_TILE_M * 4;
 };
 
 template <int PLANES>
@@ -130,41 +131,44 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
         const char *px1 = px0 + 4 * (u64)xstride * sizeof(u64);
         const char *pa = (const char *)(wfrag + ((size_t)m_tile * nk * 4 + wv) * 128 + lane);
 
-        auto issue_x = [&](int step, int slot) {  // raw words of `step` -> ring slot; 2 copies per wave
-            const u32 dst = x_lds + (u32)slot * AM_XSLOT;
+        // one of the wave's two copies of the raw words of `step` -> ring slot (copy c = rows 4c..4c+3 of the wave's 8)
+        auto issue_x = [&](int step, int slot, int c) {
+            const u32 dst = x_lds + (u32)slot * AM_XSLOT + c * AM_XBLOCK;
             if ((step + 1) * AM_TILE_K <= n_v) {
-                dma_load16(px0, dst);
-                dma_load16(px1, dst + AM_XBLOCK);
-                px0 += step_bytes;
-                px1 += step_bytes;
+                dma_load16(c ? px1 : px0, dst);
             } else {
                 const int st = step < nk ? step : nk - 1;
-#pragma unroll
-                for (int c = 0; c < 2; c++) {
-                    int v = st * AM_TILE_K + row0 + 4 * c;
-                    v = v < n_v ? v : n_v - 1;
-                    dma_load16(xlane + (u64)(u32)v * (u64)xstride, dst + c * AM_XBLOCK);
-                }
+                int v = st * AM_TILE_K + row0 + 4 * c;
+                v = v < n_v ? v : n_v - 1;
+                dma_load16(xlane + (u64)(u32)v * (u64)xstride, dst);
+            }
+            if (c == 1 && (step + 1) * AM_TILE_K <= n_v) {
+                px0 += step_bytes;
+                px1 += step_bytes;
             }
         };
-        auto issue_a = [&](int step, int slot) {  // this wave's fragments of `step` -> ring slot; 2 copies
-            const u32 dst = a_lds + (u32)slot * AM_ASLOT;
-            dma_load16(pa, dst);
-            dma_load16(pa + 1024, dst + 1024);
-            pa += step + 1 < nk ? 8192 : 0;
+        // one of the wave's two weight fragments of `step` -> ring slot
+        auto issue_a = [&](int step, int slot, int c) {
+            dma_load16(pa + c * 1024, a_lds + (u32)slot * AM_ASLOT + c * 1024);
+            if (c == 1) pa += step + 1 < nk ? 8192 : 0;
         };
-        auto planes_of = [&](int slot, u32 *pl) {  // read the thread's 4 raw words, transpose
+        auto raw_words = [&](int slot, u64 *w) {
             const char *src = x_rd + slot * AM_XSLOT;
-            u64 w[4];
 #pragma unroll
             for (int j = 0; j < 4; j++) w[j] = *(const u64 *)(src + j * 256);
-            transpose4((u32)w[0], (u32)w[1], (u32)w[2], (u32)w[3], pl);
-            transpose4((u32)(w[0] >> 32), (u32)(w[1] >> 32), (u32)(w[2] >> 32), (u32)(w[3] >> 32), pl + 4);
         };
         auto write_planes = [&](int parity, const u32 *pl) {
             int *cells = p_wr + parity * (LY::plane_bytes / 4);
 #pragma unroll
             for (int p = 0; p < PLANES; p++) cells[p * AM_PLANE_CELLS * 4] = (int)(pl[p] ^ 0x80808080u);
+        };
+        auto build_planes = [&](int slot, int parity) {
+            u64 w[4];
+            u32 pl[8];
+            raw_words(slot, w);
+            transpose4((u32)w[0], (u32)w[1], (u32)w[2], (u32)w[3], pl);
+            transpose4((u32)(w[0] >> 32), (u32)(w[1] >> 32), (u32)(w[2] >> 32), (u32)(w[3] >> 32), pl + 4);
+            write_planes(parity, pl);
         };
 
         v16i acc[PLANES][2];
@@ -178,49 +182,81 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
         // drain the previous item's loads and stores: inside the step loop only the copies are in flight
         wait_vmcnt<0>();
         __syncthreads();  // every wave is done with the LDS contents of the previous item
-        // prologue: X(0), then (X(t+1), A(t)) for t = 0..DEPTH-1  -- same order as the steady state
-        issue_x(0, 0);
+        ((int *)(smem + LY::bias_off))[tid] = bias[m_tile * AM_TILE_M + tid];
+        // Copies are issued in one fixed order, "iteration j issues X(j+9) then A(j+8)", from j = -9 on, so that
+        // waiting until at most 24 copies are outstanding always means: everything of iteration j-6 has landed.
+        issue_x(0, 0, 0);
+        issue_x(0, 0, 1);
 #pragma unroll
-        for (int t = 0; t < AM_DEPTH; t++) {
-            issue_x(t + 1, t + 1);
-            issue_a(t, t);
+        for (int t = 0; t < AM_DEPTH; t++) {  // iterations -8 .. -2
+            issue_x(t + 1, t + 1, 0);
+            issue_x(t + 1, t + 1, 1);
+            issue_a(t, t, 0);
+            issue_a(t, t, 1);
         }
         wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(0), X(1), A(0) have landed
         __syncthreads();
-        {
-            u32 pl[8];
-            planes_of(0, pl);
-            write_planes(0, pl);
-        }
+        build_planes(0, 0);
+        build_planes(1, 1);
+        __syncthreads();  // planes(0), planes(1) visible; X(0) consumed by everyone
+        issue_x(AM_RING, 0, 0);  // iteration -1
+        issue_x(AM_RING, 0, 1);
+        issue_a(AM_DEPTH, AM_DEPTH, 0);
+        issue_a(AM_DEPTH, AM_DEPTH, 1);
+        // fragments of step 0 into registers
+        v4i bfc[PLANES], a0c, a1c;
+#pragma unroll
+        for (int p = 0; p < PLANES; p++) bfc[p] = p_rd[p * AM_PLANE_CELLS];
+        a0c = *(const v4i *)a_rd;
+        a1c = *(const v4i *)(a_rd + 1024);
+        wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(2), A(1) have landed
         __syncthreads();
 
-        // nk is a multiple of AM_RING (the plan pads the operand count with zero weights)
+        // nk is a multiple of AM_RING (the plan pads the operand count with zero weights).
+        // Step ks multiplies from registers filled during step ks-1; meanwhile it reads the fragments of step
+        // ks+1 (planes buffer (ks+1)&1, A slot (ks+1)%RING), builds the planes of step ks+2 from the raw words
+        // in X slot (ks+2)%RING into planes buffer ks&1 (whose contents are already in registers), and issues
+        // the copies X(ks+9) -> slot of X(ks+1) and A(ks+8) -> slot of A(ks).  Scheduling fences keep the LDS
+        // reads, the copies and the vector work spread between the matrix instructions.
         for (int ks0 = 0; ks0 < nk; ks0 += AM_RING) {
 #pragma unroll
             for (int s = 0; s < AM_RING; s++) {
                 const int ks = ks0 + s;
-                // fragments of this step: planes(ks) in buffer s&1, A(ks) in slot s
-                const char *ar = a_rd + s * AM_ASLOT;
-                const v4i a0 = *(const v4i *)ar, a1 = *(const v4i *)(ar + 1024);
-                const v4i *pb = p_rd + (s & 1) * (LY::plane_bytes / 16);
-                v4i bf[PLANES];
-#pragma unroll
-                for (int p = 0; p < PLANES; p++) bf[p] = pb[p * AM_PLANE_CELLS];
-                // planes of step ks+1 (slot (s+1) % RING), in the shadow of the products of step ks
+                const v4i *pbn = p_rd + ((s + 1) & 1) * (LY::plane_bytes / 16);
+                const char *arn = a_rd + ((s + 1) % AM_RING) * AM_ASLOT;
+                v4i bfn[PLANES], a0n, a1n;
+                u64 xw[4];
                 u32 pl[8];
-                planes_of((s + 1) % AM_RING, pl);
+                a0n = *(const v4i *)arn;
+                a1n = *(const v4i *)(arn + 1024);
+                raw_words((s + 2) % AM_RING, xw);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int p = 0; p < PLANES; p++) {
-                    acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0, bf[p], acc[p][0], 0, 0, 0);
-                    acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1, bf[p], acc[p][1], 0, 0, 0);
+                    acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0c, bfc[p], acc[p][0], 0, 0, 0);
+                    acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1c, bfc[p], acc[p][1], 0, 0, 0);
+                    bfn[p] = pbn[p * AM_PLANE_CELLS];
+                    if (p == 0) issue_x(ks + AM_RING + 1, (s + 1) % AM_RING, 0);
+                    if (p == 1) {
+                        issue_x(ks + AM_RING + 1, (s + 1) % AM_RING, 1);
+                        transpose4((u32)xw[0], (u32)xw[1], (u32)xw[2], (u32)xw[3], pl);
+                    }
+                    if (p == 2) {
+                        issue_a(ks + AM_RING, s, 0);
+                        transpose4((u32)(xw[0] >> 32), (u32)(xw[1] >> 32), (u32)(xw[2] >> 32), (u32)(xw[3] >> 32), pl + 4);
+                    }
+                    if (p == 3) {
+                        issue_a(ks + AM_RING, s, 1);
+                        write_planes(s & 1, pl);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                write_planes((s + 1) & 1, pl);
-                // refill: X(ks+RING) takes the slot of X(ks), A(ks+DEPTH) the slot of A(ks-1);
-                // both were last read before the previous barrier
-                issue_x(ks + AM_RING, s);
-                issue_a(ks + AM_DEPTH, (s + AM_DEPTH) % AM_RING);
-                wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(ks+2) and A(ks+1) have landed
+                wait_vmcnt<4 * (AM_DEPTH - 1)>();  // X(ks+3) and A(ks+2) have landed
                 __syncthreads();
+#pragma unroll
+                for (int p = 0; p < PLANES; p++) bfc[p] = bfn[p];
+                a0c = a0n;
+                a1c = a1n;
             }
         }
 
@@ -236,6 +272,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
 #pragma unroll
         for (int p = 0; p < PLANES; p++) ones |= (u64)1 << (8 * p);
         v4i *scr = (v4i *)smem + tid;  // chunk (p, c) of this thread at scr[(p*4 + c) * 256]
+        const int *bl = (const int *)(smem + LY::bias_off);
 #pragma unroll
         for (int mb = 0; mb < 2; mb++) {
 #pragma unroll
@@ -250,7 +287,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
                 const int ib = i0 + mb * 32 + 8 * c + 4 * g;  // rows ib .. ib+3
                 int64_t t[4];
 #pragma unroll
-                for (int e = 0; e < 4; e++) t[e] = (int64_t)((u64)(int64_t)bias[ib + e] * ones);
+                for (int e = 0; e < 4; e++) t[e] = (int64_t)((u64)(int64_t)bl[ib - m_tile * AM_TILE_M + e] * ones);
 #pragma unroll
                 for (int p = 0; p < PLANES; p++) {
                     const v4i t4 = scr[(p * 4 + c) * AM_THREADS];
