@@ -236,17 +236,29 @@ __global__ __launch_bounds__(EW_THREADS) void k_rescale(u64 *ct, int l1, int lim
     const u64 ql = pc[last].q;
     const u64 xl = mul_shoup(c[(size_t)last * N + idx], consts[last], consts[l1 + last], ql);
     const bool neg = xl > ql / 2;
-    for (int i = 0; i < last; i++) {
-        const u64 q = pc[i].q;
-        u64 v = mul_shoup(c[(size_t)i * N + idx], consts[i], consts[l1 + i], q);
-        u64 r = xl;
-        if (r >= q) {
-            r -= q;
-            if (r >= q) r %= q;
+    // the update is in place, so the compiler must assume every store may feed the next load; limbs are
+    // therefore loaded four at a time ahead of their stores to keep several loads in flight
+    for (int i0 = 0; i0 < last; i0 += 4) {
+        u64 in[4];
+#pragma unroll
+        for (int j = 0; j < 4; j++)
+            if (i0 + j < last) in[j] = c[(size_t)(i0 + j) * N + idx];
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int i = i0 + j;
+            if (i < last) {
+                const u64 q = pc[i].q;
+                const u64 v = mul_shoup(in[j], consts[i], consts[l1 + i], q);
+                u64 r = xl;
+                if (r >= q) {
+                    r -= q;
+                    if (r >= q) r %= q;
+                }
+                // centred representative of limb l: values above q_l/2 stand for themselves minus q_l
+                if (neg) r = sub_mod(r, consts[4 * l1 + i], q);
+                c[(size_t)i * N + idx] = mul_shoup(sub_mod(v, r, q), consts[2 * l1 + i], consts[3 * l1 + i], q);
+            }
         }
-        // centred representative of limb l: values above q_l/2 stand for themselves minus q_l
-        if (neg) r = sub_mod(r, consts[4 * l1 + i], q);
-        c[(size_t)i * N + idx] = mul_shoup(sub_mod(v, r, q), consts[2 * l1 + i], consts[3 * l1 + i], q);
     }
 }
 
