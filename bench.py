@@ -254,6 +254,8 @@ def main():
     ap.add_argument("--workload", default="ffn2560", choices=[w.name for w in wl.WORKLOADS])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-keyswitch-leg", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (calibrates profiler byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -288,6 +290,13 @@ def main():
     if w.name == "keyswitch":
         line["rotations"] = {"value": w.batch / (ms * 1e-3), "unit": "rotations/s", "workload": "keyswitch"}
     del r
+    if args.copy_probe:
+        a = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        torch.add(a, 1, out=b)
+        torch.cuda.synchronize()
+        del a, b
     if w.name != "keyswitch" and not args.no_keyswitch_leg:
         kw = wl.BY_NAME["keyswitch"]
         rk = Runner(kw)

@@ -88,7 +88,7 @@ template <int PLANES>
 __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
                                                                 const int32_t *bias, int m, const PrimeConst *pc, int N, int l1,
                                                                 int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n,
-                                                                int n_tiles_m, int workers_per_xcd) {
+                                                                int n_tiles_m, int workers_per_xcd, int m_group) {
     HIP_DYNAMIC_SHARED(char, smem)
     typedef AmLayout<PLANES> LY;
     const int tid = threadIdx.x;
@@ -108,12 +108,19 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
     const size_t per_poly = (size_t)l1 * N;
     const size_t ct_words_out = (size_t)2 * limb_stride_out * N;
     const int xcd = blockIdx.x & 7, worker = blockIdx.x >> 3;
-    const int items = ((n_tiles_n + 7) / 8) * n_tiles_m;
+    const int n_nt = (n_tiles_n + 7) / 8;  // word tiles of this XCD
+    const int items = n_nt * n_tiles_m;
+    const int per_group = n_nt * m_group, last_group = (n_tiles_m - 1) / m_group;
     const u64 step_bytes = (u64)AM_TILE_K * xstride * sizeof(u64);
 
     for (int item = worker; item < items; item += workers_per_xcd) {
-        const int m_tile = item % n_tiles_m;
-        const int nt = (item / n_tiles_m) * 8 + xcd;
+        // items are ordered: group of m_group output tiles, word tile, output tile inside the group; the
+        // workers of an XCD therefore share both operand words and weight fragments through its L2
+        const int mg = item / per_group < last_group ? item / per_group : last_group;
+        const int j = item - mg * per_group;
+        const int gsize = n_tiles_m - mg * m_group < m_group ? n_tiles_m - mg * m_group : m_group;
+        const int m_tile = mg * m_group + j % gsize;
+        const int nt = (j / gsize) * 8 + xcd;
         if (nt >= n_tiles_n) continue;
         const size_t word0 = (size_t)nt * AM_TILE_N;
         const int poly = (int)(word0 / per_poly);
@@ -306,14 +313,14 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const u64 *xbase
 template <int P>
 static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
                       const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n, int n_tiles_m,
-                      int workers) {
+                      int workers, int m_group) {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
         attr_set = true;
     }
     hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, xbase, xstride, n_v, n_kpad, wfrag, bias, m,
-                       ctx->d_pc, ctx->N, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+                       ctx->d_pc, ctx->N, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers, m_group);
 }
 
 void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
@@ -331,10 +338,9 @@ void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int
     const int workers = n_cu / 8;  // one persistent workgroup per CU; workgroup b runs on XCD b % 8
     const unsigned grid = 8u * (unsigned)workers;
     const v4i *wf = (const v4i *)d_wt;
+    const int m_group = 8;  // 8 output tiles x 4 word tiles in flight per XCD
     if (planes <= 5)
-        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
-    else if (planes <= 7)
-        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers, m_group);
     else
-        am_launch<8>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers);
+        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m, workers, m_group);
 }

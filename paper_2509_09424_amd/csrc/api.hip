@@ -876,7 +876,7 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
     std::vector<int32_t> bias;
     if (mfma_ok) {
         const int need = (qbits + 7) / 8;
-        p->planes = need <= 5 ? 5 : need <= 7 ? 7 : 8;
+        p->planes = need <= 5 ? 5 : 7;  // qbits <= 56: never more than seven byte planes
         wt.assign((size_t)p->m_pad * p->n_kpad, 0);
         bias.assign(p->m_pad, 0);
     }

@@ -194,10 +194,10 @@ def test_matmul_several_packed_inputs(small4):
 
 
 def test_matmul_many_operands_and_wide_primes():
-    """Long sums: 300 operands on 50-bit primes (matrix-core kernel, several k-steps and two
-    256-output tiles) and 40 operands on 60-bit primes (plain-ALU kernel with mid-loop reductions,
+    """Long sums: 300 operands on 50-bit primes (matrix-core kernel, several k-steps, nine
+    256-output tiles: one full group of eight plus a ragged one) and 40 operands on 60-bit primes (plain-ALU kernel with mid-loop reductions,
     the only valid one there)."""
-    for params, d, m in (((8, 50, 3, 60, 1, 3, 40), 300, 290), ((8, 60, 2, 61, 1, 2, 40), 40, 33)):
+    for params, d, m in (((8, 50, 3, 60, 1, 3, 40), 300, 2100), ((8, 60, 2, 61, 1, 2, 40), 40, 33)):
         p = Pair(params)
         try:
             rng = np.random.default_rng(8)

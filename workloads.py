@@ -106,3 +106,20 @@ def error_poly(rng, shape):
     """Rounded Gaussian, sigma 3.2, clipped at +-19 (about 6 sigma), int8."""
     e = np.rint(rng.normal(0.0, ERROR_SIGMA, size=shape))
     return np.clip(e, -19, 19).astype(np.int8)
+
+
+# Synthetic residue words for tests that need far more ciphertext data than anything could
+# encrypt: word w of operand v, a fixed 64-bit mix cut to `bits` bits (always a valid residue of a
+# prime of more than `bits` bits).  Only +, *, ^, >>, & on 64-bit integers with wrap-around, written
+# so that numpy uint64 arrays and torch int64 tensors give the same low bits (shifts are masked,
+# so logical and arithmetic shifts agree).
+_MIX1, _MIX2, _MIX3 = 0x1E3779B97F4A7C15, 0x3F58476D1CE4E5B9, 0x14D049BB133111EB
+
+
+def synthetic_words(v, w, bits):
+    """v, w: integer arrays/tensors (broadcast against each other) of one 64-bit integer type."""
+    h = (v + 1) * _MIX1 + (w + 1) * _MIX2
+    h = h ^ ((h >> 29) & ((1 << 35) - 1))
+    h = h * _MIX3
+    h = h ^ ((h >> 32) & ((1 << 32) - 1))
+    return (h >> 11) & ((1 << bits) - 1)
