@@ -151,32 +151,38 @@ def kernel_profile(runner):
 
 
 def roofline_for(w, prof):
-    """Roofline entry of the dominant kernel class of the step."""
+    """Roofline entry of the dominant kernel class of the step (largest total time)."""
     N, L, K, alpha = w.N, w.q_count, w.p_count, w.alpha
-    unit = 8.0 * N
+    unit = 8.0 * N  # bytes of one limb
     ext = L + K
     beta = -(-L // alpha)
-    groups = {
-        "ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"],
-        "inner_product": ["inner_product"], "modup": ["modup"], "moddown": ["moddown"],
-        "accumulate": ["accumulate"], "accumulate_mfma": ["accumulate_mfma"], "mul_scalar_rescale": ["mul_scalar_rescale"],
+    if w.name == "keyswitch":
+        n_rot, n_raise = w.batch, w.batch
+    else:
+        n_in = -(-w.d_in // w.c_tot)
+        n_rot, n_raise = w.d_in - n_in, n_in
+    # HBM-bound classes: algorithmic limb-units per step (every operand read once, every result written once)
+    hbm = {
+        # fused path (N = 2^16, ciphertext primes below 2^50)
+        "ks_pre": n_raise * 2 * L,
+        "ks_modup_fcols": n_raise * (3 * L + beta * ext + L),        # y, c1, c0 in; raised digits and P*c0 out
+        "ks_frows": n_raise * 2 * (beta * ext + L),
+        "ks_inner_irows": n_rot * (beta * ext + L + 2 * beta * ext + 2 * ext),  # digits, P*c0, key in; accumulators out
+        "ks_icols_special": n_rot * 4 * K,                                     # special limbs in, split residues out
+        "ks_icols_moddown": n_rot * (2 * L + 2 * K + 2 * L),                   # accumulators and residues in, ciphertext out
+        # unfused path
+        "ntt": 2 * (n_raise * beta * ext + n_rot * 2 * ext),
+        "inner_product": n_rot * (3 * beta * ext + 2 * ext),
+        "modup": n_raise * (L + beta * ext),
+        "moddown": n_rot * (2 * ext + 3 * L),
+        "mul_scalar_rescale": (w.d_mid or 0) * (2 * L + 2 * (L - 1)),
     }
-    tot = {g: sum(prof.get(k, (0.0, 0))[0] for k in ks) for g, ks in groups.items()}
+    members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
+    classes = list(hbm) + ["accumulate", "accumulate_mfma"]
+    tot = {g: sum(prof.get(k, (0.0, 0))[0] for k in members.get(g, [g])) for g in classes}
     dom = max(tot, key=tot.get)
     ms = tot[dom]
-    if w.name == "keyswitch":
-        n_rot, n_modup = w.batch, w.batch
-    else:
-        c_tot = w.c_tot
-        n_in = -(-w.d_in // c_tot)
-        n_rot = w.d_in - n_in
-        n_modup = n_in
-    if dom == "ntt":
-        limbs = n_modup * beta * ext + n_rot * 2 * ext  # forward on raised digits + inverse on both accumulators
-        algo = 2 * unit * limbs  # each limb read once and written once
-        return dom, {"bound": "hbm", "achieved": algo / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": algo / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None, "kernel": "ntt (both passes, forward+inverse)",
-                     "launch_ms": ms, "limb_transforms": limbs}
+    launches = sum(prof.get(k, (0.0, 0))[1] for k in members.get(dom, [dom]))
     if dom == "accumulate_mfma":
         # Alg. 1 on the matrix cores: one int8 multiply-add per (output, operand, limb word, byte plane); 7 planes at 50 bits
         planes = -(-w.q_bits // 8)
@@ -184,25 +190,32 @@ def roofline_for(w, prof):
         dm = w.d_in * (w.d_mid or w.d_out) + (w.d_mid * w.d_out if w.d_mid else 0)
         ops = 2.0 * dm * 2 * L * N * planes
         return dom, {"bound": "mfma", "achieved": ops / (ms * 1e-3) / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None, "kernel": "accumulate_mfma",
-                     "launch_ms": ms, "launches": prof.get("accumulate_mfma", (0, 1))[1]}
-    if dom == "inner_product":
-        algo = unit * n_rot * (3 * beta * ext + 2 * ext)
-    elif dom == "modup":
-        algo = unit * n_modup * (L + beta * ext)
-    elif dom == "moddown":
-        algo = unit * n_rot * (2 * ext + 3 * L)
-    elif dom == "mul_scalar_rescale":
-        algo = unit * w.d_mid * (2 * L + 2 * (L - 1))
-    else:
+                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None, "kernel": dom,
+                     "launch_ms": ms / max(launches, 1), "launches": launches}
+    if dom == "accumulate":
         # Alg. 1: one 64-bit add/sub per non-zero weight per limb word
         nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
         ops = nnz * 2 * L * N
         return dom, {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": U64_ADD_PEAK / 1e12, "unit": "Tadd64/s",
-                     "frac": ops / (ms * 1e-3) / U64_ADD_PEAK, "traffic": None, "kernel": "accumulate", "launch_ms": ms}
-    gbs = algo / (ms * 1e-3) / 1e9
+                     "frac": ops / (ms * 1e-3) / U64_ADD_PEAK, "traffic": None, "kernel": dom,
+                     "launch_ms": ms / max(launches, 1), "launches": launches}
+    gbs = unit * hbm[dom] / (ms * 1e-3) / 1e9
     return dom, {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
-                 "traffic": None, "kernel": dom, "launch_ms": ms}
+                 "traffic": None, "kernel": dom, "launch_ms": ms / max(launches, 1), "launches": launches}
+
+
+def hbm_fractions(w, prof):
+    """Algorithmic GB/s of every HBM-bound kernel class that ran in the step (for the key-switch target)."""
+    out = {}
+    for name in list(prof):
+        one = {name: prof[name]}
+        try:
+            dom, roof = roofline_for(w, one)
+        except ZeroDivisionError:
+            continue
+        if dom == name and roof["bound"] == "hbm" and roof["achieved"] > 0:
+            out[name] = {"GB/s": round(roof["achieved"], 1), "frac": round(roof["frac"], 4)}
+    return out
 
 
 def cpu_baseline(w):
@@ -285,7 +298,7 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "log_n": w.log_n, "q_limbs": w.q_count, "p_limbs": w.p_count, "alpha": w.alpha,
                    "tokens": w.tokens, "d_in": w.d_in, "d_mid": w.d_mid, "d_out": w.d_out, "placement": w.placement},
-        "decrypt_max_abs_err": err, "roofline": roof, "kernels_ms_per_step": kernels,
+        "decrypt_max_abs_err": err, "roofline": roof, "kernels_ms_per_step": kernels, "hbm_kernels": hbm_fractions(w, prof),
     }
     if w.name == "keyswitch":
         line["rotations"] = {"value": w.batch / (ms * 1e-3), "unit": "rotations/s", "workload": "keyswitch"}
@@ -306,7 +319,7 @@ def main():
         kprof = kernel_profile(rk)
         _, kroof = roofline_for(kw, kprof)
         line["rotations"] = {"value": kw.batch / (kms * 1e-3), "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": kms,
-                             "decrypt_max_abs_err": kerr, "roofline": kroof,
+                             "decrypt_max_abs_err": kerr, "roofline": kroof, "hbm_kernels": hbm_fractions(kw, kprof),
                              "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(kprof.items())}}
         log("key-switch leg: %.1f rotations/s" % line["rotations"]["value"])
     if not args.no_cpu_baseline:

@@ -228,6 +228,9 @@ extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
             }
         }
     }
+    // the fused key-switching kernels need every ciphertext prime on the fp64 path
+    ctx->ks16 = ctx->log_n == 16;
+    for (int i = 0; i < ctx->L; i++) ctx->ks16 = ctx->ks16 && pcs[i].pad[0] != 0;
     std::vector<double> cs(2 * (size_t)N);
     for (size_t e = 0; e < cs.size(); e++) cs[e] = (double)cosl(M_PIl * (long double)e / (long double)N);
     ctx->rot_exp.resize(N / 2);
@@ -246,6 +249,13 @@ extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
 }
 
 static void free_modconst(ensi_ctx *ctx) {
+    for (auto &kv : ctx->ks16c) {
+        (void)hipFree((void *)kv.second.hat_fp);
+        (void)hipFree((void *)kv.second.pmod_fp);
+        (void)hipFree((void *)kv.second.down_p);
+        (void)hipFree((void *)kv.second.down_p_fp);
+        (void)hipFree((void *)kv.second.down_q);
+    }
     for (auto &kv : ctx->modup) {
         (void)hipFree(kv.second.inv);
         (void)hipFree(kv.second.inv_s);
@@ -271,6 +281,8 @@ extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
     if (ctx->d_rot_exp) (void)hipFree(ctx->d_rot_exp);
     if (ctx->ws_digits) (void)hipFree(ctx->ws_digits);
     if (ctx->ws_u) (void)hipFree(ctx->ws_u);
+    if (ctx->ws_y) (void)hipFree(ctx->ws_y);
+    if (ctx->ws_ysp) (void)hipFree(ctx->ws_ysp);
     if (ctx->ws_virt) (void)hipFree(ctx->ws_virt);
     if (ctx->ws_desc) (void)hipFree(ctx->ws_desc);
     if (ctx->ws_plan) (void)hipFree(ctx->ws_plan);
@@ -367,6 +379,93 @@ static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
             upload(&mc.pinv, pinv) != hipSuccess || upload(&mc.pinv_s, pinv_s) != hipSuccess || upload(&mc.negtab, negtab) != hipSuccess)
             ENSI_FAIL(ctx, ENSI_E_HIP, "uploading ModDown constants failed");
         it = ctx->moddown.insert({l1, mc}).first;
+    }
+    *out = &it->second;
+    return ENSI_OK;
+}
+
+// Constants of the fused N = 2^16 key switch at level l1 (shares the integer ModUp tables).
+static int get_ks16(ensi_ctx *ctx, int l1, const Ks16Const **out) {
+    auto it = ctx->ks16c.find(l1);
+    if (it == ctx->ks16c.end()) {
+        const ModUpConst *mu;
+        int rc = get_modup(ctx, l1, &mu);
+        if (rc) return rc;
+        Ks16Const kc;
+        memset(&kc, 0, sizeof(kc));
+        const int K = ctx->K, L = ctx->L, ext = l1 + K, alpha = ctx->alpha;
+        kc.l1 = l1;
+        kc.K = K;
+        kc.L = L;
+        kc.alpha = alpha;
+        kc.beta = mu->beta;
+        for (int j = 0; j < 8; j++) kc.n_src[j] = mu->n_src[j];
+        kc.inv = mu->inv;  // [beta][alpha] with digit j starting at limb j*alpha: the index is the limb itself
+        kc.inv_s = mu->inv_s;
+        kc.hat_mont = mu->hat;
+        const u64 n_ring = (u64)ctx->N;
+        auto prime_of = [&](int e) { return ctx->primes[e < l1 ? e : L + (e - l1)]; };
+        auto is_fp = [&](u64 t) { return t < ((u64)1 << 50); };
+        std::vector<double> hat_fp((size_t)kc.beta * ext * alpha * 2, 0.0), pmod((size_t)l1 * 2), down_p_fp((size_t)K * 2, 0.0),
+            down_q((size_t)l1 * (2 + 4 * K));
+        std::vector<u64> down_p((size_t)K * 2);
+        for (int j = 0; j < kc.beta; j++) {
+            const int first = j * alpha, ns = kc.n_src[j];
+            for (int e = 0; e < ext; e++) {
+                const u64 t = prime_of(e);
+                if ((e >= first && e < first + ns) || !is_fp(t)) continue;
+                for (int a = 0; a < ns; a++) {
+                    u64 h = 1;
+                    for (int b = 0; b < ns; b++)
+                        if (b != a) h = hm_mulmod(h, ctx->primes[first + b] % t, t);
+                    hat_fp[(((size_t)j * ext + e) * alpha + a) * 2] = (double)h;
+                    hat_fp[(((size_t)j * ext + e) * alpha + a) * 2 + 1] = (double)h / (double)t;
+                }
+            }
+        }
+        for (int i = 0; i < l1; i++) {
+            const u64 q = ctx->primes[i];
+            u64 P = 1;
+            for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
+            pmod[2 * i] = (double)P;
+            pmod[2 * i + 1] = (double)P / (double)q;
+            double *dq = &down_q[(size_t)i * (2 + 4 * K)];
+            const u64 sc = hm_mulmod(hm_invmod(n_ring % q, q), hm_invmod(P, q), q);
+            dq[0] = (double)sc;
+            dq[1] = (double)sc / (double)q;
+            for (int k = 0; k < K; k++) {
+                const u64 h = hm_invmod(ctx->primes[L + k] % q, q);
+                const u64 h30 = hm_mulmod(h, ((u64)1 << 30) % q, q);
+                dq[2 + 4 * k] = (double)h;
+                dq[3 + 4 * k] = (double)h / (double)q;
+                dq[4 + 4 * k] = (double)h30;
+                dq[5 + 4 * k] = (double)h30 / (double)q;
+            }
+        }
+        for (int k = 0; k < K; k++) {
+            const u64 pk = ctx->primes[L + k];
+            u64 prod = 1;
+            for (int b = 0; b < K; b++)
+                if (b != k) prod = hm_mulmod(prod, ctx->primes[L + b] % pk, pk);
+            const u64 cs = hm_mulmod(hm_invmod(n_ring % pk, pk), hm_invmod(prod, pk), pk);
+            down_p[2 * k] = cs;
+            down_p[2 * k + 1] = hm_shoup(cs, pk);
+            if (is_fp(pk)) {
+                down_p_fp[2 * k] = (double)cs;
+                down_p_fp[2 * k + 1] = (double)cs / (double)pk;
+            }
+        }
+        double *d_hat = nullptr, *d_pmod = nullptr, *d_dpf = nullptr, *d_dq = nullptr;
+        u64 *d_dp = nullptr;
+        if (upload(&d_hat, hat_fp) != hipSuccess || upload(&d_pmod, pmod) != hipSuccess || upload(&d_dp, down_p) != hipSuccess ||
+            upload(&d_dpf, down_p_fp) != hipSuccess || upload(&d_dq, down_q) != hipSuccess)
+            ENSI_FAIL(ctx, ENSI_E_HIP, "uploading key-switch constants failed");
+        kc.hat_fp = d_hat;
+        kc.pmod_fp = d_pmod;
+        kc.down_p = d_dp;
+        kc.down_p_fp = d_dpf;
+        kc.down_q = d_dq;
+        it = ctx->ks16c.insert({l1, kc}).first;
     }
     *out = &it->second;
     return ENSI_OK;
@@ -511,6 +610,7 @@ extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_
             launch_key_assemble(ctx, kb, ka, sk->d_s_hat, d_e.as<u64>(), d_sg.as<u64>(), d_fac.as<u64>(), mext, st);
             launch_to_mont(ctx, ka, ext, mext, st);
         }
+        if (ctx->ks16) launch_ks16_key_format(ctx, key, beta, st);
     }
     if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
         ensi_gk_free(gk);
@@ -736,17 +836,60 @@ extern "C" int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct,
 }
 
 // --------------------------------------------------------------------- rotation
-// Runs inner product -> inverse transform -> ModDown for n_rot descriptors already on the device.
+// Words of the raised form of one ciphertext at level l1 (fused path: digits of c1 and P*c0).
+static size_t raised_words(const ensi_ctx *ctx, int l1) {
+    const size_t ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    return (beta * ext + (ctx->ks16 ? l1 : 0)) * (size_t)ctx->N;
+}
+
+// Digit decomposition, ModUp and forward transform of n_ct ciphertexts into ws_digits (which must hold
+// n_ct * raised_words).
+static int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct, hipStream_t st) {
+    int rc;
+    if (ctx->ks16) {
+        const Ks16Const *kc;
+        if ((rc = get_ks16(ctx, l1, &kc))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_y, &ctx->ws_y_words, (size_t)n_ct * l1 * ctx->N))) return rc;
+        launch_ks16_raise(ctx, *kc, ct_base, ct_stride_words, limb_stride, n_ct, ctx->ws_y, ctx->ws_digits, st);
+        return ENSI_OK;
+    }
+    const ModUpConst *mu;
+    if ((rc = get_modup(ctx, l1, &mu))) return rc;
+    const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    launch_modup(ctx, *mu, ct_base, ct_stride_words, limb_stride, n_ct, ctx->ws_digits, st);
+    launch_ntt(ctx, ctx->ws_digits, n_ct * beta * ext, make_map(ctx, l1, true), false, st);
+    return ENSI_OK;
+}
+
+// Runs inner product -> inverse transform -> ModDown (+ phi_g(c0)) for n_rot descriptors already on the device.
 static int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out,
                          hipStream_t st) {
+    int rc;
+    if (ctx->ks16) {
+        const Ks16Const *kc;
+        if ((rc = get_ks16(ctx, l1, &kc))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_ysp, &ctx->ws_ysp_words, (size_t)n_rot * 2 * ctx->K * ctx->N))) return rc;
+        launch_ks16_switch(ctx, *kc, d_desc, n_rot, ctx->ws_u, ctx->ws_ysp, limb_stride_out, st);
+        return ENSI_OK;
+    }
     const ModDownConst *md;
-    int rc = get_moddown(ctx, l1, &md);
-    if (rc) return rc;
+    if ((rc = get_moddown(ctx, l1, &md))) return rc;
     const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
     launch_inner(ctx, d_desc, n_rot, l1, beta, ctx->ws_u, st);
     launch_ntt(ctx, ctx->ws_u, n_rot * 2 * ext, make_map(ctx, l1, true), true, st);
     launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, ctx->ws_u, st);
     return ENSI_OK;
+}
+
+// Ciphertexts per group of a batched rotation (environment override for tuning).
+static int rot_chunk() {
+    static int v = 0;
+    if (!v) {
+        const char *e = getenv("ENSI_ROT_CHUNK");
+        v = e ? atoi(e) : 8;
+        if (v < 1) v = 1;
+    }
+    return v;
 }
 
 static int ensure_desc(ensi_ctx *ctx, size_t n) {
@@ -766,30 +909,33 @@ extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, 
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "rotate: in and out must not overlap");
     hipStream_t st = (hipStream_t)stream;
     const int N = ctx->N, l1 = in->limbs, ext = l1 + ctx->K, n = in->n;
-    const int beta = (l1 + ctx->alpha - 1) / ctx->alpha;
     std::vector<RotDesc> desc(n);
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    // ciphertexts are processed in groups small enough for their raised digits and accumulators to stay
+    // in the memory-side cache between the kernels
+    const int chunk = std::min(n, ctx->ks16 ? rot_chunk() : n);
+    const size_t rw = raised_words(ctx, l1);
     int rc;
-    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)n * beta * ext * N))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)n * 2 * ext * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 2 * ext * N))) return rc;
     if ((rc = ensure_desc(ctx, n))) return rc;
     for (int c = 0; c < n; c++) {
         const u32 g = galois_element(ctx, steps[c]);
         auto it = gk->keys.find(g);
         if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "rotate: no Galois key for step %d", steps[c]);
         desc[c].c0 = in->d + (size_t)c * in_ct;
-        desc[c].digits = ctx->ws_digits + (size_t)c * beta * ext * N;
+        desc[c].digits = ctx->ws_digits + (size_t)(c % chunk) * rw;
         desc[c].key = it->second;
         desc[c].out = out->d + (size_t)c * out_ct;
         desc[c].g = g;
         desc[c].g_inv = inv_mod_2n(g, N);
     }
-    const ModUpConst *mu;
-    if ((rc = get_modup(ctx, l1, &mu))) return rc;
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), n * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-    launch_modup(ctx, *mu, in->d, in_ct, in->limbs_alloc, n, ctx->ws_digits, st);
-    launch_ntt(ctx, ctx->ws_digits, n * beta * ext, make_map(ctx, l1, true), false, st);
-    if ((rc = run_rotations(ctx, ctx->ws_desc, n, l1, in->limbs_alloc, out->limbs_alloc, st))) return rc;
+    for (int c0 = 0; c0 < n; c0 += chunk) {
+        const int cnt = std::min(chunk, n - c0);
+        if ((rc = raise_cts(ctx, l1, in->d + (size_t)c0 * in_ct, in_ct, in->limbs_alloc, cnt, st))) return rc;
+        if ((rc = run_rotations(ctx, ctx->ws_desc + c0, cnt, l1, in->limbs_alloc, out->limbs_alloc, st))) return rc;
+    }
     out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
@@ -940,7 +1086,7 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "matmul: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
     hipStream_t st = (hipStream_t)stream;
-    const int l1 = in->limbs, ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    const int l1 = in->limbs, ext = l1 + ctx->K;
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
     int rc;
     MatmulPlan *plan;
@@ -967,7 +1113,7 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     const int chunk = 128;
     const u64 *xbase = in->d;
     if (n_rot) {
-        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)beta * ext * N))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, raised_words(ctx, l1)))) return rc;
         if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, n_rot) * 2 * ext * N))) return rc;
         if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)n_v * in_ct))) return rc;
         if ((rc = ensure_desc(ctx, n_rot))) return rc;
@@ -997,13 +1143,9 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
         }
         ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
         // ---- unpack: one ModUp per packed input, shared by all its rotations
-        const ModUpConst *mu;
-        if ((rc = get_modup(ctx, l1, &mu))) return rc;
-        LimbMap mext = make_map(ctx, l1, true);
         for (int G = 0; G < n_in; G++) {
             if (!groups[G].second) continue;
-            launch_modup(ctx, *mu, in->d + (size_t)G * in_ct, in_ct, in->limbs_alloc, 1, ctx->ws_digits, st);
-            launch_ntt(ctx, ctx->ws_digits, beta * ext, mext, false, st);
+            if ((rc = raise_cts(ctx, l1, in->d + (size_t)G * in_ct, in_ct, in->limbs_alloc, 1, st))) return rc;
             for (int o = 0; o < groups[G].second; o += chunk) {
                 const int cnt = std::min(chunk, groups[G].second - o);
                 if ((rc = run_rotations(ctx, ctx->ws_desc + groups[G].first + o, cnt, l1, in->limbs_alloc, in->limbs_alloc, st))) return rc;

@@ -51,6 +51,19 @@ struct ModDownConst {
     u64 *negtab;   // [l1][K+1]  j * (P mod q_i) mod q_i: what j negative centred residues add to the conversion
 };
 
+// Constants of the fused N = 2^16 key switch at one level (limbs = l1); all pointers device memory.
+struct Ks16Const {
+    int32_t l1, K, L, alpha, beta;
+    int32_t n_src[8];          // limbs in digit j
+    const u64 *inv, *inv_s;    // [l1]               (Q_j/q_a)^{-1} mod q_a of the digit that holds limb a, and its Shoup companion
+    const u64 *hat_mont;       // [beta][ext][alpha] (Q_j/q_a) mod t, Montgomery form
+    const double *hat_fp;      // [beta][ext][alpha][2]  the same value and value/t as doubles (targets below 2^50 only)
+    const double *pmod_fp;     // [l1][2]            P mod q_i and (P mod q_i)/q_i
+    const u64 *down_p;         // [K][2]             N^{-1} (P/p_k)^{-1} mod p_k and its Shoup companion
+    const double *down_p_fp;   // [K][2]             the same value and value/p_k (special primes below 2^50 only)
+    const double *down_q;      // [l1][2 + 4K]       N^{-1} P^{-1} mod q_i, /q_i; per k: p_k^{-1}, /q_i, 2^30 p_k^{-1}, /q_i
+};
+
 // One rotation to perform: everything the fused kernels need, device-resident.
 struct RotDesc {
     const u64 *c0;      // source polynomial c0: [limb_stride_in][N]
@@ -93,6 +106,10 @@ struct ensi_ctx {
     std::vector<u32> rot_exp;
     std::map<int, ModUpConst> modup;      // by l1
     std::map<int, ModDownConst> moddown;  // by l1
+    bool ks16 = false;                    // N = 2^16 and every ciphertext prime below 2^50: fused key-switching kernels
+    std::map<int, Ks16Const> ks16c;       // by l1
+    u64 *ws_y = nullptr; size_t ws_y_words = 0;   // inner factors of the basis conversion (ModUp)
+    u64 *ws_ysp = nullptr; size_t ws_ysp_words = 0;  // centred special-limb residues (ModDown)
     // scratch for key switching, grown on demand
     u64 *ws_digits = nullptr; size_t ws_digits_words = 0;
     u64 *ws_u = nullptr; size_t ws_u_words = 0;
@@ -171,6 +188,15 @@ struct ScopedTimer {
 // Transform n_inst limb rows in place; row r uses prime map.prime[r % map.n].
 void launch_ntt(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);
 void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);  // N = 2^16 only
+
+// fused key switch for N = 2^16 (keyswitch16.hip)
+void launch_ks16_key_format(ensi_ctx *ctx, u64 *key, int beta_full, hipStream_t st);
+// raises n_ct ciphertexts: dig [n_ct][beta*ext + l1][N] receives the transformed digits of c1 and P*c0
+void launch_ks16_raise(ensi_ctx *ctx, const Ks16Const &kc, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct,
+                       u64 *ybuf, u64 *dig, hipStream_t st);
+// inner product + inverse transform + ModDown for n_rot descriptors (desc.digits = the ciphertext's block of dig)
+void launch_ks16_switch(ensi_ctx *ctx, const Ks16Const &kc, const RotDesc *d_desc, int n_rot, u64 *u, u64 *ysp, int limb_stride_out,
+                        hipStream_t st);
 
 void launch_modup(ensi_ctx *ctx, const ModUpConst &mc, const u64 *ct_base, size_t ct_stride_words, int limb_stride,
                   int n_ct, u64 *digits, hipStream_t st);

@@ -23,111 +23,10 @@
 #include <algorithm>
 
 #include "common.h"
+#include "ntt16_core.h"
 
 #define N16_THREADS 256
 #define N16_LOG 16
-
-struct ArithInt {
-    typedef u64 T;
-    u64 q, two_q, ninv, ninv_s;
-    __device__ __forceinline__ void init(const PrimeConst &pc) {
-        q = pc.q;
-        two_q = 2 * pc.q;
-        ninv = pc.n_inv;
-        ninv_s = pc.n_inv_s;
-    }
-    __device__ __forceinline__ T load(u64 x) const { return x; }
-    __device__ __forceinline__ T center(T x) const { return x; }
-    __device__ __forceinline__ void ct(T &x, T &y, u64 w, u64 ws) const {  // in/out [0,4q)
-        const T xs = csub(x, two_q);
-        const T t = mul_shoup_lazy(y, w, ws, q);
-        x = xs + t;
-        y = xs - t + two_q;
-    }
-    __device__ __forceinline__ void gs(T &u, T &v, u64 w, u64 ws) const {  // in/out [0,2q)
-        const T s = csub(u + v, two_q);
-        v = mul_shoup_lazy(u - v + two_q, w, ws, q);
-        u = s;
-    }
-    __device__ __forceinline__ T mid(T x) const { return x; }
-    __device__ __forceinline__ u64 store_fwd(T x) const { return csub(csub(x, two_q), q); }
-    __device__ __forceinline__ u64 store_inv(T x) const { return csub(x, q); }
-    __device__ __forceinline__ u64 store_inv_scaled(T x) const { return mul_shoup(x, ninv, ninv_s, q); }
-};
-
-struct ArithFp {
-    typedef double T;
-    double p, pinv, ninv, ninv_p;
-    __device__ __forceinline__ void init(const PrimeConst &pc) {
-        p = (double)pc.q;
-        pinv = __longlong_as_double((long long)pc.pad[1]);
-        ninv = (double)pc.n_inv;
-        ninv_p = __longlong_as_double((long long)pc.pad[2]);
-    }
-    __device__ __forceinline__ T load(u64 x) const { return (double)x; }
-    __device__ __forceinline__ T mid(T x) const { return fma(-rint(x * pinv), p, x); }  // -> |x| <= p/2
-    __device__ __forceinline__ T center(T x) const { return mid(x); }
-    __device__ __forceinline__ T mulmod(T y, T w, T wp) const {  // |y| < 2^53 -> |result| < 2.5p, exact integer
-        const double h = y * w;
-        const double l = fma(y, w, -h);
-        const double q = rint(y * wp);
-        return fma(-q, p, h) + l;
-    }
-    __device__ __forceinline__ void ct(T &x, T &y, u64 w, u64 ws) const {
-        const T t = mulmod(y, __longlong_as_double((long long)w), __longlong_as_double((long long)ws));
-        y = x - t;
-        x = x + t;
-    }
-    __device__ __forceinline__ void gs(T &u, T &v, u64 w, u64 ws) const {
-        const T s = u + v;
-        v = mulmod(u - v, __longlong_as_double((long long)w), __longlong_as_double((long long)ws));
-        u = s;
-    }
-    __device__ __forceinline__ u64 canon(T x) const {
-        T r = mid(x);
-        r = r < 0.0 ? r + p : r;
-        return (u64)r;
-    }
-    __device__ __forceinline__ u64 store_fwd(T x) const { return canon(x); }
-    __device__ __forceinline__ u64 store_inv(T x) const { return canon(x); }
-    __device__ __forceinline__ u64 store_inv_scaled(T x) const { return canon(mulmod(mid(x), ninv, ninv_p)); }
-};
-
-// Four Cooley-Tukey stages on 16 elements whose local index i is the 4 index bits of the step
-// (bit 3 = largest distance).  tw/tws: the prime's forward table and its companion.
-template <class A>
-__device__ __forceinline__ void ct4(const A &ar, typename A::T *v, const u64 *tw, const u64 *tws, u32 mbase) {
-#pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const int d = 8 >> k;
-#pragma unroll
-        for (int g = 0; g < (1 << k); g++) {
-            const u64 w = tw[(mbase << k) + g], ws = tws[(mbase << k) + g];
-#pragma unroll
-            for (int o = 0; o < d; o++) {
-                const int i0 = g * 2 * d + o;
-                ar.ct(v[i0], v[i0 + d], w, ws);
-            }
-        }
-    }
-}
-// The inverse of ct4 up to the factor 16 (inverse table).
-template <class A>
-__device__ __forceinline__ void gs4(const A &ar, typename A::T *v, const u64 *tw, const u64 *tws, u32 mbase) {
-#pragma unroll
-    for (int k = 3; k >= 0; k--) {
-        const int d = 8 >> k;
-#pragma unroll
-        for (int g = 0; g < (1 << k); g++) {
-            const u64 w = tw[(mbase << k) + g], ws = tws[(mbase << k) + g];
-#pragma unroll
-            for (int o = 0; o < d; o++) {
-                const int i0 = g * 2 * d + o;
-                ar.gs(v[i0], v[i0 + d], w, ws);
-            }
-        }
-    }
-}
 
 // ---- column pass: tile = 256 rows x 16 columns; thread (c = tid%16, j = tid/16)
 template <bool FWD, class A>
@@ -167,7 +66,6 @@ __device__ __forceinline__ void cols_body(u64 *g, const u64 *tw, const u64 *tws,
 // padded by one word per 16 so that both the strided and the contiguous 16-element patterns are
 // conflict-free; global traffic is fully coalesced (the contiguous-per-thread layout only ever
 // touches LDS).
-__device__ __forceinline__ int rpad(int p) { return p + (p >> 4); }
 
 template <bool FWD, class A>
 __device__ __forceinline__ void rows_body(u64 *g, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds, int r0) {
