@@ -167,7 +167,8 @@ def roofline_for(w, prof):
         "ks_pre": n_raise * 2 * L,
         "ks_modup_fcols": n_raise * (3 * L + beta * ext + L),        # y, c1, c0 in; raised digits and P*c0 out
         "ks_frows": n_raise * 2 * (beta * ext + L),
-        "ks_inner_irows": n_rot * (beta * ext + L + 2 * beta * ext + 2 * ext),  # digits, P*c0, key in; accumulators out
+        "ks_inner_irows": n_rot * (3 * beta * L + L + 2 * L),                  # ciphertext limbs: digits, key, P*c0 in; accumulators out
+        "ks_inner_irows_wide": n_rot * (3 * beta * K + 2 * K),                 # special limbs (integer arithmetic)
         "ks_icols_special": n_rot * 4 * K,                                     # special limbs in, split residues out
         "ks_icols_moddown": n_rot * (2 * L + 2 * K + 2 * L),                   # accumulators and residues in, ciphertext out
         # unfused path

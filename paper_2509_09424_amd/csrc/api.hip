@@ -881,16 +881,11 @@ static int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1
     return ENSI_OK;
 }
 
-// Ciphertexts per group of a batched rotation (environment override for tuning).
-static int rot_chunk() {
-    static int v = 0;
-    if (!v) {
-        const char *e = getenv("ENSI_ROT_CHUNK");
-        v = e ? atoi(e) : 8;
-        if (v < 1) v = 1;
-    }
-    return v;
-}
+// Ciphertexts per group of a batched rotation: bounds the workspace (about 31 MiB of raised digits per
+// ciphertext at 13 limbs).  Smaller groups were measured slower: the kernels are not limited by HBM alone,
+// so keeping the intermediates of a group inside the memory-side cache gains less than the shorter
+// launches lose.
+static int rot_chunk() { return 64; }
 
 static int ensure_desc(ensi_ctx *ctx, size_t n) {
     if (ctx->ws_desc_n >= n) return ENSI_OK;
@@ -911,8 +906,6 @@ extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, 
     const int N = ctx->N, l1 = in->limbs, ext = l1 + ctx->K, n = in->n;
     std::vector<RotDesc> desc(n);
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
-    // ciphertexts are processed in groups small enough for their raised digits and accumulators to stay
-    // in the memory-side cache between the kernels
     const int chunk = std::min(n, ctx->ks16 ? rot_chunk() : n);
     const size_t rw = raised_words(ctx, l1);
     int rc;
@@ -1186,10 +1179,23 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
             consts[4 * l1 + i] = ql % q;
         }
     }
+    // fp64 constants when every active prime is below 2^50: k, k/q, q_l^{-1}, q_l^{-1}/q, 1/q
+    bool fp = true;
+    for (int i = 0; i < l1; i++) fp = fp && ctx->primes[i] < ((u64)1 << 50);
+    std::vector<double> fconsts(5 * (size_t)l1, 0.0);
+    for (int i = 0; i < l1 && fp; i++) {
+        const double q = (double)ctx->primes[i];
+        fconsts[i] = (double)consts[i];
+        fconsts[l1 + i] = (double)consts[i] / q;
+        fconsts[2 * l1 + i] = (double)consts[2 * l1 + i];
+        fconsts[3 * l1 + i] = (double)consts[2 * l1 + i] / q;
+        fconsts[4 * l1 + i] = 1.0 / q;
+    }
     int rc;
-    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, consts.size()))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, 2 * consts.size()))) return rc;
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan, consts.data(), consts.size() * 8, hipMemcpyHostToDevice, st));
-    launch_rescale(ctx, ct->d, ct->n, l1, ct->limbs_alloc, ctx->ws_plan, st);
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan + consts.size(), fconsts.data(), fconsts.size() * 8, hipMemcpyHostToDevice, st));
+    launch_rescale(ctx, ct->d, ct->n, l1, ct->limbs_alloc, ctx->ws_plan, fp ? (const double *)(ctx->ws_plan + consts.size()) : nullptr, st);
     ct->limbs = l1 - 1;
     ct->scale = ct->scale * kr / (fabs(kappa) * (double)ql);
     ENSI_HIP(ctx, hipGetLastError());

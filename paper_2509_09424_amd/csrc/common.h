@@ -206,7 +206,9 @@ void launch_moddown(ensi_ctx *ctx, const ModDownConst &mc, const RotDesc *d_desc
 // operand v of the signed sums is the ciphertext at xbase + v*xstride words
 void launch_accumulate(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, const u32 *d_masks, int m, int l1,
                        int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
-void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, hipStream_t st);
+// d_fconsts != nullptr selects the fp64 kernel (all active primes below 2^50)
+void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, const double *d_fconsts,
+                    hipStream_t st);
 // planes: 5, 7 or 8 (byte planes contracted); weights d_wt [m_pad][n_kpad], m_pad multiple of 256, n_kpad of 32
 void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
                             int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);

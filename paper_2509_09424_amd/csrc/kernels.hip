@@ -262,10 +262,59 @@ __global__ __launch_bounds__(EW_THREADS) void k_rescale(u64 *ct, int l1, int lim
     }
 }
 
-void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, hipStream_t st) {
+// The same step in fp64 for primes below 2^50 (64-bit integer multiplies are several times slower than
+// fp64 FMAs here): residues are exact integers in doubles and x*w mod q is
+// h = x*w; l = fma(x,w,-h); t = rint(x*(w/q)); r = fma(-t,q,h) + l, exact because h - t*q and l are
+// integers below 2^53.  fconsts: [5][l1] doubles: k mod q_i, (k mod q_i)/q_i, q_l^{-1} mod q_i, that/q_i, 1/q_i.
+// All limbs of a coefficient are loaded before the first store, so the in-place update keeps l1 loads in
+// flight per thread.  grid (N/256, 2, n_ct)
+struct FpMod {
+    double q, qinv;
+    __device__ __forceinline__ double mid(double x) const { return fma(-rint(x * qinv), q, x); }
+    __device__ __forceinline__ double mulmod(double x, double w, double wq) const {
+        const double h = x * w;
+        const double l = fma(x, w, -h);
+        const double t = rint(x * wq);
+        return fma(-t, q, h) + l;
+    }
+};
+template <int MAXL>
+__global__ __launch_bounds__(EW_THREADS) void k_rescale_fp(u64 *ct, int l1, int limb_stride, int N, const PrimeConst *pc, const double *fc) {
+    const int idx = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    u64 *c = ct + ((size_t)blockIdx.z * 2 + blockIdx.y) * limb_stride * N + idx;
+    const int last = l1 - 1;
+    u64 in[MAXL];
+#pragma unroll
+    for (int i = 0; i < MAXL; i++)
+        if (i < l1) in[i] = c[(size_t)i * N];
+    FpMod ml = {(double)pc[last].q, fc[4 * l1 + last]};
+    double xl = 0.0;
+#pragma unroll
+    for (int i = 0; i < MAXL; i++)
+        if (i == last) xl = ml.mid(ml.mulmod((double)in[i], fc[last], fc[l1 + last]));  // centred [c_l * k]_{q_l}
+#pragma unroll
+    for (int i = 0; i < MAXL; i++) {
+        if (i < last) {
+            FpMod m = {(double)pc[i].q, fc[4 * l1 + i]};
+            const double v = m.mulmod((double)in[i], fc[i], fc[l1 + i]) - m.mid(xl);
+            double r = m.mid(m.mulmod(m.mid(v), fc[2 * l1 + i], fc[3 * l1 + i]));
+            r = r < 0.0 ? r + m.q : r;
+            c[(size_t)i * N] = (u64)r;
+        }
+    }
+}
+
+void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, const double *d_fconsts,
+                    hipStream_t st) {
     ScopedTimer t(ctx, "mul_scalar_rescale", st);
     dim3 grid((ctx->N + EW_THREADS - 1) / EW_THREADS, 2, n_ct);
-    hipLaunchKernelGGL(k_rescale, grid, dim3(EW_THREADS), 0, st, ct, l1, limb_stride, ctx->N, ctx->d_pc, d_consts);
+    if (d_fconsts && l1 <= 16)
+        hipLaunchKernelGGL(k_rescale_fp<16>, grid, dim3(EW_THREADS), 0, st, ct, l1, limb_stride, ctx->N, ctx->d_pc, d_fconsts);
+    else if (d_fconsts)
+        hipLaunchKernelGGL(k_rescale_fp<ENSI_MAX_EXT>, grid, dim3(EW_THREADS), 0, st, ct, l1, limb_stride, ctx->N, ctx->d_pc, d_fconsts);
+    else
+        hipLaunchKernelGGL(k_rescale, grid, dim3(EW_THREADS), 0, st, ct, l1, limb_stride, ctx->N, ctx->d_pc, d_consts);
 }
 
 // ------------------------------------------------------------- element-wise

@@ -168,11 +168,20 @@ __device__ __forceinline__ u32 ks_perm(u32 k, u32 g) {
     return __brev((es - 1) >> 1) >> 16;
 }
 
-__global__ __launch_bounds__(KS_THREADS) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
-                                                                 u64 *u) {
-    __shared__ u64 lds[4096 + 256];
+// FP: the limbs of primes below 2^50 (fp64 arithmetic) or the wider ones (integer arithmetic); the two
+// are separate kernels so that each gets its own register allocation.  limb_list holds the extended-
+// basis limb index of each grid slot z.
+struct LimbList {
+    int32_t n;
+    int32_t e[ENSI_MAX_EXT];
+};
+
+template <bool FP>
+__global__ __launch_bounds__(KS_THREADS, 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
+                                                                 u64 *u, LimbList limbs) {
+    __shared__ u64 lds[(FP ? 1 : 2) * (4096 + 256)];
     const int tid = threadIdx.x, rho = tid >> 4, j16 = tid & 15;
-    const int e = blockIdx.z, rot = blockIdx.y;
+    const int rot = blockIdx.y, e = limbs.e[blockIdx.z];
     const int l1 = kc.l1, ext = l1 + kc.K, ext_full = kc.L + kc.K, beta = kc.beta;
     const RotDesc d = desc[rot];
     const int prime = ks_ext_prime(e, l1, kc.L);
@@ -183,20 +192,20 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_inner_irows(Ks16Const kc, c
     const u64 *key = d.key + (size_t)prime * KS_N + (size_t)r0 * 256 + tid;
     const size_t kstride = (size_t)ext_full * KS_N;  // words between b_j and a_j, and half the distance between digits
     u64 *uo = u + ((size_t)rot * 2 * ext + e) * KS_N + (size_t)r0 * 256;
-    if (pc.pad[0]) {
+    if (FP) {
         ArithFp ar;
         ar.init(pc);
         double a0[16], a1[16];
         u32 ks[16];
-        const u64 *c0h = d.digits + ((size_t)beta * ext + e) * KS_N;
 #pragma unroll
         for (int i = 0; i < 16; i++) ks[i] = ks_perm((u32)((r0 + i) * 256 + tid), d.g);
+        const u64 *c0h = d.digits + ((size_t)beta * ext + e) * KS_N;
 #pragma unroll
         for (int i = 0; i < 16; i++) {
             a0[i] = e < l1 ? as_f64(c0h[ks[i]]) : 0.0;
             a1[i] = 0.0;
         }
-        // one digit at a time: its 48 loads are issued together, then consumed
+        // one digit at a time; the operands of KS_BATCH positions are loaded together, then consumed
 #pragma unroll 1
         for (int jd = 0; jd < beta; jd++) {
             const u64 *dj = dg + (size_t)jd * ext * KS_N;
@@ -233,43 +242,61 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_inner_irows(Ks16Const kc, c
             for (int i = 0; i < 16; i++) o[16 * i] = as_u64(ar.mid(v[i]));
         }
     } else {
+        // Montgomery products summed in 128 bits, reduced once per four digits (4 * 2^120 < p * 2^64).  The
+        // sums of eight positions at a time go straight to LDS (one tile per polynomial).
         ArithInt ar;
         ar.init(pc);
-        u64 a0[16], a1[16];
-        u32 ks[16];
-#pragma unroll
-        for (int i = 0; i < 16; i++) {
-            ks[i] = ks_perm((u32)((r0 + i) * 256 + tid), d.g);
-            a0[i] = 0;
-            a1[i] = 0;
-        }
+        u64 *lds1 = lds + 4096 + 256;
 #pragma unroll 1
-        for (int jd = 0; jd < beta; jd++) {
-            const u64 *dj = dg + (size_t)jd * ext * KS_N;
-            const u64 *kj = key + (size_t)jd * 2 * kstride;
-            u64 x[16], k0[16], k1[16];
+        for (int h = 0; h < 16; h += 8) {
+            u64 t0[8], t1[8];
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
-                x[i] = dj[ks[i]];
-                k0[i] = kj[i * 256];
-                k1[i] = kj[kstride + i * 256];
+            for (int i = 0; i < 8; i++) t0[i] = t1[i] = 0;
+#pragma unroll 1
+            for (int j0 = 0; j0 < beta; j0 += 4) {
+                acc128 s0[8], s1[8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    s0[i] = {0, 0};
+                    s1[i] = {0, 0};
+                }
+#pragma unroll 1
+                for (int jd = j0; jd < beta && jd < j0 + 4; jd++) {
+                    const u64 *dj = dg + (size_t)jd * ext * KS_N;
+                    const u64 *kj = key + (size_t)jd * 2 * kstride + h * 256;
+                    u64 x[8], k0[8], k1[8];
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        x[i] = dj[ks_perm((u32)((r0 + h + i) * 256 + tid), d.g)];
+                        k0[i] = kj[i * 256];
+                        k1[i] = kj[kstride + i * 256];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        mac128(s0[i], x[i], k0[i]);
+                        mac128(s1[i], x[i], k1[i]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; i++) {
+                    t0[i] = add_mod(t0[i], mont_reduce(s0[i], pc.q, pc.qneg_inv), pc.q);
+                    t1[i] = add_mod(t1[i], mont_reduce(s1[i], pc.q, pc.qneg_inv), pc.q);
+                }
             }
 #pragma unroll
-            for (int i = 0; i < 16; i++) {
-                a0[i] = add_mod(a0[i], mont_mul(x[i], k0[i], pc.q, pc.qneg_inv), pc.q);
-                a1[i] = add_mod(a1[i], mont_mul(x[i], k1[i], pc.q, pc.qneg_inv), pc.q);
+            for (int i = 0; i < 8; i++) {
+                lds[rpad(tid + 256 * (h + i))] = t0[i];
+                lds1[rpad(tid + 256 * (h + i))] = t1[i];
             }
         }
+        __syncthreads();
         u64 v[16];
-#pragma unroll
+#pragma unroll 1
         for (int poly = 0; poly < 2; poly++) {
-            if (poly) __syncthreads();
+            u64 *lp = poly ? lds1 : lds;
 #pragma unroll
-            for (int i = 0; i < 16; i++) lds[rpad(tid + 256 * i)] = poly ? a1[i] : a0[i];
-            __syncthreads();
-#pragma unroll
-            for (int i = 0; i < 16; i++) v[i] = lds[rpad(rho * 256 + 16 * j16 + i)];
-            rows_inv_regs(ar, v, tw, tw + KS_N, lds, rho, j16, (u32)(r0 + rho));
+            for (int i = 0; i < 16; i++) v[i] = lp[rpad(rho * 256 + 16 * j16 + i)];
+            rows_inv_regs(ar, v, tw, tw + KS_N, lp, rho, j16, (u32)(r0 + rho));
             u64 *o = uo + (size_t)poly * ext * KS_N + rho * 256 + j16;
 #pragma unroll
             for (int i = 0; i < 16; i++) o[16 * i] = ar.store_inv(v[i]);
@@ -414,9 +441,21 @@ void launch_ks16_raise(ensi_ctx *ctx, const Ks16Const &kc, const u64 *ct_base, s
 
 void launch_ks16_switch(ensi_ctx *ctx, const Ks16Const &kc, const RotDesc *d_desc, int n_rot, u64 *u, u64 *ysp, int limb_stride_out,
                         hipStream_t st) {
-    {
+    // limbs of wide primes (integer arithmetic, ALU-bound) first, then the fp64 limbs (memory-bound)
+    LimbList wide, fp;
+    wide.n = fp.n = 0;
+    for (int e = 0; e < kc.l1 + kc.K; e++) {
+        const u64 q = ctx->primes[e < kc.l1 ? e : kc.L + (e - kc.l1)];
+        LimbList &dst = q < ((u64)1 << 50) ? fp : wide;
+        dst.e[dst.n++] = e;
+    }
+    if (wide.n) {
+        ScopedTimer t(ctx, "ks_inner_irows_wide", st);
+        hipLaunchKernelGGL(k_ks16_inner_irows<false>, dim3(16, n_rot, wide.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, wide);
+    }
+    if (fp.n) {
         ScopedTimer t(ctx, "ks_inner_irows", st);
-        hipLaunchKernelGGL(k_ks16_inner_irows, dim3(16, n_rot, kc.l1 + kc.K), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u);
+        hipLaunchKernelGGL(k_ks16_inner_irows<true>, dim3(16, n_rot, fp.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, fp);
     }
     {
         ScopedTimer t(ctx, "ks_icols_special", st);
