@@ -286,6 +286,7 @@ extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
     if (ctx->ws_virt) (void)hipFree(ctx->ws_virt);
     if (ctx->ws_desc) (void)hipFree(ctx->ws_desc);
     if (ctx->ws_plan) (void)hipFree(ctx->ws_plan);
+    if (ctx->ws_xp) (void)hipFree(ctx->ws_xp);
     for (MatmulPlan *p : ctx->plans) free_plan(p);
     for (auto &p : ctx->pending) {
         (void)hipEventDestroy(p.second.first);
@@ -1147,10 +1148,11 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     }
     // ---- Alg. 1: signed sums
     const bool use_mfma = plan->planes > 0 && ctx->accumulate_mode != 1;
-    if (use_mfma)
-        launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc,
-                               out->d, out->limbs_alloc, st);
-    else
+    if (use_mfma) {
+        if ((rc = launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc,
+                                         out->d, out->limbs_alloc, st)))
+            return rc;
+    } else
         launch_accumulate(ctx, xbase, in_ct, n_v, plan->d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
     out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());

@@ -116,6 +116,7 @@ struct ensi_ctx {
     RotDesc *ws_desc = nullptr; size_t ws_desc_n = 0;
     u64 *ws_virt = nullptr; size_t ws_virt_words = 0;   // unpacked (rotated) operands of the matmul
     u64 *ws_plan = nullptr; size_t ws_plan_words = 0;   // operand pointer table, small constants
+    u64 *ws_xp = nullptr; size_t ws_xp_words = 0;       // byte planes of the accumulate's operands (one slice of the words)
     std::vector<MatmulPlan *> plans;                    // cached per weight matrix (weights are static server-side)
     int accumulate_mode = 0;                            // 0 auto, 1 plain-ALU kernel, 2 matrix-core kernel where valid
     // sampler state for NULL randomness
@@ -209,9 +210,10 @@ void launch_accumulate(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v,
 // d_fconsts != nullptr selects the fp64 kernel (all active primes below 2^50)
 void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, const u64 *d_consts, const double *d_fconsts,
                     hipStream_t st);
-// planes: 5, 7 or 8 (byte planes contracted); weights d_wt [m_pad][n_kpad], m_pad multiple of 256, n_kpad of 32
-void launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
-                            int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
+// planes: 5 or 7 byte planes contracted; weights d_wt in fragment order [m_pad/256][n_kpad/32][4][2][64][16], n_kpad a
+// multiple of 256.  Grows ctx->ws_xp (byte planes of a slice of the operand words); returns an ENSI_E_* code.
+int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
+                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
 
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
