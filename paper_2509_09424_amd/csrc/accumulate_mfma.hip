@@ -119,20 +119,26 @@ __global__ __launch_bounds__(AM_THREADS) void k_byte_planes(const u64 *xbase, u3
     }
 }
 
+// primes of the active limbs and their reciprocals, passed by value so that the recombination reads them with
+// scalar loads (a vector load there would make the compiler wait for every copy in flight)
+struct AmPrimes {
+    u64 q[ENSI_MAX_EXT];
+    double q_inv[ENSI_MAX_EXT];
+};
+
 template <int PLANES>
 struct AmLayout {
     static constexpr int bring_off = 0;                                  // [AM_RING][AM_BSLOT]
     static constexpr int aring_off = bring_off + AM_RING * AM_BSLOT;     // [4 waves][AM_RING][AM_ASLOT]
-    static constexpr int bias_off = aring_off + 4 * AM_RING * AM_ASLOT;  // [256] offset terms of the item's outputs
-    static constexpr int total = bias_off + AM_TILE_M * 4;
-    static_assert(PLANES * 4 * AM_THREADS * 16 <= bias_off, "the recombination scratch must fit below the offset terms");
+    static constexpr int bias_off = aring_off + 4 * AM_RING * AM_ASLOT;  // [2][256] offset terms of an item's outputs
+    static constexpr int total = bias_off + 2 * AM_TILE_M * 4;
 };
 
 // xp: plane tiles of the slice, [word tile][nk][PLANES][1024]; nt_begin: first word tile of the slice
 // (of n_tiles_n); nk = n_kpad / 32, a multiple of AM_RING.
 template <int PLANES>
 __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int nt_begin, int n_kpad, const v4i *wfrag, const int32_t *bias,
-                                                                int m, const PrimeConst *pc, int N, int l1, u64 *out, int limb_stride_out,
+                                                                int m, AmPrimes pr, int N, int l1, u64 *out, int limb_stride_out,
                                                                 int n_tiles_n, int n_tiles_m, int workers_per_xcd, int m_group) {
     HIP_DYNAMIC_SHARED(char, smem)
     typedef AmLayout<PLANES> LY;
@@ -155,37 +161,93 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
     const int items = n_nt * n_tiles_m;
     const int per_group = n_nt * m_group, last_group = (n_tiles_m - 1) / m_group;
 
-    for (int item = worker; item < items; item += workers_per_xcd) {
-        // items are ordered: group of m_group output tiles, word tile, output tile inside the group; the
-        // workers of an XCD therefore share both plane tiles and weight fragments through its L2
+    // item index -> (output tile, word tile of the slice); false for the padding slots of the last group of 8 word tiles.
+    // Items are ordered: group of m_group output tiles, word tile, output tile inside the group; the workers of an
+    // XCD therefore share both plane tiles and weight fragments through its L2.
+    auto decode = [&](int item, int &m_tile, int &nt_local) {
         const int mg = item / per_group < last_group ? item / per_group : last_group;
         const int j = item - mg * per_group;
         const int gsize = n_tiles_m - mg * m_group < m_group ? n_tiles_m - mg * m_group : m_group;
-        const int m_tile = mg * m_group + j % gsize;
-        const int nt_local = (j / gsize) * 8 + xcd;
-        if (nt_local >= n_tiles_n) continue;
+        m_tile = mg * m_group + j % gsize;
+        nt_local = (j / gsize) * 8 + xcd;
+        return nt_local < n_tiles_n;
+    };
+    auto next_valid = [&](int item) {
+        int mt, nt;
+        while (item < items && !decode(item, mt, nt)) item += workers_per_xcd;
+        return item;
+    };
+
+    // The copies of all items of this workgroup form one stream of steps: the ring never drains between items.
+    // pb/pa are the running per-lane source pointers of the stream.
+    const char *pb[2], *pa;
+    auto seek = [&](int item) {
+        int mt, nt;
+        decode(item, mt, nt);
+        const char *pbase = xp + (size_t)nt * nk * PLANES * 1024 + lane * 16;
+        pb[0] = pbase + pb0 * 1024;
+        pb[1] = pbase + pb1 * 1024;
+        pa = (const char *)(wfrag + ((size_t)mt * nk * 4 + wv) * 128 + lane);
+    };
+    // one of the wave's two plane tiles of the stream's next step -> ring slot
+    auto issue_b = [&](int slot, int c) {
+        dma_load16(pb[c], (c ? b_lds1 : b_lds0) + (u32)slot * AM_BSLOT);
+        pb[c] += PLANES * 1024;
+    };
+    // one of the wave's two weight fragments of the stream's next step -> ring slot
+    auto issue_a = [&](int slot, int c) {
+        dma_load16(pa + c * 1024, a_lds + (u32)slot * AM_ASLOT + c * 1024);
+        if (c == 1) pa += 8192;
+    };
+
+    // offset terms of an item's 256 outputs -> one of two LDS buffers (64 per wave); issued one item ahead
+    const u32 bias_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::bias_off + wv * 256));
+    auto issue_bias = [&](int item, int buf) {
+        int mt, nt;
+        decode(item, mt, nt);
+        dma_load4(bias + mt * AM_TILE_M + wv * 64 + lane, bias_lds + (u32)buf * (AM_TILE_M * 4));
+    };
+
+    int item = next_valid(worker);
+    if (item >= items) return;
+    issue_bias(item, 0);
+    // Copies are issued in one fixed order, "iteration j issues B(j+8) then A(j+8) into slot j % 8" (j counts the
+    // steps of the stream), from j = -8 on, so that waiting until at most 24 copies are outstanding always means:
+    // everything of iteration j-6 has landed.
+    seek(item);
+#pragma unroll
+    for (int t = 0; t < AM_RING; t++) {  // iterations -8 .. -1: steps 0..7 of the first item
+        issue_b(t, 0);
+        issue_b(t, 1);
+        issue_a(t, 0);
+        issue_a(t, 1);
+    }
+    wait_vmcnt<4 * (AM_DEPTH - 1)>();  // steps 0 and 1 have landed
+    __syncthreads();
+    // Fragments live in two register sets used alternately: step ks multiplies from set ks & 1 while the
+    // fragments of step ks+1 are read into the other set.  (With one set, the LDS read that refills a
+    // fragment's registers has to wait for the matrix instructions still reading them, and every later
+    // instruction of the wave queues behind it.)  nk is even, so every item starts on set 0.
+    v4i bf[2][PLANES], af[2][2];
+#pragma unroll
+    for (int p = 0; p < PLANES; p++) bf[0][p] = *(const v4i *)(b_rd + p * 1024);
+    af[0][0] = *(const v4i *)a_rd;
+    af[0][1] = *(const v4i *)(a_rd + 1024);
+    __syncthreads();  // slot 0 has been read by every wave before step 0 refills it
+
+    for (int it = 0; item < items; it++) {
+        int m_tile, nt_local;
+        decode(item, m_tile, nt_local);
+        const int next = next_valid(item + workers_per_xcd);
         const size_t word0 = (size_t)(nt_begin + nt_local) * AM_TILE_N;
         const int poly = (int)(word0 / per_poly);
         const size_t rem = word0 - (size_t)poly * per_poly;
         const int limb = (int)(rem / N);
         const size_t off_out = (size_t)poly * limb_stride_out * N + rem;
         const int i0 = m_tile * AM_TILE_M + wv * 64;
-        // running per-lane source pointers, advanced once per step while steps remain (copies issued for
-        // steps past the end re-read the last step into slots nobody reads any more)
-        const char *pbase = xp + (size_t)nt_local * nk * PLANES * 1024 + lane * 16;
-        const char *pb[2] = {pbase + pb0 * 1024, pbase + pb1 * 1024};
-        const char *pa = (const char *)(wfrag + ((size_t)m_tile * nk * 4 + wv) * 128 + lane);
-
-        // one of the wave's two plane tiles of `step` -> ring slot
-        auto issue_b = [&](int step, int slot, int c) {
-            dma_load16(pb[c], (c ? b_lds1 : b_lds0) + (u32)slot * AM_BSLOT);
-            pb[c] += step + 1 < nk ? PLANES * 1024 : 0;
-        };
-        // one of the wave's two weight fragments of `step` -> ring slot
-        auto issue_a = [&](int step, int slot, int c) {
-            dma_load16(pa + c * 1024, a_lds + (u32)slot * AM_ASLOT + c * 1024);
-            if (c == 1) pa += step + 1 < nk ? 8192 : 0;
-        };
+        // offset terms of this item's outputs: copied one item ahead into two buffers used alternately (the
+        // other one may still be read by a wave that has not finished the previous item's recombination)
+        const int *bl = (const int *)(smem + LY::bias_off) + (it & 1) * AM_TILE_M;
 
         v16i acc[PLANES][2];
 #pragma unroll
@@ -195,104 +257,76 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
 #pragma unroll
                 for (int r = 0; r < 16; r++) acc[p][mb][r] = 0;
 
-        // drain the previous item's loads and stores: inside the step loop only the copies are in flight
-        wait_vmcnt<0>();
-        __syncthreads();  // every wave is done with the LDS contents of the previous item
-        ((int *)(smem + LY::bias_off))[tid] = bias[m_tile * AM_TILE_M + tid];
-        // Copies are issued in one fixed order, "iteration j issues B(j+8) then A(j+8) into slot j % 8", from
-        // j = -8 on, so that waiting until at most 24 copies are outstanding always means: everything of
-        // iteration j-6 has landed.
-#pragma unroll
-        for (int t = 0; t < AM_RING; t++) {  // iterations -8 .. -1
-            issue_b(t, t, 0);
-            issue_b(t, t, 1);
-            issue_a(t, t, 0);
-            issue_a(t, t, 1);
-        }
-        wait_vmcnt<4 * (AM_DEPTH - 1)>();  // steps 0 and 1 have landed
-        __syncthreads();
-        // fragments of step 0 into registers
-        v4i bfc[PLANES], a0c, a1c;
-#pragma unroll
-        for (int p = 0; p < PLANES; p++) bfc[p] = *(const v4i *)(b_rd + p * 1024);
-        a0c = *(const v4i *)a_rd;
-        a1c = *(const v4i *)(a_rd + 1024);
-        __syncthreads();  // slot 0 has been read by every wave before step 0 refills it
-
-        // nk is a multiple of AM_RING (the plan pads the operand count with zero weights).
         // Step ks multiplies from registers filled during step ks-1; meanwhile it reads the fragments of step
-        // ks+1 from slot (ks+1) % RING and issues the copies of step ks+8 into slot ks % RING (read during step
-        // ks-1, before the barrier that ended it).  Scheduling fences keep the LDS reads and the copies spread
-        // between the matrix instructions.
+        // ks+1 from slot (ks+1) % RING and issues the copies of the stream's step ks+8 into slot ks % RING (read
+        // during step ks-1, before the barrier that ended it).  During the last 8 steps of an item the stream
+        // has moved on to the first 8 steps of the next item (after the last item: of the same item again,
+        // which nobody reads).  Scheduling fences keep the LDS reads and the copies spread between the matrix
+        // instructions.
         for (int ks0 = 0; ks0 < nk; ks0 += AM_RING) {
+            if (ks0 + AM_RING == nk) {
+                seek(next < items ? next : item);
+                if (next < items) issue_bias(next, (it + 1) & 1);
+            }
 #pragma unroll
             for (int s = 0; s < AM_RING; s++) {
-                const int ks = ks0 + s;
+                const int cur = s & 1, nxt = cur ^ 1;
                 const char *brn = b_rd + ((s + 1) % AM_RING) * AM_BSLOT;
                 const char *arn = a_rd + ((s + 1) % AM_RING) * AM_ASLOT;
-                v4i bfn[PLANES], a0n, a1n;
-                a0n = *(const v4i *)arn;
-                a1n = *(const v4i *)(arn + 1024);
+                af[nxt][0] = *(const v4i *)arn;
+                af[nxt][1] = *(const v4i *)(arn + 1024);
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int p = 0; p < PLANES; p++) {
-                    acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a0c, bfc[p], acc[p][0], 0, 0, 0);
-                    acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a1c, bfc[p], acc[p][1], 0, 0, 0);
-                    bfn[p] = *(const v4i *)(brn + p * 1024);
-                    if (p == 0) issue_b(ks + AM_RING, s, 0);
-                    if (p == 1) issue_b(ks + AM_RING, s, 1);
-                    if (p == 2) issue_a(ks + AM_RING, s, 0);
-                    if (p == 3) issue_a(ks + AM_RING, s, 1);
+                    bf[nxt][p] = *(const v4i *)(brn + p * 1024);
+                    __builtin_amdgcn_sched_barrier(0);
+                    acc[p][0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[cur][0], bf[cur][p], acc[p][0], 0, 0, 0);
+                    acc[p][1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(af[cur][1], bf[cur][p], acc[p][1], 0, 0, 0);
+                    if (p == 0) issue_b(s, 0);
+                    if (p == 1) issue_b(s, 1);
+                    if (p == 2) issue_a(s, 0);
+                    if (p == 3) issue_a(s, 1);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                wait_vmcnt<4 * (AM_DEPTH - 1)>();  // step ks+2 has landed
-                __syncthreads();
+                // keep this step's fragments alive up to here, so that the register allocator cannot hand
+                // their registers to the next step's fragments while matrix instructions still read them
 #pragma unroll
-                for (int p = 0; p < PLANES; p++) bfc[p] = bfn[p];
-                a0c = a0n;
-                a1c = a1n;
+                for (int p = 0; p < PLANES; p++) asm volatile("" ::"v"(bf[cur][p]));
+                asm volatile("" ::"v"(af[cur][0]), "v"(af[cur][1]));
+                // The stores of the previous item's recombination are younger than the copies this step needs
+                // but older than the ones it issued; the first step of an item therefore waits for everything
+                // except its own copies, which drains those stores whatever order stores and loads complete in.
+                if (ks0 == 0 && s == 0) wait_vmcnt<4>();
+                else wait_vmcnt<4 * (AM_DEPTH - 1)>();  // step ks+2 has landed
+                __syncthreads();
             }
         }
+        // here bf[0]/af[0] already hold step 0 of the next item
 
         // Recombine planes, add the offset term 128 * sum_v W'[v][i] * sum_p 256^p, reduce mod q, store.
         // Accumulator register r of a lane holds output row 8*(r/4) + 4*(lane/32) + r%4 of the 32x32
-        // block, column lane%32.  The accumulators go through LDS (all rings and planes are dead by
-        // now) so that the recombination can be a rolled loop with few live registers.
-        wait_vmcnt<0>();
-        __syncthreads();
-        const u64 q = pc[limb].q;
-        const double q_inv = 1.0 / (double)q;
+        // block, column lane%32.
+        const u64 q = pr.q[limb];
+        const double q_inv = pr.q_inv[limb];
         u64 ones = 0;
 #pragma unroll
         for (int p = 0; p < PLANES; p++) ones |= (u64)1 << (8 * p);
-        v4i *scr = (v4i *)smem + tid;  // chunk (p, c) of this thread at scr[(p*4 + c) * 256]
-        const int *bl = (const int *)(smem + LY::bias_off);
 #pragma unroll
         for (int mb = 0; mb < 2; mb++) {
 #pragma unroll
-            for (int p = 0; p < PLANES; p++)
-#pragma unroll
-                for (int c = 0; c < 4; c++) {
-                    v4i t4 = {acc[p][mb][4 * c], acc[p][mb][4 * c + 1], acc[p][mb][4 * c + 2], acc[p][mb][4 * c + 3]};
-                    scr[(p * 4 + c) * AM_THREADS] = t4;
-                }
-#pragma unroll 1
             for (int c = 0; c < 4; c++) {
                 const int ib = i0 + mb * 32 + 8 * c + 4 * g;  // rows ib .. ib+3
-                int64_t t[4];
+                const v4i b4 = *(const v4i *)(bl + (ib - m_tile * AM_TILE_M));
 #pragma unroll
-                for (int e = 0; e < 4; e++) t[e] = (int64_t)((u64)(int64_t)bl[ib - m_tile * AM_TILE_M + e] * ones);
+                for (int e = 0; e < 4; e++) {
+                    int64_t t = (int64_t)((u64)(int64_t)b4[e] * ones);
 #pragma unroll
-                for (int p = 0; p < PLANES; p++) {
-                    const v4i t4 = scr[(p * 4 + c) * AM_THREADS];
-#pragma unroll
-                    for (int e = 0; e < 4; e++) t[e] += (int64_t)((u64)(int64_t)t4[e] << (8 * p));
+                    for (int p = 0; p < PLANES; p++) t += (int64_t)((u64)(int64_t)acc[p][mb][4 * c + e] << (8 * p));
+                    if (ib + e < m) out[(size_t)(ib + e) * ct_words_out + off_out + nl] = reduce_signed(t, q, q_inv);
                 }
-#pragma unroll
-                for (int e = 0; e < 4; e++)
-                    if (ib + e < m) out[(size_t)(ib + e) * ct_words_out + off_out + nl] = reduce_signed(t[e], q, q_inv);
             }
         }
+        item = next;
     }
     wait_vmcnt<0>();  // no copy may still be in flight into LDS when the workgroup ends
 }
@@ -307,6 +341,11 @@ static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *x
         attr_set = true;
     }
     const int nk = n_kpad / AM_TILE_K;
+    AmPrimes pr;
+    for (int i = 0; i < ENSI_MAX_EXT; i++) {
+        pr.q[i] = i < l1 ? ctx->primes[i] : 1;
+        pr.q_inv[i] = 1.0 / (double)pr.q[i];
+    }
     for (int nt0 = 0; nt0 < n_tiles_n; nt0 += slice_tiles) {
         const int cnt = std::min(slice_tiles, n_tiles_n - nt0);
         {
@@ -317,7 +356,7 @@ static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *x
         {
             ScopedTimer t(ctx, "accumulate_mfma", st);
             hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, (const char *)xp, nt0, n_kpad, wfrag,
-                               bias, m, ctx->d_pc, ctx->N, l1, out, limb_stride_out, cnt, n_tiles_m, workers, m_group);
+                               bias, m, pr, ctx->N, l1, out, limb_stride_out, cnt, n_tiles_m, workers, m_group);
         }
     }
 }

@@ -13,6 +13,10 @@ __device__ __forceinline__ void dma_load16(const void *lane_addr, uint32_t lds_w
     // lds_wave_base must be wave-uniform (derive it with readfirstlane where the compiler cannot tell)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_addr), "s"(lds_wave_base) : "memory");
 }
+// Same with 4 bytes per lane: 64 x 4 bytes land contiguously at lds_wave_base.
+__device__ __forceinline__ void dma_load4(const void *lane_addr, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(lane_addr), "s"(lds_wave_base) : "memory");
+}
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
     // s_waitcnt immediate: vmcnt in bits 3:0 and 15:14; expcnt (6:4) and lgkmcnt (11:8) left at "no wait"
