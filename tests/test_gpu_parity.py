@@ -340,3 +340,40 @@ def test_full_ring_matmul_bit_exact(full):
     out.free()
     g_ct.free()
     g_gk.free()
+
+
+@pytest.mark.parametrize("params,why", [
+    ((16, 45, 4, 48, 2, 2, 36), "every prime below 2^50: the special limbs take the fp64 path of the fused kernels too"),
+    ((16, 55, 3, 60, 1, 2, 40), "ciphertext primes above 2^50: the unfused integer kernels at N = 2^16"),
+], ids=["all-fp", "wide-q"])
+def test_full_ring_rotate_other_prime_sizes(params, why):
+    p = Pair(params)
+    steps = [3, -5]
+    o_gks, g_gk = p.galois_keys(steps)
+    z = p.rng.uniform(-1, 1, (len(steps), p.n))
+    for limbs in (p.pr.L, 1):
+        o_cts, g_ct = p.encrypt_both(z, limbs)
+        out = p.ctx.rotate(g_gk, g_ct, steps)
+        want = [p.o.rotate(c, o_gks[st]) for c, st in zip(o_cts, steps)]
+        assert np.array_equal(out.export(), stack_cts(want)), (why, limbs)
+        out.free()
+        g_ct.free()
+    g_gk.free()
+    p.close()
+
+
+def test_full_ring_rotate_batch_longer_than_one_group(full):
+    """More ciphertexts than the library raises at once (groups of 64), at a low level to keep the oracle quick."""
+    p = full
+    n_ct = 67
+    steps = [1 if i % 2 else -1 for i in range(n_ct)]
+    o_gks, g_gk = p.galois_keys([1, -1])
+    z = p.rng.uniform(-1, 1, (n_ct, p.n))
+    o_cts, g_ct = p.encrypt_both(z, 2)
+    out = p.ctx.rotate(g_gk, g_ct, steps)
+    got = out.export()
+    for i in (0, 1, 62, 63, 64, 65, 66):
+        assert np.array_equal(got[i], p.o.rotate(o_cts[i], o_gks[steps[i]]).limbs()), i
+    out.free()
+    g_ct.free()
+    g_gk.free()
