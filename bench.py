@@ -219,10 +219,10 @@ def hbm_fractions(w, prof):
     return out
 
 
-def cpu_baseline(w):
-    """The CPU oracle, as it stands, on a bounded sample of the workload: one hoisted
-    rotation at the workload's parameters plus the Alg. 1 sum of one output column over
-    a sample of its operands; extrapolated linearly to the step's rotation and add counts."""
+def cpu_baseline(w, budget_s=12.0):
+    """The CPU oracle, as it stands, on a bounded sample of the workload (about `budget_s` seconds of CPU
+    work): repeated ModUps, hoisted rotations and Alg. 1 ciphertext add/subs at the workload's
+    parameters; extrapolated linearly to the step's counts."""
     from oracle import Oracle, Params
     t_setup = time.time()
     pr = Params(*w.param_tuple())
@@ -235,29 +235,48 @@ def cpu_baseline(w):
     gk = o.galois_keygen(sk, step, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 4)
     o._key_at_level(gk, pr.L)
     log("oracle set-up %.1f s" % (time.time() - t_setup))
-    t0 = time.perf_counter()
-    digits = o.mod_up(ct.c1)
-    t_modup = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    rot = o.rotate_from_digits(ct.c0, digits, gk, ct.scale)
-    t_rot = time.perf_counter() - t0
+
+    def repeat(fn, seconds):
+        n, t0 = 0, time.perf_counter()
+        while True:
+            out = fn()
+            n += 1
+            dt = time.perf_counter() - t0
+            if dt >= seconds:
+                return out, dt / n, n
+
     cores = len(os.sched_getaffinity(0))
     if w.name == "keyswitch":
+        digits, t_modup, n1 = repeat(lambda: o.mod_up(ct.c1), budget_s * 0.3)
+        rot, t_rot, n2 = repeat(lambda: o.rotate_from_digits(ct.c0, digits, gk, ct.scale), budget_s * 0.7)
         per = t_modup + t_rot
         return {"value": 1.0 / per, "unit": "rotations/s", "cores": cores, "kind": "oracle",
-                "sample": "1 full rotation (ModUp + key switch) at the workload's parameters"}
-    n_terms = 64
-    t0 = time.perf_counter()
-    o.accumulate([(rot if k % 2 else ct, 1 if k % 3 else -1) for k in range(n_terms)], pr.L, ct.scale)
-    t_add = (time.perf_counter() - t0) / n_terms
+                "sample": "%d ModUps (%.3f s each) + %d key switches (%.3f s each) at the workload's parameters" % (n1, t_modup, n2, t_rot)}
+    digits, t_modup, n1 = repeat(lambda: o.mod_up(ct.c1), budget_s * 0.15)
+    rot, t_rot, n2 = repeat(lambda: o.rotate_from_digits(ct.c0, digits, gk, ct.scale), budget_s * 0.45)
+    n_terms = 256
+    terms = [(rot if k % 2 else ct, 1 if k % 3 else -1) for k in range(n_terms)]
+    _, t_acc, n3 = repeat(lambda: o.accumulate(terms, pr.L, ct.scale), budget_s * 0.4)
+    t_add = t_acc / n_terms
     c_tot = w.c_tot
     n_in = -(-w.d_in // c_tot)
     n_rot = w.d_in - n_in
     nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
     total = n_in * t_modup + n_rot * t_rot + nnz * t_add
     return {"value": total * 1e3, "unit": "ms/layer", "cores": cores, "kind": "oracle",
-            "sample": "1 ModUp (%.2f s) + 1 hoisted rotation (%.2f s) + %d ciphertext add/subs (%.4f s each), extrapolated "
-                      "linearly to %d ModUps, %d rotations, %.3g add/subs" % (t_modup, t_rot, n_terms, t_add, n_in, n_rot, nnz)}
+            "sample": "%d ModUps (%.3f s each) + %d hoisted rotations (%.3f s each) + %d ciphertext add/subs (%.5f s each), "
+                      "extrapolated linearly to %d ModUps, %d rotations, %.3g add/subs" % (n1, t_modup, n2, t_rot, n3 * n_terms, t_add, n_in, n_rot, nnz)}
+
+
+def stagewise_rotation_units(w):
+    """Limb-units (8N bytes) one rotation moves when every stage of the textbook hybrid key switch goes
+    through HBM exactly once: inverse transform of c1, ModUp, transform of the raised digits, key inner
+    product, inverse transform of the special limbs, ModDown, transform back, combination with c0."""
+    L, K = w.q_count, w.p_count
+    beta = -(-L // w.alpha)
+    ext = L + K
+    E = beta * ext - L
+    return 2 * L + (L + E) + 2 * E + (3 * beta * ext + 2 * ext) + 4 * K + (2 * K + 2 * L) + 4 * L + 7 * L
 
 
 def main():
@@ -302,7 +321,10 @@ def main():
         "decrypt_max_abs_err": err, "roofline": roof, "kernels_ms_per_step": kernels, "hbm_kernels": hbm_fractions(w, prof),
     }
     if w.name == "keyswitch":
-        line["rotations"] = {"value": w.batch / (ms * 1e-3), "unit": "rotations/s", "workload": "keyswitch"}
+        rps = w.batch / (ms * 1e-3)
+        gbs = rps * stagewise_rotation_units(w) * 8.0 * w.N / 1e9
+        line["rotations"] = {"value": rps, "unit": "rotations/s", "workload": "keyswitch",
+                             "stagewise": {"units_per_rotation": stagewise_rotation_units(w), "GB/s": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}}
     del r
     if args.copy_probe:
         a = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
@@ -319,7 +341,9 @@ def main():
         kerr = rk.check()
         kprof = kernel_profile(rk)
         _, kroof = roofline_for(kw, kprof)
+        kgbs = kw.batch / (kms * 1e-3) * stagewise_rotation_units(kw) * 8.0 * kw.N / 1e9
         line["rotations"] = {"value": kw.batch / (kms * 1e-3), "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": kms,
+                             "stagewise": {"units_per_rotation": stagewise_rotation_units(kw), "GB/s": kgbs, "frac_of_hbm_peak": kgbs / HBM_PEAK_GBS},
                              "decrypt_max_abs_err": kerr, "roofline": kroof, "hbm_kernels": hbm_fractions(kw, kprof),
                              "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(kprof.items())}}
         log("key-switch leg: %.1f rotations/s" % line["rotations"]["value"])
