@@ -99,17 +99,20 @@ __global__ __launch_bounds__(AM_THREADS) void k_byte_planes(const u64 *xbase, u3
     // destination dword of this thread inside a plane tile: lane (k4/4)*32 + ln, dword k4 % 4
     const int dst = ((k4 >> 2) * 32 + ln) * 4 + (k4 & 3);
     v4i *out = (v4i *)(xp + ((size_t)nt_local * nk + (size_t)blockIdx.y * 8) * PLANES * 1024);
-    for (int s8 = 0; s8 < 8; s8++) {
-        const int step = blockIdx.y * 8 + s8;
-        u64 w[4];
+    // all 32 words of the block's 8 steps are requested before the first is used
+    u64 w[8][4];
+#pragma unroll
+    for (int s8 = 0; s8 < 8; s8++)
 #pragma unroll
         for (int j = 0; j < 4; j++) {
-            const int v = step * AM_TILE_K + 4 * k4 + j;
-            w[j] = v < n_v ? xw[(size_t)v * xstride] : 0;
+            const int v = (blockIdx.y * 8 + s8) * AM_TILE_K + 4 * k4 + j;
+            w[s8][j] = v < n_v ? xw[(size_t)v * xstride] : 0;
         }
+#pragma unroll
+    for (int s8 = 0; s8 < 8; s8++) {
         u32 pl[8];
-        transpose4((u32)w[0], (u32)w[1], (u32)w[2], (u32)w[3], pl);
-        transpose4((u32)(w[0] >> 32), (u32)(w[1] >> 32), (u32)(w[2] >> 32), (u32)(w[3] >> 32), pl + 4);
+        transpose4((u32)w[s8][0], (u32)w[s8][1], (u32)w[s8][2], (u32)w[s8][3], pl);
+        transpose4((u32)(w[s8][0] >> 32), (u32)(w[s8][1] >> 32), (u32)(w[s8][2] >> 32), (u32)(w[s8][3] >> 32), pl + 4);
         u32 *st = stage[s8 & 1];
 #pragma unroll
         for (int p = 0; p < PLANES; p++) st[p * 256 + dst] = pl[p] ^ 0x80808080u;
