@@ -158,17 +158,20 @@ def roofline_for(w, prof):
     beta = -(-L // alpha)
     if w.name == "keyswitch":
         n_rot, n_raise = w.batch, w.batch
+        n_key = n_rot  # every rotation streams its key
     else:
         n_in = -(-w.d_in // w.c_tot)
         n_rot, n_raise = w.d_in - n_in, n_in
+        # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
+        n_key = -(-n_in // 16) * (min(w.c_tot, w.d_in) - 1)
     # HBM-bound classes: algorithmic limb-units per step (every operand read once, every result written once)
     hbm = {
         # fused path (N = 2^16, ciphertext primes below 2^50)
         "ks_pre": n_raise * 2 * L,
         "ks_modup_fcols": n_raise * (3 * L + beta * ext + L),        # y, c1, c0 in; raised digits and P*c0 out
         "ks_frows": n_raise * 2 * (beta * ext + L),
-        "ks_inner_irows": n_rot * (3 * beta * L + L + 2 * L),                  # ciphertext limbs: digits, key, P*c0 in; accumulators out
-        "ks_inner_irows_wide": n_rot * (3 * beta * K + 2 * K),                 # special limbs (integer arithmetic)
+        "ks_inner_irows": n_rot * (beta * L + L + 2 * L) + n_key * 2 * beta * L,   # ciphertext limbs: digits, P*c0, key in; accumulators out
+        "ks_inner_irows_wide": n_rot * (beta * K + 2 * K) + n_key * 2 * beta * K,  # special limbs (integer arithmetic)
         "ks_icols_special": n_rot * 4 * K,                                     # special limbs in, split residues out
         "ks_icols_moddown": n_rot * (2 * L + 2 * K + 2 * L),                   # accumulators and residues in, ciphertext out
         # unfused path

@@ -1107,42 +1107,50 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     const int chunk = 128;
     const u64 *xbase = in->d;
     if (n_rot) {
-        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, raised_words(ctx, l1)))) return rc;
+        const int GS = std::min(n_in, 16);  // packed inputs raised together (about 48 MiB of digits each at 16 limbs)
+        const size_t rw = raised_words(ctx, l1);
+        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)GS * rw))) return rc;
         if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)std::min(chunk, n_rot) * 2 * ext * N))) return rc;
         if ((rc = grow(ctx, &ctx->ws_virt, &ctx->ws_virt_words, (size_t)n_v * in_ct))) return rc;
         if ((rc = ensure_desc(ctx, n_rot))) return rc;
         xbase = ctx->ws_virt;
+        // Packed inputs are raised GS at a time and their rotations ordered by amount, so that the GS
+        // rotations that use one key sit next to each other in a launch: the blocks that read a key tile then
+        // run at nearly the same time on one XCD and all but the first read are served by its L2.
         std::vector<RotDesc> desc;
-        std::vector<std::pair<int, int>> groups;  // (first descriptor, count) per packed input
-        for (int G = 0; G < n_in; G++) {
+        std::vector<std::pair<int, int>> groups;  // (first descriptor, count) per group of GS packed inputs
+        for (int G0 = 0; G0 < n_in; G0 += GS) {
             const int first = (int)desc.size();
             for (int rho = 0; rho < c_tot; rho++) {
-                const int v = vid[(size_t)G * c_tot + rho];
-                if (v < 0) continue;
-                u64 *slot = ctx->ws_virt + (size_t)v * in_ct;
-                if (rho == 0) {
-                    ENSI_HIP(ctx, hipMemcpyAsync(slot, in->d + (size_t)G * in_ct, in_ct * sizeof(u64), hipMemcpyDeviceToDevice, st));
-                    continue;
+                for (int G = G0; G < std::min(G0 + GS, n_in); G++) {
+                    const int v = vid[(size_t)G * c_tot + rho];
+                    if (v < 0) continue;
+                    u64 *slot = ctx->ws_virt + (size_t)v * in_ct;
+                    if (rho == 0) {
+                        ENSI_HIP(ctx, hipMemcpyAsync(slot, in->d + (size_t)G * in_ct, in_ct * sizeof(u64), hipMemcpyDeviceToDevice, st));
+                        continue;
+                    }
+                    RotDesc ds;
+                    ds.c0 = in->d + (size_t)G * in_ct;
+                    ds.digits = ctx->ws_digits + (size_t)(G - G0) * rw;
+                    ds.key = key_of[rho];
+                    ds.out = slot;
+                    ds.g = g_of[rho];
+                    ds.g_inv = inv_mod_2n(ds.g, N);
+                    desc.push_back(ds);
                 }
-                RotDesc ds;
-                ds.c0 = in->d + (size_t)G * in_ct;
-                ds.digits = ctx->ws_digits;
-                ds.key = key_of[rho];
-                ds.out = slot;
-                ds.g = g_of[rho];
-                ds.g_inv = inv_mod_2n(ds.g, N);
-                desc.push_back(ds);
             }
             groups.push_back({first, (int)desc.size() - first});
         }
         ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
         // ---- unpack: one ModUp per packed input, shared by all its rotations
-        for (int G = 0; G < n_in; G++) {
-            if (!groups[G].second) continue;
-            if ((rc = raise_cts(ctx, l1, in->d + (size_t)G * in_ct, in_ct, in->limbs_alloc, 1, st))) return rc;
-            for (int o = 0; o < groups[G].second; o += chunk) {
-                const int cnt = std::min(chunk, groups[G].second - o);
-                if ((rc = run_rotations(ctx, ctx->ws_desc + groups[G].first + o, cnt, l1, in->limbs_alloc, in->limbs_alloc, st))) return rc;
+        for (size_t gi = 0; gi < groups.size(); gi++) {
+            if (!groups[gi].second) continue;
+            const int G0 = (int)gi * GS, cnt_in = std::min(GS, n_in - G0);
+            if ((rc = raise_cts(ctx, l1, in->d + (size_t)G0 * in_ct, in_ct, in->limbs_alloc, cnt_in, st))) return rc;
+            for (int o = 0; o < groups[gi].second; o += chunk) {
+                const int cnt = std::min(chunk, groups[gi].second - o);
+                if ((rc = run_rotations(ctx, ctx->ws_desc + groups[gi].first + o, cnt, l1, in->limbs_alloc, in->limbs_alloc, st))) return rc;
             }
         }
     }
