@@ -150,6 +150,13 @@ def kernel_profile(runner):
     return prof
 
 
+# HBM-side bytes per launch of a workload's dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised under profiles/ (counter x calibration factor, averaged over the launches of one step).
+MEASURED_TRAFFIC = {
+    ("ffn2560", "accumulate_mfma"): (837.0 + 145.5) * 2.0 ** 30 / 9,
+}
+
+
 def roofline_for(w, prof):
     """Roofline entry of the dominant kernel class of the step (largest total time)."""
     N, L, K, alpha = w.N, w.q_count, w.p_count, w.alpha
@@ -194,8 +201,8 @@ def roofline_for(w, prof):
         dm = w.d_in * (w.d_mid or w.d_out) + (w.d_mid * w.d_out if w.d_mid else 0)
         ops = 2.0 * dm * 2 * L * N * planes
         return dom, {"bound": "mfma", "achieved": ops / (ms * 1e-3) / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": None, "kernel": dom,
-                     "launch_ms": ms / max(launches, 1), "launches": launches}
+                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": MEASURED_TRAFFIC.get((w.name, dom)), "kernel": dom,
+                     "launch_ms": ms / max(launches, 1), "launches": launches, "ops_per_launch": ops / max(launches, 1)}
     if dom == "accumulate":
         # Alg. 1: one 64-bit add/sub per non-zero weight per limb word
         nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
