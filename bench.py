@@ -36,9 +36,10 @@ def log(msg):
 
 
 class Runner:
-    def __init__(self, w, seed=1):
+    def __init__(self, w, seed=1, separate_rescale=False):
         from paper_2509_09424_amd import binding
         self.w = w
+        self.separate_rescale = separate_rescale
         self.ctx = binding.Context(*w.param_tuple(), seed=seed)
         self.N, self.n = w.N, w.n_slots
         self.L, self.K, self.alpha = w.q_count, w.p_count, w.alpha
@@ -92,9 +93,13 @@ class Runner:
             if getattr(self, "mid", None) is not None:
                 self.mid.free()
             mid = self.ctx.ct_wrap(self.ct_out.device_ptr, w.d_mid, self.L, self.ct_in.scale)
-            self.ctx.mul_scalar_rescale(mid, w.kappa)
             self.mid = mid
-            self.ctx.ternary_matmul(None, mid, self.n, w.d_mid, self.W2, "zero", self.ct_out2)
+            if self.separate_rescale:
+                self.ctx.mul_scalar_rescale(mid, w.kappa)
+                self.ctx.ternary_matmul(None, mid, self.n, w.d_mid, self.W2, "zero", self.ct_out2)
+            else:
+                # scalar-multiply + rescale applied while the second layer reads its operands
+                self.ctx.rescale_ternary_matmul(mid, w.kappa, self.W2, self.ct_out2)
 
     def check(self):
         """Decrypts a few outputs and compares with the float64 product (sanity, untimed)."""
@@ -187,6 +192,9 @@ def roofline_for(w, prof):
         "modup": n_raise * (L + beta * ext),
         "moddown": n_rot * (2 * ext + 3 * L),
         "mul_scalar_rescale": (w.d_mid or 0) * (2 * L + 2 * (L - 1)),
+        # plane split: 8 bytes read + planes bytes written per operand word (units of 8 bytes per word: /N below)
+        "byte_planes": (w.d_in * 2 * L + (0 if "rescale_byte_planes" in prof else (w.d_mid or 0) * 2 * (L - 1))) * (8 + 7) / 8.0,
+        "rescale_byte_planes": (w.d_mid or 0) * (2 * L + 2 * (L - 1) * 7 / 8.0),
     }
     members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
     classes = list(hbm) + ["accumulate", "accumulate_mfma"]
@@ -215,11 +223,13 @@ def roofline_for(w, prof):
                  "traffic": None, "kernel": dom, "launch_ms": ms / max(launches, 1), "launches": launches}
 
 
-def hbm_fractions(w, prof):
+def hbm_fractions(w, prof_all):
     """Algorithmic GB/s of every HBM-bound kernel class that ran in the step (for the key-switch target)."""
     out = {}
-    for name in list(prof):
-        one = {name: prof[name]}
+    for name in list(prof_all):
+        one = {name: prof_all[name]}
+        if name == "byte_planes" and "rescale_byte_planes" in prof_all:
+            one["rescale_byte_planes"] = (0.0, 0)
         try:
             dom, roof = roofline_for(w, one)
         except ZeroDivisionError:
@@ -297,6 +307,8 @@ def main():
     ap.add_argument("--workload", default="ffn2560", choices=[w.name for w in wl.WORKLOADS])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-keyswitch-leg", action="store_true")
+    ap.add_argument("--separate-rescale", action="store_true",
+                    help="FFN workload: run scalar-multiply + rescale as its own in-place pass instead of inside the second layer")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB read + 1 GiB write elementwise kernel (calibrates profiler byte counters)")
     args = ap.parse_args()
@@ -311,7 +323,7 @@ def main():
     w = wl.BY_NAME[args.workload]
     log("workload %s on %s" % (w.name, torch.cuda.get_device_name(0)))
     t0 = time.time()
-    r = Runner(w)
+    r = Runner(w, separate_rescale=args.separate_rescale)
     r.setup()
     log("set-up done in %.1f s" % (time.time() - t0))
     ms = time_steps(r, args.steps, args.warmup)

@@ -170,6 +170,16 @@ int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode);
  * scale' = scale * round(kappa q_l) / (kappa q_l). */
 int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stream);
 
+/* The step between two PCMM layers and the second layer (Alg. 1) as one call: the same result as
+ * ensi_mul_scalar_rescale(in, kappa) followed by ensi_ternary_matmul(NULL, in, s = N/2, d = in->n, W, m,
+ * ENSI_PLACE_ZERO, out), i.e. `in` holds one activation column per ciphertext (the paper's own packing, no
+ * rotations) and out_i = sum_j W[j][i] * rescale(kappa * in_j).  W: host int8[in->n][m].  out: batch of m
+ * ciphertexts with one limb less than `in`.  Where the matrix-core path applies (all active primes below
+ * 2^50), the rescaled operands are formed while the accumulate reads them and never written to memory.
+ * `in` is consumed: its handle takes the level and scale of the rescaled batch, its words are unspecified
+ * afterwards (rescaled in place or left as they were). */
+int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

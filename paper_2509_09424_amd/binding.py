@@ -21,7 +21,7 @@ EXPORTED = [
     "ensi_pk_free", "ensi_galois_keygen", "ensi_gk_free", "ensi_encode", "ensi_pt_import", "ensi_pt_export",
     "ensi_pt_free", "ensi_ct_alloc", "ensi_ct_wrap", "ensi_ct_free", "ensi_ct_info", "ensi_ct_export",
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
-    "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -191,6 +191,16 @@ class Context:
     def mul_scalar_rescale(self, ct, kappa, stream=0):
         self._check(self.lib.ensi_mul_scalar_rescale(self.h, ct.h, ctypes.c_double(kappa), ctypes.c_void_p(stream)))
         return ct
+
+    def rescale_ternary_matmul(self, ct_in, kappa, W, ct_out=None, stream=0):
+        W = np.ascontiguousarray(W, dtype=np.int8)
+        if W.ndim != 2 or W.shape[0] != ct_in.n:
+            raise EnsiError("W must be int8 [n_in][m]")
+        m = W.shape[1]
+        if ct_out is None:
+            ct_out = self.ct_alloc(m, ct_in.limbs - 1)
+        self._check(self.lib.ensi_rescale_ternary_matmul(self.h, ct_in.h, ctypes.c_double(kappa), _ptr(W), m, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):
         prime_idx = np.ascontiguousarray(prime_idx, dtype=np.int32)

@@ -24,7 +24,10 @@
 // once instead of once per output tile (10 to 27 times at the benchmark shapes), which
 // takes the byte shuffling, the plane stores and a second LDS buffer out of the
 // contraction's inner loop.  The plane array of a whole operand array can exceed the
-// memory left, so the host works through the word tiles in slices.
+// memory left, so the host works through the coefficients in slices (a slice holds a
+// range of 32-coefficient tiles of every limb of both polynomials).  The split can apply
+// the scalar-multiply + rescale step between two layers on the fly (k_byte_planes<.., true>):
+// the rescaled operands then never exist as 64-bit words in memory.
 //
 // k_accumulate_mfma.  A work item is 256 outputs x 32 consecutive words; inside it each
 // of the 4 waves owns 64 outputs (two 32x32 blocks) for all byte planes and walks the
@@ -80,36 +83,26 @@ __device__ __forceinline__ u64 reduce_signed(int64_t t, u64 q, double q_inv) {
 }
 
 // ---------------------------------------------------------------- byte planes of the operands
-// grid (word tiles of the slice, n_kpad / 256); each block converts 8 steps of one word tile.
-// Thread (k4 = tid / 32, ln = tid % 32) handles operands 4*k4 .. 4*k4+3 of the step, word ln: its four
-// words give one dword (4 operand bytes) of every plane.  The tile is staged in LDS and written out as
+// Slice-local word tile: nt_local = pl * cw + ctile, pl = poly * l1 + limb, ctile = coefficient tile - c0.
+// Thread (k4 = tid / 32, ln = tid % 32) handles operands 4*k4 .. 4*k4+3 of a step, word ln: its four
+// words give one dword (4 operand bytes) of every plane.  A plane tile is staged in LDS and written out as
 // whole 16-byte lane entries.  Bytes are stored as u - 128 (u xor 0x80); operands beyond n_v are zero
 // words (their weights are zero).
-template <int PLANES>
-__global__ __launch_bounds__(AM_THREADS) void k_byte_planes(const u64 *xbase, u32 xstride, int n_v, int nk, int N, int l1, int limb_stride_in,
-                                                            int nt_begin, char *xp) {
-    __shared__ u32 stage[2][PLANES * 256];
-    const int tid = threadIdx.x, k4 = tid >> 5, ln = tid & 31;
-    const int nt_local = blockIdx.x, nt = nt_begin + nt_local;
-    const size_t per_poly = (size_t)l1 * N;
-    const size_t word0 = (size_t)nt * AM_TILE_N;
-    const int poly = (int)(word0 / per_poly);
-    const size_t off_in = (size_t)poly * limb_stride_in * N + (word0 - (size_t)poly * per_poly);
-    const u64 *xw = xbase + off_in + ln;
-    // destination dword of this thread inside a plane tile: lane (k4/4)*32 + ln, dword k4 % 4
-    const int dst = ((k4 >> 2) * 32 + ln) * 4 + (k4 & 3);
-    v4i *out = (v4i *)(xp + ((size_t)nt_local * nk + (size_t)blockIdx.y * 8) * PLANES * 1024);
-    // all 32 words of the block's 8 steps are requested before the first is used
-    u64 w[8][4];
+struct AmFp {  // fp64 arithmetic on exact integers modulo a prime below 2^50 (as in the rescale kernel)
+    double q, qinv;
+    __device__ __forceinline__ double mid(double x) const { return fma(-rint(x * qinv), q, x); }
+    __device__ __forceinline__ double mulmod(double x, double w, double wq) const {
+        const double h = x * w;
+        const double l = fma(x, w, -h);
+        const double t = rint(x * wq);
+        return fma(-t, q, h) + l;
+    }
+};
+
+template <int PLANES, int STEPS>
+__device__ __forceinline__ void planes_out(const u64 (&w)[STEPS][4], u32 (*stage)[PLANES * 256], int dst, v4i *out, int tid) {
 #pragma unroll
-    for (int s8 = 0; s8 < 8; s8++)
-#pragma unroll
-        for (int j = 0; j < 4; j++) {
-            const int v = (blockIdx.y * 8 + s8) * AM_TILE_K + 4 * k4 + j;
-            w[s8][j] = v < n_v ? xw[(size_t)v * xstride] : 0;
-        }
-#pragma unroll
-    for (int s8 = 0; s8 < 8; s8++) {
+    for (int s8 = 0; s8 < STEPS; s8++) {
         u32 pl[8];
         transpose4((u32)w[s8][0], (u32)w[s8][1], (u32)w[s8][2], (u32)w[s8][3], pl);
         transpose4((u32)(w[s8][0] >> 32), (u32)(w[s8][1] >> 32), (u32)(w[s8][2] >> 32), (u32)(w[s8][3] >> 32), pl + 4);
@@ -119,6 +112,91 @@ __global__ __launch_bounds__(AM_THREADS) void k_byte_planes(const u64 *xbase, u3
         __syncthreads();  // (the other staging buffer was read before the previous barrier)
         const v4i *sv = (const v4i *)st;
         for (int e = tid; e < PLANES * 64; e += AM_THREADS) out[(size_t)s8 * PLANES * 64 + e] = sv[e];
+    }
+}
+
+// grid (cw, nk / 8, 2 * l1); each block converts 8 steps of one word tile.
+template <int PLANES>
+__global__ __launch_bounds__(AM_THREADS) void k_byte_planes(const u64 *xbase, u32 xstride, int n_v, int nk, int N, int l1, int limb_stride_in,
+                                                            int c0, int cw, char *xp) {
+    __shared__ u32 stage[2][PLANES * 256];
+    const int tid = threadIdx.x, k4 = tid >> 5, ln = tid & 31;
+    const int pl = blockIdx.z, poly = pl / l1, limb = pl - poly * l1;
+    const u64 *xw = xbase + ((size_t)poly * limb_stride_in + limb) * N + (size_t)(c0 + blockIdx.x) * AM_TILE_N + ln;
+    // destination dword of this thread inside a plane tile: lane (k4/4)*32 + ln, dword k4 % 4
+    const int dst = ((k4 >> 2) * 32 + ln) * 4 + (k4 & 3);
+    v4i *out = (v4i *)(xp + (((size_t)pl * cw + blockIdx.x) * nk + (size_t)blockIdx.y * 8) * PLANES * 1024);
+    // all 32 words of the block's 8 steps are requested before the first is used
+    u64 w[8][4];
+#pragma unroll
+    for (int s8 = 0; s8 < 8; s8++)
+#pragma unroll
+        for (int j = 0; j < 4; j++) {
+            const int v = (blockIdx.y * 8 + s8) * AM_TILE_K + 4 * k4 + j;
+            w[s8][j] = v < n_v ? xw[(size_t)v * xstride] : 0;
+        }
+    planes_out<PLANES, 8>(w, stage, dst, out, tid);
+}
+
+// The same with the scalar-multiply + rescale step applied on the way: the operands are read at l1 + 1
+// limbs, c <- c * k, limb l1 dropped with rounding to nearest (c_i <- (c_i k - [c_l k]) q_l^-1 mod q_i with
+// the centred representative of limb l1), and the planes of the l1 remaining limbs written.  fc: [5][l1+1]
+// doubles: k mod q_i, that / q_i, q_l^-1 mod q_i, that / q_i, 1 / q_i.  grid (cw, nk / 4, 2): a block keeps
+// the centred last-limb residues of its 32 coefficients x 128 operands in registers and walks the limbs
+// (4 steps per block keep the register count low enough for four blocks per CU).
+#define AM_RS_STEPS 4
+template <int PLANES>
+__global__ __launch_bounds__(AM_THREADS) void k_byte_planes_rescale(const u64 *xbase, u32 xstride, int n_v, int nk, int N, int l1,
+                                                                    int limb_stride_in, int c0, int cw, char *xp, const PrimeConst *pc,
+                                                                    const double *fc) {
+    __shared__ u32 stage[2][PLANES * 256];
+    const int tid = threadIdx.x, k4 = tid >> 5, ln = tid & 31;
+    const int poly = blockIdx.z, lin = l1 + 1;
+    const u64 *xw = xbase + (size_t)poly * limb_stride_in * N + (size_t)(c0 + blockIdx.x) * AM_TILE_N + ln;
+    const int dst = ((k4 >> 2) * 32 + ln) * 4 + (k4 & 3);
+    u64 w[AM_RS_STEPS][4];
+    double xl[AM_RS_STEPS][4];
+    // operand rows of this thread: row[s8] + j * xstride for j < n_live[s8] (a multiple of four operands except in
+    // the last step of a ragged operand count; dead operands re-read row j = 0 and are zeroed before the split)
+    const u64 *row[AM_RS_STEPS];
+    int n_live[AM_RS_STEPS];
+#pragma unroll
+    for (int s8 = 0; s8 < AM_RS_STEPS; s8++) {
+        const int v0 = (blockIdx.y * AM_RS_STEPS + s8) * AM_TILE_K + 4 * k4;
+        n_live[s8] = min(max(n_v - v0, 0), 4);
+        row[s8] = xw + (size_t)(n_live[s8] ? v0 : 0) * xstride;
+    }
+    {
+        const AmFp ml = {(double)pc[l1].q, fc[4 * lin + l1]};
+        const double kl = fc[l1], kl_q = fc[lin + l1];
+#pragma unroll
+        for (int s8 = 0; s8 < AM_RS_STEPS; s8++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[s8][j] = row[s8][(size_t)(j < n_live[s8] ? j : 0) * xstride + (size_t)l1 * N];
+#pragma unroll
+        for (int s8 = 0; s8 < AM_RS_STEPS; s8++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) xl[s8][j] = ml.mid(ml.mulmod((double)w[s8][j], kl, kl_q));
+    }
+    for (int limb = 0; limb < l1; limb++) {
+        const AmFp m = {(double)pc[limb].q, fc[4 * lin + limb]};
+        const double k = fc[limb], k_q = fc[lin + limb], qi = fc[2 * lin + limb], qi_q = fc[3 * lin + limb];
+#pragma unroll
+        for (int s8 = 0; s8 < AM_RS_STEPS; s8++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) w[s8][j] = row[s8][(size_t)(j < n_live[s8] ? j : 0) * xstride + (size_t)limb * N];
+#pragma unroll
+        for (int s8 = 0; s8 < AM_RS_STEPS; s8++)
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                const double t = m.mulmod((double)w[s8][j], k, k_q) - m.mid(xl[s8][j]);
+                double r = m.mid(m.mulmod(m.mid(t), qi, qi_q));
+                r = r < 0.0 ? r + m.q : r;
+                w[s8][j] = j < n_live[s8] ? (u64)r : 0;
+            }
+        v4i *out = (v4i *)(xp + ((((size_t)poly * l1 + limb) * cw + blockIdx.x) * nk + (size_t)blockIdx.y * AM_RS_STEPS) * PLANES * 1024);
+        __syncthreads();  // the staging buffers of the previous limb have been written out
+        planes_out<PLANES, AM_RS_STEPS>(w, stage, dst, out, tid);
     }
 }
 
@@ -137,10 +215,10 @@ struct AmLayout {
     static constexpr int total = bias_off + 2 * AM_TILE_M * 4;
 };
 
-// xp: plane tiles of the slice, [word tile][nk][PLANES][1024]; nt_begin: first word tile of the slice
-// (of n_tiles_n); nk = n_kpad / 32, a multiple of AM_RING.
+// xp: plane tiles of the slice, [word tile][nk][PLANES][1024]; the slice covers coefficient tiles c0 .. c0+cw-1
+// of all 2*l1 limb rows (n_tiles_n = 2*l1*cw word tiles); nk = n_kpad / 32, a multiple of AM_RING.
 template <int PLANES>
-__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int nt_begin, int n_kpad, const v4i *wfrag, const int32_t *bias,
+__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int c0, int cw, int n_kpad, const v4i *wfrag, const int32_t *bias,
                                                                 int m, AmPrimes pr, int N, int l1, u64 *out, int limb_stride_out,
                                                                 int n_tiles_n, int n_tiles_m, int workers_per_xcd, int m_group) {
     HIP_DYNAMIC_SHARED(char, smem)
@@ -157,7 +235,6 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
     const u32 a_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::aring_off + wv * AM_RING * AM_ASLOT));
     const char *a_rd = smem + LY::aring_off + wv * AM_RING * AM_ASLOT + lane * 16;
     const char *b_rd = smem + LY::bring_off + lane * 16;
-    const size_t per_poly = (size_t)l1 * N;
     const size_t ct_words_out = (size_t)2 * limb_stride_out * N;
     const int xcd = blockIdx.x & 7, worker = blockIdx.x >> 3;
     const int n_nt = (n_tiles_n + 7) / 8;  // word tiles of this XCD
@@ -242,11 +319,8 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
         int m_tile, nt_local;
         decode(item, m_tile, nt_local);
         const int next = next_valid(item + workers_per_xcd);
-        const size_t word0 = (size_t)(nt_begin + nt_local) * AM_TILE_N;
-        const int poly = (int)(word0 / per_poly);
-        const size_t rem = word0 - (size_t)poly * per_poly;
-        const int limb = (int)(rem / N);
-        const size_t off_out = (size_t)poly * limb_stride_out * N + rem;
+        const int pl = nt_local / cw, poly = pl / l1, limb = pl - poly * l1;
+        const size_t off_out = ((size_t)poly * limb_stride_out + limb) * N + (size_t)(c0 + nt_local - pl * cw) * AM_TILE_N;
         const int i0 = m_tile * AM_TILE_M + wv * 64;
         // offset terms of this item's outputs: copied one item ahead into two buffers used alternately (the
         // other one may still be read by a wave that has not finished the previous item's recombination)
@@ -336,48 +410,51 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
 
 template <int P>
 static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
-                      const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_n, int n_tiles_m,
-                      int workers, int m_group, char *xp, int slice_tiles) {
+                      const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_m, int workers,
+                      int m_group, char *xp, int slice_ctiles, const double *d_rescale) {
     static bool attr_set = false;
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
         attr_set = true;
     }
-    const int nk = n_kpad / AM_TILE_K;
+    const int nk = n_kpad / AM_TILE_K, ctiles = ctx->N / AM_TILE_N;
     AmPrimes pr;
     for (int i = 0; i < ENSI_MAX_EXT; i++) {
         pr.q[i] = i < l1 ? ctx->primes[i] : 1;
         pr.q_inv[i] = 1.0 / (double)pr.q[i];
     }
-    for (int nt0 = 0; nt0 < n_tiles_n; nt0 += slice_tiles) {
-        const int cnt = std::min(slice_tiles, n_tiles_n - nt0);
+    for (int c0 = 0; c0 < ctiles; c0 += slice_ctiles) {
+        const int cw = std::min(slice_ctiles, ctiles - c0);
         {
-            ScopedTimer t(ctx, "byte_planes", st);
-            hipLaunchKernelGGL(k_byte_planes<P>, dim3(cnt, nk / 8), dim3(AM_THREADS), 0, st, xbase, xstride, n_v, nk, ctx->N, l1, limb_stride_in,
-                               nt0, xp);
+            ScopedTimer t(ctx, d_rescale ? "rescale_byte_planes" : "byte_planes", st);
+            if (d_rescale)
+                hipLaunchKernelGGL(k_byte_planes_rescale<P>, dim3(cw, nk / AM_RS_STEPS, 2), dim3(AM_THREADS), 0, st, xbase, xstride, n_v, nk, ctx->N, l1,
+                                   limb_stride_in, c0, cw, xp, ctx->d_pc, d_rescale);
+            else
+                hipLaunchKernelGGL(k_byte_planes<P>, dim3(cw, nk / 8, 2 * l1), dim3(AM_THREADS), 0, st, xbase, xstride, n_v, nk, ctx->N, l1,
+                                   limb_stride_in, c0, cw, xp);
         }
         {
             ScopedTimer t(ctx, "accumulate_mfma", st);
-            hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, (const char *)xp, nt0, n_kpad, wfrag,
-                               bias, m, pr, ctx->N, l1, out, limb_stride_out, cnt, n_tiles_m, workers, m_group);
+            hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, (const char *)xp, c0, cw, n_kpad, wfrag,
+                               bias, m, pr, ctx->N, l1, out, limb_stride_out, 2 * l1 * cw, n_tiles_m, workers, m_group);
         }
     }
 }
 
-// Bytes of plane workspace the contraction asks for: all word tiles if they fit the budget, else a slice.
-static int am_slice_tiles(int n_tiles_n, int n_kpad, int planes) {
-    const size_t per_tile = (size_t)(n_kpad / AM_TILE_K) * (planes <= 5 ? 5 : 7) * 1024;
+// Coefficient tiles per slice: all of them if their planes fit the budget.
+static int am_slice_ctiles(int ctiles, int l1, int n_kpad, int planes) {
+    const size_t per_ctile = (size_t)2 * l1 * (n_kpad / AM_TILE_K) * (planes <= 5 ? 5 : 7) * 1024;
     const size_t budget = (size_t)16 << 30;
-    size_t tiles = budget / per_tile;
-    if (tiles >= (size_t)n_tiles_n) return n_tiles_n;
-    tiles = tiles / 64 * 64;  // whole groups of 8 word tiles per XCD
-    return (int)std::max<size_t>(tiles, 64);
+    return (int)std::min<size_t>((size_t)ctiles, std::max<size_t>(budget / per_ctile, 1));
 }
 
+// d_rescale != nullptr: the operands are read at l1 + 1 limbs and the scalar-multiply + rescale step is applied while
+// their planes are built (constants as for k_rescale_fp at l1 + 1 limbs); out is at l1 limbs.
 int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
-                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st) {
-    const size_t words = (size_t)2 * l1 * ctx->N;
-    const int n_tiles_n = (int)(words / AM_TILE_N);
+                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
+                           hipStream_t st) {
+    const int ctiles = ctx->N / AM_TILE_N;
     const int n_tiles_m = (m + AM_TILE_M - 1) / AM_TILE_M;
     static int n_cu = 0;
     if (!n_cu) {
@@ -390,8 +467,8 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
     const v4i *wf = (const v4i *)d_wt;
     const int m_group = 8;  // 8 output tiles x 4 word tiles in flight per XCD
     const int P = planes <= 5 ? 5 : 7;
-    const int slice_tiles = am_slice_tiles(n_tiles_n, n_kpad, P);
-    const size_t xp_words = ((size_t)slice_tiles * (n_kpad / AM_TILE_K) * P * 1024 + 7) / 8;
+    const int slice_ctiles = am_slice_ctiles(ctiles, l1, n_kpad, P);
+    const size_t xp_words = ((size_t)slice_ctiles * 2 * l1 * (n_kpad / AM_TILE_K) * P * 1024 + 7) / 8;
     if (ctx->ws_xp_words < xp_words) {
         if (ctx->ws_xp) (void)hipFree(ctx->ws_xp);
         ctx->ws_xp = nullptr;
@@ -403,10 +480,10 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
         ctx->ws_xp_words = xp_words;
     }
     if (P == 5)
-        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m,
-                     workers, m_group, (char *)ctx->ws_xp, slice_tiles);
+        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, workers,
+                     m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale);
     else
-        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_n, n_tiles_m,
-                     workers, m_group, (char *)ctx->ws_xp, slice_tiles);
+        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, workers,
+                     m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale);
     return ENSI_OK;
 }

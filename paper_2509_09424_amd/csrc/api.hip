@@ -1158,7 +1158,7 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     const bool use_mfma = plan->planes > 0 && ctx->accumulate_mode != 1;
     if (use_mfma) {
         if ((rc = launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc,
-                                         out->d, out->limbs_alloc, st)))
+                                         out->d, out->limbs_alloc, nullptr, st)))
             return rc;
     } else
         launch_accumulate(ctx, xbase, in_ct, n_v, plan->d_masks, m, l1, in->limbs_alloc, out->d, out->limbs_alloc, st);
@@ -1168,11 +1168,11 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
 }
 
 // -------------------------------------------------------------------- rescale
-extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stream) {
-    if (!ctx || !ct || !(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
-    if (ct->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
-    hipStream_t st = (hipStream_t)stream;
-    const int l1 = ct->limbs;
+// Constants of the scalar-multiply + rescale step at l1 limbs, uploaded to ws_plan: integer set [5][l1]
+// (k mod q_i, Shoup(k), q_l^{-1} mod q_i, Shoup(.), q_l mod q_i) followed by the fp64 set [5][l1] (k, k/q, q_l^{-1},
+// q_l^{-1}/q, 1/q), the latter only meaningful when every active prime is below 2^50 (*fp).
+static int upload_rescale_consts(ensi_ctx *ctx, int l1, double kappa, hipStream_t st, const u64 **d_consts, const double **d_fconsts,
+                                 bool *fp_out, double *kr_out) {
     const u64 ql = ctx->primes[l1 - 1];
     const double kr = floor(fabs(kappa) * (double)ql + 0.5);
     const u64 kabs = (u64)kr;
@@ -1189,7 +1189,6 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
             consts[4 * l1 + i] = ql % q;
         }
     }
-    // fp64 constants when every active prime is below 2^50: k, k/q, q_l^{-1}, q_l^{-1}/q, 1/q
     bool fp = true;
     for (int i = 0; i < l1; i++) fp = fp && ctx->primes[i] < ((u64)1 << 50);
     std::vector<double> fconsts(5 * (size_t)l1, 0.0);
@@ -1205,9 +1204,60 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
     if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, 2 * consts.size()))) return rc;
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan, consts.data(), consts.size() * 8, hipMemcpyHostToDevice, st));
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan + consts.size(), fconsts.data(), fconsts.size() * 8, hipMemcpyHostToDevice, st));
-    launch_rescale(ctx, ct->d, ct->n, l1, ct->limbs_alloc, ctx->ws_plan, fp ? (const double *)(ctx->ws_plan + consts.size()) : nullptr, st);
+    *d_consts = ctx->ws_plan;
+    *d_fconsts = (const double *)(ctx->ws_plan + consts.size());
+    *fp_out = fp;
+    *kr_out = kr;
+    return ENSI_OK;
+}
+
+extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stream) {
+    if (!ctx || !ct || !(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
+    if (ct->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
+    hipStream_t st = (hipStream_t)stream;
+    const int l1 = ct->limbs;
+    const u64 *d_consts;
+    const double *d_fconsts;
+    bool fp;
+    double kr;
+    int rc;
+    if ((rc = upload_rescale_consts(ctx, l1, kappa, st, &d_consts, &d_fconsts, &fp, &kr))) return rc;
+    launch_rescale(ctx, ct->d, ct->n, l1, ct->limbs_alloc, d_consts, fp ? d_fconsts : nullptr, st);
     ct->limbs = l1 - 1;
-    ct->scale = ct->scale * kr / (fabs(kappa) * (double)ql);
+    ct->scale = ct->scale * kr / (fabs(kappa) * (double)ctx->primes[l1 - 1]);
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+extern "C" int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out,
+                                           void *stream) {
+    if (!ctx || !in || !W || !out || m < 1 || !(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
+    if (in->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
+    if (out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input (%d vs %d limbs)", out->limbs, in->limbs);
+    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
+    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const int N = ctx->N, d = in->n, l1_in = in->limbs, l1 = l1_in - 1;
+    int rc;
+    MatmulPlan *plan;
+    if ((rc = get_plan(ctx, W, N / 2, d, m, ENSI_PLACE_ZERO, 1, d, l1, &plan))) return rc;
+    bool fp = true;
+    for (int i = 0; i < l1_in; i++) fp = fp && ctx->primes[i] < ((u64)1 << 50);
+    if (!fp || plan->planes == 0 || ctx->accumulate_mode == 1) {
+        // no fused form for these parameters: the two steps one after the other
+        if ((rc = ensi_mul_scalar_rescale(ctx, in, kappa, stream))) return rc;
+        return ensi_ternary_matmul(ctx, nullptr, in, N / 2, d, W, m, ENSI_PLACE_ZERO, out, stream);
+    }
+    const u64 *d_consts;
+    const double *d_fconsts;
+    double kr;
+    if ((rc = upload_rescale_consts(ctx, l1_in, kappa, st, &d_consts, &d_fconsts, &fp, &kr))) return rc;
+    if ((rc = launch_accumulate_mfma(ctx, in->d, (size_t)2 * in->limbs_alloc * N, d, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1,
+                                     in->limbs_alloc, out->d, out->limbs_alloc, d_fconsts, st)))
+        return rc;
+    in->limbs = l1;
+    in->scale = in->scale * kr / (fabs(kappa) * (double)ctx->primes[l1_in - 1]);
+    out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
 }

@@ -212,8 +212,10 @@ void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, c
                     hipStream_t st);
 // planes: 5 or 7 byte planes contracted; weights d_wt in fragment order [m_pad/256][n_kpad/32][4][2][64][16], n_kpad a
 // multiple of 256.  Grows ctx->ws_xp (byte planes of a slice of the operand words); returns an ENSI_E_* code.
+// d_rescale != nullptr: operands are read at l1 + 1 limbs and multiplied/rescaled on the fly (fp64 constants [5][l1+1]).
 int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
-                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, hipStream_t st);
+                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
+                           hipStream_t st);
 
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);

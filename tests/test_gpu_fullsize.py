@@ -55,7 +55,9 @@ def test_ffn_rescale_and_down_projection_full_size():
         mid = ctx.ct_wrap(mid_t.data_ptr(), d, L, 2.0 ** w.log_scale)
         ctx.mul_scalar_rescale(mid, w.kappa)
         assert mid.limbs == L - 1
-        out = ctx.ternary_matmul(None, mid, w.n_slots, d, W2, "zero")
+        out_t = torch.empty(m * 2 * (L - 1) * N, dtype=torch.int64, device="cuda")
+        out = ctx.ct_wrap(out_t.data_ptr(), m, L - 1, 1.0)
+        ctx.ternary_matmul(None, mid, w.n_slots, d, W2, "zero", out)
         torch.cuda.synchronize()
         assert out.limbs == L - 1 and out.n == m
 
@@ -100,10 +102,28 @@ def test_ffn_rescale_and_down_projection_full_size():
             terms = [(Ciphertext(resc[v, 0], resc[v, 1], 1.0), int(W2[v, i])) for v in nz]
             want = o_s.accumulate(terms, L - 1, 1.0).limbs()
             assert np.array_equal(got, want), "output %d" % i
+        # the same two steps as one call (rescale applied while the accumulate reads its operands): every output
+        # word must equal the two-step result
         out.free()
+        mid.free()
+        for v0 in range(0, d, 64):
+            v = torch.arange(v0, min(v0 + 64, d), dtype=torch.int64, device="cuda")[:, None]
+            mid_t[v0:v0 + v.shape[0]] = wl.synthetic_words(v, widx, bits)
+        torch.cuda.synchronize()
+        mid = ctx.ct_wrap(mid_t.data_ptr(), d, L, 2.0 ** w.log_scale)
+        out2_t = torch.empty_like(out_t)
+        out2 = ctx.ct_wrap(out2_t.data_ptr(), m, L - 1, 1.0)
+        ctx.rescale_ternary_matmul(mid, w.kappa, W2, out2)
+        torch.cuda.synchronize()
+        assert mid.limbs == L - 1 and abs(out2.scale / scale_out - 1) < 1e-12
+        assert torch.equal(out2_t, out_t), "fused rescale + matmul differs from the two-step result"
+        out2.free()
         mid.free()
     finally:
         ctx.close()
+        # hand the 180 GB of test tensors back to the device (the library allocates outside torch's pool)
+        mid_t = out_t = out2_t = widx = None
+        torch.cuda.empty_cache()
 
 
 def test_attention_projection_full_size():

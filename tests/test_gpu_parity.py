@@ -238,6 +238,40 @@ def test_mul_scalar_rescale_bit_exact_and_two_layer(small4):
         g_ct.free()
 
 
+def test_rescale_fused_into_second_layer_bit_exact(small4):
+    """Scalar-multiply + rescale applied while the second layer's accumulate reads its operands
+    (one call) against the oracle's two steps, on both accumulate paths and for a ragged operand count."""
+    p = small4
+    d, m = 37, 70
+    rng = np.random.default_rng(9)
+    W = wl.ternary_weights(rng, d, m)
+    X = rng.uniform(-1, 1, (p.n, d))
+    for limbs, kappa in ((p.pr.L, 2.0 ** -5), (3, -0.3)):
+        o_cts, _ = p.encrypt_both(X.T, limbs)
+        o_mid = [p.o.mul_scalar_rescale(c, kappa) for c in o_cts]
+        want = stack_cts(p.o.ternary_matmul(o_mid, p.n, d, W, "zero", {}))
+        for mode in (1, 2):
+            g_ct = p.ctx.ct_import(stack_cts(o_cts), o_cts[0].scale)
+            p.ctx.set_accumulate_mode(mode)
+            out = p.ctx.rescale_ternary_matmul(g_ct, kappa, W)
+            assert out.limbs == limbs - 1 and g_ct.limbs == limbs - 1
+            assert np.array_equal(out.export(), want), "accumulate mode %d, limbs %d" % (mode, limbs)
+            assert out.scale == o_mid[0].scale == g_ct.scale
+            if mode == 2:
+                dec = p.ctx.decrypt(p.g_sk, out)
+                assert np.abs(dec.T - (kappa * X) @ W.astype(np.float64)).max() < 1e-3
+            out.free()
+            g_ct.free()
+        p.ctx.set_accumulate_mode(0)
+    E = p.binding.EnsiError
+    one = p.ctx.ct_import(stack_cts(o_cts)[:, :, :1], 1.0)
+    dst = p.ctx.ct_alloc(m, 1)
+    with pytest.raises(E, match="code -3"):
+        p.ctx.rescale_ternary_matmul(one, 0.5, W, dst)  # no limb left to drop
+    dst.free()
+    one.free()
+
+
 def test_error_paths(tiny):
     E = tiny.binding.EnsiError
     z = np.zeros((1, tiny.n))
