@@ -924,6 +924,12 @@ extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, 
         desc[c].g = g;
         desc[c].g_inv = inv_mod_2n(g, N);
     }
+    // inside a group, rotations that use the same key are made neighbours: the blocks reading a key tile then run
+    // at nearly the same time on one XCD and share it through L2 (a descriptor carries its own source and
+    // destination, so the order inside a launch is free)
+    for (int c0 = 0; c0 < n; c0 += chunk)
+        std::stable_sort(desc.begin() + c0, desc.begin() + std::min(n, c0 + chunk),
+                         [](const RotDesc &a, const RotDesc &b) { return (uintptr_t)a.key < (uintptr_t)b.key; });
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), n * sizeof(RotDesc), hipMemcpyHostToDevice, st));
     for (int c0 = 0; c0 < n; c0 += chunk) {
         const int cnt = std::min(chunk, n - c0);
