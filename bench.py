@@ -158,7 +158,7 @@ def kernel_profile(runner):
 # HBM-side bytes per launch of a workload's dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised under profiles/ (counter x calibration factor, averaged over the launches of one step).
 MEASURED_TRAFFIC = {
-    ("ffn2560", "accumulate_mfma"): (837.0 + 145.5) * 2.0 ** 30 / 9,
+    ("ffn2560", "accumulate_mfma"): (842.7 + 145.5) * 2.0 ** 30 / 9,
 }
 
 
