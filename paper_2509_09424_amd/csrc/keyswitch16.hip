@@ -177,7 +177,7 @@ struct LimbList {
 };
 
 template <bool FP>
-__global__ __launch_bounds__(KS_THREADS, 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
+__global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
                                                                  u64 *u, LimbList limbs) {
     __shared__ u64 lds[(FP ? 1 : 2) * (4096 + 256)];
     const int tid = threadIdx.x, rho = tid >> 4, j16 = tid & 15;
