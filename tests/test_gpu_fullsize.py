@@ -126,11 +126,12 @@ def test_ffn_rescale_and_down_projection_full_size():
         torch.cuda.empty_cache()
 
 
-def test_attention_projection_full_size():
-    """Attention-projection workload (128 tokens, 2560 x 2560, diagonal placement, 10 packed
-    inputs, 255 Galois keys): unpack rotations against the oracle on sampled outputs, then
-    the workload's own weights."""
-    w = wl.BY_NAME["attn2560"]
+@pytest.mark.parametrize("name", ["attn2560", "paper1536"])
+def test_projection_full_size(name):
+    """Projection workloads at full size -- attention projection (128 tokens, 2560 x 2560, 10 packed inputs,
+    255 Galois keys) and the paper's QKV shape (2048 tokens, 1536 x 1536, 96 packed inputs, 15 keys), diagonal
+    placement: unpack rotations against the oracle on sampled outputs, then the workload's own weights."""
+    w = wl.BY_NAME[name]
     p = Pair(w.param_tuple())
     try:
         rng = wl.rng_for(w.index)

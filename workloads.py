@@ -62,6 +62,9 @@ WORKLOADS = [
     Workload("ffn2560", 4, 16, 50, 16, 60, 4, 4, 40, tokens=128, d_in=2560, d_out=2560, d_mid=6912, placement="zero",
              act="normal", kappa=2.0 ** -5),
 ]
+# One of the paper's own PCMM shapes (Table III, QKV projection): 2048 tokens, 1536 x 1536 -- 16 columns per
+# ciphertext, 96 packed inputs, 15 rotation amounts.  Not a BASELINE configuration: a bench/test extra.
+WORKLOADS.append(Workload("paper1536", 5, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
