@@ -8,6 +8,10 @@ What is computed, and from where:
     (Homomorphic Encryption and RNS-CKKS; SIMD Encoding; Rotation);
   * the multiplication-free plaintext-ciphertext product: Alg. 1 (PCMM) and the
     worked toy example before it, which fixes the index order Y = X W;
+  * plaintext multiplication (Preliminaries, Multiplication) followed by one
+    rescale, the secure RoPE protocol (Alg. 2) built on it, and the mask-and-add
+    merge of block-placed outputs into densely packed ciphertexts (not in the
+    paper: it closes the loop of the packed reading of Alg. 1);
   * everything the paper leaves to its CKKS library (transform, hybrid key
     switching, rescale): the standard published definitions, in the order
     decompose -> ModUp -> automorphism -> key inner product -> ModDown.
@@ -150,17 +154,19 @@ class Oracle:
         return out
 
     # -------------------------------------------------------------- encoding
-    def encode_coeffs(self, z):
+    def encode_coeffs(self, z, scale=None):
         """pi: real slot vector (zero-padded to N/2) -> signed integer coefficients.
         m_k = round((2 Delta/N) Re sum_j z_j conj(zeta_j^k)), zeta_j = exp(i pi 5^j / N),
-        rounding half away from zero.  Evaluated with one length-2N FFT."""
+        rounding half away from zero.  Evaluated with one length-2N FFT.  Delta is the
+        parameter set's scale unless another one is given."""
         N = self.N
+        scale = self.pr.scale if scale is None else scale
         zz = np.zeros(self.n, dtype=np.float64)
         zz[: len(z)] = np.asarray(z, dtype=np.float64)
         A = np.zeros(2 * N, dtype=np.complex128)
         A[self.rot_exp] = zz
         A[2 * N - self.rot_exp] = zz  # conjugate positions (real input)
-        m = np.fft.fft(A)[:N].real * (self.pr.scale / N)
+        m = np.fft.fft(A)[:N].real * (scale / N)
         return (np.sign(m) * np.floor(np.abs(m) + 0.5)).astype(np.int64)
 
     def encode_coeffs_direct(self, z):
@@ -396,3 +402,103 @@ class Oracle:
             last = np.stack([np.where(neg, (top % np.uint64(m) + np.uint64(m - ql % m)) % np.uint64(m), top % np.uint64(m)) for m in rest])
             out.append(self.mul_scalar(self.sub(np.ascontiguousarray(c[: l1 - 1]), last, rest), ql_inv, rest))
         return Ciphertext(out[0], out[1], ct.scale * k / (kappa * ql))
+
+    # ---------------------------------------------- plaintext multiplication
+    def rescale(self, ct):
+        """Drops limb l: c'_i = (c_i - [c_l]) q_l^{-1} mod q_i, [c_l] the centred
+        representative of limb l in (-q_l/2, q_l/2], i.e. the exact integer quotient
+        round(c / q_l) of the centred coefficient; the scale is divided by q_l."""
+        pr = self.pr
+        l1 = ct.l1
+        ql = pr.q[l1 - 1]
+        rest = pr.q[: l1 - 1]
+        ql_inv = [pow(ql, -1, m) for m in rest]
+        out = []
+        for c in (ct.c0, ct.c1):
+            top = c[l1 - 1]
+            neg = top > np.uint64(ql // 2)
+            last = np.stack([np.where(neg, (top % np.uint64(m) + np.uint64(m - ql % m)) % np.uint64(m), top % np.uint64(m)) for m in rest])
+            out.append(self.mul_scalar(self.sub(np.ascontiguousarray(c[: l1 - 1]), last, rest), ql_inv, rest))
+        return Ciphertext(out[0], out[1], ct.scale / ql)
+
+    def pmult(self, ct, pt, pt_scale):
+        """PMult (Preliminaries, Multiplication): (c0 m, c1 m) in R_{Q_l}; pt is the
+        plaintext polynomial m as [l1][N] residues; the scales multiply.  No rescale."""
+        q = self.pr.q[: ct.l1]
+        return Ciphertext(self.polymul(ct.c0, pt, q), self.polymul(ct.c1, pt, q), ct.scale * pt_scale)
+
+    def add_ct(self, a, b):
+        """Add (Preliminaries): component-wise sum; both at the same level and scale."""
+        q = self.pr.q[: a.l1]
+        return Ciphertext(self.add(a.c0, b.c0, q), self.add(a.c1, b.c1, q), a.scale)
+
+    def pmult_sum_rescale(self, terms, pt_scale):
+        """Rescale(sum_t ct_t [x] pt_t): the products are added at the product scale and the
+        sum is rescaled once.  terms: list of (Ciphertext, pt residues [l1][N])."""
+        acc = None
+        for ct, pt in terms:
+            prod = self.pmult(ct, pt, pt_scale)
+            acc = prod if acc is None else self.add_ct(acc, prod)
+        return self.rescale(acc)
+
+    # -------------------------------------------------------- Alg. 2 (RoPE)
+    @staticmethod
+    def rope_masks(n):
+        """neg = (-1, 0, -1, 0, ...), pos = (0, 1, 0, 1, ...) over n slots (Alg. 2, first step)."""
+        j = np.arange(n)
+        return np.where(j % 2 == 0, -1.0, 0.0), np.where(j % 2 == 1, 1.0, 0.0)
+
+    def rope_plaintexts(self, cos, sin, l1):
+        """The three plaintext polynomials Alg. 2 multiplies by, as integer coefficients
+        [3][N] at scale q_l (the prime the rescale drops, so the ciphertext scale is
+        unchanged): cos, neg (.) sin and pos (.) sin.  The 0/+-1 masks are applied to the
+        sin vector in the clear: multiplying a ciphertext by a mask and then by sin would
+        cost two levels, and the paper's operation table gives RoPE one level."""
+        neg, pos = self.rope_masks(self.n)
+        ql = float(self.pr.q[l1 - 1])
+        c = np.zeros(self.n)
+        s = np.zeros(self.n)
+        c[: len(cos)] = cos
+        s[: len(sin)] = sin
+        return np.stack([self.encode_coeffs(v, ql) for v in (c, neg * s, pos * s)])
+
+    def rope(self, q_ct, pts, gk_plus, gk_minus):
+        """Alg. 2 on one ciphertext: r = Rot(q; 1) [x] neg, l = Rot(q; -1) [x] pos, t = r + l,
+        y = q [x] cos + t [x] sin, with the masks folded into sin (rope_plaintexts) so that
+        y = Rescale(q [x] cos + Rot(q; 1) [x] (neg sin) + Rot(q; -1) [x] (pos sin)).
+        pts: integer coefficients [3][N] from rope_plaintexts; gk_plus / gk_minus: Galois keys
+        of steps +1 and -1.  One ModUp serves both rotations."""
+        l1 = q_ct.l1
+        prm = self.pr.q[:l1]
+        ql = float(prm[-1])
+        rns = [self.i64_to_rns(p, prm) for p in pts]
+        digits = self.mod_up(q_ct.c1)
+        r = self.rotate_from_digits(q_ct.c0, digits, gk_plus, q_ct.scale)
+        l = self.rotate_from_digits(q_ct.c0, digits, gk_minus, q_ct.scale)
+        return self.pmult_sum_rescale([(q_ct, rns[0]), (r, rns[1]), (l, rns[2])], ql)
+
+    # ------------------------------------------- merge of placed outputs
+    def block_masks(self, s, c_tot, l1):
+        """Integer coefficients [c_tot][N] of the slot masks 1 on block b = slots [b s, (b+1) s),
+        0 elsewhere, at scale q_l."""
+        ql = float(self.pr.q[l1 - 1])
+        out = []
+        for b in range(c_tot):
+            z = np.zeros(self.n)
+            z[b * s:(b + 1) * s] = 1.0
+            out.append(self.encode_coeffs(z, ql))
+        return np.stack(out)
+
+    def merge(self, cts, masks, c_tot):
+        """Packs outputs placed by block (output i carries its column in block i mod c_tot)
+        into dense ciphertexts: packed_G = Rescale(sum_b y_{G c_tot + b} [x] mask_b).  masks:
+        integer coefficients from block_masks.  A ragged last group simply has fewer terms."""
+        l1 = cts[0].l1
+        prm = self.pr.q[:l1]
+        ql = float(prm[-1])
+        rns = [self.i64_to_rns(m, prm) for m in masks]
+        out = []
+        for g0 in range(0, len(cts), c_tot):
+            grp = cts[g0:g0 + c_tot]
+            out.append(self.pmult_sum_rescale([(ct, rns[b]) for b, ct in enumerate(grp)], ql))
+        return out

@@ -251,6 +251,120 @@ def _enc(o, rng, pk, z, l1):
     return o.encrypt(o.encode(z, l1), pk, wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), wl.error_poly(rng, o.N))
 
 
+def test_pure_rescale_is_exact_division(all_small):
+    """Rescale without a constant: the centred integer coefficient divided by q_l, rounded to nearest."""
+    pr = all_small[1]
+    o = Oracle(pr)
+    from oracle.ckks import Ciphertext
+    rng = np.random.default_rng(19)
+    l1 = pr.L - 1
+    q = pr.q[:l1]
+    c0 = np.stack([rng.integers(0, m, size=o.N, dtype=np.uint64) for m in q])
+    c1 = np.stack([rng.integers(0, m, size=o.N, dtype=np.uint64) for m in q])
+    c0[-1, :4] = [0, q[-1] // 2, q[-1] // 2 + 1, q[-1] - 1]  # both sides of the centring threshold
+    out = o.rescale(Ciphertext(c0, c1, 3.0 * q[-1]))
+    ql = q[-1]
+    assert out.l1 == l1 - 1 and out.scale == 3.0
+    for idx in list(range(4)) + list(range(4, o.N, 37)):
+        for src, dst in ((c0, out.c0), (c1, out.c1)):
+            val, Q = crt([src[i, idx] for i in range(l1)], q)
+            val = val - Q if val > Q // 2 else val
+            exact = (2 * val + ql) // (2 * ql)  # round to nearest (q_l odd: no ties)
+            assert abs(exact * ql - val) <= ql // 2
+            assert [int(dst[i, idx]) for i in range(l1 - 1)] == [exact % m for m in q[:-1]]
+
+
+def test_pmult_against_schoolbook_and_slotwise_product():
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 6)
+    o = Oracle(pr)
+    rng = np.random.default_rng(23)
+    sk, pk = _keys(o, rng)
+    l1 = 4
+    q = pr.q[:l1]
+    ql = float(q[-1])
+    z = rng.uniform(-1, 1, o.n)
+    wv = rng.uniform(-2, 2, o.n)
+    ct = _enc(o, rng, pk, z, l1)
+    m = o.encode_coeffs(wv, ql)
+    # the encoding at another scale decodes back at that scale
+    assert np.abs(o.decode_coeffs(m.astype(np.float64), ql).real - wv).max() < 1e-9
+    pt = o.i64_to_rns(m, q)
+    prod = o.pmult(ct, pt, ql)
+    assert prod.scale == ct.scale * ql and prod.l1 == l1
+    # each component is the negacyclic product with the integer polynomial m (schoolbook, per prime)
+    for comp_in, comp_out in ((ct.c0, prod.c0), (ct.c1, prod.c1)):
+        for i, m_i in enumerate(q):
+            assert np.array_equal(comp_out[i], o.polymul_naive(comp_in[i], pt[i], m_i))
+    # and the slots multiply; the rescale brings the scale back and drops one limb
+    out = o.pmult_sum_rescale([(ct, pt)], ql)
+    assert out.l1 == l1 - 1 and abs(out.scale / ct.scale - 1) < 1e-12
+    assert np.abs(o.decrypt(out, sk) - z * wv).max() < 1e-3
+    # a sum of two products is rescaled once
+    z2 = rng.uniform(-1, 1, o.n)
+    w2 = rng.uniform(-2, 2, o.n)
+    ct2 = _enc(o, rng, pk, z2, l1)
+    pt2 = o.i64_to_rns(o.encode_coeffs(w2, ql), q)
+    out2 = o.pmult_sum_rescale([(ct, pt), (ct2, pt2)], ql)
+    assert np.abs(o.decrypt(out2, sk) - (z * wv + z2 * w2)).max() < 1e-3
+
+
+def test_rope_against_the_rotary_formula():
+    """Alg. 2 against the pairwise rotation of the positional-encoding equation written out on
+    cleartext: (x_{2k}, x_{2k+1}) -> (x_{2k} cos - x_{2k+1} sin, x_{2k+1} cos + x_{2k} sin)."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 8)
+    o = Oracle(pr)
+    rng = np.random.default_rng(29)
+    sk, pk = _keys(o, rng)
+    l1 = pr.L
+    x = rng.uniform(-1, 1, o.n)
+    theta = rng.uniform(0, 2 * np.pi, o.n // 2)
+    cos, sin = np.repeat(np.cos(theta), 2), np.repeat(np.sin(theta), 2)
+    # slot-dependent values that are not pairwise equal would also be handled; make one pair unequal
+    cos[0], cos[1], sin[0], sin[1] = 0.3, -0.7, 0.9, 0.2
+    want = np.empty_like(x)
+    want[0::2] = x[0::2] * cos[0::2] - x[1::2] * sin[0::2]
+    want[1::2] = x[1::2] * cos[1::2] + x[0::2] * sin[1::2]
+    ct = _enc(o, rng, pk, x, l1)
+    beta = pr.beta(pr.L)
+    gk_p = o.galois_keygen(sk, 1, wl.error_poly(rng, (beta, o.N)), 31)
+    gk_m = o.galois_keygen(sk, -1, wl.error_poly(rng, (beta, o.N)), 31)
+    pts = o.rope_plaintexts(cos, sin, l1)
+    y = o.rope(ct, pts, gk_p, gk_m)
+    assert y.l1 == l1 - 1 and abs(y.scale / ct.scale - 1) < 1e-12  # one level, scale kept
+    assert np.abs(o.decrypt(y, sk) - want).max() < 1e-3
+    neg, pos = Oracle.rope_masks(8)
+    assert neg.tolist() == [-1, 0, -1, 0, -1, 0, -1, 0] and pos.tolist() == [0, 1, 0, 1, 0, 1, 0, 1]
+
+
+def test_merge_packs_placed_outputs():
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 7)
+    o = Oracle(pr)
+    rng = np.random.default_rng(37)
+    sk, pk = _keys(o, rng)
+    l1 = 3
+    s, c_tot = 8, 8  # n = 64 slots
+    m = 19           # two full groups and a ragged one
+    Y = rng.uniform(-1, 1, (m, s))
+    cts = []
+    for i in range(m):
+        z = rng.uniform(-1, 1, o.n)  # other blocks hold unrelated values
+        b = i % c_tot
+        z[b * s:(b + 1) * s] = Y[i]
+        cts.append(_enc(o, rng, pk, z, l1))
+    masks = o.block_masks(s, c_tot, l1)
+    packed = o.merge(cts, masks, c_tot)
+    assert len(packed) == 3 and all(p.l1 == l1 - 1 for p in packed)
+    for G, p in enumerate(packed):
+        dec = o.decrypt(p, sk)
+        for b in range(c_tot):
+            i = G * c_tot + b
+            want = Y[i] if i < m else np.zeros(s)
+            assert np.abs(dec[b * s:(b + 1) * s] - want).max() < 1e-3
+
+
 @pytest.mark.parametrize("widx,log_n", [(0, 10), (1, 10), (3, 10)])
 def test_key_switch_noise_and_rotation(widx, log_n):
     w = wl.WORKLOADS[widx]
