@@ -102,6 +102,11 @@ void ensi_gk_free(ensi_gk *gk);
  * round-half-away((2 Delta/N) sum_j z_j cos(pi 5^j k / N)).  `limbs` = number
  * of active Q limbs (level + 1). */
 int ensi_encode(ensi_ctx *ctx, const double *slots, int32_t n_pt, int32_t n_slots, int32_t limbs, ensi_pt **pt);
+/* The same encoding at another scale (1 <= scale < 2^63 / max|slot|), e.g. the prime a following rescale
+ * drops, so that multiplying by the plaintext and rescaling leaves a ciphertext's scale unchanged. */
+int ensi_encode_at(ensi_ctx *ctx, const double *slots, int32_t n_pt, int32_t n_slots, int32_t limbs, double scale, ensi_pt **pt);
+/* Sets the scale a plaintext batch is taken to be encoded at (imported coefficients start at the context's). */
+int ensi_pt_set_scale(ensi_pt *pt, double scale);
 /* coeffs: host int64[n_pt][N] signed integer coefficients (already encoded). */
 int ensi_pt_import(ensi_ctx *ctx, const int64_t *coeffs, int32_t n_pt, int32_t limbs, ensi_pt **pt);
 /* coeffs: host int64[n_pt][N], centred representative of limb 0 (exact only while |m| < q_0/2). */
@@ -179,6 +184,44 @@ int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stre
  * `in` is consumed: its handle takes the level and scale of the rescaled batch, its words are unspecified
  * afterwards (rescaled in place or left as they were). */
 int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out, void *stream);
+
+/* ---- PMult (Preliminaries, Multiplication) summed and rescaled once ------ */
+/* out_o = Rescale( sum_{t in [begin[o], begin[o+1])} in[term_ct[t]] (x) pt[term_pt[t]] ),  o = 0..n_out-1.
+ * A product multiplies both ciphertext polynomials by the plaintext polynomial in R_{Q_l}; the products of one
+ * output are added at the product scale and limb l is dropped once: c_i <- (c_i - [c_l]) q_l^{-1} mod q_i with
+ * [c_l] the centred representative.  begin: host int32[n_out+1], begin[0] = 0, non-decreasing; term_ct, term_pt:
+ * host int32[begin[n_out]], indices into the batches `in` and `pt` (pt needs at least in's limbs; an output
+ * without terms is the zero ciphertext).  out: batch of n_out ciphertexts with one limb less than `in`, must not
+ * overlap `in`; its scale becomes in.scale * pt.scale / q_l.  The plaintext batch is transformed on its first
+ * use and keeps that form until freed. */
+int ensi_pmult_sum_rescale(ensi_ctx *ctx, const ensi_ct *in, const ensi_pt *pt, const int32_t *begin, const int32_t *term_ct,
+                           const int32_t *term_pt, int32_t n_out, ensi_ct *out, void *stream);
+/* Selects the kernels of the plaintext multiplication: 0 = automatic (the fused N = 2^16 kernels whenever the
+ * ring is 2^16 and every ciphertext prime is below 2^50, else the generic ones), 1 = always the generic
+ * kernels.  Both give identical residues. */
+int ensi_set_pmult_mode(ensi_ctx *ctx, int32_t mode);
+
+/* ---- merge of block-placed outputs into packed ciphertexts --------------- */
+/* Not in the paper: with several activation columns per ciphertext (c_tot = (N/2)/s), Alg. 1 leaves output
+ * column i in slot block i mod c_tot of its own ciphertext (ENSI_PLACE_DIAGONAL); masking each output to its
+ * block and adding c_tot of them gives the packed form the next layer reads:
+ *   out_G = Rescale( sum_{b < c_tot} in[G c_tot + b] (x) mask_b ),  G = 0..ceil(in.n / c_tot)-1,
+ * mask_b = 1 on slots [b s, (b+1) s), 0 elsewhere.  ensi_block_masks encodes the c_tot masks at `limbs` limbs and
+ * scale q_{limbs-1} (the prime the rescale drops: the ciphertext scale is unchanged). */
+int ensi_block_masks(ensi_ctx *ctx, int32_t s, int32_t c_tot, int32_t limbs, ensi_pt **pt);
+int ensi_merge(ensi_ctx *ctx, const ensi_ct *in, const ensi_pt *masks, int32_t c_tot, ensi_ct *out, void *stream);
+
+/* ---- Alg. 2 (secure RoPE) ----------------------------------------------- */
+/* out_i = in_i (x) cos + (Rot(in_i; 1) (x) neg + Rot(in_i; -1) (x) pos) (x) sin with neg = (-1,0,-1,0,...),
+ * pos = (0,1,0,1,...): slot 2k becomes x_2k cos_2k - x_2k+1 sin_2k, slot 2k+1 becomes x_2k+1 cos_2k+1 +
+ * x_2k sin_2k+1.  The 0/+-1 masks are applied to the sin vector in the clear, so the protocol costs the one
+ * level the paper's operation table gives it: ensi_rope_plaintexts encodes cos, neg (.) sin and pos (.) sin
+ * (host double[n_slots] each) at `limbs` limbs and scale q_{limbs-1}, and ensi_rope evaluates
+ *   out_i = Rescale( in_i (x) pt_0 + Rot(in_i; 1) (x) pt_1 + Rot(in_i; -1) (x) pt_2 )
+ * with one ModUp per input shared by its two rotations.  gk must hold keys for steps +1 and -1.  out: batch of
+ * in.n ciphertexts with one limb less than `in`, must not overlap it. */
+int ensi_rope_plaintexts(ensi_ctx *ctx, const double *cos_v, const double *sin_v, int32_t n_slots, int32_t limbs, ensi_pt **pt);
+int ensi_rope(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const ensi_pt *pt, ensi_ct *out, void *stream);
 
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host

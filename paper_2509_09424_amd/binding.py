@@ -21,7 +21,8 @@ EXPORTED = [
     "ensi_pk_free", "ensi_galois_keygen", "ensi_gk_free", "ensi_encode", "ensi_pt_import", "ensi_pt_export",
     "ensi_pt_free", "ensi_ct_alloc", "ensi_ct_wrap", "ensi_ct_free", "ensi_ct_info", "ensi_ct_export",
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
-    "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
+    "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -126,6 +127,16 @@ class Context:
         self._check(self.lib.ensi_pt_import(self.h, _ptr(coeffs), coeffs.shape[0], limbs, ctypes.byref(pt)))
         return _Handle(self, pt, "ensi_pt_free", n=coeffs.shape[0])
 
+    def encode_at(self, slots, limbs, scale):
+        slots = np.ascontiguousarray(np.atleast_2d(slots), dtype=np.float64)
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_encode_at(self.h, _ptr(slots), slots.shape[0], slots.shape[1], limbs, ctypes.c_double(scale), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=slots.shape[0])
+
+    def pt_set_scale(self, pt, scale):
+        self._check(self.lib.ensi_pt_set_scale(pt.h, ctypes.c_double(scale)))
+        return pt
+
     def pt_export(self, pt):
         out = np.empty((pt.n, self.N), dtype=np.int64)
         self._check(self.lib.ensi_pt_export(self.h, pt.h, _ptr(out)))
@@ -200,6 +211,48 @@ class Context:
         if ct_out is None:
             ct_out = self.ct_alloc(m, ct_in.limbs - 1)
         self._check(self.lib.ensi_rescale_ternary_matmul(self.h, ct_in.h, ctypes.c_double(kappa), _ptr(W), m, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def pmult_sum_rescale(self, ct_in, pt, begin, term_ct, term_pt, ct_out=None, stream=0):
+        begin = np.ascontiguousarray(begin, dtype=np.int32)
+        term_ct = np.ascontiguousarray(term_ct, dtype=np.int32)
+        term_pt = np.ascontiguousarray(term_pt, dtype=np.int32)
+        n_out = len(begin) - 1
+        if n_out < 1 or len(term_ct) != begin[-1] or len(term_pt) != begin[-1]:
+            raise EnsiError("begin must hold n_out + 1 offsets and end at the number of terms")
+        if ct_out is None:
+            ct_out = self.ct_alloc(n_out, ct_in.limbs - 1)
+        self._check(self.lib.ensi_pmult_sum_rescale(self.h, ct_in.h, pt.h, _ptr(begin), _ptr(term_ct), _ptr(term_pt), n_out, ct_out.h,
+                                                    ctypes.c_void_p(stream)))
+        return ct_out
+
+    def set_pmult_mode(self, mode):
+        self._check(self.lib.ensi_set_pmult_mode(self.h, int(mode)))
+
+    def block_masks(self, s, c_tot, limbs):
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_block_masks(self.h, int(s), int(c_tot), int(limbs), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=c_tot)
+
+    def merge(self, ct_in, masks, c_tot, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(-(-ct_in.n // c_tot), ct_in.limbs - 1)
+        self._check(self.lib.ensi_merge(self.h, ct_in.h, masks.h, int(c_tot), ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def rope_plaintexts(self, cos, sin, limbs):
+        cos = np.ascontiguousarray(cos, dtype=np.float64)
+        sin = np.ascontiguousarray(sin, dtype=np.float64)
+        if cos.ndim != 1 or cos.shape != sin.shape:
+            raise EnsiError("cos and sin must be vectors of equal length")
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_rope_plaintexts(self.h, _ptr(cos), _ptr(sin), len(cos), int(limbs), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=3)
+
+    def rope(self, gk, ct_in, pt, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(ct_in.n, ct_in.limbs - 1)
+        self._check(self.lib.ensi_rope(self.h, gk.h, ct_in.h, pt.h, ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

@@ -64,6 +64,31 @@ struct Ks16Const {
     const double *down_q;      // [l1][2 + 4K]       N^{-1} P^{-1} mod q_i, /q_i; per k: p_k^{-1}, /q_i, 2^30 p_k^{-1}, /q_i
 };
 
+// One product of a plaintext multiplication: source ciphertext ([2][limb_stride][N] words) and plaintext index.
+struct PmTerm {
+    const u64 *src;
+    int32_t pt;
+    int32_t pad;
+};
+// q_l^{-1} mod q_i and that divided by q_i, for the rescale that ends the fused plaintext multiplication
+struct PmRescale {
+    double w[ENSI_MAX_EXT], wp[ENSI_MAX_EXT];
+};
+// One group of outputs of out_o = Rescale(sum_t src_t (x) pt_t): outputs [0, n_out) of this group own the terms
+// [begin[o], begin[o+1]) with begin[0] = t_base; every array is device memory.
+struct PmGroup {
+    const PmTerm *terms;    // whole table
+    const int32_t *begin;   // this group's slice of the offsets: n_out + 1 entries
+    int t_base, n_terms, n_out;
+    int l1, limb_stride_in;
+    const u64 *pt;          // d_mont or d_fp of the plaintext batch
+    int pt_limbs;
+    u64 *ws_a, *ws_b, *ws_last;
+    u64 *out;               // first output ciphertext of the group
+    size_t out_stride;      // words between output ciphertexts
+    int limb_stride_out;
+};
+
 // One rotation to perform: everything the fused kernels need, device-resident.
 struct RotDesc {
     const u64 *c0;      // source polynomial c0: [limb_stride_in][N]
@@ -117,8 +142,14 @@ struct ensi_ctx {
     u64 *ws_virt = nullptr; size_t ws_virt_words = 0;   // unpacked (rotated) operands of the matmul
     u64 *ws_plan = nullptr; size_t ws_plan_words = 0;   // operand pointer table, small constants
     u64 *ws_xp = nullptr; size_t ws_xp_words = 0;       // byte planes of the accumulate's operands (one slice of the words)
+    u64 *ws_pa = nullptr; size_t ws_pa_words = 0;       // plaintext multiplication: transformed sources of a group of outputs
+    u64 *ws_pb = nullptr; size_t ws_pb_words = 0;       //   sums of products of the group
+    u64 *ws_pl = nullptr; size_t ws_pl_words = 0;       //   centred last limbs of the group
+    u64 *ws_pt = nullptr; size_t ws_pt_words = 0;       //   term table and offsets
+    u64 *ws_rot = nullptr; size_t ws_rot_words = 0;     // rotated copies of the inputs of Alg. 2
     std::vector<MatmulPlan *> plans;                    // cached per weight matrix (weights are static server-side)
     int accumulate_mode = 0;                            // 0 auto, 1 plain-ALU kernel, 2 matrix-core kernel where valid
+    int pmult_mode = 0;                                 // 0 auto, 1 always the generic kernels
     // sampler state for NULL randomness
     u64 sampler_ctr = 0;
     // timers
@@ -144,7 +175,11 @@ struct ensi_gk {
 struct ensi_pt {
     ensi_ctx *ctx;
     int n, limbs;
+    double scale;
     u64 *d;  // [n][limbs][N] coefficient form
+    // multiplier forms, built on first use by a plaintext multiplication
+    mutable u64 *d_mont = nullptr;  // transform domain, Montgomery form
+    mutable u64 *d_fp = nullptr;    // transform domain, doubles in [0,q), register order of the row pass (N = 2^16)
 };
 struct ensi_ct {
     ensi_ctx *ctx;
@@ -217,6 +252,12 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
                            int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
                            hipStream_t st);
 
+// plaintext multiplication (pmult.hip).  The generic pair works for every ring size and prime; the fused one needs
+// N = 2^16 and ciphertext primes below 2^50.
+void launch_pm_generic(ensi_ctx *ctx, const PmGroup &g, const u64 *d_consts, const double *d_fconsts, hipStream_t st);
+void launch_pm16(ensi_ctx *ctx, const PmGroup &g, const PmRescale &rs, hipStream_t st);
+void launch_pm16_pt_format(ensi_ctx *ctx, const u64 *ntt_form, int n_rows, u64 *out, hipStream_t st);
+
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_uniform(ensi_ctx *ctx, u64 *out, const LimbMap &map, u64 seed, u64 stream_id, hipStream_t st);
@@ -229,7 +270,9 @@ void launch_to_mont(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, hi
 void launch_key_assemble(ensi_ctx *ctx, u64 *b_out, const u64 *a, const u64 *s_mont, const u64 *e, const u64 *sg,
                          const u64 *d_factor, const LimbMap &map, hipStream_t st);
 void launch_automorphism_coef(ensi_ctx *ctx, u64 *out, const u64 *in, const LimbMap &map, u32 g_inv, hipStream_t st);
-void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int64_t *d_coeffs, hipStream_t st);
+// plaintext y of the batch holds its n_slots values in slots [slot0 + y*slot_step, ...+n_slots), zeros elsewhere
+void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale, int64_t *d_coeffs,
+                   hipStream_t st);
 void launch_crt_center(ensi_ctx *ctx, const u64 *m, int n_ct, int n_limbs_used, double *out, hipStream_t st);
 void launch_center_i64(ensi_ctx *ctx, const u64 *m, size_t stride_words, int n, int64_t *out, hipStream_t st);
 void launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale,

@@ -456,25 +456,28 @@ void launch_automorphism_coef(ensi_ctx *ctx, u64 *out, const u64 *in, const Limb
 // ---------------------------------------------------------------- encode / decode
 // Column-wise SIMD encoding pi (paper, Preliminaries): the defining sum, in fp64.
 // coefficient k = round_half_away((2*scale/N) * sum_j z_j cos(pi * 5^j * k / N)).
-__global__ __launch_bounds__(EW_THREADS) void k_encode(const double *slots, int n_slots, const double *cos_tab, const u32 *rot_exp,
-                                                       int N, double factor, int64_t *coeffs) {
+// Plaintext y holds its n_slots values in slots [slot0 + y*slot_step, ... + n_slots); all other slots are zero.
+__global__ __launch_bounds__(EW_THREADS) void k_encode(const double *slots, int n_slots, int slot0, int slot_step, const double *cos_tab,
+                                                       const u32 *rot_exp, int N, double factor, int64_t *coeffs) {
     const int k = blockIdx.x * EW_THREADS + threadIdx.x;
     if (k >= N) return;
     const double *z = slots + (size_t)blockIdx.y * n_slots;
+    const u32 *re = rot_exp + slot0 + (size_t)blockIdx.y * slot_step;
     const u32 mask = 2 * (u32)N - 1;
     double acc = 0.0;
     for (int j = 0; j < n_slots; j++) {
-        const u32 e = (u32)(((u64)rot_exp[j] * (u32)k) & mask);
+        const u32 e = (u32)(((u64)re[j] * (u32)k) & mask);
         acc += z[j] * cos_tab[e];
     }
     const double m = acc * factor;
     const double r = floor(fabs(m) + 0.5);
     coeffs[(size_t)blockIdx.y * N + k] = (int64_t)(m < 0 ? -r : r);
 }
-void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int64_t *d_coeffs, hipStream_t st) {
+void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale, int64_t *d_coeffs,
+                   hipStream_t st) {
     dim3 grid((ctx->N + EW_THREADS - 1) / EW_THREADS, n_pt);
-    hipLaunchKernelGGL(k_encode, grid, dim3(EW_THREADS), 0, st, d_slots, n_slots, ctx->d_cos, ctx->d_rot_exp, ctx->N,
-                       2.0 * ctx->scale / ctx->N, d_coeffs);
+    hipLaunchKernelGGL(k_encode, grid, dim3(EW_THREADS), 0, st, d_slots, n_slots, slot0, slot_step, ctx->d_cos, ctx->d_rot_exp, ctx->N,
+                       2.0 * scale / ctx->N, d_coeffs);
 }
 
 // Garner CRT of limbs 0 and 1 (rows 0,1 of each [n_used][N] block), centred, as double.
