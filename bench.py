@@ -64,6 +64,42 @@ class Runner:
             self.ct_out = self.ctx.ct_alloc(w.batch, self.L)
             self.X = X
             return
+        if w.op == "rope":
+            # Alg. 2 on the packed query ciphertexts: one angle per slot pair
+            n_ct = -(-w.d_in // w.c_tot)
+            self.X = rng.uniform(-1.0, 1.0, size=(n_ct, self.n))
+            theta = rng.uniform(0.0, 2.0 * np.pi, self.n // 2)
+            self.cos, self.sin = np.repeat(np.cos(theta), 2), np.repeat(np.sin(theta), 2)
+            pt = self.ctx.encode(self.X, self.L)
+            self.ct_in = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            self.gk = self.ctx.galois_keygen(self.sk, [1, -1], None, 13)
+            self.pt = self.ctx.rope_plaintexts(self.cos, self.sin, self.L)
+            self.ct_out = self.ctx.ct_alloc(n_ct, self.L - 1)
+            return
+        if w.op == "merge":
+            # d_in block-placed outputs: one group of c_tot encrypted columns, repeated for every packed output
+            import torch
+            c_tot, s = w.c_tot, w.tokens
+            self.Y = rng.uniform(-1.0, 1.0, size=(c_tot, s))
+            z = rng.uniform(-1.0, 1.0, size=(c_tot, self.n))  # the other blocks hold unrelated values
+            for b in range(c_tot):
+                z[b, b * s:(b + 1) * s] = self.Y[b]
+            pt = self.ctx.encode(z, self.L)
+            grp = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            words = 2 * self.L * self.N
+            self.buf = torch.empty((w.d_in, words), dtype=torch.int64, device="cuda")
+            scale = grp.scale
+            host = torch.from_numpy(grp.export().view(np.int64).reshape(c_tot, words)).cuda()
+            for g0 in range(0, w.d_in, c_tot):
+                self.buf[g0:g0 + c_tot] = host[: min(c_tot, w.d_in - g0)]
+            torch.cuda.synchronize()
+            grp.free()
+            self.ct_in = self.ctx.ct_wrap(self.buf.data_ptr(), w.d_in, self.L, scale)
+            self.pt = self.ctx.block_masks(s, c_tot, self.L)
+            self.ct_out = self.ctx.ct_alloc(-(-w.d_in // c_tot), self.L - 1)
+            return
         self.W = wl.ternary_weights(rng, w.d_in, w.d_mid or w.d_out)
         self.X = wl.activations(rng, w.tokens, w.d_in, w.act)
         if w.d_mid:
@@ -87,6 +123,12 @@ class Runner:
         if w.name == "keyswitch":
             self.ctx.rotate(self.gk, self.ct_in, self.steps, self.ct_out)
             return
+        if w.op == "rope":
+            self.ctx.rope(self.gk, self.ct_in, self.pt, self.ct_out)
+            return
+        if w.op == "merge":
+            self.ctx.merge(self.ct_in, self.pt, w.c_tot, self.ct_out)
+            return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
@@ -109,6 +151,15 @@ class Runner:
             dec = self.ctx.decrypt(self.sk, self.ct_out)
             err = max(np.abs(dec[b] - np.roll(self.X[b], -self.steps[b])).max() for b in range(w.batch))
             return float(err)
+        if w.op == "rope":
+            x, c, s_ = self.X, self.cos, self.sin
+            ref = np.empty_like(x)
+            ref[:, 0::2] = x[:, 0::2] * c[0::2] - x[:, 1::2] * s_[0::2]
+            ref[:, 1::2] = x[:, 1::2] * c[1::2] + x[:, 0::2] * s_[1::2]
+            return float(np.abs(self.ctx.decrypt(self.sk, self.ct_out) - ref).max())
+        if w.op == "merge":
+            dec = self.ctx.decrypt(self.sk, self.ct_out)
+            return float(np.abs(dec - self.Y.reshape(1, -1)).max())
         ref = self.X @ self.W.astype(np.float64)
         out = self.ct_out
         if w.d_mid:
@@ -168,9 +219,18 @@ def roofline_for(w, prof):
     unit = 8.0 * N  # bytes of one limb
     ext = L + K
     beta = -(-L // alpha)
+    pm_terms = pm_out = 0
     if w.name == "keyswitch":
         n_rot, n_raise = w.batch, w.batch
         n_key = n_rot  # every rotation streams its key
+    elif w.op == "rope":
+        n_ct = -(-w.d_in // w.c_tot)
+        n_rot, n_raise = 2 * n_ct, n_ct
+        n_key = 2 * -(-n_ct // 32)  # inputs are rotated 32 at a time, a key is read once per group
+        pm_terms, pm_out = 3 * n_ct, n_ct
+    elif w.op == "merge":
+        n_rot = n_raise = n_key = 0
+        pm_terms, pm_out = w.d_in, -(-w.d_in // w.c_tot)
     else:
         n_in = -(-w.d_in // w.c_tot)
         n_rot, n_raise = w.d_in - n_in, n_in
@@ -195,6 +255,11 @@ def roofline_for(w, prof):
         # plane split: 8 bytes read + planes bytes written per operand word (units of 8 bytes per word: /N below)
         "byte_planes": (w.d_in * 2 * L + (0 if "rescale_byte_planes" in prof else (w.d_mid or 0) * 2 * (L - 1))) * (8 + 7) / 8.0,
         "rescale_byte_planes": (w.d_mid or 0) * (2 * L + 2 * (L - 1) * 7 / 8.0),
+        # plaintext multiplication, summed and rescaled (the few plaintext limbs are not counted)
+        "pm_fcols": pm_terms * 4 * L,                      # source limbs in, column-transformed limbs out
+        "pm_frows_mac_irows": (pm_terms + pm_out) * 2 * L,  # those in, one sum per output limb out
+        "pm_icols_last": pm_out * 4,
+        "pm_icols_rescale": pm_out * (2 * (L - 1) + 2 + 2 * (L - 1)),
     }
     members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
     classes = list(hbm) + ["accumulate", "accumulate_mfma"]
@@ -251,7 +316,7 @@ def cpu_baseline(w, budget_s=12.0):
     sk, pk = o.keygen(wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), 3)
     z = rng.uniform(-1, 1, o.n)
     ct = o.encrypt(o.encode(z, pr.L), pk, wl.ternary_poly(rng, o.N), wl.error_poly(rng, o.N), wl.error_poly(rng, o.N))
-    step = w.tokens if w.tokens else 1
+    step = w.tokens if (w.tokens and w.op == "matmul") else 1
     gk = o.galois_keygen(sk, step, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 4)
     o._key_at_level(gk, pr.L)
     log("oracle set-up %.1f s" % (time.time() - t_setup))
@@ -272,6 +337,22 @@ def cpu_baseline(w, budget_s=12.0):
         per = t_modup + t_rot
         return {"value": 1.0 / per, "unit": "rotations/s", "cores": cores, "kind": "oracle",
                 "sample": "%d ModUps (%.3f s each) + %d key switches (%.3f s each) at the workload's parameters" % (n1, t_modup, n2, t_rot)}
+    if w.op == "rope":
+        n_ct = -(-w.d_in // w.c_tot)
+        gk_m = o.galois_keygen(sk, -1, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 4)
+        o._key_at_level(gk_m, pr.L)
+        theta = rng.uniform(0, 2 * np.pi, o.n // 2)
+        pts = o.rope_plaintexts(np.repeat(np.cos(theta), 2), np.repeat(np.sin(theta), 2), pr.L)
+        _, t_one, n1 = repeat(lambda: o.rope(ct, pts, gk, gk_m), budget_s)
+        return {"value": n_ct * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
+                "sample": "%d ciphertexts through Alg. 2 (%.3f s each), extrapolated linearly to %d" % (n1, t_one, n_ct)}
+    if w.op == "merge":
+        masks = o.block_masks(w.tokens, 2, pr.L)
+        mask_rns = o.i64_to_rns(masks[0], pr.q)
+        _, t_one, n1 = repeat(lambda: o.pmult(ct, mask_rns, float(pr.q[-1])), budget_s)
+        return {"value": w.d_in * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
+                "sample": "%d plaintext multiplications (%.3f s each), extrapolated linearly to %d (additions and rescales left out)"
+                          % (n1, t_one, w.d_in)}
     digits, t_modup, n1 = repeat(lambda: o.mod_up(ct.c1), budget_s * 0.15)
     rot, t_rot, n2 = repeat(lambda: o.rotate_from_digits(ct.c0, digits, gk, ct.scale), budget_s * 0.45)
     n_terms = 256
@@ -335,7 +416,7 @@ def main():
     kernels = {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(prof.items())}
     line = {
         "metric": "encrypted ternary matmul ms/layer + key-switched rotations/sec at N=2^16",
-        "value": ms, "unit": "ms/layer" if w.name != "keyswitch" else "ms/batch",
+        "value": ms, "unit": "ms/layer" if (w.name != "keyswitch" and w.op == "matmul") else "ms/batch",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "log_n": w.log_n, "q_limbs": w.q_count, "p_limbs": w.p_count, "alpha": w.alpha,

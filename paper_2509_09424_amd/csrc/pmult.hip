@@ -27,6 +27,9 @@
 
 #define PM_THREADS 256
 #define PM_N 65536
+#ifndef PM_MAC_BLOCKS
+#define PM_MAC_BLOCKS 2
+#endif
 
 __device__ __forceinline__ double pm_f64(u64 x) { return __longlong_as_double((long long)x); }
 __device__ __forceinline__ u64 pm_u64(double x) { return (u64)__double_as_longlong(x); }
@@ -128,50 +131,97 @@ __global__ __launch_bounds__(PM_THREADS) void k_pm16_fcols(PmGroup g, const Prim
     for (int k = 0; k < 16; k++) out[(size_t)(16 * jj + k) * 256] = pm_u64(ar.mid(v[k]));
 }
 
-// grid (16, 2*l1, n_out)
-__global__ __launch_bounds__(PM_THREADS, 2) void k_pm16_frows_mac_irows(PmGroup g, const PrimeConst *pcs, const u64 *tw_all) {
+// Four Cooley-Tukey stages like ct4, with the 15 twiddles (value, companion) of the step read from a table in LDS:
+// entry (1 << k) - 1 + g serves stage k, butterfly group g.
+__device__ __forceinline__ void pm_ct4_tab(const ArithFp &ar, double *v, const ulonglong2 *tab) {
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int d = 8 >> k;
+#pragma unroll
+        for (int gq = 0; gq < (1 << k); gq++) {
+            const ulonglong2 w = tab[(1 << k) - 1 + gq];
+#pragma unroll
+            for (int o = 0; o < d; o++) {
+                const int i0 = gq * 2 * d + o;
+                ar.ct(v[i0], v[i0 + d], w.x, w.y);
+            }
+        }
+    }
+}
+
+// grid (16 * 2*l1 * n_out).  The operand of the next term is fetched while the current forward pass runs.  The
+// twiddles of a pass's first step depend on the row only and sit in LDS (the 16 threads of a row read the same
+// word); those of the second step differ per thread and stay in registers across all terms.
+__global__ __launch_bounds__(PM_THREADS, PM_MAC_BLOCKS) void k_pm16_frows_mac_irows(PmGroup g, const PrimeConst *pcs, const u64 *tw_all) {
     __shared__ u64 lds[4096 + 256];
+    __shared__ ulonglong2 tw1[16 * 16];
     const int tid = threadIdx.x, rho = tid >> 4, j = tid & 15;
-    const int y = blockIdx.y, i = y % g.l1, o = blockIdx.z;
-    const int r0 = blockIdx.x * 16;
+    // Workgroups are dealt to the eight XCDs in turn.  The two polynomials of an output tile multiply by the same
+    // plaintext tile, so their blocks are made consecutive on one XCD (ids n and n + 8) and the second read of
+    // the tile is served by that XCD's L2.
+    const u32 id = blockIdx.x, q = (id >> 4) * 8 + (id & 7);
+    const int cpoly = (id >> 3) & 1, tile = q & 15, i = (q >> 4) % g.l1, o = (q >> 4) / g.l1;
+    const int y = cpoly * g.l1 + i;
+    const int r0 = tile * 16;
     ArithFp ar;
     ar.init(pcs[i]);
     const u64 *twf = tw_all + (size_t)i * 4 * PM_N, *twi = twf + 2 * PM_N;
+    const u32 r = (u32)(r0 + rho);
+    if (j < 15) {
+        const int k = 31 - __clz(j + 1), gq = j + 1 - (1 << k);
+        const u32 idx = ((256u + r) << k) + gq;
+        tw1[rho * 16 + j] = make_ulonglong2(twf[idx], twf[PM_N + idx]);
+    }
+    const ulonglong2 *tab = tw1 + rho * 16;
     const int t0 = g.begin[o], t1 = g.begin[o + 1];
-    double acc[16];
+    double acc[16], nv[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) acc[k] = 0.0;
+    const size_t term = (size_t)2 * g.l1 * PM_N;  // words per term in ws_a
+    const size_t a_off = (size_t)y * PM_N + (size_t)r0 * 256 + rho * 256 + j;
+    const size_t b_off = (size_t)i * PM_N + (size_t)tile * 4096 + tid;
+    if (t0 < t1) {
+        const u64 *a = g.ws_a + (size_t)(t0 - g.t_base) * term + a_off;
+#pragma unroll
+        for (int k = 0; k < 16; k++) nv[k] = pm_f64(a[16 * k]);
+    }
+    double *l = (double *)lds;
+    __syncthreads();
 #pragma unroll 1
     for (int t = t0; t < t1; t++) {
-        const u64 *a = g.ws_a + ((size_t)(t - g.t_base) * 2 * g.l1 + y) * PM_N + (size_t)r0 * 256 + rho * 256 + j;
-        const u64 *b = g.pt + ((size_t)g.terms[t].pt * g.pt_limbs + i) * PM_N + (size_t)blockIdx.x * 4096 + tid;
-        double v[16];
+        const u64 *a = g.ws_a + (size_t)(t - g.t_base) * term + a_off;
+        const u64 *b = g.pt + (size_t)g.terms[t].pt * g.pt_limbs * PM_N + b_off;
+        double v[16], w[16];
 #pragma unroll
-        for (int k = 0; k < 16; k++) v[k] = pm_f64(a[16 * k]);
-        rows_fwd_regs(ar, v, twf, twf + PM_N, lds, rho, j, (u32)(r0 + rho));
-        // the plaintext is fetched eight values at a time after the pass, so that its registers are not live
-        // across the butterflies (the other block on the unit covers the latency)
-        __builtin_amdgcn_sched_barrier(0);
+        for (int k = 0; k < 16; k++) w[k] = pm_f64(b[256 * k]);
 #pragma unroll
-        for (int h = 0; h < 16; h += 8) {
-            double w[8];
+        for (int k = 0; k < 16; k++) v[k] = nv[k];
+        if (t + 1 < t1) {
 #pragma unroll
-            for (int k = 0; k < 8; k++) w[k] = pm_f64(b[256 * (h + k)]);
-#pragma unroll
-            for (int k = 0; k < 8; k++) acc[h + k] += ar.mulmod_np(ar.mid(v[h + k]), w[k]);
+            for (int k = 0; k < 16; k++) nv[k] = pm_f64(a[term + 16 * k]);
         }
+        // forward row pass (the steps of rows_fwd_regs)
+        pm_ct4_tab(ar, v, tab);
+#pragma unroll
+        for (int k = 0; k < 16; k++) l[rpad(rho * 256 + j + 16 * k)] = ar.mid(v[k]);
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 16; k++) v[k] = l[rpad(rho * 256 + 16 * j + k)];
+        ct4(ar, v, twf, twf + PM_N, (256u + r) * 16u + j);
+#pragma unroll
+        for (int k = 0; k < 16; k++) acc[k] += ar.mulmod_np(ar.mid(v[k]), w[k]);
         // a product is below 0.7 q in magnitude: eight of them stay exact in a double
         if (((t - t0) & 7) == 7) {
 #pragma unroll
             for (int k = 0; k < 16; k++) acc[k] = ar.mid(acc[k]);
         }
-        __syncthreads();  // the tile is reused by the next term's exchange
+        __syncthreads();  // the tile is reused by the next exchange
     }
     double v[16];
 #pragma unroll
     for (int k = 0; k < 16; k++) v[k] = ar.mid(acc[k]);
-    rows_inv_regs(ar, v, twi, twi + PM_N, lds, rho, j, (u32)(r0 + rho));
-    u64 *out = g.ws_b + ((size_t)o * 2 * g.l1 + y) * PM_N + (size_t)r0 * 256 + rho * 256 + j;
+    rows_inv_regs(ar, v, twi, twi + PM_N, lds, rho, j, r);
+    u64 *out = g.ws_b + (size_t)o * term + a_off;
 #pragma unroll
     for (int k = 0; k < 16; k++) out[16 * k] = pm_u64(ar.mid(v[k]));
 }
@@ -230,7 +280,7 @@ void launch_pm16(ensi_ctx *ctx, const PmGroup &g, const PmRescale &rs, hipStream
     }
     {
         ScopedTimer t(ctx, "pm_frows_mac_irows", st);
-        hipLaunchKernelGGL(k_pm16_frows_mac_irows, dim3(16, 2 * g.l1, g.n_out), dim3(PM_THREADS), 0, st, g, ctx->d_pc, ctx->d_tw);
+        hipLaunchKernelGGL(k_pm16_frows_mac_irows, dim3(16 * 2 * g.l1 * g.n_out), dim3(PM_THREADS), 0, st, g, ctx->d_pc, ctx->d_tw);
     }
     {
         ScopedTimer t(ctx, "pm_icols_last", st);

@@ -37,6 +37,7 @@ class Workload:
     act: str = "uniform"  # "uniform" [-1,1] or "normal" N(0,1) clipped to [-4,4]
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
+    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2) or "merge" (block merge of placed outputs)
 
     @property
     def N(self):
@@ -65,6 +66,11 @@ WORKLOADS = [
 # One of the paper's own PCMM shapes (Table III, QKV projection): 2048 tokens, 1536 x 1536 -- 16 columns per
 # ciphertext, 96 packed inputs, 15 rotation amounts.  Not a BASELINE configuration: a bench/test extra.
 WORKLOADS.append(Workload("paper1536", 5, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
+# The paper's RoPE shape (Table III: 2048 x 96 per head, 16 heads): the 1536 query columns of 2048 tokens, 16 per
+# ciphertext, i.e. 96 ciphertexts; and the merge of that projection's 1536 block-placed outputs into 96 packed
+# ciphertexts.  Bench/test extras like paper1536.
+WORKLOADS.append(Workload("rope1536", 6, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, act="uniform", op="rope"))
+WORKLOADS.append(Workload("merge1536", 7, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, act="uniform", op="merge"))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
