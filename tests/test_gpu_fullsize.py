@@ -195,3 +195,89 @@ def test_projection_full_size(name):
         g_gk.free()
     finally:
         p.close()
+
+
+def test_rope_full_size():
+    """Alg. 2 at the shape the benchmark times (rope1536: 96 packed ciphertexts at 16 limbs, three groups of the
+    batched rotation): a sample of the outputs against the oracle bit for bit, all of them after decryption."""
+    w = wl.BY_NAME["rope1536"]
+    p = Pair(w.param_tuple())
+    try:
+        L = p.pr.L
+        n_ct = -(-w.d_in // w.c_tot)
+        rng = wl.rng_for(w.index)
+        x = rng.uniform(-1.0, 1.0, size=(n_ct, p.n))
+        theta = rng.uniform(0.0, 2.0 * np.pi, p.n // 2)
+        cos, sin = np.repeat(np.cos(theta), 2), np.repeat(np.sin(theta), 2)
+        want = np.empty_like(x)
+        want[:, 0::2] = x[:, 0::2] * cos[0::2] - x[:, 1::2] * sin[0::2]
+        want[:, 1::2] = x[:, 1::2] * cos[1::2] + x[:, 0::2] * sin[1::2]
+        o_gks, g_gk = p.galois_keys([1, -1])
+        o_cts, g_ct = p.encrypt_both(x, L)
+        pts = p.o.rope_plaintexts(cos, sin, L)
+        g_pt = p.ctx.pt_set_scale(p.ctx.pt_import(pts, L), float(p.pr.q[L - 1]))
+        out = p.ctx.rope(g_gk, g_ct, g_pt)
+        assert out.n == n_ct and out.limbs == L - 1
+        n_o, limbs_o, scale_o, base_o = out._info()
+        ct_words = 2 * limbs_o * p.N
+        for i in (0, 31, 32, n_ct - 1):
+            one = p.ctx.ct_wrap(int(base_o) + 8 * ct_words * i, 1, limbs_o, scale_o)
+            got = one.export()[0]
+            one.free()
+            assert np.array_equal(got, p.o.rope(o_cts[i], pts, o_gks[1], o_gks[-1]).limbs()), "ciphertext %d" % i
+        assert np.abs(p.ctx.decrypt(p.g_sk, out) - want).max() < 1e-3
+        for h in (g_ct, g_pt, out, g_gk):
+            h.free()
+    finally:
+        p.close()
+
+
+def test_merge_full_size():
+    """The merge at the shape the benchmark times (merge1536: 1536 block-placed outputs at 16 limbs into 96 packed
+    ciphertexts, three groups of 32 outputs).  Inputs are synthetic residue words generated identically on the
+    device and on the host; a sample of packed outputs is compared with the oracle bit for bit."""
+    import torch
+    from paper_2509_09424_amd import binding
+    w = wl.BY_NAME["merge1536"]
+    ctx = binding.Context(*w.param_tuple(), seed=3)
+    N, L, m, c_tot, s = w.N, w.q_count, w.d_in, w.c_tot, w.tokens
+    words = 2 * L * N
+    bits = w.q_bits - 1
+    try:
+        in_t = torch.empty((m, words), dtype=torch.int64, device="cuda")
+        widx = torch.arange(words, dtype=torch.int64, device="cuda")[None, :]
+        for v0 in range(0, m, 64):
+            v = torch.arange(v0, min(v0 + 64, m), dtype=torch.int64, device="cuda")[:, None]
+            in_t[v0:v0 + v.shape[0]] = wl.synthetic_words(v, widx, bits)
+        torch.cuda.synchronize()
+        qs, ps = ctx.primes()
+        pr = Params(w.log_n, w.q_bits, L, w.p_bits, w.p_count, w.alpha, w.log_scale, q=qs, p=ps)
+        o = Oracle(pr)
+        masks = o.block_masks(s, c_tot, L)
+        ql = float(qs[L - 1])
+        g_masks = ctx.pt_set_scale(ctx.pt_import(masks, L), ql)
+        src = ctx.ct_wrap(in_t.data_ptr(), m, L, 2.0 ** w.log_scale)
+        out = ctx.merge(src, g_masks, c_tot)
+        torch.cuda.synchronize()
+        assert out.n == m // c_tot and out.limbs == L - 1 and abs(out.scale / 2.0 ** w.log_scale - 1) < 1e-12
+        n_o, limbs_o, scale_o, base_o = out._info()
+        ct_words = 2 * limbs_o * N
+        rns = [o.i64_to_rns(mk, pr.q[:L]) for mk in masks]
+        hidx = np.arange(words, dtype=np.uint64)
+        for G in (0, 31, 32, m // c_tot - 1):
+            terms = []
+            for b in range(c_tot):
+                with np.errstate(over="ignore"):
+                    x = wl.synthetic_words(np.uint64(G * c_tot + b), hidx, bits).reshape(2, L, N)
+                terms.append((Ciphertext(np.ascontiguousarray(x[0]), np.ascontiguousarray(x[1]), 1.0), rns[b]))
+            want = o.pmult_sum_rescale(terms, ql).limbs()
+            one = ctx.ct_wrap(int(base_o) + 8 * ct_words * G, 1, limbs_o, scale_o)
+            got = one.export()[0]
+            one.free()
+            assert np.array_equal(got, want), "packed output %d" % G
+        for h in (src, out, g_masks):
+            h.free()
+    finally:
+        ctx.close()
+        in_t = widx = None
+        torch.cuda.empty_cache()
