@@ -12,6 +12,10 @@ What is computed, and from where:
     rescale, the secure RoPE protocol (Alg. 2) built on it, and the mask-and-add
     merge of block-placed outputs into densely packed ciphertexts (not in the
     paper: it closes the loop of the packed reading of Alg. 1);
+  * ciphertext-ciphertext multiplication (Preliminaries, Multiplication: Mult)
+    with relinearisation by the evaluation key and one rescale, and the
+    ciphertext-ciphertext matrix product of the CCMM section built on it
+    (element extraction by a one-hot mask and doubling rotate-and-add steps);
   * everything the paper leaves to its CKKS library (transform, hybrid key
     switching, rescale): the standard published definitions, in the order
     decompose -> ModUp -> automorphism -> key inner product -> ModDown.
@@ -55,6 +59,7 @@ def _u64(x):
 
 
 GK_STREAM_TAG = 2 << 56
+RK_STREAM_TAG = 3 << 56
 PK_STREAM = 1
 
 
@@ -203,27 +208,45 @@ class Oracle:
         b = self.add(self.sub(np.zeros_like(a), self.polymul(a, s_rns, pr.q), pr.q), e_rns, pr.q)
         return sk, (b, a)
 
-    def galois_keygen(self, sk, step, e, seed):
-        """Key for Rot(.; step): for every digit j of the full chain,
-        (b_j, a_j) over Q_L * P with b_j = -a_j s + e_j + [P]_{q_i} phi_g(s) on the
-        limbs i of digit j only.  e: int8[beta][N]."""
+    def _switch_keygen(self, sk, target, e, seed, stream_base):
+        """Hybrid key-switching key from the secret `target` ([L+K][N] residues, coefficient form) to s:
+        for every digit j of the full chain, (b_j, a_j) over Q_L * P with b_j = -a_j s + e_j +
+        [P]_{q_i} target on the limbs i of digit j only.  e: int8[beta][N]."""
         pr = self.pr
-        g = pr.galois_element(step)
         ext = pr.q + pr.p
         ids = list(range(pr.L + pr.K))
         s_ext = self.small_to_rns(sk, ext)
-        s_g = self.automorphism(s_ext, g, ext)
         beta = pr.beta(pr.L)
         bs, as_ = [], []
         for j in range(beta):
-            a = self.uniform(seed, GK_STREAM_TAG | (g << 8) | j, ids, ext)
+            a = self.uniform(seed, stream_base | j, ids, ext)
             e_rns = self.small_to_rns(e[j], ext)
             b = self.add(self.sub(np.zeros_like(a), self.polymul(a, s_ext, ext), ext), e_rns, ext)
             factor = [(pr.P % ext[i]) if i in pr.digit_limbs(j, pr.L) else 0 for i in ids]
-            b = self.add(b, self.mul_scalar(s_g, factor, ext), ext)
+            b = self.add(b, self.mul_scalar(target, factor, ext), ext)
             bs.append(b)
             as_.append(a)
-        return {"g": g, "step": step, "b": np.stack(bs), "a": np.stack(as_), "ntt": {}}
+        return np.stack(bs), np.stack(as_)
+
+    def galois_keygen(self, sk, step, e, seed):
+        """Key for Rot(.; step): switches from phi_g(s) to s (g = 5^step); uniform streams
+        GK_STREAM_TAG | g << 8 | j."""
+        pr = self.pr
+        g = pr.galois_element(step)
+        ext = pr.q + pr.p
+        s_g = self.automorphism(self.small_to_rns(sk, ext), g, ext)
+        b, a = self._switch_keygen(sk, s_g, e, seed, GK_STREAM_TAG | (g << 8))
+        return {"g": g, "step": step, "b": b, "a": a, "ntt": {}}
+
+    def relin_keygen(self, sk, e, seed):
+        """Evaluation key of Mult (paper, Preliminaries: KeyGen, evk): switches from s^2 to s;
+        uniform streams RK_STREAM_TAG | j.  Used through the same inner product as a rotation
+        key with the identity automorphism (g = 1)."""
+        pr = self.pr
+        ext = pr.q + pr.p
+        s_ext = self.small_to_rns(sk, ext)
+        b, a = self._switch_keygen(sk, self.polymul(s_ext, s_ext, ext), e, seed, RK_STREAM_TAG)
+        return {"g": 1, "step": 0, "b": b, "a": a, "ntt": {}}
 
     # ------------------------------------------------------- encrypt/decrypt
     def encrypt(self, pt_rns, pk, v, e0, e1):
@@ -501,4 +524,73 @@ class Oracle:
         for g0 in range(0, len(cts), c_tot):
             grp = cts[g0:g0 + c_tot]
             out.append(self.pmult_sum_rescale([(ct, rns[b]) for b, ct in enumerate(grp)], ql))
+        return out
+
+    # ------------------------------------- ciphertext-ciphertext multiplication
+    def drop_limbs(self, ct, l1):
+        """Level alignment: the same ciphertext modulo Q_{l1} (its last limbs are dropped, the
+        scale is unchanged)."""
+        return Ciphertext(np.ascontiguousarray(ct.c0[:l1]), np.ascontiguousarray(ct.c1[:l1]), ct.scale)
+
+    def tensor_sum(self, pairs):
+        """sum_t a_t (x) b_t before relinearisation: (d0, d1, d2) = (sum a0 b0, sum a0 b1 + a1 b0,
+        sum a1 b1), which decrypts under (1, s, s^2)."""
+        l1 = pairs[0][0].l1
+        q = self.pr.q[:l1]
+        d = [np.zeros((l1, self.N), dtype=np.uint64) for _ in range(3)]
+        for a, b in pairs:
+            d[0] = self.add(d[0], self.polymul(a.c0, b.c0, q), q)
+            d[1] = self.add(d[1], self.add(self.polymul(a.c0, b.c1, q), self.polymul(a.c1, b.c0, q), q), q)
+            d[2] = self.add(d[2], self.polymul(a.c1, b.c1, q), q)
+        return d
+
+    def relinearize(self, d, rk, scale):
+        """(d0, d1, d2) -> (d0 + KS_0(d2), d1 + KS_1(d2)) with the evaluation key: the hybrid key
+        switch of the rotation (decompose, ModUp, inner product, ModDown) with g = 1."""
+        ks = self.rotate_from_digits(d[0], self.mod_up(d[2]), rk, scale)
+        q = self.pr.q[: d[0].shape[0]]
+        return Ciphertext(ks.c0, self.add(ks.c1, d[1], q), scale)
+
+    def mult_sum_relin_rescale(self, pairs, rk):
+        """Rescale(Relin(sum_t a_t (x) b_t)): Mult (paper, Preliminaries) on every pair, the
+        products added before the one relinearisation and the one rescale."""
+        a0, b0 = pairs[0]
+        return self.rescale(self.relinearize(self.tensor_sum(pairs), rk, a0.scale * b0.scale))
+
+    # ------------------------------------------------------------------ CCMM
+    def one_hot_masks(self, ks, l1):
+        """Integer coefficients [len(ks)][N] of the masks (0,..,0,1,0,..,0) with the 1 in slot k, at scale q_l."""
+        ql = float(self.pr.q[l1 - 1])
+        out = []
+        for k in ks:
+            z = np.zeros(self.n)
+            z[k] = 1.0
+            out.append(self.encode_coeffs(z, ql))
+        return np.stack(out)
+
+    def replicate(self, ct, mask, gks):
+        """The element-extraction step of the CCMM section: keep one slot (PMult by its mask, one
+        rescale), then copy it into every slot by log2(N/2) rotate-and-add steps with doubling
+        strides, t <- t + Rot(t; 2^r).  gks: dict 2^r -> Galois key.  The figure with the paper's own
+        schedule is not in the text; this is the doubling schedule that reaches the logarithmic
+        rotation count it states."""
+        l1 = ct.l1
+        ql = float(self.pr.q[l1 - 1])
+        t = self.pmult_sum_rescale([(ct, self.i64_to_rns(mask, self.pr.q[:l1]))], ql)
+        r = 1
+        while r < self.n:
+            t = self.add_ct(t, self.rotate(t, gks[r]))
+            r *= 2
+        return t
+
+    def ccmm(self, a_cts, b_cts, d, rk, gks):
+        """C = A B on ciphertexts (CCMM section): A column-encoded (a_j = column j, tokens along the
+        slots), b_i = column i of B with B[j, i] in slot j; c_i = sum_j a_j (x) b_i^(j), where
+        b_i^(j) is B[j, i] replicated into every slot.  Costs two levels (mask, product)."""
+        l1 = b_cts[0].l1
+        masks = self.one_hot_masks(range(d), l1)
+        out = []
+        for b in b_cts:
+            reps = [self.replicate(b, masks[j], gks) for j in range(d)]
+            out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a_cts[j], l1 - 1), reps[j]) for j in range(d)], rk))
         return out

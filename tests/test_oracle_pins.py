@@ -405,6 +405,86 @@ def test_rotate_at_lower_level():
     assert np.abs(o.decrypt(rot, sk) - np.roll(z, -3)).max() < 1e-3
 
 
+# ------------------------------------------- ciphertext x ciphertext, CCMM
+def test_relinearised_product_keeps_the_phase_and_multiplies_slots():
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 8)
+    o = Oracle(pr)
+    from oracle.ckks import Ciphertext
+    rng = np.random.default_rng(61)
+    sk, pk = _keys(o, rng)
+    l1 = 5  # partial second digit (alpha = 3)
+    za, zb, zc, zd = (rng.uniform(-1, 1, o.n) for _ in range(4))
+    a, b, c, d = (_enc(o, rng, pk, z, l1) for z in (za, zb, zc, zd))
+    rk = o.relin_keygen(sk, wl.error_poly(rng, (pr.beta(pr.L), o.N)), 17)
+    # the evaluation key is a key-switching key for s^2: b_j + a_j s - P s^2 is small on the limbs of digit j
+    ext = pr.q + pr.p
+    s_ext = o.small_to_rns(sk, ext)
+    s2 = o.polymul(s_ext, s_ext, ext)
+    for j in range(pr.beta(pr.L)):
+        lhs = o.add(rk["b"][j], o.polymul(rk["a"][j], s_ext, ext), ext)
+        for i in range(len(ext)):
+            want = (pr.P % ext[i]) if i in pr.digit_limbs(j, pr.L) else 0
+            diff = (lhs[i].astype(object) - want * s2[i].astype(object)) % ext[i]
+            diff = np.where(diff > ext[i] // 2, diff - ext[i], diff)
+            assert np.abs(diff).max() <= 19, (j, i)
+    # tensor product: decrypts under (1, s, s^2) to the product of the two phases (schoolbook check on limb 0)
+    q = pr.q[:l1]
+    dd = o.tensor_sum([(a, b)])
+    s_q = o.small_to_rns(sk, q)
+    pa = o.add(a.c0, o.polymul(a.c1, s_q, q), q)
+    pb = o.add(b.c0, o.polymul(b.c1, s_q, q), q)
+    s2q = o.polymul(s_q, s_q, q)
+    phase = o.add(o.add(dd[0], o.polymul(dd[1], s_q, q), q), o.polymul(dd[2], s2q, q), q)
+    assert np.array_equal(phase[0], o.polymul_naive(pa[0], pb[0], q[0]))
+    # relinearisation changes the phase by a small polynomial only
+    rl = o.relinearize(dd, rk, a.scale * b.scale)
+    ph2 = o.add(rl.c0, o.polymul(rl.c1, s_q, q), q)
+    diff = o.sub(ph2[:2], phase[:2], q[:2])
+    noise = o.decrypt_coeffs(Ciphertext(diff, np.zeros_like(diff), 1.0), np.zeros(o.N, dtype=np.int8))
+    assert np.abs(noise).max() < 2.0 ** 20  # against a product scale of 2^80
+    # Mult: slots multiply, one level, scale Delta^2 / q_l; a sum of two products is rescaled once
+    out = o.mult_sum_relin_rescale([(a, b)], rk)
+    assert out.l1 == l1 - 1 and abs(out.scale / (pr.scale ** 2 / q[-1]) - 1) < 1e-12
+    assert np.abs(o.decrypt(out, sk) - za * zb).max() < 1e-3
+    out2 = o.mult_sum_relin_rescale([(a, b), (c, d)], rk)
+    assert np.abs(o.decrypt(out2, sk) - (za * zb + zc * zd)).max() < 1e-3
+    # dropping limbs keeps the message
+    assert np.abs(o.decrypt(o.drop_limbs(a, 3), sk) - za).max() < 1e-3
+
+
+def test_replicate_and_ccmm_against_numpy():
+    """CCMM section: c_i = sum_j a_j (x) b_i^(j) equals the float64 product A B."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 5)  # 16 slots
+    o = Oracle(pr)
+    rng = np.random.default_rng(67)
+    sk, pk = _keys(o, rng)
+    l1 = 4
+    s_tok, d, m = o.n, 3, 2
+    A = rng.uniform(-1, 1, (s_tok, d))
+    B = rng.uniform(-1, 1, (d, m))
+    beta = pr.beta(pr.L)
+    gks = {}
+    r = 1
+    while r < o.n:
+        gks[r] = o.galois_keygen(sk, r, wl.error_poly(rng, (beta, o.N)), 71)
+        r *= 2
+    rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 73)
+    a_cts = [_enc(o, rng, pk, A[:, j], l1) for j in range(d)]
+    b_cts = []
+    for i in range(m):
+        z = rng.uniform(-1, 1, o.n)  # slots beyond d hold unrelated values
+        z[:d] = B[:, i]
+        b_cts.append(_enc(o, rng, pk, z, l1))
+    rep = o.replicate(b_cts[1], o.one_hot_masks([2], l1)[0], gks)
+    assert rep.l1 == l1 - 1 and np.abs(o.decrypt(rep, sk) - B[2, 1]).max() < 1e-3
+    C = o.ccmm(a_cts, b_cts, d, rk, gks)
+    assert len(C) == m and all(c.l1 == l1 - 2 for c in C)
+    for i in range(m):
+        assert np.abs(o.decrypt(C[i], sk) - (A @ B)[:, i]).max() < 1e-3
+
+
 # -------------------------------------------------------------------- PCMM
 def _read_toy():
     W, Y = [], {}
