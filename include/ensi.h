@@ -223,6 +223,38 @@ int ensi_merge(ensi_ctx *ctx, const ensi_ct *in, const ensi_pt *masks, int32_t c
 int ensi_rope_plaintexts(ensi_ctx *ctx, const double *cos_v, const double *sin_v, int32_t n_slots, int32_t limbs, ensi_pt **pt);
 int ensi_rope(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const ensi_pt *pt, ensi_ct *out, void *stream);
 
+/* ---- Mult (Preliminaries, Multiplication) and the CCMM section ---------- */
+/* Evaluation key (Preliminaries, KeyGen: evk): the hybrid key-switching key from s^2 to s, same digit structure as
+ * a Galois key; e: host int8[beta][N] or NULL; the uniform parts are the streams (3 << 56) | j of seed_a.  The
+ * returned key set holds only this key; free with ensi_gk_free. */
+int ensi_relin_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int8_t *e, uint64_t seed_a, ensi_gk **rk);
+/* Level alignment: the handle's ciphertexts are read modulo Q_{limbs} from now on (limbs <= current limbs; the
+ * scale and the words are unchanged). */
+int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs);
+/* out_o = Rescale( Relin( sum_{t in [begin[o], begin[o+1])} a[term_a[t]] (x) b[term_b[t]] ) ),  o = 0..n_out-1.
+ * A product is the tensor product (a0 b0, a0 b1 + a1 b0, a1 b1) in R_{Q_l}; the products of one output are added,
+ * the third polynomial is switched from s^2 to s with the evaluation key (decompose, ModUp, inner product,
+ * ModDown, as in ensi_rotate with the identity automorphism) and limb l is dropped once with rounding to nearest.
+ * a, b: batches at the same number of limbs; begin/term_a/term_b as in ensi_pmult_sum_rescale; out: n_out
+ * ciphertexts with one limb less, not overlapping a or b; out.scale = a.scale * b.scale / q_l. */
+int ensi_mult_sum_relin_rescale(ensi_ctx *ctx, const ensi_gk *rk, const ensi_ct *a, const ensi_ct *b, const int32_t *begin,
+                                const int32_t *term_a, const int32_t *term_b, int32_t n_out, ensi_ct *out, void *stream);
+/* Element extraction of the CCMM section: out_o holds, in every slot, the value that slot k_o of in[src[o]] held:
+ * one product with the one-hot mask masks[mask_idx[o]] (1 in slot k_o, else 0) and one rescale, then log2(N/2)
+ * steps t <- t + Rot(t; 2^r), r = 0, 1, ... (the figure with the paper's own schedule is not part of its text;
+ * this is the doubling schedule with the logarithmic rotation count it states).  gk must hold keys for the steps
+ * 2^r, r = 0..log2(N/2)-1.  ensi_one_hot_masks encodes the masks of slots 0..count-1 at `limbs` limbs and scale
+ * q_{limbs-1}.  src, mask_idx: host int32[n_out]; out: n_out ciphertexts with one limb less than `in`. */
+int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, ensi_pt **pt);
+int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
+                   const int32_t *mask_idx, int32_t n_out, ensi_ct *out, void *stream);
+/* C = A B on ciphertexts (CCMM section): A: d column ciphertexts (a_j = column j of A, tokens along the slots),
+ * B: m column ciphertexts (b_i holds B[j][i] in slot j, j < d), both at the same number of limbs l;
+ * c_i = Rescale(Relin(sum_j a_j (x) b_i^(j))) with b_i^(j) = B[j][i] replicated into every slot (ensi_replicate
+ * with masks[j]; a_j is read at the level of the replicated elements).  out: m ciphertexts with l - 2 limbs. */
+int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
+              ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

@@ -22,7 +22,8 @@ EXPORTED = [
     "ensi_pt_free", "ensi_ct_alloc", "ensi_ct_wrap", "ensi_ct_free", "ensi_ct_info", "ensi_ct_export",
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
-    "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_one_hot_masks", "ensi_replicate", "ensi_ccmm", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -111,6 +112,12 @@ class Context:
         gk = ctypes.c_void_p()
         self._check(self.lib.ensi_galois_keygen(self.h, sk.h, _ptr(steps), len(steps), _ptr(e), ctypes.c_uint64(seed_a), ctypes.byref(gk)))
         return _Handle(self, gk, "ensi_gk_free")
+
+    def relin_keygen(self, sk, e=None, seed_a=0):
+        e = _i8(e, (self.beta, self.N))
+        rk = ctypes.c_void_p()
+        self._check(self.lib.ensi_relin_keygen(self.h, sk.h, _ptr(e), ctypes.c_uint64(seed_a), ctypes.byref(rk)))
+        return _Handle(self, rk, "ensi_gk_free")
 
     # ---- plaintexts
     def encode(self, slots, limbs):
@@ -253,6 +260,45 @@ class Context:
         if ct_out is None:
             ct_out = self.ct_alloc(ct_in.n, ct_in.limbs - 1)
         self._check(self.lib.ensi_rope(self.h, gk.h, ct_in.h, pt.h, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def ct_drop_limbs(self, ct, limbs):
+        self._check(self.lib.ensi_ct_drop_limbs(ct.h, int(limbs)))
+        return ct
+
+    def mult_sum_relin_rescale(self, rk, ct_a, ct_b, begin, term_a, term_b, ct_out=None, stream=0):
+        begin = np.ascontiguousarray(begin, dtype=np.int32)
+        term_a = np.ascontiguousarray(term_a, dtype=np.int32)
+        term_b = np.ascontiguousarray(term_b, dtype=np.int32)
+        n_out = len(begin) - 1
+        if n_out < 1 or len(term_a) != begin[-1] or len(term_b) != begin[-1]:
+            raise EnsiError("begin must hold n_out + 1 offsets and end at the number of terms")
+        if ct_out is None:
+            ct_out = self.ct_alloc(n_out, ct_a.limbs - 1)
+        self._check(self.lib.ensi_mult_sum_relin_rescale(self.h, rk.h, ct_a.h, ct_b.h, _ptr(begin), _ptr(term_a), _ptr(term_b), n_out,
+                                                         ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def one_hot_masks(self, count, limbs):
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_one_hot_masks(self.h, int(count), int(limbs), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=count)
+
+    def replicate(self, gk, ct_in, src, masks, mask_idx, ct_out=None, stream=0):
+        src = np.ascontiguousarray(src, dtype=np.int32)
+        mask_idx = np.ascontiguousarray(mask_idx, dtype=np.int32)
+        if len(src) != len(mask_idx) or len(src) < 1:
+            raise EnsiError("one source and one mask index per output")
+        if ct_out is None:
+            ct_out = self.ct_alloc(len(src), ct_in.limbs - 1)
+        self._check(self.lib.ensi_replicate(self.h, gk.h, ct_in.h, _ptr(src), masks.h, _ptr(mask_idx), len(src), ct_out.h,
+                                            ctypes.c_void_p(stream)))
+        return ct_out
+
+    def ccmm(self, rk, gk, ct_a, ct_b, masks, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(ct_b.n, ct_b.limbs - 2)
+        self._check(self.lib.ensi_ccmm(self.h, rk.h, gk.h, ct_a.h, ct_b.h, masks.h, ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

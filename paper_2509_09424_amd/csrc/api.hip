@@ -292,6 +292,12 @@ extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
     if (ctx->ws_pl) (void)hipFree(ctx->ws_pl);
     if (ctx->ws_pt) (void)hipFree(ctx->ws_pt);
     if (ctx->ws_rot) (void)hipFree(ctx->ws_rot);
+    if (ctx->ws_ma) (void)hipFree(ctx->ws_ma);
+    if (ctx->ws_md) (void)hipFree(ctx->ws_md);
+    if (ctx->ws_me) (void)hipFree(ctx->ws_me);
+    if (ctx->ws_mt) (void)hipFree(ctx->ws_mt);
+    if (ctx->ws_rep) (void)hipFree(ctx->ws_rep);
+    if (ctx->ws_rtmp) (void)hipFree(ctx->ws_rtmp);
     for (MatmulPlan *p : ctx->plans) free_plan(p);
     for (auto &p : ctx->pending) {
         (void)hipEventDestroy(p.second.first);
@@ -559,6 +565,53 @@ extern "C" void ensi_pk_free(ensi_pk *pk) {
     delete pk;
 }
 
+// Scratch of the switching-key generation (one secret, any number of keys).
+struct KeygenScratch {
+    DevBuf d_s, d_target, d_e8, d_e, d_fac, d_s8;
+};
+static int keygen_scratch(ensi_ctx *ctx, const ensi_sk *sk, KeygenScratch &k, hipStream_t st) {
+    const int N = ctx->N, ext = ctx->L + ctx->K;
+    if (k.d_s.alloc((size_t)ext * N * 8) != hipSuccess || k.d_target.alloc((size_t)ext * N * 8) != hipSuccess || k.d_e8.alloc(N) != hipSuccess ||
+        k.d_e.alloc((size_t)ext * N * 8) != hipSuccess || k.d_fac.alloc((size_t)ext * 8) != hipSuccess || k.d_s8.alloc(N) != hipSuccess)
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in key generation");
+    (void)hipMemcpy(k.d_s8.p, sk->s.data(), N, hipMemcpyHostToDevice);
+    launch_small_to_rns(ctx, k.d_s8.as<int8_t>(), 1, make_map(ctx, ctx->L, true), k.d_s.as<u64>(), st);  // coefficient form of s
+    return ENSI_OK;
+}
+// key <- hybrid key-switching key from the secret in k.d_target (transform domain, ordinary residues) to s:
+// per digit j, (b_j, a_j) with b_j = -a_j s + e_j + [P]_{q_i} target on the limbs of digit j.  e: host
+// int8[beta][N] or NULL; a_j is the uniform stream stream_base | j.
+static void make_switch_key(ensi_ctx *ctx, const ensi_sk *sk, KeygenScratch &k, const int8_t *e, uint64_t seed_a, u64 stream_base, u64 *key,
+                            hipStream_t st) {
+    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
+    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
+    LimbMap mext = make_map(ctx, L, true);
+    std::vector<int8_t> ev(N);
+    for (int j = 0; j < beta; j++) {
+        u64 *kb = key + (size_t)(j * 2) * ext * N, *ka = kb + (size_t)ext * N;
+        if (e) memcpy(ev.data(), e + (size_t)j * N, N);
+        else sample_error(ctx, ev.data(), N);
+        (void)hipMemcpyAsync(k.d_e8.p, ev.data(), N, hipMemcpyHostToDevice, st);
+        (void)hipStreamSynchronize(st);
+        launch_small_to_rns(ctx, k.d_e8.as<int8_t>(), 1, mext, k.d_e.as<u64>(), st);
+        launch_ntt(ctx, k.d_e.as<u64>(), ext, mext, false, st);
+        launch_uniform(ctx, ka, mext, seed_a, stream_base | (u64)j, st);
+        launch_ntt(ctx, ka, ext, mext, false, st);
+        std::vector<u64> fac(ext, 0);
+        for (int i = j * ctx->alpha; i < std::min((j + 1) * ctx->alpha, L); i++) {
+            const u64 q = ctx->primes[i];
+            u64 P = 1;
+            for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
+            fac[i] = hm_to_mont(P, q);
+        }
+        (void)hipMemcpyAsync(k.d_fac.p, fac.data(), ext * 8, hipMemcpyHostToDevice, st);
+        (void)hipStreamSynchronize(st);
+        launch_key_assemble(ctx, kb, ka, sk->d_s_hat, k.d_e.as<u64>(), k.d_target.as<u64>(), k.d_fac.as<u64>(), mext, st);
+        launch_to_mont(ctx, ka, ext, mext, st);
+    }
+    if (ctx->ks16) launch_ks16_key_format(ctx, key, beta, st);
+}
+
 extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_t *steps, int32_t n_steps, const int8_t *e,
                                   uint64_t seed_a, ensi_gk **out) {
     if (!ctx || !sk || !out || (n_steps > 0 && !steps) || n_steps < 0) return ENSI_E_BADARG;
@@ -568,20 +621,12 @@ extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_
     LimbMap mext = make_map(ctx, L, true);
     ensi_gk *gk = new ensi_gk();
     gk->ctx = ctx;
-    DevBuf d_s, d_sg, d_e8, d_e, d_fac;
-    if (d_s.alloc((size_t)ext * N * 8) != hipSuccess || d_sg.alloc((size_t)ext * N * 8) != hipSuccess || d_e8.alloc(N) != hipSuccess ||
-        d_e.alloc((size_t)ext * N * 8) != hipSuccess || d_fac.alloc((size_t)ext * 8) != hipSuccess) {
+    KeygenScratch k;
+    int rc;
+    if ((rc = keygen_scratch(ctx, sk, k, st))) {
         ensi_gk_free(gk);
-        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in galois_keygen");
+        return rc;
     }
-    DevBuf d_s8;
-    if (d_s8.alloc(N) != hipSuccess) {
-        ensi_gk_free(gk);
-        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in galois_keygen");
-    }
-    (void)hipMemcpy(d_s8.p, sk->s.data(), N, hipMemcpyHostToDevice);
-    launch_small_to_rns(ctx, d_s8.as<int8_t>(), 1, mext, d_s.as<u64>(), st);  // coefficient form of s
-    std::vector<int8_t> ev(N);
     for (int t = 0; t < n_steps; t++) {
         const u32 g = galois_element(ctx, steps[t]);
         if (gk->keys.count(g)) continue;
@@ -592,35 +637,47 @@ extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_
         }
         gk->keys[g] = key;
         // phi_g(s), transform domain
-        launch_automorphism_coef(ctx, d_sg.as<u64>(), d_s.as<u64>(), mext, inv_mod_2n(g, N), st);
-        launch_ntt(ctx, d_sg.as<u64>(), ext, mext, false, st);
-        for (int j = 0; j < beta; j++) {
-            u64 *kb = key + (size_t)(j * 2) * ext * N, *ka = kb + (size_t)ext * N;
-            if (e) memcpy(ev.data(), e + ((size_t)t * beta + j) * N, N);
-            else sample_error(ctx, ev.data(), N);
-            (void)hipMemcpyAsync(d_e8.p, ev.data(), N, hipMemcpyHostToDevice, st);
-            (void)hipStreamSynchronize(st);
-            launch_small_to_rns(ctx, d_e8.as<int8_t>(), 1, mext, d_e.as<u64>(), st);
-            launch_ntt(ctx, d_e.as<u64>(), ext, mext, false, st);
-            launch_uniform(ctx, ka, mext, seed_a, ((u64)2 << 56) | ((u64)g << 8) | (u64)j, st);
-            launch_ntt(ctx, ka, ext, mext, false, st);
-            std::vector<u64> fac(ext, 0);
-            for (int i = j * ctx->alpha; i < std::min((j + 1) * ctx->alpha, L); i++) {
-                const u64 q = ctx->primes[i];
-                u64 P = 1;
-                for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
-                fac[i] = hm_to_mont(P, q);
-            }
-            (void)hipMemcpyAsync(d_fac.p, fac.data(), ext * 8, hipMemcpyHostToDevice, st);
-            (void)hipStreamSynchronize(st);
-            launch_key_assemble(ctx, kb, ka, sk->d_s_hat, d_e.as<u64>(), d_sg.as<u64>(), d_fac.as<u64>(), mext, st);
-            launch_to_mont(ctx, ka, ext, mext, st);
-        }
-        if (ctx->ks16) launch_ks16_key_format(ctx, key, beta, st);
+        launch_automorphism_coef(ctx, k.d_target.as<u64>(), k.d_s.as<u64>(), mext, inv_mod_2n(g, N), st);
+        launch_ntt(ctx, k.d_target.as<u64>(), ext, mext, false, st);
+        make_switch_key(ctx, sk, k, e ? e + (size_t)t * beta * N : nullptr, seed_a, ((u64)2 << 56) | ((u64)g << 8), key, st);
     }
     if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
         ensi_gk_free(gk);
         ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in galois_keygen");
+    }
+    *out = gk;
+    return ENSI_OK;
+}
+
+// Evaluation key of Mult: switches from s^2 to s.  Stored in a key set under the element 1 (the identity
+// automorphism), which is how the key-switch kernels are driven for a relinearisation.
+extern "C" int ensi_relin_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int8_t *e, uint64_t seed_a, ensi_gk **out) {
+    if (!ctx || !sk || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
+    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
+    hipStream_t st = nullptr;
+    LimbMap mext = make_map(ctx, L, true);
+    ensi_gk *gk = new ensi_gk();
+    gk->ctx = ctx;
+    KeygenScratch k;
+    int rc;
+    if ((rc = keygen_scratch(ctx, sk, k, st))) {
+        ensi_gk_free(gk);
+        return rc;
+    }
+    u64 *key = nullptr;
+    if (hipMalloc((void **)&key, (size_t)beta * 2 * ext * N * 8) != hipSuccess) {
+        ensi_gk_free(gk);
+        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of the evaluation key failed");
+    }
+    gk->keys[1u] = key;
+    // s^2, transform domain: NTT(s) (.) NTT(s), the second factor in Montgomery form
+    launch_ntt(ctx, k.d_s.as<u64>(), ext, mext, false, st);
+    launch_mul_mont(ctx, k.d_target.as<u64>(), k.d_s.as<u64>(), sk->d_s_hat, ext, mext, st);
+    make_switch_key(ctx, sk, k, e, seed_a, (u64)3 << 56, key, st);
+    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
+        ensi_gk_free(gk);
+        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in relin_keygen");
     }
     *out = gk;
     return ENSI_OK;
@@ -1534,6 +1591,231 @@ extern "C" int ensi_rope(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, co
         if ((rc = pmult_core(ctx, terms, begin, l1, ls, pt, &part, st))) return rc;
     }
     out->scale = in->scale * pt->scale / (double)ctx->primes[l1 - 1];
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ----------------------------------------------- ciphertext-ciphertext products
+extern "C" int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs) {
+    if (!ct || limbs < 1 || limbs > ct->limbs) return ENSI_E_BADARG;
+    ct->limbs = limbs;
+    return ENSI_OK;
+}
+
+// out_o = Rescale(Relin(sum_{t in [begin[o], begin[o+1])} a_t (x) b_t)); operands have l1 limbs.  Outputs are
+// handled in groups of at most one rotation chunk whose operand polynomials fit a bounded workspace.
+static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &terms, const std::vector<int32_t> &begin, int l1,
+                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st) {
+    const int N = ctx->N, n_out = (int)begin.size() - 1, ext = l1 + ctx->K;
+    if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ciphertext multiplication: no limb left to drop");
+    if (out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the operands (%d vs %d limbs)", out->limbs, l1);
+    if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_out);
+    const size_t term_words = (size_t)4 * l1 * N;
+    const int max_terms = (int)std::max<size_t>(1, ((size_t)1 << 30) / term_words);
+    const int max_out = ctx->ks16 ? rot_chunk() : 64;
+    std::vector<int> cut(1, 0);
+    size_t need_a = 1, need_o = 0;
+    for (int o0 = 0; o0 < n_out;) {
+        int o1 = o0 + 1;
+        while (o1 < n_out && begin[o1 + 1] - begin[o0] <= max_terms && o1 - o0 < max_out) o1++;
+        cut.push_back(o1);
+        need_a = std::max(need_a, (size_t)(begin[o1] - begin[o0]));
+        need_o = std::max(need_o, (size_t)(o1 - o0));
+        o0 = o1;
+    }
+    int rc;
+    const size_t rw = raised_words(ctx, l1);
+    if ((rc = grow(ctx, &ctx->ws_ma, &ctx->ws_ma_words, need_a * term_words))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_md, &ctx->ws_md_words, need_o * 3 * l1 * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_me, &ctx->ws_me_words, need_o * 2 * l1 * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, need_o * rw))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, need_o * 2 * ext * N))) return rc;
+    if ((rc = ensure_desc(ctx, need_o))) return rc;
+    const size_t tw = terms.size() * (sizeof(MmTerm) / 8), bw = (begin.size() + 1) / 2;
+    if ((rc = grow(ctx, &ctx->ws_mt, &ctx->ws_mt_words, tw + bw + 2))) return rc;
+    if (!terms.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt, terms.data(), terms.size() * sizeof(MmTerm), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + tw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
+    const u64 *d_consts;
+    const double *d_fconsts;
+    bool fp;
+    if ((rc = upload_rescale_consts(ctx, l1, 1.0, false, st, &d_consts, &d_fconsts, &fp))) return rc;
+    for (size_t k = 0; k + 1 < cut.size(); k++) {
+        const int o0 = cut[k], o1 = cut[k + 1], cnt = o1 - o0;
+        MmGroup g;
+        g.terms = (const MmTerm *)ctx->ws_mt;
+        g.begin = (const int32_t *)(ctx->ws_mt + tw) + o0;
+        g.t_base = begin[o0];
+        g.n_terms = begin[o1] - begin[o0];
+        g.n_out = cnt;
+        g.l1 = l1;
+        g.limb_stride_a = limb_stride_a;
+        g.limb_stride_b = limb_stride_b;
+        g.ws_a = ctx->ws_ma;
+        g.ws_d = ctx->ws_md;
+        g.ws_e = ctx->ws_me;
+        g.out_stride = (size_t)2 * out->limbs_alloc * N;
+        g.out = out->d + (size_t)o0 * g.out_stride;
+        g.limb_stride_out = out->limbs_alloc;
+        launch_mm_tensor(ctx, g, st);
+        // relinearisation: (d0, d2) of every output goes through the key switch like a ciphertext (c0, c1) under
+        // the identity automorphism; the result is (d0 + KS_0(d2), KS_1(d2))
+        std::vector<RotDesc> desc(cnt);
+        for (int c = 0; c < cnt; c++) {
+            desc[c].c0 = ctx->ws_md + (size_t)c * 3 * l1 * N;
+            desc[c].digits = ctx->ws_digits + (size_t)c * rw;
+            desc[c].key = rkey;
+            desc[c].out = ctx->ws_me + (size_t)c * 2 * l1 * N;
+            desc[c].g = 1;
+            desc[c].g_inv = 1;
+        }
+        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), cnt * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        if ((rc = raise_cts(ctx, l1, ctx->ws_md, (size_t)3 * l1 * N, l1, cnt, st))) return rc;
+        if ((rc = run_rotations(ctx, ctx->ws_desc, cnt, l1, l1, l1, st))) return rc;
+        launch_mm_add_d1(ctx, g, st);
+        launch_rescale(ctx, ctx->ws_me, cnt, l1, l1, d_consts, fp ? d_fconsts : nullptr, st);
+        launch_mm_scatter(ctx, g, st);
+    }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+static int relin_key(ensi_ctx *ctx, const ensi_gk *rk, const u64 **key) {
+    auto it = rk->keys.find(1u);
+    if (it == rk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "the key set holds no evaluation key (ensi_relin_keygen)");
+    *key = it->second;
+    return ENSI_OK;
+}
+
+extern "C" int ensi_mult_sum_relin_rescale(ensi_ctx *ctx, const ensi_gk *rk, const ensi_ct *a, const ensi_ct *b, const int32_t *begin,
+                                           const int32_t *term_a, const int32_t *term_b, int32_t n_out, ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !a || !b || !begin || !out || n_out < 1) return ENSI_E_BADARG;
+    if (a->limbs != b->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "operands at different levels (%d vs %d limbs)", a->limbs, b->limbs);
+    if (begin[0] != 0) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must start at 0");
+    for (int o = 0; o < n_out; o++)
+        if (begin[o + 1] < begin[o]) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must not decrease");
+    const int T = begin[n_out];
+    if (T > 0 && (!term_a || !term_b)) return ENSI_E_BADARG;
+    if (a->d == out->d || b->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ciphertext multiplication: operands and out must not overlap");
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const size_t a_ct = (size_t)2 * a->limbs_alloc * ctx->N, b_ct = (size_t)2 * b->limbs_alloc * ctx->N;
+    std::vector<MmTerm> terms(T);
+    for (int t = 0; t < T; t++) {
+        if (term_a[t] < 0 || term_a[t] >= a->n || term_b[t] < 0 || term_b[t] >= b->n)
+            ENSI_FAIL(ctx, ENSI_E_BADARG, "term %d names ciphertexts %d of %d and %d of %d", t, term_a[t], a->n, term_b[t], b->n);
+        terms[t].a = a->d + (size_t)term_a[t] * a_ct;
+        terms[t].b = b->d + (size_t)term_b[t] * b_ct;
+    }
+    std::vector<int32_t> bg(begin, begin + n_out + 1);
+    if ((rc = mult_core(ctx, key, terms, bg, a->limbs, a->limbs_alloc, b->limbs_alloc, out, (hipStream_t)stream))) return rc;
+    out->scale = a->scale * b->scale / (double)ctx->primes[a->limbs - 1];
+    return ENSI_OK;
+}
+
+// ------------------------------------------------------------------------ CCMM
+extern "C" int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !out || count < 1 || count > ctx->N / 2 || limbs < 2 || limbs > ctx->L) return ENSI_E_BADARG;
+    std::vector<double> ones(count, 1.0);
+    return encode_window(ctx, ones.data(), count, 1, 0, 1, limbs, (double)ctx->primes[limbs - 1], out);
+}
+
+// rep_o = the value in slot mask_idx[o] of in[src[o]], copied into every slot: one product with the one-hot mask
+// and one rescale, then log2(N/2) steps t <- t + Rot(t; 2^r).  rep: n ciphertexts with in.limbs - 1 limbs.
+static int replicate_core(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const std::vector<int32_t> &src, const ensi_pt *masks,
+                          const std::vector<int32_t> &mask_idx, ensi_ct *rep, hipStream_t st) {
+    const int N = ctx->N, n = (int)src.size(), l1 = in->limbs, lo = l1 - 1;
+    const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
+    std::vector<PmTerm> terms(n);
+    std::vector<int32_t> begin(n + 1);
+    for (int o = 0; o < n; o++) {
+        if (src[o] < 0 || src[o] >= in->n) ENSI_FAIL(ctx, ENSI_E_BADARG, "replicate: ciphertext index %d outside the batch of %d", src[o], in->n);
+        terms[o] = {in->d + (size_t)src[o] * in_ct, mask_idx[o], 0};
+        begin[o] = o;
+    }
+    begin[n] = n;
+    int rc;
+    if ((rc = pmult_core(ctx, terms, begin, l1, in->limbs_alloc, masks, rep, st))) return rc;
+    rep->scale = in->scale * masks->scale / (double)ctx->primes[l1 - 1];
+    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * lo * N))) return rc;
+    ensi_ct tmp;
+    tmp.ctx = ctx;
+    tmp.n = n;
+    tmp.limbs = tmp.limbs_alloc = lo;
+    tmp.scale = rep->scale;
+    tmp.d = ctx->ws_rtmp;
+    tmp.owns = false;
+    std::vector<int32_t> steps(n);
+    for (int r = 1; r < N / 2; r *= 2) {
+        std::fill(steps.begin(), steps.end(), r);
+        if ((rc = ensi_rotate(ctx, gk, rep, steps.data(), &tmp, (void *)st))) return rc;
+        launch_ct_add(ctx, rep->d, rep->limbs_alloc, tmp.d, lo, lo, n, st);
+    }
+    return ENSI_OK;
+}
+
+extern "C" int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
+                              const int32_t *mask_idx, int32_t n_out, ensi_ct *out, void *stream) {
+    if (!ctx || !gk || !in || !src || !masks || !mask_idx || !out || n_out < 1) return ENSI_E_BADARG;
+    if (in->limbs < 2 || out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "replicate: output must be one level below the input");
+    if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "replicate: output batch holds %d ciphertexts, need %d", out->n, n_out);
+    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "replicate: in and out must not overlap");
+    std::vector<int32_t> s(src, src + n_out), mi(mask_idx, mask_idx + n_out);
+    int rc = replicate_core(ctx, gk, in, s, masks, mi, out, (hipStream_t)stream);
+    if (rc) return rc;
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+extern "C" int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
+                         ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !gk || !A || !B || !masks || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, d = A->n, m = B->n, l1 = B->limbs;
+    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    if (l1 < 3 || out->limbs != l1 - 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be two levels below the operands");
+    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, m);
+    if (masks->n < d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d one-hot masks for %d rows of B", masks->n, d);
+    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int lo = l1 - 1;
+    // outputs in groups: the d replicated elements of each of up to `per` columns of B at a time
+    const int per = std::max(1, std::min(m, 512 / d));
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (size_t)per * d * 2 * lo * N))) return rc;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    for (int i0 = 0; i0 < m; i0 += per) {
+        const int cnt = std::min(per, m - i0);
+        ensi_ct rep;
+        rep.ctx = ctx;
+        rep.n = cnt * d;
+        rep.limbs = rep.limbs_alloc = lo;
+        rep.scale = 1.0;
+        rep.d = ctx->ws_rep;
+        rep.owns = false;
+        std::vector<int32_t> src(cnt * d), mi(cnt * d);
+        for (int c = 0; c < cnt; c++)
+            for (int j = 0; j < d; j++) {
+                src[c * d + j] = i0 + c;  // element (j, i) is slot j of column ciphertext i
+                mi[c * d + j] = j;
+            }
+        if ((rc = replicate_core(ctx, gk, B, src, masks, mi, &rep, st))) return rc;
+        // c_i = sum_j a_j (x) rep_(i,j); a_j is read at the level of the replicated elements (its last limb dropped)
+        std::vector<MmTerm> terms(cnt * d);
+        std::vector<int32_t> begin(cnt + 1);
+        for (int c = 0; c < cnt; c++) {
+            begin[c] = c * d;
+            for (int j = 0; j < d; j++) terms[c * d + j] = {A->d + (size_t)j * a_ct, rep.d + (size_t)(c * d + j) * 2 * lo * N};
+        }
+        begin[cnt] = cnt * d;
+        ensi_ct part = *out;
+        part.owns = false;
+        part.d = out->d + (size_t)i0 * out_ct;
+        part.n = cnt;
+        if ((rc = mult_core(ctx, key, terms, begin, lo, A->limbs_alloc, lo, &part, st))) return rc;
+        out->scale = A->scale * rep.scale / (double)ctx->primes[lo - 1];
+    }
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
 }

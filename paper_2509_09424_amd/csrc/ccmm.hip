@@ -1,0 +1,121 @@
+// Ciphertext-ciphertext multiplication (paper, Preliminaries: Multiplication, Mult) for the ciphertext-
+// ciphertext matrix product of the CCMM section:  out_o = Rescale(Relin(sum_t a_t (x) b_t)).
+//
+// The tensor product of two ciphertexts is three polynomials (d0, d1, d2) = (a0 b0, a0 b1 + a1 b0, a1 b1),
+// products in R_{Q_l}, i.e. pointwise in the transform domain.  The products of one output are added there,
+// transformed back once, d2 is key-switched from s^2 to s with the evaluation key (the same raise / inner
+// product / ModDown kernels as a rotation, with the identity automorphism, fed (d0, d2) as if it were a
+// ciphertext so that d0 is added on the way), d1 is added and the result rescaled.
+//
+// Kernels here: the gather of the four operand polynomials of every product, the multiply-add that forms
+// (d0, d2, d1) per output, the addition of d1 and a strided ciphertext addition (used by the rotate-and-add
+// steps of the element replication).  Transforms, key switch, rescale and the final strided copy are the
+// library's existing kernels.
+#include "common.h"
+
+#define MM_THREADS 256
+
+// grid (ceil(N/256), 4*l1, n_terms): ws_a[t][p*l1+i][N], p = 0..3 for a0, a1, b0, b1
+__global__ __launch_bounds__(MM_THREADS) void k_mm_gather(MmGroup g, int N) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int y = blockIdx.y, p = y / g.l1, i = y - p * g.l1, t = blockIdx.z;
+    const MmTerm tm = g.terms[g.t_base + t];
+    const u64 *src = (p < 2 ? tm.a + ((size_t)p * g.limb_stride_a + i) * N : tm.b + ((size_t)(p - 2) * g.limb_stride_b + i) * N);
+    g.ws_a[((size_t)t * 4 * g.l1 + y) * N + idx] = src[idx];
+}
+
+// grid (ceil(N/256), l1, n_out): ws_d[o][0|1|2][i][N] <- d0, d2, d1 (transform domain).  Operands are ordinary
+// residues: a Montgomery product carries a factor 2^-64, removed once per sum with 2^128 mod q.
+__global__ __launch_bounds__(MM_THREADS) void k_mm_tensor_mac(MmGroup g, int N, const PrimeConst *pcs) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int i = blockIdx.y, o = blockIdx.z;
+    const PrimeConst pc = pcs[i];
+    const u64 q = pc.q, qn = pc.qneg_inv;
+    const int t0 = g.begin[o], t1 = g.begin[o + 1];
+    u64 d0 = 0, d1 = 0, d2 = 0;
+    const size_t poly = (size_t)g.l1 * N;
+    for (int t = t0; t < t1; t++) {
+        const u64 *x = g.ws_a + ((size_t)(t - g.t_base) * 4 * g.l1 + i) * N + idx;
+        const u64 a0 = x[0], a1 = x[poly], b0 = x[2 * poly], b1 = x[3 * poly];
+        d0 = add_mod(d0, mont_mul(a0, b0, q, qn), q);
+        d1 = add_mod(d1, add_mod(mont_mul(a0, b1, q, qn), mont_mul(a1, b0, q, qn), q), q);
+        d2 = add_mod(d2, mont_mul(a1, b1, q, qn), q);
+    }
+    u64 *out = g.ws_d + ((size_t)o * 3 * g.l1 + i) * N + idx;
+    out[0] = mont_mul(d0, pc.r2, q, qn);
+    out[poly] = mont_mul(d2, pc.r2, q, qn);
+    out[2 * poly] = mont_mul(d1, pc.r2, q, qn);
+}
+
+// grid (ceil(N/256), l1, n_out): ws_e[o][1][i] += ws_d[o][2][i]  (d1 joins the second polynomial)
+__global__ __launch_bounds__(MM_THREADS) void k_mm_add_d1(MmGroup g, int N, const PrimeConst *pcs) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int i = blockIdx.y, o = blockIdx.z;
+    u64 *e = g.ws_e + ((size_t)o * 2 * g.l1 + g.l1 + i) * N + idx;
+    *e = add_mod(*e, g.ws_d[((size_t)o * 3 * g.l1 + 2 * g.l1 + i) * N + idx], pcs[i].q);
+}
+
+// grid (ceil(N/256), 2*l1, n): a[c][poly][i] += b[c][poly][i] on batches with their own limb strides
+__global__ __launch_bounds__(MM_THREADS) void k_ct_add(u64 *a, int stride_a, const u64 *b, int stride_b, int l1, int N, const PrimeConst *pcs) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int y = blockIdx.y, p = y / l1, i = y - p * l1, c = blockIdx.z;
+    u64 *x = a + ((size_t)c * 2 * stride_a + (size_t)p * stride_a + i) * N + idx;
+    *x = add_mod(*x, b[((size_t)c * 2 * stride_b + (size_t)p * stride_b + i) * N + idx], pcs[i].q);
+}
+
+// grid (ceil(N/256), 2*(l1-1), n_out): the rescaled limbs of ws_e (limb stride l1) to the output ciphertexts
+__global__ __launch_bounds__(MM_THREADS) void k_mm_scatter(MmGroup g, int N) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int lo = g.l1 - 1;
+    const int y = blockIdx.y, c = y / lo, i = y - c * lo, o = blockIdx.z;
+    g.out[(size_t)o * g.out_stride + ((size_t)c * g.limb_stride_out + i) * N + idx] = g.ws_e[((size_t)o * 2 * g.l1 + c * g.l1 + i) * N + idx];
+}
+
+static LimbMap mm_map(int l1) {
+    LimbMap m;
+    m.n = l1;
+    for (int e = 0; e < ENSI_MAX_EXT; e++) m.prime[e] = e < l1 ? e : 0;
+    return m;
+}
+
+// gather -> forward transform -> tensor multiply-add -> inverse transform: leaves (d0, d2, d1) of every output of
+// the group in ws_d, coefficient form
+void launch_mm_tensor(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
+    const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
+    const LimbMap map = mm_map(g.l1);
+    if (g.n_terms > 0) {
+        {
+            ScopedTimer t(ctx, "mm_gather", st);
+            hipLaunchKernelGGL(k_mm_gather, dim3(nb, 4 * g.l1, g.n_terms), dim3(MM_THREADS), 0, st, g, N);
+        }
+        launch_ntt(ctx, g.ws_a, g.n_terms * 4 * g.l1, map, false, st);
+    }
+    {
+        ScopedTimer t(ctx, "mm_tensor_mac", st);
+        hipLaunchKernelGGL(k_mm_tensor_mac, dim3(nb, g.l1, g.n_out), dim3(MM_THREADS), 0, st, g, N, ctx->d_pc);
+    }
+    launch_ntt(ctx, g.ws_d, g.n_out * 3 * g.l1, map, true, st);
+}
+
+void launch_mm_add_d1(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
+    const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
+    ScopedTimer t(ctx, "mm_add_d1", st);
+    hipLaunchKernelGGL(k_mm_add_d1, dim3(nb, g.l1, g.n_out), dim3(MM_THREADS), 0, st, g, N, ctx->d_pc);
+}
+
+void launch_ct_add(ensi_ctx *ctx, u64 *a, int stride_a, const u64 *b, int stride_b, int l1, int n, hipStream_t st) {
+    const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
+    ScopedTimer t(ctx, "ct_add", st);
+    hipLaunchKernelGGL(k_ct_add, dim3(nb, 2 * l1, n), dim3(MM_THREADS), 0, st, a, stride_a, b, stride_b, l1, N, ctx->d_pc);
+}
+
+void launch_mm_scatter(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
+    const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
+    ScopedTimer t(ctx, "mm_scatter", st);
+    hipLaunchKernelGGL(k_mm_scatter, dim3(nb, 2 * (g.l1 - 1), g.n_out), dim3(MM_THREADS), 0, st, g, N);
+}

@@ -89,6 +89,24 @@ struct PmGroup {
     int limb_stride_out;
 };
 
+// One ciphertext-ciphertext product: the two operand ciphertexts ([2][limb_stride][N] words each).
+struct MmTerm {
+    const u64 *a, *b;
+};
+// One group of outputs of out_o = Rescale(Relin(sum_t a_t (x) b_t)); same conventions as PmGroup.
+struct MmGroup {
+    const MmTerm *terms;
+    const int32_t *begin;
+    int t_base, n_terms, n_out;
+    int l1, limb_stride_a, limb_stride_b;
+    u64 *ws_a;   // [n_terms][4][l1][N] operand polynomials a0, a1, b0, b1 (transformed in place)
+    u64 *ws_d;   // [n_out][3][l1][N]   d0, d2, d1: (d0, d2) is laid out like a ciphertext for the key switch
+    u64 *ws_e;   // [n_out][2][l1][N]   relinearised product
+    u64 *out;
+    size_t out_stride;
+    int limb_stride_out;
+};
+
 // One rotation to perform: everything the fused kernels need, device-resident.
 struct RotDesc {
     const u64 *c0;      // source polynomial c0: [limb_stride_in][N]
@@ -147,6 +165,12 @@ struct ensi_ctx {
     u64 *ws_pl = nullptr; size_t ws_pl_words = 0;       //   centred last limbs of the group
     u64 *ws_pt = nullptr; size_t ws_pt_words = 0;       //   term table and offsets
     u64 *ws_rot = nullptr; size_t ws_rot_words = 0;     // rotated copies of the inputs of Alg. 2
+    u64 *ws_ma = nullptr; size_t ws_ma_words = 0;       // ciphertext products: operand polynomials of a group
+    u64 *ws_md = nullptr; size_t ws_md_words = 0;       //   (d0, d2, d1) per output
+    u64 *ws_me = nullptr; size_t ws_me_words = 0;       //   relinearised products
+    u64 *ws_mt = nullptr; size_t ws_mt_words = 0;       //   term table and offsets
+    u64 *ws_rep = nullptr; size_t ws_rep_words = 0;     // CCMM: replicated elements of B
+    u64 *ws_rtmp = nullptr; size_t ws_rtmp_words = 0;   //   rotated copy during a rotate-and-add step
     std::vector<MatmulPlan *> plans;                    // cached per weight matrix (weights are static server-side)
     int accumulate_mode = 0;                            // 0 auto, 1 plain-ALU kernel, 2 matrix-core kernel where valid
     int pmult_mode = 0;                                 // 0 auto, 1 always the generic kernels
@@ -257,6 +281,13 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
 void launch_pm_generic(ensi_ctx *ctx, const PmGroup &g, const u64 *d_consts, const double *d_fconsts, hipStream_t st);
 void launch_pm16(ensi_ctx *ctx, const PmGroup &g, const PmRescale &rs, hipStream_t st);
 void launch_pm16_pt_format(ensi_ctx *ctx, const u64 *ntt_form, int n_rows, u64 *out, hipStream_t st);
+
+// ciphertext-ciphertext products (ccmm.hip)
+void launch_mm_tensor(ensi_ctx *ctx, const MmGroup &g, hipStream_t st);
+void launch_mm_add_d1(ensi_ctx *ctx, const MmGroup &g, hipStream_t st);
+void launch_mm_scatter(ensi_ctx *ctx, const MmGroup &g, hipStream_t st);
+// a += b on batches of n ciphertexts with l1 active limbs and their own limb strides
+void launch_ct_add(ensi_ctx *ctx, u64 *a, int stride_a, const u64 *b, int stride_b, int l1, int n, hipStream_t st);
 
 void launch_small_to_rns(ensi_ctx *ctx, const int8_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);
 void launch_i64_to_rns(ensi_ctx *ctx, const int64_t *d_in, int n_poly, const LimbMap &map, u64 *out, hipStream_t st);

@@ -1,0 +1,136 @@
+"""GPU parity of ciphertext-ciphertext multiplication (Mult with one relinearisation and one rescale), of the
+element replication and of the CCMM product built on them, through the C ABI: every output limb must equal the
+oracle's bit for bit (same keys from the same seeded randomness, plaintext masks encoded by the oracle)."""
+import numpy as np
+import pytest
+
+import workloads as wl
+from helpers import Pair, stack_cts
+
+pytestmark = pytest.mark.gpu
+
+SMALL4 = (10, 50, 6, 60, 4, 4, 40)
+WIDE = (10, 55, 4, 60, 2, 2, 40)      # ciphertext primes above 2^50: integer kernels throughout
+TINY5 = (5, 50, 5, 60, 3, 3, 40)      # 16 slots: the whole CCMM against numpy in a blink
+KEYSWITCH = wl.WORKLOADS[1].param_tuple()
+
+
+def relin_keys(p, seed=77):
+    e = wl.error_poly(p.rng, (p.pr.beta(p.pr.L), p.N))
+    return p.o.relin_keygen(p.o_sk, e, seed), p.ctx.relin_keygen(p.g_sk, e, seed)
+
+
+def mult_case(p, l1, n_ct=4):
+    z = p.rng.uniform(-1, 1, (2 * n_ct, p.n))
+    o_cts, g_ct = p.encrypt_both(z, l1)
+    return z, o_cts, g_ct
+
+
+@pytest.mark.parametrize("params,l1", [(SMALL4, 6), (SMALL4, 5), (WIDE, 4)], ids=["six-limbs", "partial-digit", "wide-primes"])
+def test_mult_sum_relin_rescale_small_ring(params, l1):
+    p = Pair(params)
+    o_rk, g_rk = relin_keys(p)
+    z, o_cts, g_ct = mult_case(p, l1)
+    # output 0: one product; 1: nothing; 2: a sum of five products with repeated operands; 3: a square
+    begin = [0, 1, 1, 6, 7]
+    ta = [0, 1, 2, 3, 4, 5, 6]
+    tb = [7, 6, 5, 4, 3, 1, 6]
+    out = p.ctx.mult_sum_relin_rescale(g_rk, g_ct, g_ct, begin, ta, tb)
+    got = out.export()
+    assert out.limbs == l1 - 1 and abs(out.scale / (p.pr.scale ** 2 / p.pr.q[l1 - 1]) - 1) < 1e-12
+    for o in range(4):
+        pairs = [(o_cts[ta[t]], o_cts[tb[t]]) for t in range(begin[o], begin[o + 1])]
+        if pairs:
+            want = p.o.mult_sum_relin_rescale(pairs, o_rk).limbs()
+            ref = sum(z[ta[t]] * z[tb[t]] for t in range(begin[o], begin[o + 1]))
+            dec = p.ctx.decrypt(p.g_sk, out)[o]
+            assert np.abs(dec - ref).max() < 1e-3, o
+        else:
+            want = np.zeros((2, l1 - 1, p.N), dtype=np.uint64)
+        assert np.array_equal(got[o], want), o
+    # without an evaluation key in the set
+    _, g_gk = p.galois_keys([3])
+    with pytest.raises(p.binding.EnsiError, match="code -2"):
+        p.ctx.mult_sum_relin_rescale(g_gk, g_ct, g_ct, [0, 1], [0], [1], out)
+    for h in (g_ct, out, g_rk, g_gk):
+        h.free()
+    p.close()
+
+
+def test_mult_full_ring():
+    """N = 2^16: the transform and key-switch kernels of the fused path carry the product; a low level keeps the
+    oracle quick; operands whose limb stride is wider than their level."""
+    p = Pair(KEYSWITCH)
+    o_rk, g_rk = relin_keys(p)
+    l1 = 4
+    z, o_cts, g_ct = mult_case(p, l1, n_ct=2)
+    p.ctx.ct_drop_limbs(g_ct, 3)
+    o3 = [p.o.drop_limbs(c, 3) for c in o_cts]
+    out = p.ctx.mult_sum_relin_rescale(g_rk, g_ct, g_ct, [0, 2, 3], [0, 1, 2], [3, 2, 2])
+    want = [p.o.mult_sum_relin_rescale([(o3[0], o3[3]), (o3[1], o3[2])], o_rk), p.o.mult_sum_relin_rescale([(o3[2], o3[2])], o_rk)]
+    assert out.limbs == 2 and np.array_equal(out.export(), stack_cts(want))
+    dec = p.ctx.decrypt(p.g_sk, out)
+    assert np.abs(dec[0] - (z[0] * z[3] + z[1] * z[2])).max() < 1e-3 and np.abs(dec[1] - z[2] ** 2).max() < 1e-3
+    for h in (g_ct, out, g_rk):
+        h.free()
+    p.close()
+
+
+def doubling_keys(p):
+    steps = []
+    r = 1
+    while r < p.n:
+        steps.append(r)
+        r *= 2
+    return p.galois_keys(steps)
+
+
+@pytest.mark.parametrize("params", [TINY5, SMALL4], ids=["16-slots", "512-slots"])
+def test_replicate_against_oracle(params):
+    p = Pair(params)
+    l1 = p.pr.L
+    o_gks, g_gk = doubling_keys(p)
+    z = p.rng.uniform(-1, 1, (2, p.n))
+    o_cts, g_ct = p.encrypt_both(z, l1)
+    ks = [0, 3, p.n - 1]
+    masks = p.o.one_hot_masks(ks, l1)
+    g_masks = p.ctx.pt_set_scale(p.ctx.pt_import(masks, l1), float(p.pr.q[l1 - 1]))
+    src, mi = [0, 1, 1, 0], [1, 0, 2, 2]
+    out = p.ctx.replicate(g_gk, g_ct, src, g_masks, mi)
+    want = [p.o.replicate(o_cts[src[o]], masks[mi[o]], o_gks) for o in range(4)]
+    assert out.limbs == l1 - 1 and np.array_equal(out.export(), stack_cts(want))
+    dec = p.ctx.decrypt(p.g_sk, out)
+    for o in range(4):
+        assert np.abs(dec[o] - z[src[o], ks[mi[o]]]).max() < 1e-3, o
+    # the library's own one-hot masks decode to the same selection
+    lib = p.ctx.one_hot_masks(4, l1)
+    out2 = p.ctx.replicate(g_gk, g_ct, [1], lib, [3])
+    assert np.abs(p.ctx.decrypt(p.g_sk, out2)[0] - z[1, 3]).max() < 1e-3
+    for h in (g_ct, g_masks, lib, out, out2, g_gk):
+        h.free()
+    p.close()
+
+
+def test_ccmm_against_oracle_and_numpy():
+    """CCMM section, C = A B: 16 tokens, d = 3, m = 2 at a 16-slot ring (every step of the oracle in a second)."""
+    p = Pair(TINY5)
+    l1 = p.pr.L
+    d, m = 3, 2
+    A = p.rng.uniform(-1, 1, (p.n, d))
+    Bm = p.rng.uniform(-1, 1, (d, m))
+    o_gks, g_gk = doubling_keys(p)
+    o_rk, g_rk = relin_keys(p)
+    zb = p.rng.uniform(-1, 1, (m, p.n))  # slots beyond d hold unrelated values
+    zb[:, :d] = Bm.T
+    o_a, g_a = p.encrypt_both(A.T, l1)
+    o_b, g_b = p.encrypt_both(zb, l1)
+    masks = p.o.one_hot_masks(range(d), l1)
+    g_masks = p.ctx.pt_set_scale(p.ctx.pt_import(masks, l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.ccmm(g_rk, g_gk, g_a, g_b, g_masks)
+    want = p.o.ccmm(o_a, o_b, d, o_rk, o_gks)
+    assert out.n == m and out.limbs == l1 - 2 and abs(out.scale / want[0].scale - 1) < 1e-12
+    assert np.array_equal(out.export(), stack_cts(want))
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - (A @ Bm).T).max() < 1e-3
+    for h in (g_a, g_b, g_masks, out, g_gk, g_rk):
+        h.free()
+    p.close()
