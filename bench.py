@@ -77,6 +77,29 @@ class Runner:
             self.pt = self.ctx.rope_plaintexts(self.cos, self.sin, self.L)
             self.ct_out = self.ctx.ct_alloc(n_ct, self.L - 1)
             return
+        if w.op == "ccmm":
+            # C = A B: A = d_in columns of `n` tokens, B = d_out columns with their d_in entries in the first slots
+            d, m = w.d_in, w.d_out
+            self.A = rng.uniform(-1.0, 1.0, size=(self.n, d))
+            self.B = rng.uniform(-1.0, 1.0, size=(d, m))
+            zb = np.zeros((m, self.n))
+            zb[:, :d] = self.B.T
+            pt = self.ctx.encode(np.ascontiguousarray(self.A.T), self.L)
+            self.ct_a = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            pt = self.ctx.encode(zb, self.L)
+            self.ct_in = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            steps, r = [], 1
+            while r < self.n:
+                steps.append(r)
+                r *= 2
+            self.gk = self.ctx.galois_keygen(self.sk, steps, None, 13)
+            self.rk = self.ctx.relin_keygen(self.sk, None, 17)
+            self.period = 1 << (d - 1).bit_length()
+            self.pt = self.ctx.periodic_masks(self.period, d, self.L)
+            self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
+            return
         if w.op == "merge":
             # d_in block-placed outputs: one group of c_tot encrypted columns, repeated for every packed output
             import torch
@@ -129,6 +152,9 @@ class Runner:
         if w.op == "merge":
             self.ctx.merge(self.ct_in, self.pt, w.c_tot, self.ct_out)
             return
+        if w.op == "ccmm":
+            self.ctx.ccmm(self.rk, self.gk, self.ct_a, self.ct_in, self.pt, self.period, self.ct_out)
+            return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
@@ -160,6 +186,9 @@ class Runner:
         if w.op == "merge":
             dec = self.ctx.decrypt(self.sk, self.ct_out)
             return float(np.abs(dec - self.Y.reshape(1, -1)).max())
+        if w.op == "ccmm":
+            dec = self.ctx.decrypt(self.sk, self.ct_out)
+            return float(np.abs(dec - (self.A @ self.B).T).max())
         ref = self.X @ self.W.astype(np.float64)
         out = self.ct_out
         if w.d_mid:
@@ -220,6 +249,7 @@ def roofline_for(w, prof):
     ext = L + K
     beta = -(-L // alpha)
     pm_terms = pm_out = 0
+    Lp = L  # level of the plaintext multiplication (the CCMM's key switches run one level below it)
     if w.name == "keyswitch":
         n_rot, n_raise = w.batch, w.batch
         n_key = n_rot  # every rotation streams its key
@@ -231,6 +261,17 @@ def roofline_for(w, prof):
     elif w.op == "merge":
         n_rot = n_raise = n_key = 0
         pm_terms, pm_out = w.d_in, -(-w.d_in // w.c_tot)
+    elif w.op == "ccmm":
+        # every element of B: one mask product and log2(period) rotate-and-add steps one level down (the log2(n/period)
+        # steps per column at the top level and the relinearisations are few and counted with them)
+        n_el = w.d_in * w.d_out
+        lp = ((w.d_in - 1).bit_length())
+        L = L - 1
+        ext = L + K
+        beta = -(-L // alpha)
+        n_rot = n_raise = n_el * lp + w.d_out * (w.log_n - 1 - lp) + w.d_out
+        n_key = lp * -(-n_el // 64) + (w.log_n - 1 - lp) + 1
+        pm_terms = pm_out = n_el
     else:
         n_in = -(-w.d_in // w.c_tot)
         n_rot, n_raise = w.d_in - n_in, n_in
@@ -256,10 +297,10 @@ def roofline_for(w, prof):
         "byte_planes": (w.d_in * 2 * L + (0 if "rescale_byte_planes" in prof else (w.d_mid or 0) * 2 * (L - 1))) * (8 + 7) / 8.0,
         "rescale_byte_planes": (w.d_mid or 0) * (2 * L + 2 * (L - 1) * 7 / 8.0),
         # plaintext multiplication, summed and rescaled (the few plaintext limbs are not counted)
-        "pm_fcols": pm_terms * 4 * L,                      # source limbs in, column-transformed limbs out
-        "pm_frows_mac_irows": (pm_terms + pm_out) * 2 * L,  # those in, one sum per output limb out
+        "pm_fcols": pm_terms * 4 * Lp,                      # source limbs in, column-transformed limbs out
+        "pm_frows_mac_irows": (pm_terms + pm_out) * 2 * Lp,  # those in, one sum per output limb out
         "pm_icols_last": pm_out * 4,
-        "pm_icols_rescale": pm_out * (2 * (L - 1) + 2 + 2 * (L - 1)),
+        "pm_icols_rescale": pm_out * (2 * (Lp - 1) + 2 + 2 * (Lp - 1)),
     }
     members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
     classes = list(hbm) + ["accumulate", "accumulate_mfma"]

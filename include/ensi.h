@@ -249,11 +249,19 @@ int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, ensi_pt **pt
 int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
                    const int32_t *mask_idx, int32_t n_out, ensi_ct *out, void *stream);
 /* C = A B on ciphertexts (CCMM section): A: d column ciphertexts (a_j = column j of A, tokens along the slots),
- * B: m column ciphertexts (b_i holds B[j][i] in slot j, j < d), both at the same number of limbs l;
- * c_i = Rescale(Relin(sum_j a_j (x) b_i^(j))) with b_i^(j) = B[j][i] replicated into every slot (ensi_replicate
- * with masks[j]; a_j is read at the level of the replicated elements).  out: m ciphertexts with l - 2 limbs. */
+ * B: m column ciphertexts (b_i holds B[j][i] in slot j for j < d and ZERO in every other slot), both at the same
+ * number of limbs l;  c_i = Rescale(Relin(sum_j a_j (x) b_i^(j))) with b_i^(j) = B[j][i] replicated into every
+ * slot.  Element extraction in two stages, `period` a power of two with d <= period <= N/2: per column,
+ * log2((N/2)/period) steps u <- u + Rot(u; r), r = period, 2 period, ... make it periodic (u[p] = b[p mod period],
+ * no level); per element, one product with masks[j] (1 in the slots congruent to j modulo period) and one
+ * rescale, then log2(period) steps t <- t + Rot(t; r), r = 1, 2, ..., period/2.  (The figure with the paper's own
+ * baby-step giant-step schedule is not part of its text; this one shares the giant steps among the elements of a
+ * column.)  gk must hold keys for the steps 2^r, r = 0..log2(N/2)-1; masks: at least d plaintexts from
+ * ensi_periodic_masks(period, count >= d, limbs = l); a_j is read at the level of the replicated elements.
+ * out: m ciphertexts with l - 2 limbs. */
+int ensi_periodic_masks(ensi_ctx *ctx, int32_t period, int32_t count, int32_t limbs, ensi_pt **pt);
 int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
-              ensi_ct *out, void *stream);
+              int32_t period, ensi_ct *out, void *stream);
 
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host

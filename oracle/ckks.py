@@ -583,14 +583,55 @@ class Oracle:
             r *= 2
         return t
 
-    def ccmm(self, a_cts, b_cts, d, rk, gks):
+    def periodic_masks(self, period, count, l1):
+        """Integer coefficients [count][N] of the masks with a 1 in every slot congruent to j modulo
+        `period` (j = 0..count-1), 0 elsewhere, at scale q_l."""
+        ql = float(self.pr.q[l1 - 1])
+        out = []
+        for j in range(count):
+            z = np.zeros(self.n)
+            z[j::period] = 1.0
+            out.append(self.encode_coeffs(z, ql))
+        return np.stack(out)
+
+    def spread_periods(self, ct, period, gks):
+        """Giant steps of the element extraction, shared by all elements of a column: a ciphertext
+        whose slots beyond the first `period` are zero becomes periodic, u[p] = ct[p mod period], by
+        u <- u + Rot(u; r) for r = period, 2 period, ..., N/4.  No level is consumed."""
+        u = ct
+        r = period
+        while r < self.n:
+            u = self.add_ct(u, self.rotate(u, gks[r]))
+            r *= 2
+        return u
+
+    def extract_from_periodic(self, u, mask, period, gks):
+        """Baby steps, per element: keep the slots congruent to j modulo the period (PMult by the
+        periodic mask, one rescale), then fill every window of `period` slots from its single
+        non-zero entry by t <- t + Rot(t; r), r = 1, 2, ..., period/2."""
+        l1 = u.l1
+        ql = float(self.pr.q[l1 - 1])
+        t = self.pmult_sum_rescale([(u, self.i64_to_rns(mask, self.pr.q[:l1]))], ql)
+        r = 1
+        while r < period:
+            t = self.add_ct(t, self.rotate(t, gks[r]))
+            r *= 2
+        return t
+
+    def ccmm(self, a_cts, b_cts, d, period, rk, gks):
         """C = A B on ciphertexts (CCMM section): A column-encoded (a_j = column j, tokens along the
-        slots), b_i = column i of B with B[j, i] in slot j; c_i = sum_j a_j (x) b_i^(j), where
-        b_i^(j) is B[j, i] replicated into every slot.  Costs two levels (mask, product)."""
+        slots), b_i = column i of B with B[j, i] in slot j < d and zeros in every other slot;
+        c_i = sum_j a_j (x) b_i^(j), where b_i^(j) is B[j, i] replicated into every slot.  Element
+        extraction in two stages (period = a power of two >= d): log2(n/period) rotate-and-add steps
+        per column make it periodic, then per element one mask product and log2(period) steps.  The
+        figure with the paper's own baby-step giant-step schedule is not in its text; this one shares
+        the giant steps among the d elements of a column and has the logarithmic rotation count per
+        element the text states.  Costs two levels (mask, product)."""
         l1 = b_cts[0].l1
-        masks = self.one_hot_masks(range(d), l1)
+        masks = self.periodic_masks(period, d, l1)
         out = []
         for b in b_cts:
-            reps = [self.replicate(b, masks[j], gks) for j in range(d)]
+            u = self.spread_periods(b, period, gks)
+            reps = [self.extract_from_periodic(u, masks[j], period, gks) for j in range(d)]
             out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a_cts[j], l1 - 1), reps[j]) for j in range(d)], rk))
         return out

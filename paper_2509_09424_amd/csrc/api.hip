@@ -1720,16 +1720,37 @@ extern "C" int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, e
     return encode_window(ctx, ones.data(), count, 1, 0, 1, limbs, (double)ctx->primes[limbs - 1], out);
 }
 
-// rep_o = the value in slot mask_idx[o] of in[src[o]], copied into every slot: one product with the one-hot mask
-// and one rescale, then log2(N/2) steps t <- t + Rot(t; 2^r).  rep: n ciphertexts with in.limbs - 1 limbs.
-static int replicate_core(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const std::vector<int32_t> &src, const ensi_pt *masks,
-                          const std::vector<int32_t> &mask_idx, ensi_ct *rep, hipStream_t st) {
-    const int N = ctx->N, n = (int)src.size(), l1 = in->limbs, lo = l1 - 1;
+// t <- t + Rot(t; r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch (the rotated copy goes
+// through a workspace).
+static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st) {
+    const int N = ctx->N, n = t->n, l1 = t->limbs;
+    int rc;
+    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N))) return rc;
+    ensi_ct tmp;
+    tmp.ctx = ctx;
+    tmp.n = n;
+    tmp.limbs = tmp.limbs_alloc = l1;
+    tmp.scale = t->scale;
+    tmp.d = ctx->ws_rtmp;
+    tmp.owns = false;
+    std::vector<int32_t> steps(n);
+    for (int r = r_begin; r < r_end; r *= 2) {
+        std::fill(steps.begin(), steps.end(), r);
+        if ((rc = ensi_rotate(ctx, gk, t, steps.data(), &tmp, (void *)st))) return rc;
+        launch_ct_add(ctx, t->d, t->limbs_alloc, tmp.d, l1, l1, n, st);
+    }
+    return ENSI_OK;
+}
+
+// rep_o = Rescale(in[src[o]] (x) masks[mask_idx[o]]): n ciphertexts with in.limbs - 1 limbs
+static int mask_rescale(ensi_ctx *ctx, const ensi_ct *in, const std::vector<int32_t> &src, const ensi_pt *masks,
+                        const std::vector<int32_t> &mask_idx, ensi_ct *rep, hipStream_t st) {
+    const int N = ctx->N, n = (int)src.size(), l1 = in->limbs;
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
     std::vector<PmTerm> terms(n);
     std::vector<int32_t> begin(n + 1);
     for (int o = 0; o < n; o++) {
-        if (src[o] < 0 || src[o] >= in->n) ENSI_FAIL(ctx, ENSI_E_BADARG, "replicate: ciphertext index %d outside the batch of %d", src[o], in->n);
+        if (src[o] < 0 || src[o] >= in->n) ENSI_FAIL(ctx, ENSI_E_BADARG, "ciphertext index %d outside the batch of %d", src[o], in->n);
         terms[o] = {in->d + (size_t)src[o] * in_ct, mask_idx[o], 0};
         begin[o] = o;
     }
@@ -1737,21 +1758,16 @@ static int replicate_core(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, c
     int rc;
     if ((rc = pmult_core(ctx, terms, begin, l1, in->limbs_alloc, masks, rep, st))) return rc;
     rep->scale = in->scale * masks->scale / (double)ctx->primes[l1 - 1];
-    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * lo * N))) return rc;
-    ensi_ct tmp;
-    tmp.ctx = ctx;
-    tmp.n = n;
-    tmp.limbs = tmp.limbs_alloc = lo;
-    tmp.scale = rep->scale;
-    tmp.d = ctx->ws_rtmp;
-    tmp.owns = false;
-    std::vector<int32_t> steps(n);
-    for (int r = 1; r < N / 2; r *= 2) {
-        std::fill(steps.begin(), steps.end(), r);
-        if ((rc = ensi_rotate(ctx, gk, rep, steps.data(), &tmp, (void *)st))) return rc;
-        launch_ct_add(ctx, rep->d, rep->limbs_alloc, tmp.d, lo, lo, n, st);
-    }
     return ENSI_OK;
+}
+
+// rep_o = the value in slot mask_idx[o] of in[src[o]], copied into every slot: one product with the one-hot mask
+// and one rescale, then log2(N/2) steps t <- t + Rot(t; 2^r).
+static int replicate_core(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const std::vector<int32_t> &src, const ensi_pt *masks,
+                          const std::vector<int32_t> &mask_idx, ensi_ct *rep, hipStream_t st) {
+    int rc;
+    if ((rc = mask_rescale(ctx, in, src, masks, mask_idx, rep, st))) return rc;
+    return doubling_steps(ctx, gk, rep, 1, ctx->N / 2, st);
 }
 
 extern "C" int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
@@ -1767,40 +1783,68 @@ extern "C" int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *i
     return ENSI_OK;
 }
 
+extern "C" int ensi_periodic_masks(ensi_ctx *ctx, int32_t period, int32_t count, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !out || period < 1 || (period & (period - 1)) || period > ctx->N / 2 || count < 1 || count > period || limbs < 2 || limbs > ctx->L)
+        return ENSI_E_BADARG;
+    const int n = ctx->N / 2;
+    std::vector<double> z((size_t)count * n, 0.0);
+    for (int j = 0; j < count; j++)
+        for (int p = j; p < n; p += period) z[(size_t)j * n + p] = 1.0;
+    return encode_window(ctx, z.data(), count, n, 0, 0, limbs, (double)ctx->primes[limbs - 1], out);
+}
+
 extern "C" int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
-                         ensi_ct *out, void *stream) {
+                         int32_t period, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !masks || !out) return ENSI_E_BADARG;
     const int N = ctx->N, d = A->n, m = B->n, l1 = B->limbs;
+    if (period < 1 || (period & (period - 1)) || period > N / 2 || period < d)
+        ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two between the inner dimension %d and %d", d, N / 2);
     if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
     if (l1 < 3 || out->limbs != l1 - 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be two levels below the operands");
     if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, m);
-    if (masks->n < d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d one-hot masks for %d rows of B", masks->n, d);
+    if (masks->n < d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d masks for %d rows of B", masks->n, d);
     if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
     hipStream_t st = (hipStream_t)stream;
     const u64 *key;
     int rc;
     if ((rc = relin_key(ctx, rk, &key))) return rc;
     const int lo = l1 - 1;
-    // outputs in groups: the d replicated elements of each of up to `per` columns of B at a time
+    // outputs in groups: up to `per` columns of B at a time, their d replicated elements side by side
     const int per = std::max(1, std::min(m, 512 / d));
-    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (size_t)per * d * 2 * lo * N))) return rc;
-    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    const size_t u_words = (size_t)per * 2 * l1 * N;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, u_words + (size_t)per * d * 2 * lo * N))) return rc;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, b_ct = (size_t)2 * B->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
     for (int i0 = 0; i0 < m; i0 += per) {
         const int cnt = std::min(per, m - i0);
+        // giant steps, once per column: u[p] = b[p mod period]
+        ensi_ct u;
+        u.ctx = ctx;
+        u.n = cnt;
+        u.limbs = u.limbs_alloc = l1;
+        u.scale = B->scale;
+        u.d = ctx->ws_rep;
+        u.owns = false;
+        for (int c = 0; c < cnt; c++)
+            for (int poly = 0; poly < 2; poly++)
+                ENSI_HIP(ctx, hipMemcpyAsync(u.d + ((size_t)c * 2 + poly) * l1 * N, B->d + (size_t)(i0 + c) * b_ct + (size_t)poly * B->limbs_alloc * N,
+                                             (size_t)l1 * N * 8, hipMemcpyDeviceToDevice, st));
+        if ((rc = doubling_steps(ctx, gk, &u, period, N / 2, st))) return rc;
+        // baby steps, per element: mask the slots congruent to j, fill every window of `period` slots
         ensi_ct rep;
         rep.ctx = ctx;
         rep.n = cnt * d;
         rep.limbs = rep.limbs_alloc = lo;
         rep.scale = 1.0;
-        rep.d = ctx->ws_rep;
+        rep.d = ctx->ws_rep + u_words;
         rep.owns = false;
         std::vector<int32_t> src(cnt * d), mi(cnt * d);
         for (int c = 0; c < cnt; c++)
             for (int j = 0; j < d; j++) {
-                src[c * d + j] = i0 + c;  // element (j, i) is slot j of column ciphertext i
+                src[c * d + j] = c;
                 mi[c * d + j] = j;
             }
-        if ((rc = replicate_core(ctx, gk, B, src, masks, mi, &rep, st))) return rc;
+        if ((rc = mask_rescale(ctx, &u, src, masks, mi, &rep, st))) return rc;
+        if ((rc = doubling_steps(ctx, gk, &rep, 1, period, st))) return rc;
         // c_i = sum_j a_j (x) rep_(i,j); a_j is read at the level of the replicated elements (its last limb dropped)
         std::vector<MmTerm> terms(cnt * d);
         std::vector<int32_t> begin(cnt + 1);

@@ -111,26 +111,32 @@ def test_replicate_against_oracle(params):
     p.close()
 
 
-def test_ccmm_against_oracle_and_numpy():
-    """CCMM section, C = A B: 16 tokens, d = 3, m = 2 at a 16-slot ring (every step of the oracle in a second)."""
-    p = Pair(TINY5)
+@pytest.mark.parametrize("params,d,m,period", [(TINY5, 3, 2, 4), (SMALL4, 5, 3, 8), (SMALL4, 8, 2, 8)], ids=["16-slots", "512-slots", "d-equals-period"])
+def test_ccmm_against_oracle_and_numpy(params, d, m, period):
+    """CCMM section, C = A B, with the two-stage element extraction."""
+    p = Pair(params)
     l1 = p.pr.L
-    d, m = 3, 2
     A = p.rng.uniform(-1, 1, (p.n, d))
     Bm = p.rng.uniform(-1, 1, (d, m))
     o_gks, g_gk = doubling_keys(p)
     o_rk, g_rk = relin_keys(p)
-    zb = p.rng.uniform(-1, 1, (m, p.n))  # slots beyond d hold unrelated values
+    zb = np.zeros((m, p.n))  # B[j, i] in slot j of ciphertext i, zeros elsewhere
     zb[:, :d] = Bm.T
     o_a, g_a = p.encrypt_both(A.T, l1)
     o_b, g_b = p.encrypt_both(zb, l1)
-    masks = p.o.one_hot_masks(range(d), l1)
+    masks = p.o.periodic_masks(period, d, l1)
     g_masks = p.ctx.pt_set_scale(p.ctx.pt_import(masks, l1), float(p.pr.q[l1 - 1]))
-    out = p.ctx.ccmm(g_rk, g_gk, g_a, g_b, g_masks)
-    want = p.o.ccmm(o_a, o_b, d, o_rk, o_gks)
+    out = p.ctx.ccmm(g_rk, g_gk, g_a, g_b, g_masks, period)
+    want = p.o.ccmm(o_a, o_b, d, period, o_rk, o_gks)
     assert out.n == m and out.limbs == l1 - 2 and abs(out.scale / want[0].scale - 1) < 1e-12
     assert np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - (A @ Bm).T).max() < 1e-3
-    for h in (g_a, g_b, g_masks, out, g_gk, g_rk):
+    # the library's own masks
+    lib = p.ctx.periodic_masks(period, d, l1)
+    out2 = p.ctx.ccmm(g_rk, g_gk, g_a, g_b, lib, period)
+    assert np.abs(p.ctx.decrypt(p.g_sk, out2) - (A @ Bm).T).max() < 1e-3
+    with pytest.raises(p.binding.EnsiError, match="code -1"):
+        p.ctx.ccmm(g_rk, g_gk, g_a, g_b, g_masks, 3, out)  # not a power of two
+    for h in (g_a, g_b, g_masks, lib, out, out2, g_gk, g_rk):
         h.free()
     p.close()

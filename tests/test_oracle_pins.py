@@ -474,12 +474,20 @@ def test_replicate_and_ccmm_against_numpy():
     a_cts = [_enc(o, rng, pk, A[:, j], l1) for j in range(d)]
     b_cts = []
     for i in range(m):
-        z = rng.uniform(-1, 1, o.n)  # slots beyond d hold unrelated values
+        z = np.zeros(o.n)  # B[j, i] in slot j, zeros elsewhere
         z[:d] = B[:, i]
         b_cts.append(_enc(o, rng, pk, z, l1))
-    rep = o.replicate(b_cts[1], o.one_hot_masks([2], l1)[0], gks)
-    assert rep.l1 == l1 - 1 and np.abs(o.decrypt(rep, sk) - B[2, 1]).max() < 1e-3
-    C = o.ccmm(a_cts, b_cts, d, rk, gks)
+    # the general extraction: any slot of any ciphertext into every slot
+    zf = rng.uniform(-1, 1, o.n)
+    rep = o.replicate(_enc(o, rng, pk, zf, l1), o.one_hot_masks([5], l1)[0], gks)
+    assert rep.l1 == l1 - 1 and np.abs(o.decrypt(rep, sk) - zf[5]).max() < 1e-3
+    # the two-stage extraction of the matrix product: giant steps make the column periodic, baby steps fill
+    period = 4
+    u = o.spread_periods(b_cts[0], period, gks)
+    assert u.l1 == l1 and np.abs(o.decrypt(u, sk) - np.tile(np.concatenate([B[:, 0], [0.0]]), o.n // period)).max() < 1e-3
+    one = o.extract_from_periodic(u, o.periodic_masks(period, d, l1)[1], period, gks)
+    assert one.l1 == l1 - 1 and np.abs(o.decrypt(one, sk) - B[1, 0]).max() < 1e-3
+    C = o.ccmm(a_cts, b_cts, d, period, rk, gks)
     assert len(C) == m and all(c.l1 == l1 - 2 for c in C)
     for i in range(m):
         assert np.abs(o.decrypt(C[i], sk) - (A @ B)[:, i]).max() < 1e-3

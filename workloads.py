@@ -37,7 +37,7 @@ class Workload:
     act: str = "uniform"  # "uniform" [-1,1] or "normal" N(0,1) clipped to [-4,4]
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
-    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2) or "merge" (block merge of placed outputs)
+    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs) or "ccmm"
 
     @property
     def N(self):
@@ -71,6 +71,10 @@ WORKLOADS.append(Workload("paper1536", 5, 16, 50, 16, 60, 4, 4, 40, tokens=2048,
 # ciphertexts.  Bench/test extras like paper1536.
 WORKLOADS.append(Workload("rope1536", 6, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, act="uniform", op="rope"))
 WORKLOADS.append(Workload("merge1536", 7, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, act="uniform", op="merge"))
+# A slice of the paper's attention-score product (Table III: Q K^T per head, head width 96): A = d_in = 96 column
+# ciphertexts, B = d_out = 8 columns of K^T, one head per ciphertext, tokens filling the slot axis.  The full
+# product has 2048 such columns per head; a step of 8 keeps the benchmark to about a second.
+WORKLOADS.append(Workload("ccmm96", 8, 16, 50, 16, 60, 4, 4, 40, tokens=32768, d_in=96, d_out=8, act="uniform", op="ccmm"))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
