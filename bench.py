@@ -387,6 +387,18 @@ def cpu_baseline(w, budget_s=12.0):
         _, t_one, n1 = repeat(lambda: o.rope(ct, pts, gk, gk_m), budget_s)
         return {"value": n_ct * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
                 "sample": "%d ciphertexts through Alg. 2 (%.3f s each), extrapolated linearly to %d" % (n1, t_one, n_ct)}
+    if w.op == "ccmm":
+        lp = (w.d_in - 1).bit_length()
+        n_el = w.d_in * w.d_out
+        n_rot = n_el * lp + w.d_out * (w.log_n - 1 - lp)
+        _, t_rot, n1 = repeat(lambda: o.rotate(ct, gk), budget_s * 0.5)
+        mask_rns = o.i64_to_rns(o.periodic_masks(1 << lp, 1, pr.L)[0], pr.q)
+        _, t_pm, n2 = repeat(lambda: o.pmult(ct, mask_rns, float(pr.q[-1])), budget_s * 0.2)
+        _, t_ts, n3 = repeat(lambda: o.tensor_sum([(ct, ct)]), budget_s * 0.3)
+        return {"value": (n_rot * t_rot + n_el * (t_pm + t_ts)) * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
+                "sample": "%d rotations (%.3f s each), %d plaintext products (%.3f s), %d tensor products (%.3f s), extrapolated linearly to "
+                          "%d rotations and %d of each product (additions, relinearisations and rescales left out)"
+                          % (n1, t_rot, n2, t_pm, n3, t_ts, n_rot, n_el)}
     if w.op == "merge":
         masks = o.block_masks(w.tokens, 2, pr.L)
         mask_rns = o.i64_to_rns(masks[0], pr.q)

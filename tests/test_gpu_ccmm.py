@@ -140,3 +140,29 @@ def test_ccmm_against_oracle_and_numpy(params, d, m, period):
     for h in (g_a, g_b, g_masks, lib, out, out2, g_gk, g_rk):
         h.free()
     p.close()
+
+
+def test_ccmm_full_ring_at_the_benchmark_parameters():
+    """N = 2^16 with the 16 + 4 limb chain of the ccmm96 benchmark workload (fused key-switch and multiplication
+    kernels), a narrow product (d = 4, one output column) so that the oracle's 13 giant steps, 8 baby steps and
+    4 products take seconds.  Bit-exact against the oracle, and against numpy after decryption."""
+    w = wl.BY_NAME["ccmm96"]
+    p = Pair(w.param_tuple())
+    l1, d, m, period = p.pr.L, 4, 1, 4
+    A = p.rng.uniform(-1, 1, (p.n, d))
+    Bm = p.rng.uniform(-1, 1, (d, m))
+    o_gks, g_gk = doubling_keys(p)
+    o_rk, g_rk = relin_keys(p)
+    zb = np.zeros((m, p.n))
+    zb[:, :d] = Bm.T
+    o_a, g_a = p.encrypt_both(A.T, l1)
+    o_b, g_b = p.encrypt_both(zb, l1)
+    masks = p.o.periodic_masks(period, d, l1)
+    g_masks = p.ctx.pt_set_scale(p.ctx.pt_import(masks, l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.ccmm(g_rk, g_gk, g_a, g_b, g_masks, period)
+    want = p.o.ccmm(o_a, o_b, d, period, o_rk, o_gks)
+    assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - (A @ Bm).T).max() < 1e-3
+    for h in (g_a, g_b, g_masks, out, g_gk, g_rk):
+        h.free()
+    p.close()
