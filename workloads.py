@@ -64,7 +64,7 @@ WORKLOADS = [
              act="normal", kappa=2.0 ** -5),
 ]
 # One of the paper's own PCMM shapes (Table III, QKV projection): 2048 tokens, 1536 x 1536 -- 16 columns per
-# ciphertext, 96 packed inputs, 15 rotation amounts.  Not a BASELINE configuration: a bench/test extra.
+# ciphertext, 96 packed inputs, 15 rotation amounts.  Not one of the five benchmark configurations: a bench/test extra.
 WORKLOADS.append(Workload("paper1536", 5, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
 # The paper's RoPE shape (Table III: 2048 x 96 per head, 16 heads): the 1536 query columns of 2048 tokens, 16 per
 # ciphertext, i.e. 96 ciphertexts; and the merge of that projection's 1536 block-placed outputs into 96 packed
