@@ -126,7 +126,7 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_up_fcols(Ks16Const kc, cons
 }
 
 // ------------------------------------------------------------------ forward row pass (in place)
-// grid (16, beta*ext + l1, n_ct)
+// grid (16 * (beta*ext + l1) * n_ct)
 template <class A>
 __device__ __forceinline__ void frows_body(u64 *g, const u64 *tw, const PrimeConst &pc, u64 *lds, int r0) {
     A ar;
@@ -144,14 +144,16 @@ __device__ __forceinline__ void frows_body(u64 *g, const u64 *tw, const PrimeCon
     for (int i = 0; i < 16; i++) g[tid + 256 * i] = lds[rpad(tid + 256 * i)];
 }
 
-__global__ __launch_bounds__(KS_THREADS) void k_ks16_frows(Ks16Const kc, const PrimeConst *pcs, const u64 *tw_all, u64 *dig) {
+__global__ __launch_bounds__(KS_THREADS) void k_ks16_frows(Ks16Const kc, const PrimeConst *pcs, const u64 *tw_all, u64 *dig, int n_ct) {
     __shared__ u64 lds[4096 + 256];
-    const int R = blockIdx.y, ct = blockIdx.z;
+    // The ciphertext index runs fastest: blocks that share a tile of the twiddle table (same limb, same rows) are
+    // launched together, n_ct / 8 of them on every XCD, and fetch it from memory once per XCD.
+    const int ct = blockIdx.x % n_ct, tile = (blockIdx.x / n_ct) & 15, R = blockIdx.x / (n_ct * 16);
     const int l1 = kc.l1, ext = l1 + kc.K, n_rows = kc.beta * ext + l1;
     const int prime = R < kc.beta * ext ? ks_ext_prime(R % ext, l1, kc.L) : R - kc.beta * ext;
     const PrimeConst pc = pcs[prime];
     const u64 *tw = tw_all + (size_t)prime * 4 * KS_N;
-    const int r0 = blockIdx.x * 16;
+    const int r0 = tile * 16;
     u64 *g = dig + ((size_t)ct * n_rows + R) * KS_N + (size_t)r0 * 256;
     if (pc.pad[0]) frows_body<ArithFp>(g, tw, pc, lds, r0);
     else frows_body<ArithInt>(g, tw, pc, lds, r0);
@@ -435,7 +437,7 @@ void launch_ks16_raise(ensi_ctx *ctx, const Ks16Const &kc, const u64 *ct_base, s
     }
     {
         ScopedTimer t(ctx, "ks_frows", st);
-        hipLaunchKernelGGL(k_ks16_frows, dim3(16, n_rows, n_ct), dim3(KS_THREADS), 0, st, kc, ctx->d_pc, ctx->d_tw, dig);
+        hipLaunchKernelGGL(k_ks16_frows, dim3(16 * n_rows * n_ct), dim3(KS_THREADS), 0, st, kc, ctx->d_pc, ctx->d_tw, dig, n_ct);
     }
 }
 
