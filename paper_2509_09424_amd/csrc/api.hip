@@ -1216,7 +1216,7 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
                         ENSI_HIP(ctx, hipMemcpyAsync(slot, in->d + (size_t)G * in_ct, in_ct * sizeof(u64), hipMemcpyDeviceToDevice, st));
                         continue;
                     }
-                    RotDesc ds;
+                    RotDesc ds = {};
                     ds.c0 = in->d + (size_t)G * in_ct;
                     ds.digits = ctx->ws_digits + (size_t)(G - G0) * rw;
                     ds.key = key_of[rho];
@@ -1720,11 +1720,41 @@ extern "C" int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, e
     return encode_window(ctx, ones.data(), count, 1, 0, 1, limbs, (double)ctx->primes[limbs - 1], out);
 }
 
-// t <- t + Rot(t; r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch (the rotated copy goes
-// through a workspace).
+// t <- t + Rot(t; r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch.  On the fused path the last
+// key-switch kernel adds its result to the source ciphertext directly; otherwise the rotated copy goes through a
+// workspace and is added by a separate kernel.
 static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st) {
-    const int N = ctx->N, n = t->n, l1 = t->limbs;
+    const int N = ctx->N, n = t->n, l1 = t->limbs, ext = l1 + ctx->K;
     int rc;
+    if (ctx->ks16) {
+        const int chunk = std::min(n, rot_chunk());
+        const size_t rw = raised_words(ctx, l1), ct_words = (size_t)2 * t->limbs_alloc * N;
+        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
+        if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 2 * ext * N))) return rc;
+        if ((rc = ensure_desc(ctx, chunk))) return rc;
+        std::vector<RotDesc> desc(chunk);
+        for (int r = r_begin; r < r_end; r *= 2) {
+            const u32 g = galois_element(ctx, r);
+            auto it = gk->keys.find(g);
+            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", r);
+            for (int c0 = 0; c0 < n; c0 += chunk) {
+                const int cnt = std::min(chunk, n - c0);
+                for (int c = 0; c < cnt; c++) {
+                    desc[c].c0 = t->d + (size_t)(c0 + c) * ct_words;
+                    desc[c].digits = ctx->ws_digits + (size_t)c * rw;
+                    desc[c].key = it->second;
+                    desc[c].out = t->d + (size_t)(c0 + c) * ct_words;
+                    desc[c].g = g;
+                    desc[c].g_inv = inv_mod_2n(g, N);
+                    desc[c].accumulate = 1;
+                }
+                ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), cnt * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+                if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
+                if ((rc = run_rotations(ctx, ctx->ws_desc, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
+            }
+        }
+        return ENSI_OK;
+    }
     if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N))) return rc;
     ensi_ct tmp;
     tmp.ctx = ctx;

@@ -115,6 +115,8 @@ struct RotDesc {
     u64 *out;           // destination ciphertext: [2][limb_stride_out][N]
     u32 g;              // Galois element
     u32 g_inv;          // its inverse mod 2N
+    u32 accumulate;     // fused N = 2^16 kernels only: add the result to what `out` holds instead of overwriting it
+    u32 pad;
 };
 
 // Everything about one ternary_matmul that depends only on (W, s, d, m, placement).

@@ -399,6 +399,17 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, co
             }
         }
     }
+    if (desc[rot].accumulate) {
+        // out <- out + result: `out` may be the rotation's own source (every read of the source happened in the
+        // raise kernels, which have finished), which turns t <- t + Rot(t; r) into one pass
+        const u64 q = pc.q;
+#pragma unroll
+        for (int i = 0; i < 16; i++) {
+            u64 *o = out + (size_t)(jj + 16 * i) * 256;
+            *o = add_mod(*o, ar.canon(v[i]), q);
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 16; i++) out[(size_t)(jj + 16 * i) * 256] = ar.canon(v[i]);
 }
