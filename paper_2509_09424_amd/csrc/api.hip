@@ -1731,28 +1731,34 @@ static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_be
         const size_t rw = raised_words(ctx, l1), ct_words = (size_t)2 * t->limbs_alloc * N;
         if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
         if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 2 * ext * N))) return rc;
-        if ((rc = ensure_desc(ctx, chunk))) return rc;
-        std::vector<RotDesc> desc(chunk);
+        // the descriptors of all steps go up in one copy: step k, ciphertext c at index k * n + c
+        std::vector<RotDesc> desc;
         for (int r = r_begin; r < r_end; r *= 2) {
             const u32 g = galois_element(ctx, r);
             auto it = gk->keys.find(g);
             if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", r);
-            for (int c0 = 0; c0 < n; c0 += chunk) {
-                const int cnt = std::min(chunk, n - c0);
-                for (int c = 0; c < cnt; c++) {
-                    desc[c].c0 = t->d + (size_t)(c0 + c) * ct_words;
-                    desc[c].digits = ctx->ws_digits + (size_t)c * rw;
-                    desc[c].key = it->second;
-                    desc[c].out = t->d + (size_t)(c0 + c) * ct_words;
-                    desc[c].g = g;
-                    desc[c].g_inv = inv_mod_2n(g, N);
-                    desc[c].accumulate = 1;
-                }
-                ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), cnt * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-                if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
-                if ((rc = run_rotations(ctx, ctx->ws_desc, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
+            for (int c = 0; c < n; c++) {
+                RotDesc d = {};
+                d.c0 = t->d + (size_t)c * ct_words;
+                d.digits = ctx->ws_digits + (size_t)(c % chunk) * rw;
+                d.key = it->second;
+                d.out = t->d + (size_t)c * ct_words;
+                d.g = g;
+                d.g_inv = inv_mod_2n(g, N);
+                d.accumulate = 1;
+                desc.push_back(d);
             }
         }
+        if (desc.empty()) return ENSI_OK;
+        if ((rc = ensure_desc(ctx, desc.size()))) return rc;
+        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        const int n_steps = (int)(desc.size() / n);
+        for (int k = 0; k < n_steps; k++)
+            for (int c0 = 0; c0 < n; c0 += chunk) {
+                const int cnt = std::min(chunk, n - c0);
+                if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
+                if ((rc = run_rotations(ctx, ctx->ws_desc + (size_t)k * n + c0, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
+            }
         return ENSI_OK;
     }
     if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N))) return rc;
