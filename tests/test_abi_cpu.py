@@ -36,3 +36,25 @@ def test_error_codes_and_null_handling_without_gpu():
     bad = binding._Params(3, 50, 2, 60, 1, 1, 40, 0)  # log_n below the supported range
     h = ctypes.c_void_p()
     assert lib.ensi_ctx_create(ctypes.byref(bad), ctypes.byref(h)) == -1 and not h.value
+
+
+def test_null_arguments_of_the_later_entry_points_without_gpu():
+    """Every entry point rejects null handles before it touches the device."""
+    lib = binding.load()
+    n = None
+    d = ctypes.c_double
+    assert lib.ensi_pt_set_scale(n, d(1.0)) == -1
+    assert lib.ensi_ct_drop_limbs(n, 1) == -1
+    assert lib.ensi_encode_at(n, n, 1, 1, 1, d(2.0), n) == -1
+    assert lib.ensi_pmult_sum_rescale(n, n, n, n, n, n, 1, n, n) == -1
+    assert lib.ensi_set_pmult_mode(n, 0) == -1
+    assert lib.ensi_block_masks(n, 1, 1, 2, n) == -1
+    assert lib.ensi_merge(n, n, n, 1, n, n) == -1
+    assert lib.ensi_rope_plaintexts(n, n, n, 1, 2, n) == -1
+    assert lib.ensi_rope(n, n, n, n, n, n) == -1
+    assert lib.ensi_relin_keygen(n, n, n, ctypes.c_uint64(0), n) == -1
+    assert lib.ensi_mult_sum_relin_rescale(n, n, n, n, n, n, n, 1, n, n) == -1
+    assert lib.ensi_one_hot_masks(n, 1, 2, n) == -1
+    assert lib.ensi_periodic_masks(n, 2, 1, 2, n) == -1
+    assert lib.ensi_replicate(n, n, n, n, n, n, 1, n, n) == -1
+    assert lib.ensi_ccmm(n, n, n, n, n, n, 2, n, n) == -1
