@@ -28,14 +28,15 @@ def sample_positions(N):
     return np.concatenate([np.arange(0, 192), np.arange(N // 2 - 64, N // 2 + 64), np.arange(N - 192, N)])
 
 
-def test_ffn_rescale_and_down_projection_full_size():
-    """FFN workload, second half: 6912 ciphertexts at 16 limbs are multiplied by kappa and
-    rescaled, then contracted with the 6912 x 2560 ternary matrix (zero placement, one column
-    per ciphertext).  Inputs are synthetic residue words (not encryptions: parity is on RNS
-    words), generated identically by torch on the device and numpy on the host."""
+@pytest.mark.parametrize("name", ["ffn2560", "paperffn"])
+def test_ffn_rescale_and_down_projection_full_size(name):
+    """FFN workloads, second half: the d_mid ciphertexts at 16 limbs (6912 for the BitNet shape, 4096 for the
+    paper's) are multiplied by kappa and rescaled, then contracted with the d_mid x d_out ternary matrix (zero
+    placement, one column per ciphertext).  Inputs are synthetic residue words (not encryptions: parity is on
+    RNS words), generated identically by torch on the device and numpy on the host."""
     import torch
     from paper_2509_09424_amd import binding
-    w = wl.BY_NAME["ffn2560"]
+    w = wl.BY_NAME[name]
     rng = wl.rng_for(w.index)
     wl.ternary_weights(rng, w.d_in, w.d_mid)  # same draw order as the benchmark
     wl.activations(rng, w.tokens, w.d_in, w.act)
@@ -85,7 +86,7 @@ def test_ffn_rescale_and_down_projection_full_size():
 
         # the rescaled operands themselves (a sample of them, read back from the device buffer)
         mid_view = mid_t.view(d, 2, L, N)
-        for v in (0, 1, 3455, d - 1):
+        for v in (0, 1, d // 2 - 1, d - 1):
             got = mid_view[v, :, :L - 1, :].cpu().numpy().astype(np.uint64)[:, :, pos]
             assert np.array_equal(got, resc[v]), "rescaled operand %d" % v
 
@@ -94,7 +95,7 @@ def test_ffn_rescale_and_down_projection_full_size():
         assert o_s.N == S
         n_o, limbs_o, scale_o, base_o = out._info()
         ct_words = 2 * limbs_o * N
-        for i in (0, 255, 256, 1279, m - 1):
+        for i in (0, 255, 256, m // 2 - 1, m - 1):
             one = ctx.ct_wrap(int(base_o) + 8 * ct_words * i, 1, limbs_o, scale_o)
             got = one.export()[0][:, :, pos]
             one.free()

@@ -75,6 +75,10 @@ WORKLOADS.append(Workload("merge1536", 7, 16, 50, 16, 60, 4, 4, 40, tokens=2048,
 # ciphertexts, B = d_out = 8 columns of K^T, one head per ciphertext, tokens filling the slot axis.  The full
 # product has 2048 such columns per head; a step of 8 keeps the benchmark to about a second.
 WORKLOADS.append(Workload("ccmm96", 8, 16, 50, 16, 60, 4, 4, 40, tokens=32768, d_in=96, d_out=8, act="uniform", op="ccmm"))
+# The paper's feed-forward shape (Table III: 2048 x 1536 -> 4096 -> 1536), run like ffn2560: 16 columns per input
+# ciphertext, first layer placed in block 0, scalar-multiply + rescale, rotation-free second layer.
+WORKLOADS.append(Workload("paperffn", 9, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, d_out=1536, d_mid=4096, placement="zero",
+                          act="normal", kappa=2.0 ** -5))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
