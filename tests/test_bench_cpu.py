@@ -1,0 +1,47 @@
+"""No-GPU checks of the benchmark's host logic: the algorithmic byte / operation counts behind the roofline
+entries, for every workload shape, against counts written out by hand."""
+import bench
+import workloads as wl
+
+
+def test_every_workload_has_a_roofline_entry_for_each_kernel_class():
+    classes = ["ks_pre", "ks_modup_fcols", "ks_frows", "ks_inner_irows", "ks_inner_irows_wide", "ks_icols_special",
+               "ks_icols_moddown", "byte_planes", "pm_fcols", "pm_frows_mac_irows", "pm_icols_last", "pm_icols_rescale"]
+    for w in wl.WORKLOADS:
+        if w.log_n != 16:
+            continue
+        for c in classes:
+            dom, roof = bench.roofline_for(w, {c: (1.0, 1)})
+            assert dom == c and roof["bound"] == "hbm" and roof["peak"] == 8000.0
+            assert roof["achieved"] >= 0.0 and abs(roof["frac"] - roof["achieved"] / 8000.0) < 1e-12
+
+
+def test_key_switch_counts_of_the_microbenchmark():
+    w = wl.BY_NAME["keyswitch"]  # 64 rotations, L = 10, K = 3, alpha = 3 -> beta = 4, ext = 13
+    unit = 8.0 * w.N
+    _, roof = bench.roofline_for(w, {"ks_frows": (1.0, 1)})
+    assert abs(roof["achieved"] - 64 * 2 * (4 * 13 + 10) * unit / 1e-3 / 1e9) < 1e-6  # digits and P*c0 in and out
+    _, roof = bench.roofline_for(w, {"ks_inner_irows": (2.0, 1)})
+    units = 64 * (4 * 10 + 10 + 2 * 10) + 64 * 2 * 4 * 10  # digits, P*c0, accumulators; one key per rotation
+    assert abs(roof["achieved"] - units * unit / 2e-3 / 1e9) < 1e-6
+    assert bench.stagewise_rotation_units(w) == 486
+
+
+def test_matrix_core_operation_count():
+    w = wl.BY_NAME["ffn2560"]
+    _, roof = bench.roofline_for(w, {"accumulate_mfma": (100.0, 9)})
+    ops = 2.0 * (2560 * 6912 + 6912 * 2560) * 2 * 16 * 65536 * 7  # outputs x operands x limb words x byte planes
+    assert roof["bound"] == "mfma" and roof["peak"] == 5000.0
+    assert abs(roof["achieved"] - ops / 0.1 / 1e12) < 1e-6 and roof["launches"] == 9
+
+
+def test_plaintext_multiplication_counts():
+    w = wl.BY_NAME["merge1536"]  # 1536 products into 96 outputs at 16 limbs
+    unit = 8.0 * w.N
+    _, roof = bench.roofline_for(w, {"pm_frows_mac_irows": (1.0, 3)})
+    assert abs(roof["achieved"] - (1536 + 96) * 2 * 16 * unit / 1e-3 / 1e9) < 1e-6
+    w = wl.BY_NAME["rope1536"]  # 96 ciphertexts: 3 products each, 2 rotations sharing one raise
+    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 3)})
+    assert abs(roof["achieved"] - 3 * 96 * 4 * 16 * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 3)})
+    assert abs(roof["achieved"] - 96 * 2 * 16 * unit / 1e-3 / 1e9) < 1e-6
