@@ -108,7 +108,10 @@ def test_pmult_errors(full):
     low = p.ctx.ct_import(np.zeros((1, 2, 1, p.N), dtype=np.uint64), 1.0)
     with pytest.raises(p.binding.EnsiError, match="code -3"):
         p.ctx.pmult_sum_rescale(low, g_pt, [0, 1], [0], [0], bad)  # no limb left to drop
-    for h in (g_ct, g_pt, bad, low):
+    # a call whose every output is empty: zero ciphertexts, nothing read
+    none = p.ctx.pmult_sum_rescale(g_ct, g_pt, [0, 0, 0], [], [])
+    assert none.n == 2 and none.limbs == 2 and not none.export().any()
+    for h in (g_ct, g_pt, bad, low, none):
         h.free()
 
 
@@ -188,6 +191,22 @@ def test_rope_small_ring(params, l1):
     for h in (g_ct, g_pt, lib_pt, out, out2, g_gk):
         h.free()
     p.close()
+
+
+def test_rope_single_ciphertext_full_ring(full):
+    """The smallest batch: one ciphertext, one group, at the top level of the parameter set."""
+    p = full
+    l1 = p.pr.L
+    x, cos, sin, want = rope_case(p, 1, l1, 53)
+    o_gks, g_gk = p.galois_keys([1, -1])
+    o_cts, g_ct = p.encrypt_both(x, l1)
+    pts = p.o.rope_plaintexts(cos, sin, l1)
+    g_pt = p.ctx.pt_set_scale(p.ctx.pt_import(pts, l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.rope(g_gk, g_ct, g_pt)
+    assert np.array_equal(out.export()[0], p.o.rope(o_cts[0], pts, o_gks[1], o_gks[-1]).limbs())
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - want).max() < 1e-3
+    for h in (g_ct, g_pt, out, g_gk):
+        h.free()
 
 
 def test_rope_full_ring(full):
