@@ -1411,7 +1411,10 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms, const std
 
     // groups of outputs: at most 8 GiB of transformed sources, at least one output
     const size_t term_words = (size_t)2 * l1 * N;
-    const int max_terms = (int)std::max<size_t>(1, ((size_t)1 << 30) / term_words);
+    // a group's terms index one grid dimension of the transform kernels (at most 65535)
+    const int max_terms = (int)std::min<size_t>(65535, std::max<size_t>(1, ((size_t)1 << 30) / term_words));
+    for (int o = 0; o < n_out; o++)
+        if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
     std::vector<int> cut(1, 0);
     size_t need_a = 1, need_b = 0;
     for (int o0 = 0; o0 < n_out;) {
@@ -1611,7 +1614,9 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     if (out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the operands (%d vs %d limbs)", out->limbs, l1);
     if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_out);
     const size_t term_words = (size_t)4 * l1 * N;
-    const int max_terms = (int)std::max<size_t>(1, ((size_t)1 << 30) / term_words);
+    const int max_terms = (int)std::min<size_t>(65535, std::max<size_t>(1, ((size_t)1 << 30) / term_words));
+    for (int o = 0; o < n_out; o++)
+        if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
     const int max_out = ctx->ks16 ? rot_chunk() : 64;
     std::vector<int> cut(1, 0);
     size_t need_a = 1, need_o = 0;
