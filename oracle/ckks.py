@@ -635,3 +635,41 @@ class Oracle:
             reps = [self.extract_from_periodic(u, masks[j], period, gks) for j in range(d)]
             out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a_cts[j], l1 - 1), reps[j]) for j in range(d)], rk))
         return out
+
+    # ------------------------------------------- CCMM with several heads per ciphertext
+    def block_start_mask(self, s, l1):
+        """Integer coefficients [N] of the mask with a 1 in the first slot of every block of s slots, at scale q_l."""
+        z = np.zeros(self.n)
+        z[::s] = 1.0
+        return self.encode_coeffs(z, float(self.pr.q[l1 - 1]))
+
+    def extract_blockwise(self, ct, i, s, mask0, gks):
+        """Element extraction when a ciphertext packs one block of s slots per head: slot i of every
+        block is copied into all s slots of its block.  Rot(.; i) brings it to the block's first
+        slot, the block-start mask keeps it (PMult, one rescale), and log2(s) steps
+        t <- t + Rot(t; -r), r = 1, 2, ..., s/2 fill the block upwards without touching the next one.
+        gks: dict step -> Galois key, with the steps i and -2^k."""
+        l1 = ct.l1
+        ql = float(self.pr.q[l1 - 1])
+        t = self.rotate(ct, gks[i]) if i else ct
+        t = self.pmult_sum_rescale([(t, self.i64_to_rns(mask0, self.pr.q[:l1]))], ql)
+        r = 1
+        while r < s:
+            t = self.add_ct(t, self.rotate(t, gks[-r]))
+            r *= 2
+        return t
+
+    def ccmm_blocks(self, a_cts, b_cts, s, cols, rk, gks):
+        """C_h = A_h B_h for all heads h at once (CCMM section, the column-encoded by row-encoded
+        form): ciphertext j of A holds column j of every A_h (head h in slot block h, s tokens), and
+        ciphertext j of B holds, in slot h s + i, the entry B_h[j, i] -- i.e. B^T column-encoded,
+        as K is for Q K^T.  Output column i (one ciphertext, block h = column i of C_h) is
+        sum_j a_j (x) b^(j,i) with b^(j,i) the block-wise replication of slot i of b_j.  cols: the
+        output columns to compute.  Two levels (mask, product)."""
+        l1 = b_cts[0].l1
+        mask0 = self.block_start_mask(s, l1)
+        out = []
+        for i in cols:
+            reps = [self.extract_blockwise(b, i, s, mask0, gks) for b in b_cts]
+            out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a, l1 - 1), r) for a, r in zip(a_cts, reps)], rk))
+        return out

@@ -493,6 +493,34 @@ def test_replicate_and_ccmm_against_numpy():
         assert np.abs(o.decrypt(C[i], sk) - (A @ B)[:, i]).max() < 1e-3
 
 
+def test_blockwise_extraction_and_ccmm_over_heads():
+    """Several heads per ciphertext: Q_h K_h^T for every head at once against numpy."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 6)  # 32 slots: 4 heads of 8 tokens
+    o = Oracle(pr)
+    rng = np.random.default_rng(79)
+    sk, pk = _keys(o, rng)
+    l1, s, heads, d = 4, 8, 4, 3
+    Q = rng.uniform(-1, 1, (heads, s, d))
+    K = rng.uniform(-1, 1, (heads, s, d))
+    a_cts = [_enc(o, rng, pk, np.concatenate([Q[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    b_cts = [_enc(o, rng, pk, np.concatenate([K[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    beta = pr.beta(pr.L)
+    cols = [0, 3, 7]
+    steps = [c for c in cols if c] + [-1, -2, -4]
+    gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 83) for st in steps}
+    rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 89)
+    mask0 = o.block_start_mask(s, l1)
+    rep = o.extract_blockwise(b_cts[1], 3, s, mask0, gks)
+    want = np.concatenate([np.full(s, K[h][3, 1]) for h in range(heads)])
+    assert rep.l1 == l1 - 1 and np.abs(o.decrypt(rep, sk) - want).max() < 1e-3
+    C = o.ccmm_blocks(a_cts, b_cts, s, cols, rk, gks)
+    assert len(C) == len(cols) and all(c.l1 == l1 - 2 for c in C)
+    for c, i in zip(C, cols):
+        ref = np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)])
+        assert np.abs(o.decrypt(c, sk) - ref).max() < 1e-3, i
+
+
 # -------------------------------------------------------------------- PCMM
 def _read_toy():
     W, Y = [], {}
