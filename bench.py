@@ -100,6 +100,27 @@ class Runner:
             self.pt = self.ctx.periodic_masks(self.period, d, self.L)
             self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
             return
+        if w.op == "ccmm_blocks":
+            # Q K^T for every head: ciphertext j holds column j of all heads (head h in block h)
+            d, m, sl = w.d_in, w.d_out, w.tokens
+            heads = self.n // sl
+            self.Q = rng.uniform(-1.0, 1.0, size=(heads, sl, d))
+            self.K = rng.uniform(-1.0, 1.0, size=(heads, sl, d))
+            za = np.stack([np.concatenate([self.Q[h][:, j] for h in range(heads)]) for j in range(d)])
+            zb = np.stack([np.concatenate([self.K[h][:, j] for h in range(heads)]) for j in range(d)])
+            pt = self.ctx.encode(za, self.L)
+            self.ct_a = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            pt = self.ctx.encode(zb, self.L)
+            self.ct_in = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            self.cols = list(range(m))
+            steps = [c for c in self.cols if c] + [-(1 << k) for k in range(sl.bit_length() - 1)]
+            self.gk = self.ctx.galois_keygen(self.sk, steps, None, 13)
+            self.rk = self.ctx.relin_keygen(self.sk, None, 17)
+            self.pt = self.ctx.block_start_mask(sl, self.L)
+            self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
+            return
         if w.op == "merge":
             # d_in block-placed outputs: one group of c_tot encrypted columns, repeated for every packed output
             import torch
@@ -155,6 +176,9 @@ class Runner:
         if w.op == "ccmm":
             self.ctx.ccmm(self.rk, self.gk, self.ct_a, self.ct_in, self.pt, self.period, self.ct_out)
             return
+        if w.op == "ccmm_blocks":
+            self.ctx.ccmm_blocks(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, self.cols, self.pt, self.ct_out)
+            return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
@@ -189,6 +213,11 @@ class Runner:
         if w.op == "ccmm":
             dec = self.ctx.decrypt(self.sk, self.ct_out)
             return float(np.abs(dec - (self.A @ self.B).T).max())
+        if w.op == "ccmm_blocks":
+            dec = self.ctx.decrypt(self.sk, self.ct_out)
+            heads = self.n // w.tokens
+            ref = np.stack([np.concatenate([(self.Q[h] @ self.K[h].T)[:, i] for h in range(heads)]) for i in self.cols])
+            return float(np.abs(dec - ref).max())
         ref = self.X @ self.W.astype(np.float64)
         out = self.ct_out
         if w.d_mid:
@@ -261,6 +290,18 @@ def roofline_for(w, prof):
     elif w.op == "merge":
         n_rot = n_raise = n_key = 0
         pm_terms, pm_out = w.d_in, -(-w.d_in // w.c_tot)
+    elif w.op == "ccmm_blocks":
+        # per element: one aligning rotation (the raise shared by all columns of a ciphertext of B), one mask product and
+        # log2(s) fill steps one level down; per output one relinearisation
+        n_el = w.d_in * w.d_out
+        lp = w.tokens.bit_length() - 1
+        L = L - 1
+        ext = L + K
+        beta = -(-L // alpha)
+        n_rot = n_el * (1 + lp) + w.d_out
+        n_raise = w.d_in + n_el * lp + w.d_out
+        n_key = -(-w.d_in // 16) * w.d_out + lp * -(-n_el // 64) + 1
+        pm_terms = pm_out = n_el
     elif w.op == "ccmm":
         # every element of B: one mask product and log2(period) rotate-and-add steps one level down (the log2(n/period)
         # steps per column at the top level and the relinearisations are few and counted with them)
@@ -387,10 +428,14 @@ def cpu_baseline(w, budget_s=12.0):
         _, t_one, n1 = repeat(lambda: o.rope(ct, pts, gk, gk_m), budget_s)
         return {"value": n_ct * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
                 "sample": "%d ciphertexts through Alg. 2 (%.3f s each), extrapolated linearly to %d" % (n1, t_one, n_ct)}
-    if w.op == "ccmm":
-        lp = (w.d_in - 1).bit_length()
+    if w.op in ("ccmm", "ccmm_blocks"):
         n_el = w.d_in * w.d_out
-        n_rot = n_el * lp + w.d_out * (w.log_n - 1 - lp)
+        if w.op == "ccmm":
+            lp = (w.d_in - 1).bit_length()
+            n_rot = n_el * lp + w.d_out * (w.log_n - 1 - lp)
+        else:
+            lp = w.tokens.bit_length() - 1
+            n_rot = n_el * (1 + lp)
         _, t_rot, n1 = repeat(lambda: o.rotate(ct, gk), budget_s * 0.5)
         mask_rns = o.i64_to_rns(o.periodic_masks(1 << lp, 1, pr.L)[0], pr.q)
         _, t_pm, n2 = repeat(lambda: o.pmult(ct, mask_rns, float(pr.q[-1])), budget_s * 0.2)

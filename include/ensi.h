@@ -263,6 +263,19 @@ int ensi_periodic_masks(ensi_ctx *ctx, int32_t period, int32_t count, int32_t li
 int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
               int32_t period, ensi_ct *out, void *stream);
 
+/* The same product with several heads per ciphertext (the column-encoded by row-encoded form of the CCMM section,
+ * e.g. Q K^T): ciphertext j of A holds column j of every A_h, head h in slot block h (s slots per block, s a power
+ * of two); ciphertext j of B holds B_h[j][i] in slot h s + i (i.e. B^T column-encoded, as K is).  Output c holds,
+ * in block h, column cols[c] of C_h = A_h B_h:  out_c = Rescale(Relin(sum_j a_j (x) b^(j, cols[c]))), where
+ * b^(j, i) is slot i of every block of b_j copied into all s slots of its block: Rot(b_j; i) brings it to the block's
+ * first slot (one ModUp per b_j serves all i), the block-start mask keeps it (one product, one rescale), and log2(s)
+ * steps t <- t + Rot(t; -r), r = 1, 2, ..., s/2 fill the block upwards.  gk must hold keys for the steps cols[c] and
+ * -2^k (k < log2 s); mask: one plaintext from ensi_block_start_mask(s, limbs = l).  A, B: d ciphertexts each at l
+ * limbs; out: n_cols ciphertexts at l - 2 limbs. */
+int ensi_block_start_mask(ensi_ctx *ctx, int32_t s, int32_t limbs, ensi_pt **pt);
+int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
+                     const int32_t *cols, int32_t n_cols, const ensi_pt *mask, ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

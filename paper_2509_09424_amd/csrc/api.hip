@@ -1725,10 +1725,10 @@ extern "C" int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, e
     return encode_window(ctx, ones.data(), count, 1, 0, 1, limbs, (double)ctx->primes[limbs - 1], out);
 }
 
-// t <- t + Rot(t; r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch.  On the fused path the last
+// t <- t + Rot(t; sign * r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch.  On the fused path the last
 // key-switch kernel adds its result to the source ciphertext directly; otherwise the rotated copy goes through a
 // workspace and is added by a separate kernel.
-static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st) {
+static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st, int sign = 1) {
     const int N = ctx->N, n = t->n, l1 = t->limbs, ext = l1 + ctx->K;
     int rc;
     if (ctx->ks16) {
@@ -1739,9 +1739,9 @@ static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_be
         // the descriptors of all steps go up in one copy: step k, ciphertext c at index k * n + c
         std::vector<RotDesc> desc;
         for (int r = r_begin; r < r_end; r *= 2) {
-            const u32 g = galois_element(ctx, r);
+            const u32 g = galois_element(ctx, sign * r);
             auto it = gk->keys.find(g);
-            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", r);
+            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", sign * r);
             for (int c = 0; c < n; c++) {
                 RotDesc d = {};
                 d.c0 = t->d + (size_t)c * ct_words;
@@ -1776,7 +1776,7 @@ static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_be
     tmp.owns = false;
     std::vector<int32_t> steps(n);
     for (int r = r_begin; r < r_end; r *= 2) {
-        std::fill(steps.begin(), steps.end(), r);
+        std::fill(steps.begin(), steps.end(), sign * r);
         if ((rc = ensi_rotate(ctx, gk, t, steps.data(), &tmp, (void *)st))) return rc;
         launch_ct_add(ctx, t->d, t->limbs_alloc, tmp.d, l1, l1, n, st);
     }
@@ -1887,6 +1887,129 @@ extern "C" int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, co
         if ((rc = mask_rescale(ctx, &u, src, masks, mi, &rep, st))) return rc;
         if ((rc = doubling_steps(ctx, gk, &rep, 1, period, st))) return rc;
         // c_i = sum_j a_j (x) rep_(i,j); a_j is read at the level of the replicated elements (its last limb dropped)
+        std::vector<MmTerm> terms(cnt * d);
+        std::vector<int32_t> begin(cnt + 1);
+        for (int c = 0; c < cnt; c++) {
+            begin[c] = c * d;
+            for (int j = 0; j < d; j++) terms[c * d + j] = {A->d + (size_t)j * a_ct, rep.d + (size_t)(c * d + j) * 2 * lo * N};
+        }
+        begin[cnt] = cnt * d;
+        ensi_ct part = *out;
+        part.owns = false;
+        part.d = out->d + (size_t)i0 * out_ct;
+        part.n = cnt;
+        if ((rc = mult_core(ctx, key, terms, begin, lo, A->limbs_alloc, lo, &part, st))) return rc;
+        out->scale = A->scale * rep.scale / (double)ctx->primes[lo - 1];
+    }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// --------------------------------------------- CCMM, several heads per ciphertext
+extern "C" int ensi_block_start_mask(ensi_ctx *ctx, int32_t s, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !out || s < 1 || (s & (s - 1)) || s > ctx->N / 2 || limbs < 2 || limbs > ctx->L) return ENSI_E_BADARG;
+    const int n = ctx->N / 2;
+    std::vector<double> z(n, 0.0);
+    for (int p = 0; p < n; p += s) z[p] = 1.0;
+    return encode_window(ctx, z.data(), 1, n, 0, 0, limbs, (double)ctx->primes[limbs - 1], out);
+}
+
+// out[c * d + j] = Rot(B_j; cols[c]) for c < cnt, j < d: the d ciphertexts of B are raised in groups of up to 16 and
+// every group serves all its rotations (rotations by the same amount, hence the same key, are neighbours).  A
+// column index 0 is a plain copy.  out: cnt * d ciphertexts at limb stride l1.
+static int rotate_columns(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *B, const int32_t *cols, int cnt, u64 *out, hipStream_t st) {
+    const int N = ctx->N, d = B->n, l1 = B->limbs, ext = l1 + ctx->K;
+    const size_t b_ct = (size_t)2 * B->limbs_alloc * N, o_ct = (size_t)2 * l1 * N, rw = raised_words(ctx, l1);
+    const int GS = std::min(d, 16), per = std::max(1, rot_chunk() * 2 / GS);  // rotation amounts per launch
+    int rc;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)GS * rw))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)GS * per * 2 * ext * N))) return rc;
+    if ((rc = ensure_desc(ctx, (size_t)GS * per))) return rc;
+    std::vector<const u64 *> key(cnt, nullptr);
+    std::vector<u32> gel(cnt, 1);
+    for (int c = 0; c < cnt; c++) {
+        if (cols[c] == 0) continue;
+        gel[c] = galois_element(ctx, cols[c]);
+        auto it = gk->keys.find(gel[c]);
+        if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", cols[c]);
+        key[c] = it->second;
+    }
+    for (int j0 = 0; j0 < d; j0 += GS) {
+        const int gs = std::min(GS, d - j0);
+        bool raised = false;
+        for (int c0 = 0; c0 < cnt; c0 += per) {
+            std::vector<RotDesc> desc;
+            for (int c = c0; c < std::min(cnt, c0 + per); c++)
+                for (int j = 0; j < gs; j++) {
+                    u64 *dst = out + (size_t)(c * d + j0 + j) * o_ct;
+                    const u64 *src = B->d + (size_t)(j0 + j) * b_ct;
+                    if (cols[c] == 0) {
+                        for (int poly = 0; poly < 2; poly++)
+                            ENSI_HIP(ctx, hipMemcpyAsync(dst + (size_t)poly * l1 * N, src + (size_t)poly * B->limbs_alloc * N, (size_t)l1 * N * 8,
+                                                         hipMemcpyDeviceToDevice, st));
+                        continue;
+                    }
+                    RotDesc r = {};
+                    r.c0 = src;
+                    r.digits = ctx->ws_digits + (size_t)j * rw;
+                    r.key = key[c];
+                    r.out = dst;
+                    r.g = gel[c];
+                    r.g_inv = inv_mod_2n(gel[c], N);
+                    desc.push_back(r);
+                }
+            if (desc.empty()) continue;
+            if (!raised) {
+                if ((rc = raise_cts(ctx, l1, B->d + (size_t)j0 * b_ct, b_ct, B->limbs_alloc, gs, st))) return rc;
+                raised = true;
+            }
+            ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+            if ((rc = run_rotations(ctx, ctx->ws_desc, (int)desc.size(), l1, B->limbs_alloc, l1, st))) return rc;
+        }
+    }
+    return ENSI_OK;
+}
+
+extern "C" int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
+                                const int32_t *cols, int32_t n_cols, const ensi_pt *mask, ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !gk || !A || !B || !cols || !mask || !out || n_cols < 1) return ENSI_E_BADARG;
+    const int N = ctx->N, d = A->n, l1 = B->limbs;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
+    if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
+    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    if (l1 < 3 || out->limbs != l1 - 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be two levels below the operands");
+    if (out->n != n_cols) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, n_cols);
+    for (int c = 0; c < n_cols; c++)
+        if (cols[c] < 0 || cols[c] >= s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: output column %d outside a block of %d", cols[c], s);
+    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int lo = l1 - 1;
+    const int per = std::max(1, std::min((int)n_cols, 512 / d));
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, (size_t)per * d * 2 * l1 * N))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (size_t)per * d * 2 * lo * N))) return rc;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    for (int i0 = 0; i0 < n_cols; i0 += per) {
+        const int cnt = std::min(per, n_cols - i0);
+        // slot i of every block to the block's first slot
+        if ((rc = rotate_columns(ctx, gk, B, cols + i0, cnt, ctx->ws_rot, st))) return rc;
+        ensi_ct al;
+        al.ctx = ctx;
+        al.n = cnt * d;
+        al.limbs = al.limbs_alloc = l1;
+        al.scale = B->scale;
+        al.d = ctx->ws_rot;
+        al.owns = false;
+        // keep the block starts, then fill every block upwards
+        ensi_ct rep = al;
+        rep.limbs = rep.limbs_alloc = lo;
+        rep.d = ctx->ws_rep;
+        std::vector<int32_t> src(cnt * d), mi(cnt * d, 0);
+        for (int k = 0; k < cnt * d; k++) src[k] = k;
+        if ((rc = mask_rescale(ctx, &al, src, mask, mi, &rep, st))) return rc;
+        if ((rc = doubling_steps(ctx, gk, &rep, 1, s, st, -1))) return rc;
         std::vector<MmTerm> terms(cnt * d);
         std::vector<int32_t> begin(cnt + 1);
         for (int c = 0; c < cnt; c++) {

@@ -166,3 +166,59 @@ def test_ccmm_full_ring_at_the_benchmark_parameters():
     for h in (g_a, g_b, g_masks, out, g_gk, g_rk):
         h.free()
     p.close()
+
+
+def heads_case(p, l1, s, d, cols):
+    heads = p.n // s
+    Q = p.rng.uniform(-1, 1, (heads, s, d))
+    K = p.rng.uniform(-1, 1, (heads, s, d))
+    za = np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)])
+    zb = np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)])
+    o_a, g_a = p.encrypt_both(za, l1)
+    o_b, g_b = p.encrypt_both(zb, l1)
+    steps = sorted(set(c for c in cols if c)) + [-(1 << k) for k in range(s.bit_length() - 1)]
+    o_gks, g_gk = p.galois_keys(steps)
+    ref = np.stack([np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)]) for i in cols])
+    return o_a, g_a, o_b, g_b, o_gks, g_gk, ref
+
+
+@pytest.mark.parametrize("params,l1,s,d,cols", [(SMALL4, 6, 64, 5, [0, 1, 63]), (SMALL4, 4, 512, 3, [7]), (WIDE, 4, 128, 18, [5, 0])],
+                         ids=["8-heads", "one-head", "wide-primes-two-groups"])
+def test_ccmm_blocks_small_ring(params, l1, s, d, cols):
+    """Several heads per ciphertext (Q K^T form): bit-exact against the oracle, numpy after decryption."""
+    p = Pair(params)
+    o_a, g_a, o_b, g_b, o_gks, g_gk, ref = heads_case(p, l1, s, d, cols)
+    o_rk, g_rk = relin_keys(p)
+    mask0 = p.o.block_start_mask(s, l1)
+    g_mask = p.ctx.pt_set_scale(p.ctx.pt_import(mask0[None, :], l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, cols, g_mask)
+    want = p.o.ccmm_blocks(o_a, o_b, s, cols, o_rk, o_gks)
+    assert out.n == len(cols) and out.limbs == l1 - 2
+    assert np.array_equal(out.export(), stack_cts(want))
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    lib = p.ctx.block_start_mask(s, l1)
+    out2 = p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, cols, lib)
+    assert np.abs(p.ctx.decrypt(p.g_sk, out2) - ref).max() < 1e-3
+    with pytest.raises(p.binding.EnsiError, match="code -1"):
+        p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, [s], g_mask, out2 if len(cols) == 1 else None)  # column outside the block
+    for h in (g_a, g_b, g_mask, lib, out, out2, g_gk, g_rk):
+        h.free()
+    p.close()
+
+
+def test_ccmm_blocks_full_ring():
+    """N = 2^16 (fused kernels), 16 heads of 2048 tokens as in the paper's attention shape, a narrow inner
+    dimension and a low level so that the oracle's 11 fill steps per element take seconds."""
+    p = Pair(KEYSWITCH)
+    l1, s, d, cols = 4, 2048, 2, [3, 0]
+    o_a, g_a, o_b, g_b, o_gks, g_gk, ref = heads_case(p, l1, s, d, cols)
+    o_rk, g_rk = relin_keys(p)
+    mask0 = p.o.block_start_mask(s, l1)
+    g_mask = p.ctx.pt_set_scale(p.ctx.pt_import(mask0[None, :], l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, cols, g_mask)
+    want = p.o.ccmm_blocks(o_a, o_b, s, cols, o_rk, o_gks)
+    assert np.array_equal(out.export(), stack_cts(want))
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    for h in (g_a, g_b, g_mask, out, g_gk, g_rk):
+        h.free()
+    p.close()

@@ -37,7 +37,7 @@ class Workload:
     act: str = "uniform"  # "uniform" [-1,1] or "normal" N(0,1) clipped to [-4,4]
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
-    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs) or "ccmm"
+    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs) "ccmm" or "ccmm_blocks"
 
     @property
     def N(self):
@@ -79,6 +79,10 @@ WORKLOADS.append(Workload("ccmm96", 8, 16, 50, 16, 60, 4, 4, 40, tokens=32768, d
 # ciphertext, first layer placed in block 0, scalar-multiply + rescale, rotation-free second layer.
 WORKLOADS.append(Workload("paperffn", 9, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=1536, d_out=1536, d_mid=4096, placement="zero",
                           act="normal", kappa=2.0 ** -5))
+# The paper's attention-score product at its own packing (Table III: (2048 x 96) by (2048 x 96)^T, 16 heads): Q and K
+# column-encoded with the 16 heads of a column in the 16 blocks of one ciphertext (96 ciphertexts each); a step
+# computes d_out = 8 of the 2048 output columns for all heads at once.
+WORKLOADS.append(Workload("ccmmqk", 10, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=8, act="uniform", op="ccmm_blocks"))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
