@@ -58,3 +58,5 @@ def test_null_arguments_of_the_later_entry_points_without_gpu():
     assert lib.ensi_periodic_masks(n, 2, 1, 2, n) == -1
     assert lib.ensi_replicate(n, n, n, n, n, n, 1, n, n) == -1
     assert lib.ensi_ccmm(n, n, n, n, n, n, 2, n, n) == -1
+    assert lib.ensi_block_start_mask(n, 2, 2, n) == -1
+    assert lib.ensi_ccmm_blocks(n, n, n, n, n, 2, n, 1, n, n, n) == -1
