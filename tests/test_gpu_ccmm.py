@@ -222,3 +222,22 @@ def test_ccmm_blocks_full_ring():
     for h in (g_a, g_b, g_mask, out, g_gk, g_rk):
         h.free()
     p.close()
+
+
+def test_ccmm_blocks_at_the_benchmark_parameters():
+    """The 16 + 4 limb chain and the 16 x 2048 packing of the ccmmqk benchmark workload, with a narrow inner
+    dimension (d = 2, one output column) so that the oracle's 22 fill steps at 15 limbs take seconds."""
+    w = wl.BY_NAME["ccmmqk"]
+    p = Pair(w.param_tuple())
+    l1, s, d, cols = p.pr.L, w.tokens, 2, [5]
+    o_a, g_a, o_b, g_b, o_gks, g_gk, ref = heads_case(p, l1, s, d, cols)
+    o_rk, g_rk = relin_keys(p)
+    mask0 = p.o.block_start_mask(s, l1)
+    g_mask = p.ctx.pt_set_scale(p.ctx.pt_import(mask0[None, :], l1), float(p.pr.q[l1 - 1]))
+    out = p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, cols, g_mask)
+    want = p.o.ccmm_blocks(o_a, o_b, s, cols, o_rk, o_gks)
+    assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    for h in (g_a, g_b, g_mask, out, g_gk, g_rk):
+        h.free()
+    p.close()
