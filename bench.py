@@ -90,13 +90,10 @@ class Runner:
             pt = self.ctx.encode(zb, self.L)
             self.ct_in = self.ctx.encrypt(self.pk, pt)
             pt.free()
-            steps, r = [], 1
-            while r < self.n:
-                steps.append(r)
-                r *= 2
+            self.period = 1 << (d - 1).bit_length()
+            steps = sorted(set(self.ctx.fill_steps(self.period, self.n) + self.ctx.fill_steps(1, self.period)))
             self.gk = self.ctx.galois_keygen(self.sk, steps, None, 13)
             self.rk = self.ctx.relin_keygen(self.sk, None, 17)
-            self.period = 1 << (d - 1).bit_length()
             self.pt = self.ctx.periodic_masks(self.period, d, self.L)
             self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
             return
@@ -115,7 +112,7 @@ class Runner:
             self.ct_in = self.ctx.encrypt(self.pk, pt)
             pt.free()
             self.cols = list(range(m))
-            steps = [c for c in self.cols if c] + [-(1 << k) for k in range(sl.bit_length() - 1)]
+            steps = [c for c in self.cols if c] + self.ctx.fill_steps(1, sl, -1)
             self.gk = self.ctx.galois_keygen(self.sk, steps, None, 13)
             self.rk = self.ctx.relin_keygen(self.sk, None, 17)
             self.pt = self.ctx.block_start_mask(sl, self.L)
@@ -271,6 +268,19 @@ MEASURED_TRAFFIC = {
 }
 
 
+def fill_counts(r_begin, r_end):
+    """(rotations, raises) of the library's rotate-and-add fill between two strides: steps of radix four (three
+    rotations on one raise) while two doublings remain, then a single doubling."""
+    rot = raises = 0
+    r = r_begin
+    while r < r_end:
+        if 2 * r < r_end:
+            rot, raises, r = rot + 3, raises + 1, r * 4
+        else:
+            rot, raises, r = rot + 1, raises + 1, r * 2
+    return rot, raises
+
+
 def roofline_for(w, prof):
     """Roofline entry of the dominant kernel class of the step (largest total time)."""
     N, L, K, alpha = w.N, w.q_count, w.p_count, w.alpha
@@ -294,24 +304,27 @@ def roofline_for(w, prof):
         # per element: one aligning rotation (the raise shared by all columns of a ciphertext of B), one mask product and
         # log2(s) fill steps one level down; per output one relinearisation
         n_el = w.d_in * w.d_out
-        lp = w.tokens.bit_length() - 1
+        f_rot, f_raise = fill_counts(1, w.tokens)
         L = L - 1
         ext = L + K
         beta = -(-L // alpha)
-        n_rot = n_el * (1 + lp) + w.d_out
-        n_raise = w.d_in + n_el * lp + w.d_out
-        n_key = -(-w.d_in // 16) * w.d_out + lp * -(-n_el // 64) + 1
+        n_rot = n_el * (1 + f_rot) + w.d_out
+        n_raise = w.d_in + n_el * f_raise + w.d_out
+        n_key = -(-w.d_in // 16) * w.d_out + f_rot * -(-n_el // 64) + 1
         pm_terms = pm_out = n_el
     elif w.op == "ccmm":
         # every element of B: one mask product and log2(period) rotate-and-add steps one level down (the log2(n/period)
         # steps per column at the top level and the relinearisations are few and counted with them)
         n_el = w.d_in * w.d_out
-        lp = ((w.d_in - 1).bit_length())
+        period = 1 << (w.d_in - 1).bit_length()
+        b_rot, b_raise = fill_counts(1, period)
+        g_rot, g_raise = fill_counts(period, w.n_slots)
         L = L - 1
         ext = L + K
         beta = -(-L // alpha)
-        n_rot = n_raise = n_el * lp + w.d_out * (w.log_n - 1 - lp) + w.d_out
-        n_key = lp * -(-n_el // 64) + (w.log_n - 1 - lp) + 1
+        n_rot = n_el * b_rot + w.d_out * g_rot + w.d_out
+        n_raise = n_el * b_raise + w.d_out * g_raise + w.d_out
+        n_key = b_rot * -(-n_el // 64) + g_rot + 1
         pm_terms = pm_out = n_el
     else:
         n_in = -(-w.d_in // w.c_tot)
@@ -431,11 +444,10 @@ def cpu_baseline(w, budget_s=12.0):
     if w.op in ("ccmm", "ccmm_blocks"):
         n_el = w.d_in * w.d_out
         if w.op == "ccmm":
-            lp = (w.d_in - 1).bit_length()
-            n_rot = n_el * lp + w.d_out * (w.log_n - 1 - lp)
+            period = 1 << (w.d_in - 1).bit_length()
+            n_rot = n_el * fill_counts(1, period)[0] + w.d_out * fill_counts(period, w.n_slots)[0]
         else:
-            lp = w.tokens.bit_length() - 1
-            n_rot = n_el * (1 + lp)
+            n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
         _, t_rot, n1 = repeat(lambda: o.rotate(ct, gk), budget_s * 0.5)
         mask_rns = o.i64_to_rns(o.periodic_masks(1 << lp, 1, pr.L)[0], pr.q)
         _, t_pm, n2 = repeat(lambda: o.pmult(ct, mask_rns, float(pr.q[-1])), budget_s * 0.2)

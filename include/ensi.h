@@ -239,11 +239,16 @@ int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs);
  * ciphertexts with one limb less, not overlapping a or b; out.scale = a.scale * b.scale / q_l. */
 int ensi_mult_sum_relin_rescale(ensi_ctx *ctx, const ensi_gk *rk, const ensi_ct *a, const ensi_ct *b, const int32_t *begin,
                                 const int32_t *term_a, const int32_t *term_b, int32_t n_out, ensi_ct *out, void *stream);
+/* The rotate-and-add fill used by the element extraction below, t <- sum_{e < r_end / r_begin} Rot(t; sign e r_begin)
+ * (r_end / r_begin a power of two): while two doublings remain they are taken as one step of radix four,
+ * t <- t + Rot(t; r) + Rot(t; 2r) + Rot(t; 3r), whose three rotations share one ModUp of t; a last single doubling is
+ * t <- t + Rot(t; r).  ensi_fill_steps writes the rotation steps this schedule uses (the Galois keys a caller has to
+ * provide) to steps_out (capacity cap) and returns their number (or a negative ENSI_E_* code). */
+int ensi_fill_steps(int32_t r_begin, int32_t r_end, int32_t sign, int32_t *steps_out, int32_t cap);
 /* Element extraction of the CCMM section: out_o holds, in every slot, the value that slot k_o of in[src[o]] held:
- * one product with the one-hot mask masks[mask_idx[o]] (1 in slot k_o, else 0) and one rescale, then log2(N/2)
- * steps t <- t + Rot(t; 2^r), r = 0, 1, ... (the figure with the paper's own schedule is not part of its text;
- * this is the doubling schedule with the logarithmic rotation count it states).  gk must hold keys for the steps
- * 2^r, r = 0..log2(N/2)-1.  ensi_one_hot_masks encodes the masks of slots 0..count-1 at `limbs` limbs and scale
+ * one product with the one-hot mask masks[mask_idx[o]] (1 in slot k_o, else 0) and one rescale, then the fill
+ * over all N/2 slots (the figure with the paper's own schedule is not part of its text; this schedule has the
+ * logarithmic rotation count it states).  gk must hold keys for ensi_fill_steps(1, N/2, 1).  ensi_one_hot_masks encodes the masks of slots 0..count-1 at `limbs` limbs and scale
  * q_{limbs-1}.  src, mask_idx: host int32[n_out]; out: n_out ciphertexts with one limb less than `in`. */
 int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, ensi_pt **pt);
 int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
@@ -251,12 +256,11 @@ int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const in
 /* C = A B on ciphertexts (CCMM section): A: d column ciphertexts (a_j = column j of A, tokens along the slots),
  * B: m column ciphertexts (b_i holds B[j][i] in slot j for j < d and ZERO in every other slot), both at the same
  * number of limbs l;  c_i = Rescale(Relin(sum_j a_j (x) b_i^(j))) with b_i^(j) = B[j][i] replicated into every
- * slot.  Element extraction in two stages, `period` a power of two with d <= period <= N/2: per column,
- * log2((N/2)/period) steps u <- u + Rot(u; r), r = period, 2 period, ... make it periodic (u[p] = b[p mod period],
- * no level); per element, one product with masks[j] (1 in the slots congruent to j modulo period) and one
- * rescale, then log2(period) steps t <- t + Rot(t; r), r = 1, 2, ..., period/2.  (The figure with the paper's own
+ * slot.  Element extraction in two stages, `period` a power of two with d <= period <= N/2: per column, the fill
+ * with steps period, 2 period, ... makes it periodic (u[p] = b[p mod period], no level); per element, one product
+ * with masks[j] (1 in the slots congruent to j modulo period) and one rescale, then the fill over a period.  (The figure with the paper's own
  * baby-step giant-step schedule is not part of its text; this one shares the giant steps among the elements of a
- * column.)  gk must hold keys for the steps 2^r, r = 0..log2(N/2)-1; masks: at least d plaintexts from
+ * column.)  gk must hold keys for ensi_fill_steps(period, N/2, 1) and ensi_fill_steps(1, period, 1); masks: at least d plaintexts from
  * ensi_periodic_masks(period, count >= d, limbs = l); a_j is read at the level of the replicated elements.
  * out: m ciphertexts with l - 2 limbs. */
 int ensi_periodic_masks(ensi_ctx *ctx, int32_t period, int32_t count, int32_t limbs, ensi_pt **pt);
@@ -268,9 +272,9 @@ int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct
  * of two); ciphertext j of B holds B_h[j][i] in slot h s + i (i.e. B^T column-encoded, as K is).  Output c holds,
  * in block h, column cols[c] of C_h = A_h B_h:  out_c = Rescale(Relin(sum_j a_j (x) b^(j, cols[c]))), where
  * b^(j, i) is slot i of every block of b_j copied into all s slots of its block: Rot(b_j; i) brings it to the block's
- * first slot (one ModUp per b_j serves all i), the block-start mask keeps it (one product, one rescale), and log2(s)
- * steps t <- t + Rot(t; -r), r = 1, 2, ..., s/2 fill the block upwards.  gk must hold keys for the steps cols[c] and
- * -2^k (k < log2 s); mask: one plaintext from ensi_block_start_mask(s, limbs = l).  A, B: d ciphertexts each at l
+ * first slot (one ModUp per b_j serves all i), the block-start mask keeps it (one product, one rescale), and the
+ * fill with negative steps copies it upwards through the block.  gk must hold keys for the steps cols[c] and for
+ * ensi_fill_steps(1, s, -1); mask: one plaintext from ensi_block_start_mask(s, limbs = l).  A, B: d ciphertexts each at l
  * limbs; out: n_cols ciphertexts at l - 2 limbs. */
 int ensi_block_start_mask(ensi_ctx *ctx, int32_t s, int32_t limbs, ensi_pt **pt);
 int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,

@@ -568,20 +568,42 @@ class Oracle:
             out.append(self.encode_coeffs(z, ql))
         return np.stack(out)
 
+    @staticmethod
+    def fill_steps(r_begin, r_end, sign=1):
+        """Rotation steps of the rotate-and-add fill t <- sum_{e < r_end / r_begin} Rot(t; sign e r_begin)
+        (r_end / r_begin a power of two), as a list of groups: while two doublings remain they are taken
+        as one step of radix four, t <- t + Rot(t; r) + Rot(t; 2r) + Rot(t; 3r), whose three rotations
+        share one ModUp of t; a last single doubling is t <- t + Rot(t; r)."""
+        groups, r = [], r_begin
+        while r < r_end:
+            if 2 * r < r_end:
+                groups.append([sign * r, sign * 2 * r, sign * 3 * r])
+                r *= 4
+            else:
+                groups.append([sign * r])
+                r *= 2
+        return groups
+
+    def fill(self, t, r_begin, r_end, gks, sign=1):
+        """The fill of fill_steps on a ciphertext; gks: dict step -> Galois key."""
+        for group in self.fill_steps(r_begin, r_end, sign):
+            digits = self.mod_up(t.c1)
+            acc = t
+            for step in group:
+                acc = self.add_ct(acc, self.rotate_from_digits(t.c0, digits, gks[step], t.scale))
+            t = acc
+        return t
+
     def replicate(self, ct, mask, gks):
         """The element-extraction step of the CCMM section: keep one slot (PMult by its mask, one
-        rescale), then copy it into every slot by log2(N/2) rotate-and-add steps with doubling
-        strides, t <- t + Rot(t; 2^r).  gks: dict 2^r -> Galois key.  The figure with the paper's own
-        schedule is not in the text; this is the doubling schedule that reaches the logarithmic
+        rescale), then copy it into every slot by the rotate-and-add fill of fill_steps over all
+        N/2 slots.  gks: dict step -> Galois key for the steps of fill_steps(1, N/2).  The figure with the paper's own
+        schedule is not in the text; this rotate-and-add schedule reaches the logarithmic
         rotation count it states."""
         l1 = ct.l1
         ql = float(self.pr.q[l1 - 1])
         t = self.pmult_sum_rescale([(ct, self.i64_to_rns(mask, self.pr.q[:l1]))], ql)
-        r = 1
-        while r < self.n:
-            t = self.add_ct(t, self.rotate(t, gks[r]))
-            r *= 2
-        return t
+        return self.fill(t, 1, self.n, gks)
 
     def periodic_masks(self, period, count, l1):
         """Integer coefficients [count][N] of the masks with a 1 in every slot congruent to j modulo
@@ -597,26 +619,17 @@ class Oracle:
     def spread_periods(self, ct, period, gks):
         """Giant steps of the element extraction, shared by all elements of a column: a ciphertext
         whose slots beyond the first `period` are zero becomes periodic, u[p] = ct[p mod period], by
-        u <- u + Rot(u; r) for r = period, 2 period, ..., N/4.  No level is consumed."""
-        u = ct
-        r = period
-        while r < self.n:
-            u = self.add_ct(u, self.rotate(u, gks[r]))
-            r *= 2
-        return u
+        the fill of fill_steps(period, N/2).  No level is consumed."""
+        return self.fill(ct, period, self.n, gks)
 
     def extract_from_periodic(self, u, mask, period, gks):
         """Baby steps, per element: keep the slots congruent to j modulo the period (PMult by the
         periodic mask, one rescale), then fill every window of `period` slots from its single
-        non-zero entry by t <- t + Rot(t; r), r = 1, 2, ..., period/2."""
+        non-zero entry by the fill of fill_steps(1, period)."""
         l1 = u.l1
         ql = float(self.pr.q[l1 - 1])
         t = self.pmult_sum_rescale([(u, self.i64_to_rns(mask, self.pr.q[:l1]))], ql)
-        r = 1
-        while r < period:
-            t = self.add_ct(t, self.rotate(t, gks[r]))
-            r *= 2
-        return t
+        return self.fill(t, 1, period, gks)
 
     def ccmm(self, a_cts, b_cts, d, period, rk, gks):
         """C = A B on ciphertexts (CCMM section): A column-encoded (a_j = column j, tokens along the
@@ -647,17 +660,13 @@ class Oracle:
         """Element extraction when a ciphertext packs one block of s slots per head: slot i of every
         block is copied into all s slots of its block.  Rot(.; i) brings it to the block's first
         slot, the block-start mask keeps it (PMult, one rescale), and log2(s) steps
-        t <- t + Rot(t; -r), r = 1, 2, ..., s/2 fill the block upwards without touching the next one.
+        the fill of fill_steps(1, s, -1) copies it upwards through the block without touching the next one.
         gks: dict step -> Galois key, with the steps i and -2^k."""
         l1 = ct.l1
         ql = float(self.pr.q[l1 - 1])
         t = self.rotate(ct, gks[i]) if i else ct
         t = self.pmult_sum_rescale([(t, self.i64_to_rns(mask0, self.pr.q[:l1]))], ql)
-        r = 1
-        while r < s:
-            t = self.add_ct(t, self.rotate(t, gks[-r]))
-            r *= 2
-        return t
+        return self.fill(t, 1, s, gks, sign=-1)
 
     def ccmm_blocks(self, a_cts, b_cts, s, cols, rk, gks):
         """C_h = A_h B_h for all heads h at once (CCMM section, the column-encoded by row-encoded

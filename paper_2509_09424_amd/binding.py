@@ -23,7 +23,7 @@ EXPORTED = [
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
-    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -278,6 +278,13 @@ class Context:
         self._check(self.lib.ensi_mult_sum_relin_rescale(self.h, rk.h, ct_a.h, ct_b.h, _ptr(begin), _ptr(term_a), _ptr(term_b), n_out,
                                                          ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
+
+    def fill_steps(self, r_begin, r_end, sign=1):
+        out = np.zeros(128, dtype=np.int32)
+        n = self.lib.ensi_fill_steps(int(r_begin), int(r_end), int(sign), _ptr(out), len(out))
+        if n < 0 or n > len(out):
+            raise EnsiError("ensi_fill_steps failed with code %d" % n)
+        return [int(x) for x in out[:n]]
 
     def one_hot_masks(self, count, limbs):
         pt = ctypes.c_void_p()

@@ -1725,60 +1725,98 @@ extern "C" int ensi_one_hot_masks(ensi_ctx *ctx, int32_t count, int32_t limbs, e
     return encode_window(ctx, ones.data(), count, 1, 0, 1, limbs, (double)ctx->primes[limbs - 1], out);
 }
 
-// t <- t + Rot(t; sign * r) for r = r_begin, 2 r_begin, ... below r_end, in place on a batch.  On the fused path the last
-// key-switch kernel adds its result to the source ciphertext directly; otherwise the rotated copy goes through a
-// workspace and is added by a separate kernel.
+// The rotate-and-add fill t <- sum_{e < r_end / r_begin} Rot(t; sign * e * r_begin): groups of steps taken together.
+// While two doublings remain they are one step of radix four, t <- t + Rot(t; r) + Rot(t; 2r) + Rot(t; 3r), whose
+// three rotations share one ModUp of t; a last single doubling is t <- t + Rot(t; r).
+static std::vector<std::vector<int>> fill_groups(int r_begin, int r_end, int sign) {
+    std::vector<std::vector<int>> groups;
+    for (int r = r_begin; r < r_end;) {
+        if (2 * r < r_end) {
+            groups.push_back({sign * r, sign * 2 * r, sign * 3 * r});
+            r *= 4;
+        } else {
+            groups.push_back({sign * r});
+            r *= 2;
+        }
+    }
+    return groups;
+}
+
+extern "C" int ensi_fill_steps(int32_t r_begin, int32_t r_end, int32_t sign, int32_t *steps_out, int32_t cap) {
+    if (r_begin < 1 || r_end < r_begin || (sign != 1 && sign != -1) || (cap > 0 && !steps_out)) return ENSI_E_BADARG;
+    int n = 0;
+    for (const auto &grp : fill_groups(r_begin, r_end, sign))
+        for (int st : grp) {
+            if (n < cap) steps_out[n] = st;
+            n++;
+        }
+    return n;
+}
+
+// The fill in place on a batch.  On the fused path a group's rotations share the raise of t, and the last key-switch
+// kernel of each adds its result to t directly (one launch sequence per rotation amount, so that no two blocks
+// update the same word); otherwise every rotated copy goes through a workspace and is added by a separate kernel.
 static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st, int sign = 1) {
     const int N = ctx->N, n = t->n, l1 = t->limbs, ext = l1 + ctx->K;
+    const auto groups = fill_groups(r_begin, r_end, sign);
     int rc;
     if (ctx->ks16) {
         const int chunk = std::min(n, rot_chunk());
         const size_t rw = raised_words(ctx, l1), ct_words = (size_t)2 * t->limbs_alloc * N;
         if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
         if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 2 * ext * N))) return rc;
-        // the descriptors of all steps go up in one copy: step k, ciphertext c at index k * n + c
+        // the descriptors of all rotations go up in one copy: rotation amount k (in schedule order), ciphertext c at k * n + c
         std::vector<RotDesc> desc;
-        for (int r = r_begin; r < r_end; r *= 2) {
-            const u32 g = galois_element(ctx, sign * r);
-            auto it = gk->keys.find(g);
-            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", sign * r);
-            for (int c = 0; c < n; c++) {
-                RotDesc d = {};
-                d.c0 = t->d + (size_t)c * ct_words;
-                d.digits = ctx->ws_digits + (size_t)(c % chunk) * rw;
-                d.key = it->second;
-                d.out = t->d + (size_t)c * ct_words;
-                d.g = g;
-                d.g_inv = inv_mod_2n(g, N);
-                d.accumulate = 1;
-                desc.push_back(d);
+        for (const auto &grp : groups)
+            for (int step : grp) {
+                const u32 g = galois_element(ctx, step);
+                auto it = gk->keys.find(g);
+                if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", step);
+                for (int c = 0; c < n; c++) {
+                    RotDesc d = {};
+                    d.c0 = t->d + (size_t)c * ct_words;
+                    d.digits = ctx->ws_digits + (size_t)(c % chunk) * rw;
+                    d.key = it->second;
+                    d.out = t->d + (size_t)c * ct_words;
+                    d.g = g;
+                    d.g_inv = inv_mod_2n(g, N);
+                    d.accumulate = 1;
+                    desc.push_back(d);
+                }
             }
-        }
         if (desc.empty()) return ENSI_OK;
         if ((rc = ensure_desc(ctx, desc.size()))) return rc;
         ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-        const int n_steps = (int)(desc.size() / n);
-        for (int k = 0; k < n_steps; k++)
+        size_t k = 0;
+        for (const auto &grp : groups) {
             for (int c0 = 0; c0 < n; c0 += chunk) {
                 const int cnt = std::min(chunk, n - c0);
+                // every rotation of the group reads the digits of t as it was before the group
                 if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
-                if ((rc = run_rotations(ctx, ctx->ws_desc + (size_t)k * n + c0, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
+                for (size_t e = 0; e < grp.size(); e++)
+                    if ((rc = run_rotations(ctx, ctx->ws_desc + (k + e) * n + c0, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
             }
+            k += grp.size();
+        }
         return ENSI_OK;
     }
-    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N))) return rc;
-    ensi_ct tmp;
-    tmp.ctx = ctx;
-    tmp.n = n;
-    tmp.limbs = tmp.limbs_alloc = l1;
-    tmp.scale = t->scale;
-    tmp.d = ctx->ws_rtmp;
-    tmp.owns = false;
+    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N * 3))) return rc;
     std::vector<int32_t> steps(n);
-    for (int r = r_begin; r < r_end; r *= 2) {
-        std::fill(steps.begin(), steps.end(), sign * r);
-        if ((rc = ensi_rotate(ctx, gk, t, steps.data(), &tmp, (void *)st))) return rc;
-        launch_ct_add(ctx, t->d, t->limbs_alloc, tmp.d, l1, l1, n, st);
+    for (const auto &grp : groups) {
+        // all rotated copies of the group are formed from t before any of them is added
+        for (size_t e = 0; e < grp.size(); e++) {
+            ensi_ct tmp;
+            tmp.ctx = ctx;
+            tmp.n = n;
+            tmp.limbs = tmp.limbs_alloc = l1;
+            tmp.scale = t->scale;
+            tmp.d = ctx->ws_rtmp + e * (size_t)n * 2 * l1 * N;
+            tmp.owns = false;
+            std::fill(steps.begin(), steps.end(), grp[e]);
+            if ((rc = ensi_rotate(ctx, gk, t, steps.data(), &tmp, (void *)st))) return rc;
+        }
+        for (size_t e = 0; e < grp.size(); e++)
+            launch_ct_add(ctx, t->d, t->limbs_alloc, ctx->ws_rtmp + e * (size_t)n * 2 * l1 * N, l1, l1, n, st);
     }
     return ENSI_OK;
 }

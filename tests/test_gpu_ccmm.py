@@ -76,13 +76,12 @@ def test_mult_full_ring():
     p.close()
 
 
-def doubling_keys(p):
-    steps = []
-    r = 1
-    while r < p.n:
-        steps.append(r)
-        r *= 2
-    return p.galois_keys(steps)
+def doubling_keys(p, period=None):
+    """Keys for the steps of the library's fill schedule (the oracle follows its own and must find its keys here)."""
+    steps = set(p.ctx.fill_steps(1, p.n))
+    if period:
+        steps |= set(p.ctx.fill_steps(period, p.n)) | set(p.ctx.fill_steps(1, period))
+    return p.galois_keys(sorted(steps))
 
 
 @pytest.mark.parametrize("params", [TINY5, SMALL4], ids=["16-slots", "512-slots"])
@@ -118,7 +117,7 @@ def test_ccmm_against_oracle_and_numpy(params, d, m, period):
     l1 = p.pr.L
     A = p.rng.uniform(-1, 1, (p.n, d))
     Bm = p.rng.uniform(-1, 1, (d, m))
-    o_gks, g_gk = doubling_keys(p)
+    o_gks, g_gk = doubling_keys(p, period)
     o_rk, g_rk = relin_keys(p)
     zb = np.zeros((m, p.n))  # B[j, i] in slot j of ciphertext i, zeros elsewhere
     zb[:, :d] = Bm.T
@@ -151,7 +150,7 @@ def test_ccmm_full_ring_at_the_benchmark_parameters():
     l1, d, m, period = p.pr.L, 4, 1, 4
     A = p.rng.uniform(-1, 1, (p.n, d))
     Bm = p.rng.uniform(-1, 1, (d, m))
-    o_gks, g_gk = doubling_keys(p)
+    o_gks, g_gk = doubling_keys(p, period)
     o_rk, g_rk = relin_keys(p)
     zb = np.zeros((m, p.n))
     zb[:, :d] = Bm.T
@@ -176,7 +175,7 @@ def heads_case(p, l1, s, d, cols):
     zb = np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)])
     o_a, g_a = p.encrypt_both(za, l1)
     o_b, g_b = p.encrypt_both(zb, l1)
-    steps = sorted(set(c for c in cols if c)) + [-(1 << k) for k in range(s.bit_length() - 1)]
+    steps = sorted(set(c for c in cols if c)) + p.ctx.fill_steps(1, s, -1)
     o_gks, g_gk = p.galois_keys(steps)
     ref = np.stack([np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)]) for i in cols])
     return o_a, g_a, o_b, g_b, o_gks, g_gk, ref

@@ -465,11 +465,11 @@ def test_replicate_and_ccmm_against_numpy():
     A = rng.uniform(-1, 1, (s_tok, d))
     B = rng.uniform(-1, 1, (d, m))
     beta = pr.beta(pr.L)
-    gks = {}
-    r = 1
-    while r < o.n:
-        gks[r] = o.galois_keygen(sk, r, wl.error_poly(rng, (beta, o.N)), 71)
-        r *= 2
+    period = 4
+    steps = {st for grp in Oracle.fill_steps(1, o.n) + Oracle.fill_steps(period, o.n) + Oracle.fill_steps(1, period) for st in grp}
+    gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 71) for st in sorted(steps)}
+    # the fill schedule: radix four while two doublings remain, the sum of all shifts in any case
+    assert Oracle.fill_steps(1, 16) == [[1, 2, 3], [4, 8, 12]] and Oracle.fill_steps(2, 16, -1) == [[-2, -4, -6], [-8]]
     rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 73)
     a_cts = [_enc(o, rng, pk, A[:, j], l1) for j in range(d)]
     b_cts = []
@@ -477,12 +477,15 @@ def test_replicate_and_ccmm_against_numpy():
         z = np.zeros(o.n)  # B[j, i] in slot j, zeros elsewhere
         z[:d] = B[:, i]
         b_cts.append(_enc(o, rng, pk, z, l1))
+    # the fill is the sum of all shifts, whatever the radix of its steps
+    zs = rng.uniform(-1, 1, o.n)
+    filled = o.fill(_enc(o, rng, pk, zs, l1), 1, 8, gks)
+    assert filled.l1 == l1 and np.abs(o.decrypt(filled, sk) - sum(np.roll(zs, -e) for e in range(8))).max() < 1e-3
     # the general extraction: any slot of any ciphertext into every slot
     zf = rng.uniform(-1, 1, o.n)
     rep = o.replicate(_enc(o, rng, pk, zf, l1), o.one_hot_masks([5], l1)[0], gks)
     assert rep.l1 == l1 - 1 and np.abs(o.decrypt(rep, sk) - zf[5]).max() < 1e-3
     # the two-stage extraction of the matrix product: giant steps make the column periodic, baby steps fill
-    period = 4
     u = o.spread_periods(b_cts[0], period, gks)
     assert u.l1 == l1 and np.abs(o.decrypt(u, sk) - np.tile(np.concatenate([B[:, 0], [0.0]]), o.n // period)).max() < 1e-3
     one = o.extract_from_periodic(u, o.periodic_masks(period, d, l1)[1], period, gks)
@@ -507,7 +510,7 @@ def test_blockwise_extraction_and_ccmm_over_heads():
     b_cts = [_enc(o, rng, pk, np.concatenate([K[h][:, j] for h in range(heads)]), l1) for j in range(d)]
     beta = pr.beta(pr.L)
     cols = [0, 3, 7]
-    steps = [c for c in cols if c] + [-1, -2, -4]
+    steps = [c for c in cols if c] + [st for grp in Oracle.fill_steps(1, s, -1) for st in grp]
     gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 83) for st in steps}
     rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 89)
     mask0 = o.block_start_mask(s, l1)
