@@ -321,11 +321,10 @@ class Oracle:
             gk["ntt"] = {l1: (primes, kb, ka)}
         return gk["ntt"][l1]
 
-    def rotate_from_digits(self, c0, digits, gk, scale):
-        """Steps c-f of the rotation: automorphism of every raised digit and of c0,
-        key inner product over the extended basis, ModDown, add phi_g(c0)."""
+    def _key_inner_product(self, digits, gk, l1):
+        """Automorphism of every raised digit and the inner product with the key over the extended
+        basis: (u0, u1), transform domain."""
         pr = self.pr
-        l1 = c0.shape[0]
         g = gk["g"]
         primes, kb, ka = self._key_at_level(gk, l1)
         qv = _u64(primes)
@@ -335,10 +334,31 @@ class Oracle:
             dg = self.ntt(self.automorphism(digits[j], g, primes), primes)
             self.lib.orc_pointwise_mac(_p(u0), _p(dg), _p(np.ascontiguousarray(kb[j])), len(primes), self.N, _p(qv))
             self.lib.orc_pointwise_mac(_p(u1), _p(dg), _p(np.ascontiguousarray(ka[j])), len(primes), self.N, _p(qv))
+        return primes, u0, u1
+
+    def rotate_from_digits(self, c0, digits, gk, scale):
+        """Steps c-f of the rotation: automorphism of every raised digit and of c0,
+        key inner product over the extended basis, ModDown, add phi_g(c0)."""
+        return self.rotate_sum_from_digits(c0, digits, [gk], scale)
+
+    def rotate_sum_from_digits(self, c0, digits, gks, scale):
+        """sum_k Rot(.; step_k) of one ciphertext with one ModDown: the key inner products of all
+        members are added over the extended basis before the inverse transform and the division by
+        P (ModDown is linear up to its rounding, so this is a key switch of the sum with one
+        rounding instead of one per member), then sum_k phi_{g_k}(c0) is added.  With one member it
+        is the rotation itself."""
+        l1 = c0.shape[0]
+        u0 = u1 = None
+        for gk in gks:
+            primes, v0, v1 = self._key_inner_product(digits, gk, l1)
+            u0 = v0 if u0 is None else self.add(u0, v0, primes)
+            u1 = v1 if u1 is None else self.add(u1, v1, primes)
         u0 = self.ntt(u0, primes, inverse=True)
         u1 = self.ntt(u1, primes, inverse=True)
-        q = pr.q[:l1]
-        out0 = self.add(self.automorphism(np.ascontiguousarray(c0), g, q), self.mod_down(u0, l1), q)
+        q = self.pr.q[:l1]
+        out0 = self.mod_down(u0, l1)
+        for gk in gks:
+            out0 = self.add(out0, self.automorphism(np.ascontiguousarray(c0), gk["g"], q), q)
         out1 = self.mod_down(u1, l1)
         return Ciphertext(out0, out1, scale)
 
@@ -573,7 +593,8 @@ class Oracle:
         """Rotation steps of the rotate-and-add fill t <- sum_{e < r_end / r_begin} Rot(t; sign e r_begin)
         (r_end / r_begin a power of two), as a list of groups: while two doublings remain they are taken
         as one step of radix four, t <- t + Rot(t; r) + Rot(t; 2r) + Rot(t; 3r), whose three rotations
-        share one ModUp of t; a last single doubling is t <- t + Rot(t; r)."""
+        share one ModUp of t and one ModDown (rotate_sum_from_digits); a last single doubling is
+        t <- t + Rot(t; r)."""
         groups, r = [], r_begin
         while r < r_end:
             if 2 * r < r_end:
@@ -587,11 +608,7 @@ class Oracle:
     def fill(self, t, r_begin, r_end, gks, sign=1):
         """The fill of fill_steps on a ciphertext; gks: dict step -> Galois key."""
         for group in self.fill_steps(r_begin, r_end, sign):
-            digits = self.mod_up(t.c1)
-            acc = t
-            for step in group:
-                acc = self.add_ct(acc, self.rotate_from_digits(t.c0, digits, gks[step], t.scale))
-            t = acc
+            t = self.add_ct(t, self.rotate_sum_from_digits(t.c0, self.mod_up(t.c1), [gks[step] for step in group], t.scale))
         return t
 
     def replicate(self, ct, mask, gks):

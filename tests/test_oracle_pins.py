@@ -391,6 +391,33 @@ def test_key_switch_noise_and_rotation(widx, log_n):
         assert np.abs(noise).max() < pr.scale * 1e-3 / math.sqrt(o.N)
 
 
+def test_sum_of_rotations_with_one_moddown():
+    """Two rotations of one ciphertext switched together: the sum of the two slot shifts, and within a few
+    units per coefficient of the two rotations done separately."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 9)
+    o = Oracle(pr)
+    rng = np.random.default_rng(21)
+    sk, pk = _keys(o, rng)
+    z = rng.uniform(-1, 1, o.n)
+    ct = _enc(o, rng, pk, z, pr.L)
+    beta = pr.beta(pr.L)
+    gks = [o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 6) for st in (2, -5)]
+    digits = o.mod_up(ct.c1)
+    both = o.rotate_sum_from_digits(ct.c0, digits, gks, ct.scale)
+    assert np.abs(o.decrypt(both, sk) - (np.roll(z, -2) + np.roll(z, 5))).max() < 1e-3
+    one = o.rotate_sum_from_digits(ct.c0, digits, gks[:1], ct.scale)
+    assert np.array_equal(one.limbs(), o.rotate(ct, gks[0]).limbs())
+    sep = o.add_ct(o.rotate(ct, gks[0]), o.rotate(ct, gks[1]))
+    q = np.array(pr.q[:pr.L], dtype=np.int64)[None, :, None]
+    diff = (both.limbs().astype(np.int64) - sep.limbs().astype(np.int64)) % q
+    diff = np.where(diff > q // 2, diff - q, diff)
+    # the same up to the rounding of the division by P and the small multiples of P the fast basis conversion adds:
+    # a small integer polynomial, identical on every limb
+    assert 1 <= np.abs(diff).max() <= pr.K + 1
+    assert all(np.array_equal(diff[:, 0], diff[:, i]) for i in range(1, pr.L))
+
+
 def test_rotate_at_lower_level():
     w = wl.WORKLOADS[4]
     pr = small_params(w, 9)
