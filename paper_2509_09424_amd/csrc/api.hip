@@ -943,22 +943,45 @@ static int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride
 }
 
 // Runs inner product -> inverse transform -> ModDown (+ phi_g(c0)) for n_rot descriptors already on the device.
+// members > 1: the descriptors come in groups of `members` rotations of one ciphertext (same source, digits and
+// destination); a group's inner products are added over the extended basis and brought back by one inverse
+// transform and one ModDown, and the destination receives sum_k phi_{g_k}(c0) with it.  h_desc: host copy of the
+// descriptors (needed by the unfused path of a grouped call only).
 static int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out,
-                         hipStream_t st) {
+                         hipStream_t st, int members = 1, const RotDesc *h_desc = nullptr) {
     int rc;
     if (ctx->ks16) {
         const Ks16Const *kc;
         if ((rc = get_ks16(ctx, l1, &kc))) return rc;
-        if ((rc = grow(ctx, &ctx->ws_ysp, &ctx->ws_ysp_words, (size_t)n_rot * 2 * ctx->K * ctx->N))) return rc;
-        launch_ks16_switch(ctx, *kc, d_desc, n_rot, ctx->ws_u, ctx->ws_ysp, limb_stride_out, st);
+        if ((rc = grow(ctx, &ctx->ws_ysp, &ctx->ws_ysp_words, (size_t)(n_rot / members) * 2 * ctx->K * ctx->N))) return rc;
+        launch_ks16_switch(ctx, *kc, d_desc, n_rot, ctx->ws_u, ctx->ws_ysp, limb_stride_out, st, members);
         return ENSI_OK;
     }
     const ModDownConst *md;
     if ((rc = get_moddown(ctx, l1, &md))) return rc;
-    const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
+    const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha, N = ctx->N;
+    const LimbMap mext = make_map(ctx, l1, true);
     launch_inner(ctx, d_desc, n_rot, l1, beta, ctx->ws_u, st);
-    launch_ntt(ctx, ctx->ws_u, n_rot * 2 * ext, make_map(ctx, l1, true), true, st);
-    launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, ctx->ws_u, st);
+    if (members == 1) {
+        launch_ntt(ctx, ctx->ws_u, n_rot * 2 * ext, mext, true, st);
+        launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, ctx->ws_u, st);
+        return ENSI_OK;
+    }
+    if (!h_desc) ENSI_FAIL(ctx, ENSI_E_BADARG, "grouped rotations need the host descriptors");
+    const LimbMap mq = make_map(ctx, l1, false);
+    const size_t W = (size_t)2 * ext * N;  // accumulator words of one rotation
+    if ((rc = grow(ctx, &ctx->ws_y, &ctx->ws_y_words, (size_t)l1 * N))) return rc;
+    for (int g = 0; g < n_rot / members; g++) {
+        u64 *ug = ctx->ws_u + (size_t)g * members * W;
+        for (int e = 1; e < members; e++) launch_add(ctx, ug, ug, ug + (size_t)e * W, 2 * ext, mext, st);
+        launch_ntt(ctx, ug, 2 * ext, mext, true, st);
+        launch_moddown(ctx, *md, d_desc + (size_t)g * members, 1, limb_stride_in, limb_stride_out, ug, st);  // adds phi_{g_0}(c0)
+        for (int e = 1; e < members; e++) {
+            const RotDesc &h = h_desc[(size_t)g * members + e];
+            launch_automorphism_coef(ctx, ctx->ws_y, h.c0, mq, h.g_inv, st);
+            launch_add(ctx, h.out, h.out, ctx->ws_y, l1, mq, st);
+        }
+    }
     return ENSI_OK;
 }
 
@@ -1753,70 +1776,61 @@ extern "C" int ensi_fill_steps(int32_t r_begin, int32_t r_end, int32_t sign, int
     return n;
 }
 
-// The fill in place on a batch.  On the fused path a group's rotations share the raise of t, and the last key-switch
-// kernel of each adds its result to t directly (one launch sequence per rotation amount, so that no two blocks
-// update the same word); otherwise every rotated copy goes through a workspace and is added by a separate kernel.
+// The fill in place on a batch.  The rotations of a group share the raise of t and are switched back together (one
+// inverse transform and one ModDown per group).  On the fused path the last key-switch kernel adds the group's
+// result to t directly (legal in place: every read of t happens in the raise kernels); otherwise the group's
+// result goes through a workspace and is added by a separate kernel.
 static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_begin, int r_end, hipStream_t st, int sign = 1) {
     const int N = ctx->N, n = t->n, l1 = t->limbs, ext = l1 + ctx->K;
     const auto groups = fill_groups(r_begin, r_end, sign);
+    if (groups.empty()) return ENSI_OK;
     int rc;
-    if (ctx->ks16) {
-        const int chunk = std::min(n, rot_chunk());
-        const size_t rw = raised_words(ctx, l1), ct_words = (size_t)2 * t->limbs_alloc * N;
-        if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
-        if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 2 * ext * N))) return rc;
-        // the descriptors of all rotations go up in one copy: rotation amount k (in schedule order), ciphertext c at k * n + c
-        std::vector<RotDesc> desc;
-        for (const auto &grp : groups)
-            for (int step : grp) {
-                const u32 g = galois_element(ctx, step);
-                auto it = gk->keys.find(g);
-                if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", step);
-                for (int c = 0; c < n; c++) {
+    const bool fused = ctx->ks16;
+    const int chunk = std::min(n, fused ? rot_chunk() : 16);
+    const size_t rw = raised_words(ctx, l1), ct_words = (size_t)2 * t->limbs_alloc * N, tmp_words = (size_t)2 * l1 * N;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)chunk * rw))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)chunk * 3 * 2 * ext * N))) return rc;
+    if (!fused && (rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)chunk * tmp_words))) return rc;
+    // descriptors of all groups in one copy; per group and chunk: ciphertext c, member e at base + c * members + e
+    std::vector<RotDesc> desc;
+    std::vector<size_t> base;  // per (group, chunk) in launch order
+    for (const auto &grp : groups) {
+        std::vector<std::pair<u32, const u64 *>> gk_of;
+        for (int step : grp) {
+            const u32 g = galois_element(ctx, step);
+            auto it = gk->keys.find(g);
+            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", step);
+            gk_of.push_back({g, it->second});
+        }
+        for (int c0 = 0; c0 < n; c0 += chunk) {
+            base.push_back(desc.size());
+            for (int c = c0; c < std::min(n, c0 + chunk); c++)
+                for (const auto &ge : gk_of) {
                     RotDesc d = {};
                     d.c0 = t->d + (size_t)c * ct_words;
-                    d.digits = ctx->ws_digits + (size_t)(c % chunk) * rw;
-                    d.key = it->second;
-                    d.out = t->d + (size_t)c * ct_words;
-                    d.g = g;
-                    d.g_inv = inv_mod_2n(g, N);
-                    d.accumulate = 1;
+                    d.digits = ctx->ws_digits + (size_t)(c - c0) * rw;
+                    d.key = ge.second;
+                    d.out = fused ? t->d + (size_t)c * ct_words : ctx->ws_rtmp + (size_t)(c - c0) * tmp_words;
+                    d.g = ge.first;
+                    d.g_inv = inv_mod_2n(ge.first, N);
+                    d.accumulate = fused ? 1 : 0;
                     desc.push_back(d);
                 }
-            }
-        if (desc.empty()) return ENSI_OK;
-        if ((rc = ensure_desc(ctx, desc.size()))) return rc;
-        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
-        size_t k = 0;
-        for (const auto &grp : groups) {
-            for (int c0 = 0; c0 < n; c0 += chunk) {
-                const int cnt = std::min(chunk, n - c0);
-                // every rotation of the group reads the digits of t as it was before the group
-                if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
-                for (size_t e = 0; e < grp.size(); e++)
-                    if ((rc = run_rotations(ctx, ctx->ws_desc + (k + e) * n + c0, cnt, l1, t->limbs_alloc, t->limbs_alloc, st))) return rc;
-            }
-            k += grp.size();
         }
-        return ENSI_OK;
     }
-    if ((rc = grow(ctx, &ctx->ws_rtmp, &ctx->ws_rtmp_words, (size_t)n * 2 * l1 * N * 3))) return rc;
-    std::vector<int32_t> steps(n);
+    if ((rc = ensure_desc(ctx, desc.size()))) return rc;
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+    size_t k = 0;
     for (const auto &grp : groups) {
-        // all rotated copies of the group are formed from t before any of them is added
-        for (size_t e = 0; e < grp.size(); e++) {
-            ensi_ct tmp;
-            tmp.ctx = ctx;
-            tmp.n = n;
-            tmp.limbs = tmp.limbs_alloc = l1;
-            tmp.scale = t->scale;
-            tmp.d = ctx->ws_rtmp + e * (size_t)n * 2 * l1 * N;
-            tmp.owns = false;
-            std::fill(steps.begin(), steps.end(), grp[e]);
-            if ((rc = ensi_rotate(ctx, gk, t, steps.data(), &tmp, (void *)st))) return rc;
+        const int members = (int)grp.size();
+        for (int c0 = 0; c0 < n; c0 += chunk, k++) {
+            const int cnt = std::min(chunk, n - c0);
+            if ((rc = raise_cts(ctx, l1, t->d + (size_t)c0 * ct_words, ct_words, t->limbs_alloc, cnt, st))) return rc;
+            if ((rc = run_rotations(ctx, ctx->ws_desc + base[k], cnt * members, l1, t->limbs_alloc, fused ? t->limbs_alloc : l1, st, members,
+                                    desc.data() + base[k])))
+                return rc;
+            if (!fused) launch_ct_add(ctx, t->d + (size_t)c0 * ct_words, t->limbs_alloc, ctx->ws_rtmp, l1, l1, cnt, st);
         }
-        for (size_t e = 0; e < grp.size(); e++)
-            launch_ct_add(ctx, t->d, t->limbs_alloc, ctx->ws_rtmp + e * (size_t)n * 2 * l1 * N, l1, l1, n, st);
     }
     return ENSI_OK;
 }

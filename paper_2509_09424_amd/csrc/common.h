@@ -257,8 +257,10 @@ void launch_ks16_key_format(ensi_ctx *ctx, u64 *key, int beta_full, hipStream_t 
 void launch_ks16_raise(ensi_ctx *ctx, const Ks16Const &kc, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct,
                        u64 *ybuf, u64 *dig, hipStream_t st);
 // inner product + inverse transform + ModDown for n_rot descriptors (desc.digits = the ciphertext's block of dig)
+// members > 1: the descriptors come in groups of `members` rotations of one ciphertext (same digits and destination);
+// a group's inner products are added before one inverse transform and one ModDown
 void launch_ks16_switch(ensi_ctx *ctx, const Ks16Const &kc, const RotDesc *d_desc, int n_rot, u64 *u, u64 *ysp, int limb_stride_out,
-                        hipStream_t st);
+                        hipStream_t st, int members = 1);
 
 void launch_modup(ensi_ctx *ctx, const ModUpConst &mc, const u64 *ct_base, size_t ct_stride_words, int limb_stride,
                   int n_ct, u64 *digits, hipStream_t st);

@@ -178,34 +178,40 @@ struct LimbList {
     int32_t e[ENSI_MAX_EXT];
 };
 
+// members > 1: the block adds the inner products of `members` consecutive descriptors (rotations of one ciphertext:
+// same digits, their own Galois element and key) before the inverse pass, so that the group is brought back to
+// the ciphertext basis by one inverse transform and one ModDown; grid y then counts groups.
 template <bool FP>
 __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
-                                                                 u64 *u, LimbList limbs) {
+                                                                 u64 *u, LimbList limbs, int members) {
     __shared__ u64 lds[(FP ? 1 : 2) * (4096 + 256)];
     const int tid = threadIdx.x, rho = tid >> 4, j16 = tid & 15;
     const int rot = blockIdx.y, e = limbs.e[blockIdx.z];
     const int l1 = kc.l1, ext = l1 + kc.K, ext_full = kc.L + kc.K, beta = kc.beta;
-    const RotDesc d = desc[rot];
     const int prime = ks_ext_prime(e, l1, kc.L);
     const PrimeConst pc = pcs[prime];
     const u64 *tw = tw_all + (size_t)prime * 4 * KS_N + 2 * KS_N;
     const int r0 = blockIdx.x * 16;
-    const u64 *dg = d.digits + (size_t)e * KS_N;
-    const u64 *key = d.key + (size_t)prime * KS_N + (size_t)r0 * 256 + tid;
     const size_t kstride = (size_t)ext_full * KS_N;  // words between b_j and a_j, and half the distance between digits
     u64 *uo = u + ((size_t)rot * 2 * ext + e) * KS_N + (size_t)r0 * 256;
     if (FP) {
         ArithFp ar;
         ar.init(pc);
         double a0[16], a1[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) a0[i] = a1[i] = 0.0;
+#pragma unroll 1
+        for (int mem = 0; mem < members; mem++) {
+        const RotDesc d = desc[rot * members + mem];
+        const u64 *dg = d.digits + (size_t)e * KS_N;
+        const u64 *key = d.key + (size_t)prime * KS_N + (size_t)r0 * 256 + tid;
         u32 ks[16];
 #pragma unroll
         for (int i = 0; i < 16; i++) ks[i] = ks_perm((u32)((r0 + i) * 256 + tid), d.g);
         const u64 *c0h = d.digits + ((size_t)beta * ext + e) * KS_N;
+        if (e < l1) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) {
-            a0[i] = e < l1 ? as_f64(c0h[ks[i]]) : 0.0;
-            a1[i] = 0.0;
+            for (int i = 0; i < 16; i++) a0[i] += as_f64(c0h[ks[i]]);
         }
         // one digit at a time; the operands of KS_BATCH positions are loaded together, then consumed
 #pragma unroll 1
@@ -227,6 +233,15 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
                     a1[h + i] += ar.mulmod_np(x[i], k1[i]);
                 }
             }
+        }
+        if (members > 1) {
+            // a member adds up to beta + 1 terms below 0.7 p: reduced between members, the sums stay exact integers
+#pragma unroll
+            for (int i = 0; i < 16; i++) {
+                a0[i] = ar.mid(a0[i]);
+                a1[i] = ar.mid(a1[i]);
+            }
+        }
         }
         double *l = (double *)lds;
         double v[16];
@@ -254,6 +269,11 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
             u64 t0[8], t1[8];
 #pragma unroll
             for (int i = 0; i < 8; i++) t0[i] = t1[i] = 0;
+#pragma unroll 1
+            for (int mem = 0; mem < members; mem++) {
+            const RotDesc d = desc[rot * members + mem];
+            const u64 *dg = d.digits + (size_t)e * KS_N;
+            const u64 *key = d.key + (size_t)prime * KS_N + (size_t)r0 * 256 + tid;
 #pragma unroll 1
             for (int j0 = 0; j0 < beta; j0 += 4) {
                 acc128 s0[8], s1[8];
@@ -284,6 +304,7 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
                     t0[i] = add_mod(t0[i], mont_reduce(s0[i], pc.q, pc.qneg_inv), pc.q);
                     t1[i] = add_mod(t1[i], mont_reduce(s1[i], pc.q, pc.qneg_inv), pc.q);
                 }
+            }
             }
 #pragma unroll
             for (int i = 0; i < 8; i++) {
@@ -363,7 +384,7 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_special(Ks16Const kc,
 
 // grid (l1, 32, n_rot): blockIdx.y = poly * 16 + column tile
 __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
-                                                                const u64 *u, const u64 *ysp, int limb_stride_out) {
+                                                                const u64 *u, const u64 *ysp, int limb_stride_out, int members) {
     __shared__ u64 lds[4096];
     const int tid = threadIdx.x, c = tid & 15, jj = tid >> 4;
     const int limb = blockIdx.x, poly = blockIdx.y >> 4, rot = blockIdx.z;
@@ -371,7 +392,8 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, co
     const size_t col = (size_t)(blockIdx.y & 15) * 16 + c;
     const u64 *src = u + (((size_t)rot * 2 + poly) * ext + limb) * KS_N + col;
     const u64 *ys = ysp + ((size_t)rot * 2 + poly) * K * KS_N + col;
-    u64 *out = desc[rot].out + ((size_t)poly * limb_stride_out + limb) * KS_N + col;
+    const RotDesc dl = desc[rot * members];  // the group's first descriptor carries the destination
+    u64 *out = dl.out + ((size_t)poly * limb_stride_out + limb) * KS_N + col;
     const PrimeConst pc = pcs[limb];
     const u64 *tw = tw_all + (size_t)limb * 4 * KS_N + 2 * KS_N;
     ArithFp ar;
@@ -399,7 +421,7 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, co
             }
         }
     }
-    if (desc[rot].accumulate) {
+    if (dl.accumulate) {
         // out <- out + result: `out` may be the rotation's own source (every read of the source happened in the
         // raise kernels, which have finished), which turns t <- t + Rot(t; r) into one pass
         const u64 q = pc.q;
@@ -453,7 +475,9 @@ void launch_ks16_raise(ensi_ctx *ctx, const Ks16Const &kc, const u64 *ct_base, s
 }
 
 void launch_ks16_switch(ensi_ctx *ctx, const Ks16Const &kc, const RotDesc *d_desc, int n_rot, u64 *u, u64 *ysp, int limb_stride_out,
-                        hipStream_t st) {
+                        hipStream_t st, int members) {
+    // n_rot descriptors in groups of `members` (1: every rotation on its own); u and ysp are indexed by group
+    const int n_grp = n_rot / members;
     // limbs of wide primes (integer arithmetic, ALU-bound) first, then the fp64 limbs (memory-bound)
     LimbList wide, fp;
     wide.n = fp.n = 0;
@@ -464,19 +488,20 @@ void launch_ks16_switch(ensi_ctx *ctx, const Ks16Const &kc, const RotDesc *d_des
     }
     if (wide.n) {
         ScopedTimer t(ctx, "ks_inner_irows_wide", st);
-        hipLaunchKernelGGL(k_ks16_inner_irows<false>, dim3(16, n_rot, wide.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, wide);
+        hipLaunchKernelGGL(k_ks16_inner_irows<false>, dim3(16, n_grp, wide.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, wide,
+                           members);
     }
     if (fp.n) {
         ScopedTimer t(ctx, "ks_inner_irows", st);
-        hipLaunchKernelGGL(k_ks16_inner_irows<true>, dim3(16, n_rot, fp.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, fp);
+        hipLaunchKernelGGL(k_ks16_inner_irows<true>, dim3(16, n_grp, fp.n), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, fp, members);
     }
     {
         ScopedTimer t(ctx, "ks_icols_special", st);
-        hipLaunchKernelGGL(k_ks16_icols_special, dim3(16, 2 * kc.K, n_rot), dim3(KS_THREADS), 0, st, kc, ctx->d_pc, ctx->d_tw, u, ysp);
+        hipLaunchKernelGGL(k_ks16_icols_special, dim3(16, 2 * kc.K, n_grp), dim3(KS_THREADS), 0, st, kc, ctx->d_pc, ctx->d_tw, u, ysp);
     }
     {
         ScopedTimer t(ctx, "ks_icols_moddown", st);
-        hipLaunchKernelGGL(k_ks16_icols_down, dim3(kc.l1, 32, n_rot), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, ysp,
-                           limb_stride_out);
+        hipLaunchKernelGGL(k_ks16_icols_down, dim3(kc.l1, 32, n_grp), dim3(KS_THREADS), 0, st, kc, d_desc, ctx->d_pc, ctx->d_tw, u, ysp,
+                           limb_stride_out, members);
     }
 }
