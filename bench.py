@@ -288,6 +288,7 @@ def roofline_for(w, prof):
     ext = L + K
     beta = -(-L // alpha)
     pm_terms = pm_out = 0
+    n_sw = None  # key switches brought back to the ciphertext basis (grouped rotations share one); default: every rotation
     Lp = L  # level of the plaintext multiplication (the CCMM's key switches run one level below it)
     if w.name == "keyswitch":
         n_rot, n_raise = w.batch, w.batch
@@ -310,6 +311,7 @@ def roofline_for(w, prof):
         beta = -(-L // alpha)
         n_rot = n_el * (1 + f_rot) + w.d_out
         n_raise = w.d_in + n_el * f_raise + w.d_out
+        n_sw = n_el * (1 + f_raise) + w.d_out
         n_key = -(-w.d_in // 16) * w.d_out + f_rot * -(-n_el // 64) + 1
         pm_terms = pm_out = n_el
     elif w.op == "ccmm":
@@ -324,6 +326,7 @@ def roofline_for(w, prof):
         beta = -(-L // alpha)
         n_rot = n_el * b_rot + w.d_out * g_rot + w.d_out
         n_raise = n_el * b_raise + w.d_out * g_raise + w.d_out
+        n_sw = n_raise
         n_key = b_rot * -(-n_el // 64) + g_rot + 1
         pm_terms = pm_out = n_el
     else:
@@ -331,16 +334,18 @@ def roofline_for(w, prof):
         n_rot, n_raise = w.d_in - n_in, n_in
         # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
         n_key = -(-n_in // 16) * (min(w.c_tot, w.d_in) - 1)
+    if n_sw is None:
+        n_sw = n_rot
     # HBM-bound classes: algorithmic limb-units per step (every operand read once, every result written once)
     hbm = {
         # fused path (N = 2^16, ciphertext primes below 2^50)
         "ks_pre": n_raise * 2 * L,
         "ks_modup_fcols": n_raise * (3 * L + beta * ext + L),        # y, c1, c0 in; raised digits and P*c0 out
         "ks_frows": n_raise * 2 * (beta * ext + L),
-        "ks_inner_irows": n_rot * (beta * L + L + 2 * L) + n_key * 2 * beta * L,   # ciphertext limbs: digits, P*c0, key in; accumulators out
-        "ks_inner_irows_wide": n_rot * (beta * K + 2 * K) + n_key * 2 * beta * K,  # special limbs (integer arithmetic)
-        "ks_icols_special": n_rot * 4 * K,                                     # special limbs in, split residues out
-        "ks_icols_moddown": n_rot * (2 * L + 2 * K + 2 * L),                   # accumulators and residues in, ciphertext out
+        "ks_inner_irows": n_rot * (beta * L + L) + n_sw * 2 * L + n_key * 2 * beta * L,   # ciphertext limbs: digits, P*c0, key in; accumulators out
+        "ks_inner_irows_wide": n_rot * beta * K + n_sw * 2 * K + n_key * 2 * beta * K,    # special limbs (integer arithmetic)
+        "ks_icols_special": n_sw * 4 * K,                                      # special limbs in, split residues out
+        "ks_icols_moddown": n_sw * (2 * L + 2 * K + 2 * L),                    # accumulators and residues in, ciphertext out
         # unfused path
         "ntt": 2 * (n_raise * beta * ext + n_rot * 2 * ext),
         "inner_product": n_rot * (3 * beta * ext + 2 * ext),
