@@ -699,3 +699,55 @@ class Oracle:
             reps = [self.extract_blockwise(b, i, s, mask0, gks) for b in b_cts]
             out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a, l1 - 1), r) for a, r in zip(a_cts, reps)], rk))
         return out
+
+    # ------------------------- CCMM over heads, element extraction in baby steps and giant steps
+    def block_head_mask(self, s, period, l1):
+        """Integer coefficients [N] of the mask with a 1 in the first `period` slots of every block of s slots, at scale q_l."""
+        z = np.zeros(self.n)
+        for x in range(period):
+            z[x::s] = 1.0
+        return self.encode_coeffs(z, float(self.pr.q[l1 - 1]))
+
+    def spread_segment(self, ct, g, s, period, mask_head, gks):
+        """Giant step of the block-wise extraction, shared by the `period` elements of a segment:
+        Rot(.; g period) brings slots [g period, (g+1) period) of every block to the block's start,
+        the head mask keeps them (PMult, one rescale), and the fill of fill_steps(period, s, -1)
+        repeats them upwards through the block: slot h s + x then holds slot h s + g period +
+        (x mod period) of the input."""
+        l1 = ct.l1
+        t = self.rotate(ct, gks[g * period]) if g else ct
+        t = self.pmult_sum_rescale([(t, self.i64_to_rns(mask_head, self.pr.q[:l1]))], float(self.pr.q[l1 - 1]))
+        return self.fill(t, period, s, gks, sign=-1)
+
+    def extract_from_segment(self, w, b, period, mask_start, gks):
+        """Baby step, per element: Rot(.; b) brings element b of every period of the spread segment
+        to the period's first slot, the mask of the slots congruent to 0 modulo the period keeps it
+        (PMult, one rescale) and the fill of fill_steps(1, period, -1) copies it upwards through its
+        period.  Nothing crosses a block boundary: every read stays below the block's end."""
+        l1 = w.l1
+        t = self.rotate(w, gks[b]) if b else w
+        t = self.pmult_sum_rescale([(t, self.i64_to_rns(mask_start, self.pr.q[:l1]))], float(self.pr.q[l1 - 1]))
+        return self.fill(t, 1, period, gks, sign=-1)
+
+    def ccmm_bsgs(self, a_cts, b_cts, s, period, terms, rk, gks):
+        """CCMM section, several heads per ciphertext (blocks of s slots), with the element
+        extraction split into giant and baby steps: out_o = sum over (ia, ib, slot) in terms[o] of
+        a_ia (x) E(b_ib, slot), where E copies slot `slot` of every block of b_ib into all s slots
+        of its block, slot = g period + b.  Segments (ib, g) and elements (ib, slot) that several
+        terms name are formed once.  Q K^T: terms[o] = [(j, j, i_o) for j]; weights times V:
+        terms[i] = [(j, i, j) for j].  Three levels (two masks, the product)."""
+        l1 = b_cts[0].l1
+        mask_head = self.block_head_mask(s, period, l1)
+        mask_start = self.periodic_masks(period, 1, l1 - 1)[0]
+        segs, reps, out = {}, {}, []
+        for tl in terms:
+            pairs = []
+            for ia, ib, slot in tl:
+                g, b = divmod(slot, period)
+                if (ib, g) not in segs:
+                    segs[(ib, g)] = self.spread_segment(b_cts[ib], g, s, period, mask_head, gks)
+                if (ib, slot) not in reps:
+                    reps[(ib, slot)] = self.extract_from_segment(segs[(ib, g)], b, period, mask_start, gks)
+                pairs.append((self.drop_limbs(a_cts[ia], l1 - 2), reps[(ib, slot)]))
+            out.append(self.mult_sum_relin_rescale(pairs, rk))
+        return out

@@ -551,6 +551,54 @@ def test_blockwise_extraction_and_ccmm_over_heads():
         assert np.abs(o.decrypt(c, sk) - ref).max() < 1e-3, i
 
 
+def test_giant_and_baby_step_extraction_over_heads():
+    """Block-wise extraction in giant and baby steps: the spread segment, one extracted element, and both
+    attention products (Q K^T and weights times V) for every head at once against numpy."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 6)  # 32 slots: 2 heads of 16 tokens
+    o = Oracle(pr)
+    rng = np.random.default_rng(97)
+    sk, pk = _keys(o, rng)
+    l1, s, heads, d, period = 5, 16, 2, 3, 4
+    Q = rng.uniform(-1, 1, (heads, s, d))
+    K = rng.uniform(-1, 1, (heads, s, d))
+    a_cts = [_enc(o, rng, pk, np.concatenate([Q[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    b_cts = [_enc(o, rng, pk, np.concatenate([K[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    beta = pr.beta(pr.L)
+    cols = [0, 6, 15]
+    steps = set(range(1, period)) | {g * period for g in range(1, s // period)}
+    steps |= {st for grp in Oracle.fill_steps(period, s, -1) + Oracle.fill_steps(1, period, -1) for st in grp}
+    gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 101) for st in sorted(steps)}
+    rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 103)
+    # the head mask: ones in the first `period` slots of every block
+    mh = o.block_head_mask(s, period, l1)
+    z = o.decode_coeffs(mh.astype(np.float64), float(pr.q[l1 - 1]))
+    assert np.abs(z - np.tile(np.concatenate([np.ones(period), np.zeros(s - period)]), heads)).max() < 1e-9
+    # giant step: segment 1 of every block, repeated through the block
+    seg = o.spread_segment(b_cts[2], 1, s, period, mh, gks)
+    want = np.concatenate([np.tile(K[h][period:2 * period, 2], s // period) for h in range(heads)])
+    assert seg.l1 == l1 - 1 and np.abs(o.decrypt(seg, sk) - want).max() < 1e-3
+    # baby step: element 2 of that segment, i.e. slot 6 of every block, in all slots of its block
+    one = o.extract_from_segment(seg, 2, period, o.periodic_masks(period, 1, l1 - 1)[0], gks)
+    want = np.concatenate([np.full(s, K[h][6, 2]) for h in range(heads)])
+    assert one.l1 == l1 - 2 and np.abs(o.decrypt(one, sk) - want).max() < 1e-3
+    # Q K^T, columns 0, 6 (giant and baby step both non-trivial) and 15 (last slot of a block)
+    C = o.ccmm_bsgs(a_cts, b_cts, s, period, [[(j, j, i) for j in range(d)] for i in cols], rk, gks)
+    assert len(C) == len(cols) and all(c.l1 == l1 - 3 for c in C)
+    for c, i in zip(C, cols):
+        ref = np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)])
+        assert np.abs(o.decrypt(c, sk) - ref).max() < 1e-3, i
+    # weights times V: a_j = column j of the s x s weights (j < s), v_i = column i of V; out_i = sum_j a_j (x) E(v_i, j)
+    Wt = rng.uniform(-1, 1, (heads, s, s)) / 4
+    V = rng.uniform(-1, 1, (heads, s, 2))
+    w_cts = [_enc(o, rng, pk, np.concatenate([Wt[h][:, j] for h in range(heads)]), l1) for j in range(s)]
+    v_cts = [_enc(o, rng, pk, np.concatenate([V[h][:, i] for h in range(heads)]), l1) for i in range(2)]
+    O = o.ccmm_bsgs(w_cts, v_cts, s, period, [[(j, i, j) for j in range(s)] for i in range(2)], rk, gks)
+    for i in range(2):
+        ref = np.concatenate([(Wt[h] @ V[h])[:, i] for h in range(heads)])
+        assert O[i].l1 == l1 - 3 and np.abs(o.decrypt(O[i], sk) - ref).max() < 1e-3, i
+
+
 # -------------------------------------------------------------------- PCMM
 def _read_toy():
     W, Y = [], {}
