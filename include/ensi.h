@@ -280,6 +280,27 @@ int ensi_block_start_mask(ensi_ctx *ctx, int32_t s, int32_t limbs, ensi_pt **pt)
 int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
                      const int32_t *cols, int32_t n_cols, const ensi_pt *mask, ensi_ct *out, void *stream);
 
+/* The block-wise product with the element extraction split into giant and baby steps (CCMM section: masks,
+ * rotations and a shared part of the work per group of elements; the figure with the paper's own schedule is not in
+ * its text), over term lists so that both attention products fit:
+ *   out_o = Rescale(Relin(sum over t in [begin[o], begin[o+1]) of A[term_a[t]] (x) E(B[term_b[t]], term_slot[t]))),
+ * where E(b, slot) is slot `slot` of every block of s slots of b copied into all s slots of its block.
+ * Q K^T: terms of output o are (j, j, i_o) for all j; weights times V: terms of output i are (j, i, j) for all j.
+ * With slot = g period + e:  giant step, once per (b, g): Rot(b; g period) brings the segment to the block's start,
+ * the head mask keeps its `period` slots (one product, one rescale), the fill with steps -period, -2 period, ... repeats
+ * it through the block; baby step, per element: Rot(.; e) brings the element to the start of every period, the mask of
+ * the slots congruent to 0 modulo the period keeps it (one product, one rescale), the fill with steps -1, -2, ... copies it
+ * through the period.  Elements and segments named by several terms of a call are formed once.
+ * gk must hold keys for the steps g period and e in use and for ensi_fill_steps(period, s, -1) and
+ * ensi_fill_steps(1, period, -1).  mask_head: ensi_block_head_mask(s, period, limbs = l); mask_start:
+ * ensi_periodic_masks(period, 1, limbs = l - 1).  A, B at l limbs (l >= 4); out: n_out ciphertexts at l - 3 limbs.
+ * begin: host int32[n_out + 1]; term_*: host int32[begin[n_out]].  An output's products are relinearised together,
+ * so all its distinct elements are held at once (about 2 (l - 2) N words each); outputs are grouped up to 512 elements. */
+int ensi_block_head_mask(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **pt);
+int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s, int32_t period,
+                   const int32_t *begin, const int32_t *term_a, const int32_t *term_b, const int32_t *term_slot, int32_t n_out,
+                   const ensi_pt *mask_head, const ensi_pt *mask_start, ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

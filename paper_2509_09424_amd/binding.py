@@ -23,7 +23,7 @@ EXPORTED = [
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
-    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -324,6 +324,23 @@ class Context:
             ct_out = self.ct_alloc(len(cols), ct_b.limbs - 2)
         self._check(self.lib.ensi_ccmm_blocks(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), _ptr(cols), len(cols), mask.h, ct_out.h,
                                               ctypes.c_void_p(stream)))
+        return ct_out
+
+    def block_head_mask(self, s, period, limbs):
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_block_head_mask(self.h, int(s), int(period), int(limbs), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=1)
+
+    def ccmm_bsgs(self, rk, gk, ct_a, ct_b, s, period, terms, mask_head, mask_start, ct_out=None, stream=0):
+        """terms: per output a list of (index into ct_a, index into ct_b, slot)."""
+        begin = np.zeros(len(terms) + 1, dtype=np.int32)
+        begin[1:] = np.cumsum([len(t) for t in terms])
+        flat = np.array([x for t in terms for x in t], dtype=np.int32).reshape(-1, 3)
+        ta, tb, ts = (np.ascontiguousarray(flat[:, k]) for k in range(3))
+        if ct_out is None:
+            ct_out = self.ct_alloc(len(terms), ct_b.limbs - 3)
+        self._check(self.lib.ensi_ccmm_bsgs(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), _ptr(begin), _ptr(ta), _ptr(tb),
+                                            _ptr(ts), len(terms), mask_head.h, mask_start.h, ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

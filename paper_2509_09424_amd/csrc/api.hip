@@ -8,6 +8,7 @@
 
 #include <algorithm>
 #include <random>
+#include <set>
 
 #include "common.h"
 #include "hostmath.h"
@@ -2075,6 +2076,230 @@ extern "C" int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk 
         part.n = cnt;
         if ((rc = mult_core(ctx, key, terms, begin, lo, A->limbs_alloc, lo, &part, st))) return rc;
         out->scale = A->scale * rep.scale / (double)ctx->primes[lo - 1];
+    }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ---------------------- CCMM, several heads per ciphertext, extraction in giant and baby steps
+extern "C" int ensi_block_head_mask(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !out || s < 1 || (s & (s - 1)) || s > ctx->N / 2 || period < 1 || (period & (period - 1)) || period > s || limbs < 2 ||
+        limbs > ctx->L)
+        return ENSI_E_BADARG;
+    const int n = ctx->N / 2;
+    std::vector<double> z(n, 0.0);
+    for (int p = 0; p < n; p += s)
+        for (int x = 0; x < period; x++) z[p + x] = 1.0;
+    return encode_window(ctx, z.data(), 1, n, 0, 0, limbs, (double)ctx->primes[limbs - 1], out);
+}
+
+struct RotJob {
+    int src;       // index into the source batch
+    int32_t step;  // rotation amount; 0 = copy
+    u64 *dst;      // destination ciphertext, limb stride l1
+};
+
+// dst_k = Rot(src batch[job.src]; job.step) for every job: the sources are raised in groups of up to 16 neighbours
+// and each raise serves all the rotations of its ciphertexts (jobs of a group ordered by amount, so that rotations
+// with the same key are neighbours).  Source batch: ciphertext stride src_ct words, limb stride limb_stride_in.
+static int rotate_jobs(ensi_ctx *ctx, const ensi_gk *gk, const u64 *src, size_t src_ct, int limb_stride_in, int n_src, int l1,
+                       std::vector<RotJob> jobs, hipStream_t st) {
+    const int N = ctx->N, ext = l1 + ctx->K;
+    const size_t rw = raised_words(ctx, l1);
+    const int GS = 16, per = std::max(1, rot_chunk() * 2 / GS);
+    int rc;
+    if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, (size_t)GS * rw))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, (size_t)GS * per * 2 * ext * N))) return rc;
+    if ((rc = ensure_desc(ctx, (size_t)GS * per))) return rc;
+    for (const RotJob &j : jobs)
+        if (j.src < 0 || j.src >= n_src) ENSI_FAIL(ctx, ENSI_E_BADARG, "rotation source %d outside the batch of %d", j.src, n_src);
+    std::stable_sort(jobs.begin(), jobs.end(), [&](const RotJob &a, const RotJob &b) {
+        const int ga = a.src / GS, gb = b.src / GS;
+        return ga != gb ? ga < gb : a.step != b.step ? a.step < b.step : a.src < b.src;
+    });
+    for (size_t k0 = 0; k0 < jobs.size();) {
+        const int grp = jobs[k0].src / GS;
+        size_t k1 = k0;
+        int lo = n_src, hi = -1;
+        bool any = false;
+        while (k1 < jobs.size() && jobs[k1].src / GS == grp) {
+            if (jobs[k1].step) {
+                lo = std::min(lo, jobs[k1].src);
+                hi = std::max(hi, jobs[k1].src);
+                any = true;
+            }
+            k1++;
+        }
+        if (any && (rc = raise_cts(ctx, l1, src + (size_t)lo * src_ct, src_ct, limb_stride_in, hi - lo + 1, st))) return rc;
+        std::vector<RotDesc> desc;
+        auto flush = [&]() -> int {
+            if (desc.empty()) return ENSI_OK;
+            if (hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st) != hipSuccess)
+                ENSI_FAIL(ctx, ENSI_E_HIP, "descriptor copy failed");
+            const int r = run_rotations(ctx, ctx->ws_desc, (int)desc.size(), l1, limb_stride_in, l1, st);
+            desc.clear();
+            return r;
+        };
+        for (size_t k = k0; k < k1; k++) {
+            const RotJob &j = jobs[k];
+            const u64 *from = src + (size_t)j.src * src_ct;
+            if (j.step == 0) {
+                for (int poly = 0; poly < 2; poly++)
+                    ENSI_HIP(ctx, hipMemcpyAsync(j.dst + (size_t)poly * l1 * N, from + (size_t)poly * limb_stride_in * N, (size_t)l1 * N * 8,
+                                                 hipMemcpyDeviceToDevice, st));
+                continue;
+            }
+            const u32 g = galois_element(ctx, j.step);
+            auto it = gk->keys.find(g);
+            if (it == gk->keys.end()) ENSI_FAIL(ctx, ENSI_E_NOKEY, "no Galois key for step %d", j.step);
+            RotDesc r = {};
+            r.c0 = from;
+            r.digits = ctx->ws_digits + (size_t)(j.src - lo) * rw;
+            r.key = it->second;
+            r.out = j.dst;
+            r.g = g;
+            r.g_inv = inv_mod_2n(g, N);
+            desc.push_back(r);
+            if ((int)desc.size() == GS * per && (rc = flush())) return rc;
+        }
+        if ((rc = flush())) return rc;
+        k0 = k1;
+    }
+    return ENSI_OK;
+}
+
+extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
+                              int32_t period, const int32_t *begin, const int32_t *term_a, const int32_t *term_b, const int32_t *term_slot,
+                              int32_t n_out, const ensi_pt *mask_head, const ensi_pt *mask_start, ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !gk || !A || !B || !begin || !mask_head || !mask_start || !out || n_out < 1) return ENSI_E_BADARG;
+    const int N = ctx->N, l1 = B->limbs;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
+    if (period < 1 || (period & (period - 1)) || period > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
+    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    if (l1 < 4 || out->limbs != l1 - 3) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be three levels below the operands");
+    if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, n_out);
+    if (mask_head->n < 1 || mask_start->n < 1 || mask_head->limbs < l1 || mask_start->limbs < l1 - 1)
+        ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the masks need %d and %d limbs", l1, l1 - 1);
+    if (begin[0] != 0) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must start at 0");
+    for (int o = 0; o < n_out; o++)
+        if (begin[o + 1] < begin[o]) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must not decrease");
+    const int T = begin[n_out];
+    if (T > 0 && (!term_a || !term_b || !term_slot)) return ENSI_E_BADARG;
+    for (int t = 0; t < T; t++)
+        if (term_a[t] < 0 || term_a[t] >= A->n || term_b[t] < 0 || term_b[t] >= B->n || term_slot[t] < 0 || term_slot[t] >= s)
+            ENSI_FAIL(ctx, ENSI_E_BADARG, "term %d names ciphertexts %d of %d and %d of %d, slot %d of %d", t, term_a[t], A->n, term_b[t], B->n,
+                      term_slot[t], s);
+    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int l2 = l1 - 1, l3 = l1 - 2;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, b_ct = (size_t)2 * B->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    const size_t seg_ct = (size_t)2 * l2 * N, rep_ct = (size_t)2 * l3 * N;
+
+    // groups of outputs whose distinct elements fit the workspace (an output is never split: its products are
+    // relinearised together)
+    const size_t cap = 512;
+    struct Chunk {
+        int o0, o1;
+        std::vector<std::pair<int, int>> segs, els;  // (b, g) and (b, slot), in order of first use
+        std::vector<int> el_seg, term_el;            // segment of each element; element of each term from begin[o0] on
+    };
+    std::vector<Chunk> chunks;
+    for (int o0 = 0; o0 < n_out;) {
+        Chunk c;
+        c.o0 = o0;
+        std::map<std::pair<int, int>, int> seg_id, el_id;
+        int o = o0;
+        for (; o < n_out; o++) {
+            size_t fresh = 0;
+            std::set<std::pair<int, int>> seen;
+            for (int t = begin[o]; t < begin[o + 1]; t++) {
+                const std::pair<int, int> e(term_b[t], term_slot[t]);
+                if (!el_id.count(e) && seen.insert(e).second) fresh++;
+            }
+            if (o > o0 && c.els.size() + fresh > cap) break;
+            for (int t = begin[o]; t < begin[o + 1]; t++) {
+                const std::pair<int, int> e(term_b[t], term_slot[t]), g(term_b[t], term_slot[t] / period);
+                auto ie = el_id.find(e);
+                if (ie == el_id.end()) {
+                    auto ig = seg_id.find(g);
+                    if (ig == seg_id.end()) {
+                        ig = seg_id.emplace(g, (int)c.segs.size()).first;
+                        c.segs.push_back(g);
+                    }
+                    ie = el_id.emplace(e, (int)c.els.size()).first;
+                    c.els.push_back(e);
+                    c.el_seg.push_back(ig->second);
+                }
+                c.term_el.push_back(ie->second);
+            }
+        }
+        c.o1 = o;
+        o0 = o;
+        chunks.push_back(std::move(c));
+    }
+    size_t max_seg = 1, max_el = 1;
+    for (const Chunk &c : chunks) {
+        max_seg = std::max(max_seg, c.segs.size());
+        max_el = std::max(max_el, c.els.size());
+    }
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max(max_seg * 2 * l1 * N, max_el * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, max_seg * seg_ct + max_el * rep_ct))) return rc;
+
+    for (const Chunk &c : chunks) {
+        const int S = (int)c.segs.size(), E = (int)c.els.size();
+        ensi_ct view;
+        view.ctx = ctx;
+        view.owns = false;
+        // giant steps: segment g of every block to the block's start, kept by the head mask, repeated through the block
+        std::vector<RotJob> jobs(S);
+        for (int k = 0; k < S; k++) jobs[k] = {c.segs[k].first, c.segs[k].second * period, ctx->ws_rot + (size_t)k * 2 * l1 * N};
+        if (S && (rc = rotate_jobs(ctx, gk, B->d, b_ct, B->limbs_alloc, B->n, l1, jobs, st))) return rc;
+        ensi_ct al = view, seg = view, rep = view;
+        al.n = S;
+        al.limbs = al.limbs_alloc = l1;
+        al.scale = B->scale;
+        al.d = ctx->ws_rot;
+        seg.n = S;
+        seg.limbs = seg.limbs_alloc = l2;
+        seg.d = ctx->ws_rep;
+        seg.scale = B->scale;
+        if (S) {
+            std::vector<int32_t> src(S), mi(S, 0);
+            for (int k = 0; k < S; k++) src[k] = k;
+            if ((rc = mask_rescale(ctx, &al, src, mask_head, mi, &seg, st))) return rc;
+            if ((rc = doubling_steps(ctx, gk, &seg, period, s, st, -1))) return rc;
+        }
+        // baby steps: element b of every period to the period's start, kept by the period-start mask, copied through the period
+        jobs.assign(E, RotJob());
+        for (int k = 0; k < E; k++) jobs[k] = {c.el_seg[k], c.els[k].second % period, ctx->ws_rot + (size_t)k * seg_ct};
+        if (E && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, S, l2, jobs, st))) return rc;
+        al.n = E;
+        al.limbs = al.limbs_alloc = l2;
+        al.scale = seg.scale;
+        rep.n = E;
+        rep.limbs = rep.limbs_alloc = l3;
+        rep.d = ctx->ws_rep + max_seg * seg_ct;
+        rep.scale = seg.scale;
+        if (E) {
+            std::vector<int32_t> src(E), mi(E, 0);
+            for (int k = 0; k < E; k++) src[k] = k;
+            if ((rc = mask_rescale(ctx, &al, src, mask_start, mi, &rep, st))) return rc;
+            if ((rc = doubling_steps(ctx, gk, &rep, 1, period, st, -1))) return rc;
+        }
+        const int tb = begin[c.o0], cnt = c.o1 - c.o0;
+        std::vector<MmTerm> terms(begin[c.o1] - tb);
+        std::vector<int32_t> bg(cnt + 1);
+        for (int o = 0; o <= cnt; o++) bg[o] = begin[c.o0 + o] - tb;
+        for (size_t t = 0; t < terms.size(); t++) terms[t] = {A->d + (size_t)term_a[tb + t] * a_ct, rep.d + (size_t)c.term_el[t] * rep_ct};
+        ensi_ct part = *out;
+        part.owns = false;
+        part.d = out->d + (size_t)c.o0 * out_ct;
+        part.n = cnt;
+        if ((rc = mult_core(ctx, key, terms, bg, l3, A->limbs_alloc, l3, &part, st))) return rc;
+        out->scale = A->scale * rep.scale / (double)ctx->primes[l3 - 1];
     }
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;

@@ -62,3 +62,5 @@ def test_null_arguments_of_the_later_entry_points_without_gpu():
     assert lib.ensi_fill_steps(0, 8, 1, n, 0) == -1 and lib.ensi_fill_steps(1, 8, 0, n, 0) == -1
     assert lib.ensi_fill_steps(1, 32, -1, n, 0) == 7  # a pure host query: -1 -2 -3 | -4 -8 -12 | -16
     assert lib.ensi_ccmm_blocks(n, n, n, n, n, 2, n, 1, n, n, n) == -1
+    assert lib.ensi_block_head_mask(n, 4, 2, 2, n) == -1
+    assert lib.ensi_ccmm_bsgs(n, n, n, n, n, 4, 2, n, n, n, n, 1, n, n, n, n) == -1

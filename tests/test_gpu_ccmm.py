@@ -240,3 +240,128 @@ def test_ccmm_blocks_at_the_benchmark_parameters():
     for h in (g_a, g_b, g_mask, out, g_gk, g_rk):
         h.free()
     p.close()
+
+
+# ------------------------------------------------ extraction in giant and baby steps, term lists
+def bsgs_keys(p, s, period, slots):
+    steps = {sl % period for sl in slots} | {sl // period * period for sl in slots}
+    steps |= set(p.ctx.fill_steps(period, s, -1)) | set(p.ctx.fill_steps(1, period, -1))
+    return p.galois_keys(sorted(st for st in steps if st))
+
+
+def bsgs_masks(p, s, period, l1):
+    mh = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.block_head_mask(s, period, l1)[None, :], l1), float(p.pr.q[l1 - 1]))
+    ms = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.periodic_masks(period, 1, l1 - 1), l1 - 1), float(p.pr.q[l1 - 2]))
+    return mh, ms
+
+
+@pytest.mark.parametrize("params,l1,s,period,d,cols", [(SMALL4, 6, 64, 8, 5, [0, 1, 9, 63, 15]), (SMALL4, 5, 512, 64, 3, [77]),
+                                                       (WIDE, 4, 128, 16, 18, [5, 37])],
+                         ids=["8-heads", "one-head", "wide-primes-two-groups"])
+def test_ccmm_bsgs_qk_form_small_ring(params, l1, s, period, d, cols):
+    """Q K^T over heads with the extraction in giant and baby steps: bit-exact against the oracle, numpy after
+    decryption; the library's own masks give the same product within the bound."""
+    p = Pair(params)
+    heads = p.n // s
+    Q = p.rng.uniform(-1, 1, (heads, s, d))
+    K = p.rng.uniform(-1, 1, (heads, s, d))
+    o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_b, g_b = p.encrypt_both(np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_gks, g_gk = bsgs_keys(p, s, period, cols)
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    terms = [[(j, j, i) for j in range(d)] for i in cols]
+    out = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    want = p.o.ccmm_bsgs(o_a, o_b, s, period, terms, o_rk, o_gks)
+    assert out.n == len(cols) and out.limbs == l1 - 3
+    assert np.array_equal(out.export(), stack_cts(want))
+    ref = np.stack([np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)]) for i in cols])
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.periodic_masks(period, 1, l1 - 1)
+    out2 = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, lh, ls)
+    assert np.abs(p.ctx.decrypt(p.g_sk, out2) - ref).max() < 1e-3
+    with pytest.raises(p.binding.EnsiError, match="code -1"):
+        p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, [[(0, 0, s)]], mh, ms)  # slot outside the block
+    with pytest.raises(p.binding.EnsiError, match="code -3"):
+        p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, ms, ms)  # head mask one level short
+    for h in (g_a, g_b, mh, ms, lh, ls, out, out2, g_gk, g_rk):
+        h.free()
+    p.close()
+
+
+def test_ccmm_bsgs_weights_times_v_small_ring():
+    """The other attention product: out_i = sum_j a_j (x) E(v_i, j) with the s columns of the weights in a and the
+    columns of V in b; an output without terms, elements shared between outputs, more than 16 sources per stage."""
+    p = Pair(SMALL4)
+    l1, s, period, m = 5, 32, 4, 2
+    heads = p.n // s
+    Wt = p.rng.uniform(-1, 1, (heads, s, s)) / 4
+    V = p.rng.uniform(-1, 1, (heads, s, m))
+    o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Wt[h][:, j] for h in range(heads)]) for j in range(s)]), l1)
+    o_b, g_b = p.encrypt_both(np.stack([np.concatenate([V[h][:, i] for h in range(heads)]) for i in range(m)]), l1)
+    o_gks, g_gk = bsgs_keys(p, s, period, range(s))
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    # outputs 0, 1: the product; 2: nothing; 3: a sum that reuses elements of output 0 with other columns of a
+    terms = [[(j, i, j) for j in range(s)] for i in range(m)] + [[], [(1, 0, 0), (0, 0, 1), (5, 1, 31)]]
+    out = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    want = p.o.ccmm_bsgs(o_a, o_b, s, period, [t for t in terms if t], o_rk, o_gks)
+    got = out.export()
+    assert out.limbs == l1 - 3 and np.array_equal(got[[0, 1, 3]], stack_cts(want)) and not got[2].any()
+    dec = p.ctx.decrypt(p.g_sk, out)
+    for i in range(m):
+        assert np.abs(dec[i] - np.concatenate([(Wt[h] @ V[h])[:, i] for h in range(heads)])).max() < 1e-3
+    ref3 = np.concatenate([Wt[h][:, 1] * V[h][0, 0] + Wt[h][:, 0] * V[h][1, 0] + Wt[h][:, 5] * V[h][31, 1] for h in range(heads)])
+    assert np.abs(dec[3] - ref3).max() < 1e-3
+    for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
+        h.free()
+    p.close()
+
+
+def test_ccmm_bsgs_full_ring():
+    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 16, a narrow inner dimension and a low level so
+    that the oracle's fills take seconds; two columns of one segment and one of another."""
+    p = Pair(KEYSWITCH)
+    l1, s, period, d, cols = 5, 2048, 16, 2, [35, 32, 2047]
+    heads = p.n // s
+    Q = p.rng.uniform(-1, 1, (heads, s, d))
+    K = p.rng.uniform(-1, 1, (heads, s, d))
+    o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_b, g_b = p.encrypt_both(np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_gks, g_gk = bsgs_keys(p, s, period, cols)
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    terms = [[(j, j, i) for j in range(d)] for i in cols]
+    out = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    want = p.o.ccmm_bsgs(o_a, o_b, s, period, terms, o_rk, o_gks)
+    assert out.limbs == l1 - 3 and np.array_equal(out.export(), stack_cts(want))
+    ref = np.stack([np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)]) for i in cols])
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
+        h.free()
+    p.close()
+
+
+def test_ccmm_bsgs_at_the_benchmark_parameters():
+    """The 16 + 4 limb chain and the 16 x 2048 packing of the attention benchmark workloads, period 16, with a
+    narrow inner dimension (two terms, one output) so that the oracle's fills at 13 to 15 limbs take seconds."""
+    w = wl.BY_NAME["ccmmqk"]
+    p = Pair(w.param_tuple())
+    l1, s, period, d, cols = p.pr.L, w.tokens, 16, 2, [1029]
+    heads = p.n // s
+    Q = p.rng.uniform(-1, 1, (heads, s, d))
+    K = p.rng.uniform(-1, 1, (heads, s, d))
+    o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_b, g_b = p.encrypt_both(np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_gks, g_gk = bsgs_keys(p, s, period, cols)
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    terms = [[(j, j, i) for j in range(d)] for i in cols]
+    out = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    want = p.o.ccmm_bsgs(o_a, o_b, s, period, terms, o_rk, o_gks)
+    assert out.limbs == l1 - 3 and np.array_equal(out.export(), stack_cts(want))
+    ref = np.stack([np.concatenate([(Q[h] @ K[h].T)[:, i] for h in range(heads)]) for i in cols])
+    assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
+        h.free()
+    p.close()
