@@ -118,6 +118,44 @@ class Runner:
             self.pt = self.ctx.block_start_mask(sl, self.L)
             self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
             return
+        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+            # both attention products for every head at once, element extraction in giant and baby steps
+            sl, P = w.tokens, w.period
+            heads = self.n // sl
+            if w.op == "ccmm_bsgs":
+                # Q K^T: ciphertext j holds column j of all heads; a step forms the columns of segment 1
+                d, m = w.d_in, w.d_out
+                self.Q = rng.uniform(-1.0, 1.0, size=(heads, sl, d))
+                self.K = rng.uniform(-1.0, 1.0, size=(heads, sl, d))
+                za = np.stack([np.concatenate([self.Q[h][:, j] for h in range(heads)]) for j in range(d)])
+                zb = np.stack([np.concatenate([self.K[h][:, j] for h in range(heads)]) for j in range(d)])
+                self.cols = list(range(P, P + m))
+                self.terms = [[(j, j, i) for j in range(d)] for i in self.cols]
+                self.ref = np.stack([np.concatenate([(self.Q[h] @ self.K[h].T)[:, i] for h in range(heads)]) for i in self.cols])
+            else:
+                # weights times V: ciphertext j of A holds column j of the weights of all heads (d_in of them), B the
+                # d_out columns of V; output i sums over the d_in tokens j
+                d, m = w.d_in, w.d_out
+                self.Wt = rng.uniform(-1.0, 1.0, size=(heads, sl, d)) / 16
+                self.V = rng.uniform(-1.0, 1.0, size=(heads, sl, m))
+                za = np.stack([np.concatenate([self.Wt[h][:, j] for h in range(heads)]) for j in range(d)])
+                zb = np.stack([np.concatenate([self.V[h][:, i] for h in range(heads)]) for i in range(m)])
+                self.terms = [[(j, i, j) for j in range(d)] for i in range(m)]
+                self.ref = np.stack([np.concatenate([self.Wt[h] @ self.V[h][:d, i] for h in range(heads)]) for i in range(m)])
+            pt = self.ctx.encode(za, self.L)
+            self.ct_a = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            pt = self.ctx.encode(zb, self.L)
+            self.ct_in = self.ctx.encrypt(self.pk, pt)
+            pt.free()
+            slots = sorted({t[2] for tl in self.terms for t in tl})
+            steps = {x % P for x in slots} | {x // P * P for x in slots} | set(self.ctx.fill_steps(P, sl, -1)) | set(self.ctx.fill_steps(1, P, -1))
+            self.gk = self.ctx.galois_keygen(self.sk, sorted(x for x in steps if x), None, 13)
+            self.rk = self.ctx.relin_keygen(self.sk, None, 17)
+            self.pt = self.ctx.block_head_mask(sl, P, self.L)
+            self.pt2 = self.ctx.periodic_masks(P, 1, self.L - 1)
+            self.ct_out = self.ctx.ct_alloc(len(self.terms), self.L - 3)
+            return
         if w.op == "merge":
             # d_in block-placed outputs: one group of c_tot encrypted columns, repeated for every packed output
             import torch
@@ -176,6 +214,9 @@ class Runner:
         if w.op == "ccmm_blocks":
             self.ctx.ccmm_blocks(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, self.cols, self.pt, self.ct_out)
             return
+        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+            self.ctx.ccmm_bsgs(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.terms, self.pt, self.pt2, self.ct_out)
+            return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
@@ -215,6 +256,8 @@ class Runner:
             heads = self.n // w.tokens
             ref = np.stack([np.concatenate([(self.Q[h] @ self.K[h].T)[:, i] for h in range(heads)]) for i in self.cols])
             return float(np.abs(dec - ref).max())
+        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+            return float(np.abs(self.ctx.decrypt(self.sk, self.ct_out) - self.ref).max())
         ref = self.X @ self.W.astype(np.float64)
         out = self.ct_out
         if w.d_mid:
@@ -285,35 +328,25 @@ def roofline_for(w, prof):
     """Roofline entry of the dominant kernel class of the step (largest total time)."""
     N, L, K, alpha = w.N, w.q_count, w.p_count, w.alpha
     unit = 8.0 * N  # bytes of one limb
-    ext = L + K
-    beta = -(-L // alpha)
-    pm_terms = pm_out = 0
-    n_sw = None  # key switches brought back to the ciphertext basis (grouped rotations share one); default: every rotation
-    Lp = L  # level of the plaintext multiplication (the CCMM's key switches run one level below it)
+    # key-switch work as stages at one level each: (limbs, rotations, raises, switch-backs to the ciphertext basis --
+    # grouped rotations share one --, keys streamed); plaintext multiplications as (limbs, products, outputs)
+    ks, pm = [], []
     if w.name == "keyswitch":
-        n_rot, n_raise = w.batch, w.batch
-        n_key = n_rot  # every rotation streams its key
+        ks.append((L, w.batch, w.batch, w.batch, w.batch))  # every rotation streams its key
     elif w.op == "rope":
         n_ct = -(-w.d_in // w.c_tot)
-        n_rot, n_raise = 2 * n_ct, n_ct
-        n_key = 2 * -(-n_ct // 32)  # inputs are rotated 32 at a time, a key is read once per group
-        pm_terms, pm_out = 3 * n_ct, n_ct
+        ks.append((L, 2 * n_ct, n_ct, 2 * n_ct, 2 * -(-n_ct // 32)))  # inputs are rotated 32 at a time, a key is read once per group
+        pm.append((L, 3 * n_ct, n_ct))
     elif w.op == "merge":
-        n_rot = n_raise = n_key = 0
-        pm_terms, pm_out = w.d_in, -(-w.d_in // w.c_tot)
+        pm.append((L, w.d_in, -(-w.d_in // w.c_tot)))
     elif w.op == "ccmm_blocks":
         # per element: one aligning rotation (the raise shared by all columns of a ciphertext of B), one mask product and
         # log2(s) fill steps one level down; per output one relinearisation
         n_el = w.d_in * w.d_out
         f_rot, f_raise = fill_counts(1, w.tokens)
-        L = L - 1
-        ext = L + K
-        beta = -(-L // alpha)
-        n_rot = n_el * (1 + f_rot) + w.d_out
-        n_raise = w.d_in + n_el * f_raise + w.d_out
-        n_sw = n_el * (1 + f_raise) + w.d_out
-        n_key = -(-w.d_in // 16) * w.d_out + f_rot * -(-n_el // 64) + 1
-        pm_terms = pm_out = n_el
+        ks.append((L - 1, n_el * (1 + f_rot) + w.d_out, w.d_in + n_el * f_raise + w.d_out, n_el * (1 + f_raise) + w.d_out,
+                   -(-w.d_in // 16) * w.d_out + f_rot * -(-n_el // 64) + 1))
+        pm.append((L, n_el, n_el))
     elif w.op == "ccmm":
         # every element of B: one mask product and log2(period) rotate-and-add steps one level down (the log2(n/period)
         # steps per column at the top level and the relinearisations are few and counted with them)
@@ -321,45 +354,62 @@ def roofline_for(w, prof):
         period = 1 << (w.d_in - 1).bit_length()
         b_rot, b_raise = fill_counts(1, period)
         g_rot, g_raise = fill_counts(period, w.n_slots)
-        L = L - 1
-        ext = L + K
-        beta = -(-L // alpha)
-        n_rot = n_el * b_rot + w.d_out * g_rot + w.d_out
         n_raise = n_el * b_raise + w.d_out * g_raise + w.d_out
-        n_sw = n_raise
-        n_key = b_rot * -(-n_el // 64) + g_rot + 1
-        pm_terms = pm_out = n_el
+        ks.append((L - 1, n_el * b_rot + w.d_out * g_rot + w.d_out, n_raise, n_raise, b_rot * -(-n_el // 64) + g_rot + 1))
+        pm.append((L, n_el, n_el))
+    elif w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+        # giant steps per segment (aligning rotation at the top level, head mask, fill over the block one level down),
+        # baby steps per element (aligning rotation there, period-start mask, fill over the period two levels down),
+        # one relinearisation per output
+        P = w.period
+        if w.op == "ccmm_bsgs":
+            n_el, n_seg, n_src = w.d_in * w.d_out, w.d_in * -(-w.d_out // P), w.d_in
+        else:
+            n_el, n_seg, n_src = w.d_in * w.d_out, -(-w.d_in // P) * w.d_out, w.d_out
+        g_rot, g_raise = fill_counts(P, w.tokens)
+        b_rot, b_raise = fill_counts(1, P)
+        ks.append((L, n_seg, n_src, n_seg, -(-n_src // 16) * max(1, n_seg // max(n_src, 1))))
+        ks.append((L - 1, n_seg * g_rot + n_el, n_seg * (g_raise + 1), n_seg * g_raise + n_el, g_rot * -(-n_seg // 64) + (P - 1) * -(-n_seg // 16)))
+        ks.append((L - 2, n_el * b_rot + w.d_out, n_el * b_raise + w.d_out, n_el * b_raise + w.d_out, b_rot * -(-n_el // 64) + 1))
+        pm.append((L, n_seg, n_seg))
+        pm.append((L - 1, n_el, n_el))
     else:
         n_in = -(-w.d_in // w.c_tot)
-        n_rot, n_raise = w.d_in - n_in, n_in
         # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
-        n_key = -(-n_in // 16) * (min(w.c_tot, w.d_in) - 1)
-    if n_sw is None:
-        n_sw = n_rot
+        ks.append((L, w.d_in - n_in, n_in, w.d_in - n_in, -(-n_in // 16) * (min(w.c_tot, w.d_in) - 1)))
+
+    def ks_sum(f):
+        return sum(f(l, -(-l // alpha), l + K, n_rot, n_raise, n_sw, n_key) for l, n_rot, n_raise, n_sw, n_key in ks)
+
+    def pm_sum(f):
+        return sum(f(l, t, o) for l, t, o in pm)
+
     # HBM-bound classes: algorithmic limb-units per step (every operand read once, every result written once)
     hbm = {
         # fused path (N = 2^16, ciphertext primes below 2^50)
-        "ks_pre": n_raise * 2 * L,
-        "ks_modup_fcols": n_raise * (3 * L + beta * ext + L),        # y, c1, c0 in; raised digits and P*c0 out
-        "ks_frows": n_raise * 2 * (beta * ext + L),
-        "ks_inner_irows": n_rot * (beta * L + L) + n_sw * 2 * L + n_key * 2 * beta * L,   # ciphertext limbs: digits, P*c0, key in; accumulators out
-        "ks_inner_irows_wide": n_rot * beta * K + n_sw * 2 * K + n_key * 2 * beta * K,    # special limbs (integer arithmetic)
-        "ks_icols_special": n_sw * 4 * K,                                      # special limbs in, split residues out
-        "ks_icols_moddown": n_sw * (2 * L + 2 * K + 2 * L),                    # accumulators and residues in, ciphertext out
+        "ks_pre": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * 2 * l),
+        "ks_modup_fcols": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * (3 * l + b * e + l)),        # y, c1, c0 in; raised digits and P*c0 out
+        "ks_frows": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * 2 * (b * e + l)),
+        # ciphertext limbs: digits, P*c0, key in; accumulators out
+        "ks_inner_irows": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (b * l + l) + sw * 2 * l + key * 2 * b * l),
+        # special limbs (integer arithmetic)
+        "ks_inner_irows_wide": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * b * K + sw * 2 * K + key * 2 * b * K),
+        "ks_icols_special": ks_sum(lambda l, b, e, rot, ra, sw, key: sw * 4 * K),                    # special limbs in, split residues out
+        "ks_icols_moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: sw * (2 * l + 2 * K + 2 * l)),  # accumulators and residues in, ciphertext out
         # unfused path
-        "ntt": 2 * (n_raise * beta * ext + n_rot * 2 * ext),
-        "inner_product": n_rot * (3 * beta * ext + 2 * ext),
-        "modup": n_raise * (L + beta * ext),
-        "moddown": n_rot * (2 * ext + 3 * L),
+        "ntt": ks_sum(lambda l, b, e, rot, ra, sw, key: 2 * (ra * b * e + rot * 2 * e)),
+        "inner_product": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (3 * b * e + 2 * e)),
+        "modup": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * (l + b * e)),
+        "moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (2 * e + 3 * l)),
         "mul_scalar_rescale": (w.d_mid or 0) * (2 * L + 2 * (L - 1)),
         # plane split: 8 bytes read + planes bytes written per operand word (units of 8 bytes per word: /N below)
         "byte_planes": (w.d_in * 2 * L + (0 if "rescale_byte_planes" in prof else (w.d_mid or 0) * 2 * (L - 1))) * (8 + 7) / 8.0,
         "rescale_byte_planes": (w.d_mid or 0) * (2 * L + 2 * (L - 1) * 7 / 8.0),
         # plaintext multiplication, summed and rescaled (the few plaintext limbs are not counted)
-        "pm_fcols": pm_terms * 4 * Lp,                      # source limbs in, column-transformed limbs out
-        "pm_frows_mac_irows": (pm_terms + pm_out) * 2 * Lp,  # those in, one sum per output limb out
-        "pm_icols_last": pm_out * 4,
-        "pm_icols_rescale": pm_out * (2 * (Lp - 1) + 2 + 2 * (Lp - 1)),
+        "pm_fcols": pm_sum(lambda l, t, o: t * 4 * l),                      # source limbs in, column-transformed limbs out
+        "pm_frows_mac_irows": pm_sum(lambda l, t, o: (t + o) * 2 * l),      # those in, one sum per output limb out
+        "pm_icols_last": pm_sum(lambda l, t, o: o * 4),
+        "pm_icols_rescale": pm_sum(lambda l, t, o: o * (2 * (l - 1) + 2 + 2 * (l - 1))),
     }
     members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
     classes = list(hbm) + ["accumulate", "accumulate_mfma"]
@@ -446,21 +496,25 @@ def cpu_baseline(w, budget_s=12.0):
         _, t_one, n1 = repeat(lambda: o.rope(ct, pts, gk, gk_m), budget_s)
         return {"value": n_ct * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
                 "sample": "%d ciphertexts through Alg. 2 (%.3f s each), extrapolated linearly to %d" % (n1, t_one, n_ct)}
-    if w.op in ("ccmm", "ccmm_blocks"):
-        n_el = w.d_in * w.d_out
+    if w.op in ("ccmm", "ccmm_blocks", "ccmm_bsgs", "ccmm_bsgs_av"):
+        n_el = n_pm = w.d_in * w.d_out
         if w.op == "ccmm":
             period = 1 << (w.d_in - 1).bit_length()
             n_rot = n_el * fill_counts(1, period)[0] + w.d_out * fill_counts(period, w.n_slots)[0]
-        else:
+        elif w.op == "ccmm_blocks":
             n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
+        else:
+            n_seg = w.d_in * -(-w.d_out // w.period) if w.op == "ccmm_bsgs" else -(-w.d_in // w.period) * w.d_out
+            n_rot = n_seg * (1 + fill_counts(w.period, w.tokens)[0]) + n_el * (1 + fill_counts(1, w.period)[0])
+            n_pm = n_el + n_seg
         _, t_rot, n1 = repeat(lambda: o.rotate(ct, gk), budget_s * 0.5)
-        mask_rns = o.i64_to_rns(o.periodic_masks(1 << lp, 1, pr.L)[0], pr.q)
+        mask_rns = o.i64_to_rns(o.periodic_masks(16, 1, pr.L)[0], pr.q)
         _, t_pm, n2 = repeat(lambda: o.pmult(ct, mask_rns, float(pr.q[-1])), budget_s * 0.2)
         _, t_ts, n3 = repeat(lambda: o.tensor_sum([(ct, ct)]), budget_s * 0.3)
-        return {"value": (n_rot * t_rot + n_el * (t_pm + t_ts)) * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
-                "sample": "%d rotations (%.3f s each), %d plaintext products (%.3f s), %d tensor products (%.3f s), extrapolated linearly to "
-                          "%d rotations and %d of each product (additions, relinearisations and rescales left out)"
-                          % (n1, t_rot, n2, t_pm, n3, t_ts, n_rot, n_el)}
+        return {"value": (n_rot * t_rot + n_pm * t_pm + n_el * t_ts) * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
+                "sample": "%d rotations (%.3f s each), %d plaintext products (%.3f s), %d tensor products (%.3f s) at the top level, "
+                          "extrapolated linearly to %d rotations, %d plaintext and %d tensor products (additions, relinearisations "
+                          "and rescales left out)" % (n1, t_rot, n2, t_pm, n3, t_ts, n_rot, n_pm, n_el)}
     if w.op == "merge":
         masks = o.block_masks(w.tokens, 2, pr.L)
         mask_rns = o.i64_to_rns(masks[0], pr.q)

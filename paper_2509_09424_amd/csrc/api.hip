@@ -1637,33 +1637,57 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ciphertext multiplication: no limb left to drop");
     if (out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the operands (%d vs %d limbs)", out->limbs, l1);
     if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_out);
-    const size_t term_words = (size_t)4 * l1 * N;
-    const int max_terms = (int)std::min<size_t>(65535, std::max<size_t>(1, ((size_t)1 << 30) / term_words));
     for (int o = 0; o < n_out; o++)
         if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
+    // groups of outputs: at most 8 GiB of transformed operands (a group's distinct operand ciphertexts, by address:
+    // one that enters several products is gathered and transformed once), at most 65535 products, at least one output
+    const size_t max_ops = std::max<size_t>(2, ((size_t)1 << 30) / ((size_t)2 * l1 * N));
     const int max_out = ctx->ks16 ? rot_chunk() : 64;
     std::vector<int> cut(1, 0);
+    std::vector<MmOperand> ops;
+    std::vector<MmPair> pairs(terms.size());
+    std::vector<size_t> op_base(1, 0);
     size_t need_a = 1, need_o = 0;
     for (int o0 = 0; o0 < n_out;) {
-        int o1 = o0 + 1;
-        while (o1 < n_out && begin[o1 + 1] - begin[o0] <= max_terms && o1 - o0 < max_out) o1++;
+        std::map<std::pair<const u64 *, int>, int> id;
+        int o1 = o0;
+        for (; o1 < n_out && o1 - o0 < max_out && begin[o1 + 1] - begin[o0] <= 65535; o1++) {
+            if (o1 > o0) {  // would this output's new operands still fit?
+                std::map<std::pair<const u64 *, int>, int> fresh;
+                for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
+                    const auto ka = std::make_pair(terms[t].a, limb_stride_a), kb = std::make_pair(terms[t].b, limb_stride_b);
+                    if (!id.count(ka)) fresh.emplace(ka, 0);
+                    if (!id.count(kb)) fresh.emplace(kb, 0);
+                }
+                if (id.size() + fresh.size() > max_ops) break;
+            }
+            for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
+                auto ia = id.emplace(std::make_pair(terms[t].a, limb_stride_a), (int)id.size());
+                if (ia.second) ops.push_back({terms[t].a, limb_stride_a, 0});
+                auto ib = id.emplace(std::make_pair(terms[t].b, limb_stride_b), (int)id.size());
+                if (ib.second) ops.push_back({terms[t].b, limb_stride_b, 0});
+                pairs[t] = {ia.first->second, ib.first->second};
+            }
+        }
         cut.push_back(o1);
-        need_a = std::max(need_a, (size_t)(begin[o1] - begin[o0]));
+        op_base.push_back(ops.size());
+        need_a = std::max(need_a, id.size());
         need_o = std::max(need_o, (size_t)(o1 - o0));
         o0 = o1;
     }
     int rc;
     const size_t rw = raised_words(ctx, l1);
-    if ((rc = grow(ctx, &ctx->ws_ma, &ctx->ws_ma_words, need_a * term_words))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_ma, &ctx->ws_ma_words, need_a * 2 * l1 * N))) return rc;
     if ((rc = grow(ctx, &ctx->ws_md, &ctx->ws_md_words, need_o * 3 * l1 * N))) return rc;
     if ((rc = grow(ctx, &ctx->ws_me, &ctx->ws_me_words, need_o * 2 * l1 * N))) return rc;
     if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, need_o * rw))) return rc;
     if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, need_o * 2 * ext * N))) return rc;
     if ((rc = ensure_desc(ctx, need_o))) return rc;
-    const size_t tw = terms.size() * (sizeof(MmTerm) / 8), bw = (begin.size() + 1) / 2;
-    if ((rc = grow(ctx, &ctx->ws_mt, &ctx->ws_mt_words, tw + bw + 2))) return rc;
-    if (!terms.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt, terms.data(), terms.size() * sizeof(MmTerm), hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + tw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
+    const size_t ow = ops.size() * (sizeof(MmOperand) / 8), pw = pairs.size() * (sizeof(MmPair) / 8), bw = (begin.size() + 1) / 2;
+    if ((rc = grow(ctx, &ctx->ws_mt, &ctx->ws_mt_words, ow + pw + bw + 2))) return rc;
+    if (!ops.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt, ops.data(), ops.size() * sizeof(MmOperand), hipMemcpyHostToDevice, st));
+    if (!pairs.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + ow, pairs.data(), pairs.size() * sizeof(MmPair), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + ow + pw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
     const u64 *d_consts;
     const double *d_fconsts;
     bool fp;
@@ -1671,14 +1695,14 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     for (size_t k = 0; k + 1 < cut.size(); k++) {
         const int o0 = cut[k], o1 = cut[k + 1], cnt = o1 - o0;
         MmGroup g;
-        g.terms = (const MmTerm *)ctx->ws_mt;
-        g.begin = (const int32_t *)(ctx->ws_mt + tw) + o0;
+        g.ops = (const MmOperand *)ctx->ws_mt + op_base[k];
+        g.pairs = (const MmPair *)(ctx->ws_mt + ow) + begin[o0];
+        g.begin = (const int32_t *)(ctx->ws_mt + ow + pw) + o0;
         g.t_base = begin[o0];
         g.n_terms = begin[o1] - begin[o0];
+        g.n_ops = (int)(op_base[k + 1] - op_base[k]);
         g.n_out = cnt;
         g.l1 = l1;
-        g.limb_stride_a = limb_stride_a;
-        g.limb_stride_b = limb_stride_b;
         g.ws_a = ctx->ws_ma;
         g.ws_d = ctx->ws_md;
         g.ws_e = ctx->ws_me;
@@ -2199,13 +2223,21 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
     const size_t seg_ct = (size_t)2 * l2 * N, rep_ct = (size_t)2 * l3 * N;
 
     // groups of outputs whose distinct elements fit the workspace (an output is never split: its products are
-    // relinearised together)
-    const size_t cap = 512;
+    // relinearised together); the segments are formed once for the whole call when there are at most 1024 of them,
+    // else once per group
+    const size_t cap = 512, cap_seg = 1024;
     struct Chunk {
         int o0, o1;
         std::vector<std::pair<int, int>> segs, els;  // (b, g) and (b, slot), in order of first use
         std::vector<int> el_seg, term_el;            // segment of each element; element of each term from begin[o0] on
     };
+    std::vector<std::pair<int, int>> all_segs;
+    std::map<std::pair<int, int>, int> all_seg_id;
+    for (int t = 0; t < T; t++) {
+        const std::pair<int, int> g(term_b[t], term_slot[t] / period);
+        if (all_seg_id.emplace(g, (int)all_segs.size()).second) all_segs.push_back(g);
+    }
+    const bool shared = all_segs.size() <= cap_seg;
     std::vector<Chunk> chunks;
     for (int o0 = 0; o0 < n_out;) {
         Chunk c;
@@ -2224,14 +2256,20 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
                 const std::pair<int, int> e(term_b[t], term_slot[t]), g(term_b[t], term_slot[t] / period);
                 auto ie = el_id.find(e);
                 if (ie == el_id.end()) {
-                    auto ig = seg_id.find(g);
-                    if (ig == seg_id.end()) {
-                        ig = seg_id.emplace(g, (int)c.segs.size()).first;
-                        c.segs.push_back(g);
+                    int sid;
+                    if (shared) {
+                        sid = all_seg_id[g];
+                    } else {
+                        auto ig = seg_id.find(g);
+                        if (ig == seg_id.end()) {
+                            ig = seg_id.emplace(g, (int)c.segs.size()).first;
+                            c.segs.push_back(g);
+                        }
+                        sid = ig->second;
                     }
                     ie = el_id.emplace(e, (int)c.els.size()).first;
                     c.els.push_back(e);
-                    c.el_seg.push_back(ig->second);
+                    c.el_seg.push_back(sid);
                 }
                 c.term_el.push_back(ie->second);
             }
@@ -2240,7 +2278,7 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
         o0 = o;
         chunks.push_back(std::move(c));
     }
-    size_t max_seg = 1, max_el = 1;
+    size_t max_seg = shared ? std::max<size_t>(1, all_segs.size()) : 1, max_el = 1;
     for (const Chunk &c : chunks) {
         max_seg = std::max(max_seg, c.segs.size());
         max_el = std::max(max_el, c.els.size());
@@ -2248,41 +2286,50 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
     if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max(max_seg * 2 * l1 * N, max_el * seg_ct)))) return rc;
     if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, max_seg * seg_ct + max_el * rep_ct))) return rc;
 
-    for (const Chunk &c : chunks) {
-        const int S = (int)c.segs.size(), E = (int)c.els.size();
-        ensi_ct view;
-        view.ctx = ctx;
-        view.owns = false;
-        // giant steps: segment g of every block to the block's start, kept by the head mask, repeated through the block
+    ensi_ct view;
+    view.ctx = ctx;
+    view.owns = false;
+    ensi_ct seg = view;
+    seg.limbs = seg.limbs_alloc = l2;
+    seg.d = ctx->ws_rep;
+    seg.scale = B->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
+    // giant steps: segment g of every block to the block's start, kept by the head mask, repeated through the block
+    auto spread = [&](const std::vector<std::pair<int, int>> &segs) -> int {
+        const int S = (int)segs.size();
+        seg.n = S;
+        if (!S) return ENSI_OK;
+        int r;
         std::vector<RotJob> jobs(S);
-        for (int k = 0; k < S; k++) jobs[k] = {c.segs[k].first, c.segs[k].second * period, ctx->ws_rot + (size_t)k * 2 * l1 * N};
-        if (S && (rc = rotate_jobs(ctx, gk, B->d, b_ct, B->limbs_alloc, B->n, l1, jobs, st))) return rc;
-        ensi_ct al = view, seg = view, rep = view;
+        for (int k = 0; k < S; k++) jobs[k] = {segs[k].first, segs[k].second * period, ctx->ws_rot + (size_t)k * 2 * l1 * N};
+        if ((r = rotate_jobs(ctx, gk, B->d, b_ct, B->limbs_alloc, B->n, l1, jobs, st))) return r;
+        ensi_ct al = view;
         al.n = S;
         al.limbs = al.limbs_alloc = l1;
         al.scale = B->scale;
         al.d = ctx->ws_rot;
-        seg.n = S;
-        seg.limbs = seg.limbs_alloc = l2;
-        seg.d = ctx->ws_rep;
-        seg.scale = B->scale;
-        if (S) {
-            std::vector<int32_t> src(S), mi(S, 0);
-            for (int k = 0; k < S; k++) src[k] = k;
-            if ((rc = mask_rescale(ctx, &al, src, mask_head, mi, &seg, st))) return rc;
-            if ((rc = doubling_steps(ctx, gk, &seg, period, s, st, -1))) return rc;
-        }
+        std::vector<int32_t> src(S), mi(S, 0);
+        for (int k = 0; k < S; k++) src[k] = k;
+        if ((r = mask_rescale(ctx, &al, src, mask_head, mi, &seg, st))) return r;
+        return doubling_steps(ctx, gk, &seg, period, s, st, -1);
+    };
+    if (shared && (rc = spread(all_segs))) return rc;
+
+    for (const Chunk &c : chunks) {
+        const int E = (int)c.els.size();
+        if (!shared && (rc = spread(c.segs))) return rc;
         // baby steps: element b of every period to the period's start, kept by the period-start mask, copied through the period
-        jobs.assign(E, RotJob());
+        ensi_ct al = view, rep = view;
+        std::vector<RotJob> jobs(E);
         for (int k = 0; k < E; k++) jobs[k] = {c.el_seg[k], c.els[k].second % period, ctx->ws_rot + (size_t)k * seg_ct};
-        if (E && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, S, l2, jobs, st))) return rc;
+        if (E && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, seg.n, l2, jobs, st))) return rc;
         al.n = E;
         al.limbs = al.limbs_alloc = l2;
         al.scale = seg.scale;
+        al.d = ctx->ws_rot;
         rep.n = E;
         rep.limbs = rep.limbs_alloc = l3;
         rep.d = ctx->ws_rep + max_seg * seg_ct;
-        rep.scale = seg.scale;
+        rep.scale = seg.scale * mask_start->scale / (double)ctx->primes[l2 - 1];
         if (E) {
             std::vector<int32_t> src(E), mi(E, 0);
             for (int k = 0; k < E; k++) src[k] = k;

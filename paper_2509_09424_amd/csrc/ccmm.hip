@@ -7,7 +7,8 @@
 // product / ModDown kernels as a rotation, with the identity automorphism, fed (d0, d2) as if it were a
 // ciphertext so that d0 is added on the way), d1 is added and the result rescaled.
 //
-// Kernels here: the gather of the four operand polynomials of every product, the multiply-add that forms
+// Kernels here: the gather of the two polynomials of every distinct operand of a group (an operand that enters
+// several products is transformed once), the multiply-add that forms
 // (d0, d2, d1) per output, the addition of d1 and a strided ciphertext addition (used by the rotate-and-add
 // steps of the element replication).  Transforms, key switch, rescale and the final strided copy are the
 // library's existing kernels.
@@ -15,14 +16,14 @@
 
 #define MM_THREADS 256
 
-// grid (ceil(N/256), 4*l1, n_terms): ws_a[t][p*l1+i][N], p = 0..3 for a0, a1, b0, b1
-__global__ __launch_bounds__(MM_THREADS) void k_mm_gather(MmGroup g, int N) {
-    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+// grid (ceil(N/256) * n_ops, 2*l1): ws_a[u][p*l1+i][N] <- polynomial p, limb i of distinct operand u
+__global__ __launch_bounds__(MM_THREADS) void k_mm_gather(MmGroup g, int N, int nb) {
+    const int u = blockIdx.x / nb;
+    const int idx = (blockIdx.x - u * nb) * MM_THREADS + threadIdx.x;
     if (idx >= N) return;
-    const int y = blockIdx.y, p = y / g.l1, i = y - p * g.l1, t = blockIdx.z;
-    const MmTerm tm = g.terms[g.t_base + t];
-    const u64 *src = (p < 2 ? tm.a + ((size_t)p * g.limb_stride_a + i) * N : tm.b + ((size_t)(p - 2) * g.limb_stride_b + i) * N);
-    g.ws_a[((size_t)t * 4 * g.l1 + y) * N + idx] = src[idx];
+    const int y = blockIdx.y, p = y / g.l1, i = y - p * g.l1;
+    const MmOperand op = g.ops[u];
+    g.ws_a[((size_t)u * 2 * g.l1 + y) * N + idx] = op.p[((size_t)p * op.limb_stride + i) * N + idx];
 }
 
 // grid (ceil(N/256), l1, n_out): ws_d[o][0|1|2][i][N] <- d0, d2, d1 (transform domain).  Operands are ordinary
@@ -37,8 +38,10 @@ __global__ __launch_bounds__(MM_THREADS) void k_mm_tensor_mac(MmGroup g, int N, 
     u64 d0 = 0, d1 = 0, d2 = 0;
     const size_t poly = (size_t)g.l1 * N;
     for (int t = t0; t < t1; t++) {
-        const u64 *x = g.ws_a + ((size_t)(t - g.t_base) * 4 * g.l1 + i) * N + idx;
-        const u64 a0 = x[0], a1 = x[poly], b0 = x[2 * poly], b1 = x[3 * poly];
+        const MmPair pr = g.pairs[t - g.t_base];
+        const u64 *xa = g.ws_a + ((size_t)pr.a * 2 * g.l1 + i) * N + idx;
+        const u64 *xb = g.ws_a + ((size_t)pr.b * 2 * g.l1 + i) * N + idx;
+        const u64 a0 = xa[0], a1 = xa[poly], b0 = xb[0], b1 = xb[poly];
         d0 = add_mod(d0, mont_mul(a0, b0, q, qn), q);
         d1 = add_mod(d1, add_mod(mont_mul(a0, b1, q, qn), mont_mul(a1, b0, q, qn), q), q);
         d2 = add_mod(d2, mont_mul(a1, b1, q, qn), q);
@@ -88,12 +91,12 @@ static LimbMap mm_map(int l1) {
 void launch_mm_tensor(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
     const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
     const LimbMap map = mm_map(g.l1);
-    if (g.n_terms > 0) {
+    if (g.n_ops > 0) {
         {
             ScopedTimer t(ctx, "mm_gather", st);
-            hipLaunchKernelGGL(k_mm_gather, dim3(nb, 4 * g.l1, g.n_terms), dim3(MM_THREADS), 0, st, g, N);
+            hipLaunchKernelGGL(k_mm_gather, dim3((unsigned)nb * g.n_ops, 2 * g.l1), dim3(MM_THREADS), 0, st, g, N, nb);
         }
-        launch_ntt(ctx, g.ws_a, g.n_terms * 4 * g.l1, map, false, st);
+        launch_ntt(ctx, g.ws_a, g.n_ops * 2 * g.l1, map, false, st);
     }
     {
         ScopedTimer t(ctx, "mm_tensor_mac", st);

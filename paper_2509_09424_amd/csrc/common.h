@@ -89,17 +89,27 @@ struct PmGroup {
     int limb_stride_out;
 };
 
-// One ciphertext-ciphertext product: the two operand ciphertexts ([2][limb_stride][N] words each).
+// One ciphertext-ciphertext product as the host describes it: the two operand ciphertexts.
 struct MmTerm {
     const u64 *a, *b;
 };
+// On the device a group of outputs names every distinct operand ciphertext once ([2][limb_stride][N] words each), so
+// that an operand shared by several products is gathered and transformed once, and its products as index pairs.
+struct MmOperand {
+    const u64 *p;
+    int32_t limb_stride, pad;
+};
+struct MmPair {
+    int32_t a, b;
+};
 // One group of outputs of out_o = Rescale(Relin(sum_t a_t (x) b_t)); same conventions as PmGroup.
 struct MmGroup {
-    const MmTerm *terms;
+    const MmOperand *ops;  // [n_ops]
+    const MmPair *pairs;   // [n_terms], term t of the batch at index t - t_base
     const int32_t *begin;
-    int t_base, n_terms, n_out;
-    int l1, limb_stride_a, limb_stride_b;
-    u64 *ws_a;   // [n_terms][4][l1][N] operand polynomials a0, a1, b0, b1 (transformed in place)
+    int t_base, n_terms, n_ops, n_out;
+    int l1;
+    u64 *ws_a;   // [n_ops][2][l1][N] operand polynomials (transformed in place)
     u64 *ws_d;   // [n_out][3][l1][N]   d0, d2, d1: (d0, d2) is laid out like a ciphertext for the key switch
     u64 *ws_e;   // [n_out][2][l1][N]   relinearised product
     u64 *out;

@@ -365,3 +365,31 @@ def test_ccmm_bsgs_at_the_benchmark_parameters():
     for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
         h.free()
     p.close()
+
+
+def test_ccmm_bsgs_more_segments_than_are_kept_for_a_call():
+    """Period 1 makes every slot its own segment: 40 ciphertexts of 32-slot blocks name 1280 segments, more than the
+    library keeps for a whole call, so each group of outputs forms its own; outputs of 430, 430 and 420 elements
+    give three groups."""
+    p = Pair(SMALL4)
+    l1, s, period, nb = 5, 32, 1, 40
+    heads = p.n // s
+    za = p.rng.uniform(-1, 1, (nb, p.n)) / 8
+    zb = p.rng.uniform(-1, 1, (nb, p.n))
+    o_a, g_a = p.encrypt_both(za, l1)
+    o_b, g_b = p.encrypt_both(zb, l1)
+    o_gks, g_gk = bsgs_keys(p, s, period, range(s))
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    pairs = [(b, sl) for b in range(nb) for sl in range(s)]
+    terms = [[(b, b, sl) for b, sl in pairs[0:430]], [(b, b, sl) for b, sl in pairs[430:860]], [(b, b, sl) for b, sl in pairs[860:1280]]]
+    out = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    want = p.o.ccmm_bsgs(o_a, o_b, s, period, terms, o_rk, o_gks)
+    assert np.array_equal(out.export(), stack_cts(want))
+    dec = p.ctx.decrypt(p.g_sk, out)
+    for o, tl in enumerate(terms):
+        ref = sum(za[b] * np.repeat(zb[b].reshape(heads, s)[:, sl], s) for b, _, sl in tl)
+        assert np.abs(dec[o] - ref).max() < 1e-3, o
+    for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
+        h.free()
+    p.close()

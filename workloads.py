@@ -37,7 +37,9 @@ class Workload:
     act: str = "uniform"  # "uniform" [-1,1] or "normal" N(0,1) clipped to [-4,4]
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
-    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs) "ccmm" or "ccmm_blocks"
+    op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs), "ccmm", "ccmm_blocks",
+    #                     "ccmm_bsgs" (Q K^T form) or "ccmm_bsgs_av" (weights times V form)
+    period: int = 0  # baby-step range of the block-wise element extraction in giant and baby steps
 
     @property
     def N(self):
@@ -83,6 +85,13 @@ WORKLOADS.append(Workload("paperffn", 9, 16, 50, 16, 60, 4, 4, 40, tokens=2048, 
 # column-encoded with the 16 heads of a column in the 16 blocks of one ciphertext (96 ciphertexts each); a step
 # computes d_out = 8 of the 2048 output columns for all heads at once.
 WORKLOADS.append(Workload("ccmmqk", 10, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=8, act="uniform", op="ccmm_blocks"))
+# The same product with the element extraction in giant and baby steps (period 16): a step computes the d_out = 16
+# output columns of one segment (columns 16..31), whose giant steps are shared.  Three levels instead of two.
+WORKLOADS.append(Workload("ccmmqkbsgs", 11, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_bsgs", period=16))
+# A slice of the paper's other attention product (Table III: (2048 x 2048) by (2048 x 96), 16 heads): the attention
+# weights column-encoded (column j = one ciphertext, 16 heads in its blocks), V column-encoded.  Output column i is
+# sum_j a_j (x) E(v_i, j) over the 2048 tokens j; a step forms d_out = 1 output over the first d_in = 512 of them.
+WORKLOADS.append(Workload("ccmmav", 12, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_bsgs_av", period=16))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
