@@ -398,7 +398,7 @@ def roofline_for(w, prof):
         "ks_icols_moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: sw * (2 * l + 2 * K + 2 * l)),  # accumulators and residues in, ciphertext out
         # unfused path
         "ntt": ks_sum(lambda l, b, e, rot, ra, sw, key: 2 * (ra * b * e + rot * 2 * e)),
-        "inner_product": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (3 * b * e + 2 * e)),
+        "inner_product": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (b * e + 2 * e) + key * 2 * b * e),  # digits in, accumulators out; keys
         "modup": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * (l + b * e)),
         "moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (2 * e + 3 * l)),
         "mul_scalar_rescale": (w.d_mid or 0) * (2 * L + 2 * (L - 1)),

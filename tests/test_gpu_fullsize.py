@@ -127,10 +127,11 @@ def test_ffn_rescale_and_down_projection_full_size(name):
         torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("name", ["attn2560", "paper1536"])
+@pytest.mark.parametrize("name", ["attn2560", "paper1536", "paper1536n14"])
 def test_projection_full_size(name):
     """Projection workloads at full size -- attention projection (128 tokens, 2560 x 2560, 10 packed inputs,
-    255 Galois keys) and the paper's QKV shape (2048 tokens, 1536 x 1536, 96 packed inputs, 15 keys), diagonal
+    255 Galois keys) and the paper's QKV shape (2048 tokens, 1536 x 1536; 96 packed inputs and 15 keys at N = 2^16,
+    384 packed inputs and 3 keys at the paper's default ring N = 2^14, where the unfused kernels run), diagonal
     placement: unpack rotations against the oracle on sampled outputs, then the workload's own weights."""
     w = wl.BY_NAME[name]
     p = Pair(w.param_tuple())

@@ -92,6 +92,10 @@ WORKLOADS.append(Workload("ccmmqkbsgs", 11, 16, 50, 16, 60, 4, 4, 40, tokens=204
 # weights column-encoded (column j = one ciphertext, 16 heads in its blocks), V column-encoded.  Output column i is
 # sum_j a_j (x) E(v_i, j) over the 2048 tokens j; a step forms d_out = 1 output over the first d_in = 512 of them.
 WORKLOADS.append(Workload("ccmmav", 12, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_bsgs_av", period=16))
+# The paper's QKV projection shape at its default ring (N' = 2^14: 8192 slots, 4 columns of 2048 tokens per
+# ciphertext, 384 packed inputs, 3 rotation amounts) on a chain that fits that ring (6 x 50-bit + 2 x 60-bit primes).
+# The fused N = 2^16 kernels do not apply: transforms, ModUp, inner product and ModDown run as separate kernels.
+WORKLOADS.append(Workload("paper1536n14", 13, 14, 50, 6, 60, 2, 2, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
