@@ -290,7 +290,8 @@ int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const 
  * the head mask keeps its `period` slots (one product, one rescale), the fill with steps -period, -2 period, ... repeats
  * it through the block; baby step, per element: Rot(.; e) brings the element to the start of every period, the mask of
  * the slots congruent to 0 modulo the period keeps it (one product, one rescale), the fill with steps -1, -2, ... copies it
- * through the period.  Elements and segments named by several terms of a call are formed once.
+ * through the period.  An element named by several terms of a group of outputs is formed once; the segments are formed
+ * once for the whole call when it names at most 1024 of them (about 2 (l - 1) N words each), else once per group.
  * gk must hold keys for the steps g period and e in use and for ensi_fill_steps(period, s, -1) and
  * ensi_fill_steps(1, period, -1).  mask_head: ensi_block_head_mask(s, period, limbs = l); mask_start:
  * ensi_periodic_masks(period, 1, limbs = l - 1).  A, B at l limbs (l >= 4); out: n_out ciphertexts at l - 3 limbs.
