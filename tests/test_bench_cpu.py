@@ -45,3 +45,19 @@ def test_plaintext_multiplication_counts():
     assert abs(roof["achieved"] - 3 * 96 * 4 * 16 * unit / 1e-3 / 1e9) < 1e-6
     _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 3)})
     assert abs(roof["achieved"] - 96 * 2 * 16 * unit / 1e-3 / 1e9) < 1e-6
+
+
+def test_giant_and_baby_step_counts():
+    w = wl.BY_NAME["ccmmqkbsgs"]  # 96 segments and 1536 elements at period 16, blocks of 2048; 16 + 4 limbs, alpha 4
+    assert bench.fill_counts(16, 2048) == (10, 4) and bench.fill_counts(1, 16) == (6, 2)
+    unit = 8.0 * w.N
+    _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
+    # raises: 96 inputs at 16 limbs; per segment 4 fill groups and one for its baby rotations at 15; per element 2 and per output 1 at 14
+    raises = 96 * 2 * 16 + 96 * (4 + 1) * 2 * 15 + (1536 * 2 + 16) * 2 * 14
+    assert abs(roof["achieved"] - raises * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})
+    assert abs(roof["achieved"] - (96 * 4 * 16 + 1536 * 4 * 15) * unit / 1e-3 / 1e9) < 1e-6
+    w = wl.BY_NAME["ccmmav"]  # one column of V: 32 segments, 512 elements
+    _, roof = bench.roofline_for(w, {"ks_icols_special": (1.0, 1)})
+    switches = 32 + (32 * 4 + 512) + (512 * 2 + 1)
+    assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6

@@ -284,6 +284,10 @@ def test_ccmm_bsgs_qk_form_small_ring(params, l1, s, period, d, cols):
         p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, [[(0, 0, s)]], mh, ms)  # slot outside the block
     with pytest.raises(p.binding.EnsiError, match="code -3"):
         p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, ms, ms)  # head mask one level short
+    _, g_few = p.galois_keys([1])
+    with pytest.raises(p.binding.EnsiError, match="code -2"):
+        p.ctx.ccmm_bsgs(g_rk, g_few, g_a, g_b, s, period, [[(0, 0, s - 1)]], mh, ms)  # no key for the giant step
+    g_few.free()
     for h in (g_a, g_b, mh, ms, lh, ls, out, out2, g_gk, g_rk):
         h.free()
     p.close()
