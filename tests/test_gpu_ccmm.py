@@ -397,3 +397,36 @@ def test_ccmm_bsgs_more_segments_than_are_kept_for_a_call():
     for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
         h.free()
     p.close()
+
+
+def test_ccmm_forms_share_one_context():
+    """The extraction forms, a batched rotation and a plain product run one after the other on one context at
+    N = 2^16 (they share its workspaces, which grow and are reused): every result equals the oracle's, and the first
+    call repeated at the end gives the same words again."""
+    p = Pair(KEYSWITCH)
+    l1, s, period, d, cols = 5, 2048, 16, 2, [35, 2047]
+    heads = p.n // s
+    Q = p.rng.uniform(-1, 1, (heads, s, d))
+    K = p.rng.uniform(-1, 1, (heads, s, d))
+    o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    o_b, g_b = p.encrypt_both(np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
+    steps = {sl % period for sl in cols} | {sl // period * period for sl in cols} | set(cols)
+    steps |= set(p.ctx.fill_steps(period, s, -1)) | set(p.ctx.fill_steps(1, period, -1)) | set(p.ctx.fill_steps(1, s, -1))
+    o_gks, g_gk = p.galois_keys(sorted(st for st in steps if st))
+    o_rk, g_rk = relin_keys(p)
+    mh, ms = bsgs_masks(p, s, period, l1)
+    m0 = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.block_start_mask(s, l1)[None, :], l1), float(p.pr.q[l1 - 1]))
+    terms = [[(j, j, i) for j in range(d)] for i in cols]
+    first = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms).export()
+    assert np.array_equal(first, stack_cts(p.o.ccmm_bsgs(o_a, o_b, s, period, terms, o_rk, o_gks)))
+    rot = p.ctx.rotate(g_gk, g_a, [cols[0], -1])
+    assert np.array_equal(rot.export(), stack_cts([p.o.rotate(o_a[0], o_gks[cols[0]]), p.o.rotate(o_a[1], o_gks[-1])]))
+    blocks = p.ctx.ccmm_blocks(g_rk, g_gk, g_a, g_b, s, cols, m0)
+    assert np.array_equal(blocks.export(), stack_cts(p.o.ccmm_blocks(o_a, o_b, s, cols, o_rk, o_gks)))
+    prod = p.ctx.mult_sum_relin_rescale(g_rk, g_a, g_b, [0, 2], [0, 1], [0, 1])
+    assert np.array_equal(prod.export(), stack_cts([p.o.mult_sum_relin_rescale([(o_a[0], o_b[0]), (o_a[1], o_b[1])], o_rk)]))
+    again = p.ctx.ccmm_bsgs(g_rk, g_gk, g_a, g_b, s, period, terms, mh, ms)
+    assert np.array_equal(again.export(), first)
+    for h in (g_a, g_b, mh, ms, m0, rot, blocks, prod, again, g_gk, g_rk):
+        h.free()
+    p.close()
