@@ -700,6 +700,72 @@ class Oracle:
             out.append(self.mult_sum_relin_rescale([(self.drop_limbs(a, l1 - 1), r) for a, r in zip(a_cts, reps)], rk))
         return out
 
+    # ------------- CCMM over heads, a whole segment of output columns at once (no baby-step fills)
+    def segment_masks(self, s, period, l1):
+        """Integer coefficients [3 period][N] of the masks that sort the diagonals of ccmm_segment into
+        columns, at scale q_l: for r < period, R_r (index r) = 1 in the slots of every block whose offset
+        is congruent to r modulo the period; R_r^- (index period + r) = R_r without the last period of
+        the block; T_r (index 2 period + r) = R_r in the last period only."""
+        ql = float(self.pr.q[l1 - 1])
+        out = []
+        for kind in range(3):
+            for r in range(period):
+                z = np.zeros(self.n)
+                for b0 in range(0, self.n, s):
+                    if kind != 2:
+                        z[b0 + r:b0 + s - (period if kind == 1 else 0):period] = 1.0
+                    else:
+                        z[b0 + s - period + r] = 1.0
+                out.append(self.encode_coeffs(z, ql))
+        return np.stack(out)
+
+    @staticmethod
+    def segment_mask_terms(period, c):
+        """Which diagonal feeds output column c of a segment through which mask: a list of
+        (e, primed, mask index into segment_masks).  Slot x of diagonal D_e holds column
+        (x + e) mod period, so column c takes the residue class r = (c - e) mod period of D_e; where
+        that class meets the last e slots of a block (r >= period - e) those slots come from D'_e."""
+        terms = []
+        for e in range(period):
+            r = (c - e) % period
+            if e and r >= period - e:
+                terms.append((e, False, period + r))
+                terms.append((e, True, 2 * period + r))
+            else:
+                terms.append((e, False, r))
+        return terms
+
+    def ccmm_segment(self, a_cts, b_cts, s, period, g, rk, gks):
+        """CCMM section, several heads per ciphertext, the `period` output columns g period ..
+        (g+1) period - 1 of C_h = A_h B_h at once (the Q K^T form: ciphertext j of B holds B_h[j, i] in
+        slot h s + i).  The replication of an element stops at the giant step: w_j = the segment of b_j
+        repeated through every block (spread_segment).  Then Rot(w_j; e) puts, in slot x, element
+        (x + e) mod period of the segment, so D_e = Rescale(Relin(sum_j a_j (x) Rot(w_j; e))) holds in
+        slot x the entry of output column (x + e) mod period: the period diagonals hold all entries of
+        the period columns.  A rotation by e reads past the block's end in its last e slots; there
+        D'_e, built with Rot(w_j; e - period), holds the same entries.  One more plaintext product
+        sorts them: column c = Rescale(sum_e mask (.) D_e [+ mask' (.) D'_e]) (segment_mask_terms).
+        Three levels (head mask, product, sorting masks); per segment 2 period - 1 rotations per
+        ciphertext of B (one ModUp) instead of `period` extractions with their own fills."""
+        l1 = b_cts[0].l1
+        mask_head = self.block_head_mask(s, period, l1)
+        w = [self.spread_segment(b, g, s, period, mask_head, gks) for b in b_cts]
+        a2 = [self.drop_limbs(a, l1 - 1) for a in a_cts]
+        diag, diag_p = [], [None]
+        for e in range(period):
+            rot = [self.rotate(wj, gks[e]) for wj in w] if e else w
+            diag.append(self.mult_sum_relin_rescale(list(zip(a2, rot)), rk))
+            if e:
+                rot = [self.rotate(wj, gks[e - period]) for wj in w]
+                diag_p.append(self.mult_sum_relin_rescale(list(zip(a2, rot)), rk))
+        masks = self.segment_masks(s, period, l1 - 2)
+        q = self.pr.q[:l1 - 2]
+        out = []
+        for c in range(period):
+            terms = [((diag_p if primed else diag)[e], self.i64_to_rns(masks[mi], q)) for e, primed, mi in self.segment_mask_terms(period, c)]
+            out.append(self.pmult_sum_rescale(terms, float(self.pr.q[l1 - 3])))
+        return out
+
     # ------------------------- CCMM over heads, element extraction in baby steps and giant steps
     def block_head_mask(self, s, period, l1):
         """Integer coefficients [N] of the mask with a 1 in the first `period` slots of every block of s slots, at scale q_l."""

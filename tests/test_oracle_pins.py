@@ -599,6 +599,46 @@ def test_giant_and_baby_step_extraction_over_heads():
         assert O[i].l1 == l1 - 3 and np.abs(o.decrypt(O[i], sk) - ref).max() < 1e-3, i
 
 
+def test_segment_of_columns_from_diagonals():
+    """The segment form of the block-wise CCMM: masks, the diagonal arrangement, and the columns against numpy."""
+    w = wl.WORKLOADS[1]
+    pr = small_params(w, 6)  # 32 slots: 2 heads of 16 tokens
+    o = Oracle(pr)
+    rng = np.random.default_rng(107)
+    sk, pk = _keys(o, rng)
+    l1, s, heads, d, period = 5, 16, 2, 3, 4
+    Q = rng.uniform(-1, 1, (heads, s, d))
+    K = rng.uniform(-1, 1, (heads, s, d))
+    a_cts = [_enc(o, rng, pk, np.concatenate([Q[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    b_cts = [_enc(o, rng, pk, np.concatenate([K[h][:, j] for h in range(heads)]), l1) for j in range(d)]
+    beta = pr.beta(pr.L)
+    steps = set(range(1, period)) | set(range(1 - period, 0)) | {g * period for g in range(1, s // period)}
+    steps |= {st for grp in Oracle.fill_steps(period, s, -1) for st in grp}
+    gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 109) for st in sorted(steps)}
+    rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 113)
+    # the sorting masks partition the slots: for every e the masks of the terms of all columns cover each slot once
+    masks = o.segment_masks(s, period, l1 - 2)
+    dec = np.stack([o.decode_coeffs(m.astype(np.float64), float(pr.q[l1 - 3])) for m in masks])
+    assert np.abs(dec - np.round(dec)).max() < 1e-9
+    dec = np.round(dec)
+    for r in range(period):
+        assert np.array_equal(dec[r], dec[period + r] + dec[2 * period + r]) and dec[2 * period + r].sum() == heads
+    assert np.array_equal(dec[:period].sum(axis=0), np.ones(o.n))
+    S = np.stack([Q[h] @ K[h].T for h in range(heads)])  # [head][token][column]
+    x = np.arange(s)
+    for c in range(period):
+        for e, primed, mi in Oracle.segment_mask_terms(period, c):
+            sel = dec[mi][:s] > 0
+            assert np.all((x[sel] + e) % period == c)               # the diagonal holds column c there
+            assert np.all(x[sel] + e >= s if primed else x[sel] + e < s)  # and the rotation it was built with stays inside the block
+    for g in (0, 2, 3):
+        C = o.ccmm_segment(a_cts, b_cts, s, period, g, rk, gks)
+        assert len(C) == period and all(c.l1 == l1 - 3 for c in C)
+        for c in range(period):
+            ref = np.concatenate([S[h][:, g * period + c] for h in range(heads)])
+            assert np.abs(o.decrypt(C[c], sk) - ref).max() < 1e-3, (g, c)
+
+
 # -------------------------------------------------------------------- PCMM
 def _read_toy():
     W, Y = [], {}
