@@ -302,6 +302,24 @@ int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const en
                    const int32_t *begin, const int32_t *term_a, const int32_t *term_b, const int32_t *term_slot, int32_t n_out,
                    const ensi_pt *mask_head, const ensi_pt *mask_start, ensi_ct *out, void *stream);
 
+/* A whole segment of output columns of the block-wise product at once (the Q K^T form of ensi_ccmm_blocks: ciphertext
+ * j of B holds B_h[j][i] in slot h s + i): out_c, c < period, holds in block h column g period + c of C_h = A_h B_h.
+ * The replication of an element stops at the giant step of ensi_ccmm_bsgs: w_j = segment g of b_j repeated through
+ * every block.  Rot(w_j; e) then holds, in slot x, element (x + e) mod period of the segment, so the diagonal
+ * D_e = Rescale(Relin(sum_j a_j (x) Rot(w_j; e))) holds in slot x the entry of output column (x + e) mod period; in
+ * the last e slots of a block, where that rotation reads the next block, D'_e built with Rot(w_j; e - period) holds
+ * the same entries.  One plaintext product sorts the 2 period - 1 diagonals into the period columns:
+ * out_c = Rescale(sum_e R (.) D_e [+ T (.) D'_e]) with the masks of ensi_segment_masks.  Per segment and ciphertext
+ * of B: one giant step, one ModUp and 2 period - 2 rotations, and no per-element fill.
+ * gk: keys for the steps g period, ensi_fill_steps(period, s, -1), 1 .. period - 1 and -(period - 1) .. -1.
+ * mask_head: ensi_block_head_mask(s, period, limbs = l); masks: ensi_segment_masks(s, period, limbs = l - 2), 3 period
+ * plaintexts: for r < period, index r = the slots of every block congruent to r modulo the period, index period + r
+ * = those without the block's last period, index 2 period + r = those of the last period only.
+ * A, B: d ciphertexts each at l limbs (l >= 4); out: period ciphertexts at l - 3 limbs. */
+int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **pt);
+int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s, int32_t period,
+                      int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

@@ -23,7 +23,7 @@ EXPORTED = [
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
-    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -341,6 +341,18 @@ class Context:
             ct_out = self.ct_alloc(len(terms), ct_b.limbs - 3)
         self._check(self.lib.ensi_ccmm_bsgs(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), _ptr(begin), _ptr(ta), _ptr(tb),
                                             _ptr(ts), len(terms), mask_head.h, mask_start.h, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def segment_masks(self, s, period, limbs):
+        pt = ctypes.c_void_p()
+        self._check(self.lib.ensi_segment_masks(self.h, int(s), int(period), int(limbs), ctypes.byref(pt)))
+        return _Handle(self, pt, "ensi_pt_free", n=3 * period)
+
+    def ccmm_segment(self, rk, gk, ct_a, ct_b, s, period, g, mask_head, masks, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(int(period), ct_b.limbs - 3)
+        self._check(self.lib.ensi_ccmm_segment(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), int(g), mask_head.h, masks.h,
+                                               ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

@@ -2192,6 +2192,32 @@ static int rotate_jobs(ensi_ctx *ctx, const ensi_gk *gk, const u64 *src, size_t 
     return ENSI_OK;
 }
 
+// Giant steps of the block-wise extraction: for every (ciphertext b of B, segment g) of `segs`, Rot(b; g period) brings
+// the segment to the start of every block, the head mask keeps its `period` slots (one product, one rescale) and the
+// fill with steps -period, -2 period, ... repeats it through the block.  seg: a view whose storage (segs.size()
+// ciphertexts at B.limbs - 1 limbs) the caller provides; ws_rot must hold segs.size() ciphertexts at B.limbs limbs.
+static int spread_segments(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *B, const std::vector<std::pair<int, int>> &segs, int s, int period,
+                           const ensi_pt *mask_head, ensi_ct *seg, hipStream_t st) {
+    const int S = (int)segs.size(), N = ctx->N, l1 = B->limbs;
+    seg->n = S;
+    if (!S) return ENSI_OK;
+    int r;
+    std::vector<RotJob> jobs(S);
+    for (int k = 0; k < S; k++) jobs[k] = {segs[k].first, segs[k].second * period, ctx->ws_rot + (size_t)k * 2 * l1 * N};
+    if ((r = rotate_jobs(ctx, gk, B->d, (size_t)2 * B->limbs_alloc * N, B->limbs_alloc, B->n, l1, jobs, st))) return r;
+    ensi_ct al;
+    al.ctx = ctx;
+    al.owns = false;
+    al.n = S;
+    al.limbs = al.limbs_alloc = l1;
+    al.scale = B->scale;
+    al.d = ctx->ws_rot;
+    std::vector<int32_t> src(S), mi(S, 0);
+    for (int k = 0; k < S; k++) src[k] = k;
+    if ((r = mask_rescale(ctx, &al, src, mask_head, mi, seg, st))) return r;
+    return doubling_steps(ctx, gk, seg, period, s, st, -1);
+}
+
 extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
                               int32_t period, const int32_t *begin, const int32_t *term_a, const int32_t *term_b, const int32_t *term_slot,
                               int32_t n_out, const ensi_pt *mask_head, const ensi_pt *mask_start, ensi_ct *out, void *stream) {
@@ -2219,7 +2245,7 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
     int rc;
     if ((rc = relin_key(ctx, rk, &key))) return rc;
     const int l2 = l1 - 1, l3 = l1 - 2;
-    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, b_ct = (size_t)2 * B->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, out_ct = (size_t)2 * out->limbs_alloc * N;
     const size_t seg_ct = (size_t)2 * l2 * N, rep_ct = (size_t)2 * l3 * N;
 
     // groups of outputs whose distinct elements fit the workspace (an output is never split: its products are
@@ -2293,25 +2319,7 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
     seg.limbs = seg.limbs_alloc = l2;
     seg.d = ctx->ws_rep;
     seg.scale = B->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
-    // giant steps: segment g of every block to the block's start, kept by the head mask, repeated through the block
-    auto spread = [&](const std::vector<std::pair<int, int>> &segs) -> int {
-        const int S = (int)segs.size();
-        seg.n = S;
-        if (!S) return ENSI_OK;
-        int r;
-        std::vector<RotJob> jobs(S);
-        for (int k = 0; k < S; k++) jobs[k] = {segs[k].first, segs[k].second * period, ctx->ws_rot + (size_t)k * 2 * l1 * N};
-        if ((r = rotate_jobs(ctx, gk, B->d, b_ct, B->limbs_alloc, B->n, l1, jobs, st))) return r;
-        ensi_ct al = view;
-        al.n = S;
-        al.limbs = al.limbs_alloc = l1;
-        al.scale = B->scale;
-        al.d = ctx->ws_rot;
-        std::vector<int32_t> src(S), mi(S, 0);
-        for (int k = 0; k < S; k++) src[k] = k;
-        if ((r = mask_rescale(ctx, &al, src, mask_head, mi, &seg, st))) return r;
-        return doubling_steps(ctx, gk, &seg, period, s, st, -1);
-    };
+    auto spread = [&](const std::vector<std::pair<int, int>> &segs) -> int { return spread_segments(ctx, gk, B, segs, s, period, mask_head, &seg, st); };
     if (shared && (rc = spread(all_segs))) return rc;
 
     for (const Chunk &c : chunks) {
@@ -2348,6 +2356,113 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
         if ((rc = mult_core(ctx, key, terms, bg, l3, A->limbs_alloc, l3, &part, st))) return rc;
         out->scale = A->scale * rep.scale / (double)ctx->primes[l3 - 1];
     }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ------------- CCMM, several heads per ciphertext: a whole segment of output columns from its diagonals
+extern "C" int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **out) {
+    if (!ctx || !out || s < 1 || (s & (s - 1)) || s > ctx->N / 2 || period < 1 || (period & (period - 1)) || period > s || limbs < 2 ||
+        limbs > ctx->L)
+        return ENSI_E_BADARG;
+    const int n = ctx->N / 2;
+    std::vector<double> z((size_t)3 * period * n, 0.0);
+    for (int kind = 0; kind < 3; kind++)
+        for (int r = 0; r < period; r++) {
+            double *m = z.data() + ((size_t)kind * period + r) * n;
+            for (int b0 = 0; b0 < n; b0 += s) {
+                if (kind == 2) m[b0 + s - period + r] = 1.0;
+                else
+                    for (int x = r; x < s - (kind == 1 ? period : 0); x += period) m[b0 + x] = 1.0;
+            }
+        }
+    return encode_window(ctx, z.data(), 3 * period, n, 0, 0, limbs, (double)ctx->primes[limbs - 1], out);
+}
+
+extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
+                                 int32_t period, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !gk || !A || !B || !mask_head || !masks || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, d = A->n, l1 = B->limbs, P = period;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
+    if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
+    if (g < 0 || g >= s / P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: segment %d outside a block of %d segments", g, s / P);
+    if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
+    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    if (l1 < 4 || out->limbs != l1 - 3) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be three levels below the operands");
+    if (out->n != P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, P);
+    if (mask_head->n < 1 || mask_head->limbs < l1 || masks->n < 3 * P || masks->limbs < l1 - 2)
+        ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the head mask needs %d limbs, the %d sorting masks %d", l1, 3 * P, l1 - 2);
+    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int l2 = l1 - 1, l3 = l1 - 2, n_diag = 2 * P - 1;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, seg_ct = (size_t)2 * l2 * N, dg_ct = (size_t)2 * l3 * N;
+    // diagonal k: k < P is D_k (operand rotated by k), k >= P is D'_{k-P+1} (rotated by k - P + 1 - P)
+    auto amount = [&](int k) { return k < P ? k : k - 2 * P + 1; };
+    const int per = std::max(1, 1536 / std::max(d, 1));  // diagonals whose rotated operands are held at once
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (size_t)std::min(per, n_diag) * d * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (size_t)d * seg_ct + (size_t)n_diag * dg_ct))) return rc;
+    ensi_ct seg;
+    seg.ctx = ctx;
+    seg.owns = false;
+    seg.limbs = seg.limbs_alloc = l2;
+    seg.d = ctx->ws_rep;
+    seg.scale = B->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
+    std::vector<std::pair<int, int>> segs(d);
+    for (int j = 0; j < d; j++) segs[j] = {j, g};
+    if ((rc = spread_segments(ctx, gk, B, segs, s, P, mask_head, &seg, st))) return rc;
+    // the diagonals: D = Rescale(Relin(sum_j a_j (x) Rot(w_j; amount))), one raise of the w_j per group of diagonals
+    ensi_ct diag = seg;
+    diag.n = n_diag;
+    diag.limbs = diag.limbs_alloc = l3;
+    diag.d = ctx->ws_rep + (size_t)d * seg_ct;
+    diag.scale = A->scale * seg.scale / (double)ctx->primes[l2 - 1];
+    for (int k0 = 0; k0 < n_diag; k0 += per) {
+        const int cnt = std::min(per, n_diag - k0);
+        std::vector<RotJob> jobs;
+        std::vector<MmTerm> terms((size_t)cnt * d);
+        std::vector<int32_t> begin(cnt + 1);
+        for (int k = 0; k < cnt; k++) {
+            begin[k] = k * d;
+            const int am = amount(k0 + k);
+            for (int j = 0; j < d; j++) {
+                const u64 *b = seg.d + (size_t)j * seg_ct;
+                if (am) {
+                    u64 *dst = ctx->ws_rot + ((size_t)k * d + j) * seg_ct;
+                    jobs.push_back({j, am, dst});
+                    b = dst;
+                }
+                terms[(size_t)k * d + j] = {A->d + (size_t)j * a_ct, b};
+            }
+        }
+        begin[cnt] = cnt * d;
+        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, d, l2, jobs, st))) return rc;
+        ensi_ct part = diag;
+        part.d = diag.d + (size_t)k0 * dg_ct;
+        part.n = cnt;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &part, st))) return rc;
+    }
+    // sorting: slot x of D_e holds column (x + e) mod P; column c takes the class r = (c - e) mod P of D_e, and from D'_e
+    // where that class meets the last e slots of a block
+    std::vector<PmTerm> pt;
+    std::vector<int32_t> pb(P + 1);
+    for (int c = 0; c < P; c++) {
+        pb[c] = (int32_t)pt.size();
+        for (int e = 0; e < P; e++) {
+            const int r = ((c - e) % P + P) % P;
+            if (e && r >= P - e) {
+                pt.push_back({diag.d + (size_t)e * dg_ct, P + r, 0});
+                pt.push_back({diag.d + (size_t)(P - 1 + e) * dg_ct, 2 * P + r, 0});
+            } else {
+                pt.push_back({diag.d + (size_t)e * dg_ct, r, 0});
+            }
+        }
+    }
+    pb[P] = (int32_t)pt.size();
+    if ((rc = pmult_core(ctx, pt, pb, l3, l3, masks, out, st))) return rc;
+    out->scale = diag.scale * masks->scale / (double)ctx->primes[l3 - 1];
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
 }
