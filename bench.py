@@ -118,11 +118,11 @@ class Runner:
             self.pt = self.ctx.block_start_mask(sl, self.L)
             self.ct_out = self.ctx.ct_alloc(m, self.L - 2)
             return
-        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av", "ccmm_segment"):
             # both attention products for every head at once, element extraction in giant and baby steps
             sl, P = w.tokens, w.period
             heads = self.n // sl
-            if w.op == "ccmm_bsgs":
+            if w.op in ("ccmm_bsgs", "ccmm_segment"):
                 # Q K^T: ciphertext j holds column j of all heads; a step forms the columns of segment 1
                 d, m = w.d_in, w.d_out
                 self.Q = rng.uniform(-1.0, 1.0, size=(heads, sl, d))
@@ -149,11 +149,18 @@ class Runner:
             self.ct_in = self.ctx.encrypt(self.pk, pt)
             pt.free()
             slots = sorted({t[2] for tl in self.terms for t in tl})
-            steps = {x % P for x in slots} | {x // P * P for x in slots} | set(self.ctx.fill_steps(P, sl, -1)) | set(self.ctx.fill_steps(1, P, -1))
+            steps = {x // P * P for x in slots} | set(self.ctx.fill_steps(P, sl, -1))
+            if w.op == "ccmm_segment":
+                # the whole segment 1 from its diagonals: rotations by 1 .. P-1 and -(P-1) .. -1 of the spread operands
+                assert m == P
+                steps |= set(range(1, P)) | set(range(1 - P, 0))
+                self.pt2 = self.ctx.segment_masks(sl, P, self.L - 2)
+            else:
+                steps |= {x % P for x in slots} | set(self.ctx.fill_steps(1, P, -1))
+                self.pt2 = self.ctx.periodic_masks(P, 1, self.L - 1)
             self.gk = self.ctx.galois_keygen(self.sk, sorted(x for x in steps if x), None, 13)
             self.rk = self.ctx.relin_keygen(self.sk, None, 17)
             self.pt = self.ctx.block_head_mask(sl, P, self.L)
-            self.pt2 = self.ctx.periodic_masks(P, 1, self.L - 1)
             self.ct_out = self.ctx.ct_alloc(len(self.terms), self.L - 3)
             return
         if w.op == "merge":
@@ -217,6 +224,9 @@ class Runner:
         if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
             self.ctx.ccmm_bsgs(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.terms, self.pt, self.pt2, self.ct_out)
             return
+        if w.op == "ccmm_segment":
+            self.ctx.ccmm_segment(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, 1, self.pt, self.pt2, self.ct_out)
+            return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
@@ -256,7 +266,7 @@ class Runner:
             heads = self.n // w.tokens
             ref = np.stack([np.concatenate([(self.Q[h] @ self.K[h].T)[:, i] for h in range(heads)]) for i in self.cols])
             return float(np.abs(dec - ref).max())
-        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
+        if w.op in ("ccmm_bsgs", "ccmm_bsgs_av", "ccmm_segment"):
             return float(np.abs(self.ctx.decrypt(self.sk, self.ct_out) - self.ref).max())
         ref = self.X @ self.W.astype(np.float64)
         out = self.ct_out
@@ -373,6 +383,18 @@ def roofline_for(w, prof):
         ks.append((L - 2, n_el * b_rot + w.d_out, n_el * b_raise + w.d_out, n_el * b_raise + w.d_out, b_rot * -(-n_el // 64) + 1))
         pm.append((L, n_seg, n_seg))
         pm.append((L - 1, n_el, n_el))
+    elif w.op == "ccmm_segment":
+        # per ciphertext of B: one giant step (aligning rotation at the top level, head mask, fill over the block one level
+        # down) and 2P-2 rotations of the spread operand on one raise; 2P-1 relinearisations two levels down; the sorting
+        # products of the 2P-1 diagonals into P columns
+        P, dd = w.period, w.d_in
+        g_rot, g_raise = fill_counts(P, w.tokens)
+        n_diag = 2 * P - 1
+        ks.append((L, dd, dd, dd, -(-dd // 16)))
+        ks.append((L - 1, dd * g_rot + dd * (n_diag - 1) + n_diag, dd * (g_raise + 1) + n_diag, dd * g_raise + dd * (n_diag - 1) + n_diag,
+                   g_rot * -(-dd // 64) + (n_diag - 1) * -(-dd // 16) + 1))
+        pm.append((L, dd, dd))
+        pm.append((L - 2, P * P + P * (P - 1) // 2, P))
     else:
         n_in = -(-w.d_in // w.c_tot)
         # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
@@ -496,13 +518,18 @@ def cpu_baseline(w, budget_s=12.0):
         _, t_one, n1 = repeat(lambda: o.rope(ct, pts, gk, gk_m), budget_s)
         return {"value": n_ct * t_one * 1e3, "unit": "ms/batch", "cores": cores, "kind": "oracle",
                 "sample": "%d ciphertexts through Alg. 2 (%.3f s each), extrapolated linearly to %d" % (n1, t_one, n_ct)}
-    if w.op in ("ccmm", "ccmm_blocks", "ccmm_bsgs", "ccmm_bsgs_av"):
+    if w.op in ("ccmm", "ccmm_blocks", "ccmm_bsgs", "ccmm_bsgs_av", "ccmm_segment"):
         n_el = n_pm = w.d_in * w.d_out
         if w.op == "ccmm":
             period = 1 << (w.d_in - 1).bit_length()
             n_rot = n_el * fill_counts(1, period)[0] + w.d_out * fill_counts(period, w.n_slots)[0]
         elif w.op == "ccmm_blocks":
             n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
+        elif w.op == "ccmm_segment":
+            n_diag = 2 * w.period - 1
+            n_rot = w.d_in * (1 + fill_counts(w.period, w.tokens)[0] + n_diag - 1)
+            n_el = w.d_in * n_diag
+            n_pm = w.d_in + w.period * w.period + w.period * (w.period - 1) // 2
         else:
             n_seg = w.d_in * -(-w.d_out // w.period) if w.op == "ccmm_bsgs" else -(-w.d_in // w.period) * w.d_out
             n_rot = n_seg * (1 + fill_counts(w.period, w.tokens)[0]) + n_el * (1 + fill_counts(1, w.period)[0])

@@ -92,11 +92,16 @@ void launch_mm_tensor(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
     const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
     const LimbMap map = mm_map(g.l1);
     if (g.n_ops > 0) {
-        {
-            ScopedTimer t(ctx, "mm_gather", st);
-            hipLaunchKernelGGL(k_mm_gather, dim3((unsigned)nb * g.n_ops, 2 * g.l1), dim3(MM_THREADS), 0, st, g, N, nb);
+        if (ctx->log_n == 16) {
+            // the forward column pass reads the operands where they lie
+            launch_ntt16_gather(ctx, g.ws_a, g.ops, g.n_ops, g.l1, st);
+        } else {
+            {
+                ScopedTimer t(ctx, "mm_gather", st);
+                hipLaunchKernelGGL(k_mm_gather, dim3((unsigned)nb * g.n_ops, 2 * g.l1), dim3(MM_THREADS), 0, st, g, N, nb);
+            }
+            launch_ntt(ctx, g.ws_a, g.n_ops * 2 * g.l1, map, false, st);
         }
-        launch_ntt(ctx, g.ws_a, g.n_ops * 2 * g.l1, map, false, st);
     }
     {
         ScopedTimer t(ctx, "mm_tensor_mac", st);

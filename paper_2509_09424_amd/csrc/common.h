@@ -260,6 +260,7 @@ struct ScopedTimer {
 // Transform n_inst limb rows in place; row r uses prime map.prime[r % map.n].
 void launch_ntt(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);
 void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st);  // N = 2^16 only
+void launch_ntt16_gather(ensi_ctx *ctx, u64 *data, const MmOperand *ops, int n_ops, int l1, hipStream_t st);  // N = 2^16 only
 
 // fused key switch for N = 2^16 (keyswitch16.hip)
 void launch_ks16_key_format(ensi_ctx *ctx, u64 *key, int beta_full, hipStream_t st);

@@ -29,15 +29,16 @@
 #define N16_LOG 16
 
 // ---- column pass: tile = 256 rows x 16 columns; thread (c = tid%16, j = tid/16)
+// gin: where the forward pass reads its tile (the same place as g for a transform in place)
 template <bool FWD, class A>
-__device__ __forceinline__ void cols_body(u64 *g, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds) {
+__device__ __forceinline__ void cols_body(u64 *g, const u64 *gin, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds) {
     A ar;
     ar.init(pc);
     const int tid = threadIdx.x, c = tid & 15, j = tid >> 4;
     typename A::T v[16];
     if (FWD) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) v[i] = ar.load(g[(size_t)(j + 16 * i) * 256 + c]);
+        for (int i = 0; i < 16; i++) v[i] = ar.load(gin[(size_t)(j + 16 * i) * 256 + c]);
         ct4(ar, v, tw, tws, 1u);
 #pragma unroll
         for (int i = 0; i < 16; i++) ((typename A::T *)lds)[(j + 16 * i) * 16 + c] = ar.mid(v[i]);
@@ -117,8 +118,26 @@ __global__ __launch_bounds__(N16_THREADS) void k_ntt16_cols(u64 *data, const u64
     const size_t N = (size_t)1 << N16_LOG;
     const u64 *tw = tw_all + (size_t)prime * 4 * N + (FWD ? 0 : 2 * N);
     u64 *g = data + (size_t)inst * N + (size_t)blockIdx.x * 16;
-    if (pc.pad[0]) cols_body<FWD, ArithFp>(g, tw, tw + N, pc, lds);
-    else cols_body<FWD, ArithInt>(g, tw, tw + N, pc, lds);
+    if (pc.pad[0]) cols_body<FWD, ArithFp>(g, g, tw, tw + N, pc, lds);
+    else cols_body<FWD, ArithInt>(g, g, tw, tw + N, pc, lds);
+}
+
+// Forward column pass that reads every limb from its operand ciphertext and writes the operand array of the
+// ciphertext products: row inst = (operand u, polynomial p, limb i) of data <- ops[u].p[p][i], column-transformed.
+// l1 limbs per polynomial, limb i under prime i.
+__global__ __launch_bounds__(N16_THREADS) void k_ntt16_cols_gather(u64 *data, const MmOperand *ops, int l1, const u64 *tw_all,
+                                                                    const PrimeConst *pcs) {
+    __shared__ u64 lds[4096];
+    const int inst = blockIdx.y;
+    const int u = inst / (2 * l1), y = inst - u * 2 * l1, p = y / l1, prime = y - p * l1;
+    const PrimeConst pc = pcs[prime];
+    const size_t N = (size_t)1 << N16_LOG;
+    const u64 *tw = tw_all + (size_t)prime * 4 * N;
+    const MmOperand op = ops[u];
+    const u64 *gin = op.p + ((size_t)p * op.limb_stride + prime) * N + (size_t)blockIdx.x * 16;
+    u64 *g = data + (size_t)inst * N + (size_t)blockIdx.x * 16;
+    if (pc.pad[0]) cols_body<true, ArithFp>(g, gin, tw, tw + N, pc, lds);
+    else cols_body<true, ArithInt>(g, gin, tw, tw + N, pc, lds);
 }
 
 template <bool FWD>
@@ -133,6 +152,28 @@ __global__ __launch_bounds__(N16_THREADS) void k_ntt16_rows(u64 *data, const u64
     u64 *g = data + (size_t)inst * N + (size_t)r0 * 256;
     if (pc.pad[0]) rows_body<FWD, ArithFp>(g, tw, tw + N, pc, lds, r0);
     else rows_body<FWD, ArithInt>(g, tw, tw + N, pc, lds, r0);
+}
+
+// Forward transform of n_ops operand ciphertexts (two polynomials of l1 limbs each, limb i under prime i) from where they
+// lie into data[n_ops][2][l1][N]: the column pass gathers, the row pass runs in place.  ops: device array.
+void launch_ntt16_gather(ensi_ctx *ctx, u64 *data, const MmOperand *ops, int n_ops, int l1, hipStream_t st) {
+    LimbMap map;
+    map.n = l1;
+    for (int e = 0; e < ENSI_MAX_EXT; e++) map.prime[e] = e < l1 ? e : 0;
+    const int per = 32768 / (2 * l1);  // operands per launch (grid y below 65536)
+    for (int done = 0; done < n_ops; done += per) {
+        const int cnt = std::min(per, n_ops - done);
+        u64 *d = data + (size_t)done * 2 * l1 * ctx->N;
+        dim3 grid(16, cnt * 2 * l1);
+        {
+            ScopedTimer t(ctx, "ntt_fwd_cols", st);
+            hipLaunchKernelGGL(k_ntt16_cols_gather, grid, dim3(N16_THREADS), 0, st, d, ops + done, l1, ctx->d_tw, ctx->d_pc);
+        }
+        {
+            ScopedTimer t(ctx, "ntt_fwd_rows", st);
+            hipLaunchKernelGGL(k_ntt16_rows<true>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+        }
+    }
 }
 
 void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool inverse, hipStream_t st) {

@@ -38,7 +38,7 @@ class Workload:
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
     op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs), "ccmm", "ccmm_blocks",
-    #                     "ccmm_bsgs" (Q K^T form) or "ccmm_bsgs_av" (weights times V form)
+    #                     "ccmm_bsgs" (Q K^T form), "ccmm_bsgs_av" (weights times V form) or "ccmm_segment"
     period: int = 0  # baby-step range of the block-wise element extraction in giant and baby steps
 
     @property
@@ -88,6 +88,8 @@ WORKLOADS.append(Workload("ccmmqk", 10, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # The same product with the element extraction in giant and baby steps (period 16): a step computes the d_out = 16
 # output columns of one segment (columns 16..31), whose giant steps are shared.  Three levels instead of two.
 WORKLOADS.append(Workload("ccmmqkbsgs", 11, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_bsgs", period=16))
+# The same 16 output columns as a whole segment from its diagonals (no per-element fills).
+WORKLOADS.append(Workload("ccmmqkseg", 14, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_segment", period=16))
 # A slice of the paper's other attention product (Table III: (2048 x 2048) by (2048 x 96), 16 heads): the attention
 # weights column-encoded (column j = one ciphertext, 16 heads in its blocks), V column-encoded.  Output column i is
 # sum_j a_j (x) E(v_i, j) over the 2048 tokens j; a step forms d_out = 1 output over the first d_in = 512 of them.
