@@ -766,6 +766,55 @@ class Oracle:
             out.append(self.pmult_sum_rescale(terms, float(self.pr.q[l1 - 3])))
         return out
 
+    def diagonalise_weights(self, a_cts, s, period):
+        """The left operand of ccmm_av in the arrangement its right operand's rotations need: a_cts
+        = the `period` columns g period + c of A (column-encoded, one block of s slots per head);
+        returns 2 period - 1 ciphertexts one level down.  Entry e < period: slot x holds column
+        (x + e) mod period where x + e stays inside the block, 0 in the block's last e slots; entry
+        period - 1 + e (e >= 1): the same column in those last e slots, 0 elsewhere.  Plaintext
+        products with the masks of segment_masks, summed and rescaled once."""
+        l1 = a_cts[0].l1
+        masks = self.segment_masks(s, period, l1)
+        q = self.pr.q[:l1]
+        ql = float(self.pr.q[l1 - 1])
+        lo, hi = [], []
+        for e in range(period):
+            tl, th = [], []
+            for c in range(period):
+                r = (c - e) % period
+                if e and r >= period - e:
+                    tl.append((a_cts[c], self.i64_to_rns(masks[period + r], q)))
+                    th.append((a_cts[c], self.i64_to_rns(masks[2 * period + r], q)))
+                else:
+                    tl.append((a_cts[c], self.i64_to_rns(masks[r], q)))
+            lo.append(self.pmult_sum_rescale(tl, ql))
+            if e:
+                hi.append(self.pmult_sum_rescale(th, ql))
+        return lo + hi
+
+    def ccmm_av(self, ad_segs, v_cts, s, period, g0, rk, gks):
+        """CCMM section, several heads per ciphertext, the weights-times-V form: out_i = sum_j a_j (x)
+        E(v_i, j) over the tokens j of the segments g0, g0 + 1, ... (ad_segs[k] = diagonalise_weights
+        of the columns of segment g0 + k), without replicating single elements: with w = the
+        segment of v_i repeated through every block (spread_segment), slot x of Rot(w; e) holds
+        V[g period + (x + e) mod period, i], which is what entry e of the diagonalised weights
+        multiplies in that slot; the last e slots of a block take Rot(w; e - period) and entry
+        period - 1 + e.  All products of an output are added, relinearised and rescaled once.  Two
+        levels (masks on both operands, the product)."""
+        l1 = v_cts[0].l1
+        mask_head = self.block_head_mask(s, period, l1)
+        out = []
+        for v in v_cts:
+            pairs = []
+            for k, ad in enumerate(ad_segs):
+                w = self.spread_segment(v, g0 + k, s, period, mask_head, gks)
+                for e in range(period):
+                    pairs.append((ad[e], self.rotate(w, gks[e]) if e else w))
+                for e in range(1, period):
+                    pairs.append((ad[period - 1 + e], self.rotate(w, gks[e - period])))
+            out.append(self.mult_sum_relin_rescale(pairs, rk))
+        return out
+
     # ------------------------- CCMM over heads, element extraction in baby steps and giant steps
     def block_head_mask(self, s, period, l1):
         """Integer coefficients [N] of the mask with a 1 in the first `period` slots of every block of s slots, at scale q_l."""
