@@ -320,6 +320,27 @@ int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, 
 int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s, int32_t period,
                       int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream);
 
+/* The other attention product, weights times V, without replicating single elements (CCMM section; A = the s x s
+ * weights of every head column-encoded, ciphertext j = column j with head h in block h; V column-encoded alike):
+ *   out_i = Rescale(Relin(sum over the tokens j of the given segments of a_j (x) E(v_i, j))).
+ * ensi_diagonalise_weights rearranges whole segments of A once, for all columns of V: A holds n_seg * period columns
+ * (segment k = columns k period .. (k+1) period - 1 of the range); out[k (2 period - 1) + e], e < period, holds in slot
+ * x the entry of column (x + e) mod period of segment k, except in the block's last e slots, which out[k (2 period - 1)
+ * + period - 1 + e] (e >= 1) holds, zero elsewhere: plaintext products with ensi_segment_masks(s, period, limbs = l),
+ * summed and rescaled once; out at l - 1 limbs.
+ * ensi_ccmm_av then takes, per column v_i and segment g0 + k, w = that segment of v_i repeated through every block
+ * (the giant step of ensi_ccmm_bsgs): slot x of Rot(w; e) holds V[(g0 + k) period + (x + e) mod period][i], the
+ * factor of diagonal e in that slot; the last e slots of a block pair Rot(w; e - period) with diagonal period - 1 + e.
+ * One ModUp of w serves its 2 period - 2 rotations; all products of an output are added, relinearised and rescaled
+ * once.  Two levels below V.  gk: keys for the steps (g0 + k) period, ensi_fill_steps(period, s, -1), 1 .. period - 1
+ * and -(period - 1) .. -1.  Ad: n_seg (2 period - 1) ciphertexts at l - 1 limbs; V: m ciphertexts at l limbs (l >= 3);
+ * mask_head: ensi_block_head_mask(s, period, limbs = l); out: m ciphertexts at l - 2 limbs.  An output holds its
+ * n_seg (2 period - 1) operand pairs at once (about 4 (l - 1) N words each); callers with many segments split the range
+ * and add the partial outputs. */
+int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, ensi_ct *out, void *stream);
+int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
+                 int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream);
+
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host
  * int32[n_limbs]; 0..L-1 = q, L..L+K-1 = p).  In place.  Forward output order

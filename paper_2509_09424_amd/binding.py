@@ -23,7 +23,7 @@ EXPORTED = [
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
-    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -353,6 +353,19 @@ class Context:
             ct_out = self.ct_alloc(int(period), ct_b.limbs - 3)
         self._check(self.lib.ensi_ccmm_segment(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), int(g), mask_head.h, masks.h,
                                                ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def diagonalise_weights(self, ct_a, s, period, masks, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(ct_a.n // int(period) * (2 * int(period) - 1), ct_a.limbs - 1)
+        self._check(self.lib.ensi_diagonalise_weights(self.h, ct_a.h, int(s), int(period), masks.h, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def ccmm_av(self, rk, gk, ct_ad, ct_v, s, period, g0, mask_head, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(ct_v.n, ct_v.limbs - 2)
+        self._check(self.lib.ensi_ccmm_av(self.h, rk.h, gk.h, ct_ad.h, ct_v.h, int(s), int(period), int(g0), mask_head.h, ct_out.h,
+                                          ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

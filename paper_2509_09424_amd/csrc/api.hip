@@ -2467,6 +2467,118 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
     return ENSI_OK;
 }
 
+// ------------- CCMM, several heads per ciphertext: weights times V from diagonalised weights
+extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, ensi_ct *out,
+                                        void *stream) {
+    if (!ctx || !A || !masks || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, P = period, l1 = A->limbs;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "the block length must be a power of two up to %d", N / 2);
+    if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "the period must be a power of two up to the block length");
+    if (A->n < P || A->n % P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "the weights come in whole segments of %d columns, got %d", P, A->n);
+    const int n_seg = A->n / P, n_diag = 2 * P - 1;
+    if (l1 < 2 || out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input");
+    if (out->n != n_seg * n_diag) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_seg * n_diag);
+    if (masks->n < 3 * P || masks->limbs < l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "need %d sorting masks at %d limbs", 3 * P, l1);
+    if (A->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "in and out must not overlap");
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N;
+    std::vector<PmTerm> pt;
+    std::vector<int32_t> pb(1, 0);
+    for (int g = 0; g < n_seg; g++) {
+        const u64 *col = A->d + (size_t)g * P * a_ct;
+        for (int e = 0; e < P; e++) {  // entry e: column (x + e) mod P in slot x, without the block's last e slots
+            for (int c = 0; c < P; c++) {
+                const int r = ((c - e) % P + P) % P;
+                pt.push_back({col + (size_t)c * a_ct, (e && r >= P - e) ? P + r : r, 0});
+            }
+            pb.push_back((int32_t)pt.size());
+        }
+        for (int e = 1; e < P; e++) {  // entry P - 1 + e: the same column in those last e slots
+            for (int c = 0; c < P; c++) {
+                const int r = ((c - e) % P + P) % P;
+                if (r >= P - e) pt.push_back({col + (size_t)c * a_ct, 2 * P + r, 0});
+            }
+            pb.push_back((int32_t)pt.size());
+        }
+    }
+    int rc;
+    if ((rc = pmult_core(ctx, pt, pb, l1, A->limbs_alloc, masks, out, (hipStream_t)stream))) return rc;
+    out->scale = A->scale * masks->scale / (double)ctx->primes[l1 - 1];
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
+                            int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream) {
+    if (!ctx || !rk || !gk || !Ad || !V || !mask_head || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, P = period, l1 = V->limbs, m = V->n;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
+    if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
+    const int n_diag = 2 * P - 1;
+    if (Ad->n < n_diag || Ad->n % n_diag) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: the diagonalised weights come %d to a segment, got %d", n_diag, Ad->n);
+    const int n_seg = Ad->n / n_diag;
+    if (g0 < 0 || g0 + n_seg > s / P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: segments %d .. %d outside a block of %d segments", g0, g0 + n_seg - 1, s / P);
+    if (l1 < 3 || Ad->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the diagonalised weights must be one level below V (%d vs %d limbs)", Ad->limbs, l1);
+    if (out->limbs != l1 - 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be two levels below V");
+    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, m);
+    if (mask_head->n < 1 || mask_head->limbs < l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the head mask needs %d limbs", l1);
+    if ((size_t)n_seg * n_diag > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d segments give more than 65535 products per output", n_seg);
+    if (Ad->d == out->d || V->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int l2 = l1 - 1;
+    const size_t ad_ct = (size_t)2 * Ad->limbs_alloc * N, seg_ct = (size_t)2 * l2 * N, out_ct = (size_t)2 * out->limbs_alloc * N;
+    // outputs whose rotated operands are held at once (an output's products are relinearised together)
+    const int per = std::max(1, 1536 / (n_seg * std::max(1, n_diag - 1)));
+    const size_t n_rot = (size_t)std::min(per, m) * n_seg * (n_diag - 1), n_sg = (size_t)std::min(per, m) * n_seg;
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max(n_sg * 2 * l1 * N, std::max<size_t>(n_rot, 1) * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, n_sg * seg_ct))) return rc;
+    for (int i0 = 0; i0 < m; i0 += per) {
+        const int cnt = std::min(per, m - i0);
+        ensi_ct seg;
+        seg.ctx = ctx;
+        seg.owns = false;
+        seg.limbs = seg.limbs_alloc = l2;
+        seg.d = ctx->ws_rep;
+        seg.scale = V->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
+        std::vector<std::pair<int, int>> segs;
+        for (int i = 0; i < cnt; i++)
+            for (int k = 0; k < n_seg; k++) segs.push_back({i0 + i, g0 + k});
+        if ((rc = spread_segments(ctx, gk, V, segs, s, P, mask_head, &seg, st))) return rc;
+        // diagonal k < P pairs with the spread rotated by k, diagonal P - 1 + e with the spread rotated by e - P
+        std::vector<RotJob> jobs;
+        std::vector<MmTerm> terms;
+        std::vector<int32_t> begin(1, 0);
+        for (int i = 0; i < cnt; i++) {
+            for (int k = 0; k < n_seg; k++) {
+                const int sg = i * n_seg + k;
+                const u64 *w = seg.d + (size_t)sg * seg_ct;
+                for (int q = 0; q < n_diag; q++) {
+                    const int am = q < P ? q : q - 2 * P + 1;
+                    const u64 *b = w;
+                    if (am) {
+                        u64 *dst = ctx->ws_rot + ((size_t)sg * (n_diag - 1) + (q - 1)) * seg_ct;
+                        jobs.push_back({sg, am, dst});
+                        b = dst;
+                    }
+                    terms.push_back({Ad->d + ((size_t)k * n_diag + q) * ad_ct, b});
+                }
+            }
+            begin.push_back((int32_t)terms.size());
+        }
+        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, (int)segs.size(), l2, jobs, st))) return rc;
+        ensi_ct part = *out;
+        part.owns = false;
+        part.d = out->d + (size_t)i0 * out_ct;
+        part.n = cnt;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, Ad->limbs_alloc, l2, &part, st))) return rc;
+        out->scale = Ad->scale * seg.scale / (double)ctx->primes[l2 - 1];
+    }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
 // ------------------------------------------------------------------------- NTT
 extern "C" int ensi_ntt(ensi_ctx *ctx, void *data, int32_t n_limbs, const int32_t *prime_idx, int32_t inverse, void *stream) {
     if (!ctx || !data || !prime_idx || n_limbs < 1) return ENSI_E_BADARG;
