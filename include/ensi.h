@@ -327,7 +327,9 @@ int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const
  * (segment k = columns k period .. (k+1) period - 1 of the range); out[k (2 period - 1) + e], e < period, holds in slot
  * x the entry of column (x + e) mod period of segment k, except in the block's last e slots, which out[k (2 period - 1)
  * + period - 1 + e] (e >= 1) holds, zero elsewhere: plaintext products with ensi_segment_masks(s, period, limbs = l),
- * summed and rescaled once; out at l - 1 limbs.
+ * summed and rescaled once; out at l - 1 limbs.  prepare != 0 leaves out in the transform domain, where ensi_ccmm_av
+ * reads it in place for every column of V (out must then be allocated at exactly l - 1 limbs); such a batch is no
+ * ciphertext for any other entry point (export and decrypt refuse it).
  * ensi_ccmm_av then takes, per column v_i and segment g0 + k, w = that segment of v_i repeated through every block
  * (the giant step of ensi_ccmm_bsgs): slot x of Rot(w; e) holds V[(g0 + k) period + (x + e) mod period][i], the
  * factor of diagonal e in that slot; the last e slots of a block pair Rot(w; e - period) with diagonal period - 1 + e.
@@ -337,7 +339,8 @@ int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const
  * mask_head: ensi_block_head_mask(s, period, limbs = l); out: m ciphertexts at l - 2 limbs.  An output holds its
  * n_seg (2 period - 1) operand pairs at once (about 4 (l - 1) N words each); callers with many segments split the range
  * and add the partial outputs. */
-int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, ensi_ct *out, void *stream);
+int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, int32_t prepare, ensi_ct *out,
+                             void *stream);
 int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
                  int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream);
 

@@ -802,6 +802,7 @@ extern "C" int ensi_ct_info(const ensi_ct *ct, int32_t *n, int32_t *limbs, doubl
 }
 extern "C" int ensi_ct_export(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *out) {
     if (!ctx || !ct || !out) return ENSI_E_BADARG;
+    if (ct->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the batch holds prepared weights, which only ensi_ccmm_av reads");
     const size_t N = ctx->N;
     ENSI_HIP(ctx, hipDeviceSynchronize());
     if (ct->limbs == ct->limbs_alloc) {
@@ -887,6 +888,7 @@ extern "C" int ensi_encrypt(ensi_ctx *ctx, const ensi_pk *pk, const ensi_pt *pt,
 
 extern "C" int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct, int32_t slot_begin, int32_t n_slots, double *slots_out) {
     if (!ctx || !sk || !ct || !slots_out || slot_begin < 0 || n_slots < 1 || slot_begin + n_slots > ctx->N / 2) return ENSI_E_BADARG;
+    if (ct->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the batch holds prepared weights, which only ensi_ccmm_av reads");
     const int N = ctx->N, n = ct->n;
     const int use = std::min(ct->limbs, 2);
     hipStream_t st = nullptr;
@@ -1631,8 +1633,9 @@ extern "C" int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs) {
 
 // out_o = Rescale(Relin(sum_{t in [begin[o], begin[o+1])} a_t (x) b_t)); operands have l1 limbs.  Outputs are
 // handled in groups of at most one rotation chunk whose operand polynomials fit a bounded workspace.
+// a_pre: the a operands already hold their transform (limb stride l1): they are read in place
 static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &terms, const std::vector<int32_t> &begin, int l1,
-                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st) {
+                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st, bool a_pre = false) {
     const int N = ctx->N, n_out = (int)begin.size() - 1, ext = l1 + ctx->K;
     if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ciphertext multiplication: no limb left to drop");
     if (out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the operands (%d vs %d limbs)", out->limbs, l1);
@@ -1643,35 +1646,53 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     // one that enters several products is gathered and transformed once), at most 65535 products, at least one output
     const size_t max_ops = std::max<size_t>(2, ((size_t)1 << 30) / ((size_t)2 * l1 * N));
     const int max_out = ctx->ks16 ? rot_chunk() : 64;
+    if (a_pre && limb_stride_a != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "prepared operands have %d limbs, the product runs at %d", limb_stride_a, l1);
     std::vector<int> cut(1, 0);
     std::vector<MmOperand> ops;
     std::vector<MmPair> pairs(terms.size());
     std::vector<size_t> op_base(1, 0);
+    std::vector<int> n_gather;  // per group: operands to gather and transform (they come first in the group's list)
     size_t need_a = 1, need_o = 0;
     for (int o0 = 0; o0 < n_out;) {
         std::map<std::pair<const u64 *, int>, int> id;
-        int o1 = o0;
+        std::vector<MmOperand> gops;
+        int o1 = o0, n_np = 0;
         for (; o1 < n_out && o1 - o0 < max_out && begin[o1 + 1] - begin[o0] <= 65535; o1++) {
             if (o1 > o0) {  // would this output's new operands still fit?
                 std::map<std::pair<const u64 *, int>, int> fresh;
                 for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
                     const auto ka = std::make_pair(terms[t].a, limb_stride_a), kb = std::make_pair(terms[t].b, limb_stride_b);
-                    if (!id.count(ka)) fresh.emplace(ka, 0);
+                    if (!a_pre && !id.count(ka)) fresh.emplace(ka, 0);
                     if (!id.count(kb)) fresh.emplace(kb, 0);
                 }
-                if (id.size() + fresh.size() > max_ops) break;
+                if ((size_t)n_np + fresh.size() > max_ops) break;
             }
             for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
                 auto ia = id.emplace(std::make_pair(terms[t].a, limb_stride_a), (int)id.size());
-                if (ia.second) ops.push_back({terms[t].a, limb_stride_a, 0});
+                if (ia.second) {
+                    gops.push_back({terms[t].a, nullptr, limb_stride_a, a_pre ? 1 : 0});
+                    n_np += a_pre ? 0 : 1;
+                }
                 auto ib = id.emplace(std::make_pair(terms[t].b, limb_stride_b), (int)id.size());
-                if (ib.second) ops.push_back({terms[t].b, limb_stride_b, 0});
+                if (ib.second) {
+                    gops.push_back({terms[t].b, nullptr, limb_stride_b, 0});
+                    n_np++;
+                }
                 pairs[t] = {ia.first->second, ib.first->second};
             }
         }
+        // operands to transform first, prepared ones after them
+        std::vector<int> where(gops.size());
+        int at_np = 0, at_pre = n_np;
+        for (size_t u = 0; u < gops.size(); u++) where[u] = gops[u].pre ? at_pre++ : at_np++;
+        std::vector<MmOperand> sorted(gops.size());
+        for (size_t u = 0; u < gops.size(); u++) sorted[where[u]] = gops[u];
+        for (int t = begin[o0]; t < begin[o1]; t++) pairs[t] = {where[pairs[t].a], where[pairs[t].b]};
+        ops.insert(ops.end(), sorted.begin(), sorted.end());
+        n_gather.push_back(n_np);
         cut.push_back(o1);
         op_base.push_back(ops.size());
-        need_a = std::max(need_a, id.size());
+        need_a = std::max(need_a, (size_t)n_np);
         need_o = std::max(need_o, (size_t)(o1 - o0));
         o0 = o1;
     }
@@ -1683,6 +1704,9 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     if ((rc = grow(ctx, &ctx->ws_digits, &ctx->ws_digits_words, need_o * rw))) return rc;
     if ((rc = grow(ctx, &ctx->ws_u, &ctx->ws_u_words, need_o * 2 * ext * N))) return rc;
     if ((rc = ensure_desc(ctx, need_o))) return rc;
+    for (size_t k = 0; k + 1 < op_base.size(); k++)
+        for (size_t u = op_base[k]; u < op_base[k + 1]; u++)
+            ops[u].t = ops[u].pre ? ops[u].p : ctx->ws_ma + (u - op_base[k]) * 2 * l1 * N;
     const size_t ow = ops.size() * (sizeof(MmOperand) / 8), pw = pairs.size() * (sizeof(MmPair) / 8), bw = (begin.size() + 1) / 2;
     if ((rc = grow(ctx, &ctx->ws_mt, &ctx->ws_mt_words, ow + pw + bw + 2))) return rc;
     if (!ops.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt, ops.data(), ops.size() * sizeof(MmOperand), hipMemcpyHostToDevice, st));
@@ -1700,7 +1724,7 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
         g.begin = (const int32_t *)(ctx->ws_mt + ow + pw) + o0;
         g.t_base = begin[o0];
         g.n_terms = begin[o1] - begin[o0];
-        g.n_ops = (int)(op_base[k + 1] - op_base[k]);
+        g.n_ops = n_gather[k];
         g.n_out = cnt;
         g.l1 = l1;
         g.ws_a = ctx->ws_ma;
@@ -2468,9 +2492,10 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
 }
 
 // ------------- CCMM, several heads per ciphertext: weights times V from diagonalised weights
-extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, ensi_ct *out,
-                                        void *stream) {
+extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, int32_t prepare,
+                                        ensi_ct *out, void *stream) {
     if (!ctx || !A || !masks || !out) return ENSI_E_BADARG;
+    if (A->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the weights are already prepared");
     const int N = ctx->N, P = period, l1 = A->limbs;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "the period must be a power of two up to the block length");
@@ -2501,8 +2526,15 @@ extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t
         }
     }
     int rc;
+    out->prepared = false;
     if ((rc = pmult_core(ctx, pt, pb, l1, A->limbs_alloc, masks, out, (hipStream_t)stream))) return rc;
     out->scale = A->scale * masks->scale / (double)ctx->primes[l1 - 1];
+    if (prepare) {
+        // left in the transform domain, where every column of V multiplies it: ensi_ccmm_av reads it in place
+        if (out->limbs_alloc != out->limbs) ENSI_FAIL(ctx, ENSI_E_SHAPE, "prepared weights need a batch allocated at %d limbs", out->limbs);
+        launch_ntt(ctx, out->d, out->n * 2 * out->limbs, make_map(ctx, out->limbs, false), false, (hipStream_t)stream);
+        out->prepared = true;
+    }
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
 }
@@ -2572,7 +2604,7 @@ extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk,
         part.owns = false;
         part.d = out->d + (size_t)i0 * out_ct;
         part.n = cnt;
-        if ((rc = mult_core(ctx, key, terms, begin, l2, Ad->limbs_alloc, l2, &part, st))) return rc;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, Ad->limbs_alloc, l2, &part, st, Ad->prepared))) return rc;
         out->scale = Ad->scale * seg.scale / (double)ctx->primes[l2 - 1];
     }
     ENSI_HIP(ctx, hipGetLastError());

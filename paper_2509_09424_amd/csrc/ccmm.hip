@@ -39,8 +39,8 @@ __global__ __launch_bounds__(MM_THREADS) void k_mm_tensor_mac(MmGroup g, int N, 
     const size_t poly = (size_t)g.l1 * N;
     for (int t = t0; t < t1; t++) {
         const MmPair pr = g.pairs[t - g.t_base];
-        const u64 *xa = g.ws_a + ((size_t)pr.a * 2 * g.l1 + i) * N + idx;
-        const u64 *xb = g.ws_a + ((size_t)pr.b * 2 * g.l1 + i) * N + idx;
+        const u64 *xa = g.ops[pr.a].t + (size_t)i * N + idx;
+        const u64 *xb = g.ops[pr.b].t + (size_t)i * N + idx;
         const u64 a0 = xa[0], a1 = xa[poly], b0 = xb[0], b1 = xb[poly];
         d0 = add_mod(d0, mont_mul(a0, b0, q, qn), q);
         d1 = add_mod(d1, add_mod(mont_mul(a0, b1, q, qn), mont_mul(a1, b0, q, qn), q), q);

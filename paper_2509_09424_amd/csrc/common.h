@@ -96,15 +96,17 @@ struct MmTerm {
 // On the device a group of outputs names every distinct operand ciphertext once ([2][limb_stride][N] words each), so
 // that an operand shared by several products is gathered and transformed once, and its products as index pairs.
 struct MmOperand {
-    const u64 *p;
-    int32_t limb_stride, pad;
+    const u64 *p;  // where the operand lies
+    const u64 *t;  // its transformed polynomials, [2][l1][N]: a slot of the group's operand array, or p itself
+    int32_t limb_stride;
+    int32_t pre;   // p already holds the transform (prepared operands, limb stride l1): neither gathered nor transformed
 };
 struct MmPair {
     int32_t a, b;
 };
 // One group of outputs of out_o = Rescale(Relin(sum_t a_t (x) b_t)); same conventions as PmGroup.
 struct MmGroup {
-    const MmOperand *ops;  // [n_ops]
+    const MmOperand *ops;  // the group's operands; the first n_ops are gathered and transformed, prepared ones follow
     const MmPair *pairs;   // [n_terms], term t of the batch at index t - t_base
     const int32_t *begin;
     int t_base, n_terms, n_ops, n_out;
@@ -223,6 +225,7 @@ struct ensi_ct {
     double scale;
     u64 *d;
     bool owns;
+    bool prepared = false;  // holds transform-domain data that only ensi_ccmm_av reads (ensi_diagonalise_weights)
 };
 
 #define ENSI_FAIL(ctx, code, ...)                              \

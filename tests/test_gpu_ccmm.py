@@ -538,6 +538,14 @@ def test_ccmm_av_small_ring(params, l1, s, period, g0, n_seg, m):
     assert out.n == m and out.limbs == l1 - 2
     assert np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    # the weights left in the transform domain: the same words come out
+    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    assert np.array_equal(outp.export(), stack_cts(want))
+    with pytest.raises(p.binding.EnsiError, match="code -1"):
+        adp.export()
+    adp.free()
+    outp.free()
     lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.segment_masks(s, period, l1)
     ad2 = p.ctx.diagonalise_weights(g_a, s, period, ls)
     out2 = p.ctx.ccmm_av(g_rk, g_gk, ad2, g_v, s, period, g0, lh)
@@ -567,7 +575,10 @@ def test_ccmm_av_full_ring():
     want = p.o.ccmm_av(o_ad, o_v, s, period, g0, o_rk, o_gks)
     assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
-    for h in (g_a, g_v, mh, ms, ad, out, g_gk, g_rk):
+    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)  # weights left in the transform domain
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    assert np.array_equal(outp.export(), stack_cts(want))
+    for h in (g_a, g_v, mh, ms, ad, adp, out, outp, g_gk, g_rk):
         h.free()
     p.close()
 
@@ -586,6 +597,9 @@ def test_ccmm_av_at_the_benchmark_parameters():
     want = p.o.ccmm_av(o_ad, o_v, s, period, g0, o_rk, o_gks)
     assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
-    for h in (g_a, g_v, mh, ms, ad, out, g_gk, g_rk):
+    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)  # weights left in the transform domain
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    assert np.array_equal(outp.export(), stack_cts(want))
+    for h in (g_a, g_v, mh, ms, ad, adp, out, outp, g_gk, g_rk):
         h.free()
     p.close()

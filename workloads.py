@@ -38,7 +38,7 @@ class Workload:
     batch: int = 0  # key-switch microbench: number of ciphertexts
     kappa: float = 0.0  # scalar applied before the rescale between two layers
     op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs), "ccmm", "ccmm_blocks",
-    #                     "ccmm_bsgs" (Q K^T form), "ccmm_bsgs_av" (weights times V form) or "ccmm_segment"
+    #                     "ccmm_bsgs" (Q K^T form), "ccmm_bsgs_av" (weights times V form), "ccmm_segment" or "ccmm_av"
     period: int = 0  # baby-step range of the block-wise element extraction in giant and baby steps
 
     @property
@@ -98,6 +98,8 @@ WORKLOADS.append(Workload("ccmmav", 12, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # ciphertext, 384 packed inputs, 3 rotation amounts) on a chain that fits that ring (6 x 50-bit + 2 x 60-bit primes).
 # The fused N = 2^16 kernels do not apply: transforms, ModUp, inner product and ModDown run as separate kernels.
 WORKLOADS.append(Workload("paper1536n14", 13, 14, 50, 6, 60, 2, 2, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
+# The same slice of weights times V from diagonalised weights (prepared once for all 96 columns of V, outside the step).
+WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_av", period=16))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
