@@ -61,3 +61,16 @@ def test_giant_and_baby_step_counts():
     _, roof = bench.roofline_for(w, {"ks_icols_special": (1.0, 1)})
     switches = 32 + (32 * 4 + 512) + (512 * 2 + 1)
     assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
+
+
+def test_segment_form_counts():
+    w = wl.BY_NAME["ccmmqkseg"]  # 96 ciphertexts of K, period 16: 31 diagonals
+    unit = 8.0 * w.N
+    _, roof = bench.roofline_for(w, {"ks_icols_special": (1.0, 1)})
+    switches = 96 + (96 * 4 + 96 * 30 + 31)  # aligning rotations; fill groups, rotations of the spread operands, relinearisations
+    assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})
+    assert abs(roof["achieved"] - (96 * 4 * 16 + (256 + 120) * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    w = wl.BY_NAME["ccmmavseg"]  # one column of V, 32 segments
+    _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
+    assert abs(roof["achieved"] - (1 * 2 * 16 + (32 * 5 + 1) * 2 * 15) * unit / 1e-3 / 1e9) < 1e-6
