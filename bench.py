@@ -376,7 +376,7 @@ def roofline_for(w, prof):
     unit = 8.0 * N  # bytes of one limb
     # key-switch work as stages at one level each: (limbs, rotations, raises, switch-backs to the ciphertext basis --
     # grouped rotations share one --, keys streamed); plaintext multiplications as (limbs, products, outputs)
-    ks, pm = [], []
+    ks, pm, mm = [], [], []  # mm: ciphertext products as (limbs, distinct operands transformed, outputs)
     if w.name == "keyswitch":
         ks.append((L, w.batch, w.batch, w.batch, w.batch))  # every rotation streams its key
     elif w.op == "rope":
@@ -393,6 +393,7 @@ def roofline_for(w, prof):
         ks.append((L - 1, n_el * (1 + f_rot) + w.d_out, w.d_in + n_el * f_raise + w.d_out, n_el * (1 + f_raise) + w.d_out,
                    -(-w.d_in // 16) * w.d_out + f_rot * -(-n_el // 64) + 1))
         pm.append((L, n_el, n_el))
+        mm.append((L - 1, w.d_in + n_el, w.d_out))
     elif w.op == "ccmm":
         # every element of B: one mask product and log2(period) rotate-and-add steps one level down (the log2(n/period)
         # steps per column at the top level and the relinearisations are few and counted with them)
@@ -403,6 +404,7 @@ def roofline_for(w, prof):
         n_raise = n_el * b_raise + w.d_out * g_raise + w.d_out
         ks.append((L - 1, n_el * b_rot + w.d_out * g_rot + w.d_out, n_raise, n_raise, b_rot * -(-n_el // 64) + g_rot + 1))
         pm.append((L, n_el, n_el))
+        mm.append((L - 1, w.d_in + n_el, w.d_out))
     elif w.op in ("ccmm_bsgs", "ccmm_bsgs_av"):
         # giant steps per segment (aligning rotation at the top level, head mask, fill over the block one level down),
         # baby steps per element (aligning rotation there, period-start mask, fill over the period two levels down),
@@ -419,6 +421,7 @@ def roofline_for(w, prof):
         ks.append((L - 2, n_el * b_rot + w.d_out, n_el * b_raise + w.d_out, n_el * b_raise + w.d_out, b_rot * -(-n_el // 64) + 1))
         pm.append((L, n_seg, n_seg))
         pm.append((L - 1, n_el, n_el))
+        mm.append((L - 2, w.d_in + n_el, w.d_out))
     elif w.op == "ccmm_av":
         # per column of V and segment: one giant step (aligning rotation at the top level, head mask, fill over the block one
         # level down) and 2P-2 rotations of the spread operand on one raise; one relinearisation per output
@@ -429,6 +432,7 @@ def roofline_for(w, prof):
         ks.append((L - 1, n_sg * (g_rot + 2 * P - 2) + m, n_sg * (g_raise + 1) + m, n_sg * (g_raise + 2 * P - 2) + m,
                    g_rot * -(-n_sg // 64) + (2 * P - 2) * -(-n_sg // 16) + 1))
         pm.append((L, n_sg, n_sg))
+        mm.append((L - 1, n_sg * (2 * P - 1), m))  # the prepared weights are not transformed again
     elif w.op == "ccmm_segment":
         # per ciphertext of B: one giant step (aligning rotation at the top level, head mask, fill over the block one level
         # down) and 2P-2 rotations of the spread operand on one raise; 2P-1 relinearisations two levels down; the sorting
@@ -441,10 +445,13 @@ def roofline_for(w, prof):
                    g_rot * -(-dd // 64) + (n_diag - 1) * -(-dd // 16) + 1))
         pm.append((L, dd, dd))
         pm.append((L - 2, P * P + P * (P - 1) // 2, P))
+        mm.append((L - 1, dd + dd * n_diag, n_diag))
     else:
         n_in = -(-w.d_in // w.c_tot)
         # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
         ks.append((L, w.d_in - n_in, n_in, w.d_in - n_in, -(-n_in // 16) * (min(w.c_tot, w.d_in) - 1)))
+
+    fused_ks = w.log_n == 16 and w.q_bits <= 50  # the key switch transforms inside its own kernels
 
     def ks_sum(f):
         return sum(f(l, -(-l // alpha), l + K, n_rot, n_raise, n_sw, n_key) for l, n_rot, n_raise, n_sw, n_key in ks)
@@ -465,7 +472,10 @@ def roofline_for(w, prof):
         "ks_icols_special": ks_sum(lambda l, b, e, rot, ra, sw, key: sw * 4 * K),                    # special limbs in, split residues out
         "ks_icols_moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: sw * (2 * l + 2 * K + 2 * l)),  # accumulators and residues in, ciphertext out
         # unfused path
-        "ntt": ks_sum(lambda l, b, e, rot, ra, sw, key: 2 * (ra * b * e + rot * 2 * e)),
+        # library transforms: of the key switch on the unfused path; of the ciphertext products' operands (two passes, each
+        # limb in and out) and of their three sums per output, back
+        "ntt": (0 if fused_ks else ks_sum(lambda l, b, e, rot, ra, sw, key: 2 * (ra * b * e + rot * 2 * e)))
+               + sum(4 * (ops * 2 * l + outs * 3 * l) for l, ops, outs in mm),
         "inner_product": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (b * e + 2 * e) + key * 2 * b * e),  # digits in, accumulators out; keys
         "modup": ks_sum(lambda l, b, e, rot, ra, sw, key: ra * (l + b * e)),
         "moddown": ks_sum(lambda l, b, e, rot, ra, sw, key: rot * (2 * e + 3 * l)),

@@ -71,6 +71,9 @@ def test_segment_form_counts():
     assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
     _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})
     assert abs(roof["achieved"] - (96 * 4 * 16 + (256 + 120) * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    # library transforms of the products: 96 + 96 * 31 operands (two polynomials of 15 limbs, two passes, in and out), 31 x 3 sums back
+    _, roof = bench.roofline_for(w, {"ntt_fwd_cols": (1.0, 1)})
+    assert abs(roof["achieved"] - 4 * ((96 + 96 * 31) * 2 * 15 + 31 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
     w = wl.BY_NAME["ccmmavseg"]  # one column of V, 32 segments
     _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
     assert abs(roof["achieved"] - (1 * 2 * 16 + (32 * 5 + 1) * 2 * 15) * unit / 1e-3 / 1e9) < 1e-6
