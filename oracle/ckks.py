@@ -766,13 +766,28 @@ class Oracle:
             out.append(self.pmult_sum_rescale(terms, float(self.pr.q[l1 - 3])))
         return out
 
-    def diagonalise_weights(self, a_cts, s, period):
+    @staticmethod
+    def diagonal_schedule(period, baby):
+        """Baby steps and giant steps over the diagonals of a segment: diagonal q (q < period: rotation
+        amount q; q >= period: amount q - 2 period + 1, the one used in the last slots of a block) has
+        amount = e1 + t with 0 <= e1 < baby and t a multiple of baby; returns the list of (e1, t).
+        The operand that is rotated per product only moves by e1; the other operand is pre-rotated by
+        -t and the sum of all products with the same t is rotated by t afterwards."""
+        out = []
+        for q in range(2 * period - 1):
+            amount = q if q < period else q - 2 * period + 1
+            e1 = amount % baby
+            out.append((e1, amount - e1))
+        return out
+
+    def diagonalise_weights(self, a_cts, s, period, baby, gks):
         """The left operand of ccmm_av in the arrangement its right operand's rotations need: a_cts
         = the `period` columns g period + c of A (column-encoded, one block of s slots per head);
         returns 2 period - 1 ciphertexts one level down.  Entry e < period: slot x holds column
         (x + e) mod period where x + e stays inside the block, 0 in the block's last e slots; entry
-        period - 1 + e (e >= 1): the same column in those last e slots, 0 elsewhere.  Plaintext
-        products with the masks of segment_masks, summed and rescaled once."""
+        period - 1 + e (e >= 1): the same column in those last e slots, 0 elsewhere (plaintext
+        products with the masks of segment_masks, summed and rescaled once); each entry is then
+        rotated by -t, its giant step of diagonal_schedule."""
         l1 = a_cts[0].l1
         masks = self.segment_masks(s, period, l1)
         q = self.pr.q[:l1]
@@ -790,29 +805,38 @@ class Oracle:
             lo.append(self.pmult_sum_rescale(tl, ql))
             if e:
                 hi.append(self.pmult_sum_rescale(th, ql))
-        return lo + hi
+        sched = self.diagonal_schedule(period, baby)
+        return [self.rotate(ct, gks[-t]) if t else ct for ct, (_, t) in zip(lo + hi, sched)]
 
-    def ccmm_av(self, ad_segs, v_cts, s, period, g0, rk, gks):
+    def ccmm_av(self, ad_segs, v_cts, s, period, baby, g0, rk, gks):
         """CCMM section, several heads per ciphertext, the weights-times-V form: out_i = sum_j a_j (x)
         E(v_i, j) over the tokens j of the segments g0, g0 + 1, ... (ad_segs[k] = diagonalise_weights
         of the columns of segment g0 + k), without replicating single elements: with w = the
         segment of v_i repeated through every block (spread_segment), slot x of Rot(w; e) holds
-        V[g period + (x + e) mod period, i], which is what entry e of the diagonalised weights
-        multiplies in that slot; the last e slots of a block take Rot(w; e - period) and entry
-        period - 1 + e.  All products of an output are added, relinearised and rescaled once.  Two
-        levels (masks on both operands, the product)."""
+        V[g period + (x + e) mod period, i], which is what diagonal e of the weights multiplies in
+        that slot; the last e slots of a block take Rot(w; e - period) and diagonal period - 1 + e.
+        Baby steps and giant steps over the diagonals (diagonal_schedule): w is only rotated by e1 <
+        baby; the products whose diagonals share a giant step t are added, relinearised and rescaled
+        together and that sum is rotated by t; out_i is the sum over t.  Two levels (masks on both
+        operands, the product)."""
         l1 = v_cts[0].l1
         mask_head = self.block_head_mask(s, period, l1)
+        sched = self.diagonal_schedule(period, baby)
         out = []
         for v in v_cts:
-            pairs = []
+            groups = {}
             for k, ad in enumerate(ad_segs):
                 w = self.spread_segment(v, g0 + k, s, period, mask_head, gks)
-                for e in range(period):
-                    pairs.append((ad[e], self.rotate(w, gks[e]) if e else w))
-                for e in range(1, period):
-                    pairs.append((ad[period - 1 + e], self.rotate(w, gks[e - period])))
-            out.append(self.mult_sum_relin_rescale(pairs, rk))
+                rot = [w] + [self.rotate(w, gks[e1]) for e1 in range(1, baby)]
+                for q, (e1, t) in enumerate(sched):
+                    groups.setdefault(t, []).append((ad[q], rot[e1]))
+            acc = None
+            for t in sorted(groups):
+                part = self.mult_sum_relin_rescale(groups[t], rk)
+                if t:
+                    part = self.rotate(part, gks[t])
+                acc = part if acc is None else self.add_ct(acc, part)
+            out.append(acc)
         return out
 
     # ------------------------- CCMM over heads, element extraction in baby steps and giant steps

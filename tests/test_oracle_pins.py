@@ -640,8 +640,8 @@ def test_segment_of_columns_from_diagonals():
 
 
 def test_weights_times_v_from_diagonalised_weights():
-    """The weights-times-V form without single-element replication: the diagonalised weights and the product
-    over two segments against numpy."""
+    """The weights-times-V form without single-element replication: the diagonalised weights, the schedule of baby
+    and giant steps over the diagonals, and the product over segments against numpy."""
     w = wl.WORKLOADS[1]
     pr = small_params(w, 6)  # 32 slots: 2 heads of 16 tokens
     o = Oracle(pr)
@@ -653,29 +653,34 @@ def test_weights_times_v_from_diagonalised_weights():
     a_cts = [_enc(o, rng, pk, np.concatenate([Wt[h][:, j] for h in range(heads)]), l1) for j in range(s)]
     v_cts = [_enc(o, rng, pk, np.concatenate([V[h][:, i] for h in range(heads)]), l1) for i in range(m)]
     beta = pr.beta(pr.L)
-    steps = set(range(1, period)) | set(range(1 - period, 0)) | {g * period for g in range(1, s // period)}
+    steps = set(range(1, period)) | set(range(-period, 0)) | {period} | {g * period for g in range(1, s // period)}
     steps |= {st for grp in Oracle.fill_steps(period, s, -1) for st in grp}
     gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 131) for st in sorted(steps)}
     rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 137)
-    # segment 2 of the weights, diagonalised: entry e holds column 2 period + (x + e) mod period in slot x, split at the block's end
+    # every diagonal's rotation amount splits into a baby step below `baby` and a giant step that is a multiple of it
+    assert Oracle.diagonal_schedule(4, 2) == [(0, 0), (1, 0), (0, 2), (1, 2), (1, -4), (0, -2), (1, -2)]
+    assert Oracle.diagonal_schedule(4, 4) == [(0, 0), (1, 0), (2, 0), (3, 0), (1, -4), (2, -4), (3, -4)]
+    # segment 2 of the weights, diagonalised: entry e holds column 2 period + (x + e) mod period in slot x, split at the
+    # block's end, and is then shifted by its giant step
     g = 2
-    ad = o.diagonalise_weights(a_cts[g * period:(g + 1) * period], s, period)
-    assert len(ad) == 2 * period - 1 and all(c.l1 == l1 - 1 for c in ad)
     x = np.arange(s)
-    for e in range(period):
-        want = np.concatenate([np.where(x + e < s, Wt[h][x, g * period + (x + e) % period], 0.0) for h in range(heads)])
-        assert np.abs(o.decrypt(ad[e], sk) - want).max() < 1e-3, e
-        if e:
-            want = np.concatenate([np.where(x + e >= s, Wt[h][x, g * period + (x + e) % period], 0.0) for h in range(heads)])
-            assert np.abs(o.decrypt(ad[period - 1 + e], sk) - want).max() < 1e-3, e
-    # the product over segments 1 and 2, then over all four
-    for g0, n_seg in ((1, 2), (0, 4)):
-        ads = [o.diagonalise_weights(a_cts[(g0 + k) * period:(g0 + k + 1) * period], s, period) for k in range(n_seg)]
-        O = o.ccmm_av(ads, v_cts, s, period, g0, rk, gks)
+    for baby in (2, 4):
+        sched = Oracle.diagonal_schedule(period, baby)
+        ad = o.diagonalise_weights(a_cts[g * period:(g + 1) * period], s, period, baby, gks)
+        assert len(ad) == 2 * period - 1 and all(c.l1 == l1 - 1 for c in ad)
+        for q, (e1, t) in enumerate(sched):
+            e = q if q < period else q - period + 1
+            keep = (x + e < s) if q < period else (x + e >= s)
+            plain = np.concatenate([np.where(keep, Wt[h][x, g * period + (x + e) % period], 0.0) for h in range(heads)])
+            assert np.abs(o.decrypt(ad[q], sk) - np.roll(plain, t)).max() < 1e-3, (baby, q)  # Rot(.; -t)[y] = plain[y - t]
+    # the product over segments 1 and 2, then over all four, with both splits of the diagonals
+    for g0, n_seg, baby in ((1, 2, 2), (0, 4, 4), (0, 4, 1)):
+        ads = [o.diagonalise_weights(a_cts[(g0 + k) * period:(g0 + k + 1) * period], s, period, baby, gks) for k in range(n_seg)]
+        O = o.ccmm_av(ads, v_cts, s, period, baby, g0, rk, gks)
         lo, hi = g0 * period, (g0 + n_seg) * period
         for i in range(m):
             ref = np.concatenate([Wt[h][:, lo:hi] @ V[h][lo:hi, i] for h in range(heads)])
-            assert O[i].l1 == l1 - 2 and np.abs(o.decrypt(O[i], sk) - ref).max() < 1e-3, (g0, i)
+            assert O[i].l1 == l1 - 2 and np.abs(o.decrypt(O[i], sk) - ref).max() < 1e-3, (g0, baby, i)
 
 
 # -------------------------------------------------------------------- PCMM
