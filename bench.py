@@ -134,16 +134,18 @@ class Runner:
             pt = self.ctx.encode(zb, self.L)
             self.ct_in = self.ctx.encrypt(self.pk, pt)
             pt.free()
-            steps = set(range(1, P)) | set(range(1 - P, 0)) | {g * P for g in range(1, d // P)} | set(self.ctx.fill_steps(P, sl, -1))
+            self.baby = 4  # the column of V is rotated by 1 .. 3 only; the weights carry the giant steps
+            giant = {k * self.baby for k in range(1, P // self.baby + 1)}
+            steps = set(range(1, self.baby)) | giant | {-t for t in giant} | {g * P for g in range(1, d // P)} | set(self.ctx.fill_steps(P, sl, -1))
             self.gk = self.ctx.galois_keygen(self.sk, sorted(steps), None, 13)
             self.rk = self.ctx.relin_keygen(self.sk, None, 17)
             self.pt = self.ctx.block_head_mask(sl, P, self.L)
             masks = self.ctx.segment_masks(sl, P, self.L)
             # the weights are rearranged once for all columns of V: outside the timed step, its time reported beside it
-            self.ct_a = self.ctx.diagonalise_weights(ct_a, sl, P, masks, prepare=True)
+            self.ct_a = self.ctx.diagonalise_weights(self.gk, ct_a, sl, P, self.baby, masks, prepare=True)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
-            self.ctx.diagonalise_weights(ct_a, sl, P, masks, self.ct_a, prepare=True)
+            self.ctx.diagonalise_weights(self.gk, ct_a, sl, P, self.baby, masks, self.ct_a, prepare=True)
             torch.cuda.synchronize()
             self.prepare_ms = (time.perf_counter() - t0) * 1e3
             log("diagonalised %d weight columns in %.1f ms (once for all columns of V)" % (d, self.prepare_ms))
@@ -258,7 +260,7 @@ class Runner:
             self.ctx.ccmm_bsgs(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.terms, self.pt, self.pt2, self.ct_out)
             return
         if w.op == "ccmm_av":
-            self.ctx.ccmm_av(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, 0, self.pt, self.ct_out)
+            self.ctx.ccmm_av(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.baby, 0, self.pt, self.ct_out)
             return
         if w.op == "ccmm_segment":
             self.ctx.ccmm_segment(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, 1, self.pt, self.pt2, self.ct_out)
@@ -425,14 +427,15 @@ def roofline_for(w, prof):
     elif w.op == "ccmm_av":
         # per column of V and segment: one giant step (aligning rotation at the top level, head mask, fill over the block one
         # level down) and 2P-2 rotations of the spread operand on one raise; one relinearisation per output
-        P, n_seg, m = w.period, w.d_in // w.period, w.d_out
+        P, n_seg, m, baby = w.period, w.d_in // w.period, w.d_out, 4
         g_rot, g_raise = fill_counts(P, w.tokens)
-        n_sg = n_seg * m
+        n_sg, n_t = n_seg * m, 2 * P // baby  # spread operands; giant steps (sums per output)
         ks.append((L, n_sg, m, n_sg, n_seg))
-        ks.append((L - 1, n_sg * (g_rot + 2 * P - 2) + m, n_sg * (g_raise + 1) + m, n_sg * (g_raise + 2 * P - 2) + m,
-                   g_rot * -(-n_sg // 64) + (2 * P - 2) * -(-n_sg // 16) + 1))
+        ks.append((L - 1, n_sg * (g_rot + baby - 1) + n_t * m, n_sg * (g_raise + 1) + n_t * m, n_sg * (g_raise + baby - 1) + n_t * m,
+                   g_rot * -(-n_sg // 64) + (baby - 1) * -(-n_sg // 16) + 1))
+        ks.append((L - 2, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m))  # the sums rotated by their giant steps
         pm.append((L, n_sg, n_sg))
-        mm.append((L - 1, n_sg * (2 * P - 1), m))  # the prepared weights are not transformed again
+        mm.append((L - 1, n_sg * baby, n_t * m))  # the prepared weights are not transformed again
     elif w.op == "ccmm_segment":
         # per ciphertext of B: one giant step (aligning rotation at the top level, head mask, fill over the block one level
         # down) and 2P-2 rotations of the spread operand on one raise; 2P-1 relinearisations two levels down; the sorting
@@ -583,7 +586,7 @@ def cpu_baseline(w, budget_s=12.0):
             n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
         elif w.op == "ccmm_av":
             n_diag, n_sg = 2 * w.period - 1, w.d_in // w.period * w.d_out
-            n_rot = n_sg * (1 + fill_counts(w.period, w.tokens)[0] + n_diag - 1)
+            n_rot = n_sg * (1 + fill_counts(w.period, w.tokens)[0] + 3) + 7 * w.d_out
             n_el = n_sg * n_diag
             n_pm = n_sg
         elif w.op == "ccmm_segment":

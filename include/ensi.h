@@ -322,27 +322,29 @@ int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const
 
 /* The other attention product, weights times V, without replicating single elements (CCMM section; A = the s x s
  * weights of every head column-encoded, ciphertext j = column j with head h in block h; V column-encoded alike):
- *   out_i = Rescale(Relin(sum over the tokens j of the given segments of a_j (x) E(v_i, j))).
- * ensi_diagonalise_weights rearranges whole segments of A once, for all columns of V: A holds n_seg * period columns
- * (segment k = columns k period .. (k+1) period - 1 of the range); out[k (2 period - 1) + e], e < period, holds in slot
- * x the entry of column (x + e) mod period of segment k, except in the block's last e slots, which out[k (2 period - 1)
- * + period - 1 + e] (e >= 1) holds, zero elsewhere: plaintext products with ensi_segment_masks(s, period, limbs = l),
- * summed and rescaled once; out at l - 1 limbs.  prepare != 0 leaves out in the transform domain, where ensi_ccmm_av
- * reads it in place for every column of V (out must then be allocated at exactly l - 1 limbs); such a batch is no
- * ciphertext for any other entry point (export and decrypt refuse it).
- * ensi_ccmm_av then takes, per column v_i and segment g0 + k, w = that segment of v_i repeated through every block
- * (the giant step of ensi_ccmm_bsgs): slot x of Rot(w; e) holds V[(g0 + k) period + (x + e) mod period][i], the
- * factor of diagonal e in that slot; the last e slots of a block pair Rot(w; e - period) with diagonal period - 1 + e.
- * One ModUp of w serves its 2 period - 2 rotations; all products of an output are added, relinearised and rescaled
- * once.  Two levels below V.  gk: keys for the steps (g0 + k) period, ensi_fill_steps(period, s, -1), 1 .. period - 1
- * and -(period - 1) .. -1.  Ad: n_seg (2 period - 1) ciphertexts at l - 1 limbs; V: m ciphertexts at l limbs (l >= 3);
- * mask_head: ensi_block_head_mask(s, period, limbs = l); out: m ciphertexts at l - 2 limbs.  An output holds its
- * n_seg (2 period - 1) operand pairs at once (about 4 (l - 1) N words each); callers with many segments split the range
- * and add the partial outputs. */
-int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, int32_t prepare, ensi_ct *out,
-                             void *stream);
+ *   out_i = sum over the tokens j of the given segments of a_j (x) E(v_i, j)   (products relinearised and rescaled).
+ * Per column v_i and segment g, w = that segment of v_i repeated through every block (the giant step of
+ * ensi_ccmm_bsgs): slot x of Rot(w; e) holds V[g period + (x + e) mod period][i].  The weights are brought into the
+ * matching arrangement once, for all columns of V: diagonal e < period of a segment holds in slot x the entry of column
+ * (x + e) mod period, except in the block's last e slots, which diagonal period - 1 + e (e >= 1) holds, paired with
+ * Rot(w; e - period); zero elsewhere.  Baby and giant steps over the 2 period - 1 diagonals: a diagonal's rotation
+ * amount is e1 + t with 0 <= e1 < baby and t a multiple of baby; w is rotated by e1 only (one ModUp, baby - 1
+ * rotations), the diagonal is rotated by -t when it is formed, the products of all diagonals and segments that share
+ * t are added, relinearised and rescaled together, that sum is rotated by t, and out_i is the sum over t.
+ * ensi_diagonalise_weights: A holds n_seg * period columns (whole segments, in order); out[k (2 period - 1) + q] is
+ * diagonal q of segment k: plaintext products with ensi_segment_masks(s, period, limbs = l), summed and rescaled once,
+ * then rotated by -t; out: n_seg (2 period - 1) ciphertexts allocated at exactly l - 1 limbs.  prepare != 0 leaves out in
+ * the transform domain, where ensi_ccmm_av reads it in place for every column of V; such a batch is no ciphertext for
+ * any other entry point (export and decrypt refuse it).  gk: keys for the giant steps t and -t: +-baby k, k = 1 ..
+ * period / baby.
+ * ensi_ccmm_av: Ad from above (same period and baby) for the segments g0 .. g0 + n_seg - 1, at l - 1 limbs; V: m
+ * ciphertexts at l limbs (l >= 3); mask_head: ensi_block_head_mask(s, period, limbs = l); out: m ciphertexts at l - 2
+ * limbs.  gk: keys for the steps (g0 + k) period, ensi_fill_steps(period, s, -1), 1 .. baby - 1 and the giant steps.
+ * Two levels below V. */
+int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *A, int32_t s, int32_t period, int32_t baby,
+                             const ensi_pt *masks, int32_t prepare, ensi_ct *out, void *stream);
 int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
-                 int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream);
+                 int32_t baby, int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream);
 
 /* ---- transform alone (parity and measurement of the NTT kernels) -------- */
 /* data: device u64[n_limbs][N]; limb r uses prime index prime_idx[r] (host

@@ -816,9 +816,10 @@ class Oracle:
         V[g period + (x + e) mod period, i], which is what diagonal e of the weights multiplies in
         that slot; the last e slots of a block take Rot(w; e - period) and diagonal period - 1 + e.
         Baby steps and giant steps over the diagonals (diagonal_schedule): w is only rotated by e1 <
-        baby; the products whose diagonals share a giant step t are added, relinearised and rescaled
-        together and that sum is rotated by t; out_i is the sum over t.  Two levels (masks on both
-        operands, the product)."""
+        baby; the products whose diagonals share a giant step t are added and relinearised together,
+        that sum is rotated by t at the product's scale (a key switch after the rescale would add its
+        rounding to a ciphertext of scale Delta^2 / q_l, a thousand times less headroom), and out_i is
+        the sum over t, rescaled once.  Two levels (masks on both operands, the product)."""
         l1 = v_cts[0].l1
         mask_head = self.block_head_mask(s, period, l1)
         sched = self.diagonal_schedule(period, baby)
@@ -832,11 +833,12 @@ class Oracle:
                     groups.setdefault(t, []).append((ad[q], rot[e1]))
             acc = None
             for t in sorted(groups):
-                part = self.mult_sum_relin_rescale(groups[t], rk)
+                a0, b0 = groups[t][0]
+                part = self.relinearize(self.tensor_sum(groups[t]), rk, a0.scale * b0.scale)
                 if t:
                     part = self.rotate(part, gks[t])
                 acc = part if acc is None else self.add_ct(acc, part)
-            out.append(acc)
+            out.append(self.rescale(acc))
         return out
 
     # ------------------------- CCMM over heads, element extraction in baby steps and giant steps

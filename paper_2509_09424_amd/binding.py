@@ -355,18 +355,18 @@ class Context:
                                                ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
-    def diagonalise_weights(self, ct_a, s, period, masks, ct_out=None, prepare=False, stream=0):
+    def diagonalise_weights(self, gk, ct_a, s, period, baby, masks, ct_out=None, prepare=False, stream=0):
         if ct_out is None:
             ct_out = self.ct_alloc(ct_a.n // int(period) * (2 * int(period) - 1), ct_a.limbs - 1)
-        self._check(self.lib.ensi_diagonalise_weights(self.h, ct_a.h, int(s), int(period), masks.h, int(bool(prepare)), ct_out.h,
-                                                      ctypes.c_void_p(stream)))
+        self._check(self.lib.ensi_diagonalise_weights(self.h, gk.h, ct_a.h, int(s), int(period), int(baby), masks.h, int(bool(prepare)),
+                                                      ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
-    def ccmm_av(self, rk, gk, ct_ad, ct_v, s, period, g0, mask_head, ct_out=None, stream=0):
+    def ccmm_av(self, rk, gk, ct_ad, ct_v, s, period, baby, g0, mask_head, ct_out=None, stream=0):
         if ct_out is None:
             ct_out = self.ct_alloc(ct_v.n, ct_v.limbs - 2)
-        self._check(self.lib.ensi_ccmm_av(self.h, rk.h, gk.h, ct_ad.h, ct_v.h, int(s), int(period), int(g0), mask_head.h, ct_out.h,
-                                          ctypes.c_void_p(stream)))
+        self._check(self.lib.ensi_ccmm_av(self.h, rk.h, gk.h, ct_ad.h, ct_v.h, int(s), int(period), int(baby), int(g0), mask_head.h,
+                                          ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ntt(self, device_ptr, prime_idx, inverse=False, stream=0):

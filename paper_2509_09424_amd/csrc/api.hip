@@ -1633,12 +1633,14 @@ extern "C" int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs) {
 
 // out_o = Rescale(Relin(sum_{t in [begin[o], begin[o+1])} a_t (x) b_t)); operands have l1 limbs.  Outputs are
 // handled in groups of at most one rotation chunk whose operand polynomials fit a bounded workspace.
-// a_pre: the a operands already hold their transform (limb stride l1): they are read in place
+// a_pre: the a operands already hold their transform (limb stride l1): they are read in place.  rescale = false stops
+// after the relinearisation: the outputs keep l1 limbs and the product's scale.
 static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &terms, const std::vector<int32_t> &begin, int l1,
-                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st, bool a_pre = false) {
+                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st, bool a_pre = false, bool rescale = true) {
     const int N = ctx->N, n_out = (int)begin.size() - 1, ext = l1 + ctx->K;
     if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ciphertext multiplication: no limb left to drop");
-    if (out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the operands (%d vs %d limbs)", out->limbs, l1);
+    if (out->limbs != (rescale ? l1 - 1 : l1))
+        ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be %s the operands (%d vs %d limbs)", rescale ? "one level below" : "at the level of", out->limbs, l1);
     if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_out);
     for (int o = 0; o < n_out; o++)
         if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
@@ -1727,6 +1729,7 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
         g.n_ops = n_gather[k];
         g.n_out = cnt;
         g.l1 = l1;
+        g.limbs_out = rescale ? l1 - 1 : l1;
         g.ws_a = ctx->ws_ma;
         g.ws_d = ctx->ws_md;
         g.ws_e = ctx->ws_me;
@@ -1749,7 +1752,7 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
         if ((rc = raise_cts(ctx, l1, ctx->ws_md, (size_t)3 * l1 * N, l1, cnt, st))) return rc;
         if ((rc = run_rotations(ctx, ctx->ws_desc, cnt, l1, l1, l1, st))) return rc;
         launch_mm_add_d1(ctx, g, st);
-        launch_rescale(ctx, ctx->ws_me, cnt, l1, l1, d_consts, fp ? d_fconsts : nullptr, st);
+        if (rescale) launch_rescale(ctx, ctx->ws_me, cnt, l1, l1, d_consts, fp ? d_fconsts : nullptr, st);
         launch_mm_scatter(ctx, g, st);
     }
     ENSI_HIP(ctx, hipGetLastError());
@@ -2492,32 +2495,47 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
 }
 
 // ------------- CCMM, several heads per ciphertext: weights times V from diagonalised weights
-extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t s, int32_t period, const ensi_pt *masks, int32_t prepare,
-                                        ensi_ct *out, void *stream) {
-    if (!ctx || !A || !masks || !out) return ENSI_E_BADARG;
+// Baby and giant steps over the 2P - 1 diagonals of a segment: diagonal q has rotation amount q (q < P) or q - 2P + 1
+// (the one used in the last slots of a block) = e1 + t with 0 <= e1 < baby and t a multiple of baby.
+static void diagonal_schedule(int P, int baby, std::vector<int> &e1, std::vector<int> &t) {
+    e1.resize(2 * P - 1);
+    t.resize(2 * P - 1);
+    for (int q = 0; q < 2 * P - 1; q++) {
+        const int amount = q < P ? q : q - 2 * P + 1;
+        e1[q] = ((amount % baby) + baby) % baby;
+        t[q] = amount - e1[q];
+    }
+}
+
+extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *A, int32_t s, int32_t period, int32_t baby,
+                                        const ensi_pt *masks, int32_t prepare, ensi_ct *out, void *stream) {
+    if (!ctx || !gk || !A || !masks || !out) return ENSI_E_BADARG;
     if (A->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the weights are already prepared");
     const int N = ctx->N, P = period, l1 = A->limbs;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "the period must be a power of two up to the block length");
+    if (baby < 1 || (baby & (baby - 1)) || baby > P) ENSI_FAIL(ctx, ENSI_E_BADARG, "the baby-step range must be a power of two up to the period");
     if (A->n < P || A->n % P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "the weights come in whole segments of %d columns, got %d", P, A->n);
-    const int n_seg = A->n / P, n_diag = 2 * P - 1;
-    if (l1 < 2 || out->limbs != l1 - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input");
+    const int n_seg = A->n / P, n_diag = 2 * P - 1, l2 = l1 - 1;
+    if (l1 < 2 || out->limbs != l2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input");
+    if (out->limbs_alloc != l2) ENSI_FAIL(ctx, ENSI_E_SHAPE, "the output batch must be allocated at %d limbs", l2);
     if (out->n != n_seg * n_diag) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_seg * n_diag);
     if (masks->n < 3 * P || masks->limbs < l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "need %d sorting masks at %d limbs", 3 * P, l1);
     if (A->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "in and out must not overlap");
-    const size_t a_ct = (size_t)2 * A->limbs_alloc * N;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, d_ct = (size_t)2 * l2 * N;
     std::vector<PmTerm> pt;
     std::vector<int32_t> pb(1, 0);
     for (int g = 0; g < n_seg; g++) {
         const u64 *col = A->d + (size_t)g * P * a_ct;
-        for (int e = 0; e < P; e++) {  // entry e: column (x + e) mod P in slot x, without the block's last e slots
+        for (int e = 0; e < P; e++) {  // diagonal e: column (x + e) mod P in slot x, without the block's last e slots
             for (int c = 0; c < P; c++) {
                 const int r = ((c - e) % P + P) % P;
                 pt.push_back({col + (size_t)c * a_ct, (e && r >= P - e) ? P + r : r, 0});
             }
             pb.push_back((int32_t)pt.size());
         }
-        for (int e = 1; e < P; e++) {  // entry P - 1 + e: the same column in those last e slots
+        for (int e = 1; e < P; e++) {  // diagonal P - 1 + e: the same column in those last e slots
             for (int c = 0; c < P; c++) {
                 const int r = ((c - e) % P + P) % P;
                 if (r >= P - e) pt.push_back({col + (size_t)c * a_ct, 2 * P + r, 0});
@@ -2526,13 +2544,23 @@ extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t
         }
     }
     int rc;
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, (size_t)out->n * d_ct))) return rc;
+    ensi_ct tmp = *out;
+    tmp.owns = false;
+    tmp.prepared = false;
+    tmp.d = ctx->ws_rot;
     out->prepared = false;
-    if ((rc = pmult_core(ctx, pt, pb, l1, A->limbs_alloc, masks, out, (hipStream_t)stream))) return rc;
+    if ((rc = pmult_core(ctx, pt, pb, l1, A->limbs_alloc, masks, &tmp, st))) return rc;
     out->scale = A->scale * masks->scale / (double)ctx->primes[l1 - 1];
+    // every diagonal moves by minus its giant step
+    std::vector<int> e1, t;
+    diagonal_schedule(P, baby, e1, t);
+    std::vector<RotJob> jobs(out->n);
+    for (int k = 0; k < out->n; k++) jobs[k] = {k, -t[k % n_diag], out->d + (size_t)k * d_ct};
+    if ((rc = rotate_jobs(ctx, gk, tmp.d, d_ct, l2, out->n, l2, jobs, st))) return rc;
     if (prepare) {
         // left in the transform domain, where every column of V multiplies it: ensi_ccmm_av reads it in place
-        if (out->limbs_alloc != out->limbs) ENSI_FAIL(ctx, ENSI_E_SHAPE, "prepared weights need a batch allocated at %d limbs", out->limbs);
-        launch_ntt(ctx, out->d, out->n * 2 * out->limbs, make_map(ctx, out->limbs, false), false, (hipStream_t)stream);
+        launch_ntt(ctx, out->d, out->n * 2 * l2, make_map(ctx, l2, false), false, st);
         out->prepared = true;
     }
     ENSI_HIP(ctx, hipGetLastError());
@@ -2540,11 +2568,12 @@ extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_ct *A, int32_t
 }
 
 extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
-                            int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream) {
+                            int32_t baby, int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !Ad || !V || !mask_head || !out) return ENSI_E_BADARG;
     const int N = ctx->N, P = period, l1 = V->limbs, m = V->n;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
+    if (baby < 1 || (baby & (baby - 1)) || baby > P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the baby-step range must be a power of two up to the period");
     const int n_diag = 2 * P - 1;
     if (Ad->n < n_diag || Ad->n % n_diag) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: the diagonalised weights come %d to a segment, got %d", n_diag, Ad->n);
     const int n_seg = Ad->n / n_diag;
@@ -2553,19 +2582,25 @@ extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk,
     if (out->limbs != l1 - 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be two levels below V");
     if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, m);
     if (mask_head->n < 1 || mask_head->limbs < l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the head mask needs %d limbs", l1);
-    if ((size_t)n_seg * n_diag > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d segments give more than 65535 products per output", n_seg);
+    if ((size_t)n_seg * n_diag > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: %d segments give more than 65535 products per sum", n_seg);
     if (Ad->d == out->d || V->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
     hipStream_t st = (hipStream_t)stream;
     const u64 *key;
     int rc;
     if ((rc = relin_key(ctx, rk, &key))) return rc;
-    const int l2 = l1 - 1;
+    const int l2 = l1 - 1, l3 = l1 - 2;
     const size_t ad_ct = (size_t)2 * Ad->limbs_alloc * N, seg_ct = (size_t)2 * l2 * N, out_ct = (size_t)2 * out->limbs_alloc * N;
-    // outputs whose rotated operands are held at once (an output's products are relinearised together)
-    const int per = std::max(1, 1536 / (n_seg * std::max(1, n_diag - 1)));
-    const size_t n_rot = (size_t)std::min(per, m) * n_seg * (n_diag - 1), n_sg = (size_t)std::min(per, m) * n_seg;
-    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max(n_sg * 2 * l1 * N, std::max<size_t>(n_rot, 1) * seg_ct)))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, n_sg * seg_ct))) return rc;
+    std::vector<int> e1, t;
+    diagonal_schedule(P, baby, e1, t);
+    std::vector<int> giant(t);  // the distinct giant steps, ascending
+    std::sort(giant.begin(), giant.end());
+    giant.erase(std::unique(giant.begin(), giant.end()), giant.end());
+    const int nT = (int)giant.size();
+    // outputs whose rotated operands are held at once
+    const int per = std::max(1, std::min(m, 1536 / (n_seg * std::max(1, baby - 1))));
+    const size_t n_sg = (size_t)per * n_seg, n_rot = n_sg * (baby - 1), n_sum = (size_t)per * nT;
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max(n_sg * 2 * l1 * N, std::max(std::max<size_t>(n_rot, 1), n_sum) * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (n_sg + n_sum) * seg_ct))) return rc;
     for (int i0 = 0; i0 < m; i0 += per) {
         const int cnt = std::min(per, m - i0);
         ensi_ct seg;
@@ -2578,34 +2613,61 @@ extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk,
         for (int i = 0; i < cnt; i++)
             for (int k = 0; k < n_seg; k++) segs.push_back({i0 + i, g0 + k});
         if ((rc = spread_segments(ctx, gk, V, segs, s, P, mask_head, &seg, st))) return rc;
-        // diagonal k < P pairs with the spread rotated by k, diagonal P - 1 + e with the spread rotated by e - P
+        // baby steps: every spread operand rotated by 1 .. baby - 1 on one raise
         std::vector<RotJob> jobs;
+        for (int sg = 0; sg < cnt * n_seg; sg++)
+            for (int b = 1; b < baby; b++) jobs.push_back({sg, b, ctx->ws_rot + ((size_t)sg * (baby - 1) + (b - 1)) * seg_ct});
+        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, cnt * n_seg, l2, jobs, st))) return rc;
+        // one sum per output and giant step: the products of all segments' diagonals that share it
         std::vector<MmTerm> terms;
         std::vector<int32_t> begin(1, 0);
-        for (int i = 0; i < cnt; i++) {
-            for (int k = 0; k < n_seg; k++) {
-                const int sg = i * n_seg + k;
-                const u64 *w = seg.d + (size_t)sg * seg_ct;
-                for (int q = 0; q < n_diag; q++) {
-                    const int am = q < P ? q : q - 2 * P + 1;
-                    const u64 *b = w;
-                    if (am) {
-                        u64 *dst = ctx->ws_rot + ((size_t)sg * (n_diag - 1) + (q - 1)) * seg_ct;
-                        jobs.push_back({sg, am, dst});
-                        b = dst;
+        for (int i = 0; i < cnt; i++)
+            for (int g = 0; g < nT; g++) {
+                for (int k = 0; k < n_seg; k++) {
+                    const int sg = i * n_seg + k;
+                    for (int q = 0; q < n_diag; q++) {
+                        if (t[q] != giant[g]) continue;
+                        const u64 *b = e1[q] ? ctx->ws_rot + ((size_t)sg * (baby - 1) + (e1[q] - 1)) * seg_ct : seg.d + (size_t)sg * seg_ct;
+                        terms.push_back({Ad->d + ((size_t)k * n_diag + q) * ad_ct, b});
                     }
-                    terms.push_back({Ad->d + ((size_t)k * n_diag + q) * ad_ct, b});
                 }
+                begin.push_back((int32_t)terms.size());
             }
-            begin.push_back((int32_t)terms.size());
+        // relinearised, not yet rescaled: the giant steps act at the product's scale
+        ensi_ct sums = seg;
+        sums.n = cnt * nT;
+        sums.limbs = sums.limbs_alloc = l2;
+        sums.d = ctx->ws_rep + n_sg * seg_ct;
+        sums.scale = Ad->scale * seg.scale;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, Ad->limbs_alloc, l2, &sums, st, Ad->prepared, false))) return rc;
+        // giant steps: every sum rotated by its own (the rotated baby steps are no longer needed), added up per output
+        // in the slot of the output's first sum, rescaled once
+        jobs.clear();
+        for (int i = 0; i < cnt; i++)
+            for (int g = 0; g < nT; g++)
+                if (giant[g]) jobs.push_back({i * nT + g, giant[g], ctx->ws_rot + ((size_t)i * nT + g) * seg_ct});
+        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, sums.d, seg_ct, l2, cnt * nT, l2, jobs, st))) return rc;
+        const u64 *d_consts;
+        const double *d_fconsts;
+        bool fp;
+        if ((rc = upload_rescale_consts(ctx, l2, 1.0, false, st, &d_consts, &d_fconsts, &fp))) return rc;
+        for (int i = 0; i < cnt; i++) {
+            // the sum with giant step 0 stays where it is and collects the others; if there is none, the first rotated one does
+            int home = -1;
+            for (int g = 0; g < nT; g++)
+                if (!giant[g]) home = g;
+            u64 *acc = home >= 0 ? sums.d + ((size_t)i * nT + home) * seg_ct : ctx->ws_rot + (size_t)i * nT * seg_ct;
+            for (int g = 0; g < nT; g++) {
+                if (g == (home >= 0 ? home : 0)) continue;
+                launch_ct_add(ctx, acc, l2, ctx->ws_rot + ((size_t)i * nT + g) * seg_ct, l2, l2, 1, st);
+            }
+            launch_rescale(ctx, acc, 1, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+            u64 *dst = out->d + (size_t)(i0 + i) * out_ct;
+            for (int poly = 0; poly < 2; poly++)
+                ENSI_HIP(ctx, hipMemcpyAsync(dst + (size_t)poly * out->limbs_alloc * N, acc + (size_t)poly * l2 * N, (size_t)l3 * N * 8,
+                                             hipMemcpyDeviceToDevice, st));
         }
-        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, (int)segs.size(), l2, jobs, st))) return rc;
-        ensi_ct part = *out;
-        part.owns = false;
-        part.d = out->d + (size_t)i0 * out_ct;
-        part.n = cnt;
-        if ((rc = mult_core(ctx, key, terms, begin, l2, Ad->limbs_alloc, l2, &part, st, Ad->prepared))) return rc;
-        out->scale = Ad->scale * seg.scale / (double)ctx->primes[l2 - 1];
+        out->scale = sums.scale / (double)ctx->primes[l2 - 1];
     }
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;

@@ -70,11 +70,11 @@ __global__ __launch_bounds__(MM_THREADS) void k_ct_add(u64 *a, int stride_a, con
     *x = add_mod(*x, b[((size_t)c * 2 * stride_b + (size_t)p * stride_b + i) * N + idx], pcs[i].q);
 }
 
-// grid (ceil(N/256), 2*(l1-1), n_out): the rescaled limbs of ws_e (limb stride l1) to the output ciphertexts
+// grid (ceil(N/256), 2*limbs_out, n_out): the first limbs_out limbs of ws_e (limb stride l1) to the output ciphertexts
 __global__ __launch_bounds__(MM_THREADS) void k_mm_scatter(MmGroup g, int N) {
     const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
     if (idx >= N) return;
-    const int lo = g.l1 - 1;
+    const int lo = g.limbs_out;
     const int y = blockIdx.y, c = y / lo, i = y - c * lo, o = blockIdx.z;
     g.out[(size_t)o * g.out_stride + ((size_t)c * g.limb_stride_out + i) * N + idx] = g.ws_e[((size_t)o * 2 * g.l1 + c * g.l1 + i) * N + idx];
 }
@@ -125,5 +125,5 @@ void launch_ct_add(ensi_ctx *ctx, u64 *a, int stride_a, const u64 *b, int stride
 void launch_mm_scatter(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
     const int N = ctx->N, nb = (N + MM_THREADS - 1) / MM_THREADS;
     ScopedTimer t(ctx, "mm_scatter", st);
-    hipLaunchKernelGGL(k_mm_scatter, dim3(nb, 2 * (g.l1 - 1), g.n_out), dim3(MM_THREADS), 0, st, g, N);
+    hipLaunchKernelGGL(k_mm_scatter, dim3(nb, 2 * g.limbs_out, g.n_out), dim3(MM_THREADS), 0, st, g, N);
 }

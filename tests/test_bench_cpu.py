@@ -76,4 +76,5 @@ def test_segment_form_counts():
     assert abs(roof["achieved"] - 4 * ((96 + 96 * 31) * 2 * 15 + 31 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
     w = wl.BY_NAME["ccmmavseg"]  # one column of V, 32 segments
     _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
-    assert abs(roof["achieved"] - (1 * 2 * 16 + (32 * 5 + 1) * 2 * 15) * unit / 1e-3 / 1e9) < 1e-6
+    # raises: the column at 16 limbs; per segment 4 fill groups and one for its baby steps, and the 8 relinearisations, at 15; 7 giant steps at 14
+    assert abs(roof["achieved"] - (1 * 2 * 16 + (32 * 5 + 8) * 2 * 15 + 7 * 2 * 14) * unit / 1e-3 / 1e9) < 1e-6

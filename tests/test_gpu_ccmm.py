@@ -506,14 +506,15 @@ def test_ccmm_segment_at_the_benchmark_parameters():
 
 
 # ------------------------------------------------ weights times V from diagonalised weights
-def av_case(p, l1, s, period, g0, n_seg, m):
+def av_case(p, l1, s, period, baby, g0, n_seg, m):
     heads = p.n // s
     lo, hi = g0 * period, (g0 + n_seg) * period
     Wt = p.rng.uniform(-1, 1, (heads, s, s)) / 8
     V = p.rng.uniform(-1, 1, (heads, s, m))
     o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Wt[h][:, j] for h in range(heads)]) for j in range(lo, hi)]), l1)
     o_v, g_v = p.encrypt_both(np.stack([np.concatenate([V[h][:, i] for h in range(heads)]) for i in range(m)]), l1)
-    steps = set(range(1, period)) | set(range(1 - period, 0)) | {(g0 + k) * period for k in range(n_seg)} | set(p.ctx.fill_steps(period, s, -1))
+    giant = {k * baby for k in range(1, period // baby + 1)}
+    steps = set(range(1, baby)) | giant | {-t for t in giant} | {(g0 + k) * period for k in range(n_seg)} | set(p.ctx.fill_steps(period, s, -1))
     o_gks, g_gk = p.galois_keys(sorted(st for st in steps if st))
     mh = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.block_head_mask(s, period, l1)[None, :], l1), float(p.pr.q[l1 - 1]))
     ms = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.segment_masks(s, period, l1), l1), float(p.pr.q[l1 - 1]))
@@ -521,62 +522,64 @@ def av_case(p, l1, s, period, g0, n_seg, m):
     return o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref
 
 
-@pytest.mark.parametrize("params,l1,s,period,g0,n_seg,m", [(SMALL4, 5, 32, 4, 0, 8, 2), (SMALL4, 4, 64, 8, 2, 3, 3), (WIDE, 4, 128, 16, 5, 2, 1)],
-                         ids=["whole-block", "some-segments", "wide-primes"])
-def test_ccmm_av_small_ring(params, l1, s, period, g0, n_seg, m):
+@pytest.mark.parametrize("params,l1,s,period,baby,g0,n_seg,m", [(SMALL4, 5, 32, 4, 2, 0, 8, 2), (SMALL4, 4, 64, 8, 8, 2, 3, 3),
+                                                                (SMALL4, 4, 64, 8, 1, 1, 2, 1), (WIDE, 4, 128, 16, 4, 5, 2, 1)],
+                         ids=["whole-block", "some-segments-baby-steps-only", "giant-steps-only", "wide-primes"])
+def test_ccmm_av_small_ring(params, l1, s, period, baby, g0, n_seg, m):
     """Diagonalised weights and the weights-times-V product: bit-exact against the oracle, numpy after decryption;
     the library's own masks give the same product within the bound."""
     p = Pair(params)
-    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, g0, n_seg, m)
+    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, baby, g0, n_seg, m)
     o_rk, g_rk = relin_keys(p)
-    ad = p.ctx.diagonalise_weights(g_a, s, period, ms)
-    o_ad = [p.o.diagonalise_weights(o_a[k * period:(k + 1) * period], s, period) for k in range(n_seg)]
+    ad = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms)
+    o_ad = [p.o.diagonalise_weights(o_a[k * period:(k + 1) * period], s, period, baby, o_gks) for k in range(n_seg)]
     assert ad.n == n_seg * (2 * period - 1) and ad.limbs == l1 - 1
     assert np.array_equal(ad.export(), stack_cts([c for seg in o_ad for c in seg]))
-    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, g0, mh)
-    want = p.o.ccmm_av(o_ad, o_v, s, period, g0, o_rk, o_gks)
+    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, baby, g0, mh)
+    want = p.o.ccmm_av(o_ad, o_v, s, period, baby, g0, o_rk, o_gks)
     assert out.n == m and out.limbs == l1 - 2
     assert np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
     # the weights left in the transform domain: the same words come out
-    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)
-    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    adp = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms, prepare=True)
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, baby, g0, mh)
     assert np.array_equal(outp.export(), stack_cts(want))
     with pytest.raises(p.binding.EnsiError, match="code -1"):
         adp.export()
     adp.free()
     outp.free()
     lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.segment_masks(s, period, l1)
-    ad2 = p.ctx.diagonalise_weights(g_a, s, period, ls)
-    out2 = p.ctx.ccmm_av(g_rk, g_gk, ad2, g_v, s, period, g0, lh)
+    ad2 = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ls)
+    out2 = p.ctx.ccmm_av(g_rk, g_gk, ad2, g_v, s, period, baby, g0, lh)
     assert np.abs(p.ctx.decrypt(p.g_sk, out2) - ref).max() < 1e-3
     with pytest.raises(p.binding.EnsiError, match="code -1"):
-        p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, s // period - n_seg + 1, mh, out2)  # last segment outside the block
+        p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, baby, s // period - n_seg + 1, mh, out2)  # last segment outside the block
     shallow = p.ctx.ct_alloc(m, l1 - 1)
     with pytest.raises(p.binding.EnsiError, match="code -3"):
-        p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, g0, mh, shallow)  # output one level below V instead of two
+        p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, baby, g0, mh, shallow)  # output one level below V instead of two
     with pytest.raises(p.binding.EnsiError, match="code -4"):
-        p.ctx.diagonalise_weights(g_a, s, period, ms, shallow)  # output batch of the wrong size
+        p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms, shallow)  # output batch of the wrong size
     for h in (g_a, g_v, mh, ms, lh, ls, ad, ad2, out, out2, shallow, g_gk, g_rk):
         h.free()
     p.close()
 
 
 def test_ccmm_av_full_ring():
-    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 4, two segments in the middle of the block, a low level."""
+    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 4 in baby steps of 2, two segments in the middle of the
+    block, a low level."""
     p = Pair(KEYSWITCH)
-    l1, s, period, g0, n_seg, m = 4, 2048, 4, 100, 2, 1
-    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, g0, n_seg, m)
+    l1, s, period, baby, g0, n_seg, m = 4, 2048, 4, 2, 100, 2, 1
+    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, baby, g0, n_seg, m)
     o_rk, g_rk = relin_keys(p)
-    ad = p.ctx.diagonalise_weights(g_a, s, period, ms)
-    o_ad = [p.o.diagonalise_weights(o_a[k * period:(k + 1) * period], s, period) for k in range(n_seg)]
+    ad = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms)
+    o_ad = [p.o.diagonalise_weights(o_a[k * period:(k + 1) * period], s, period, baby, o_gks) for k in range(n_seg)]
     assert np.array_equal(ad.export(), stack_cts([c for seg in o_ad for c in seg]))
-    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, g0, mh)
-    want = p.o.ccmm_av(o_ad, o_v, s, period, g0, o_rk, o_gks)
+    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, baby, g0, mh)
+    want = p.o.ccmm_av(o_ad, o_v, s, period, baby, g0, o_rk, o_gks)
     assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
-    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)  # weights left in the transform domain
-    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    adp = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms, prepare=True)  # weights left in the transform domain
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, baby, g0, mh)
     assert np.array_equal(outp.export(), stack_cts(want))
     for h in (g_a, g_v, mh, ms, ad, adp, out, outp, g_gk, g_rk):
         h.free()
@@ -584,21 +587,22 @@ def test_ccmm_av_full_ring():
 
 
 def test_ccmm_av_at_the_benchmark_parameters():
-    """The 16 + 4 limb chain, the 16 x 2048 packing and the period 16 of the benchmark workload on one segment."""
+    """The 16 + 4 limb chain, the 16 x 2048 packing, the period 16 and the baby steps of 4 of the benchmark workload on
+    one segment."""
     w = wl.BY_NAME["ccmmqk"]
     p = Pair(w.param_tuple())
-    l1, s, period, g0, n_seg, m = p.pr.L, w.tokens, 16, 127, 1, 1
-    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, g0, n_seg, m)
+    l1, s, period, baby, g0, n_seg, m = p.pr.L, w.tokens, 16, 4, 127, 1, 1
+    o_a, g_a, o_v, g_v, o_gks, g_gk, mh, ms, ref = av_case(p, l1, s, period, baby, g0, n_seg, m)
     o_rk, g_rk = relin_keys(p)
-    ad = p.ctx.diagonalise_weights(g_a, s, period, ms)
-    o_ad = [p.o.diagonalise_weights(o_a, s, period)]
+    ad = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms)
+    o_ad = [p.o.diagonalise_weights(o_a, s, period, baby, o_gks)]
     assert np.array_equal(ad.export(), stack_cts(o_ad[0]))
-    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, g0, mh)
-    want = p.o.ccmm_av(o_ad, o_v, s, period, g0, o_rk, o_gks)
+    out = p.ctx.ccmm_av(g_rk, g_gk, ad, g_v, s, period, baby, g0, mh)
+    want = p.o.ccmm_av(o_ad, o_v, s, period, baby, g0, o_rk, o_gks)
     assert out.limbs == l1 - 2 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
-    adp = p.ctx.diagonalise_weights(g_a, s, period, ms, prepare=True)  # weights left in the transform domain
-    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, g0, mh)
+    adp = p.ctx.diagonalise_weights(g_gk, g_a, s, period, baby, ms, prepare=True)
+    outp = p.ctx.ccmm_av(g_rk, g_gk, adp, g_v, s, period, baby, g0, mh)
     assert np.array_equal(outp.export(), stack_cts(want))
     for h in (g_a, g_v, mh, ms, ad, adp, out, outp, g_gk, g_rk):
         h.free()
