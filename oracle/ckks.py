@@ -735,37 +735,6 @@ class Oracle:
                 terms.append((e, False, r))
         return terms
 
-    def ccmm_segment(self, a_cts, b_cts, s, period, g, rk, gks):
-        """CCMM section, several heads per ciphertext, the `period` output columns g period ..
-        (g+1) period - 1 of C_h = A_h B_h at once (the Q K^T form: ciphertext j of B holds B_h[j, i] in
-        slot h s + i).  The replication of an element stops at the giant step: w_j = the segment of b_j
-        repeated through every block (spread_segment).  Then Rot(w_j; e) puts, in slot x, element
-        (x + e) mod period of the segment, so D_e = Rescale(Relin(sum_j a_j (x) Rot(w_j; e))) holds in
-        slot x the entry of output column (x + e) mod period: the period diagonals hold all entries of
-        the period columns.  A rotation by e reads past the block's end in its last e slots; there
-        D'_e, built with Rot(w_j; e - period), holds the same entries.  One more plaintext product
-        sorts them: column c = Rescale(sum_e mask (.) D_e [+ mask' (.) D'_e]) (segment_mask_terms).
-        Three levels (head mask, product, sorting masks); per segment 2 period - 1 rotations per
-        ciphertext of B (one ModUp) instead of `period` extractions with their own fills."""
-        l1 = b_cts[0].l1
-        mask_head = self.block_head_mask(s, period, l1)
-        w = [self.spread_segment(b, g, s, period, mask_head, gks) for b in b_cts]
-        a2 = [self.drop_limbs(a, l1 - 1) for a in a_cts]
-        diag, diag_p = [], [None]
-        for e in range(period):
-            rot = [self.rotate(wj, gks[e]) for wj in w] if e else w
-            diag.append(self.mult_sum_relin_rescale(list(zip(a2, rot)), rk))
-            if e:
-                rot = [self.rotate(wj, gks[e - period]) for wj in w]
-                diag_p.append(self.mult_sum_relin_rescale(list(zip(a2, rot)), rk))
-        masks = self.segment_masks(s, period, l1 - 2)
-        q = self.pr.q[:l1 - 2]
-        out = []
-        for c in range(period):
-            terms = [((diag_p if primed else diag)[e], self.i64_to_rns(masks[mi], q)) for e, primed, mi in self.segment_mask_terms(period, c)]
-            out.append(self.pmult_sum_rescale(terms, float(self.pr.q[l1 - 3])))
-        return out
-
     @staticmethod
     def diagonal_schedule(period, baby):
         """Baby steps and giant steps over the diagonals of a segment: diagonal q (q < period: rotation
@@ -778,6 +747,47 @@ class Oracle:
             amount = q if q < period else q - 2 * period + 1
             e1 = amount % baby
             out.append((e1, amount - e1))
+        return out
+
+    def ccmm_segment(self, a_cts, b_cts, s, period, baby, g, rk, gks):
+        """CCMM section, several heads per ciphertext, the `period` output columns g period ..
+        (g+1) period - 1 of C_h = A_h B_h at once (the Q K^T form: ciphertext j of B holds B_h[j, i] in
+        slot h s + i).  The replication of an element stops at the giant step: w_j = the segment of b_j
+        repeated through every block (spread_segment).  Then Rot(w_j; e) puts, in slot x, element
+        (x + e) mod period of the segment, so D_e = sum_j a_j (x) Rot(w_j; e) holds in slot x the
+        entry of output column (x + e) mod period: the period diagonals hold all entries of the
+        period columns.  A rotation by e reads past the block's end in its last e slots; there
+        D'_e, built with Rot(w_j; e - period), holds the same entries.  Baby and giant steps over the
+        diagonals (diagonal_schedule, amount = e1 + t): w_j is rotated by e1 < baby only, a_j by -t,
+        and the relinearised sum of their products by t, at the product's scale, before its rescale.
+        One more plaintext product sorts the diagonals: column c = Rescale(sum_e mask (.) D_e [+ mask'
+        (.) D'_e]) (segment_mask_terms).  Three levels (head mask, product, sorting masks)."""
+        l1 = b_cts[0].l1
+        mask_head = self.block_head_mask(s, period, l1)
+        w = [self.spread_segment(b, g, s, period, mask_head, gks) for b in b_cts]
+        a2 = [self.drop_limbs(a, l1 - 1) for a in a_cts]
+        sched = self.diagonal_schedule(period, baby)
+        w_rot = {0: w}
+        a_rot = {0: a2}
+        for e1, t in sched:
+            if e1 not in w_rot:
+                w_rot[e1] = [self.rotate(wj, gks[e1]) for wj in w]
+            if t not in a_rot:
+                a_rot[t] = [self.rotate(aj, gks[-t]) for aj in a2]
+        d_all = []
+        for e1, t in sched:
+            pairs = list(zip(a_rot[t], w_rot[e1]))
+            part = self.relinearize(self.tensor_sum(pairs), rk, pairs[0][0].scale * pairs[0][1].scale)
+            if t:
+                part = self.rotate(part, gks[t])
+            d_all.append(self.rescale(part))
+        diag, diag_p = d_all[:period], [None] + d_all[period:]
+        masks = self.segment_masks(s, period, l1 - 2)
+        q = self.pr.q[:l1 - 2]
+        out = []
+        for c in range(period):
+            terms = [((diag_p if primed else diag)[e], self.i64_to_rns(masks[mi], q)) for e, primed, mi in self.segment_mask_terms(period, c)]
+            out.append(self.pmult_sum_rescale(terms, float(self.pr.q[l1 - 3])))
         return out
 
     def diagonalise_weights(self, a_cts, s, period, baby, gks):

@@ -612,7 +612,7 @@ def test_segment_of_columns_from_diagonals():
     a_cts = [_enc(o, rng, pk, np.concatenate([Q[h][:, j] for h in range(heads)]), l1) for j in range(d)]
     b_cts = [_enc(o, rng, pk, np.concatenate([K[h][:, j] for h in range(heads)]), l1) for j in range(d)]
     beta = pr.beta(pr.L)
-    steps = set(range(1, period)) | set(range(1 - period, 0)) | {g * period for g in range(1, s // period)}
+    steps = set(range(1, period)) | set(range(-period, 0)) | {period} | {g * period for g in range(1, s // period)}
     steps |= {st for grp in Oracle.fill_steps(period, s, -1) for st in grp}
     gks = {st: o.galois_keygen(sk, st, wl.error_poly(rng, (beta, o.N)), 109) for st in sorted(steps)}
     rk = o.relin_keygen(sk, wl.error_poly(rng, (beta, o.N)), 113)
@@ -631,8 +631,8 @@ def test_segment_of_columns_from_diagonals():
             sel = dec[mi][:s] > 0
             assert np.all((x[sel] + e) % period == c)               # the diagonal holds column c there
             assert np.all(x[sel] + e >= s if primed else x[sel] + e < s)  # and the rotation it was built with stays inside the block
-    for g in (0, 2, 3):
-        C = o.ccmm_segment(a_cts, b_cts, s, period, g, rk, gks)
+    for g, baby in ((0, 4), (2, 2), (3, 1)):
+        C = o.ccmm_segment(a_cts, b_cts, s, period, baby, g, rk, gks)
         assert len(C) == period and all(c.l1 == l1 - 3 for c in C)
         for c in range(period):
             ref = np.concatenate([S[h][:, g * period + c] for h in range(heads)])
