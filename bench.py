@@ -186,9 +186,11 @@ class Runner:
             slots = sorted({t[2] for tl in self.terms for t in tl})
             steps = {x // P * P for x in slots} | set(self.ctx.fill_steps(P, sl, -1))
             if w.op == "ccmm_segment":
-                # the whole segment 1 from its diagonals: rotations by 1 .. P-1 and -(P-1) .. -1 of the spread operands
+                # the whole segment 1 from its diagonals, in baby steps of the spread operands and giant steps of the columns of Q
                 assert m == P
-                steps |= set(range(1, P)) | set(range(1 - P, 0))
+                self.baby = 4
+                giant = {k * self.baby for k in range(1, P // self.baby + 1)}
+                steps |= set(range(1, self.baby)) | giant | {-t for t in giant}
                 self.pt2 = self.ctx.segment_masks(sl, P, self.L - 2)
             else:
                 steps |= {x % P for x in slots} | set(self.ctx.fill_steps(1, P, -1))
@@ -263,7 +265,7 @@ class Runner:
             self.ctx.ccmm_av(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.baby, 0, self.pt, self.ct_out)
             return
         if w.op == "ccmm_segment":
-            self.ctx.ccmm_segment(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, 1, self.pt, self.pt2, self.ct_out)
+            self.ctx.ccmm_segment(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.baby, 1, self.pt, self.pt2, self.ct_out)
             return
         self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
         if w.d_mid:
@@ -440,15 +442,18 @@ def roofline_for(w, prof):
         # per ciphertext of B: one giant step (aligning rotation at the top level, head mask, fill over the block one level
         # down) and 2P-2 rotations of the spread operand on one raise; 2P-1 relinearisations two levels down; the sorting
         # products of the 2P-1 diagonals into P columns
-        P, dd = w.period, w.d_in
+        P, dd, baby = w.period, w.d_in, 4
         g_rot, g_raise = fill_counts(P, w.tokens)
-        n_diag = 2 * P - 1
+        n_diag, n_t = 2 * P - 1, 2 * P // baby
         ks.append((L, dd, dd, dd, -(-dd // 16)))
-        ks.append((L - 1, dd * g_rot + dd * (n_diag - 1) + n_diag, dd * (g_raise + 1) + n_diag, dd * g_raise + dd * (n_diag - 1) + n_diag,
-                   g_rot * -(-dd // 64) + (n_diag - 1) * -(-dd // 16) + 1))
+        # one level down: the fills, the baby steps of the spread operands and the giant steps of the columns of Q on one raise
+        # each, the relinearisations, the giant steps of the sums that have one
+        n_rs = n_diag - baby
+        ks.append((L - 1, dd * (g_rot + baby - 1 + n_t - 1) + n_diag + n_rs, dd * (g_raise + 2) + n_diag + n_rs,
+                   dd * (g_raise + baby - 1 + n_t - 1) + n_diag + n_rs, g_rot * -(-dd // 64) + (baby - 1 + n_t - 1) * -(-dd // 16) + 1 + n_rs))
         pm.append((L, dd, dd))
         pm.append((L - 2, P * P + P * (P - 1) // 2, P))
-        mm.append((L - 1, dd + dd * n_diag, n_diag))
+        mm.append((L - 1, dd * (baby + n_t), n_diag))
     else:
         n_in = -(-w.d_in // w.c_tot)
         # the packed inputs (up to 16) are rotated together, so a key is read once per rotation amount
@@ -591,7 +596,7 @@ def cpu_baseline(w, budget_s=12.0):
             n_pm = n_sg
         elif w.op == "ccmm_segment":
             n_diag = 2 * w.period - 1
-            n_rot = w.d_in * (1 + fill_counts(w.period, w.tokens)[0] + n_diag - 1)
+            n_rot = w.d_in * (1 + fill_counts(w.period, w.tokens)[0] + 3 + 7) + n_diag - 4
             n_el = w.d_in * n_diag
             n_pm = w.d_in + w.period * w.period + w.period * (w.period - 1) // 2
         else:

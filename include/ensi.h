@@ -308,17 +308,20 @@ int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const en
  * every block.  Rot(w_j; e) then holds, in slot x, element (x + e) mod period of the segment, so the diagonal
  * D_e = Rescale(Relin(sum_j a_j (x) Rot(w_j; e))) holds in slot x the entry of output column (x + e) mod period; in
  * the last e slots of a block, where that rotation reads the next block, D'_e built with Rot(w_j; e - period) holds
- * the same entries.  One plaintext product sorts the 2 period - 1 diagonals into the period columns:
- * out_c = Rescale(sum_e R (.) D_e [+ T (.) D'_e]) with the masks of ensi_segment_masks.  Per segment and ciphertext
- * of B: one giant step, one ModUp and 2 period - 2 rotations, and no per-element fill.
- * gk: keys for the steps g period, ensi_fill_steps(period, s, -1), 1 .. period - 1 and -(period - 1) .. -1.
+ * the same entries.  Baby and giant steps over the 2 period - 1 diagonals: a diagonal's rotation amount is e1 + t with
+ * 0 <= e1 < baby and t a multiple of baby; w_j is rotated by e1 only, a_j by -t, and the relinearised sum of their
+ * products by t, at the product's scale, before its rescale.  One plaintext product then sorts the diagonals into the
+ * period columns: out_c = Rescale(sum_e R (.) D_e [+ T (.) D'_e]) with the masks of ensi_segment_masks.  Per segment and
+ * ciphertext of B: one giant step of the extraction, one ModUp and baby - 1 rotations; per ciphertext of A one ModUp and
+ * 2 period / baby - 1 rotations; no per-element fill.
+ * gk: keys for the steps g period, ensi_fill_steps(period, s, -1), 1 .. baby - 1 and +-baby k, k = 1 .. period / baby.
  * mask_head: ensi_block_head_mask(s, period, limbs = l); masks: ensi_segment_masks(s, period, limbs = l - 2), 3 period
  * plaintexts: for r < period, index r = the slots of every block congruent to r modulo the period, index period + r
  * = those without the block's last period, index 2 period + r = those of the last period only.
  * A, B: d ciphertexts each at l limbs (l >= 4); out: period ciphertexts at l - 3 limbs. */
 int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **pt);
 int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s, int32_t period,
-                      int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream);
+                      int32_t baby, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream);
 
 /* The other attention product, weights times V, without replicating single elements (CCMM section; A = the s x s
  * weights of every head column-encoded, ciphertext j = column j with head h in block h; V column-encoded alike):

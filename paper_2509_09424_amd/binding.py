@@ -348,11 +348,11 @@ class Context:
         self._check(self.lib.ensi_segment_masks(self.h, int(s), int(period), int(limbs), ctypes.byref(pt)))
         return _Handle(self, pt, "ensi_pt_free", n=3 * period)
 
-    def ccmm_segment(self, rk, gk, ct_a, ct_b, s, period, g, mask_head, masks, ct_out=None, stream=0):
+    def ccmm_segment(self, rk, gk, ct_a, ct_b, s, period, baby, g, mask_head, masks, ct_out=None, stream=0):
         if ct_out is None:
             ct_out = self.ct_alloc(int(period), ct_b.limbs - 3)
-        self._check(self.lib.ensi_ccmm_segment(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), int(g), mask_head.h, masks.h,
-                                               ct_out.h, ctypes.c_void_p(stream)))
+        self._check(self.lib.ensi_ccmm_segment(self.h, rk.h, gk.h, ct_a.h, ct_b.h, int(s), int(period), int(baby), int(g), mask_head.h,
+                                               masks.h, ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def diagonalise_weights(self, gk, ct_a, s, period, baby, masks, ct_out=None, prepare=False, stream=0):

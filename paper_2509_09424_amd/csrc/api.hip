@@ -1644,9 +1644,9 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, n_out);
     for (int o = 0; o < n_out; o++)
         if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
-    // groups of outputs: at most 8 GiB of transformed operands (a group's distinct operand ciphertexts, by address:
+    // groups of outputs: at most 24 GiB of transformed operands (a group's distinct operand ciphertexts, by address:
     // one that enters several products is gathered and transformed once), at most 65535 products, at least one output
-    const size_t max_ops = std::max<size_t>(2, ((size_t)1 << 30) / ((size_t)2 * l1 * N));
+    const size_t max_ops = std::max<size_t>(2, ((size_t)3 << 30) / ((size_t)2 * l1 * N));
     const int max_out = ctx->ks16 ? rot_chunk() : 64;
     if (a_pre && limb_stride_a != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "prepared operands have %d limbs, the product runs at %d", limb_stride_a, l1);
     std::vector<int> cut(1, 0);
@@ -1663,16 +1663,17 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
             if (o1 > o0) {  // would this output's new operands still fit?
                 std::map<std::pair<const u64 *, int>, int> fresh;
                 for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
-                    const auto ka = std::make_pair(terms[t].a, limb_stride_a), kb = std::make_pair(terms[t].b, limb_stride_b);
+                    const auto ka = std::make_pair(terms[t].a, terms[t].stride_a ? terms[t].stride_a : limb_stride_a), kb = std::make_pair(terms[t].b, limb_stride_b);
                     if (!a_pre && !id.count(ka)) fresh.emplace(ka, 0);
                     if (!id.count(kb)) fresh.emplace(kb, 0);
                 }
                 if ((size_t)n_np + fresh.size() > max_ops) break;
             }
             for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
-                auto ia = id.emplace(std::make_pair(terms[t].a, limb_stride_a), (int)id.size());
+                const int sa = terms[t].stride_a ? terms[t].stride_a : limb_stride_a;
+                auto ia = id.emplace(std::make_pair(terms[t].a, sa), (int)id.size());
                 if (ia.second) {
-                    gops.push_back({terms[t].a, nullptr, limb_stride_a, a_pre ? 1 : 0});
+                    gops.push_back({terms[t].a, nullptr, sa, a_pre ? 1 : 0});
                     n_np += a_pre ? 0 : 1;
                 }
                 auto ib = id.emplace(std::make_pair(terms[t].b, limb_stride_b), (int)id.size());
@@ -2406,95 +2407,6 @@ extern "C" int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int3
     return encode_window(ctx, z.data(), 3 * period, n, 0, 0, limbs, (double)ctx->primes[limbs - 1], out);
 }
 
-extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
-                                 int32_t period, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream) {
-    if (!ctx || !rk || !gk || !A || !B || !mask_head || !masks || !out) return ENSI_E_BADARG;
-    const int N = ctx->N, d = A->n, l1 = B->limbs, P = period;
-    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
-    if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
-    if (g < 0 || g >= s / P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: segment %d outside a block of %d segments", g, s / P);
-    if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
-    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
-    if (l1 < 4 || out->limbs != l1 - 3) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be three levels below the operands");
-    if (out->n != P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, P);
-    if (mask_head->n < 1 || mask_head->limbs < l1 || masks->n < 3 * P || masks->limbs < l1 - 2)
-        ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the head mask needs %d limbs, the %d sorting masks %d", l1, 3 * P, l1 - 2);
-    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
-    hipStream_t st = (hipStream_t)stream;
-    const u64 *key;
-    int rc;
-    if ((rc = relin_key(ctx, rk, &key))) return rc;
-    const int l2 = l1 - 1, l3 = l1 - 2, n_diag = 2 * P - 1;
-    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, seg_ct = (size_t)2 * l2 * N, dg_ct = (size_t)2 * l3 * N;
-    // diagonal k: k < P is D_k (operand rotated by k), k >= P is D'_{k-P+1} (rotated by k - P + 1 - P)
-    auto amount = [&](int k) { return k < P ? k : k - 2 * P + 1; };
-    const int per = std::max(1, 1536 / std::max(d, 1));  // diagonals whose rotated operands are held at once
-    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (size_t)std::min(per, n_diag) * d * seg_ct)))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, (size_t)d * seg_ct + (size_t)n_diag * dg_ct))) return rc;
-    ensi_ct seg;
-    seg.ctx = ctx;
-    seg.owns = false;
-    seg.limbs = seg.limbs_alloc = l2;
-    seg.d = ctx->ws_rep;
-    seg.scale = B->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
-    std::vector<std::pair<int, int>> segs(d);
-    for (int j = 0; j < d; j++) segs[j] = {j, g};
-    if ((rc = spread_segments(ctx, gk, B, segs, s, P, mask_head, &seg, st))) return rc;
-    // the diagonals: D = Rescale(Relin(sum_j a_j (x) Rot(w_j; amount))), one raise of the w_j per group of diagonals
-    ensi_ct diag = seg;
-    diag.n = n_diag;
-    diag.limbs = diag.limbs_alloc = l3;
-    diag.d = ctx->ws_rep + (size_t)d * seg_ct;
-    diag.scale = A->scale * seg.scale / (double)ctx->primes[l2 - 1];
-    for (int k0 = 0; k0 < n_diag; k0 += per) {
-        const int cnt = std::min(per, n_diag - k0);
-        std::vector<RotJob> jobs;
-        std::vector<MmTerm> terms((size_t)cnt * d);
-        std::vector<int32_t> begin(cnt + 1);
-        for (int k = 0; k < cnt; k++) {
-            begin[k] = k * d;
-            const int am = amount(k0 + k);
-            for (int j = 0; j < d; j++) {
-                const u64 *b = seg.d + (size_t)j * seg_ct;
-                if (am) {
-                    u64 *dst = ctx->ws_rot + ((size_t)k * d + j) * seg_ct;
-                    jobs.push_back({j, am, dst});
-                    b = dst;
-                }
-                terms[(size_t)k * d + j] = {A->d + (size_t)j * a_ct, b};
-            }
-        }
-        begin[cnt] = cnt * d;
-        if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, d, l2, jobs, st))) return rc;
-        ensi_ct part = diag;
-        part.d = diag.d + (size_t)k0 * dg_ct;
-        part.n = cnt;
-        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &part, st))) return rc;
-    }
-    // sorting: slot x of D_e holds column (x + e) mod P; column c takes the class r = (c - e) mod P of D_e, and from D'_e
-    // where that class meets the last e slots of a block
-    std::vector<PmTerm> pt;
-    std::vector<int32_t> pb(P + 1);
-    for (int c = 0; c < P; c++) {
-        pb[c] = (int32_t)pt.size();
-        for (int e = 0; e < P; e++) {
-            const int r = ((c - e) % P + P) % P;
-            if (e && r >= P - e) {
-                pt.push_back({diag.d + (size_t)e * dg_ct, P + r, 0});
-                pt.push_back({diag.d + (size_t)(P - 1 + e) * dg_ct, 2 * P + r, 0});
-            } else {
-                pt.push_back({diag.d + (size_t)e * dg_ct, r, 0});
-            }
-        }
-    }
-    pb[P] = (int32_t)pt.size();
-    if ((rc = pmult_core(ctx, pt, pb, l3, l3, masks, out, st))) return rc;
-    out->scale = diag.scale * masks->scale / (double)ctx->primes[l3 - 1];
-    ENSI_HIP(ctx, hipGetLastError());
-    return ENSI_OK;
-}
-
-// ------------- CCMM, several heads per ciphertext: weights times V from diagonalised weights
 // Baby and giant steps over the 2P - 1 diagonals of a segment: diagonal q has rotation amount q (q < P) or q - 2P + 1
 // (the one used in the last slots of a block) = e1 + t with 0 <= e1 < baby and t a multiple of baby.
 static void diagonal_schedule(int P, int baby, std::vector<int> &e1, std::vector<int> &t) {
@@ -2507,6 +2419,129 @@ static void diagonal_schedule(int P, int baby, std::vector<int> &e1, std::vector
     }
 }
 
+extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
+                                 int32_t period, int32_t baby, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out,
+                                 void *stream) {
+    if (!ctx || !rk || !gk || !A || !B || !mask_head || !masks || !out) return ENSI_E_BADARG;
+    const int N = ctx->N, d = A->n, l1 = B->limbs, P = period;
+    if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
+    if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
+    if (baby < 1 || (baby & (baby - 1)) || baby > P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the baby-step range must be a power of two up to the period");
+    if (g < 0 || g >= s / P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: segment %d outside a block of %d segments", g, s / P);
+    if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
+    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    if (l1 < 4 || out->limbs != l1 - 3) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be three levels below the operands");
+    if (out->n != P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, P);
+    if (mask_head->n < 1 || mask_head->limbs < l1 || masks->n < 3 * P || masks->limbs < l1 - 2)
+        ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: the head mask needs %d limbs, the %d sorting masks %d", l1, 3 * P, l1 - 2);
+    if (d > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: at most 65535 products per diagonal");
+    if (A->d == out->d || B->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: operands and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const u64 *key;
+    int rc;
+    if ((rc = relin_key(ctx, rk, &key))) return rc;
+    const int l2 = l1 - 1, l3 = l1 - 2, n_diag = 2 * P - 1;
+    const size_t a_ct = (size_t)2 * A->limbs_alloc * N, seg_ct = (size_t)2 * l2 * N;
+    std::vector<int> e1, t;
+    diagonal_schedule(P, baby, e1, t);
+    std::vector<int> giant(t);  // the distinct giant steps, ascending
+    std::sort(giant.begin(), giant.end());
+    giant.erase(std::unique(giant.begin(), giant.end()), giant.end());
+    const int nT = (int)giant.size();
+    auto giant_index = [&](int v) { return (int)(std::lower_bound(giant.begin(), giant.end(), v) - giant.begin()); };
+    // ws_rot: [rotated w: d (baby - 1)][rotated a: d (nT - 1)][rotated sums: n_diag], all at l2 limbs; the first stage
+    // (aligning rotations at l1 limbs) uses its start.  ws_rep: [segs: d][sums: n_diag].
+    const size_t n_w = (size_t)d * (baby - 1), n_a = (size_t)d * (nT - 1);
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (n_w + n_a + n_diag) * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, ((size_t)d + n_diag) * seg_ct))) return rc;
+    ensi_ct seg;
+    seg.ctx = ctx;
+    seg.owns = false;
+    seg.limbs = seg.limbs_alloc = l2;
+    seg.d = ctx->ws_rep;
+    seg.scale = B->scale * mask_head->scale / (double)ctx->primes[l1 - 1];
+    std::vector<std::pair<int, int>> segs(d);
+    for (int j = 0; j < d; j++) segs[j] = {j, g};
+    if ((rc = spread_segments(ctx, gk, B, segs, s, P, mask_head, &seg, st))) return rc;
+    // baby steps of the spread operands, minus the giant steps of the columns of A (read at l2 limbs)
+    u64 *w_rot = ctx->ws_rot, *a_rot = w_rot + n_w * seg_ct, *s_rot = a_rot + n_a * seg_ct;
+    std::vector<RotJob> jobs;
+    for (int j = 0; j < d; j++)
+        for (int b = 1; b < baby; b++) jobs.push_back({j, b, w_rot + ((size_t)j * (baby - 1) + (b - 1)) * seg_ct});
+    if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, d, l2, jobs, st))) return rc;
+    jobs.clear();
+    std::vector<int> a_slot(nT, -1);  // position of each nonzero giant step among the rotated copies of a column
+    for (int gi = 0, k = 0; gi < nT; gi++)
+        if (giant[gi]) a_slot[gi] = k++;
+    for (int j = 0; j < d; j++)
+        for (int gi = 0; gi < nT; gi++)
+            if (giant[gi]) jobs.push_back({j, -giant[gi], a_rot + ((size_t)j * (nT - 1) + a_slot[gi]) * seg_ct});
+    if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, A->d, a_ct, A->limbs_alloc, d, l2, jobs, st))) return rc;
+    // the diagonals: relinearised sums at the product's scale, those without a giant step first (the rotated columns of
+    // A have limb stride l2, the unrotated ones A's own)
+    ensi_ct sums = seg;
+    sums.n = n_diag;
+    sums.d = ctx->ws_rep + (size_t)d * seg_ct;
+    sums.scale = A->scale * seg.scale;
+    std::vector<int> order;
+    for (int q = 0; q < n_diag; q++)
+        if (!t[q]) order.push_back(q);
+    const int n_plain = (int)order.size();
+    for (int q = 0; q < n_diag; q++)
+        if (t[q]) order.push_back(q);
+    {
+        std::vector<MmTerm> terms;
+        std::vector<int32_t> begin(1, 0);
+        for (int k = 0; k < n_diag; k++) {
+            const int q = order[k];
+            for (int j = 0; j < d; j++) {
+                MmTerm tm;
+                tm.a = t[q] ? a_rot + ((size_t)j * (nT - 1) + a_slot[giant_index(t[q])]) * seg_ct : A->d + (size_t)j * a_ct;
+                tm.stride_a = t[q] ? l2 : A->limbs_alloc;
+                tm.b = e1[q] ? w_rot + ((size_t)j * (baby - 1) + (e1[q] - 1)) * seg_ct : seg.d + (size_t)j * seg_ct;
+                terms.push_back(tm);
+            }
+            begin.push_back((int32_t)terms.size());
+        }
+        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &sums, st, false, false))) return rc;
+    }
+    // giant steps of the sums, then the rescale of every diagonal (in place; limb stride l2)
+    jobs.clear();
+    for (int k = n_plain; k < n_diag; k++) jobs.push_back({k, t[order[k]], s_rot + (size_t)k * seg_ct});
+    if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, sums.d, seg_ct, l2, n_diag, l2, jobs, st))) return rc;
+    const u64 *d_consts;
+    const double *d_fconsts;
+    bool fp;
+    if ((rc = upload_rescale_consts(ctx, l2, 1.0, false, st, &d_consts, &d_fconsts, &fp))) return rc;
+    if (n_plain) launch_rescale(ctx, sums.d, n_plain, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+    if (n_diag > n_plain) launch_rescale(ctx, s_rot + (size_t)n_plain * seg_ct, n_diag - n_plain, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+    std::vector<const u64 *> diag(n_diag);
+    for (int k = 0; k < n_diag; k++) diag[order[k]] = k < n_plain ? sums.d + (size_t)k * seg_ct : s_rot + (size_t)k * seg_ct;
+    const double diag_scale = sums.scale / (double)ctx->primes[l2 - 1];
+    // sorting: slot x of D_e holds column (x + e) mod P; column c takes the class r = (c - e) mod P of D_e, and from D'_e
+    // where that class meets the last e slots of a block
+    std::vector<PmTerm> pt;
+    std::vector<int32_t> pb(P + 1);
+    for (int c = 0; c < P; c++) {
+        pb[c] = (int32_t)pt.size();
+        for (int e = 0; e < P; e++) {
+            const int r = ((c - e) % P + P) % P;
+            if (e && r >= P - e) {
+                pt.push_back({diag[e], P + r, 0});
+                pt.push_back({diag[P - 1 + e], 2 * P + r, 0});
+            } else {
+                pt.push_back({diag[e], r, 0});
+            }
+        }
+    }
+    pb[P] = (int32_t)pt.size();
+    if ((rc = pmult_core(ctx, pt, pb, l3, l2, masks, out, st))) return rc;
+    out->scale = diag_scale * masks->scale / (double)ctx->primes[l3 - 1];
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
+// ------------- CCMM, several heads per ciphertext: weights times V from diagonalised weights
 extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *A, int32_t s, int32_t period, int32_t baby,
                                         const ensi_pt *masks, int32_t prepare, ensi_ct *out, void *stream) {
     if (!ctx || !gk || !A || !masks || !out) return ENSI_E_BADARG;

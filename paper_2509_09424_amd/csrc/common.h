@@ -92,6 +92,8 @@ struct PmGroup {
 // One ciphertext-ciphertext product as the host describes it: the two operand ciphertexts.
 struct MmTerm {
     const u64 *a, *b;
+    int32_t stride_a = 0;  // limb stride of a where it differs from the call's (0: the call's)
+    int32_t pad = 0;
 };
 // On the device a group of outputs names every distinct operand ciphertext once ([2][limb_stride][N] words each), so
 // that an operand shared by several products is gathered and transformed once, and its products as index pairs.

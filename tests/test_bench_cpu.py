@@ -64,16 +64,17 @@ def test_giant_and_baby_step_counts():
 
 
 def test_segment_form_counts():
-    w = wl.BY_NAME["ccmmqkseg"]  # 96 ciphertexts of K, period 16: 31 diagonals
+    w = wl.BY_NAME["ccmmqkseg"]  # 96 ciphertexts of K and of Q, period 16 in baby steps of 4: 31 diagonals, 8 giant steps
     unit = 8.0 * w.N
     _, roof = bench.roofline_for(w, {"ks_icols_special": (1.0, 1)})
-    switches = 96 + (96 * 4 + 96 * 30 + 31)  # aligning rotations; fill groups, rotations of the spread operands, relinearisations
+    # aligning rotations; fill groups, baby steps of K's and giant steps of Q's operands, relinearisations, giant steps of 27 sums
+    switches = 96 + (96 * 4 + 96 * 3 + 96 * 7 + 31 + 27)
     assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
     _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})
     assert abs(roof["achieved"] - (96 * 4 * 16 + (256 + 120) * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
-    # library transforms of the products: 96 + 96 * 31 operands (two polynomials of 15 limbs, two passes, in and out), 31 x 3 sums back
+    # library transforms of the products: 96 * (4 + 8) operands (two polynomials of 15 limbs, two passes, in and out), 31 x 3 sums back
     _, roof = bench.roofline_for(w, {"ntt_fwd_cols": (1.0, 1)})
-    assert abs(roof["achieved"] - 4 * ((96 + 96 * 31) * 2 * 15 + 31 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
+    assert abs(roof["achieved"] - 4 * (96 * 12 * 2 * 15 + 31 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
     w = wl.BY_NAME["ccmmavseg"]  # one column of V, 32 segments
     _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
     # raises: the column at 16 limbs; per segment 4 fill groups and one for its baby steps, and the 8 relinearisations, at 15; 7 giant steps at 14

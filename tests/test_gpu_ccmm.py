@@ -433,13 +433,14 @@ def test_ccmm_forms_share_one_context():
 
 
 # ------------------------------------------------ a whole segment of columns from its diagonals
-def segment_case(p, l1, s, period, d, g):
+def segment_case(p, l1, s, period, baby, d, g):
     heads = p.n // s
     Q = p.rng.uniform(-1, 1, (heads, s, d))
     K = p.rng.uniform(-1, 1, (heads, s, d))
     o_a, g_a = p.encrypt_both(np.stack([np.concatenate([Q[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
     o_b, g_b = p.encrypt_both(np.stack([np.concatenate([K[h][:, j] for h in range(heads)]) for j in range(d)]), l1)
-    steps = set(range(1, period)) | set(range(1 - period, 0)) | {g * period} | set(p.ctx.fill_steps(period, s, -1))
+    giant = {k * baby for k in range(1, period // baby + 1)}
+    steps = set(range(1, baby)) | giant | {-t for t in giant} | {g * period} | set(p.ctx.fill_steps(period, s, -1))
     o_gks, g_gk = p.galois_keys(sorted(st for st in steps if st))
     mh = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.block_head_mask(s, period, l1)[None, :], l1), float(p.pr.q[l1 - 1]))
     ms = p.ctx.pt_set_scale(p.ctx.pt_import(p.o.segment_masks(s, period, l1 - 2), l1 - 2), float(p.pr.q[l1 - 3]))
@@ -447,40 +448,41 @@ def segment_case(p, l1, s, period, d, g):
     return o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref
 
 
-@pytest.mark.parametrize("params,l1,s,period,d,g", [(SMALL4, 6, 64, 8, 5, 3), (SMALL4, 5, 512, 4, 3, 0), (SMALL4, 5, 16, 16, 2, 0),
-                                                    (WIDE, 4, 128, 16, 18, 7)],
-                         ids=["8-heads", "one-head-first-segment", "segment-is-the-block", "wide-primes-two-groups"])
-def test_ccmm_segment_small_ring(params, l1, s, period, d, g):
+@pytest.mark.parametrize("params,l1,s,period,baby,d,g", [(SMALL4, 6, 64, 8, 2, 5, 3), (SMALL4, 5, 512, 4, 4, 3, 0), (SMALL4, 5, 16, 16, 4, 2, 0),
+                                                         (SMALL4, 5, 64, 8, 1, 2, 7), (WIDE, 4, 128, 16, 4, 18, 7)],
+                         ids=["8-heads", "one-head-first-segment-baby-steps-only", "segment-is-the-block", "giant-steps-only",
+                              "wide-primes-two-groups"])
+def test_ccmm_segment_small_ring(params, l1, s, period, baby, d, g):
     """A segment of output columns from its diagonals: bit-exact against the oracle, numpy after decryption; the
     library's own masks give the same product within the bound."""
     p = Pair(params)
-    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, d, g)
+    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, baby, d, g)
     o_rk, g_rk = relin_keys(p)
-    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, g, mh, ms)
-    want = p.o.ccmm_segment(o_a, o_b, s, period, g, o_rk, o_gks)
+    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, mh, ms)
+    want = p.o.ccmm_segment(o_a, o_b, s, period, baby, g, o_rk, o_gks)
     assert out.n == period and out.limbs == l1 - 3
     assert np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
     lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.segment_masks(s, period, l1 - 2)
-    out2 = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, g, lh, ls)
+    out2 = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, lh, ls)
     assert np.abs(p.ctx.decrypt(p.g_sk, out2) - ref).max() < 1e-3
     with pytest.raises(p.binding.EnsiError, match="code -1"):
-        p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, s // period, mh, ms, out2)  # segment outside the block
+        p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, s // period, mh, ms, out2)  # segment outside the block
     with pytest.raises(p.binding.EnsiError, match="code -3"):
-        p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, g, ms, ms, out2)  # head mask two levels short
+        p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, ms, ms, out2)  # head mask two levels short
     for h in (g_a, g_b, mh, ms, lh, ls, out, out2, g_gk, g_rk):
         h.free()
     p.close()
 
 
 def test_ccmm_segment_full_ring():
-    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 4, a narrow inner dimension and a low level."""
+    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 4 in baby steps of 2, a narrow inner dimension and a low level."""
     p = Pair(KEYSWITCH)
-    l1, s, period, d, g = 5, 2048, 4, 2, 511
-    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, d, g)
+    l1, s, period, baby, d, g = 5, 2048, 4, 2, 2, 511
+    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, baby, d, g)
     o_rk, g_rk = relin_keys(p)
-    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, g, mh, ms)
-    want = p.o.ccmm_segment(o_a, o_b, s, period, g, o_rk, o_gks)
+    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, mh, ms)
+    want = p.o.ccmm_segment(o_a, o_b, s, period, baby, g, o_rk, o_gks)
     assert out.limbs == l1 - 3 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
     for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
@@ -489,15 +491,15 @@ def test_ccmm_segment_full_ring():
 
 
 def test_ccmm_segment_at_the_benchmark_parameters():
-    """The 16 + 4 limb chain, the 16 x 2048 packing and the period 16 of the benchmark workload with a narrow inner
-    dimension (d = 2), so that the oracle's 2 x 40 rotations at 15 and 16 limbs take seconds."""
+    """The 16 + 4 limb chain, the 16 x 2048 packing, the period 16 and the baby steps of 4 of the benchmark workload with
+    a narrow inner dimension (d = 2)."""
     w = wl.BY_NAME["ccmmqk"]
     p = Pair(w.param_tuple())
-    l1, s, period, d, g = p.pr.L, w.tokens, 16, 2, 64
-    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, d, g)
+    l1, s, period, baby, d, g = p.pr.L, w.tokens, 16, 4, 2, 64
+    o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, baby, d, g)
     o_rk, g_rk = relin_keys(p)
-    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, g, mh, ms)
-    want = p.o.ccmm_segment(o_a, o_b, s, period, g, o_rk, o_gks)
+    out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, mh, ms)
+    want = p.o.ccmm_segment(o_a, o_b, s, period, baby, g, o_rk, o_gks)
     assert out.limbs == l1 - 3 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
     for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
