@@ -134,7 +134,7 @@ class Runner:
             pt = self.ctx.encode(zb, self.L)
             self.ct_in = self.ctx.encrypt(self.pk, pt)
             pt.free()
-            self.baby = 4  # the column of V is rotated by 1 .. 3 only; the weights carry the giant steps
+            self.baby = w.baby  # the column of V is rotated by the baby steps only; the weights carry the giant steps
             giant = {k * self.baby for k in range(1, P // self.baby + 1)}
             steps = set(range(1, self.baby)) | giant | {-t for t in giant} | {g * P for g in range(1, d // P)} | set(self.ctx.fill_steps(P, sl, -1))
             self.gk = self.ctx.galois_keygen(self.sk, sorted(steps), None, 13)
@@ -188,7 +188,7 @@ class Runner:
             if w.op == "ccmm_segment":
                 # the whole segment 1 from its diagonals, in baby steps of the spread operands and giant steps of the columns of Q
                 assert m == P
-                self.baby = 4
+                self.baby = w.baby
                 giant = {k * self.baby for k in range(1, P // self.baby + 1)}
                 steps |= set(range(1, self.baby)) | giant | {-t for t in giant}
                 self.pt2 = self.ctx.segment_masks(sl, P, self.L - 2)
@@ -429,20 +429,20 @@ def roofline_for(w, prof):
     elif w.op == "ccmm_av":
         # per column of V and segment: one giant step (aligning rotation at the top level, head mask, fill over the block one
         # level down) and 2P-2 rotations of the spread operand on one raise; one relinearisation per output
-        P, n_seg, m, baby = w.period, w.d_in // w.period, w.d_out, 4
+        P, n_seg, m, baby = w.period, w.d_in // w.period, w.d_out, w.baby
         g_rot, g_raise = fill_counts(P, w.tokens)
         n_sg, n_t = n_seg * m, 2 * P // baby  # spread operands; giant steps (sums per output)
         ks.append((L, n_sg, m, n_sg, n_seg))
         ks.append((L - 1, n_sg * (g_rot + baby - 1) + n_t * m, n_sg * (g_raise + 1) + n_t * m, n_sg * (g_raise + baby - 1) + n_t * m,
                    g_rot * -(-n_sg // 64) + (baby - 1) * -(-n_sg // 16) + 1))
-        ks.append((L - 2, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m))  # the sums rotated by their giant steps
+        ks.append((L - 1, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m, (n_t - 1) * m))  # the sums rotated by their giant steps, before the rescale
         pm.append((L, n_sg, n_sg))
         mm.append((L - 1, n_sg * baby, n_t * m))  # the prepared weights are not transformed again
     elif w.op == "ccmm_segment":
         # per ciphertext of B: one giant step (aligning rotation at the top level, head mask, fill over the block one level
         # down) and 2P-2 rotations of the spread operand on one raise; 2P-1 relinearisations two levels down; the sorting
         # products of the 2P-1 diagonals into P columns
-        P, dd, baby = w.period, w.d_in, 4
+        P, dd, baby = w.period, w.d_in, w.baby
         g_rot, g_raise = fill_counts(P, w.tokens)
         n_diag, n_t = 2 * P - 1, 2 * P // baby
         ks.append((L, dd, dd, dd, -(-dd // 16)))
@@ -591,12 +591,12 @@ def cpu_baseline(w, budget_s=12.0):
             n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
         elif w.op == "ccmm_av":
             n_diag, n_sg = 2 * w.period - 1, w.d_in // w.period * w.d_out
-            n_rot = n_sg * (1 + fill_counts(w.period, w.tokens)[0] + 3) + 7 * w.d_out
+            n_rot = n_sg * (1 + fill_counts(w.period, w.tokens)[0] + w.baby - 1) + (2 * w.period // w.baby - 1) * w.d_out
             n_el = n_sg * n_diag
             n_pm = n_sg
         elif w.op == "ccmm_segment":
             n_diag = 2 * w.period - 1
-            n_rot = w.d_in * (1 + fill_counts(w.period, w.tokens)[0] + 3 + 7) + n_diag - 4
+            n_rot = w.d_in * (1 + fill_counts(w.period, w.tokens)[0] + w.baby - 1 + 2 * w.period // w.baby - 1) + n_diag - w.baby
             n_el = w.d_in * n_diag
             n_pm = w.d_in + w.period * w.period + w.period * (w.period - 1) // 2
         else:

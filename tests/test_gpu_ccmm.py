@@ -491,8 +491,8 @@ def test_ccmm_segment_full_ring():
 
 
 def test_ccmm_segment_at_the_benchmark_parameters():
-    """The 16 + 4 limb chain, the 16 x 2048 packing, the period 16 and the baby steps of 4 of the benchmark workload with
-    a narrow inner dimension (d = 2)."""
+    """The 16 + 4 limb chain and the 16 x 2048 packing of the benchmark workload with a narrow inner dimension (d = 2),
+    at period 16 in baby steps of 4 (the benchmark runs 32 and 8, whose 1536 sorting products take the oracle a minute)."""
     w = wl.BY_NAME["ccmmqk"]
     p = Pair(w.param_tuple())
     l1, s, period, baby, d, g = p.pr.L, w.tokens, 16, 4, 2, 64
@@ -589,8 +589,8 @@ def test_ccmm_av_full_ring():
 
 
 def test_ccmm_av_at_the_benchmark_parameters():
-    """The 16 + 4 limb chain, the 16 x 2048 packing, the period 16 and the baby steps of 4 of the benchmark workload on
-    one segment."""
+    """The 16 + 4 limb chain and the 16 x 2048 packing of the benchmark workload on one segment, at period 16 in baby
+    steps of 4 (the benchmark runs 32 and 8, whose 3000 diagonalising products take the oracle a minute)."""
     w = wl.BY_NAME["ccmmqk"]
     p = Pair(w.param_tuple())
     l1, s, period, baby, g0, n_seg, m = p.pr.L, w.tokens, 16, 4, 127, 1, 1

@@ -40,6 +40,7 @@ class Workload:
     op: str = "matmul"  # "matmul" (Alg. 1, the default), "rope" (Alg. 2), "merge" (block merge of placed outputs), "ccmm", "ccmm_blocks",
     #                     "ccmm_bsgs" (Q K^T form), "ccmm_bsgs_av" (weights times V form), "ccmm_segment" or "ccmm_av"
     period: int = 0  # baby-step range of the block-wise element extraction in giant and baby steps
+    baby: int = 0  # segment forms: baby-step range over the diagonals of a segment
 
     @property
     def N(self):
@@ -88,8 +89,9 @@ WORKLOADS.append(Workload("ccmmqk", 10, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # The same product with the element extraction in giant and baby steps (period 16): a step computes the d_out = 16
 # output columns of one segment (columns 16..31), whose giant steps are shared.  Three levels instead of two.
 WORKLOADS.append(Workload("ccmmqkbsgs", 11, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_bsgs", period=16))
-# The same 16 output columns as a whole segment from its diagonals (no per-element fills).
-WORKLOADS.append(Workload("ccmmqkseg", 14, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_segment", period=16))
+# A whole segment of 32 output columns (32 .. 63) from its diagonals, in baby steps of 8 (no per-element fills).
+WORKLOADS.append(Workload("ccmmqkseg", 14, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=32, act="uniform", op="ccmm_segment", period=32,
+                          baby=8))
 # A slice of the paper's other attention product (Table III: (2048 x 2048) by (2048 x 96), 16 heads): the attention
 # weights column-encoded (column j = one ciphertext, 16 heads in its blocks), V column-encoded.  Output column i is
 # sum_j a_j (x) E(v_i, j) over the 2048 tokens j; a step forms d_out = 1 output over the first d_in = 512 of them.
@@ -99,7 +101,8 @@ WORKLOADS.append(Workload("ccmmav", 12, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # The fused N = 2^16 kernels do not apply: transforms, ModUp, inner product and ModDown run as separate kernels.
 WORKLOADS.append(Workload("paper1536n14", 13, 14, 50, 6, 60, 2, 2, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
 # The same slice of weights times V from diagonalised weights (prepared once for all 96 columns of V, outside the step).
-WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_av", period=16))
+WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_av", period=32,
+                          baby=8))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
