@@ -318,7 +318,14 @@ int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const en
  * mask_head: ensi_block_head_mask(s, period, limbs = l); masks: ensi_segment_masks(s, period, limbs = l - 2), 3 period
  * plaintexts: for r < period, index r = the slots of every block congruent to r modulo the period, index period + r
  * = those without the block's last period, index 2 period + r = those of the last period only.
- * A, B: d ciphertexts each at l limbs (l >= 4); out: period ciphertexts at l - 3 limbs. */
+ * A, B: d ciphertexts each at l limbs (l >= 4); out: period ciphertexts at l - 3 limbs.
+ * The rotations of the columns of A do not depend on the segment: ensi_ccmm_left_giant_steps forms them once,
+ * out[j nT + k] = Rot(a_j; -t_k) on the first l - 1 limbs for the nT = 2 period / baby giant steps t_k = -period,
+ * -period + baby, ..., period - baby (baby = 1: the 2 period - 1 steps -(period - 1) .. period - 1; out allocated at exactly l - 1 limbs; prepare != 0 leaves it in the transform
+ * domain, as for ensi_diagonalise_weights), and ensi_ccmm_segment takes that batch in place of A (it tells the two by
+ * their level: l limbs = plain columns, l - 1 limbs = moved columns, d nT of them). */
+int ensi_ccmm_left_giant_steps(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *A, int32_t period, int32_t baby, int32_t prepare, ensi_ct *out,
+                               void *stream);
 int ensi_segment_masks(ensi_ctx *ctx, int32_t s, int32_t period, int32_t limbs, ensi_pt **pt);
 int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s, int32_t period,
                       int32_t baby, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out, void *stream);

@@ -23,7 +23,7 @@ EXPORTED = [
     "ensi_ct_import", "ensi_encrypt", "ensi_decrypt", "ensi_rotate", "ensi_ternary_matmul",
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
-    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ccmm_left_giant_steps", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
 ]
 
 
@@ -347,6 +347,14 @@ class Context:
         pt = ctypes.c_void_p()
         self._check(self.lib.ensi_segment_masks(self.h, int(s), int(period), int(limbs), ctypes.byref(pt)))
         return _Handle(self, pt, "ensi_pt_free", n=3 * period)
+
+    def ccmm_left_giant_steps(self, gk, ct_a, period, baby, ct_out=None, prepare=False, stream=0):
+        if ct_out is None:
+            n_giant = 2 * int(period) - 1 if int(baby) == 1 else 2 * int(period) // int(baby)
+            ct_out = self.ct_alloc(ct_a.n * n_giant, ct_a.limbs - 1)
+        self._check(self.lib.ensi_ccmm_left_giant_steps(self.h, gk.h, ct_a.h, int(period), int(baby), int(bool(prepare)), ct_out.h,
+                                                        ctypes.c_void_p(stream)))
+        return ct_out
 
     def ccmm_segment(self, rk, gk, ct_a, ct_b, s, period, baby, g, mask_head, masks, ct_out=None, stream=0):
         if ct_out is None:

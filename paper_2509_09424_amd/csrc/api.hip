@@ -2419,17 +2419,56 @@ static void diagonal_schedule(int P, int baby, std::vector<int> &e1, std::vector
     }
 }
 
+// The left operand of ensi_ccmm_segment moved by minus every giant step, once for all segments:
+// out[j nT + k] = Rot(A_j; -giant_k) on the first l - 1 limbs, giant_k ascending = -P, -P + baby, ..., P - baby.
+extern "C" int ensi_ccmm_left_giant_steps(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *A, int32_t period, int32_t baby, int32_t prepare,
+                                          ensi_ct *out, void *stream) {
+    if (!ctx || !gk || !A || !out) return ENSI_E_BADARG;
+    if (A->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the operand is already prepared");
+    const int N = ctx->N, P = period, d = A->n, l2 = A->limbs - 1;
+    if (P < 1 || (P & (P - 1)) || P > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "the period must be a power of two");
+    if (baby < 1 || (baby & (baby - 1)) || baby > P) ENSI_FAIL(ctx, ENSI_E_BADARG, "the baby-step range must be a power of two up to the period");
+    std::vector<int> e1, t;
+    diagonal_schedule(P, baby, e1, t);
+    std::vector<int> giant(t);
+    std::sort(giant.begin(), giant.end());
+    giant.erase(std::unique(giant.begin(), giant.end()), giant.end());
+    const int nT = (int)giant.size();
+    if (l2 < 1 || out->limbs != l2 || out->limbs_alloc != l2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "the output batch must be allocated one level below the input");
+    if (out->n != d * nT) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, d * nT);
+    if (A->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "in and out must not overlap");
+    hipStream_t st = (hipStream_t)stream;
+    const size_t o_ct = (size_t)2 * l2 * N;
+    std::vector<RotJob> jobs;
+    for (int j = 0; j < d; j++)
+        for (int k = 0; k < nT; k++) jobs.push_back({j, -giant[k], out->d + ((size_t)j * nT + k) * o_ct});
+    int rc;
+    out->prepared = false;
+    if ((rc = rotate_jobs(ctx, gk, A->d, (size_t)2 * A->limbs_alloc * N, A->limbs_alloc, d, l2, jobs, st))) return rc;
+    out->scale = A->scale;
+    if (prepare) {
+        launch_ntt(ctx, out->d, out->n * 2 * l2, make_map(ctx, l2, false), false, st);
+        out->prepared = true;
+    }
+    ENSI_HIP(ctx, hipGetLastError());
+    return ENSI_OK;
+}
+
 extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
                                  int32_t period, int32_t baby, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out,
                                  void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !mask_head || !masks || !out) return ENSI_E_BADARG;
-    const int N = ctx->N, d = A->n, l1 = B->limbs, P = period;
+    const int N = ctx->N, d = B->n, l1 = B->limbs, P = period;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
     if (baby < 1 || (baby & (baby - 1)) || baby > P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the baby-step range must be a power of two up to the period");
     if (g < 0 || g >= s / P) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: segment %d outside a block of %d segments", g, s / P);
-    if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
-    if (A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    // A one level below B: the columns already moved by their giant steps (ensi_ccmm_left_giant_steps), 2P / baby to a column
+    const bool a_given = A->limbs == l1 - 1;
+    if (!a_given && A->limbs != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: A and B at different levels (%d vs %d limbs)", A->limbs, l1);
+    const int n_giant = baby == 1 ? 2 * P - 1 : 2 * P / baby;  // distinct giant steps of the diagonals
+    if (A->n != (a_given ? d * n_giant : d)) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A holds %d ciphertexts, B has %d rows", A->n, d);
+    if (A->prepared && !a_given) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: a prepared A must come from ensi_ccmm_left_giant_steps");
     if (l1 < 4 || out->limbs != l1 - 3) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ccmm: output must be three levels below the operands");
     if (out->n != P) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: output batch holds %d ciphertexts, need %d", out->n, P);
     if (mask_head->n < 1 || mask_head->limbs < l1 || masks->n < 3 * P || masks->limbs < l1 - 2)
@@ -2451,7 +2490,7 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
     auto giant_index = [&](int v) { return (int)(std::lower_bound(giant.begin(), giant.end(), v) - giant.begin()); };
     // ws_rot: [rotated w: d (baby - 1)][rotated a: d (nT - 1)][rotated sums: n_diag], all at l2 limbs; the first stage
     // (aligning rotations at l1 limbs) uses its start.  ws_rep: [segs: d][sums: n_diag].
-    const size_t n_w = (size_t)d * (baby - 1), n_a = (size_t)d * (nT - 1);
+    const size_t n_w = (size_t)d * (baby - 1), n_a = a_given ? 0 : (size_t)d * (nT - 1);
     if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (n_w + n_a + n_diag) * seg_ct)))) return rc;
     if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, ((size_t)d + n_diag) * seg_ct))) return rc;
     ensi_ct seg;
@@ -2473,7 +2512,7 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
     std::vector<int> a_slot(nT, -1);  // position of each nonzero giant step among the rotated copies of a column
     for (int gi = 0, k = 0; gi < nT; gi++)
         if (giant[gi]) a_slot[gi] = k++;
-    for (int j = 0; j < d; j++)
+    for (int j = 0; j < d && !a_given; j++)
         for (int gi = 0; gi < nT; gi++)
             if (giant[gi]) jobs.push_back({j, -giant[gi], a_rot + ((size_t)j * (nT - 1) + a_slot[gi]) * seg_ct});
     if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, A->d, a_ct, A->limbs_alloc, d, l2, jobs, st))) return rc;
@@ -2496,14 +2535,19 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
             const int q = order[k];
             for (int j = 0; j < d; j++) {
                 MmTerm tm;
-                tm.a = t[q] ? a_rot + ((size_t)j * (nT - 1) + a_slot[giant_index(t[q])]) * seg_ct : A->d + (size_t)j * a_ct;
-                tm.stride_a = t[q] ? l2 : A->limbs_alloc;
+                if (a_given) {
+                    tm.a = A->d + ((size_t)j * nT + giant_index(t[q])) * a_ct;
+                    tm.stride_a = A->limbs_alloc;
+                } else {
+                    tm.a = t[q] ? a_rot + ((size_t)j * (nT - 1) + a_slot[giant_index(t[q])]) * seg_ct : A->d + (size_t)j * a_ct;
+                    tm.stride_a = t[q] ? l2 : A->limbs_alloc;
+                }
                 tm.b = e1[q] ? w_rot + ((size_t)j * (baby - 1) + (e1[q] - 1)) * seg_ct : seg.d + (size_t)j * seg_ct;
                 terms.push_back(tm);
             }
             begin.push_back((int32_t)terms.size());
         }
-        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &sums, st, false, false))) return rc;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &sums, st, A->prepared, false))) return rc;
     }
     // giant steps of the sums, then the rescale of every diagonal (in place; limb stride l2)
     jobs.clear();

@@ -66,5 +66,6 @@ def test_null_arguments_of_the_later_entry_points_without_gpu():
     assert lib.ensi_ccmm_bsgs(n, n, n, n, n, 4, 2, n, n, n, n, 1, n, n, n, n) == -1
     assert lib.ensi_segment_masks(n, 4, 2, 2, n) == -1
     assert lib.ensi_ccmm_segment(n, n, n, n, n, 4, 2, 2, 0, n, n, n, n) == -1
+    assert lib.ensi_ccmm_left_giant_steps(n, n, n, 4, 2, 0, n, n) == -1
     assert lib.ensi_diagonalise_weights(n, n, n, 4, 2, 2, n, 0, n, n) == -1
     assert lib.ensi_ccmm_av(n, n, n, n, n, 4, 2, 2, 0, n, n, n) == -1

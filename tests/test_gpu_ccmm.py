@@ -463,6 +463,14 @@ def test_ccmm_segment_small_ring(params, l1, s, period, baby, d, g):
     assert out.n == period and out.limbs == l1 - 3
     assert np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
+    # the columns of A moved by their giant steps once, outside the call (as ciphertexts, then left in the transform domain)
+    for prepare in (False, True):
+        ap = p.ctx.ccmm_left_giant_steps(g_gk, g_a, period, baby, prepare=prepare)
+        assert ap.n == d * (2 * period - 1 if baby == 1 else 2 * period // baby) and ap.limbs == l1 - 1
+        outp = p.ctx.ccmm_segment(g_rk, g_gk, ap, g_b, s, period, baby, g, mh, ms)
+        assert np.array_equal(outp.export(), stack_cts(want)), prepare
+        ap.free()
+        outp.free()
     lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.segment_masks(s, period, l1 - 2)
     out2 = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, lh, ls)
     assert np.abs(p.ctx.decrypt(p.g_sk, out2) - ref).max() < 1e-3
@@ -485,7 +493,10 @@ def test_ccmm_segment_full_ring():
     want = p.o.ccmm_segment(o_a, o_b, s, period, baby, g, o_rk, o_gks)
     assert out.limbs == l1 - 3 and np.array_equal(out.export(), stack_cts(want))
     assert np.abs(p.ctx.decrypt(p.g_sk, out) - ref).max() < 1e-3
-    for h in (g_a, g_b, mh, ms, out, g_gk, g_rk):
+    ap = p.ctx.ccmm_left_giant_steps(g_gk, g_a, period, baby, prepare=True)  # columns of A moved once, in the transform domain
+    outp = p.ctx.ccmm_segment(g_rk, g_gk, ap, g_b, s, period, baby, g, mh, ms)
+    assert np.array_equal(outp.export(), stack_cts(want))
+    for h in (g_a, g_b, mh, ms, out, ap, outp, g_gk, g_rk):
         h.free()
     p.close()
 
