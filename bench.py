@@ -465,7 +465,7 @@ def roofline_for(w, prof):
         ks.append((L - 1, dd * (g_rot + baby - 1) + n_diag + n_rs, dd * (g_raise + 1) + n_diag + n_rs,
                    dd * (g_raise + baby - 1) + n_diag + n_rs, g_rot * -(-dd // 64) + (baby - 1) * -(-dd // 16) + 1 + n_rs))
         pm.append((L, dd, dd))
-        pm.append((L - 2, P * P + P * (P - 1) // 2, P))
+        pm.append((L - 2, P * P + P * (P - 1) // 2, P, n_diag))  # every diagonal enters many sorting products, transformed once
         mm.append((L - 1, dd * baby, n_diag))
     else:
         n_in = -(-w.d_in // w.c_tot)
@@ -478,7 +478,8 @@ def roofline_for(w, prof):
         return sum(f(l, -(-l // alpha), l + K, n_rot, n_raise, n_sw, n_key) for l, n_rot, n_raise, n_sw, n_key in ks)
 
     def pm_sum(f):
-        return sum(f(l, t, o) for l, t, o in pm)
+        # (limbs, products, outputs[, distinct sources: a source that enters several products is column-transformed once])
+        return sum(f(e[0], e[1], e[2], e[3] if len(e) > 3 else e[1]) for e in pm)
 
     # HBM-bound classes: algorithmic limb-units per step (every operand read once, every result written once)
     hbm = {
@@ -505,10 +506,10 @@ def roofline_for(w, prof):
         "byte_planes": (w.d_in * 2 * L + (0 if "rescale_byte_planes" in prof else (w.d_mid or 0) * 2 * (L - 1))) * (8 + 7) / 8.0,
         "rescale_byte_planes": (w.d_mid or 0) * (2 * L + 2 * (L - 1) * 7 / 8.0),
         # plaintext multiplication, summed and rescaled (the few plaintext limbs are not counted)
-        "pm_fcols": pm_sum(lambda l, t, o: t * 4 * l),                      # source limbs in, column-transformed limbs out
-        "pm_frows_mac_irows": pm_sum(lambda l, t, o: (t + o) * 2 * l),      # those in, one sum per output limb out
-        "pm_icols_last": pm_sum(lambda l, t, o: o * 4),
-        "pm_icols_rescale": pm_sum(lambda l, t, o: o * (2 * (l - 1) + 2 + 2 * (l - 1))),
+        "pm_fcols": pm_sum(lambda l, t, o, src: src * 4 * l),                    # source limbs in, column-transformed limbs out
+        "pm_frows_mac_irows": pm_sum(lambda l, t, o, src: (t + o) * 2 * l),      # those in, one sum per output limb out
+        "pm_icols_last": pm_sum(lambda l, t, o, src: o * 4),
+        "pm_icols_rescale": pm_sum(lambda l, t, o, src: o * (2 * (l - 1) + 2 + 2 * (l - 1))),
     }
     members = {"ntt": ["ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols"]}
     classes = list(hbm) + ["accumulate", "accumulate_mfma"]

@@ -1422,8 +1422,9 @@ static int pt_prepare(ensi_ctx *ctx, const ensi_pt *pt, bool fused, hipStream_t 
 
 // out_o = Rescale(sum_{t in [begin[o], begin[o+1])} src_t (x) pt_t) for every output o; sources have l1 limbs at
 // stride limb_stride_in.  Outputs are handled in groups whose transformed sources fit a bounded workspace.
-static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms, const std::vector<int32_t> &begin, int l1, int limb_stride_in,
+static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms_in, const std::vector<int32_t> &begin, int l1, int limb_stride_in,
                       const ensi_pt *pt, ensi_ct *out, hipStream_t st) {
+    std::vector<PmTerm> terms(terms_in);  // the slots are filled in below
     const int N = ctx->N, n_out = (int)begin.size() - 1;
     if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "plaintext multiplication: no limb left to drop");
     if (pt->limbs < l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "plaintext has %d limbs, ciphertexts have %d", pt->limbs, l1);
@@ -1451,13 +1452,29 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms, const std
         need_b = std::max(need_b, (size_t)(o1 - o0));
         o0 = o1;
     }
+    // per group: its distinct sources, numbered in order of first use; a source that enters several products (one
+    // ciphertext under several masks) is transformed once
+    std::vector<int32_t> owner;
+    std::vector<size_t> owner_base(1, 0);
+    need_a = 1;
+    for (size_t k = 0; k + 1 < cut.size(); k++) {
+        std::map<const u64 *, int> slot;
+        for (int t = begin[cut[k]]; t < begin[cut[k + 1]]; t++) {
+            auto it = slot.emplace(terms[t].src, (int)slot.size());
+            if (it.second) owner.push_back(t);
+            terms[t].slot = it.first->second;
+        }
+        owner_base.push_back(owner.size());
+        need_a = std::max(need_a, slot.size());
+    }
     if ((rc = grow(ctx, &ctx->ws_pa, &ctx->ws_pa_words, need_a * term_words))) return rc;
     if ((rc = grow(ctx, &ctx->ws_pb, &ctx->ws_pb_words, need_b * term_words))) return rc;
     if ((rc = grow(ctx, &ctx->ws_pl, &ctx->ws_pl_words, need_b * 2 * N))) return rc;
-    const size_t tw = terms.size() * (sizeof(PmTerm) / 8), bw = (begin.size() + 1) / 2;
-    if ((rc = grow(ctx, &ctx->ws_pt, &ctx->ws_pt_words, tw + bw + 2))) return rc;
+    const size_t tw = terms.size() * (sizeof(PmTerm) / 8), bw = (begin.size() + 1) / 2, ow = (owner.size() + 1) / 2;
+    if ((rc = grow(ctx, &ctx->ws_pt, &ctx->ws_pt_words, tw + bw + ow + 2))) return rc;
     if (!terms.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt, terms.data(), terms.size() * sizeof(PmTerm), hipMemcpyHostToDevice, st));
     ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt + tw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
+    if (!owner.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt + tw + bw, owner.data(), owner.size() * 4, hipMemcpyHostToDevice, st));
 
     const u64 ql = ctx->primes[l1 - 1];
     PmRescale rs;
@@ -1483,6 +1500,8 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms, const std
         g.t_base = begin[o0];
         g.n_terms = begin[o1] - begin[o0];
         g.n_out = o1 - o0;
+        g.owner = (const int32_t *)(ctx->ws_pt + tw + bw) + owner_base[k];
+        g.n_src = (int)(owner_base[k + 1] - owner_base[k]);
         g.l1 = l1;
         g.limb_stride_in = limb_stride_in;
         g.pt = fused ? pt->d_fp : pt->d_mont;
@@ -1515,7 +1534,7 @@ extern "C" int ensi_pmult_sum_rescale(ensi_ctx *ctx, const ensi_ct *in, const en
         if (term_ct[t] < 0 || term_ct[t] >= in->n) ENSI_FAIL(ctx, ENSI_E_BADARG, "term %d names ciphertext %d of %d", t, term_ct[t], in->n);
         terms[t].src = in->d + (size_t)term_ct[t] * in_ct;
         terms[t].pt = term_pt[t];
-        terms[t].pad = 0;
+        terms[t].slot = 0;
     }
     std::vector<int32_t> b(begin, begin + n_out + 1);
     int rc;

@@ -68,7 +68,8 @@ struct Ks16Const {
 struct PmTerm {
     const u64 *src;
     int32_t pt;
-    int32_t pad;
+    int32_t slot;  // set by the library: which of its group's distinct sources this is (a source that enters several
+                   // products is transformed once)
 };
 // q_l^{-1} mod q_i and that divided by q_i, for the rescale that ends the fused plaintext multiplication
 struct PmRescale {
@@ -80,6 +81,8 @@ struct PmGroup {
     const PmTerm *terms;    // whole table
     const int32_t *begin;   // this group's slice of the offsets: n_out + 1 entries
     int t_base, n_terms, n_out;
+    const int32_t *owner;   // this group's distinct sources: owner[slot] = a term (index into the table) that names it
+    int n_src;
     int l1, limb_stride_in;
     const u64 *pt;          // d_mont or d_fp of the plaintext batch
     int pt_limbs;

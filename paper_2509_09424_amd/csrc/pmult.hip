@@ -35,12 +35,12 @@ __device__ __forceinline__ double pm_f64(u64 x) { return __longlong_as_double((l
 __device__ __forceinline__ u64 pm_u64(double x) { return (u64)__double_as_longlong(x); }
 
 // ===================================================================== generic path
-// grid (ceil(N/256), 2*l1, n_terms): ws_a[t][c*l1+i][N] <- limb i of component c of term t's source
+// grid (ceil(N/256), 2*l1, n_src): ws_a[slot][c*l1+i][N] <- limb i of component c of the group's distinct source `slot`
 __global__ __launch_bounds__(PM_THREADS) void k_pm_gather(PmGroup g, int N) {
     const int idx = blockIdx.x * PM_THREADS + threadIdx.x;
     if (idx >= N) return;
     const int y = blockIdx.y, c = y / g.l1, i = y - c * g.l1, t = blockIdx.z;
-    const u64 *src = g.terms[g.t_base + t].src + ((size_t)c * g.limb_stride_in + i) * N;
+    const u64 *src = g.terms[g.owner[t]].src + ((size_t)c * g.limb_stride_in + i) * N;
     g.ws_a[((size_t)t * 2 * g.l1 + y) * N + idx] = src[idx];
 }
 
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(PM_THREADS) void k_pm_mac(PmGroup g, int N, const P
     const int t0 = g.begin[o], t1 = g.begin[o + 1];
     u64 acc = 0;
     for (int t = t0; t < t1; t++) {
-        const u64 a = g.ws_a[((size_t)(t - g.t_base) * 2 * g.l1 + y) * N + idx];
+        const u64 a = g.ws_a[((size_t)g.terms[t].slot * 2 * g.l1 + y) * N + idx];
         const u64 b = g.pt[((size_t)g.terms[t].pt * g.pt_limbs + i) * N + idx];
         acc = add_mod(acc, mont_mul(a, b, q, qn), q);
     }
@@ -80,11 +80,11 @@ static LimbMap pm_map(int l1) {
 void launch_pm_generic(ensi_ctx *ctx, const PmGroup &g, const u64 *d_consts, const double *d_fconsts, hipStream_t st) {
     const int N = ctx->N, nb = (N + PM_THREADS - 1) / PM_THREADS;
     const LimbMap map = pm_map(g.l1);
-    if (g.n_terms > 0) {
+    if (g.n_src > 0) {
         ScopedTimer t(ctx, "pm_gather", st);
-        hipLaunchKernelGGL(k_pm_gather, dim3(nb, 2 * g.l1, g.n_terms), dim3(PM_THREADS), 0, st, g, N);
+        hipLaunchKernelGGL(k_pm_gather, dim3(nb, 2 * g.l1, g.n_src), dim3(PM_THREADS), 0, st, g, N);
     }
-    if (g.n_terms > 0) launch_ntt(ctx, g.ws_a, g.n_terms * 2 * g.l1, map, false, st);
+    if (g.n_src > 0) launch_ntt(ctx, g.ws_a, g.n_src * 2 * g.l1, map, false, st);
     {
         ScopedTimer t(ctx, "pm_mac", st);
         hipLaunchKernelGGL(k_pm_mac, dim3(nb, 2 * g.l1, g.n_out), dim3(PM_THREADS), 0, st, g, N, ctx->d_pc);
@@ -112,13 +112,13 @@ void launch_pm16_pt_format(ensi_ctx *ctx, const u64 *ntt_form, int n_rows, u64 *
     hipLaunchKernelGGL(k_pm16_pt_format, dim3(16, n_rows), dim3(PM_THREADS), 0, st, ntt_form, out);
 }
 
-// grid (16, 2*l1, n_terms)
+// grid (16, 2*l1, n_src)
 __global__ __launch_bounds__(PM_THREADS) void k_pm16_fcols(PmGroup g, const PrimeConst *pcs, const u64 *tw_all) {
     __shared__ u64 lds[4096];
     const int tid = threadIdx.x, c16 = tid & 15, jj = tid >> 4;
     const int y = blockIdx.y, c = y / g.l1, i = y - c * g.l1, t = blockIdx.z;
     const size_t col = (size_t)blockIdx.x * 16 + c16;
-    const u64 *src = g.terms[g.t_base + t].src + ((size_t)c * g.limb_stride_in + i) * PM_N + col;
+    const u64 *src = g.terms[g.owner[t]].src + ((size_t)c * g.limb_stride_in + i) * PM_N + col;
     u64 *out = g.ws_a + ((size_t)t * 2 * g.l1 + y) * PM_N + col;
     ArithFp ar;
     ar.init(pcs[i]);
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(PM_THREADS, PM_MAC_BLOCKS) void k_pm16_frows_mac_ir
     const size_t a_off = (size_t)y * PM_N + (size_t)r0 * 256 + rho * 256 + j;
     const size_t b_off = (size_t)i * PM_N + (size_t)tile * 4096 + tid;
     if (t0 < t1) {
-        const u64 *a = g.ws_a + (size_t)(t0 - g.t_base) * term + a_off;
+        const u64 *a = g.ws_a + (size_t)g.terms[t0].slot * term + a_off;
 #pragma unroll
         for (int k = 0; k < 16; k++) nv[k] = pm_f64(a[16 * k]);
     }
@@ -189,7 +189,6 @@ __global__ __launch_bounds__(PM_THREADS, PM_MAC_BLOCKS) void k_pm16_frows_mac_ir
     __syncthreads();
 #pragma unroll 1
     for (int t = t0; t < t1; t++) {
-        const u64 *a = g.ws_a + (size_t)(t - g.t_base) * term + a_off;
         const u64 *b = g.pt + (size_t)g.terms[t].pt * g.pt_limbs * PM_N + b_off;
         double v[16], w[16];
 #pragma unroll
@@ -197,8 +196,9 @@ __global__ __launch_bounds__(PM_THREADS, PM_MAC_BLOCKS) void k_pm16_frows_mac_ir
 #pragma unroll
         for (int k = 0; k < 16; k++) v[k] = nv[k];
         if (t + 1 < t1) {
+            const u64 *a = g.ws_a + (size_t)g.terms[t + 1].slot * term + a_off;
 #pragma unroll
-            for (int k = 0; k < 16; k++) nv[k] = pm_f64(a[term + 16 * k]);
+            for (int k = 0; k < 16; k++) nv[k] = pm_f64(a[16 * k]);
         }
         // forward row pass (the steps of rows_fwd_regs)
         pm_ct4_tab(ar, v, tab);
@@ -274,9 +274,9 @@ __global__ __launch_bounds__(PM_THREADS) void k_pm16_icols_rescale(PmGroup g, Pm
 }
 
 void launch_pm16(ensi_ctx *ctx, const PmGroup &g, const PmRescale &rs, hipStream_t st) {
-    if (g.n_terms > 0) {
+    if (g.n_src > 0) {
         ScopedTimer t(ctx, "pm_fcols", st);
-        hipLaunchKernelGGL(k_pm16_fcols, dim3(16, 2 * g.l1, g.n_terms), dim3(PM_THREADS), 0, st, g, ctx->d_pc, ctx->d_tw);
+        hipLaunchKernelGGL(k_pm16_fcols, dim3(16, 2 * g.l1, g.n_src), dim3(PM_THREADS), 0, st, g, ctx->d_pc, ctx->d_tw);
     }
     {
         ScopedTimer t(ctx, "pm_frows_mac_irows", st);

@@ -71,8 +71,10 @@ def test_segment_form_counts():
     # aligning rotations; fill groups and baby steps of K's operands, relinearisations, giant steps of 55 sums (Q's columns are moved outside)
     switches = 96 + (96 * 3 + 96 * 7 + 63 + 55)
     assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
-    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})
-    assert abs(roof["achieved"] - (96 * 4 * 16 + (1024 + 496) * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})  # 96 head-mask sources at 16 limbs, the 63 diagonals at 14 (each once)
+    assert abs(roof["achieved"] - (96 * 4 * 16 + 63 * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"pm_frows_mac_irows": (1.0, 1)})  # 96 + 1520 products read, 96 + 32 sums written
+    assert abs(roof["achieved"] - ((96 + 96) * 2 * 16 + (1024 + 496 + 32) * 2 * 14) * unit / 1e-3 / 1e9) < 1e-6
     # library transforms of the products: 96 * 8 operands (two polynomials of 15 limbs, two passes, in and out), 63 x 3 sums back
     _, roof = bench.roofline_for(w, {"ntt_fwd_cols": (1.0, 1)})
     assert abs(roof["achieved"] - 4 * (96 * 8 * 2 * 15 + 63 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
