@@ -1654,8 +1654,11 @@ extern "C" int ensi_ct_drop_limbs(ensi_ct *ct, int32_t limbs) {
 // handled in groups of at most one rotation chunk whose operand polynomials fit a bounded workspace.
 // a_pre: the a operands already hold their transform (limb stride l1): they are read in place.  rescale = false stops
 // after the relinearisation: the outputs keep l1 limbs and the product's scale.
+// grid_x, grid_y > 0: the caller states that output x * grid_y + y sums a_(j,x) (x) b_(j,y) over j, with every output's terms
+// in the same order of j; where the fp64 kernels apply and the outputs make one group, the tiled multiply-add is used.
 static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &terms, const std::vector<int32_t> &begin, int l1,
-                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st, bool a_pre = false, bool rescale = true) {
+                     int limb_stride_a, int limb_stride_b, ensi_ct *out, hipStream_t st, bool a_pre = false, bool rescale = true,
+                     int grid_x = 0, int grid_y = 0) {
     const int N = ctx->N, n_out = (int)begin.size() - 1, ext = l1 + ctx->K;
     if (l1 < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "ciphertext multiplication: no limb left to drop");
     if (out->limbs != (rescale ? l1 - 1 : l1))
@@ -1750,6 +1753,13 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
         g.n_out = cnt;
         g.l1 = l1;
         g.limbs_out = rescale ? l1 - 1 : l1;
+        g.grid_x = g.grid_y = 0;
+        bool even = grid_x > 0 && grid_y > 0 && cut.size() == 2 && grid_x * grid_y == n_out && ctx->ks16 && n_out > 0;
+        for (int o = 1; o < n_out && even; o++) even = begin[o + 1] - begin[o] == begin[1] - begin[0];
+        if (even && begin[1] > begin[0]) {
+            g.grid_x = grid_x;
+            g.grid_y = grid_y;
+        }
         g.ws_a = ctx->ws_ma;
         g.ws_d = ctx->ws_md;
         g.ws_e = ctx->ws_me;
@@ -2507,11 +2517,16 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
     giant.erase(std::unique(giant.begin(), giant.end()), giant.end());
     const int nT = (int)giant.size();
     auto giant_index = [&](int v) { return (int)(std::lower_bound(giant.begin(), giant.end(), v) - giant.begin()); };
-    // ws_rot: [rotated w: d (baby - 1)][rotated a: d (nT - 1)][rotated sums: n_diag], all at l2 limbs; the first stage
-    // (aligning rotations at l1 limbs) uses its start.  ws_rep: [segs: d][sums: n_diag].
+    // The sums are laid out as a grid: entry x * baby + y pairs giant step giant[x] with baby step y (amount giant[x] + y);
+    // where no diagonal has that amount (one entry when baby > 1) the entry is formed all the same and not used.
+    const int n_sum = nT * baby;
+    std::vector<int> diag_at(n_sum, -1);
+    for (int q = 0; q < n_diag; q++) diag_at[giant_index(t[q]) * baby + e1[q]] = q;
+    // ws_rot: [rotated w: d (baby - 1)][rotated a: d (nT - 1)][rotated sums: n_sum], all at l2 limbs; the first stage
+    // (aligning rotations at l1 limbs) uses its start.  ws_rep: [segs: d][sums: n_sum].
     const size_t n_w = (size_t)d * (baby - 1), n_a = a_given ? 0 : (size_t)d * (nT - 1);
-    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (n_w + n_a + n_diag) * seg_ct)))) return rc;
-    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, ((size_t)d + n_diag) * seg_ct))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rot, &ctx->ws_rot_words, std::max((size_t)d * 2 * l1 * N, (n_w + n_a + n_sum) * seg_ct)))) return rc;
+    if ((rc = grow(ctx, &ctx->ws_rep, &ctx->ws_rep_words, ((size_t)d + n_sum) * seg_ct))) return rc;
     ensi_ct seg;
     seg.ctx = ctx;
     seg.owns = false;
@@ -2529,57 +2544,58 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
     if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, seg.d, seg_ct, l2, d, l2, jobs, st))) return rc;
     jobs.clear();
     std::vector<int> a_slot(nT, -1);  // position of each nonzero giant step among the rotated copies of a column
-    for (int gi = 0, k = 0; gi < nT; gi++)
+    int x_plain = 0;                  // the grid row without a giant step
+    for (int gi = 0, k = 0; gi < nT; gi++) {
         if (giant[gi]) a_slot[gi] = k++;
+        else x_plain = gi;
+    }
     for (int j = 0; j < d && !a_given; j++)
         for (int gi = 0; gi < nT; gi++)
             if (giant[gi]) jobs.push_back({j, -giant[gi], a_rot + ((size_t)j * (nT - 1) + a_slot[gi]) * seg_ct});
     if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, A->d, a_ct, A->limbs_alloc, d, l2, jobs, st))) return rc;
-    // the diagonals: relinearised sums at the product's scale, those without a giant step first (the rotated columns of
-    // A have limb stride l2, the unrotated ones A's own)
+    // the sums: relinearised, at the product's scale (the rotated columns of A have limb stride l2, the unrotated ones A's own)
     ensi_ct sums = seg;
-    sums.n = n_diag;
+    sums.n = n_sum;
     sums.d = ctx->ws_rep + (size_t)d * seg_ct;
     sums.scale = A->scale * seg.scale;
-    std::vector<int> order;
-    for (int q = 0; q < n_diag; q++)
-        if (!t[q]) order.push_back(q);
-    const int n_plain = (int)order.size();
-    for (int q = 0; q < n_diag; q++)
-        if (t[q]) order.push_back(q);
     {
         std::vector<MmTerm> terms;
         std::vector<int32_t> begin(1, 0);
-        for (int k = 0; k < n_diag; k++) {
-            const int q = order[k];
-            for (int j = 0; j < d; j++) {
-                MmTerm tm;
-                if (a_given) {
-                    tm.a = A->d + ((size_t)j * nT + giant_index(t[q])) * a_ct;
-                    tm.stride_a = A->limbs_alloc;
-                } else {
-                    tm.a = t[q] ? a_rot + ((size_t)j * (nT - 1) + a_slot[giant_index(t[q])]) * seg_ct : A->d + (size_t)j * a_ct;
-                    tm.stride_a = t[q] ? l2 : A->limbs_alloc;
+        for (int x = 0; x < nT; x++)
+            for (int y = 0; y < baby; y++) {
+                for (int j = 0; j < d; j++) {
+                    MmTerm tm;
+                    if (a_given) {
+                        tm.a = A->d + ((size_t)j * nT + x) * a_ct;
+                        tm.stride_a = A->limbs_alloc;
+                    } else {
+                        tm.a = giant[x] ? a_rot + ((size_t)j * (nT - 1) + a_slot[x]) * seg_ct : A->d + (size_t)j * a_ct;
+                        tm.stride_a = giant[x] ? l2 : A->limbs_alloc;
+                    }
+                    tm.b = y ? w_rot + ((size_t)j * (baby - 1) + (y - 1)) * seg_ct : seg.d + (size_t)j * seg_ct;
+                    terms.push_back(tm);
                 }
-                tm.b = e1[q] ? w_rot + ((size_t)j * (baby - 1) + (e1[q] - 1)) * seg_ct : seg.d + (size_t)j * seg_ct;
-                terms.push_back(tm);
+                begin.push_back((int32_t)terms.size());
             }
-            begin.push_back((int32_t)terms.size());
-        }
-        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &sums, st, A->prepared, false))) return rc;
+        if ((rc = mult_core(ctx, key, terms, begin, l2, A->limbs_alloc, l2, &sums, st, A->prepared, false, nT, baby))) return rc;
     }
-    // giant steps of the sums, then the rescale of every diagonal (in place; limb stride l2)
+    // giant steps of the sums, then the rescale of every diagonal (in place; limb stride l2): the row without a giant step
+    // where it is, the rows before and after it in their rotated copies
     jobs.clear();
-    for (int k = n_plain; k < n_diag; k++) jobs.push_back({k, t[order[k]], s_rot + (size_t)k * seg_ct});
-    if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, sums.d, seg_ct, l2, n_diag, l2, jobs, st))) return rc;
+    for (int k = 0; k < n_sum; k++)
+        if (diag_at[k] >= 0 && giant[k / baby]) jobs.push_back({k, giant[k / baby], s_rot + (size_t)k * seg_ct});
+    if (!jobs.empty() && (rc = rotate_jobs(ctx, gk, sums.d, seg_ct, l2, n_sum, l2, jobs, st))) return rc;
     const u64 *d_consts;
     const double *d_fconsts;
     bool fp;
     if ((rc = upload_rescale_consts(ctx, l2, 1.0, false, st, &d_consts, &d_fconsts, &fp))) return rc;
-    if (n_plain) launch_rescale(ctx, sums.d, n_plain, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
-    if (n_diag > n_plain) launch_rescale(ctx, s_rot + (size_t)n_plain * seg_ct, n_diag - n_plain, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+    launch_rescale(ctx, sums.d + (size_t)x_plain * baby * seg_ct, baby, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+    if (x_plain > 0) launch_rescale(ctx, s_rot, x_plain * baby, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
+    if (x_plain + 1 < nT)
+        launch_rescale(ctx, s_rot + (size_t)(x_plain + 1) * baby * seg_ct, (nT - x_plain - 1) * baby, l2, l2, d_consts, fp ? d_fconsts : nullptr, st);
     std::vector<const u64 *> diag(n_diag);
-    for (int k = 0; k < n_diag; k++) diag[order[k]] = k < n_plain ? sums.d + (size_t)k * seg_ct : s_rot + (size_t)k * seg_ct;
+    for (int k = 0; k < n_sum; k++)
+        if (diag_at[k] >= 0) diag[diag_at[k]] = (giant[k / baby] ? s_rot : sums.d) + (size_t)k * seg_ct;
     const double diag_scale = sums.scale / (double)ctx->primes[l2 - 1];
     // sorting: slot x of D_e holds column (x + e) mod P; column c takes the class r = (c - e) mod P of D_e, and from D'_e
     // where that class meets the last e slots of a block

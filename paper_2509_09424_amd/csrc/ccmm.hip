@@ -13,6 +13,7 @@
 // steps of the element replication).  Transforms, key switch, rescale and the final strided copy are the
 // library's existing kernels.
 #include "common.h"
+#include "ntt16_core.h"
 
 #define MM_THREADS 256
 
@@ -50,6 +51,80 @@ __global__ __launch_bounds__(MM_THREADS) void k_mm_tensor_mac(MmGroup g, int N, 
     out[0] = mont_mul(d0, pc.r2, q, qn);
     out[poly] = mont_mul(d2, pc.r2, q, qn);
     out[2 * poly] = mont_mul(d1, pc.r2, q, qn);
+}
+
+// The same sums for outputs that form a grid (MmGroup.grid_x, grid_y), primes below 2^50: a block forms a tile of 4 x 2
+// outputs for 256 words of one limb, so that every operand word it reads enters 2 or 4 products (the plain kernel reads
+// four operand words per product, most of them again and again for other outputs), and multiplies in fp64 on exact
+// integers.  grid (ceil(N/256), l1, tiles_x * tiles_y).
+#define MM_TX 4
+#define MM_TY 2
+__global__ __launch_bounds__(MM_THREADS) void k_mm_grid_mac_fp(MmGroup g, int N, const PrimeConst *pcs) {
+    const int idx = blockIdx.x * MM_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int i = blockIdx.y;
+    const int tiles_y = (g.grid_y + MM_TY - 1) / MM_TY;
+    const int x0 = (blockIdx.z / tiles_y) * MM_TX, y0 = (blockIdx.z % tiles_y) * MM_TY;
+    ArithFp ar;
+    ar.init(pcs[i]);
+    const double half = 0.5 * ar.p;
+    const size_t poly = (size_t)g.l1 * N, off = (size_t)i * N + idx;
+    const int J = g.begin[1] - g.begin[0];
+    // term j of output (x, y0) names the left operand of row x, term j of output (x0, y) the right operand of column y
+    const MmPair *pa[MM_TX], *pb[MM_TY];
+#pragma unroll
+    for (int x = 0; x < MM_TX; x++) pa[x] = g.pairs + (g.begin[(x0 + x < g.grid_x ? x0 + x : x0) * g.grid_y + y0] - g.t_base);
+#pragma unroll
+    for (int y = 0; y < MM_TY; y++) pb[y] = g.pairs + (g.begin[x0 * g.grid_y + (y0 + y < g.grid_y ? y0 + y : y0)] - g.t_base);
+    double d0[MM_TX][MM_TY], d1[MM_TX][MM_TY], d2[MM_TX][MM_TY];
+#pragma unroll
+    for (int x = 0; x < MM_TX; x++)
+#pragma unroll
+        for (int y = 0; y < MM_TY; y++) d0[x][y] = d1[x][y] = d2[x][y] = 0.0;
+    for (int j = 0; j < J; j++) {
+        double a0[MM_TX], a1[MM_TX], b0[MM_TY], b1[MM_TY];
+#pragma unroll
+        for (int x = 0; x < MM_TX; x++) {
+            const u64 *p = g.ops[pa[x][j].a].t + off;
+            const double v0 = (double)p[0], v1 = (double)p[poly];
+            a0[x] = v0 > half ? v0 - ar.p : v0;  // the left factor centred: |a| <= p/2
+            a1[x] = v1 > half ? v1 - ar.p : v1;
+        }
+#pragma unroll
+        for (int y = 0; y < MM_TY; y++) {
+            const u64 *p = g.ops[pb[y][j].b].t + off;
+            b0[y] = (double)p[0];
+            b1[y] = (double)p[poly];
+        }
+#pragma unroll
+        for (int x = 0; x < MM_TX; x++)
+#pragma unroll
+            for (int y = 0; y < MM_TY; y++) {
+                d0[x][y] += ar.mulmod_np(a0[x], b0[y]);
+                d1[x][y] += ar.mulmod_np(a0[x], b1[y]) + ar.mulmod_np(a1[x], b0[y]);
+                d2[x][y] += ar.mulmod_np(a1[x], b1[y]);
+            }
+        if ((j & 3) == 3) {
+#pragma unroll
+            for (int x = 0; x < MM_TX; x++)
+#pragma unroll
+                for (int y = 0; y < MM_TY; y++) {
+                    d0[x][y] = ar.mid(d0[x][y]);
+                    d1[x][y] = ar.mid(d1[x][y]);
+                    d2[x][y] = ar.mid(d2[x][y]);
+                }
+        }
+    }
+#pragma unroll
+    for (int x = 0; x < MM_TX; x++)
+#pragma unroll
+        for (int y = 0; y < MM_TY; y++) {
+            if (x0 + x >= g.grid_x || y0 + y >= g.grid_y) continue;
+            u64 *out = g.ws_d + ((size_t)((x0 + x) * g.grid_y + y0 + y) * 3 * g.l1 + i) * N + idx;
+            out[0] = ar.canon(d0[x][y]);
+            out[poly] = ar.canon(d2[x][y]);
+            out[2 * poly] = ar.canon(d1[x][y]);
+        }
 }
 
 // grid (ceil(N/256), l1, n_out): ws_e[o][1][i] += ws_d[o][2][i]  (d1 joins the second polynomial)
@@ -105,7 +180,12 @@ void launch_mm_tensor(ensi_ctx *ctx, const MmGroup &g, hipStream_t st) {
     }
     {
         ScopedTimer t(ctx, "mm_tensor_mac", st);
-        hipLaunchKernelGGL(k_mm_tensor_mac, dim3(nb, g.l1, g.n_out), dim3(MM_THREADS), 0, st, g, N, ctx->d_pc);
+        if (g.grid_x > 0) {
+            const int tiles = ((g.grid_x + MM_TX - 1) / MM_TX) * ((g.grid_y + MM_TY - 1) / MM_TY);
+            hipLaunchKernelGGL(k_mm_grid_mac_fp, dim3(nb, g.l1, tiles), dim3(MM_THREADS), 0, st, g, N, ctx->d_pc);
+        } else {
+            hipLaunchKernelGGL(k_mm_tensor_mac, dim3(nb, g.l1, g.n_out), dim3(MM_THREADS), 0, st, g, N, ctx->d_pc);
+        }
     }
     launch_ntt(ctx, g.ws_d, g.n_out * 3 * g.l1, map, true, st);
 }

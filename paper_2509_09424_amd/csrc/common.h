@@ -117,6 +117,8 @@ struct MmGroup {
     int t_base, n_terms, n_ops, n_out;
     int l1;
     int limbs_out;  // limbs copied to the output: l1 - 1 after the rescale, l1 without it
+    int grid_x, grid_y;  // > 0: output x * grid_y + y sums, over j, a_(j,x) (x) b_(j,y): every output has the same number of
+                         // terms in the same order, and outputs of a row share their left, of a column their right operands
     u64 *ws_a;   // [n_ops][2][l1][N] operand polynomials (transformed in place)
     u64 *ws_d;   // [n_out][3][l1][N]   d0, d2, d1: (d0, d2) is laid out like a ciphertext for the key switch
     u64 *ws_e;   // [n_out][2][l1][N]   relinearised product

@@ -483,10 +483,12 @@ def test_ccmm_segment_small_ring(params, l1, s, period, baby, d, g):
     p.close()
 
 
-def test_ccmm_segment_full_ring():
-    """N = 2^16 (fused kernels), 16 heads of 2048 tokens, period 4 in baby steps of 2, a narrow inner dimension and a low level."""
+@pytest.mark.parametrize("period,baby,g", [(4, 2, 511), (4, 1, 0), (8, 4, 255)], ids=["grid-4x2", "grid-7x1", "grid-4x4"])
+def test_ccmm_segment_full_ring(period, baby, g):
+    """N = 2^16 (fused kernels, the tiled multiply-add over the grid of giant and baby steps: one whole tile, a ragged
+    one, several), 16 heads of 2048 tokens, a narrow inner dimension and a low level."""
     p = Pair(KEYSWITCH)
-    l1, s, period, baby, d, g = 5, 2048, 4, 2, 2, 511
+    l1, s, d = 5, 2048, 2
     o_a, g_a, o_b, g_b, o_gks, g_gk, mh, ms, ref = segment_case(p, l1, s, period, baby, d, g)
     o_rk, g_rk = relin_keys(p)
     out = p.ctx.ccmm_segment(g_rk, g_gk, g_a, g_b, s, period, baby, g, mh, ms)
