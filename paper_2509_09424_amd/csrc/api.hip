@@ -1006,6 +1006,7 @@ static int ensure_desc(ensi_ctx *ctx, size_t n) {
 
 extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream) {
     if (!ctx || !gk || !in || !steps || !out) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (in->n != out->n) ENSI_FAIL(ctx, ENSI_E_SHAPE, "rotate: batch sizes differ (%d vs %d)", in->n, out->n);
     if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rotate: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "rotate: in and out must not overlap");
@@ -1182,6 +1183,7 @@ extern "C" int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode) {
 extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
                                    int32_t m, int32_t placement, ensi_ct *out, void *stream) {
     if (!ctx || !in || !W || !out || s < 1 || d < 1 || m < 1) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (placement != ENSI_PLACE_ZERO && placement != ENSI_PLACE_DIAGONAL) ENSI_FAIL(ctx, ENSI_E_BADARG, "unknown placement %d", placement);
     const int N = ctx->N, n_slots = N / 2;
     if (n_slots % s) ENSI_FAIL(ctx, ENSI_E_SHAPE, "tokens per column (%d) must divide the slot count %d", s, n_slots);
@@ -1522,6 +1524,7 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms_in, const 
 extern "C" int ensi_pmult_sum_rescale(ensi_ctx *ctx, const ensi_ct *in, const ensi_pt *pt, const int32_t *begin, const int32_t *term_ct,
                                       const int32_t *term_pt, int32_t n_out, ensi_ct *out, void *stream) {
     if (!ctx || !in || !pt || !begin || !out || n_out < 1) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (begin[0] != 0) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must start at 0");
     for (int o = 0; o < n_out; o++)
         if (begin[o + 1] < begin[o]) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must not decrease");
@@ -1553,6 +1556,7 @@ extern "C" int ensi_block_masks(ensi_ctx *ctx, int32_t s, int32_t c_tot, int32_t
 
 extern "C" int ensi_merge(ensi_ctx *ctx, const ensi_ct *in, const ensi_pt *masks, int32_t c_tot, ensi_ct *out, void *stream) {
     if (!ctx || !in || !masks || !out || c_tot < 1) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (masks->n < c_tot) ENSI_FAIL(ctx, ENSI_E_SHAPE, "merge: %d masks for %d blocks", masks->n, c_tot);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "merge: in and out must not overlap");
     const int n_out = (in->n + c_tot - 1) / c_tot;
@@ -1582,6 +1586,7 @@ extern "C" int ensi_rope_plaintexts(ensi_ctx *ctx, const double *cos_v, const do
 
 extern "C" int ensi_rope(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const ensi_pt *pt, ensi_ct *out, void *stream) {
     if (!ctx || !gk || !in || !pt || !out) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (pt->n < 3) ENSI_FAIL(ctx, ENSI_E_SHAPE, "rope: the plaintext batch must hold cos, neg*sin and pos*sin");
     if (in->n != out->n) ENSI_FAIL(ctx, ENSI_E_SHAPE, "rope: batch sizes differ (%d vs %d)", in->n, out->n);
     if (in->limbs < 2 || out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rope: output must be one level below the input");
@@ -1799,6 +1804,7 @@ static int relin_key(ensi_ctx *ctx, const ensi_gk *rk, const u64 **key) {
 extern "C" int ensi_mult_sum_relin_rescale(ensi_ctx *ctx, const ensi_gk *rk, const ensi_ct *a, const ensi_ct *b, const int32_t *begin,
                                            const int32_t *term_a, const int32_t *term_b, int32_t n_out, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !a || !b || !begin || !out || n_out < 1) return ENSI_E_BADARG;
+    if (a->prepared || b->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (a->limbs != b->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "operands at different levels (%d vs %d limbs)", a->limbs, b->limbs);
     if (begin[0] != 0) ENSI_FAIL(ctx, ENSI_E_BADARG, "term offsets must start at 0");
     for (int o = 0; o < n_out; o++)
@@ -1948,6 +1954,7 @@ static int replicate_core(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, c
 extern "C" int ensi_replicate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *src, const ensi_pt *masks,
                               const int32_t *mask_idx, int32_t n_out, ensi_ct *out, void *stream) {
     if (!ctx || !gk || !in || !src || !masks || !mask_idx || !out || n_out < 1) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (in->limbs < 2 || out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "replicate: output must be one level below the input");
     if (out->n != n_out) ENSI_FAIL(ctx, ENSI_E_SHAPE, "replicate: output batch holds %d ciphertexts, need %d", out->n, n_out);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "replicate: in and out must not overlap");
@@ -1971,6 +1978,7 @@ extern "C" int ensi_periodic_masks(ensi_ctx *ctx, int32_t period, int32_t count,
 extern "C" int ensi_ccmm(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, const ensi_pt *masks,
                          int32_t period, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !masks || !out) return ENSI_E_BADARG;
+    if (A->prepared || B->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     const int N = ctx->N, d = A->n, m = B->n, l1 = B->limbs;
     if (period < 1 || (period & (period - 1)) || period > N / 2 || period < d)
         ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two between the inner dimension %d and %d", d, N / 2);
@@ -2107,6 +2115,7 @@ static int rotate_columns(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *B, co
 extern "C" int ensi_ccmm_blocks(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *A, const ensi_ct *B, int32_t s,
                                 const int32_t *cols, int32_t n_cols, const ensi_pt *mask, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !cols || !mask || !out || n_cols < 1) return ENSI_E_BADARG;
+    if (A->prepared || B->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     const int N = ctx->N, d = A->n, l1 = B->limbs;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (B->n != d) ENSI_FAIL(ctx, ENSI_E_SHAPE, "ccmm: A has %d columns, B has %d rows", d, B->n);
@@ -2279,6 +2288,7 @@ extern "C" int ensi_ccmm_bsgs(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *g
                               int32_t period, const int32_t *begin, const int32_t *term_a, const int32_t *term_b, const int32_t *term_slot,
                               int32_t n_out, const ensi_pt *mask_head, const ensi_pt *mask_start, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !begin || !mask_head || !mask_start || !out || n_out < 1) return ENSI_E_BADARG;
+    if (A->prepared || B->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     const int N = ctx->N, l1 = B->limbs;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (period < 1 || (period & (period - 1)) || period > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
@@ -2487,6 +2497,7 @@ extern "C" int ensi_ccmm_segment(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk
                                  int32_t period, int32_t baby, int32_t g, const ensi_pt *mask_head, const ensi_pt *masks, ensi_ct *out,
                                  void *stream) {
     if (!ctx || !rk || !gk || !A || !B || !mask_head || !masks || !out) return ENSI_E_BADARG;
+    if (B->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     const int N = ctx->N, d = B->n, l1 = B->limbs, P = period;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");
@@ -2684,6 +2695,7 @@ extern "C" int ensi_diagonalise_weights(ensi_ctx *ctx, const ensi_gk *gk, const 
 extern "C" int ensi_ccmm_av(ensi_ctx *ctx, const ensi_gk *rk, const ensi_gk *gk, const ensi_ct *Ad, const ensi_ct *V, int32_t s, int32_t period,
                             int32_t baby, int32_t g0, const ensi_pt *mask_head, ensi_ct *out, void *stream) {
     if (!ctx || !rk || !gk || !Ad || !V || !mask_head || !out) return ENSI_E_BADARG;
+    if (V->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     const int N = ctx->N, P = period, l1 = V->limbs, m = V->n;
     if (s < 1 || (s & (s - 1)) || s > N / 2) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the block length must be a power of two up to %d", N / 2);
     if (P < 1 || (P & (P - 1)) || P > s) ENSI_FAIL(ctx, ENSI_E_BADARG, "ccmm: the period must be a power of two up to the block length");

@@ -561,6 +561,8 @@ def test_ccmm_av_small_ring(params, l1, s, period, baby, g0, n_seg, m):
     assert np.array_equal(outp.export(), stack_cts(want))
     with pytest.raises(p.binding.EnsiError, match="code -1"):
         adp.export()
+    with pytest.raises(p.binding.EnsiError, match="code -1"):
+        p.ctx.mult_sum_relin_rescale(g_rk, adp, adp, [0, 1], [0], [0])  # prepared weights are no ciphertexts
     adp.free()
     outp.free()
     lh, ls = p.ctx.block_head_mask(s, period, l1), p.ctx.segment_masks(s, period, l1)
