@@ -121,10 +121,13 @@ class Runner:
         if w.op == "ccmm_av":
             # weights times V from diagonalised weights: d_in tokens = d_in / period segments, d_out columns of V
             import torch
-            sl, P, d, m = w.tokens, w.period, w.d_in, w.d_out
+            sl, P, m = w.tokens, w.period, w.d_out
+            d = -(-w.d_in // P) * P  # whole segments: columns of A beyond d_in are zero, as are the entries of V they meet
             heads = self.n // sl
             self.Wt = rng.uniform(-1.0, 1.0, size=(heads, sl, d)) / 16
+            self.Wt[:, :, w.d_in:] = 0.0
             self.V = rng.uniform(-1.0, 1.0, size=(heads, sl, m))
+            self.V[:, w.d_in:, :] = 0.0
             za = np.stack([np.concatenate([self.Wt[h][:, j] for h in range(heads)]) for j in range(d)])
             zb = np.stack([np.concatenate([self.V[h][:, i] for h in range(heads)]) for i in range(m)])
             self.ref = np.stack([np.concatenate([self.Wt[h] @ self.V[h][:d, i] for h in range(heads)]) for i in range(m)])
@@ -441,7 +444,7 @@ def roofline_for(w, prof):
     elif w.op == "ccmm_av":
         # per column of V and segment: one giant step (aligning rotation at the top level, head mask, fill over the block one
         # level down) and 2P-2 rotations of the spread operand on one raise; one relinearisation per output
-        P, n_seg, m, baby = w.period, w.d_in // w.period, w.d_out, w.baby
+        P, n_seg, m, baby = w.period, -(-w.d_in // w.period), w.d_out, w.baby
         g_rot, g_raise = fill_counts(P, w.tokens)
         n_sg, n_t = n_seg * m, 2 * P // baby  # spread operands; giant steps (sums per output)
         ks.append((L, n_sg, m, n_sg, n_seg))
@@ -604,7 +607,7 @@ def cpu_baseline(w, budget_s=12.0):
         elif w.op == "ccmm_blocks":
             n_rot = n_el * (1 + fill_counts(1, w.tokens)[0])
         elif w.op == "ccmm_av":
-            n_diag, n_sg = 2 * w.period - 1, w.d_in // w.period * w.d_out
+            n_diag, n_sg = 2 * w.period - 1, -(-w.d_in // w.period) * w.d_out
             n_rot = n_sg * (1 + fill_counts(w.period, w.tokens)[0] + w.baby - 1) + (2 * w.period // w.baby - 1) * w.d_out
             n_el = n_sg * n_diag
             n_pm = n_sg

@@ -538,8 +538,9 @@ def av_case(p, l1, s, period, baby, g0, n_seg, m):
 
 
 @pytest.mark.parametrize("params,l1,s,period,baby,g0,n_seg,m", [(SMALL4, 5, 32, 4, 2, 0, 8, 2), (SMALL4, 4, 64, 8, 8, 2, 3, 3),
-                                                                (SMALL4, 4, 64, 8, 1, 1, 2, 1), (WIDE, 4, 128, 16, 4, 5, 2, 1)],
-                         ids=["whole-block", "some-segments-baby-steps-only", "giant-steps-only", "wide-primes"])
+                                                                (SMALL4, 4, 64, 8, 1, 1, 2, 1), (WIDE, 4, 128, 16, 4, 5, 2, 1),
+                                                                (SMALL4, 4, 512, 8, 2, 0, 1, 2)],
+                         ids=["whole-block", "some-segments-baby-steps-only", "giant-steps-only", "wide-primes", "one-head-one-segment"])
 def test_ccmm_av_small_ring(params, l1, s, period, baby, g0, n_seg, m):
     """Diagonalised weights and the weights-times-V product: bit-exact against the oracle, numpy after decryption;
     the library's own masks give the same product within the bound."""
