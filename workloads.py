@@ -105,9 +105,9 @@ WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048
                           baby=8))
 # The ccmm96 shape (one head of 32768 tokens per ciphertext, inner width 96) through the weights-times-V entry point: the
 # inner index is the slot index of B's columns, so A's 96 columns (padded to one segment of 128) are diagonalised once
-# and every column of B costs one giant step of the extraction, 15 baby-step rotations and 255 products.
+# and every column of B costs one giant step of the extraction, 31 baby-step rotations and 255 products.
 WORKLOADS.append(Workload("ccmm96av", 16, 16, 50, 16, 60, 4, 4, 40, tokens=32768, d_in=96, d_out=8, act="uniform", op="ccmm_av", period=128,
-                          baby=16))
+                          baby=32))
 BY_NAME = {w.name: w for w in WORKLOADS}
 
 # key-switch microbench: steps 2^0..2^14 plus the inverse rotation -1
