@@ -1438,36 +1438,39 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms_in, const 
     int rc;
     if ((rc = pt_prepare(ctx, pt, fused, st))) return rc;
 
-    // groups of outputs: at most 8 GiB of transformed sources, at least one output
+    // groups of outputs: at most 8 GiB of transformed sources and of sums, at least one output.  Per group its distinct
+    // sources are numbered in order of first use: a source that enters several products (one ciphertext under several
+    // masks) is transformed once.
     const size_t term_words = (size_t)2 * l1 * N;
-    // a group's terms index one grid dimension of the transform kernels (at most 65535)
-    const int max_terms = (int)std::min<size_t>(65535, std::max<size_t>(1, ((size_t)1 << 30) / term_words));
+    // a group's sources index one grid dimension of the transform kernels (at most 65535)
+    const size_t max_src = std::min<size_t>(65535, std::max<size_t>(1, ((size_t)1 << 30) / term_words));
     for (int o = 0; o < n_out; o++)
         if (begin[o + 1] - begin[o] > 65535) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output %d sums %d products, at most 65535", o, begin[o + 1] - begin[o]);
     std::vector<int> cut(1, 0);
-    size_t need_a = 1, need_b = 0;
-    for (int o0 = 0; o0 < n_out;) {
-        int o1 = o0 + 1;
-        while (o1 < n_out && begin[o1 + 1] - begin[o0] <= max_terms && o1 - o0 < 16384) o1++;
-        cut.push_back(o1);
-        need_a = std::max(need_a, (size_t)(begin[o1] - begin[o0]));
-        need_b = std::max(need_b, (size_t)(o1 - o0));
-        o0 = o1;
-    }
-    // per group: its distinct sources, numbered in order of first use; a source that enters several products (one
-    // ciphertext under several masks) is transformed once
     std::vector<int32_t> owner;
     std::vector<size_t> owner_base(1, 0);
-    need_a = 1;
-    for (size_t k = 0; k + 1 < cut.size(); k++) {
+    size_t need_a = 1, need_b = 0;
+    for (int o0 = 0; o0 < n_out;) {
         std::map<const u64 *, int> slot;
-        for (int t = begin[cut[k]]; t < begin[cut[k + 1]]; t++) {
-            auto it = slot.emplace(terms[t].src, (int)slot.size());
-            if (it.second) owner.push_back(t);
-            terms[t].slot = it.first->second;
+        int o1 = o0;
+        for (; o1 < n_out && (size_t)(o1 - o0) < max_src; o1++) {
+            if (o1 > o0) {  // would this output's new sources still fit?
+                std::set<const u64 *> fresh;
+                for (int t = begin[o1]; t < begin[o1 + 1]; t++)
+                    if (!slot.count(terms[t].src)) fresh.insert(terms[t].src);
+                if (slot.size() + fresh.size() > max_src) break;
+            }
+            for (int t = begin[o1]; t < begin[o1 + 1]; t++) {
+                auto it = slot.emplace(terms[t].src, (int)slot.size());
+                if (it.second) owner.push_back(t);
+                terms[t].slot = it.first->second;
+            }
         }
+        cut.push_back(o1);
         owner_base.push_back(owner.size());
         need_a = std::max(need_a, slot.size());
+        need_b = std::max(need_b, (size_t)(o1 - o0));
+        o0 = o1;
     }
     if ((rc = grow(ctx, &ctx->ws_pa, &ctx->ws_pa_words, need_a * term_words))) return rc;
     if ((rc = grow(ctx, &ctx->ws_pb, &ctx->ws_pb_words, need_b * term_words))) return rc;
@@ -1674,7 +1677,8 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
     // groups of outputs: at most 24 GiB of transformed operands (a group's distinct operand ciphertexts, by address:
     // one that enters several products is gathered and transformed once), at most 65535 products, at least one output
     const size_t max_ops = std::max<size_t>(2, ((size_t)3 << 30) / ((size_t)2 * l1 * N));
-    const int max_out = ctx->ks16 ? rot_chunk() : 64;
+    // (a grid of up to 256 outputs is kept in one group, so that the tiled multiply-add applies)
+    const int max_out = (grid_x > 0 && grid_x * grid_y == n_out && n_out <= 256) ? std::max(n_out, 64) : ctx->ks16 ? rot_chunk() : 64;
     if (a_pre && limb_stride_a != l1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "prepared operands have %d limbs, the product runs at %d", limb_stride_a, l1);
     std::vector<int> cut(1, 0);
     std::vector<MmOperand> ops;

@@ -64,20 +64,20 @@ def test_giant_and_baby_step_counts():
 
 
 def test_segment_form_counts():
-    w = wl.BY_NAME["ccmmqkseg"]  # 96 ciphertexts of K and of Q, period 32 in baby steps of 4: 63 diagonals, 16 giant steps
-    assert (w.period, w.baby, w.d_out) == (32, 4, 32) and bench.fill_counts(32, 2048) == (9, 3)
+    w = wl.BY_NAME["ccmmqkseg"]  # 96 ciphertexts of K and of Q, period 64 in baby steps of 4: 127 diagonals, 32 giant steps
+    assert (w.period, w.baby, w.d_out) == (64, 4, 64) and bench.fill_counts(64, 2048) == (7, 3)
     unit = 8.0 * w.N
     _, roof = bench.roofline_for(w, {"ks_icols_special": (1.0, 1)})
-    # aligning rotations; fill groups and baby steps of K's operands, relinearisations, giant steps of 59 sums (Q's columns are moved outside)
-    switches = 96 + (96 * 3 + 96 * 3 + 63 + 59)
+    # aligning rotations; fill groups and baby steps of K's operands, relinearisations, giant steps of 123 sums (Q's columns are moved outside)
+    switches = 96 + (96 * 3 + 96 * 3 + 127 + 123)
     assert abs(roof["achieved"] - switches * 4 * 4 * unit / 1e-3 / 1e9) < 1e-6
-    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})  # 96 head-mask sources at 16 limbs, the 63 diagonals at 14 (each once)
-    assert abs(roof["achieved"] - (96 * 4 * 16 + 63 * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
-    _, roof = bench.roofline_for(w, {"pm_frows_mac_irows": (1.0, 1)})  # 96 + 1520 products read, 96 + 32 sums written
-    assert abs(roof["achieved"] - ((96 + 96) * 2 * 16 + (1024 + 496 + 32) * 2 * 14) * unit / 1e-3 / 1e9) < 1e-6
-    # library transforms of the products: 96 * 4 operands (two polynomials of 15 limbs, two passes, in and out), 63 x 3 sums back
+    _, roof = bench.roofline_for(w, {"pm_fcols": (1.0, 1)})  # 96 head-mask sources at 16 limbs, the 127 diagonals at 14 (each once)
+    assert abs(roof["achieved"] - (96 * 4 * 16 + 127 * 4 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    _, roof = bench.roofline_for(w, {"pm_frows_mac_irows": (1.0, 1)})  # 96 + 6112 products read, 96 + 64 sums written
+    assert abs(roof["achieved"] - ((96 + 96) * 2 * 16 + (4096 + 2016 + 64) * 2 * 14) * unit / 1e-3 / 1e9) < 1e-6
+    # library transforms of the products: 96 * 4 operands (two polynomials of 15 limbs, two passes, in and out), 127 x 3 sums back
     _, roof = bench.roofline_for(w, {"ntt_fwd_cols": (1.0, 1)})
-    assert abs(roof["achieved"] - 4 * (96 * 4 * 2 * 15 + 63 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
+    assert abs(roof["achieved"] - 4 * (96 * 4 * 2 * 15 + 127 * 3 * 15) * unit / 1e-3 / 1e9) < 1e-6
     w = wl.BY_NAME["ccmmavseg"]  # one column of V, 16 segments of 32 tokens
     _, roof = bench.roofline_for(w, {"ks_pre": (1.0, 1)})
     # raises: the column at 16 limbs; per segment 3 fill groups and one for its baby steps, the 8 relinearisations and the 7 giant steps of the sums, at 15

@@ -89,8 +89,8 @@ WORKLOADS.append(Workload("ccmmqk", 10, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # The same product with the element extraction in giant and baby steps (period 16): a step computes the d_out = 16
 # output columns of one segment (columns 16..31), whose giant steps are shared.  Three levels instead of two.
 WORKLOADS.append(Workload("ccmmqkbsgs", 11, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=16, act="uniform", op="ccmm_bsgs", period=16))
-# A whole segment of 32 output columns (32 .. 63) from its diagonals, in baby steps of 4 (no per-element fills).
-WORKLOADS.append(Workload("ccmmqkseg", 14, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=32, act="uniform", op="ccmm_segment", period=32,
+# A whole segment of 64 output columns (64 .. 127) from its diagonals, in baby steps of 4 (no per-element fills).
+WORKLOADS.append(Workload("ccmmqkseg", 14, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=96, d_out=64, act="uniform", op="ccmm_segment", period=64,
                           baby=4))
 # A slice of the paper's other attention product (Table III: (2048 x 2048) by (2048 x 96), 16 heads): the attention
 # weights column-encoded (column j = one ciphertext, 16 heads in its blocks), V column-encoded.  Output column i is
