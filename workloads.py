@@ -101,7 +101,7 @@ WORKLOADS.append(Workload("ccmmav", 12, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d
 # The fused N = 2^16 kernels do not apply: transforms, ModUp, inner product and ModDown run as separate kernels.
 WORKLOADS.append(Workload("paper1536n14", 13, 14, 50, 6, 60, 2, 2, 40, tokens=2048, d_in=1536, d_out=1536, placement="diagonal", act="normal"))
 # The same slice of weights times V from diagonalised weights (prepared once for all 96 columns of V, outside the step).
-WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_av", period=32,
+WORKLOADS.append(Workload("ccmmavseg", 15, 16, 50, 16, 60, 4, 4, 40, tokens=2048, d_in=512, d_out=1, act="uniform", op="ccmm_av", period=64,
                           baby=8))
 # The ccmm96 shape (one head of 32768 tokens per ciphertext, inner width 96) through the weights-times-V entry point: the
 # inner index is the slot index of B's columns, so A's 96 columns (padded to one segment of 128) are diagonalised once
