@@ -220,23 +220,36 @@ void orc_i64_to_rns(uint64_t *out, const int64_t *in, int n_limbs, int n, const 
 }
 
 /* Counter-based uniform generator shared BY SPECIFICATION (not by code) with the
- * GPU library: two SplitMix64-finalised words per sample, reduced mod q.
+ * GPU library.  A sample is two consecutive outputs of SplitMix64 (Steele, Lea,
+ * Flood, "Fast splittable pseudorandom number generators", 2014) read as one
+ * 128-bit number and reduced mod q; the generator's starting state is a key
+ * derived from (seed, stream, prime index) with the same finaliser:
  *   mix(z): z^=z>>30; z*=0xBF58476D1CE4E5B9; z^=z>>27; z*=0x94D049BB133111EB; z^=z>>31
+ *   SplitMix64: state += G; output = mix(state),   G = 0x9E3779B97F4A7C15
  *   key = mix(mix(mix(seed) + stream) + prime_id)
- *   hi  = mix(key + G*(2i+1)),  lo = mix(key + G*(2i+2)),  G = 0x9E3779B97F4A7C15
- *   sample_i = (hi*2^64 + lo) mod q                                              */
+ *   sample_i = (output_{2i+1}*2^64 + output_{2i+2}) mod q   of the generator started at key
+ * The key derivation and the two-words-per-sample layout are this build's own
+ * format; the generator is the published one (orc_splitmix64 is pinned to its
+ * published output vectors). */
 static inline uint64_t mix64(uint64_t z) {
     z ^= z >> 30; z *= 0xBF58476D1CE4E5B9ULL;
     z ^= z >> 27; z *= 0x94D049BB133111EBULL;
     z ^= z >> 31;
     return z;
 }
+static inline uint64_t splitmix64_next(uint64_t *state) {
+    *state += 0x9E3779B97F4A7C15ULL;
+    return mix64(*state);
+}
+/* The first n outputs of SplitMix64 started at `state`. */
+void orc_splitmix64(uint64_t *out, int n, uint64_t state) {
+    for (int i = 0; i < n; i++) out[i] = splitmix64_next(&state);
+}
 void orc_uniform(uint64_t *out, int n, uint64_t seed, uint64_t stream, uint64_t prime_id, uint64_t q) {
-    const uint64_t G = 0x9E3779B97F4A7C15ULL;
-    uint64_t key = mix64(mix64(mix64(seed) + stream) + prime_id);
+    uint64_t state = mix64(mix64(mix64(seed) + stream) + prime_id);
     for (int i = 0; i < n; i++) {
-        uint64_t hi = mix64(key + G * (2 * (uint64_t)i + 1));
-        uint64_t lo = mix64(key + G * (2 * (uint64_t)i + 2));
+        uint64_t hi = splitmix64_next(&state);
+        uint64_t lo = splitmix64_next(&state);
         out[i] = (uint64_t)((((u128)hi << 64) | lo) % q);
     }
 }

@@ -130,7 +130,7 @@ def test_tiny_workload_matmul_bit_exact(tiny, placement):
     for i in range(w.d_out):
         p_i = 0 if placement == "zero" else i % w.c_tot
         err = max(err, np.abs(dec[i, p_i * w.tokens:(p_i + 1) * w.tokens] - ref[:, i]).max())
-    assert err < (1e-3 if placement == "diagonal" else 2e-3)
+    assert err < 1e-3  # both placements (the oracle measures 3.6e-4 and 2.5e-4)
     out.free()
     g_ct.free()
     g_gk.free()
