@@ -20,12 +20,21 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return; results are ready after the stream
  *     is synchronised.  Calls that return host data synchronise themselves.
+ *     A context serves ONE stream at a time: its workspaces are shared by all
+ *     calls, so calls on one context must not overlap on different streams (use
+ *     one context per concurrent stream).  Workspaces grow on demand (a device
+ *     allocation inside the call the first time a larger size is needed).
  *   - Ring degree N = 2^log_n, n = N/2 slots.  Primes: q_0..q_{L-1} of q_bits
  *     bits and p_0..p_{K-1} of p_bits bits, the largest primes = 1 mod 2N
  *     below 2^bits, descending (P chain skips members of the Q chain).
  *   - Random material is either passed in (int8 host arrays: ternary
  *     polynomials, small error polynomials) or, where the pointer is NULL,
- *     drawn by the library's own host sampler.  Uniform ring elements come from
+ *     drawn by the library: from the operating system's cryptographic generator
+ *     when params.seed is 0 (the only setting fit for real keys), from a
+ *     deterministic generator keyed by params.seed otherwise.  THE SEEDED PATH IS
+ *     FOR REPRODUCIBLE TESTS AND BENCHMARKS ONLY: the seed is a public parameter,
+ *     so a secret key drawn from it is predictable.  Uniform ring elements (the
+ *     public halves of keys, which need no secrecy) come from
  *     a counter-based generator keyed by (seed, stream id, prime index):
  *       mix(z): z^=z>>30; z*=0xBF58476D1CE4E5B9; z^=z>>27; z*=0x94D049BB133111EB; z^=z>>31
  *       key = mix(mix(mix(seed)+stream)+prime_index)
@@ -59,6 +68,7 @@ typedef struct ensi_pk ensi_pk;
 typedef struct ensi_gk ensi_gk;
 typedef struct ensi_pt ensi_pt;
 typedef struct ensi_ct ensi_ct;
+typedef struct ensi_wt ensi_wt;
 
 typedef struct ensi_params {
     int32_t log_n;     /* ring degree N = 2^log_n, 4 <= log_n <= 16 */
@@ -68,7 +78,8 @@ typedef struct ensi_params {
     int32_t p_count;   /* K: number of special primes (1..4) */
     int32_t alpha;     /* limbs per key-switching digit (1..4) */
     int32_t log_scale; /* encoding scale Delta = 2^log_scale */
-    uint64_t seed;     /* seeds the library's own sampler (used only where NULL randomness is passed) */
+    uint64_t seed;     /* 0: NULL randomness is drawn from the operating system's cryptographic generator;
+                          non-zero: from a deterministic generator keyed by this value (tests and benchmarks only) */
 } ensi_params;
 
 /* ---- context ----------------------------------------------------------- */
@@ -95,6 +106,27 @@ void ensi_pk_free(ensi_pk *pk);
 int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_t *steps, int32_t n_steps, const int8_t *e,
                        uint64_t seed_a, ensi_gk **gk);
 void ensi_gk_free(ensi_gk *gk);
+
+/* ---- key import / export (System model: the client generates the keys, the server holds only the public and
+ *      evaluation keys; Preliminaries, KeyGen) ---------------------------------------------------------------
+ * Key material crosses the boundary in coefficient form as canonical residues in [0, prime): what a client
+ * produced elsewhere (or another implementation of the same key definitions) can be loaded without the secret
+ * key ever reaching this process.  Imports check every word and fail with ENSI_E_BADARG on a value that is not
+ * below its prime.
+ * sk: host int8[N], ternary coefficients.
+ * pk: host u64[2][L][N] = (b, a) with b = -a s + e over Q_L.
+ * A switching key (Galois key of one rotation step, or the evaluation key of Mult under step 0, i.e. the identity
+ * element): host u64[beta][2][L+K][N], digit-major, per digit (b_j, a_j) over Q_L + P, beta = ceil(L/alpha).
+ * ensi_gk_import adds the key of `step` to *gk (a NULL *gk is created; an existing key of that step is replaced).
+ * ensi_gk_elements writes the Galois elements g = 5^step mod 2N of the keys a set holds (capacity cap) and returns
+ * their number. */
+int ensi_sk_import(ensi_ctx *ctx, const int8_t *s, ensi_sk **sk);
+int ensi_sk_export(ensi_ctx *ctx, const ensi_sk *sk, int8_t *s);
+int ensi_pk_import(ensi_ctx *ctx, const uint64_t *words, ensi_pk **pk);
+int ensi_pk_export(ensi_ctx *ctx, const ensi_pk *pk, uint64_t *words);
+int ensi_gk_import(ensi_ctx *ctx, ensi_gk **gk, int32_t step, const uint64_t *words);
+int ensi_gk_export(ensi_ctx *ctx, const ensi_gk *gk, int32_t step, uint64_t *words);
+int ensi_gk_elements(const ensi_gk *gk, int32_t *elements_out, int32_t cap);
 
 /* ---- plaintexts (column-wise SIMD encoding, pi) ------------------------- */
 /* slots: host double[n_pt][n_slots] real values, zero-padded to N/2 slots.
@@ -124,6 +156,10 @@ int ensi_ct_info(const ensi_ct *ct, int32_t *n, int32_t *limbs, double *scale, v
 /* host u64[n][2][limbs][N], compact (active limbs only). */
 int ensi_ct_export(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *limbs_out);
 int ensi_ct_import(ensi_ctx *ctx, const uint64_t *limbs_in, int32_t n, int32_t limbs, double scale, ensi_ct **ct);
+/* sums: host u64[n]; sums[c] = the sum modulo 2^64 of all active limb words of ciphertext c (both polynomials).
+ * A whole batch can be compared with a reference (or with another kernel's result) without downloading it, e.g.
+ * the outputs of Alg. 1 at sizes where only sampled outputs can be recomputed.  Synchronises the stream. */
+int ensi_ct_checksum(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *sums, void *stream);
 
 /* Enc_pk: ct_i = v_i pk + (m_i + e0_i, e1_i).  v, e0, e1: host int8[n_pt][N] or
  * NULL (all three given or all three NULL). */
@@ -184,6 +220,20 @@ int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa, void *stre
  * `in` is consumed: its handle takes the level and scale of the rescaled batch, its words are unspecified
  * afterwards (rescaled in place or left as they were). */
 int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out, void *stream);
+
+/* ---- Alg. 1 with the weights prepared once ------------------------------- */
+/* The weights of a layer are fixed while activations change (System model: the server holds W in the clear), so
+ * everything Alg. 1 derives from W alone -- which operands exist, the weight of each operand in each output in the
+ * layout the kernels read, the validation of the values -- can be built once, outside the step.
+ * ensi_weights_prepare does that for inputs at `limbs` limbs (W, s, d, m, placement as for ensi_ternary_matmul; W is
+ * not referenced after the call); ensi_ternary_matmul_prepared and ensi_rescale_ternary_matmul_prepared then compute
+ * exactly what ensi_ternary_matmul and ensi_rescale_ternary_matmul compute (for the latter the weights are prepared
+ * with s = N/2, d = in.n, ENSI_PLACE_ZERO and limbs = in.limbs - 1).  The plain entry points keep a small cache of
+ * plans instead, looked up by a hash of W and confirmed by comparing W byte by byte. */
+int ensi_weights_prepare(ensi_ctx *ctx, const int8_t *W, int32_t s, int32_t d, int32_t m, int32_t placement, int32_t limbs, ensi_wt **wt);
+void ensi_weights_free(ensi_wt *wt);
+int ensi_ternary_matmul_prepared(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const ensi_wt *wt, ensi_ct *out, void *stream);
+int ensi_rescale_ternary_matmul_prepared(ensi_ctx *ctx, ensi_ct *in, double kappa, const ensi_wt *wt, ensi_ct *out, void *stream);
 
 /* ---- PMult (Preliminaries, Multiplication) summed and rescaled once ------ */
 /* out_o = Rescale( sum_{t in [begin[o], begin[o+1])} in[term_ct[t]] (x) pt[term_pt[t]] ),  o = 0..n_out-1.

@@ -24,6 +24,8 @@ EXPORTED = [
     "ensi_set_accumulate_mode", "ensi_mul_scalar_rescale", "ensi_rescale_ternary_matmul", "ensi_encode_at", "ensi_pt_set_scale",
     "ensi_pmult_sum_rescale", "ensi_set_pmult_mode", "ensi_block_masks", "ensi_merge", "ensi_rope_plaintexts", "ensi_rope", "ensi_relin_keygen",
     "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ccmm_left_giant_steps", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
+    "ensi_sk_import", "ensi_sk_export", "ensi_pk_import", "ensi_pk_export", "ensi_gk_import", "ensi_gk_export", "ensi_gk_elements",
+    "ensi_ct_checksum", "ensi_weights_prepare", "ensi_weights_free", "ensi_ternary_matmul_prepared", "ensi_rescale_ternary_matmul_prepared",
 ]
 
 
@@ -51,7 +53,7 @@ def load():
             if name.endswith("_free") or name == "ensi_last_error":
                 continue
             getattr(lib, name).restype = ctypes.c_int
-        for name in ("ensi_ctx_free", "ensi_sk_free", "ensi_pk_free", "ensi_gk_free", "ensi_pt_free", "ensi_ct_free"):
+        for name in ("ensi_ctx_free", "ensi_sk_free", "ensi_pk_free", "ensi_gk_free", "ensi_pt_free", "ensi_ct_free", "ensi_weights_free"):
             getattr(lib, name).restype = None
             getattr(lib, name).argtypes = [ctypes.c_void_p]
         _lib = lib
@@ -118,6 +120,54 @@ class Context:
         rk = ctypes.c_void_p()
         self._check(self.lib.ensi_relin_keygen(self.h, sk.h, _ptr(e), ctypes.c_uint64(seed_a), ctypes.byref(rk)))
         return _Handle(self, rk, "ensi_gk_free")
+
+    def sk_import(self, s):
+        s = _i8(s, (self.N,))
+        sk = ctypes.c_void_p()
+        self._check(self.lib.ensi_sk_import(self.h, _ptr(s), ctypes.byref(sk)))
+        return _Handle(self, sk, "ensi_sk_free")
+
+    def sk_export(self, sk):
+        out = np.empty(self.N, dtype=np.int8)
+        self._check(self.lib.ensi_sk_export(self.h, sk.h, _ptr(out)))
+        return out
+
+    def pk_import(self, words):
+        a = np.ascontiguousarray(words, dtype=np.uint64)
+        if a.shape != (2, self.L, self.N):
+            raise EnsiError("expected uint64 [2][L][N]")
+        pk = ctypes.c_void_p()
+        self._check(self.lib.ensi_pk_import(self.h, _ptr(a), ctypes.byref(pk)))
+        return _Handle(self, pk, "ensi_pk_free")
+
+    def pk_export(self, pk):
+        out = np.empty((2, self.L, self.N), dtype=np.uint64)
+        self._check(self.lib.ensi_pk_export(self.h, pk.h, _ptr(out)))
+        return out
+
+    def gk_import(self, step, words, gk=None):
+        """Adds the switching key of `step` (uint64 [beta][2][L+K][N]) to the key set gk (a new set if None)."""
+        a = np.ascontiguousarray(words, dtype=np.uint64)
+        if a.shape != (self.beta, 2, self.L + self.K, self.N):
+            raise EnsiError("expected uint64 [beta][2][L+K][N]")
+        h = ctypes.c_void_p(gk.h.value if gk is not None else None)
+        self._check(self.lib.ensi_gk_import(self.h, ctypes.byref(h), int(step), _ptr(a)))
+        if gk is None:
+            gk = _Handle(self, h, "ensi_gk_free")
+        return gk
+
+    def gk_export(self, gk, step):
+        out = np.empty((self.beta, 2, self.L + self.K, self.N), dtype=np.uint64)
+        self._check(self.lib.ensi_gk_export(self.h, gk.h, int(step), _ptr(out)))
+        return out
+
+    def gk_elements(self, gk):
+        n = self.lib.ensi_gk_elements(gk.h, None, 0)
+        if n < 0:
+            raise EnsiError("ensi_gk_elements failed with code %d" % n)
+        out = np.zeros(max(n, 1), dtype=np.int32)
+        self.lib.ensi_gk_elements(gk.h, _ptr(out), n)
+        return [int(x) for x in out[:n]]
 
     # ---- plaintexts
     def encode(self, slots, limbs):
@@ -201,6 +251,27 @@ class Context:
             ct_out = self.ct_alloc(m, ct_in.limbs)
         self._check(self.lib.ensi_ternary_matmul(self.h, gk.h if gk is not None else None, ct_in.h, s, d, _ptr(W), m,
                                                  _PLACEMENTS[placement], ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def weights_prepare(self, W, s, d, placement, limbs):
+        """Everything Alg. 1 derives from the weights alone, built once; `limbs`: the level of the inputs."""
+        W = np.ascontiguousarray(W, dtype=np.int8)
+        if W.ndim != 2 or W.shape[0] != d:
+            raise EnsiError("W must be int8 [d][m]")
+        wt = ctypes.c_void_p()
+        self._check(self.lib.ensi_weights_prepare(self.h, _ptr(W), int(s), int(d), W.shape[1], _PLACEMENTS[placement], int(limbs), ctypes.byref(wt)))
+        return _Handle(self, wt, "ensi_weights_free", n=W.shape[1])
+
+    def ternary_matmul_prepared(self, gk, ct_in, wt, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(wt.n, ct_in.limbs)
+        self._check(self.lib.ensi_ternary_matmul_prepared(self.h, gk.h if gk is not None else None, ct_in.h, wt.h, ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def rescale_ternary_matmul_prepared(self, ct_in, kappa, wt, ct_out=None, stream=0):
+        if ct_out is None:
+            ct_out = self.ct_alloc(wt.n, ct_in.limbs - 1)
+        self._check(self.lib.ensi_rescale_ternary_matmul_prepared(self.h, ct_in.h, ctypes.c_double(kappa), wt.h, ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def set_accumulate_mode(self, mode):
@@ -438,6 +509,12 @@ class Ciphertexts(_Handle):
     @property
     def device_ptr(self):
         return self._info()[3]
+
+    def checksum(self, stream=0):
+        """Wrap-around 64-bit sum of the active limb words of every ciphertext of the batch."""
+        out = np.zeros(self._info()[0], dtype=np.uint64)
+        self.ctx._check(self.ctx.lib.ensi_ct_checksum(self.ctx.h, self.h, _ptr(out), ctypes.c_void_p(stream)))
+        return out
 
     def export(self):
         n, limbs, _, _ = self._info()

@@ -412,7 +412,7 @@ template <int P>
 static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
                       const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_m, int workers,
                       int m_group, char *xp, int slice_ctiles, const double *d_rescale) {
-    static bool attr_set = false;
+    bool &attr_set = ctx->am_attr_set[P == 5 ? 0 : 1];
     if (!attr_set) {
         (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
         attr_set = true;
@@ -456,7 +456,7 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
                            hipStream_t st) {
     const int ctiles = ctx->N / AM_TILE_N;
     const int n_tiles_m = (m + AM_TILE_M - 1) / AM_TILE_M;
-    static int n_cu = 0;
+    int &n_cu = ctx->n_cu;
     if (!n_cu) {
         hipDeviceProp_t prop;
         n_cu = hipGetDeviceProperties(&prop, ctx->device) == hipSuccess ? prop.multiProcessorCount : 256;

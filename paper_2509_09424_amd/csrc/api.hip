@@ -13,61 +13,33 @@
 #include "common.h"
 #include "hostmath.h"
 
-// ------------------------------------------------------------------ utilities
-namespace {
+#include "api_util.h"
 
-struct DevBuf {
-    void *p = nullptr;
-    DevBuf() {}
-    DevBuf(const DevBuf &) = delete;
-    ~DevBuf() {
-        if (p) (void)hipFree(p);
+// ------------------------------------------------------------ staged uploads
+hipError_t host_to_device(ensi_ctx *ctx, void *dst, const void *src, size_t bytes, hipStream_t st) {
+    if (!bytes) return hipSuccess;
+    StageSlot &sl = ctx->stage[ctx->stage_next];
+    ctx->stage_next = (ctx->stage_next + 1) % ENSI_STAGE_SLOTS;
+    hipError_t e;
+    if (sl.pending) {
+        if ((e = hipEventSynchronize(sl.ev)) != hipSuccess) return e;  // an earlier small copy: long finished in practice
+        sl.pending = false;
     }
-    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 8); }
-    template <class T>
-    T *as() { return (T *)p; }
-};
-
-template <class T>
-hipError_t upload(T **d, const std::vector<T> &h) {
-    hipError_t e = hipMalloc((void **)d, std::max<size_t>(h.size() * sizeof(T), 8));
-    if (e != hipSuccess) return e;
-    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+    if (sl.cap < bytes) {
+        if (sl.host) (void)hipHostFree(sl.host);
+        sl.host = nullptr;
+        sl.cap = 0;
+        const size_t cap = std::max<size_t>(bytes, 64 << 10);
+        if ((e = hipHostMalloc(&sl.host, cap, hipHostMallocDefault)) != hipSuccess) return e;
+        sl.cap = cap;
+    }
+    if (!sl.ev && (e = hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming)) != hipSuccess) return e;
+    memcpy(sl.host, src, bytes);
+    if ((e = hipMemcpyAsync(dst, sl.host, bytes, hipMemcpyHostToDevice, st)) != hipSuccess) return e;
+    if ((e = hipEventRecord(sl.ev, st)) != hipSuccess) return e;
+    sl.pending = true;
+    return hipSuccess;
 }
-
-LimbMap make_map(const ensi_ctx *ctx, int l1, bool with_p) {
-    LimbMap m;
-    m.n = l1 + (with_p ? ctx->K : 0);
-    for (int e = 0; e < ENSI_MAX_EXT; e++) m.prime[e] = 0;
-    for (int e = 0; e < m.n; e++) m.prime[e] = e < l1 ? e : ctx->L + (e - l1);
-    return m;
-}
-
-u32 galois_element(const ensi_ctx *ctx, int32_t step) {
-    const int n = ctx->N / 2;
-    int k = step % n;
-    if (k < 0) k += n;
-    return ctx->rot_exp[k];
-}
-u32 inv_mod_2n(u32 g, int N) {
-    // g odd: Newton iteration modulo a power of two
-    u32 x = g;
-    for (int i = 0; i < 5; i++) x *= 2 - g * x;
-    return x & (2 * (u32)N - 1);
-}
-
-int grow(ensi_ctx *ctx, u64 **p, size_t *have, size_t need) {
-    if (*have >= need) return ENSI_OK;
-    if (*p) ENSI_HIP(ctx, hipFree(*p));
-    *p = nullptr;
-    *have = 0;
-    hipError_t e = hipMalloc((void **)p, need * sizeof(u64));
-    if (e != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of %zu bytes failed: %s", need * sizeof(u64), hipGetErrorString(e));
-    *have = need;
-    return ENSI_OK;
-}
-
-}  // namespace
 
 // ---------------------------------------------------------------------- timers
 int timer_id(ensi_ctx *ctx, const char *name) {
@@ -300,6 +272,10 @@ extern "C" void ensi_ctx_free(ensi_ctx *ctx) {
     if (ctx->ws_rep) (void)hipFree(ctx->ws_rep);
     if (ctx->ws_rtmp) (void)hipFree(ctx->ws_rtmp);
     for (MatmulPlan *p : ctx->plans) free_plan(p);
+    for (StageSlot &sl : ctx->stage) {
+        if (sl.host) (void)hipHostFree(sl.host);
+        if (sl.ev) (void)hipEventDestroy(sl.ev);
+    }
     for (auto &p : ctx->pending) {
         (void)hipEventDestroy(p.second.first);
         (void)hipEventDestroy(p.second.second);
@@ -484,211 +460,6 @@ static int get_ks16(ensi_ctx *ctx, int l1, const Ks16Const **out) {
     return ENSI_OK;
 }
 
-// ------------------------------------------------------------------ sampling
-// The library's own sampler, used only where the caller passes NULL randomness.
-static void sample_ternary(ensi_ctx *ctx, int8_t *out, size_t n) {
-    std::mt19937_64 gen(ctx->prm.seed * 0x9E3779B97F4A7C15ULL + (++ctx->sampler_ctr));
-    std::uniform_int_distribution<int> d(-1, 1);
-    for (size_t i = 0; i < n; i++) out[i] = (int8_t)d(gen);
-}
-static void sample_error(ensi_ctx *ctx, int8_t *out, size_t n) {
-    std::mt19937_64 gen(ctx->prm.seed * 0x9E3779B97F4A7C15ULL + (++ctx->sampler_ctr));
-    std::normal_distribution<double> d(0.0, 3.2);
-    for (size_t i = 0; i < n; i++) {
-        double v = nearbyint(d(gen));
-        out[i] = (int8_t)std::max(-19.0, std::min(19.0, v));
-    }
-}
-
-// ------------------------------------------------------------------------ keys
-extern "C" int ensi_keygen(ensi_ctx *ctx, const int8_t *s, const int8_t *e, uint64_t seed_a, ensi_sk **sk_out, ensi_pk **pk_out) {
-    if (!ctx || !sk_out || !pk_out) return ENSI_E_BADARG;
-    const int N = ctx->N, L = ctx->L, ext = ctx->L + ctx->K;
-    std::vector<int8_t> sv(N), ev(N);
-    if (s) memcpy(sv.data(), s, N);
-    else sample_ternary(ctx, sv.data(), N);
-    if (e) memcpy(ev.data(), e, N);
-    else sample_error(ctx, ev.data(), N);
-    for (int i = 0; i < N; i++)
-        if (sv[i] < -1 || sv[i] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "secret coefficient %d outside {-1,0,1}", i);
-
-    hipStream_t st = nullptr;
-    LimbMap mext = make_map(ctx, L, true), mq = make_map(ctx, L, false);
-    DevBuf d_small, d_e, d_a;
-    ensi_sk *sk = new ensi_sk();
-    sk->ctx = ctx;
-    sk->s = sv;
-    sk->d_s_hat = nullptr;
-    ensi_pk *pk = new ensi_pk();
-    pk->ctx = ctx;
-    pk->d_pk = nullptr;
-    auto fail = [&](int code) {
-        ensi_sk_free(sk);
-        ensi_pk_free(pk);
-        return code;
-    };
-    if (d_small.alloc(2 * (size_t)N) != hipSuccess || d_e.alloc((size_t)L * N * 8) != hipSuccess || d_a.alloc((size_t)L * N * 8) != hipSuccess ||
-        hipMalloc((void **)&sk->d_s_hat, (size_t)ext * N * 8) != hipSuccess || hipMalloc((void **)&pk->d_pk, (size_t)2 * L * N * 8) != hipSuccess) {
-        ctx->err = "device allocation failed in keygen";
-        return fail(ENSI_E_NOMEM);
-    }
-    (void)hipMemcpy(d_small.p, sv.data(), N, hipMemcpyHostToDevice);
-    (void)hipMemcpy(d_small.as<int8_t>() + N, ev.data(), N, hipMemcpyHostToDevice);
-    // secret: residues -> transform domain -> Montgomery form, over Q_L + P
-    launch_small_to_rns(ctx, d_small.as<int8_t>(), 1, mext, sk->d_s_hat, st);
-    launch_ntt(ctx, sk->d_s_hat, ext, mext, false, st);
-    launch_to_mont(ctx, sk->d_s_hat, ext, mext, st);
-    // pk = (-a s + e, a) over Q_L
-    u64 *pk_b = pk->d_pk, *pk_a = pk->d_pk + (size_t)L * N;
-    launch_uniform(ctx, d_a.as<u64>(), mq, seed_a, 1, st);
-    launch_ntt(ctx, d_a.as<u64>(), L, mq, false, st);
-    launch_small_to_rns(ctx, d_small.as<int8_t>() + N, 1, mq, d_e.as<u64>(), st);
-    launch_ntt(ctx, d_e.as<u64>(), L, mq, false, st);
-    launch_key_assemble(ctx, pk_b, d_a.as<u64>(), sk->d_s_hat, d_e.as<u64>(), nullptr, nullptr, mq, st);
-    (void)hipMemcpyAsync(pk_a, d_a.p, (size_t)L * N * 8, hipMemcpyDeviceToDevice, st);
-    launch_to_mont(ctx, pk_a, L, mq, st);
-    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
-        ctx->err = "kernel failure in keygen";
-        return fail(ENSI_E_HIP);
-    }
-    *sk_out = sk;
-    *pk_out = pk;
-    return ENSI_OK;
-}
-extern "C" void ensi_sk_free(ensi_sk *sk) {
-    if (!sk) return;
-    if (sk->d_s_hat) (void)hipFree(sk->d_s_hat);
-    delete sk;
-}
-extern "C" void ensi_pk_free(ensi_pk *pk) {
-    if (!pk) return;
-    if (pk->d_pk) (void)hipFree(pk->d_pk);
-    delete pk;
-}
-
-// Scratch of the switching-key generation (one secret, any number of keys).
-struct KeygenScratch {
-    DevBuf d_s, d_target, d_e8, d_e, d_fac, d_s8;
-};
-static int keygen_scratch(ensi_ctx *ctx, const ensi_sk *sk, KeygenScratch &k, hipStream_t st) {
-    const int N = ctx->N, ext = ctx->L + ctx->K;
-    if (k.d_s.alloc((size_t)ext * N * 8) != hipSuccess || k.d_target.alloc((size_t)ext * N * 8) != hipSuccess || k.d_e8.alloc(N) != hipSuccess ||
-        k.d_e.alloc((size_t)ext * N * 8) != hipSuccess || k.d_fac.alloc((size_t)ext * 8) != hipSuccess || k.d_s8.alloc(N) != hipSuccess)
-        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in key generation");
-    (void)hipMemcpy(k.d_s8.p, sk->s.data(), N, hipMemcpyHostToDevice);
-    launch_small_to_rns(ctx, k.d_s8.as<int8_t>(), 1, make_map(ctx, ctx->L, true), k.d_s.as<u64>(), st);  // coefficient form of s
-    return ENSI_OK;
-}
-// key <- hybrid key-switching key from the secret in k.d_target (transform domain, ordinary residues) to s:
-// per digit j, (b_j, a_j) with b_j = -a_j s + e_j + [P]_{q_i} target on the limbs of digit j.  e: host
-// int8[beta][N] or NULL; a_j is the uniform stream stream_base | j.
-static void make_switch_key(ensi_ctx *ctx, const ensi_sk *sk, KeygenScratch &k, const int8_t *e, uint64_t seed_a, u64 stream_base, u64 *key,
-                            hipStream_t st) {
-    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
-    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
-    LimbMap mext = make_map(ctx, L, true);
-    std::vector<int8_t> ev(N);
-    for (int j = 0; j < beta; j++) {
-        u64 *kb = key + (size_t)(j * 2) * ext * N, *ka = kb + (size_t)ext * N;
-        if (e) memcpy(ev.data(), e + (size_t)j * N, N);
-        else sample_error(ctx, ev.data(), N);
-        (void)hipMemcpyAsync(k.d_e8.p, ev.data(), N, hipMemcpyHostToDevice, st);
-        (void)hipStreamSynchronize(st);
-        launch_small_to_rns(ctx, k.d_e8.as<int8_t>(), 1, mext, k.d_e.as<u64>(), st);
-        launch_ntt(ctx, k.d_e.as<u64>(), ext, mext, false, st);
-        launch_uniform(ctx, ka, mext, seed_a, stream_base | (u64)j, st);
-        launch_ntt(ctx, ka, ext, mext, false, st);
-        std::vector<u64> fac(ext, 0);
-        for (int i = j * ctx->alpha; i < std::min((j + 1) * ctx->alpha, L); i++) {
-            const u64 q = ctx->primes[i];
-            u64 P = 1;
-            for (int b = 0; b < K; b++) P = hm_mulmod(P, ctx->primes[L + b] % q, q);
-            fac[i] = hm_to_mont(P, q);
-        }
-        (void)hipMemcpyAsync(k.d_fac.p, fac.data(), ext * 8, hipMemcpyHostToDevice, st);
-        (void)hipStreamSynchronize(st);
-        launch_key_assemble(ctx, kb, ka, sk->d_s_hat, k.d_e.as<u64>(), k.d_target.as<u64>(), k.d_fac.as<u64>(), mext, st);
-        launch_to_mont(ctx, ka, ext, mext, st);
-    }
-    if (ctx->ks16) launch_ks16_key_format(ctx, key, beta, st);
-}
-
-extern "C" int ensi_galois_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int32_t *steps, int32_t n_steps, const int8_t *e,
-                                  uint64_t seed_a, ensi_gk **out) {
-    if (!ctx || !sk || !out || (n_steps > 0 && !steps) || n_steps < 0) return ENSI_E_BADARG;
-    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
-    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
-    hipStream_t st = nullptr;
-    LimbMap mext = make_map(ctx, L, true);
-    ensi_gk *gk = new ensi_gk();
-    gk->ctx = ctx;
-    KeygenScratch k;
-    int rc;
-    if ((rc = keygen_scratch(ctx, sk, k, st))) {
-        ensi_gk_free(gk);
-        return rc;
-    }
-    for (int t = 0; t < n_steps; t++) {
-        const u32 g = galois_element(ctx, steps[t]);
-        if (gk->keys.count(g)) continue;
-        u64 *key = nullptr;
-        if (hipMalloc((void **)&key, (size_t)beta * 2 * ext * N * 8) != hipSuccess) {
-            ensi_gk_free(gk);
-            ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of a Galois key failed");
-        }
-        gk->keys[g] = key;
-        // phi_g(s), transform domain
-        launch_automorphism_coef(ctx, k.d_target.as<u64>(), k.d_s.as<u64>(), mext, inv_mod_2n(g, N), st);
-        launch_ntt(ctx, k.d_target.as<u64>(), ext, mext, false, st);
-        make_switch_key(ctx, sk, k, e ? e + (size_t)t * beta * N : nullptr, seed_a, ((u64)2 << 56) | ((u64)g << 8), key, st);
-    }
-    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
-        ensi_gk_free(gk);
-        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in galois_keygen");
-    }
-    *out = gk;
-    return ENSI_OK;
-}
-
-// Evaluation key of Mult: switches from s^2 to s.  Stored in a key set under the element 1 (the identity
-// automorphism), which is how the key-switch kernels are driven for a relinearisation.
-extern "C" int ensi_relin_keygen(ensi_ctx *ctx, const ensi_sk *sk, const int8_t *e, uint64_t seed_a, ensi_gk **out) {
-    if (!ctx || !sk || !out) return ENSI_E_BADARG;
-    const int N = ctx->N, L = ctx->L, K = ctx->K, ext = L + K;
-    const int beta = (L + ctx->alpha - 1) / ctx->alpha;
-    hipStream_t st = nullptr;
-    LimbMap mext = make_map(ctx, L, true);
-    ensi_gk *gk = new ensi_gk();
-    gk->ctx = ctx;
-    KeygenScratch k;
-    int rc;
-    if ((rc = keygen_scratch(ctx, sk, k, st))) {
-        ensi_gk_free(gk);
-        return rc;
-    }
-    u64 *key = nullptr;
-    if (hipMalloc((void **)&key, (size_t)beta * 2 * ext * N * 8) != hipSuccess) {
-        ensi_gk_free(gk);
-        ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of the evaluation key failed");
-    }
-    gk->keys[1u] = key;
-    // s^2, transform domain: NTT(s) (.) NTT(s), the second factor in Montgomery form
-    launch_ntt(ctx, k.d_s.as<u64>(), ext, mext, false, st);
-    launch_mul_mont(ctx, k.d_target.as<u64>(), k.d_s.as<u64>(), sk->d_s_hat, ext, mext, st);
-    make_switch_key(ctx, sk, k, e, seed_a, (u64)3 << 56, key, st);
-    if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) {
-        ensi_gk_free(gk);
-        ENSI_FAIL(ctx, ENSI_E_HIP, "kernel failure in relin_keygen");
-    }
-    *out = gk;
-    return ENSI_OK;
-}
-extern "C" void ensi_gk_free(ensi_gk *gk) {
-    if (!gk) return;
-    for (auto &kv : gk->keys) (void)hipFree(kv.second);
-    delete gk;
-}
-
 // ------------------------------------------------------------------ plaintexts
 static int pt_from_coeffs(ensi_ctx *ctx, const int64_t *d_coeffs, int n_pt, int limbs, double scale, ensi_pt **out) {
     ensi_pt *pt = new ensi_pt();
@@ -832,6 +603,19 @@ extern "C" int ensi_ct_import(ensi_ctx *ctx, const uint64_t *in, int32_t n, int3
     return ENSI_OK;
 }
 
+extern "C" int ensi_ct_checksum(ensi_ctx *ctx, const ensi_ct *ct, uint64_t *sums, void *stream) {
+    if (!ctx || !ct || !sums) return ENSI_E_BADARG;
+    if (ct->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "the batch holds prepared weights, which only ensi_ccmm_av reads");
+    hipStream_t st = (hipStream_t)stream;
+    DevBuf d_sums;
+    if (d_sums.alloc((size_t)ct->n * 8) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in ct_checksum");
+    ENSI_HIP(ctx, hipMemsetAsync(d_sums.p, 0, (size_t)ct->n * 8, st));
+    launch_ct_checksum(ctx, ct->d, ct->n, ct->limbs, ct->limbs_alloc, d_sums.as<u64>(), st);
+    ENSI_HIP(ctx, hipMemcpyAsync(sums, d_sums.p, (size_t)ct->n * 8, hipMemcpyDeviceToHost, st));
+    ENSI_HIP(ctx, hipStreamSynchronize(st));
+    return ENSI_OK;
+}
+
 extern "C" int ensi_encrypt(ensi_ctx *ctx, const ensi_pk *pk, const ensi_pt *pt, const int8_t *v, const int8_t *e0, const int8_t *e1,
                             ensi_ct **out) {
     if (!ctx || !pk || !pt || !out) return ENSI_E_BADARG;
@@ -844,8 +628,8 @@ extern "C" int ensi_encrypt(ensi_ctx *ctx, const ensi_pk *pk, const ensi_pt *pt,
         memcpy(small.data() + pn, e0, pn);
         memcpy(small.data() + 2 * pn, e1, pn);
     } else {
-        sample_ternary(ctx, small.data(), pn);
-        sample_error(ctx, small.data() + pn, 2 * pn);
+        int rs;
+        if ((rs = sample_ternary(ctx, small.data(), pn)) || (rs = sample_error(ctx, small.data() + pn, 2 * pn))) return rs;
     }
     int rc = ensi_ct_alloc(ctx, n, l1, out);
     if (rc) return rc;
@@ -1037,7 +821,7 @@ extern "C" int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, 
     for (int c0 = 0; c0 < n; c0 += chunk)
         std::stable_sort(desc.begin() + c0, desc.begin() + std::min(n, c0 + chunk),
                          [](const RotDesc &a, const RotDesc &b) { return (uintptr_t)a.key < (uintptr_t)b.key; });
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), n * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), n * sizeof(RotDesc), st));
     for (int c0 = 0; c0 < n; c0 += chunk) {
         const int cnt = std::min(chunk, n - c0);
         if ((rc = raise_cts(ctx, l1, in->d + (size_t)c0 * in_ct, in_ct, in->limbs_alloc, cnt, st))) return rc;
@@ -1072,21 +856,14 @@ static void free_plan(MatmulPlan *p) {
 // Builds (or finds) the plan of Y = X W: which (packed input G, rotation amount rho)
 // operands exist, and the weight of each operand in each output,
 //   W'[v][i] = W[G*c_tot + (rho + p_i) mod c_tot][i],   p_i = placement block of output i.
-static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int placement, int c_tot, int n_in, int l1,
-                    MatmulPlan **out) {
-    u64 h = 0xCBF29CE484222325ULL ^ ((u64)s << 40) ^ ((u64)d << 20) ^ (u64)m ^ ((u64)placement << 60) ^ ((u64)l1 << 52);
-    h = hash_weights(W, (size_t)d * m, h);
-    for (size_t k = 0; k < ctx->plans.size(); k++) {
-        MatmulPlan *p = ctx->plans[k];
-        if (p->hash == h && p->s == s && p->d == d && p->m == m && p->placement == placement) {
-            *out = p;
-            return ENSI_OK;
-        }
-    }
+static int build_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int placement, int c_tot, int n_in, int l1, u64 h,
+                      MatmulPlan **out) {
     for (size_t k = 0; k < (size_t)d * m; k++)
         if (W[k] < -1 || W[k] > 1) ENSI_FAIL(ctx, ENSI_E_BADARG, "weight %zu is %d, outside {-1,0,1}", k, (int)W[k]);
     MatmulPlan *p = new MatmulPlan();
     p->hash = h;
+    p->l1 = l1;
+    p->w_copy.assign(W, W + (size_t)d * m);
     p->s = s; p->d = d; p->m = m; p->placement = placement; p->c_tot = c_tot; p->n_in = n_in;
     p->vid.assign((size_t)n_in * c_tot, -1);
     for (int j = 0; j < d; j++) {
@@ -1164,8 +941,31 @@ static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int pla
         free_plan(p);
         ENSI_FAIL(ctx, ENSI_E_NOMEM, "uploading the matmul plan failed");
     }
+    *out = p;
+    return ENSI_OK;
+}
+
+// The plan of (W, s, d, m, placement) at l1 limbs from the context's cache (the weights of a layer are the same call
+// after call), built on a miss.  A hit is a match of the 64-bit hash confirmed by comparing the weights byte by byte.
+// Callers that want neither the hash nor the comparison inside their step prepare the weights once
+// (ensi_weights_prepare).
+static int get_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int placement, int c_tot, int n_in, int l1,
+                    MatmulPlan **out) {
+    u64 h = 0xCBF29CE484222325ULL ^ ((u64)s << 40) ^ ((u64)d << 20) ^ (u64)m ^ ((u64)placement << 60) ^ ((u64)l1 << 52);
+    h = hash_weights(W, (size_t)d * m, h);
+    for (size_t k = 0; k < ctx->plans.size(); k++) {
+        MatmulPlan *p = ctx->plans[k];
+        if (p->hash == h && p->s == s && p->d == d && p->m == m && p->placement == placement && p->l1 == l1 &&
+            p->w_copy.size() == (size_t)d * m && memcmp(p->w_copy.data(), W, (size_t)d * m) == 0) {
+            *out = p;
+            return ENSI_OK;
+        }
+    }
+    MatmulPlan *p = nullptr;
+    int rc = build_plan(ctx, W, s, d, m, placement, c_tot, n_in, l1, h, &p);
+    if (rc) return rc;
     if (ctx->plans.size() >= 8) {
-        (void)hipDeviceSynchronize();
+        (void)hipDeviceSynchronize();  // the evicted plan's device arrays may still be read by work in flight
         free_plan(ctx->plans.front());
         ctx->plans.erase(ctx->plans.begin());
     }
@@ -1180,12 +980,12 @@ extern "C" int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode) {
     return ENSI_OK;
 }
 
-extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
-                                   int32_t m, int32_t placement, ensi_ct *out, void *stream) {
-    if (!ctx || !in || !W || !out || s < 1 || d < 1 || m < 1) return ENSI_E_BADARG;
+// Shape and level checks shared by the entry points of Alg. 1.
+static int matmul_check(ensi_ctx *ctx, const ensi_ct *in, int32_t s, int32_t d, int32_t m, int32_t placement, const ensi_ct *out, int *c_tot_out,
+                        int *n_in_out) {
     if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
     if (placement != ENSI_PLACE_ZERO && placement != ENSI_PLACE_DIAGONAL) ENSI_FAIL(ctx, ENSI_E_BADARG, "unknown placement %d", placement);
-    const int N = ctx->N, n_slots = N / 2;
+    const int n_slots = ctx->N / 2;
     if (n_slots % s) ENSI_FAIL(ctx, ENSI_E_SHAPE, "tokens per column (%d) must divide the slot count %d", s, n_slots);
     const int c_tot = n_slots / s;
     const int n_in = (d + c_tot - 1) / c_tot;
@@ -1193,12 +993,66 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
     if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
     if (in->limbs != out->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "matmul: levels differ (%d vs %d limbs)", in->limbs, out->limbs);
     if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
+    *c_tot_out = c_tot;
+    *n_in_out = n_in;
+    return ENSI_OK;
+}
+
+static int matmul_run(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, MatmulPlan *plan, ensi_ct *out, void *stream);
+
+extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int32_t s, int32_t d, const int8_t *W,
+                                   int32_t m, int32_t placement, ensi_ct *out, void *stream) {
+    if (!ctx || !in || !W || !out || s < 1 || d < 1 || m < 1) return ENSI_E_BADARG;
+    int rc, c_tot, n_in;
+    if ((rc = matmul_check(ctx, in, s, d, m, placement, out, &c_tot, &n_in))) return rc;
+    MatmulPlan *plan;
+    if ((rc = get_plan(ctx, W, s, d, m, placement, c_tot, n_in, in->limbs, &plan))) return rc;
+    return matmul_run(ctx, gk, in, plan, out, stream);
+}
+
+extern "C" int ensi_weights_prepare(ensi_ctx *ctx, const int8_t *W, int32_t s, int32_t d, int32_t m, int32_t placement, int32_t limbs,
+                                    ensi_wt **out) {
+    if (!ctx || !W || !out || s < 1 || d < 1 || m < 1 || limbs < 1 || limbs > ctx->L) return ENSI_E_BADARG;
+    *out = nullptr;
+    if (placement != ENSI_PLACE_ZERO && placement != ENSI_PLACE_DIAGONAL) ENSI_FAIL(ctx, ENSI_E_BADARG, "unknown placement %d", placement);
+    const int n_slots = ctx->N / 2;
+    if (n_slots % s) ENSI_FAIL(ctx, ENSI_E_SHAPE, "tokens per column (%d) must divide the slot count %d", s, n_slots);
+    const int c_tot = n_slots / s, n_in = (d + c_tot - 1) / c_tot;
+    MatmulPlan *plan = nullptr;
+    int rc = build_plan(ctx, W, s, d, m, placement, c_tot, n_in, limbs, 0, &plan);
+    if (rc) return rc;
+    plan->w_copy.clear();  // a prepared plan is never looked up by its weights
+    plan->w_copy.shrink_to_fit();
+    ensi_wt *wt = new ensi_wt();
+    wt->ctx = ctx;
+    wt->plan = plan;
+    wt->limbs = limbs;
+    *out = wt;
+    return ENSI_OK;
+}
+extern "C" void ensi_weights_free(ensi_wt *wt) {
+    if (!wt) return;
+    (void)hipDeviceSynchronize();  // the plan's device arrays may still be read by work in flight
+    free_plan(wt->plan);
+    delete wt;
+}
+
+extern "C" int ensi_ternary_matmul_prepared(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const ensi_wt *wt, ensi_ct *out, void *stream) {
+    if (!ctx || !in || !wt || !out || wt->ctx != ctx) return ENSI_E_BADARG;
+    const MatmulPlan *p = wt->plan;
+    if (in->limbs != wt->limbs) ENSI_FAIL(ctx, ENSI_E_LEVEL, "weights were prepared for %d limbs, the input has %d", wt->limbs, in->limbs);
+    int rc, c_tot, n_in;
+    if ((rc = matmul_check(ctx, in, p->s, p->d, p->m, p->placement, out, &c_tot, &n_in))) return rc;
+    return matmul_run(ctx, gk, in, wt->plan, out, stream);
+}
+
+// Unpack rotations and the signed sums of Alg. 1 for a validated call.
+static int matmul_run(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, MatmulPlan *plan, ensi_ct *out, void *stream) {
     hipStream_t st = (hipStream_t)stream;
+    const int N = ctx->N, s = plan->s, m = plan->m, c_tot = plan->c_tot, n_in = plan->n_in;
     const int l1 = in->limbs, ext = l1 + ctx->K;
     const size_t in_ct = (size_t)2 * in->limbs_alloc * N;
     int rc;
-    MatmulPlan *plan;
-    if ((rc = get_plan(ctx, W, s, d, m, placement, c_tot, n_in, l1, &plan))) return rc;
     const int n_v = plan->n_v, n_rot = plan->n_rot;
     const std::vector<int> &vid = plan->vid;
 
@@ -1256,7 +1110,7 @@ extern "C" int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_
             }
             groups.push_back({first, (int)desc.size() - first});
         }
-        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), st));
         // ---- unpack: one ModUp per packed input, shared by all its rotations
         for (size_t gi = 0; gi < groups.size(); gi++) {
             if (!groups[gi].second) continue;
@@ -1319,8 +1173,8 @@ static int upload_rescale_consts(ensi_ctx *ctx, int l1, double kr, bool negative
     }
     int rc;
     if ((rc = grow(ctx, &ctx->ws_plan, &ctx->ws_plan_words, 2 * consts.size()))) return rc;
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan, consts.data(), consts.size() * 8, hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_plan + consts.size(), fconsts.data(), fconsts.size() * 8, hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_plan, consts.data(), consts.size() * 8, st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_plan + consts.size(), fconsts.data(), fconsts.size() * 8, st));
     *d_consts = ctx->ws_plan;
     *d_fconsts = (const double *)(ctx->ws_plan + consts.size());
     *fp_out = fp;
@@ -1345,24 +1199,17 @@ extern "C" int ensi_mul_scalar_rescale(ensi_ctx *ctx, ensi_ct *ct, double kappa,
     return ENSI_OK;
 }
 
-extern "C" int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out,
-                                           void *stream) {
-    if (!ctx || !in || !W || !out || m < 1 || !(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
-    if (in->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
-    if (out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input (%d vs %d limbs)", out->limbs, in->limbs);
-    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
-    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
+// The fused step for a validated call; plan: the second layer's plan at in->limbs - 1 limbs.
+static int rescale_matmul_run(ensi_ctx *ctx, ensi_ct *in, double kappa, MatmulPlan *plan, ensi_ct *out, void *stream) {
     hipStream_t st = (hipStream_t)stream;
-    const int N = ctx->N, d = in->n, l1_in = in->limbs, l1 = l1_in - 1;
+    const int N = ctx->N, d = in->n, l1_in = in->limbs, l1 = l1_in - 1, m = plan->m;
     int rc;
-    MatmulPlan *plan;
-    if ((rc = get_plan(ctx, W, N / 2, d, m, ENSI_PLACE_ZERO, 1, d, l1, &plan))) return rc;
     bool fp = true;
     for (int i = 0; i < l1_in; i++) fp = fp && ctx->primes[i] < ((u64)1 << 50);
     if (!fp || plan->planes == 0 || ctx->accumulate_mode == 1) {
         // no fused form for these parameters: the two steps one after the other
         if ((rc = ensi_mul_scalar_rescale(ctx, in, kappa, stream))) return rc;
-        return ensi_ternary_matmul(ctx, nullptr, in, N / 2, d, W, m, ENSI_PLACE_ZERO, out, stream);
+        return matmul_run(ctx, nullptr, in, plan, out, stream);
     }
     const u64 *d_consts;
     const double *d_fconsts;
@@ -1376,6 +1223,37 @@ extern "C" int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double ka
     out->scale = in->scale;
     ENSI_HIP(ctx, hipGetLastError());
     return ENSI_OK;
+}
+
+static int rescale_matmul_check(ensi_ctx *ctx, const ensi_ct *in, double kappa, int32_t m, const ensi_ct *out) {
+    if (!(fabs(kappa) > 0) || fabs(kappa) >= 1.0) return ENSI_E_BADARG;
+    if (in->prepared) ENSI_FAIL(ctx, ENSI_E_BADARG, "a batch of prepared weights is read by ensi_ccmm_segment and ensi_ccmm_av only");
+    if (in->limbs < 2) ENSI_FAIL(ctx, ENSI_E_LEVEL, "rescale: no limb left to drop");
+    if (out->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "output must be one level below the input (%d vs %d limbs)", out->limbs, in->limbs);
+    if (out->n != m) ENSI_FAIL(ctx, ENSI_E_SHAPE, "output batch holds %d ciphertexts, need %d", out->n, m);
+    if (in->d == out->d) ENSI_FAIL(ctx, ENSI_E_BADARG, "matmul: in and out must not overlap");
+    return ENSI_OK;
+}
+
+extern "C" int ensi_rescale_ternary_matmul(ensi_ctx *ctx, ensi_ct *in, double kappa, const int8_t *W, int32_t m, ensi_ct *out,
+                                           void *stream) {
+    if (!ctx || !in || !W || !out || m < 1) return ENSI_E_BADARG;
+    int rc;
+    if ((rc = rescale_matmul_check(ctx, in, kappa, m, out))) return rc;
+    MatmulPlan *plan;
+    if ((rc = get_plan(ctx, W, ctx->N / 2, in->n, m, ENSI_PLACE_ZERO, 1, in->n, in->limbs - 1, &plan))) return rc;
+    return rescale_matmul_run(ctx, in, kappa, plan, out, stream);
+}
+
+extern "C" int ensi_rescale_ternary_matmul_prepared(ensi_ctx *ctx, ensi_ct *in, double kappa, const ensi_wt *wt, ensi_ct *out, void *stream) {
+    if (!ctx || !in || !wt || !out || wt->ctx != ctx) return ENSI_E_BADARG;
+    const MatmulPlan *p = wt->plan;
+    int rc;
+    if ((rc = rescale_matmul_check(ctx, in, kappa, p->m, out))) return rc;
+    if (p->c_tot != 1 || p->placement != ENSI_PLACE_ZERO || p->d != in->n)
+        ENSI_FAIL(ctx, ENSI_E_SHAPE, "the weights must be prepared for one column per ciphertext (s = N/2), d = %d, placement zero", in->n);
+    if (wt->limbs != in->limbs - 1) ENSI_FAIL(ctx, ENSI_E_LEVEL, "weights were prepared for %d limbs, the rescaled input has %d", wt->limbs, in->limbs - 1);
+    return rescale_matmul_run(ctx, in, kappa, wt->plan, out, stream);
 }
 
 // ------------------------------------------------------- plaintext multiplication
@@ -1477,9 +1355,9 @@ static int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms_in, const 
     if ((rc = grow(ctx, &ctx->ws_pl, &ctx->ws_pl_words, need_b * 2 * N))) return rc;
     const size_t tw = terms.size() * (sizeof(PmTerm) / 8), bw = (begin.size() + 1) / 2, ow = (owner.size() + 1) / 2;
     if ((rc = grow(ctx, &ctx->ws_pt, &ctx->ws_pt_words, tw + bw + ow + 2))) return rc;
-    if (!terms.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt, terms.data(), terms.size() * sizeof(PmTerm), hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt + tw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
-    if (!owner.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_pt + tw + bw, owner.data(), owner.size() * 4, hipMemcpyHostToDevice, st));
+    if (!terms.empty()) ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_pt, terms.data(), terms.size() * sizeof(PmTerm), st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_pt + tw, begin.data(), begin.size() * 4, st));
+    if (!owner.empty()) ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_pt + tw + bw, owner.data(), owner.size() * 4, st));
 
     const u64 ql = ctx->primes[l1 - 1];
     PmRescale rs;
@@ -1629,7 +1507,7 @@ extern "C" int ensi_rope(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, co
                 d.g = g[e];
                 d.g_inv = inv_mod_2n(g[e], N);
             }
-        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), st));
         if ((rc = raise_cts(ctx, l1, in->d + (size_t)c0 * ct_words, ct_words, ls, cnt, st))) return rc;
         if ((rc = run_rotations(ctx, ctx->ws_desc, 2 * cnt, l1, ls, ls, st))) return rc;
         // y = q (x) cos + Rot(q; 1) (x) (neg sin) + Rot(q; -1) (x) (pos sin), rescaled once
@@ -1743,9 +1621,9 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
             ops[u].t = ops[u].pre ? ops[u].p : ctx->ws_ma + (u - op_base[k]) * 2 * l1 * N;
     const size_t ow = ops.size() * (sizeof(MmOperand) / 8), pw = pairs.size() * (sizeof(MmPair) / 8), bw = (begin.size() + 1) / 2;
     if ((rc = grow(ctx, &ctx->ws_mt, &ctx->ws_mt_words, ow + pw + bw + 2))) return rc;
-    if (!ops.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt, ops.data(), ops.size() * sizeof(MmOperand), hipMemcpyHostToDevice, st));
-    if (!pairs.empty()) ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + ow, pairs.data(), pairs.size() * sizeof(MmPair), hipMemcpyHostToDevice, st));
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_mt + ow + pw, begin.data(), begin.size() * 4, hipMemcpyHostToDevice, st));
+    if (!ops.empty()) ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_mt, ops.data(), ops.size() * sizeof(MmOperand), st));
+    if (!pairs.empty()) ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_mt + ow, pairs.data(), pairs.size() * sizeof(MmPair), st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_mt + ow + pw, begin.data(), begin.size() * 4, st));
     const u64 *d_consts;
     const double *d_fconsts;
     bool fp;
@@ -1787,7 +1665,7 @@ static int mult_core(ensi_ctx *ctx, const u64 *rkey, const std::vector<MmTerm> &
             desc[c].g = 1;
             desc[c].g_inv = 1;
         }
-        ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), cnt * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+        ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), cnt * sizeof(RotDesc), st));
         if ((rc = raise_cts(ctx, l1, ctx->ws_md, (size_t)3 * l1 * N, l1, cnt, st))) return rc;
         if ((rc = run_rotations(ctx, ctx->ws_desc, cnt, l1, l1, l1, st))) return rc;
         launch_mm_add_d1(ctx, g, st);
@@ -1911,7 +1789,7 @@ static int doubling_steps(ensi_ctx *ctx, const ensi_gk *gk, ensi_ct *t, int r_be
         }
     }
     if ((rc = ensure_desc(ctx, desc.size()))) return rc;
-    ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+    ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), st));
     size_t k = 0;
     for (const auto &grp : groups) {
         const int members = (int)grp.size();
@@ -2109,7 +1987,7 @@ static int rotate_columns(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *B, co
                 if ((rc = raise_cts(ctx, l1, B->d + (size_t)j0 * b_ct, b_ct, B->limbs_alloc, gs, st))) return rc;
                 raised = true;
             }
-            ENSI_HIP(ctx, hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st));
+            ENSI_HIP(ctx, host_to_device(ctx, ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), st));
             if ((rc = run_rotations(ctx, ctx->ws_desc, (int)desc.size(), l1, B->limbs_alloc, l1, st))) return rc;
         }
     }
@@ -2228,7 +2106,7 @@ static int rotate_jobs(ensi_ctx *ctx, const ensi_gk *gk, const u64 *src, size_t 
         std::vector<RotDesc> desc;
         auto flush = [&]() -> int {
             if (desc.empty()) return ENSI_OK;
-            if (hipMemcpyAsync(ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), hipMemcpyHostToDevice, st) != hipSuccess)
+            if (host_to_device(ctx, ctx->ws_desc, desc.data(), desc.size() * sizeof(RotDesc), st) != hipSuccess)
                 ENSI_FAIL(ctx, ENSI_E_HIP, "descriptor copy failed");
             const int r = run_rotations(ctx, ctx->ws_desc, (int)desc.size(), l1, limb_stride_in, l1, st);
             desc.clear();

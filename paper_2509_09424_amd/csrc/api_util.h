@@ -1,0 +1,69 @@
+// Small host-side helpers shared by the translation units that hold the C ABI.
+#pragma once
+#include <algorithm>
+#include <vector>
+
+#include "common.h"
+// ------------------------------------------------------------------ utilities
+
+struct DevBuf {
+    void *p = nullptr;
+    DevBuf() {}
+    DevBuf(const DevBuf &) = delete;
+    ~DevBuf() {
+        if (p) (void)hipFree(p);
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 8); }
+    template <class T>
+    T *as() { return (T *)p; }
+};
+
+template <class T>
+inline hipError_t upload(T **d, const std::vector<T> &h) {
+    hipError_t e = hipMalloc((void **)d, std::max<size_t>(h.size() * sizeof(T), 8));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+inline LimbMap make_map(const ensi_ctx *ctx, int l1, bool with_p) {
+    LimbMap m;
+    m.n = l1 + (with_p ? ctx->K : 0);
+    for (int e = 0; e < ENSI_MAX_EXT; e++) m.prime[e] = 0;
+    for (int e = 0; e < m.n; e++) m.prime[e] = e < l1 ? e : ctx->L + (e - l1);
+    return m;
+}
+
+inline u32 galois_element(const ensi_ctx *ctx, int32_t step) {
+    const int n = ctx->N / 2;
+    int k = step % n;
+    if (k < 0) k += n;
+    return ctx->rot_exp[k];
+}
+inline u32 inv_mod_2n(u32 g, int N) {
+    // g odd: Newton iteration modulo a power of two
+    u32 x = g;
+    for (int i = 0; i < 5; i++) x *= 2 - g * x;
+    return x & (2 * (u32)N - 1);
+}
+
+inline int grow(ensi_ctx *ctx, u64 **p, size_t *have, size_t need) {
+    if (*have >= need) return ENSI_OK;
+    if (*p) ENSI_HIP(ctx, hipFree(*p));
+    *p = nullptr;
+    *have = 0;
+    hipError_t e = hipMalloc((void **)p, need * sizeof(u64));
+    if (e != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation of %zu bytes failed: %s", need * sizeof(u64), hipGetErrorString(e));
+    *have = need;
+    return ENSI_OK;
+}
+
+
+
+// The library's own sampler of small polynomials (api_keys.hip): operating-system randomness when the context's
+// seed is 0, a deterministic test generator otherwise.  Return an ENSI_E_* code.
+int sample_ternary(ensi_ctx *ctx, int8_t *out, size_t n);
+int sample_error(ensi_ctx *ctx, int8_t *out, size_t n);
+
+// dst (device) <- src (host, any memory) on the stream, through the context's ring of pinned buffers: returns at once,
+// never waits for the stream, and src may be reused or freed as soon as the call returns.
+hipError_t host_to_device(ensi_ctx *ctx, void *dst, const void *src, size_t bytes, hipStream_t st);

@@ -142,7 +142,8 @@ struct RotDesc {
 // Everything about one ternary_matmul that depends only on (W, s, d, m, placement).
 struct MatmulPlan {
     u64 hash;
-    int s, d, m, placement, c_tot, n_in;
+    std::vector<int8_t> w_copy;  // the weights the plan was built from (cache hits are confirmed byte by byte)
+    int s, d, m, placement, c_tot, n_in, l1;
     int n_v, n_rot;
     std::vector<int> vid;        // [n_in][c_tot] -> operand index or -1
     int n_kpad, m_pad, planes;   // matrix-core layout (planes = 0: not built, use the plain-ALU kernel)
@@ -156,6 +157,16 @@ struct KernelTimer {
     double ms = 0;
     int64_t count = 0;
 };
+
+// One pinned host buffer of the ring that carries small host arrays (descriptors, term tables, constants) to the
+// device: the copy is asynchronous, and the buffer is reused only after the event recorded behind its copy has fired.
+struct StageSlot {
+    void *host = nullptr;
+    size_t cap = 0;
+    hipEvent_t ev = nullptr;
+    bool pending = false;
+};
+#define ENSI_STAGE_SLOTS 8
 
 struct ensi_ctx {
     ensi_params prm;
@@ -198,6 +209,10 @@ struct ensi_ctx {
     int pmult_mode = 0;                                 // 0 auto, 1 always the generic kernels
     // sampler state for NULL randomness
     u64 sampler_ctr = 0;
+    StageSlot stage[ENSI_STAGE_SLOTS];
+    int stage_next = 0;
+    int n_cu = 0;                // compute units of the context's device (0: not queried yet)
+    bool am_attr_set[2] = {false, false};  // dynamic LDS limit of the matrix-core accumulate raised (5- and 7-plane kernels)
     // timers
     bool profiling = false;
     std::vector<KernelTimer> timers;
@@ -205,6 +220,12 @@ struct ensi_ctx {
     std::string err;
 };
 
+// Weights of one Alg. 1 product prepared once (ensi_weights_prepare): the plan, owned by the handle.
+struct ensi_wt {
+    ensi_ctx *ctx;
+    MatmulPlan *plan;
+    int limbs;
+};
 struct ensi_sk {
     ensi_ctx *ctx;
     std::vector<int8_t> s;  // host copy
@@ -323,6 +344,12 @@ void launch_mul_mont(ensi_ctx *ctx, u64 *out, const u64 *a, const u64 *b_mont, i
                      hipStream_t st);
 void launch_add(ensi_ctx *ctx, u64 *out, const u64 *a, const u64 *b, int n_rows, const LimbMap &map, hipStream_t st);
 void launch_to_mont(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, hipStream_t st);
+// stored key words (Montgomery form, or doubles on the limbs the fused N = 2^16 kernels read as such) -> ordinary residues
+void launch_key_to_plain(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, bool fp_format, hipStream_t st);
+// *d_bad += number of words >= their prime
+void launch_count_noncanonical(ensi_ctx *ctx, const u64 *data, int n_rows, const LimbMap &map, unsigned int *d_bad, hipStream_t st);
+// d_sums[c] += wrap-around sum of the active limb words of ciphertext c
+void launch_ct_checksum(ensi_ctx *ctx, const u64 *ct, int n, int l1, int limb_stride, u64 *d_sums, hipStream_t st);
 // b = -a*s + e (+ factor[row] * sg), all transform domain; s_mont in Montgomery form; writes b in Montgomery form
 void launch_key_assemble(ensi_ctx *ctx, u64 *b_out, const u64 *a, const u64 *s_mont, const u64 *e, const u64 *sg,
                          const u64 *d_factor, const LimbMap &map, hipStream_t st);

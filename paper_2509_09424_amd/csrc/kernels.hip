@@ -415,6 +415,60 @@ void launch_to_mont(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, hi
     hipLaunchKernelGGL(k_to_mont, grid, dim3(EW_THREADS), 0, st, data, map, ctx->d_pc, ctx->N);
 }
 
+// Stored key words back to ordinary residues, in place: limbs that the fused N = 2^16 kernels keep as doubles in
+// [0,p) (fp_format, primes below 2^50) are converted, every other word leaves Montgomery form.
+__global__ __launch_bounds__(EW_THREADS) void k_key_to_plain(u64 *data, LimbMap map, const PrimeConst *pc, int N, int fp_format) {
+    const int idx = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int row = blockIdx.y;
+    const PrimeConst p = pc[map.prime[row % map.n]];
+    const size_t o = (size_t)row * N + idx;
+    if (fp_format && p.pad[0]) {
+        data[o] = (u64)__longlong_as_double((long long)data[o]);
+    } else {
+        acc128 t = {data[o], 0};
+        data[o] = mont_reduce(t, p.q, p.qneg_inv);
+    }
+}
+void launch_key_to_plain(ensi_ctx *ctx, u64 *data, int n_rows, const LimbMap &map, bool fp_format, hipStream_t st) {
+    dim3 grid((ctx->N + EW_THREADS - 1) / EW_THREADS, n_rows);
+    hipLaunchKernelGGL(k_key_to_plain, grid, dim3(EW_THREADS), 0, st, data, map, ctx->d_pc, ctx->N, fp_format ? 1 : 0);
+}
+
+// Number of words of a batch of limb rows that are not canonical residues (>= their prime), added to *bad.
+__global__ __launch_bounds__(EW_THREADS) void k_count_noncanonical(const u64 *data, LimbMap map, const PrimeConst *pc, int N, unsigned int *bad) {
+    const int idx = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (idx >= N) return;
+    const int row = blockIdx.y;
+    if (data[(size_t)row * N + idx] >= pc[map.prime[row % map.n]].q) atomicAdd(bad, 1u);
+}
+void launch_count_noncanonical(ensi_ctx *ctx, const u64 *data, int n_rows, const LimbMap &map, unsigned int *d_bad, hipStream_t st) {
+    dim3 grid((ctx->N + EW_THREADS - 1) / EW_THREADS, n_rows);
+    hipLaunchKernelGGL(k_count_noncanonical, grid, dim3(EW_THREADS), 0, st, data, map, ctx->d_pc, ctx->N, d_bad);
+}
+
+// Wrap-around 64-bit sum of the active limb words of every ciphertext of a batch: sums[c] += sum of the words of
+// ciphertext c ([2][limb_stride][N], first l1 limbs of each polynomial).  grid (ceil(N / (EW_THREADS * 8)), 2 * l1, n).
+__global__ __launch_bounds__(EW_THREADS) void k_ct_checksum(const u64 *ct, int l1, int limb_stride, int N, unsigned long long *sums) {
+    __shared__ unsigned long long part[EW_THREADS / 64];
+    const int c = blockIdx.z, poly = blockIdx.y / l1, limb = blockIdx.y - poly * l1;
+    const u64 *row = ct + (((size_t)c * 2 + poly) * limb_stride + limb) * N;
+    unsigned long long acc = 0;
+    for (int i = blockIdx.x * EW_THREADS * 8 + threadIdx.x; i < N && i < (int)(blockIdx.x + 1) * EW_THREADS * 8; i += EW_THREADS) acc += row[i];
+    for (int off = 32; off; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long t = 0;
+        for (int w = 0; w < EW_THREADS / 64; w++) t += part[w];
+        atomicAdd(&sums[c], t);
+    }
+}
+void launch_ct_checksum(ensi_ctx *ctx, const u64 *ct, int n, int l1, int limb_stride, u64 *d_sums, hipStream_t st) {
+    dim3 grid((ctx->N + EW_THREADS * 8 - 1) / (EW_THREADS * 8), 2 * l1, n);
+    hipLaunchKernelGGL(k_ct_checksum, grid, dim3(EW_THREADS), 0, st, ct, l1, limb_stride, ctx->N, (unsigned long long *)d_sums);
+}
+
 // b = -a*s + e + factor[row]*sg  (transform domain); s_mont is in Montgomery form;
 // b is written in Montgomery form.  One row per limb of map.
 __global__ __launch_bounds__(EW_THREADS) void k_key_assemble(u64 *b_out, const u64 *a, const u64 *s_mont, const u64 *e, const u64 *sg,

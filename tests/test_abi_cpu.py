@@ -69,3 +69,18 @@ def test_null_arguments_of_the_later_entry_points_without_gpu():
     assert lib.ensi_ccmm_left_giant_steps(n, n, n, 4, 2, 0, n, n) == -1
     assert lib.ensi_diagonalise_weights(n, n, n, 4, 2, 2, n, 0, n, n) == -1
     assert lib.ensi_ccmm_av(n, n, n, n, n, 4, 2, 2, 0, n, n, n) == -1
+
+
+def test_null_arguments_of_key_exchange_and_prepared_weights_without_gpu():
+    lib = binding.load()
+    n = None
+    d = ctypes.c_double
+    assert lib.ensi_sk_import(n, n, n) == -1 and lib.ensi_sk_export(n, n, n) == -1
+    assert lib.ensi_pk_import(n, n, n) == -1 and lib.ensi_pk_export(n, n, n) == -1
+    assert lib.ensi_gk_import(n, n, 1, n) == -1 and lib.ensi_gk_export(n, n, 1, n) == -1
+    assert lib.ensi_gk_elements(n, n, 0) == -1
+    assert lib.ensi_ct_checksum(n, n, n, n) == -1
+    assert lib.ensi_weights_prepare(n, n, 1, 1, 1, 0, 1, n) == -1
+    assert lib.ensi_ternary_matmul_prepared(n, n, n, n, n, n) == -1
+    assert lib.ensi_rescale_ternary_matmul_prepared(n, n, d(0.5), n, n, n) == -1
+    lib.ensi_weights_free(n)  # a null handle is ignored

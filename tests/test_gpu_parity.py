@@ -348,6 +348,57 @@ def test_full_ring_rotate_bit_exact(full):
     g_gk.free()
 
 
+def test_full_ring_rotate_all_sixteen_galois_elements(full, capsys):
+    """The key-switch microbenchmark's own step set at the full level: one ciphertext per Galois element (steps
+    2^0 .. 2^14 and -1), every one bit-exact against the oracle and a left shift of the slots after decryption."""
+    p = full
+    steps = list(wl.KEYSWITCH_STEPS)
+    assert len(steps) == 16 and len({p.pr.galois_element(st) for st in steps}) == 16
+    o_gks, g_gk = p.galois_keys(steps)
+    z = p.rng.uniform(-1, 1, (len(steps), p.n))
+    o_cts, g_ct = p.encrypt_both(z, p.pr.L)
+    out = p.ctx.rotate(g_gk, g_ct, steps)
+    got = out.export()
+    for i, st in enumerate(steps):
+        assert np.array_equal(got[i], p.o.rotate(o_cts[i], o_gks[st]).limbs()), "step %d" % st
+    dec = p.ctx.decrypt(p.g_sk, out)
+    err = max(np.abs(dec[i] - np.roll(z[i], -st)).max() for i, st in enumerate(steps))
+    assert err < 1e-3
+    with capsys.disabled():
+        print("\n[cfg 2, alpha = 3] 16 Galois elements bit-exact; decrypted max abs error %.3e" % err, flush=True)
+    out.free()
+    g_ct.free()
+    g_gk.free()
+
+
+def test_full_ring_rotate_literal_three_digits(capsys):
+    """The literal reading of "dnum = 3" for the key-switch configuration: 10 ciphertext primes in three digits of
+    4, 4 and 2 limbs (alpha = 4) against three special primes.  A digit is then larger than P, so the switching
+    noise is far above the 1e-3 bound: parity (which does not depend on the noise) is gated, the decrypted error is
+    only reported."""
+    w = wl.WORKLOADS[1]
+    p = Pair((w.log_n, w.q_bits, w.q_count, w.p_bits, w.p_count, 4, w.log_scale))
+    try:
+        assert p.pr.beta(p.pr.L) == 3
+        steps = [1, -1, 1 << 7, 1 << 14]
+        o_gks, g_gk = p.galois_keys(steps)
+        z = p.rng.uniform(-1, 1, (len(steps), p.n))
+        o_cts, g_ct = p.encrypt_both(z, p.pr.L)
+        out = p.ctx.rotate(g_gk, g_ct, steps)
+        got = out.export()
+        for i, st in enumerate(steps):
+            assert np.array_equal(got[i], p.o.rotate(o_cts[i], o_gks[st]).limbs()), "step %d" % st
+        dec = p.ctx.decrypt(p.g_sk, out)
+        err = max(np.abs(dec[i] - np.roll(z[i], -st)).max() for i, st in enumerate(steps))
+        with capsys.disabled():
+            print("\n[cfg 2, literal alpha = 4, beta = 3] bit-exact; decrypted max abs error %.3e (reported, not gated)" % err, flush=True)
+        out.free()
+        g_ct.free()
+        g_gk.free()
+    finally:
+        p.close()
+
+
 def test_full_ring_matmul_bit_exact(full):
     p = full
     s, d, m = p.n // 4, 6, 5  # c_tot = 4: two packed inputs, rotations by 1..3 blocks

@@ -1005,3 +1005,31 @@ def test_uniform_stream_follows_its_specification():
     key = mix((mix((mix(seed) + stream) & M) + pid) & M)
     want = [((mix((key + G * (2 * i + 1)) & M) << 64) | mix((key + G * (2 * i + 2)) & M)) % q for i in range(o.N)]
     assert [int(x) for x in got] == want
+
+
+def test_streamed_columns_equal_the_whole_product(tiny_oracle):
+    """The helper the full-size parity tests use (the oracle's Alg. 1 on sampled columns, streamed over blocks of
+    rotation amounts, several products of one input at once) returns exactly the columns of Oracle.ternary_matmul."""
+    from helpers import oracle_columns
+    w = wl.WORKLOADS[0]
+    o = tiny_oracle
+    pr = o.pr
+    rng = wl.rng_for(w.index, salt=3)
+    W1 = wl.ternary_weights(rng, w.d_in, w.d_out)
+    W2 = wl.ternary_weights(rng, w.d_in, 40)
+    W2[:, 7] = 0
+    X = wl.activations(rng, w.tokens, w.d_in, w.act)
+    sk, pk = _keys(o, rng)
+    cts = [_enc(o, rng, pk, wl.pack_columns(X, o.n)[0], pr.L)]
+    s, c_tot = w.tokens, w.c_tot
+    e = wl.error_poly(rng, (c_tot - 1, pr.beta(pr.L), o.N))
+    gks = {rho: o.galois_keygen(sk, rho * s, e[rho - 1], 33) for rho in range(1, c_tot)}
+    full1 = o.ternary_matmul(cts, s, w.d_in, W1, "diagonal", gks)
+    full2 = o.ternary_matmul(cts, s, w.d_in, W2, "zero", gks)
+    cols1, cols2 = [0, 5, 17, 63], [0, 7, 39]
+    got1, got2 = oracle_columns(o, sk, cts, s, [(W1, "diagonal", cols1), (W2, "zero", cols2)], lambda st: e[st // s - 1], 33, block=5)
+    for i in cols1:
+        assert np.array_equal(got1[i].limbs(), full1[i].limbs()), i
+    for i in cols2:
+        assert np.array_equal(got2[i].limbs(), full2[i].limbs()), i
+    assert not got2[7].limbs().any()
