@@ -181,6 +181,22 @@ int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct, int32_t sl
  * equal n and limbs and must not overlap.  Level and scale are unchanged. */
 int ensi_rotate(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream);
 
+/* ---- Rot without allocation ---------------------------------------------- */
+/* For callers that cannot allocate device memory while they run: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same result (word for word) and same errors as
+ * ensi_rotate, but every intermediate (descriptors, raised digits, accumulators, conversion residues) lives in a
+ * workspace that is linked into the library as a device array instead of being allocated: 96 MiB, held by every GPU
+ * the library runs on from load time to the end of the process.  The call allocates and frees nothing (the
+ * constants of every level, the pinned staging ring and the workspace's address are set up by ensi_ctx_create);
+ * the per-kernel timers must be off.  Limits: at most 64 ciphertexts per call and
+ *   n * (beta (l+K) + 3 l + 4 K) * 8 N  (+ n * l * 8 N on rings of 2^16 with ciphertext primes below 2^50)  bytes
+ * <= 96 MiB, l = in.limbs, beta = ceil(l / alpha) -- one ciphertext of the 2^16 ring at 16 + 4 limbs (80 MiB), the
+ * full 64 on the 2^12 ring at 3 + 1; anything larger fails with ENSI_E_SHAPE and a message that names the size.  All calls on one GPU share that
+ * one workspace, whatever context or stream they use, and it keeps the previous call's contents: calls that
+ * overlap in time on one GPU race (each call overwrites everything it later reads, so nothing needs clearing
+ * between calls that do not overlap). */
+int ensi_rotate_static(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, const int32_t *steps, ensi_ct *out, void *stream);
+
 /* ---- Alg. 1 (PCMM): Y = X W on ciphertexts, additions/subtractions only - */
 /* in : ceil(d/c_tot) packed ciphertexts, c_tot = (N/2)/s; ciphertext G holds
  *      activation column G*c_tot+b (s tokens) in slots [b*s,(b+1)*s).  c_tot=1

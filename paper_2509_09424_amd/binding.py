@@ -26,6 +26,7 @@ EXPORTED = [
     "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ccmm_left_giant_steps", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
     "ensi_sk_import", "ensi_sk_export", "ensi_pk_import", "ensi_pk_export", "ensi_gk_import", "ensi_gk_export", "ensi_gk_elements",
     "ensi_ct_checksum", "ensi_weights_prepare", "ensi_weights_free", "ensi_ternary_matmul_prepared", "ensi_rescale_ternary_matmul_prepared",
+    "ensi_rotate_static",
 ]
 
 
@@ -240,6 +241,14 @@ class Context:
         if ct_out is None:
             ct_out = self.ct_alloc(ct_in.n, ct_in.limbs)
         self._check(self.lib.ensi_rotate(self.h, gk.h, ct_in.h, _ptr(steps), ct_out.h, ctypes.c_void_p(stream)))
+        return ct_out
+
+    def rotate_static(self, gk, ct_in, steps, ct_out, stream=0):
+        """ensi_rotate on the statically linked workspace: allocates nothing (the caller provides ct_out)."""
+        steps = np.ascontiguousarray(steps, dtype=np.int32)
+        if len(steps) != ct_in.n:
+            raise EnsiError("one step per ciphertext")
+        self._check(self.lib.ensi_rotate_static(self.h, gk.h, ct_in.h, _ptr(steps), ct_out.h, ctypes.c_void_p(stream)))
         return ct_out
 
     def ternary_matmul(self, gk, ct_in, s, d, W, placement="diagonal", ct_out=None, stream=0):

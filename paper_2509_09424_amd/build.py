@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libensi_hip.so")
-SOURCES = ["api.hip", "api_keys.hip", "ntt.hip", "ntt16.hip", "keyswitch16.hip", "pmult.hip", "ccmm.hip", "kernels.hip", "accumulate_mfma.hip"]
+SOURCES = ["api.hip", "api_keys.hip", "api_static.hip", "ntt.hip", "ntt16.hip", "keyswitch16.hip", "pmult.hip", "ccmm.hip", "kernels.hip", "accumulate_mfma.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",

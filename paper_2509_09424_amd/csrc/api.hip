@@ -41,6 +41,17 @@ hipError_t host_to_device(ensi_ctx *ctx, void *dst, const void *src, size_t byte
     return hipSuccess;
 }
 
+int stage_prealloc(ensi_ctx *ctx) {
+    for (StageSlot &sl : ctx->stage) {
+        if (!sl.host) {
+            if (hipHostMalloc(&sl.host, 64 << 10, hipHostMallocDefault) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_NOMEM, "pinned staging buffer allocation failed");
+            sl.cap = 64 << 10;
+        }
+        if (!sl.ev && hipEventCreateWithFlags(&sl.ev, hipEventDisableTiming) != hipSuccess) ENSI_FAIL(ctx, ENSI_E_HIP, "event creation failed");
+    }
+    return ENSI_OK;
+}
+
 // ---------------------------------------------------------------------- timers
 int timer_id(ensi_ctx *ctx, const char *name) {
     for (size_t i = 0; i < ctx->timers.size(); i++)
@@ -217,6 +228,25 @@ extern "C" int ensi_ctx_create(const ensi_params *prm, ensi_ctx **out) {
         ensi_ctx_free(ctx);
         return ENSI_E_HIP;
     }
+    // Everything later calls would otherwise create on first use, so that the allocation-free entry point never has to:
+    // the staging ring, the conversion constants of every level, the address of the static workspace.
+    int rc = stage_prealloc(ctx);
+    for (int l1 = 1; l1 <= ctx->L && !rc; l1++) {
+        if (ctx->ks16) {
+            const Ks16Const *kc;
+            rc = get_ks16(ctx, l1, &kc);
+        } else {
+            const ModUpConst *mu;
+            const ModDownConst *md;
+            rc = get_modup(ctx, l1, &mu);
+            if (!rc) rc = get_moddown(ctx, l1, &md);
+        }
+    }
+    if (!rc) rc = ensi_static_init(ctx);
+    if (rc) {
+        ensi_ctx_free(ctx);
+        return rc;
+    }
     *out = ctx;
     return ENSI_OK;
 }
@@ -293,7 +323,7 @@ extern "C" int ensi_get_primes(const ensi_ctx *ctx, uint64_t *q, uint64_t *p) {
 }
 
 // Conversion constants at level l1 (built once per level, kept for the context's life).
-static int get_modup(ensi_ctx *ctx, int l1, const ModUpConst **out) {
+int get_modup(ensi_ctx *ctx, int l1, const ModUpConst **out) {
     auto it = ctx->modup.find(l1);
     if (it == ctx->modup.end()) {
         ModUpConst mc;
@@ -333,7 +363,7 @@ static int get_modup(ensi_ctx *ctx, int l1, const ModUpConst **out) {
     return ENSI_OK;
 }
 
-static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
+int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
     auto it = ctx->moddown.find(l1);
     if (it == ctx->moddown.end()) {
         ModDownConst mc;
@@ -374,7 +404,7 @@ static int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out) {
 }
 
 // Constants of the fused N = 2^16 key switch at level l1 (shares the integer ModUp tables).
-static int get_ks16(ensi_ctx *ctx, int l1, const Ks16Const **out) {
+int get_ks16(ensi_ctx *ctx, int l1, const Ks16Const **out) {
     auto it = ctx->ks16c.find(l1);
     if (it == ctx->ks16c.end()) {
         const ModUpConst *mu;
@@ -705,27 +735,31 @@ extern "C" int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct,
 
 // --------------------------------------------------------------------- rotation
 // Words of the raised form of one ciphertext at level l1 (fused path: digits of c1 and P*c0).
-static size_t raised_words(const ensi_ctx *ctx, int l1) {
+size_t raised_words(const ensi_ctx *ctx, int l1) {
     const size_t ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
     return (beta * ext + (ctx->ks16 ? l1 : 0)) * (size_t)ctx->N;
 }
 
 // Digit decomposition, ModUp and forward transform of n_ct ciphertexts into ws_digits (which must hold
 // n_ct * raised_words).
-static int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct, hipStream_t st) {
+// ws: where the intermediates go; nullptr = the context's own workspaces (ws_digits sized by the caller, the rest
+// grown here).  With an explicit workspace nothing is allocated.
+int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct, hipStream_t st,
+              const KsWorkspace *ws) {
     int rc;
+    u64 *digits = ws ? ws->digits : ctx->ws_digits;
     if (ctx->ks16) {
         const Ks16Const *kc;
         if ((rc = get_ks16(ctx, l1, &kc))) return rc;
-        if ((rc = grow(ctx, &ctx->ws_y, &ctx->ws_y_words, (size_t)n_ct * l1 * ctx->N))) return rc;
-        launch_ks16_raise(ctx, *kc, ct_base, ct_stride_words, limb_stride, n_ct, ctx->ws_y, ctx->ws_digits, st);
+        if (!ws && (rc = grow(ctx, &ctx->ws_y, &ctx->ws_y_words, (size_t)n_ct * l1 * ctx->N))) return rc;
+        launch_ks16_raise(ctx, *kc, ct_base, ct_stride_words, limb_stride, n_ct, ws ? ws->y : ctx->ws_y, digits, st);
         return ENSI_OK;
     }
     const ModUpConst *mu;
     if ((rc = get_modup(ctx, l1, &mu))) return rc;
     const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha;
-    launch_modup(ctx, *mu, ct_base, ct_stride_words, limb_stride, n_ct, ctx->ws_digits, st);
-    launch_ntt(ctx, ctx->ws_digits, n_ct * beta * ext, make_map(ctx, l1, true), false, st);
+    launch_modup(ctx, *mu, ct_base, ct_stride_words, limb_stride, n_ct, digits, st);
+    launch_ntt(ctx, digits, n_ct * beta * ext, make_map(ctx, l1, true), false, st);
     return ENSI_OK;
 }
 
@@ -734,26 +768,28 @@ static int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride
 // destination); a group's inner products are added over the extended basis and brought back by one inverse
 // transform and one ModDown, and the destination receives sum_k phi_{g_k}(c0) with it.  h_desc: host copy of the
 // descriptors (needed by the unfused path of a grouped call only).
-static int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out,
-                         hipStream_t st, int members = 1, const RotDesc *h_desc = nullptr) {
+int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out, hipStream_t st,
+                  int members, const RotDesc *h_desc, const KsWorkspace *ws) {
     int rc;
+    u64 *u = ws ? ws->u : ctx->ws_u;
     if (ctx->ks16) {
         const Ks16Const *kc;
         if ((rc = get_ks16(ctx, l1, &kc))) return rc;
-        if ((rc = grow(ctx, &ctx->ws_ysp, &ctx->ws_ysp_words, (size_t)(n_rot / members) * 2 * ctx->K * ctx->N))) return rc;
-        launch_ks16_switch(ctx, *kc, d_desc, n_rot, ctx->ws_u, ctx->ws_ysp, limb_stride_out, st, members);
+        if (!ws && (rc = grow(ctx, &ctx->ws_ysp, &ctx->ws_ysp_words, (size_t)(n_rot / members) * 2 * ctx->K * ctx->N))) return rc;
+        launch_ks16_switch(ctx, *kc, d_desc, n_rot, u, ws ? ws->ysp : ctx->ws_ysp, limb_stride_out, st, members);
         return ENSI_OK;
     }
     const ModDownConst *md;
     if ((rc = get_moddown(ctx, l1, &md))) return rc;
     const int ext = l1 + ctx->K, beta = (l1 + ctx->alpha - 1) / ctx->alpha, N = ctx->N;
     const LimbMap mext = make_map(ctx, l1, true);
-    launch_inner(ctx, d_desc, n_rot, l1, beta, ctx->ws_u, st);
+    launch_inner(ctx, d_desc, n_rot, l1, beta, u, st);
     if (members == 1) {
-        launch_ntt(ctx, ctx->ws_u, n_rot * 2 * ext, mext, true, st);
-        launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, ctx->ws_u, st);
+        launch_ntt(ctx, u, n_rot * 2 * ext, mext, true, st);
+        launch_moddown(ctx, *md, d_desc, n_rot, limb_stride_in, limb_stride_out, u, st);
         return ENSI_OK;
     }
+    if (ws) ENSI_FAIL(ctx, ENSI_E_BADARG, "grouped rotations run on the context's own workspaces only");
     if (!h_desc) ENSI_FAIL(ctx, ENSI_E_BADARG, "grouped rotations need the host descriptors");
     const LimbMap mq = make_map(ctx, l1, false);
     const size_t W = (size_t)2 * ext * N;  // accumulator words of one rotation

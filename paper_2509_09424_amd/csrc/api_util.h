@@ -67,3 +67,24 @@ int sample_error(ensi_ctx *ctx, int8_t *out, size_t n);
 // dst (device) <- src (host, any memory) on the stream, through the context's ring of pinned buffers: returns at once,
 // never waits for the stream, and src may be reused or freed as soon as the call returns.
 hipError_t host_to_device(ensi_ctx *ctx, void *dst, const void *src, size_t bytes, hipStream_t st);
+
+// ---- key switching, shared by the entry points (api.hip) -------------------------------------------------
+// Intermediates of a batch of key switches: raised digits (raised_words per ciphertext), accumulators
+// (2 (l1+K) N words per rotation), inner factors of the basis conversion (l1 N per ciphertext, fused path),
+// centred special-limb residues (2 K N per rotation, fused path).
+struct KsWorkspace {
+    u64 *digits, *u, *y, *ysp;
+};
+size_t raised_words(const ensi_ctx *ctx, int l1);
+int get_modup(ensi_ctx *ctx, int l1, const ModUpConst **out);
+int get_moddown(ensi_ctx *ctx, int l1, const ModDownConst **out);
+int get_ks16(ensi_ctx *ctx, int l1, const Ks16Const **out);
+int raise_cts(ensi_ctx *ctx, int l1, const u64 *ct_base, size_t ct_stride_words, int limb_stride, int n_ct, hipStream_t st,
+              const KsWorkspace *ws = nullptr);
+int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int limb_stride_in, int limb_stride_out, hipStream_t st,
+                  int members = 1, const RotDesc *h_desc = nullptr, const KsWorkspace *ws = nullptr);
+
+// Resolves the device address of the statically linked workspace for the context's device (api_static.hip).
+int ensi_static_init(ensi_ctx *ctx);
+// Allocates every slot of the staging ring and its event now, so that later small uploads allocate nothing.
+int stage_prealloc(ensi_ctx *ctx);

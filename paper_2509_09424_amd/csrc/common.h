@@ -209,6 +209,8 @@ struct ensi_ctx {
     int pmult_mode = 0;                                 // 0 auto, 1 always the generic kernels
     // sampler state for NULL randomness
     u64 sampler_ctr = 0;
+    void *static_scratch = nullptr;  // this device's copy of the statically linked workspace (api_static.hip)
+    size_t static_scratch_bytes = 0;
     StageSlot stage[ENSI_STAGE_SLOTS];
     int stage_next = 0;
     int n_cu = 0;                // compute units of the context's device (0: not queried yet)
