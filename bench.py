@@ -29,6 +29,7 @@ HBM_PEAK_GBS = 8000.0
 INT8_MFMA_PEAK_TOPS = 5000.0  # dense int8 matrix-core peak, TOP/s
 # plain integer ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit lane-ops/s; one 64-bit add = 2 of them
 U64_ADD_PEAK = 256 * 4 * 16 * 2.4e9 / 2
+NNZ_FRACTION = 0.6  # P(-1) + P(+1) of the synthetic ternary weights
 
 
 def log(msg):
@@ -49,6 +50,17 @@ class Runner:
     def sync(self):
         import torch
         torch.cuda.synchronize()
+
+    def close(self):
+        """Frees every device-side handle of this runner and its context (a later leg needs the memory)."""
+        import torch
+        torch.cuda.synchronize()
+        for name, v in list(vars(self).items()):
+            if name != "ctx" and hasattr(v, "free") and hasattr(v, "h"):
+                v.free()
+        self.buf = None
+        self.ctx.close()
+        torch.cuda.empty_cache()
 
     # ---- workload set-up (untimed): inputs and keys made resident on the device
     def setup(self):
@@ -253,8 +265,11 @@ class Runner:
         self.gk = self.ctx.galois_keygen(self.sk, rot_steps, None, 13) if rot_steps else None
         log("generated %d Galois keys in %.1f s" % (len(rot_steps), time.time() - t0))
         self.ct_out = self.ctx.ct_alloc(w.d_mid or w.d_out, self.L)
+        # everything Alg. 1 derives from the weights alone is built once, outside the step (the weights of a layer are static)
+        self.wt = self.ctx.weights_prepare(self.W, w.tokens, w.d_in, w.placement, self.L)
         if w.d_mid:
             self.ct_out2 = self.ctx.ct_alloc(w.d_out, self.L - 1)
+            self.wt2 = self.ctx.weights_prepare(self.W2, self.n, w.d_mid, "zero", self.L - 1)
 
     def step(self):
         w = self.w
@@ -282,7 +297,7 @@ class Runner:
         if w.op == "ccmm_segment":
             self.ctx.ccmm_segment(self.rk, self.gk, self.ct_a, self.ct_in, w.tokens, w.period, self.baby, 1, self.pt, self.pt2, self.ct_out)
             return
-        self.ctx.ternary_matmul(self.gk, self.ct_in, w.tokens, w.d_in, self.W, w.placement, self.ct_out)
+        self.ctx.ternary_matmul_prepared(self.gk, self.ct_in, self.wt, self.ct_out)
         if w.d_mid:
             # the rescale works in place and lowers the level: restore the handle's level by re-wrapping
             if getattr(self, "mid", None) is not None:
@@ -291,10 +306,10 @@ class Runner:
             self.mid = mid
             if self.separate_rescale:
                 self.ctx.mul_scalar_rescale(mid, w.kappa)
-                self.ctx.ternary_matmul(None, mid, self.n, w.d_mid, self.W2, "zero", self.ct_out2)
+                self.ctx.ternary_matmul_prepared(None, mid, self.wt2, self.ct_out2)
             else:
                 # scalar-multiply + rescale applied while the second layer reads its operands
-                self.ctx.rescale_ternary_matmul(mid, w.kappa, self.W2, self.ct_out2)
+                self.ctx.rescale_ternary_matmul_prepared(mid, w.kappa, self.wt2, self.ct_out2)
 
     def check(self):
         """Decrypts a few outputs and compares with the float64 product (sanity, untimed)."""
@@ -369,11 +384,24 @@ def kernel_profile(runner):
     return prof
 
 
-# HBM-side bytes per launch of a workload's dominant kernel, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-# summarised under profiles/ (counter x calibration factor, averaged over the launches of one step).
-MEASURED_TRAFFIC = {
-    ("ffn2560", "accumulate_mfma"): (842.7 + 145.5) * 2.0 ** 30 / 9,
-}
+def profile_facts(workload, kernel):
+    """Figures that come from rocprofv3 counter runs rather than from this process, read from the tracked summary
+    profiles/bench_<workload>_kernels_and_hbm_counters.txt: lines of the form
+        @facts <kernel> key=value key=value ...
+    (fetch_GiB_per_step, write_GiB_per_step, launches_per_step, mfma_busy, valu_util, sclk_GHz).  Returns {} when the
+    summary or the line is missing, so a stale constant can never be reported."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_kernels_and_hbm_counters.txt" % workload)
+    facts = {}
+    try:
+        for line in open(path):
+            t = line.split()
+            if len(t) >= 2 and t[0] == "@facts" and t[1] == kernel:
+                for kv in t[2:]:
+                    k, _, v = kv.partition("=")
+                    facts[k] = float(v)
+    except OSError:
+        pass
+    return facts
 
 
 def fill_counts(r_begin, r_end):
@@ -524,15 +552,24 @@ def roofline_for(w, prof):
         # Alg. 1 on the matrix cores: one int8 multiply-add per (output, operand, limb word, byte plane); 7 planes at 50 bits
         planes = -(-w.q_bits // 8)
         planes = 5 if planes <= 5 else 7 if planes <= 7 else 8
-        dm = w.d_in * (w.d_mid or w.d_out) + (w.d_mid * w.d_out if w.d_mid else 0)
-        ops = 2.0 * dm * 2 * L * N * planes
-        return dom, {"bound": "mfma", "achieved": ops / (ms * 1e-3) / 1e12, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": MEASURED_TRAFFIC.get((w.name, dom)), "kernel": dom,
-                     "launch_ms": ms / max(launches, 1), "launches": launches, "ops_per_launch": ops / max(launches, 1)}
+        # (outputs x operands x limb words) of each layer; the second layer of the FFN workload runs one level down
+        cells = w.d_in * (w.d_mid or w.d_out) * 2.0 * L * N + (w.d_mid * w.d_out * 2.0 * (L - 1) * N if w.d_mid else 0)
+        ops = 2.0 * cells * planes              # dense: every weight, zero or not, is a multiply-add per byte plane
+        own = 2.0 * NNZ_FRACTION * cells * planes  # the method's own work (Alg. 1 skips zero weights), in the same unit
+        facts = profile_facts(w.name, dom)
+        traffic = None
+        if "fetch_GiB_per_step" in facts and "write_GiB_per_step" in facts:
+            traffic = (facts["fetch_GiB_per_step"] + facts["write_GiB_per_step"]) * 2.0 ** 30 / max(launches, 1)
+        tops = ops / (ms * 1e-3) / 1e12
+        return dom, {"bound": "mfma", "achieved": tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": tops / INT8_MFMA_PEAK_TOPS, "frac_dense": tops / INT8_MFMA_PEAK_TOPS,
+                     "frac_own_work": own / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "traffic": traffic, "kernel": dom,
+                     "launch_ms": ms / max(launches, 1), "launches": launches, "ops_per_launch": ops / max(launches, 1),
+                     "algorithmic_bytes_per_launch": ((w.d_in + (w.d_mid or w.d_out)) * 2 * L + ((w.d_mid + w.d_out) * 2 * (L - 1) if w.d_mid else 0)) * unit / max(launches, 1),
+                     "mfma_busy": facts.get("mfma_busy"), "valu_util": facts.get("valu_util"), "sclk_GHz": facts.get("sclk_GHz")}
     if dom == "accumulate":
         # Alg. 1: one 64-bit add/sub per non-zero weight per limb word
-        nnz = 0.6 * w.d_in * (w.d_mid or w.d_out) + (0.6 * w.d_mid * w.d_out if w.d_mid else 0)
-        ops = nnz * 2 * L * N
+        ops = NNZ_FRACTION * (w.d_in * (w.d_mid or w.d_out) * 2.0 * L * N + (w.d_mid * w.d_out * 2.0 * (L - 1) * N if w.d_mid else 0))
         return dom, {"bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12, "peak": U64_ADD_PEAK / 1e12, "unit": "Tadd64/s",
                      "frac": ops / (ms * 1e-3) / U64_ADD_PEAK, "traffic": None, "kernel": dom,
                      "launch_ms": ms / max(launches, 1), "launches": launches}
@@ -662,6 +699,82 @@ def stagewise_rotation_units(w):
     return 2 * L + (L + E) + 2 * E + (3 * beta * ext + 2 * ext) + 4 * K + (2 * K + 2 * L) + 4 * L + 7 * L
 
 
+def ntt_leg(ctx, w, n_limbs=1024, reps=5):
+    """Stand-alone transform throughput (row (a1) of the scope table): n_limbs limb rows of N words, forward then
+    inverse, in place, timed by the library's per-kernel HIP events; once on 50-bit ciphertext primes (the fp64-assisted
+    kernels) and once on the 60-bit special primes (integer kernels).  Algorithmic bytes: a transform reads and
+    writes its limb once (2 limb-units); the two-pass implementation moves each limb twice (4 limb-units)."""
+    import torch
+    N = w.N
+    buf = torch.randint(0, 1 << 49, (n_limbs, N), dtype=torch.int64, device="cuda")
+    out = {}
+    for tag, primes in (("q50", list(range(w.q_count))), ("p60", list(range(w.q_count, w.q_count + w.p_count)))):
+        idx = [primes[r % len(primes)] for r in range(n_limbs - n_limbs % len(primes))]
+        rows = len(idx)
+        ctx.ntt(buf.data_ptr(), idx, inverse=False)
+        ctx.ntt(buf.data_ptr(), idx, inverse=True)
+        torch.cuda.synchronize()
+        ctx.profile_read()
+        ctx.profile_enable(True)
+        for _ in range(reps):
+            ctx.ntt(buf.data_ptr(), idx, inverse=False)
+            ctx.ntt(buf.data_ptr(), idx, inverse=True)
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+        ms = sum(prof.get(k, (0.0, 0))[0] for k in ("ntt_fwd_cols", "ntt_fwd_rows", "ntt_inv_rows", "ntt_inv_cols")) / reps
+        units = 2 * rows  # transforms per repetition (forward + inverse of every row)
+        gbs2 = units * 2 * 8.0 * N / (ms * 1e-3) / 1e9
+        out[tag] = {"limbs": rows, "ms_fwd_plus_inv": round(ms, 4), "transforms_per_s": units / (ms * 1e-3),
+                    "GB/s_at_2_units": round(gbs2, 1), "frac_at_2_units": round(gbs2 / HBM_PEAK_GBS, 4),
+                    "GB/s_at_4_units": round(2 * gbs2, 1), "frac_at_4_units": round(2 * gbs2 / HBM_PEAK_GBS, 4),
+                    "kernels_ms": {k: round(v[0] / reps, 4) for k, v in sorted(prof.items()) if v[1]}}
+    del buf
+    return out
+
+
+def run_leg(name, steps, warmup, separate_rescale=False, with_ntt=False):
+    """One workload: set-up, timed steps, decrypted check, per-kernel profile.  Returns the leg's dictionary."""
+    w = wl.BY_NAME[name]
+    t0 = time.time()
+    r = Runner(w, separate_rescale=separate_rescale)
+    try:
+        r.setup()
+        log("%s: set-up done in %.1f s" % (name, time.time() - t0))
+        ms = time_steps(r, steps, warmup)
+        err = r.check()
+        prof = kernel_profile(r)
+        dom, roof = roofline_for(w, prof)
+        log("%s: %.3f ms/step over %d steps, decrypted max abs error %.3e, dominant kernel %s" % (name, ms, steps, err, dom))
+        leg = {"workload": name, "ms_per_step": ms, "steps": steps, "decrypt_max_abs_err": err, "roofline": roof,
+               "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(prof.items())},
+               "hbm_kernels": hbm_fractions(w, prof)}
+        if hasattr(r, "prepare_ms"):
+            leg["prepare_ms"] = r.prepare_ms
+        if w.name == "keyswitch":
+            rps = w.batch / (ms * 1e-3)
+            gbs = rps * stagewise_rotation_units(w) * 8.0 * w.N / 1e9
+            leg.update({"value": rps, "unit": "rotations/s", "ms_per_batch": ms,
+                        "stagewise": {"units_per_rotation": stagewise_rotation_units(w), "GB/s": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}})
+        if with_ntt:
+            leg["ntt"] = ntt_leg(r.ctx, w)
+        return leg
+    finally:
+        r.close()
+
+
+def compact(leg):
+    """What the extra legs contribute to the line: time, error, dominant kernel and its fraction."""
+    roof = leg["roofline"]
+    out = {"ms_per_step": round(leg["ms_per_step"], 3), "decrypt_max_abs_err": leg["decrypt_max_abs_err"], "dominant_kernel": roof["kernel"],
+           "bound": roof["bound"], "frac": round(roof["frac"], 4), "kernels_ms_per_step": {k: v["ms"] for k, v in leg["kernels_ms_per_step"].items()}}
+    if "frac_own_work" in roof:
+        out["frac_own_work"] = round(roof["frac_own_work"], 4)
+    if "prepare_ms" in leg:
+        out["prepare_ms"] = round(leg["prepare_ms"], 1)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -670,6 +783,8 @@ def main():
     ap.add_argument("--workload", default="ffn2560", choices=[w.name for w in wl.WORKLOADS])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-keyswitch-leg", action="store_true")
+    ap.add_argument("--no-extra-legs", action="store_true",
+                    help="skip the compact legs of the other BASELINE matmul configurations and of the NEXT-row workloads")
     ap.add_argument("--separate-rescale", action="store_true",
                     help="FFN workload: run scalar-multiply + rescale as its own in-place pass instead of inside the second layer")
     ap.add_argument("--copy-probe", action="store_true",
@@ -685,17 +800,8 @@ def main():
     torch.cuda.init()
     w = wl.BY_NAME[args.workload]
     log("workload %s on %s" % (w.name, torch.cuda.get_device_name(0)))
-    t0 = time.time()
-    r = Runner(w, separate_rescale=args.separate_rescale)
-    r.setup()
-    log("set-up done in %.1f s" % (time.time() - t0))
-    ms = time_steps(r, args.steps, args.warmup)
-    log("timed %d steps: %.3f ms/step" % (args.steps, ms))
-    err = r.check()
-    log("decrypted max abs error on sampled outputs: %.3e" % err)
-    prof = kernel_profile(r)
-    dom, roof = roofline_for(w, prof)
-    kernels = {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(prof.items())}
+    main_leg = run_leg(w.name, args.steps, args.warmup, separate_rescale=args.separate_rescale, with_ntt=(w.name == "keyswitch"))
+    ms = main_leg["ms_per_step"]
     line = {
         "metric": "encrypted ternary matmul ms/layer + key-switched rotations/sec at N=2^16",
         "value": ms, "unit": "ms/layer" if (w.name != "keyswitch" and w.op == "matmul") else "ms/batch",
@@ -703,14 +809,14 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
         "config": {"workload": w.name, "log_n": w.log_n, "q_limbs": w.q_count, "p_limbs": w.p_count, "alpha": w.alpha,
                    "tokens": w.tokens, "d_in": w.d_in, "d_mid": w.d_mid, "d_out": w.d_out, "placement": w.placement},
-        "decrypt_max_abs_err": err, "roofline": roof, **({"prepare_ms": r.prepare_ms} if hasattr(r, "prepare_ms") else {}), "kernels_ms_per_step": kernels, "hbm_kernels": hbm_fractions(w, prof),
+        "decrypt_max_abs_err": main_leg["decrypt_max_abs_err"], "roofline": main_leg["roofline"],
+        **({"prepare_ms": main_leg["prepare_ms"]} if "prepare_ms" in main_leg else {}),
+        "kernels_ms_per_step": main_leg["kernels_ms_per_step"], "hbm_kernels": main_leg["hbm_kernels"],
     }
     if w.name == "keyswitch":
-        rps = w.batch / (ms * 1e-3)
-        gbs = rps * stagewise_rotation_units(w) * 8.0 * w.N / 1e9
-        line["rotations"] = {"value": rps, "unit": "rotations/s", "workload": "keyswitch",
-                             "stagewise": {"units_per_rotation": stagewise_rotation_units(w), "GB/s": gbs, "frac_of_hbm_peak": gbs / HBM_PEAK_GBS}}
-    del r
+        line["rotations"] = {k: main_leg[k] for k in ("value", "unit", "stagewise")}
+        line["rotations"]["workload"] = "keyswitch"
+        line["ntt"] = main_leg["ntt"]
     if args.copy_probe:
         a = torch.zeros(1 << 27, dtype=torch.int64, device="cuda")
         b = torch.empty_like(a)
@@ -719,19 +825,25 @@ def main():
         torch.cuda.synchronize()
         del a, b
     if w.name != "keyswitch" and not args.no_keyswitch_leg:
-        kw = wl.BY_NAME["keyswitch"]
-        rk = Runner(kw)
-        rk.setup()
-        kms = time_steps(rk, max(args.steps, 5), args.warmup)
-        kerr = rk.check()
-        kprof = kernel_profile(rk)
-        _, kroof = roofline_for(kw, kprof)
-        kgbs = kw.batch / (kms * 1e-3) * stagewise_rotation_units(kw) * 8.0 * kw.N / 1e9
-        line["rotations"] = {"value": kw.batch / (kms * 1e-3), "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": kms,
-                             "stagewise": {"units_per_rotation": stagewise_rotation_units(kw), "GB/s": kgbs, "frac_of_hbm_peak": kgbs / HBM_PEAK_GBS},
-                             "decrypt_max_abs_err": kerr, "roofline": kroof, "hbm_kernels": hbm_fractions(kw, kprof),
-                             "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(kprof.items())}}
-        log("key-switch leg: %.1f rotations/s" % line["rotations"]["value"])
+        # BASELINE configs[1]: the rotations/s half of the metric, with the stand-alone transform beside it
+        k = run_leg("keyswitch", max(args.steps, 5), args.warmup, with_ntt=True)
+        line["rotations"] = {"value": k["value"], "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": k["ms_per_batch"],
+                             "stagewise": k["stagewise"], "decrypt_max_abs_err": k["decrypt_max_abs_err"], "roofline": k["roofline"],
+                             "hbm_kernels": k["hbm_kernels"], "kernels_ms_per_step": k["kernels_ms_per_step"]}
+        line["ntt"] = k["ntt"]
+        log("key-switch leg: %.1f rotations/s" % k["value"])
+    if w.name == "ffn2560" and not args.no_extra_legs:
+        # the metric is ms/layer on the three BitNet-shaped configurations: the other two as compact legs, then the rows
+        # beyond the hot path (Alg. 2, the merge, the two attention products).  A leg that fails is reported, not fatal.
+        n_extra = min(args.steps, 5)
+        for key, names in (("other_configs", ["attn2560", "proj768"]), ("next_rows", ["rope1536", "merge1536", "ccmmqkseg", "ccmmavseg"])):
+            line[key] = {}
+            for name in names:
+                try:
+                    line[key][name] = compact(run_leg(name, n_extra, 1))
+                except Exception as e:  # noqa: BLE001
+                    line[key][name] = {"error": "%s: %s" % (type(e).__name__, e)}
+                    log("%s failed: %s" % (name, e))
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(line), flush=True)

@@ -82,6 +82,35 @@ __device__ __forceinline__ u64 reduce_signed(int64_t t, u64 q, double q_inv) {
     return (u64)r;
 }
 
+// The same recombination for primes below 2^50, in double precision on exact integers (no 64-bit integer
+// multiplies, which take many quarter-rate instructions on this chip).  S_p: the plane sums from the matrix
+// pipe, b = 128 * (column sum of the weights), so that the true plane sums are T_p = S_p + b and the result is
+// sum_p T_p 2^(8p) mod q.  Planes are first paired in 32-bit integers (|T_p| < 2^22 for up to 32768 operands, so
+// T_p + 2^8 T_(p+1) < 2^31), the pairs combined into lo + 2^32 hi with |lo| < 2^47 and |hi| < 2^38 -- every product
+// by a power of two and every sum below 2^53 is exact in a double --, 2^32 hi reduced on its own (its quotient by q
+// is below 2^21, and x - k q is an integer below 2^52 that the fused multiply-add returns exactly), and lo added
+// before the final reduction to (-q/2, q/2] and the shift into [0, q).
+template <int PLANES>
+__device__ __forceinline__ u64 recombine_fp(const int (&S)[PLANES], int b, double q, double q_inv) {
+    const int b257 = b * 257;
+    const int c01 = S[0] + S[1] * 256 + b257, c23 = S[2] + S[3] * 256 + b257;
+    const double lo = fma((double)c23, 65536.0, (double)c01);
+    double hi;
+    if (PLANES == 7) {
+        const int c45 = S[4] + S[5] * 256 + b257, c6 = S[6] + b;
+        hi = fma((double)c6, 65536.0, (double)c45);
+    } else {
+        hi = (double)(S[4] + b);
+    }
+    const double x = hi * 4294967296.0;
+    const double r = fma(-rint(x * q_inv), q, x);
+    const double s = lo + r;
+    double u = fma(-rint(s * q_inv), q, s);
+    u = u < 0.0 ? u + q : u;
+    // an integer in [0, 2^52) plus 2^52 has that integer as its mantissa
+    return (u64)__double_as_longlong(u + 4503599627370496.0) & 0xFFFFFFFFFFFFFull;
+}
+
 // ---------------------------------------------------------------- byte planes of the operands
 // Slice-local word tile: nt_local = pl * cw + ctile, pl = poly * l1 + limb, ctile = coefficient tile - c0.
 // Thread (k4 = tid / 32, ln = tid % 32) handles operands 4*k4 .. 4*k4+3 of a step, word ln: its four
@@ -217,7 +246,9 @@ struct AmLayout {
 
 // xp: plane tiles of the slice, [word tile][nk][PLANES][1024]; the slice covers coefficient tiles c0 .. c0+cw-1
 // of all 2*l1 limb rows (n_tiles_n = 2*l1*cw word tiles); nk = n_kpad / 32, a multiple of AM_RING.
-template <int PLANES>
+// FP_EPI: every active prime is below 2^50, so the planes are recombined in double precision (recombine_fp); else
+// in 64-bit integers.
+template <int PLANES, bool FP_EPI>
 __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int c0, int cw, int n_kpad, const v4i *wfrag, const int32_t *bias,
                                                                 int m, AmPrimes pr, int N, int l1, u64 *out, int limb_stride_out,
                                                                 int n_tiles_n, int n_tiles_m, int workers_per_xcd, int m_group) {
@@ -384,22 +415,40 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
         // Accumulator register r of a lane holds output row 8*(r/4) + 4*(lane/32) + r%4 of the 32x32
         // block, column lane%32.
         const u64 q = pr.q[limb];
-        const double q_inv = pr.q_inv[limb];
+        const double q_inv = pr.q_inv[limb], qd = (double)q;
         u64 ones = 0;
 #pragma unroll
         for (int p = 0; p < PLANES; p++) ones |= (u64)1 << (8 * p);
+        const bool whole = i0 + 64 <= m;  // all 64 outputs of this wave exist (wave-uniform): stores need no bounds check
 #pragma unroll
         for (int mb = 0; mb < 2; mb++) {
 #pragma unroll
             for (int c = 0; c < 4; c++) {
                 const int ib = i0 + mb * 32 + 8 * c + 4 * g;  // rows ib .. ib+3
                 const v4i b4 = *(const v4i *)(bl + (ib - m_tile * AM_TILE_M));
+                u64 res[4];
 #pragma unroll
                 for (int e = 0; e < 4; e++) {
-                    int64_t t = (int64_t)((u64)(int64_t)b4[e] * ones);
+                    if (FP_EPI) {
+                        int S[PLANES];
 #pragma unroll
-                    for (int p = 0; p < PLANES; p++) t += (int64_t)((u64)(int64_t)acc[p][mb][4 * c + e] << (8 * p));
-                    if (ib + e < m) out[(size_t)(ib + e) * ct_words_out + off_out + nl] = reduce_signed(t, q, q_inv);
+                        for (int p = 0; p < PLANES; p++) S[p] = acc[p][mb][4 * c + e];
+                        res[e] = recombine_fp<PLANES>(S, b4[e], qd, q_inv);
+                    } else {
+                        int64_t t = (int64_t)((u64)(int64_t)b4[e] * ones);
+#pragma unroll
+                        for (int p = 0; p < PLANES; p++) t += (int64_t)((u64)(int64_t)acc[p][mb][4 * c + e] << (8 * p));
+                        res[e] = reduce_signed(t, q, q_inv);
+                    }
+                }
+                u64 *o = out + (size_t)ib * ct_words_out + off_out + nl;
+                if (whole) {
+#pragma unroll
+                    for (int e = 0; e < 4; e++) o[(size_t)e * ct_words_out] = res[e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; e++)
+                        if (ib + e < m) o[(size_t)e * ct_words_out] = res[e];
                 }
             }
         }
@@ -408,13 +457,13 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
     wait_vmcnt<0>();  // no copy may still be in flight into LDS when the workgroup ends
 }
 
-template <int P>
+template <int P, bool FP_EPI>
 static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
                       const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_m, int workers,
                       int m_group, char *xp, int slice_ctiles, const double *d_rescale) {
-    bool &attr_set = ctx->am_attr_set[P == 5 ? 0 : 1];
+    bool &attr_set = ctx->am_attr_set[(P == 5 ? 0 : 1) + (FP_EPI ? 0 : 2)];
     if (!attr_set) {
-        (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
+        (void)hipFuncSetAttribute((const void *)k_accumulate_mfma<P, FP_EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, AmLayout<P>::total);
         attr_set = true;
     }
     const int nk = n_kpad / AM_TILE_K, ctiles = ctx->N / AM_TILE_N;
@@ -436,7 +485,7 @@ static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *x
         }
         {
             ScopedTimer t(ctx, "accumulate_mfma", st);
-            hipLaunchKernelGGL(k_accumulate_mfma<P>, dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, (const char *)xp, c0, cw, n_kpad, wfrag,
+            hipLaunchKernelGGL((k_accumulate_mfma<P, FP_EPI>), dim3(grid), dim3(AM_THREADS), AmLayout<P>::total, st, (const char *)xp, c0, cw, n_kpad, wfrag,
                                bias, m, pr, ctx->N, l1, out, limb_stride_out, 2 * l1 * cw, n_tiles_m, workers, m_group);
         }
     }
@@ -479,11 +528,18 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
         }
         ctx->ws_xp_words = xp_words;
     }
-    if (P == 5)
-        am_launch<5>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, workers,
-                     m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale);
-    else
-        am_launch<7>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, workers,
-                     m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale);
+    bool fp_epi = true;  // the double-precision recombination is exact while every active prime is below 2^50
+    for (int i = 0; i < l1; i++) fp_epi = fp_epi && ctx->primes[i] < ((u64)1 << 50);
+#define AM_LAUNCH(PL, FP)                                                                                                              \
+    am_launch<PL, FP>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, \
+                      workers, m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale)
+    if (P == 5) {
+        if (fp_epi) AM_LAUNCH(5, true);
+        else AM_LAUNCH(5, false);
+    } else {
+        if (fp_epi) AM_LAUNCH(7, true);
+        else AM_LAUNCH(7, false);
+    }
+#undef AM_LAUNCH
     return ENSI_OK;
 }

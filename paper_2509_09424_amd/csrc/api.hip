@@ -932,7 +932,8 @@ static int build_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int p
     int qbits = 0;
     for (int i = 0; i < l1; i++) qbits = std::max(qbits, 64 - __builtin_clzll(ctx->primes[i]));
     // |sum of n_v residues| <= n_v * (2^qbits - 1) must stay below 2^63
-    const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && qbits <= 56 && (u64)n_v <= ((u64)1 << (63 - qbits));
+    // (and a plane sum of n_v bytes, shifted by eight bits, has to fit a signed 32-bit word: n_v <= 32768)
+    const bool mfma_ok = ctx->N >= 32 && n_v >= 1 && n_v <= 32768 && qbits <= 56 && (u64)n_v <= ((u64)1 << (63 - qbits));
     p->planes = 0;
     p->n_kpad = (std::max(n_v, 1) + 255) / 256 * 256;  // whole groups of eight 32-operand steps
     p->m_pad = (m + 255) / 256 * 256;

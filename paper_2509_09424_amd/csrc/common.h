@@ -214,7 +214,7 @@ struct ensi_ctx {
     StageSlot stage[ENSI_STAGE_SLOTS];
     int stage_next = 0;
     int n_cu = 0;                // compute units of the context's device (0: not queried yet)
-    bool am_attr_set[2] = {false, false};  // dynamic LDS limit of the matrix-core accumulate raised (5- and 7-plane kernels)
+    bool am_attr_set[4] = {false, false, false, false};  // dynamic LDS limit of the matrix-core accumulate kernels raised
     // timers
     bool profiling = false;
     std::vector<KernelTimer> timers;

@@ -30,9 +30,28 @@ def test_key_switch_counts_of_the_microbenchmark():
 def test_matrix_core_operation_count():
     w = wl.BY_NAME["ffn2560"]
     _, roof = bench.roofline_for(w, {"accumulate_mfma": (100.0, 9)})
-    ops = 2.0 * (2560 * 6912 + 6912 * 2560) * 2 * 16 * 65536 * 7  # outputs x operands x limb words x byte planes
+    # outputs x operands x limb words x byte planes; the second layer runs after the rescale, at 15 limbs
+    ops = 2.0 * (2560 * 6912 * 2 * 16 + 6912 * 2560 * 2 * 15) * 65536 * 7
     assert roof["bound"] == "mfma" and roof["peak"] == 5000.0
     assert abs(roof["achieved"] - ops / 0.1 / 1e12) < 1e-6 and roof["launches"] == 9
+    assert roof["frac"] == roof["frac_dense"] and abs(roof["frac_own_work"] - 0.6 * roof["frac_dense"]) < 1e-12
+    # every operand read once, every output written once: (2560 + 6912) ciphertexts at 16 limbs, (6912 + 2560) at 15
+    assert abs(roof["algorithmic_bytes_per_launch"] * 9 - (9472 * 2 * 16 + 9472 * 2 * 15) * 8.0 * 65536) < 1.0
+    w = wl.BY_NAME["attn2560"]
+    _, roof = bench.roofline_for(w, {"accumulate_mfma": (50.0, 3)})
+    assert abs(roof["achieved"] - 2.0 * 2560 * 2560 * 2 * 16 * 65536 * 7 / 0.05 / 1e12) < 1e-6
+
+
+def test_profile_facts_come_from_the_tracked_summary_or_not_at_all(tmp_path, monkeypatch):
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    assert bench.profile_facts("ffn2560", "accumulate_mfma") == {}
+    (tmp_path / "profiles").mkdir()
+    (tmp_path / "profiles" / "bench_ffn2560_kernels_and_hbm_counters.txt").write_text(
+        "# text\n@facts accumulate_mfma fetch_GiB_per_step=10.5 write_GiB_per_step=2 mfma_busy=0.6\n@facts other fetch_GiB_per_step=1\n")
+    f = bench.profile_facts("ffn2560", "accumulate_mfma")
+    assert f == {"fetch_GiB_per_step": 10.5, "write_GiB_per_step": 2.0, "mfma_busy": 0.6}
+    _, roof = bench.roofline_for(wl.BY_NAME["ffn2560"], {"accumulate_mfma": (100.0, 5)})
+    assert abs(roof["traffic"] - 12.5 * 2 ** 30 / 5) < 1e-3 and roof["mfma_busy"] == 0.6 and roof["valu_util"] is None
 
 
 def test_plaintext_multiplication_counts():
