@@ -38,6 +38,10 @@
 //   * the fragments of step k+1 are read from LDS while the matrix instructions of
 //     step k run from registers;
 //   * one barrier.
+// The step loop holds no vector-ALU instruction besides the matrix instructions: the running source addresses of the
+// copies are wave-uniform and live in scalar registers (a lane adds 16 * lane through the instruction's offset
+// operand).  Vector instructions issued between matrix instructions slow the matrix pipe down measurably -- four 64-bit
+// address updates per step cost 5 % of the kernel, an in-loop unpacking of 2-bit weights (22 instructions) 10 %.
 // The grid is persistent: one workgroup per CU, 32 per XCD.  Items that share their
 // 32 words (different output tiles) are consecutive in one XCD's list and the
 // workers of that XCD take the list round-robin, so they read the same plane tiles
@@ -255,7 +259,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
     HIP_DYNAMIC_SHARED(char, smem)
     typedef AmLayout<PLANES> LY;
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wv = tid >> 6, g = lane >> 5, nl = lane & 31;
+    const int lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), g = lane >> 5, nl = lane & 31;
     const int nk = n_kpad / AM_TILE_K;
     const u32 smem0 = lds_addr(smem);
     // the wave copies plane tiles pb0 and pb1 of every step (the last plane twice where 2*wave+1 runs past it)
@@ -291,23 +295,25 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
 
     // The copies of all items of this workgroup form one stream of steps: the ring never drains between items.
     // pb/pa are the running per-lane source pointers of the stream.
+    // pb/pa are wave-uniform (scalar registers, advanced by the scalar unit); a lane adds its own 16 * lane bytes.
     const char *pb[2], *pa;
+    const u32 lane_off = (u32)lane * 16;
     auto seek = [&](int item) {
         int mt, nt;
         decode(item, mt, nt);
-        const char *pbase = xp + (size_t)nt * nk * PLANES * 1024 + lane * 16;
+        const char *pbase = xp + (size_t)nt * nk * PLANES * 1024;
         pb[0] = pbase + pb0 * 1024;
         pb[1] = pbase + pb1 * 1024;
-        pa = (const char *)(wfrag + ((size_t)mt * nk * 4 + wv) * 128 + lane);
+        pa = (const char *)(wfrag + ((size_t)mt * nk * 4 + wv) * 128);
     };
     // one of the wave's two plane tiles of the stream's next step -> ring slot
     auto issue_b = [&](int slot, int c) {
-        dma_load16(pb[c], (c ? b_lds1 : b_lds0) + (u32)slot * AM_BSLOT);
+        dma_load16_s(pb[c], lane_off, (c ? b_lds1 : b_lds0) + (u32)slot * AM_BSLOT);
         pb[c] += PLANES * 1024;
     };
     // one of the wave's two weight fragments of the stream's next step -> ring slot
     auto issue_a = [&](int slot, int c) {
-        dma_load16(pa + c * 1024, a_lds + (u32)slot * AM_ASLOT + c * 1024);
+        dma_load16_s(pa + c * 1024, lane_off, a_lds + (u32)slot * AM_ASLOT + c * 1024);
         if (c == 1) pa += 8192;
     };
 

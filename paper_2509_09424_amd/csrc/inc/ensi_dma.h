@@ -13,6 +13,11 @@ __device__ __forceinline__ void dma_load16(const void *lane_addr, uint32_t lds_w
     // lds_wave_base must be wave-uniform (derive it with readfirstlane where the compiler cannot tell)
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(lane_addr), "s"(lds_wave_base) : "memory");
 }
+// The same copy addressed as a wave-uniform base (held in scalar registers) plus a per-lane 32-bit byte offset: the running
+// pointers of a stream then advance on the scalar unit and no vector instruction is spent on addresses.
+__device__ __forceinline__ void dma_load16_s(const void *uniform_base, uint32_t lane_offset, uint32_t lds_wave_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_offset), "s"(uniform_base), "s"(lds_wave_base) : "memory");
+}
 // Same with 4 bytes per lane: 64 x 4 bytes land contiguously at lds_wave_base.
 __device__ __forceinline__ void dma_load4(const void *lane_addr, uint32_t lds_wave_base) {
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" : : "v"(lane_addr), "s"(lds_wave_base) : "memory");
