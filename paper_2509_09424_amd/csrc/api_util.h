@@ -88,3 +88,19 @@ int run_rotations(ensi_ctx *ctx, const RotDesc *d_desc, int n_rot, int l1, int l
 int ensi_static_init(ensi_ctx *ctx);
 // Allocates every slot of the staging ring and its event now, so that later small uploads allocate nothing.
 int stage_prealloc(ensi_ctx *ctx);
+
+// ---- helpers defined in one translation unit of the C ABI and used by others ---------------------------------
+// api.hip
+int encode_window(ensi_ctx *ctx, const double *slots, int n_pt, int n_slots, int slot0, int slot_step, int limbs, double scale,
+                  ensi_pt **out);
+int rot_chunk();                           // ciphertexts per group of a batched rotation
+int ensure_desc(ensi_ctx *ctx, size_t n);  // grows the context's descriptor table to n entries
+// api_matmul.hip
+void free_plan(MatmulPlan *p);
+// Constants of the scalar-multiply + rescale step at l1 limbs (integer set and fp64 set), uploaded to the context's
+// small-constants workspace; kr = the integer the limbs are multiplied by before the division (1: plain rescale).
+int upload_rescale_consts(ensi_ctx *ctx, int l1, double kr, bool negative, hipStream_t st, const u64 **d_consts, const double **d_fconsts,
+                          bool *fp_out);
+// api_pmult.hip: out_o = Rescale(sum of the terms [begin[o], begin[o+1]) of src (x) plaintext)
+int pmult_core(ensi_ctx *ctx, const std::vector<PmTerm> &terms_in, const std::vector<int32_t> &begin, int l1, int limb_stride_in,
+               const ensi_pt *pt, ensi_ct *out, hipStream_t st);
