@@ -517,7 +517,7 @@ int encode_window(ensi_ctx *ctx, const double *slots, int n_pt, int n_slots, int
     if (d_slots.alloc((size_t)n_pt * n_slots * 8) != hipSuccess || d_coeffs.alloc((size_t)n_pt * ctx->N * 8) != hipSuccess)
         ENSI_FAIL(ctx, ENSI_E_NOMEM, "device allocation failed in encode");
     ENSI_HIP(ctx, hipMemcpy(d_slots.p, slots, (size_t)n_pt * n_slots * 8, hipMemcpyHostToDevice));
-    launch_encode(ctx, d_slots.as<double>(), n_pt, n_slots, slot0, slot_step, scale, d_coeffs.as<int64_t>(), nullptr);
+    ENSI_HIP(ctx, launch_encode(ctx, d_slots.as<double>(), n_pt, n_slots, slot0, slot_step, scale, d_coeffs.as<int64_t>(), nullptr));
     return pt_from_coeffs(ctx, d_coeffs.as<int64_t>(), n_pt, limbs, scale, out);
 }
 extern "C" int ensi_encode(ensi_ctx *ctx, const double *slots, int32_t n_pt, int32_t n_slots, int32_t limbs, ensi_pt **out) {
@@ -726,8 +726,7 @@ extern "C" int ensi_decrypt(ensi_ctx *ctx, const ensi_sk *sk, const ensi_ct *ct,
         launch_add(ctx, mc, mc, ct->d + (size_t)c * 2 * poly_words, use, mq, st);
     }
     launch_crt_center(ctx, d_m.as<u64>(), n, use, d_coef.as<double>(), st);
-    launch_decode(ctx, d_coef.as<double>(), n, slot_begin, n_slots, 1.0 / ct->scale, d_out.as<double>(), st);
-    ENSI_HIP(ctx, hipStreamSynchronize(st));
+    ENSI_HIP(ctx, launch_decode(ctx, d_coef.as<double>(), n, slot_begin, n_slots, 1.0 / ct->scale, d_out.as<double>(), st));
     ENSI_HIP(ctx, hipMemcpy(slots_out, d_out.p, (size_t)n * n_slots * 8, hipMemcpyDeviceToHost));
     return ENSI_OK;
 }

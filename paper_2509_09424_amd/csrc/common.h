@@ -357,9 +357,10 @@ void launch_key_assemble(ensi_ctx *ctx, u64 *b_out, const u64 *a, const u64 *s_m
                          const u64 *d_factor, const LimbMap &map, hipStream_t st);
 void launch_automorphism_coef(ensi_ctx *ctx, u64 *out, const u64 *in, const LimbMap &map, u32 g_inv, hipStream_t st);
 // plaintext y of the batch holds its n_slots values in slots [slot0 + y*slot_step, ...+n_slots), zeros elsewhere
-void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale, int64_t *d_coeffs,
-                   hipStream_t st);
+// (allocates its transform workspace, waits for the stream and frees it again; so does launch_decode)
+hipError_t launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale,
+                         int64_t *d_coeffs, hipStream_t st);
 void launch_crt_center(ensi_ctx *ctx, const u64 *m, int n_ct, int n_limbs_used, double *out, hipStream_t st);
 void launch_center_i64(ensi_ctx *ctx, const u64 *m, size_t stride_words, int n, int64_t *out, hipStream_t st);
-void launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale,
-                   double *d_out, hipStream_t st);
+hipError_t launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale, double *d_out,
+                         hipStream_t st);

@@ -508,30 +508,96 @@ void launch_automorphism_coef(ensi_ctx *ctx, u64 *out, const u64 *in, const Limb
 }
 
 // ---------------------------------------------------------------- encode / decode
-// Column-wise SIMD encoding pi (paper, Preliminaries): the defining sum, in fp64.
-// coefficient k = round_half_away((2*scale/N) * sum_j z_j cos(pi * 5^j * k / N)).
-// Plaintext y holds its n_slots values in slots [slot0 + y*slot_step, ... + n_slots); all other slots are zero.
-__global__ __launch_bounds__(EW_THREADS) void k_encode(const double *slots, int n_slots, int slot0, int slot_step, const double *cos_tab,
-                                                       const u32 *rot_exp, int N, double factor, int64_t *coeffs) {
+// Column-wise SIMD encoding pi (paper, Preliminaries), in fp64:
+//   coefficient k = round_half_away((2*scale/N) * sum_j z_j cos(pi * 5^j * k / N))        (encode)
+//   slot j        = (1/scale) * sum_k m_k cos(pi * 5^j * k / N)                           (decode)
+// Both sums are the real part of one length-2N discrete Fourier transform of a real vector: encode transforms the
+// vector that holds z_j at index 5^j mod 2N and reads outputs 0..N-1, decode transforms (m_0..m_{N-1}, 0..0) and reads
+// outputs 5^j mod 2N.  The transform is a self-sorting radix-2 Stockham FFT, one pass per launch over the whole batch
+// (log2(2N) passes of 2N complex doubles each way: tens of microseconds per plaintext where the defining sums took
+// hundreds of milliseconds); twiddles come from the context's table of cos(pi e / N), which holds the 2N-th roots.
+// Rounding error: below 1e-13 * ||input||_2 per output, far under one half of a coefficient at every scale in use.
+constexpr int FFT_CHUNK = 128;  // plaintexts per batch of transforms: 2 x 128 x 2N x 16 B of workspace (512 MiB at N = 2^16)
+
+__global__ __launch_bounds__(EW_THREADS) void k_fft_pass(const double2 *x, double2 *y, int n2, int s, const double *cos_tab) {
+    const int t = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (t >= n2 / 2) return;
+    x += (size_t)blockIdx.y * n2;
+    y += (size_t)blockIdx.y * n2;
+    const int q = t & (s - 1), idx = t - q;  // idx = p * s with p = t / s: the twiddle is exp(-2 pi i idx / n2)
+    const double2 a = x[t], b = x[t + n2 / 2];
+    const double c = cos_tab[idx], sn = cos_tab[(idx - n2 / 4) & (n2 - 1)];
+    const double dr = a.x - b.x, di = a.y - b.y;
+    const size_t o = (size_t)q + 2 * (size_t)idx;
+    y[o] = make_double2(a.x + b.x, a.y + b.y);
+    y[o + s] = make_double2(dr * c + di * sn, di * c - dr * sn);
+}
+// Plaintext y of the chunk holds its n_slots values in slots [slot0 + (y0 + y)*slot_step, ... + n_slots); x is zero beforehand.
+__global__ __launch_bounds__(EW_THREADS) void k_fft_scatter_slots(const double *slots, int n_slots, int slot0, int slot_step, int y0,
+                                                                  const u32 *rot_exp, int n2, double2 *x) {
+    const int j = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (j >= n_slots) return;
+    const int y = y0 + blockIdx.y;
+    x[(size_t)blockIdx.y * n2 + rot_exp[slot0 + (size_t)y * slot_step + j]] = make_double2(slots[(size_t)y * n_slots + j], 0.0);
+}
+__global__ __launch_bounds__(EW_THREADS) void k_fft_round_coeffs(const double2 *f, int N, double factor, int64_t *coeffs) {
     const int k = blockIdx.x * EW_THREADS + threadIdx.x;
     if (k >= N) return;
-    const double *z = slots + (size_t)blockIdx.y * n_slots;
-    const u32 *re = rot_exp + slot0 + (size_t)blockIdx.y * slot_step;
-    const u32 mask = 2 * (u32)N - 1;
-    double acc = 0.0;
-    for (int j = 0; j < n_slots; j++) {
-        const u32 e = (u32)(((u64)re[j] * (u32)k) & mask);
-        acc += z[j] * cos_tab[e];
-    }
-    const double m = acc * factor;
+    const double m = f[(size_t)blockIdx.y * 2 * N + k].x * factor;
     const double r = floor(fabs(m) + 0.5);
     coeffs[(size_t)blockIdx.y * N + k] = (int64_t)(m < 0 ? -r : r);
 }
-void launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale, int64_t *d_coeffs,
-                   hipStream_t st) {
-    dim3 grid((ctx->N + EW_THREADS - 1) / EW_THREADS, n_pt);
-    hipLaunchKernelGGL(k_encode, grid, dim3(EW_THREADS), 0, st, d_slots, n_slots, slot0, slot_step, ctx->d_cos, ctx->d_rot_exp, ctx->N,
-                       2.0 * scale / ctx->N, d_coeffs);
+__global__ __launch_bounds__(EW_THREADS) void k_fft_load_coeffs(const double *coeffs, int N, double2 *x) {
+    const int k = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (k >= 2 * N) return;
+    x[(size_t)blockIdx.y * 2 * N + k] = make_double2(k < N ? coeffs[(size_t)blockIdx.y * N + k] : 0.0, 0.0);
+}
+__global__ __launch_bounds__(EW_THREADS) void k_fft_gather_slots(const double2 *f, int n2, const u32 *rot_exp, int slot_begin, int n_slots,
+                                                                 double inv_scale, double *out) {
+    const int j = blockIdx.x * EW_THREADS + threadIdx.x;
+    if (j >= n_slots) return;
+    out[(size_t)blockIdx.y * n_slots + j] = f[(size_t)blockIdx.y * n2 + rot_exp[slot_begin + j]].x * inv_scale;
+}
+// All passes over `count` transforms; returns the buffer that holds the result (a or b).
+static double2 *fft_passes(ensi_ctx *ctx, double2 *a, double2 *b, int count, hipStream_t st) {
+    const int n2 = 2 * ctx->N;
+    dim3 grid((n2 / 2 + EW_THREADS - 1) / EW_THREADS, count);
+    for (int s = 1; s < n2; s *= 2) {
+        hipLaunchKernelGGL(k_fft_pass, grid, dim3(EW_THREADS), 0, st, a, b, n2, s, ctx->d_cos);
+        std::swap(a, b);
+    }
+    return a;
+}
+static hipError_t fft_workspace(ensi_ctx *ctx, int n, double2 **a, double2 **b) {
+    const size_t bytes = (size_t)std::min(n, FFT_CHUNK) * 2 * ctx->N * sizeof(double2);
+    *a = *b = nullptr;
+    hipError_t e = hipMalloc((void **)a, bytes);
+    if (e == hipSuccess) e = hipMalloc((void **)b, bytes);
+    if (e != hipSuccess && *a) {
+        (void)hipFree(*a);
+        *a = nullptr;
+    }
+    return e;
+}
+hipError_t launch_encode(ensi_ctx *ctx, const double *d_slots, int n_pt, int n_slots, int slot0, int slot_step, double scale,
+                         int64_t *d_coeffs, hipStream_t st) {
+    const int N = ctx->N, n2 = 2 * N;
+    double2 *a, *b;
+    hipError_t e = fft_workspace(ctx, n_pt, &a, &b);
+    if (e != hipSuccess) return e;
+    for (int y0 = 0; y0 < n_pt && e == hipSuccess; y0 += FFT_CHUNK) {
+        const int cnt = std::min(FFT_CHUNK, n_pt - y0);
+        e = hipMemsetAsync(a, 0, (size_t)cnt * n2 * sizeof(double2), st);
+        hipLaunchKernelGGL(k_fft_scatter_slots, dim3((n_slots + EW_THREADS - 1) / EW_THREADS, cnt), dim3(EW_THREADS), 0, st, d_slots, n_slots,
+                           slot0, slot_step, y0, ctx->d_rot_exp, n2, a);
+        const double2 *f = fft_passes(ctx, a, b, cnt, st);
+        hipLaunchKernelGGL(k_fft_round_coeffs, dim3((N + EW_THREADS - 1) / EW_THREADS, cnt), dim3(EW_THREADS), 0, st, f, N, 2.0 * scale / N,
+                           d_coeffs + (size_t)y0 * N);
+    }
+    const hipError_t e2 = hipStreamSynchronize(st);
+    (void)hipFree(a);
+    (void)hipFree(b);
+    return e != hipSuccess ? e : e2;
 }
 
 // Garner CRT of limbs 0 and 1 (rows 0,1 of each [n_used][N] block), centred, as double.
@@ -594,25 +660,23 @@ void launch_center_i64(ensi_ctx *ctx, const u64 *m, size_t stride_words, int n, 
     hipLaunchKernelGGL(k_center_i64, grid, dim3(EW_THREADS), 0, st, m, stride_words, ctx->N, ctx->primes[0], out);
 }
 
-// z_j = (1/scale) sum_k m_k cos(pi 5^j k / N) for j in [slot_begin, slot_begin+n_slots)
-__global__ __launch_bounds__(EW_THREADS) void k_decode(const double *coeffs, int N, const double *cos_tab, const u32 *rot_exp,
-                                                       int slot_begin, int n_slots, double inv_scale, double *out) {
-    const int j = blockIdx.x * EW_THREADS + threadIdx.x;
-    if (j >= n_slots) return;
-    const double *m = coeffs + (size_t)blockIdx.y * N;
-    const u32 e = rot_exp[slot_begin + j];
-    const u32 mask = 2 * (u32)N - 1;
-    double acc = 0.0;
-    u32 ek = 0;
-    for (int k = 0; k < N; k++) {
-        acc += m[k] * cos_tab[ek];
-        ek = (ek + e) & mask;
+// z_j = (1/scale) sum_k m_k cos(pi 5^j k / N) for j in [slot_begin, slot_begin+n_slots): the same transform, read at 5^j.
+hipError_t launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale, double *d_out,
+                         hipStream_t st) {
+    const int N = ctx->N, n2 = 2 * N;
+    double2 *a, *b;
+    hipError_t e = fft_workspace(ctx, n_ct, &a, &b);
+    if (e != hipSuccess) return e;
+    for (int y0 = 0; y0 < n_ct; y0 += FFT_CHUNK) {
+        const int cnt = std::min(FFT_CHUNK, n_ct - y0);
+        hipLaunchKernelGGL(k_fft_load_coeffs, dim3((n2 + EW_THREADS - 1) / EW_THREADS, cnt), dim3(EW_THREADS), 0, st,
+                           d_coeffs + (size_t)y0 * N, N, a);
+        const double2 *f = fft_passes(ctx, a, b, cnt, st);
+        hipLaunchKernelGGL(k_fft_gather_slots, dim3((n_slots + EW_THREADS - 1) / EW_THREADS, cnt), dim3(EW_THREADS), 0, st, f, n2,
+                           ctx->d_rot_exp, slot_begin, n_slots, inv_scale, d_out + (size_t)y0 * n_slots);
     }
-    out[(size_t)blockIdx.y * n_slots + j] = acc * inv_scale;
-}
-void launch_decode(ensi_ctx *ctx, const double *d_coeffs, int n_ct, int slot_begin, int n_slots, double inv_scale,
-                   double *d_out, hipStream_t st) {
-    dim3 grid((n_slots + EW_THREADS - 1) / EW_THREADS, n_ct);
-    hipLaunchKernelGGL(k_decode, grid, dim3(EW_THREADS), 0, st, d_coeffs, ctx->N, ctx->d_cos, ctx->d_rot_exp, slot_begin,
-                       n_slots, inv_scale, d_out);
+    e = hipStreamSynchronize(st);
+    (void)hipFree(a);
+    (void)hipFree(b);
+    return e;
 }
