@@ -591,6 +591,8 @@ def hbm_fractions(w, prof_all):
             continue
         if dom == name and roof["bound"] == "hbm" and roof["achieved"] > 0:
             out[name] = {"GB/s": round(roof["achieved"], 1), "frac": round(roof["frac"], 4)}
+            # vector-ALU issue-slot utilisation and memory-side rate of the same kernel, from the tracked counter summary
+            out[name].update({k: v for k, v in profile_facts("keyswitch", name).items() if k in ("valu_util", "memory_side_TBps")})
     return out
 
 
@@ -745,6 +747,13 @@ def run_leg(name, steps, warmup, separate_rescale=False, with_ntt=False):
         err = r.check()
         prof = kernel_profile(r)
         dom, roof = roofline_for(w, prof)
+        if roof["bound"] == "mfma":
+            # the data-sheet peak assumes 2.4 GHz; under matrix load the chip holds a lower clock.  A register-only loop of
+            # the same matrix instruction, run right after the timed steps, gives the rate the pipes sustain on this
+            # machine: the second ceiling the contraction is compared with.
+            sustained = r.ctx.matrix_rate_probe(0.4) / 1e12
+            roof["sustained_peak_measured"] = round(sustained, 1)
+            roof["frac_of_sustained"] = round(roof["achieved"] / sustained, 4)
         log("%s: %.3f ms/step over %d steps, decrypted max abs error %.3e, dominant kernel %s" % (name, ms, steps, err, dom))
         leg = {"workload": name, "ms_per_step": ms, "steps": steps, "decrypt_max_abs_err": err, "roofline": roof,
                "kernels_ms_per_step": {k: {"ms": round(v[0], 4), "launches": v[1]} for k, v in sorted(prof.items())},

@@ -218,6 +218,15 @@ int ensi_ternary_matmul(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, int
  * plain-ALU kernel, 2 = same as 0.  Both give identical residues. */
 int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode);
 
+/* Diagnostics for the measurement of Alg. 1's contraction: runs a register-only
+ * loop of the int8 matrix instruction the contraction is built from (one
+ * workgroup of four waves per compute unit, no memory traffic) for about
+ * `seconds` (0 < seconds <= 2) and returns the operations per second the chip
+ * sustains at the clock it holds under that load -- the ceiling the contraction
+ * can be compared with besides the data-sheet peak.  ops_per_second: host
+ * pointer.  Returns after the probe has finished. */
+int ensi_matrix_rate_probe(ensi_ctx *ctx, double seconds, double *ops_per_second, void *stream);
+
 /* ---- scalar multiply + rescale (between two PCMM layers) ---------------- */
 /* In place on the whole batch: c <- c * round(kappa q_l) mod q_i, then limb l
  * is dropped: c_i <- (c_i - [c_l]) q_l^{-1} mod q_i with [c_l] the centred

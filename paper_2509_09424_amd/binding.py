@@ -26,7 +26,7 @@ EXPORTED = [
     "ensi_ct_drop_limbs", "ensi_mult_sum_relin_rescale", "ensi_fill_steps", "ensi_one_hot_masks", "ensi_replicate", "ensi_periodic_masks", "ensi_ccmm", "ensi_block_start_mask", "ensi_ccmm_blocks", "ensi_block_head_mask", "ensi_ccmm_bsgs", "ensi_segment_masks", "ensi_ccmm_segment", "ensi_ccmm_left_giant_steps", "ensi_diagonalise_weights", "ensi_ccmm_av", "ensi_ntt", "ensi_profile_enable", "ensi_profile_read",
     "ensi_sk_import", "ensi_sk_export", "ensi_pk_import", "ensi_pk_export", "ensi_gk_import", "ensi_gk_export", "ensi_gk_elements",
     "ensi_ct_checksum", "ensi_weights_prepare", "ensi_weights_free", "ensi_ternary_matmul_prepared", "ensi_rescale_ternary_matmul_prepared",
-    "ensi_rotate_static",
+    "ensi_rotate_static", "ensi_matrix_rate_probe",
 ]
 
 
@@ -285,6 +285,12 @@ class Context:
 
     def set_accumulate_mode(self, mode):
         self._check(self.lib.ensi_set_accumulate_mode(self.h, int(mode)))
+
+    def matrix_rate_probe(self, seconds=0.3, stream=0):
+        """Sustained int8 matrix-instruction rate of the chip (operations per second), measured for about `seconds`."""
+        rate = ctypes.c_double()
+        self._check(self.lib.ensi_matrix_rate_probe(self.h, ctypes.c_double(seconds), ctypes.byref(rate), ctypes.c_void_p(stream)))
+        return rate.value
 
     def mul_scalar_rescale(self, ct, kappa, stream=0):
         self._check(self.lib.ensi_mul_scalar_rescale(self.h, ct.h, ctypes.c_double(kappa), ctypes.c_void_p(stream)))

@@ -549,3 +549,71 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
 #undef AM_LAUNCH
     return ENSI_OK;
 }
+
+// ---------------------------------------------------------------- sustained rate of the matrix instruction
+// A register-only loop of V_MFMA_I32_32X32X32_I8, eight independent accumulator blocks per wave, one workgroup of four
+// waves per CU like the contraction: what the matrix pipes deliver at the clock the chip holds under that load.  No
+// memory is touched inside the loop; the operands come from `seed` words so that the compiler cannot fold the loop.
+__global__ __launch_bounds__(AM_THREADS) void k_matrix_rate(const int *seed, int iters, int *sink) {
+    v4i a, b;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        a[i] = seed[(threadIdx.x * 4 + i) & 1023];
+        b[i] = seed[(threadIdx.x * 4 + i + 512) & 1023];
+    }
+    v16i d[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) d[j][r] = 0;
+    for (int it = 0; it < iters; it++) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) d[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, d[j], 0, 0, 0);
+    }
+    int t = 0;
+#pragma unroll
+    for (int j = 0; j < 8; j++) t += d[j][j];
+    if (t == 0x7fffffff) sink[0] = t;  // keeps the loop alive; never true for these operands in practice, harmless if it is
+}
+
+int launch_matrix_rate(ensi_ctx *ctx, double seconds, double *ops_per_second, hipStream_t st) {
+    int &n_cu = ctx->n_cu;
+    if (!n_cu) {
+        hipDeviceProp_t prop;
+        n_cu = hipGetDeviceProperties(&prop, ctx->device) == hipSuccess ? prop.multiProcessorCount : 256;
+        if (n_cu < 8) n_cu = 8;
+    }
+    std::vector<int> h(1024);
+    u64 x = 0x9E3779B97F4A7C15ull;
+    for (int &v : h) {
+        x = x * 6364136223846793005ull + 1442695040888963407ull;
+        v = (int)(x >> 32);
+    }
+    int *d_seed = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipMalloc((void **)&d_seed, (h.size() + 1) * sizeof(int));
+    if (e == hipSuccess) e = hipMemcpy(d_seed, h.data(), h.size() * sizeof(int), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    float ms = 0;
+    // about 32 pipe cycles per instruction at roughly 1.6 GHz; the measured time is what counts
+    const int iters = (int)std::max(1000.0, seconds * 1.6e9 / (32.0 * 8.0));
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(k_matrix_rate, dim3(n_cu), dim3(AM_THREADS), 0, st, d_seed, 1000, d_seed + 1024);
+        (void)hipEventRecord(e0, st);
+        hipLaunchKernelGGL(k_matrix_rate, dim3(n_cu), dim3(AM_THREADS), 0, st, d_seed, iters, d_seed + 1024);
+        (void)hipEventRecord(e1, st);
+        e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (d_seed) (void)hipFree(d_seed);
+    if (e != hipSuccess || !(ms > 0)) {
+        ctx->err = "the matrix-rate probe failed";
+        return ENSI_E_HIP;
+    }
+    const double n_inst = (double)n_cu * 4 * (double)iters * 8;
+    *ops_per_second = n_inst * 2.0 * 32 * 32 * 32 / (ms * 1e-3);
+    return ENSI_OK;
+}

@@ -160,6 +160,11 @@ extern "C" int ensi_set_accumulate_mode(ensi_ctx *ctx, int32_t mode) {
     return ENSI_OK;
 }
 
+extern "C" int ensi_matrix_rate_probe(ensi_ctx *ctx, double seconds, double *ops_per_second, void *stream) {
+    if (!ctx || !ops_per_second || !(seconds > 0) || seconds > 2.0) return ENSI_E_BADARG;
+    return launch_matrix_rate(ctx, seconds, ops_per_second, (hipStream_t)stream);
+}
+
 // Shape and level checks shared by the entry points of Alg. 1.
 static int matmul_check(ensi_ctx *ctx, const ensi_ct *in, int32_t s, int32_t d, int32_t m, int32_t placement, const ensi_ct *out, int *c_tot_out,
                         int *n_in_out) {

@@ -324,6 +324,8 @@ void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, c
 int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
                            int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
                            hipStream_t st);
+// sustained int8 matrix-instruction rate over the whole chip, measured for about `seconds`
+int launch_matrix_rate(ensi_ctx *ctx, double seconds, double *ops_per_second, hipStream_t st);
 
 // plaintext multiplication (pmult.hip).  The generic pair works for every ring size and prime; the fused one needs
 // N = 2^16 and ciphertext primes below 2^50.

@@ -83,4 +83,5 @@ def test_null_arguments_of_key_exchange_and_prepared_weights_without_gpu():
     assert lib.ensi_weights_prepare(n, n, 1, 1, 1, 0, 1, n) == -1
     assert lib.ensi_ternary_matmul_prepared(n, n, n, n, n, n) == -1
     assert lib.ensi_rescale_ternary_matmul_prepared(n, n, d(0.5), n, n, n) == -1
+    assert lib.ensi_matrix_rate_probe(n, d(0.1), n, n) == -1
     lib.ensi_weights_free(n)  # a null handle is ignored

@@ -198,3 +198,15 @@ def test_prepared_weights_give_the_same_product():
             h.free()
     finally:
         p.close()
+
+
+def test_matrix_rate_probe_reports_a_rate_below_the_data_sheet_peak():
+    from paper_2509_09424_amd import binding
+    ctx = binding.Context(*TINY, seed=1)
+    try:
+        rate = ctx.matrix_rate_probe(0.05)
+        assert 0.5e15 < rate < 5.2e15  # int8 dense peak of the chip is 5.0e15 operations per second
+        with pytest.raises(binding.EnsiError):
+            ctx.matrix_rate_probe(5.0)
+    finally:
+        ctx.close()
