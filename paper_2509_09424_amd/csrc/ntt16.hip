@@ -67,45 +67,81 @@ __device__ __forceinline__ void cols_body(u64 *g, const u64 *gin, const u64 *tw,
 // padded by one word per 16 so that both the strided and the contiguous 16-element patterns are
 // conflict-free; global traffic is fully coalesced (the contiguous-per-thread layout only ever
 // touches LDS).
+// A block runs its tile for up to N16_ROWS_GROUP limbs of the same prime (n_here of them, inst_stride words apart):
+// the tile's twiddles -- 15 pairs per row for one step, 15 pairs per thread for the other, more bytes than the tile
+// itself -- are fetched once (LDS and registers), and the next limb's tile is requested before the current one is
+// transformed.
+#define N16_ROWS_GROUP 8
 
 template <bool FWD, class A>
-__device__ __forceinline__ void rows_body(u64 *g, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds, int r0) {
+__device__ __forceinline__ void rows_body(u64 *g, size_t inst_stride, int n_here, const u64 *tw, const u64 *tws, const PrimeConst &pc, u64 *lds,
+                                          ulonglong2 *tw1, int r0) {
     A ar;
     ar.init(pc);
     const int tid = threadIdx.x, rho = tid >> 4, j = tid & 15;
     const u32 r = (u32)(r0 + rho);
     typename A::T v[16];
     typename A::T *l = (typename A::T *)lds;
+    row_table_to_lds(tw1, tw, tws, 256u + r, rho, j);
+    TwRegs tw2;
+    tw2.load(tw, tws, (256u + r) * 16u + j);
+    const ulonglong2 *tab = tw1 + rho * 16;
+    u64 nv[16];
     if (FWD) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) v[i] = ar.load(g[rho * 256 + j + 16 * i]);
-        ct4(ar, v, tw, tws, 256u + r);
+        for (int i = 0; i < 16; i++) nv[i] = g[rho * 256 + j + 16 * i];
+        __syncthreads();  // tw1 is complete
+#pragma unroll 1
+        for (int c = 0; c < n_here; c++) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) l[rpad(rho * 256 + j + 16 * i)] = ar.mid(v[i]);
-        __syncthreads();
+            for (int i = 0; i < 16; i++) v[i] = ar.load(nv[i]);
+            if (c + 1 < n_here) {
+                const u64 *gn = g + (size_t)(c + 1) * inst_stride;
 #pragma unroll
-        for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + 16 * j + i)];
-        ct4(ar, v, tw, tws, (256u + r) * 16u + j);
+                for (int i = 0; i < 16; i++) nv[i] = gn[rho * 256 + j + 16 * i];
+            }
+            ct4_tab(ar, v, tab);
 #pragma unroll
-        for (int i = 0; i < 16; i++) lds[rpad(rho * 256 + 16 * j + i)] = ar.store_fwd(v[i]);
-        __syncthreads();
+            for (int i = 0; i < 16; i++) l[rpad(rho * 256 + j + 16 * i)] = ar.mid(v[i]);
+            __syncthreads();
 #pragma unroll
-        for (int i = 0; i < 16; i++) g[tid + 256 * i] = lds[rpad(tid + 256 * i)];
+            for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + 16 * j + i)];
+            ct4_tab(ar, v, tw2);
+#pragma unroll
+            for (int i = 0; i < 16; i++) lds[rpad(rho * 256 + 16 * j + i)] = ar.store_fwd(v[i]);
+            __syncthreads();
+            u64 *go = g + (size_t)c * inst_stride;
+#pragma unroll
+            for (int i = 0; i < 16; i++) go[tid + 256 * i] = lds[rpad(tid + 256 * i)];
+            __syncthreads();  // the tile is reused by the next limb's exchange
+        }
     } else {
 #pragma unroll
-        for (int i = 0; i < 16; i++) lds[rpad(tid + 256 * i)] = g[tid + 256 * i];
-        __syncthreads();
+        for (int i = 0; i < 16; i++) nv[i] = g[tid + 256 * i];
+#pragma unroll 1
+        for (int c = 0; c < n_here; c++) {
 #pragma unroll
-        for (int i = 0; i < 16; i++) v[i] = ar.center(ar.load(lds[rpad(rho * 256 + 16 * j + i)]));
-        gs4(ar, v, tw, tws, (256u + r) * 16u + j);
+            for (int i = 0; i < 16; i++) lds[rpad(tid + 256 * i)] = nv[i];
+            __syncthreads();  // (also covers tw1 on the first round)
+            if (c + 1 < n_here) {
+                const u64 *gn = g + (size_t)(c + 1) * inst_stride;
 #pragma unroll
-        for (int i = 0; i < 16; i++) l[rpad(rho * 256 + 16 * j + i)] = ar.mid(v[i]);
-        __syncthreads();
+                for (int i = 0; i < 16; i++) nv[i] = gn[tid + 256 * i];
+            }
 #pragma unroll
-        for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + j + 16 * i)];
-        gs4(ar, v, tw, tws, 256u + r);
+            for (int i = 0; i < 16; i++) v[i] = ar.center(ar.load(lds[rpad(rho * 256 + 16 * j + i)]));
+            gs4_tab(ar, v, tw2);
 #pragma unroll
-        for (int i = 0; i < 16; i++) g[rho * 256 + j + 16 * i] = ar.store_inv(v[i]);
+            for (int i = 0; i < 16; i++) l[rpad(rho * 256 + 16 * j + i)] = ar.mid(v[i]);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + j + 16 * i)];
+            gs4_tab(ar, v, tab);
+            u64 *go = g + (size_t)c * inst_stride;
+#pragma unroll
+            for (int i = 0; i < 16; i++) go[rho * 256 + j + 16 * i] = ar.store_inv(v[i]);
+            __syncthreads();  // the tile is reused by the next limb's staging
+        }
     }
 }
 
@@ -140,18 +176,30 @@ __global__ __launch_bounds__(N16_THREADS) void k_ntt16_cols_gather(u64 *data, co
     else cols_body<true, ArithInt>(g, gin, tw, tw + N, pc, lds);
 }
 
+// grid (16, map.n * n_groups): instance inst = slot + map.n * (N16_ROWS_GROUP * group + c), c < N16_ROWS_GROUP, lies under
+// prime map.prime[slot]; n_inst instances in all.
 template <bool FWD>
-__global__ __launch_bounds__(N16_THREADS) void k_ntt16_rows(u64 *data, const u64 *tw_all, const PrimeConst *pcs, LimbMap map) {
+__global__ __launch_bounds__(N16_THREADS, 2) void k_ntt16_rows(u64 *data, const u64 *tw_all, const PrimeConst *pcs, LimbMap map, int n_inst) {
     __shared__ u64 lds[4096 + 256];
-    const int inst = blockIdx.y;
-    const int prime = map.prime[inst % map.n];
+    __shared__ ulonglong2 tw1[16 * 16];
+    const int slot = blockIdx.y % map.n, group = blockIdx.y / map.n;
+    const int inst0 = slot + map.n * N16_ROWS_GROUP * group;
+    if (inst0 >= n_inst) return;
+    const int n_here = min(N16_ROWS_GROUP, (n_inst - inst0 + map.n - 1) / map.n);
+    const int prime = map.prime[slot];
     const PrimeConst pc = pcs[prime];
     const size_t N = (size_t)1 << N16_LOG;
     const u64 *tw = tw_all + (size_t)prime * 4 * N + (FWD ? 0 : 2 * N);
     const int r0 = blockIdx.x * 16;
-    u64 *g = data + (size_t)inst * N + (size_t)r0 * 256;
-    if (pc.pad[0]) rows_body<FWD, ArithFp>(g, tw, tw + N, pc, lds, r0);
-    else rows_body<FWD, ArithInt>(g, tw, tw + N, pc, lds, r0);
+    u64 *g = data + (size_t)inst0 * N + (size_t)r0 * 256;
+    if (pc.pad[0]) rows_body<FWD, ArithFp>(g, (size_t)map.n * N, n_here, tw, tw + N, pc, lds, tw1, r0);
+    else rows_body<FWD, ArithInt>(g, (size_t)map.n * N, n_here, tw, tw + N, pc, lds, tw1, r0);
+}
+
+// Grid of the row pass over n_inst instances whose primes repeat with period `period`.
+static dim3 rows_grid(int n_inst, int period) {
+    const int reps = (n_inst + period - 1) / period;  // instances per prime slot (the last ones may be missing)
+    return dim3(16, period * ((reps + N16_ROWS_GROUP - 1) / N16_ROWS_GROUP));
 }
 
 // Forward transform of n_ops operand ciphertexts (two polynomials of l1 limbs each, limb i under prime i) from where they
@@ -171,7 +219,7 @@ void launch_ntt16_gather(ensi_ctx *ctx, u64 *data, const MmOperand *ops, int n_o
         }
         {
             ScopedTimer t(ctx, "ntt_fwd_rows", st);
-            hipLaunchKernelGGL(k_ntt16_rows<true>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+            hipLaunchKernelGGL(k_ntt16_rows<true>, rows_grid(cnt * 2 * l1, map.n), dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map, cnt * 2 * l1);
         }
     }
 }
@@ -189,12 +237,12 @@ void launch_ntt16(ensi_ctx *ctx, u64 *data, int n_inst, const LimbMap &map, bool
             }
             {
                 ScopedTimer t(ctx, "ntt_fwd_rows", st);
-                hipLaunchKernelGGL(k_ntt16_rows<true>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+                hipLaunchKernelGGL(k_ntt16_rows<true>, rows_grid(cnt, map.n), dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map, cnt);
             }
         } else {
             {
                 ScopedTimer t(ctx, "ntt_inv_rows", st);
-                hipLaunchKernelGGL(k_ntt16_rows<false>, grid, dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map);
+                hipLaunchKernelGGL(k_ntt16_rows<false>, rows_grid(cnt, map.n), dim3(N16_THREADS), 0, st, d, ctx->d_tw, ctx->d_pc, map, cnt);
             }
             {
                 ScopedTimer t(ctx, "ntt_inv_cols", st);

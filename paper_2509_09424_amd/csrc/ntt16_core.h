@@ -110,6 +110,38 @@ __device__ __forceinline__ void ct4(const A &ar, typename A::T *v, const u64 *tw
         }
     }
 }
+// ct4 with the step's 15 twiddles (value, companion) already at hand: entry (1 << k) - 1 + g serves local stage k,
+// butterfly group g.  TAB is anything indexable that yields .x (value) and .y (companion) as 64-bit words -- a table
+// in LDS shared by the threads of a row, or a per-thread array in registers -- so that a kernel that runs the same
+// step on several limbs in a row fetches the twiddles once.
+template <class A, class TAB>
+__device__ __forceinline__ void ct4_tab(const A &ar, typename A::T *v, const TAB &tab) {
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const int d = 8 >> k;
+#pragma unroll
+        for (int g = 0; g < (1 << k); g++) {
+            const u64 w = tab[(1 << k) - 1 + g].x, ws = tab[(1 << k) - 1 + g].y;
+#pragma unroll
+            for (int o = 0; o < d; o++) {
+                const int i0 = g * 2 * d + o;
+                ar.ct(v[i0], v[i0 + d], w, ws);
+            }
+        }
+    }
+}
+// The 15 twiddles of a step with base index mbase, in ct4_tab's order.
+struct TwRegs {
+    ulonglong2 t[15];
+    __device__ __forceinline__ const ulonglong2 &operator[](int i) const { return t[i]; }
+    __device__ __forceinline__ void load(const u64 *tw, const u64 *tws, u32 mbase) {
+#pragma unroll
+        for (int k = 0; k < 4; k++)
+#pragma unroll
+            for (int g = 0; g < (1 << k); g++) t[(1 << k) - 1 + g] = make_ulonglong2(tw[(mbase << k) + g], tws[(mbase << k) + g]);
+    }
+};
+
 // The inverse of ct4 up to the factor 16 (inverse table).
 template <class A>
 __device__ __forceinline__ void gs4(const A &ar, typename A::T *v, const u64 *tw, const u64 *tws, u32 mbase) {
@@ -127,7 +159,32 @@ __device__ __forceinline__ void gs4(const A &ar, typename A::T *v, const u64 *tw
         }
     }
 }
-
+// gs4 with the step's twiddles at hand (see ct4_tab).
+template <class A, class TAB>
+__device__ __forceinline__ void gs4_tab(const A &ar, typename A::T *v, const TAB &tab) {
+#pragma unroll
+    for (int k = 3; k >= 0; k--) {
+        const int d = 8 >> k;
+#pragma unroll
+        for (int g = 0; g < (1 << k); g++) {
+            const u64 w = tab[(1 << k) - 1 + g].x, ws = tab[(1 << k) - 1 + g].y;
+#pragma unroll
+            for (int o = 0; o < d; o++) {
+                const int i0 = g * 2 * d + o;
+                ar.gs(v[i0], v[i0 + d], w, ws);
+            }
+        }
+    }
+}
+// Thread (rho = tid / 16, j) of a 256-thread block puts entry j < 15 of row rho's step table (base index mbase_row,
+// which depends on the row only) into tab[rho * 16 + j]; the caller synchronises before the first use.
+__device__ __forceinline__ void row_table_to_lds(ulonglong2 *tab, const u64 *tw, const u64 *tws, u32 mbase_row, int rho, int j) {
+    if (j < 15) {
+        const int k = 31 - __clz(j + 1), g = j + 1 - (1 << k);
+        const u32 idx = (mbase_row << k) + g;
+        tab[rho * 16 + j] = make_ulonglong2(tw[idx], tws[idx]);
+    }
+}
 
 // ---- pass bodies on registers ------------------------------------------------------
 // Column pass, thread (c = tid % 16, jj = tid / 16) of a 256-thread block working on 16
