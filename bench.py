@@ -835,8 +835,10 @@ def main():
         del a, b
     if w.name != "keyswitch" and not args.no_keyswitch_leg:
         # BASELINE configs[1]: the rotations/s half of the metric, with the stand-alone transform beside it
-        k = run_leg("keyswitch", max(args.steps, 5), args.warmup, with_ntt=True)
+        # (a batch takes under 4 ms: 20 timed batches, so that the first launch's latency does not show in the mean)
+        k = run_leg("keyswitch", max(args.steps, 20), max(args.warmup, 2), with_ntt=True)
         line["rotations"] = {"value": k["value"], "unit": "rotations/s", "workload": "keyswitch", "ms_per_batch": k["ms_per_batch"],
+                             "steps": k["steps"],
                              "stagewise": k["stagewise"], "decrypt_max_abs_err": k["decrypt_max_abs_err"], "roofline": k["roofline"],
                              "hbm_kernels": k["hbm_kernels"], "kernels_ms_per_step": k["kernels_ms_per_step"]}
         line["ntt"] = k["ntt"]

@@ -329,6 +329,36 @@ def test_full_ring_ntt_roundtrip_and_evaluation_set(full):
     ct.free()
 
 
+def test_full_ring_ntt_batch_with_ragged_groups(full):
+    """A batch whose limbs cycle through three primes (two below 2^50, one above) and whose count leaves the last
+    group of every prime incomplete: the row pass runs a tile for up to eight limbs of one prime per block."""
+    import torch
+    rng = np.random.default_rng(12)
+    L = full.pr.L
+    primes = full.pr.q + full.pr.p
+    pattern = [1, L + 1, L - 1]
+    n = 29  # 10, 10 and 9 limbs per prime: groups of 8 + 2, 8 + 2, 8 + 1
+    idx = [pattern[r % 3] for r in range(n)]
+    x = np.stack([rng.integers(0, primes[i], size=full.N, dtype=np.uint64) for i in idx])
+    buf = torch.from_numpy(x.view(np.int64)).cuda()
+    full.ctx.ntt(buf.data_ptr(), idx, inverse=False)
+    torch.cuda.synchronize()
+    fwd = buf.cpu().numpy().view(np.uint64)
+    for r in (0, 1, 2, 23, 24, 26, 27, 28):  # first limbs, and the limbs of the incomplete groups
+        want = full.o.ntt(x[r:r + 1], [primes[idx[r]]])[0]
+        assert np.array_equal(np.sort(fwd[r]), np.sort(want)), r
+    # limbs of one prime are transformed alike: same input -> same output, whatever its place in a group
+    y = x.copy()
+    y[27] = x[0]
+    buf2 = torch.from_numpy(y.view(np.int64)).cuda()
+    full.ctx.ntt(buf2.data_ptr(), idx, inverse=False)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf2[27].cpu().numpy(), buf[0].cpu().numpy())
+    full.ctx.ntt(buf.data_ptr(), idx, inverse=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.cpu().numpy().view(np.uint64), x)
+
+
 def test_full_ring_rotate_bit_exact(full):
     p = full
     steps = [1, -1, 4096]
