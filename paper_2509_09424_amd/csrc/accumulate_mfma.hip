@@ -88,28 +88,28 @@ __device__ __forceinline__ u64 reduce_signed(int64_t t, u64 q, double q_inv) {
 
 // The same recombination for primes below 2^50, in double precision on exact integers (no 64-bit integer
 // multiplies, which take many quarter-rate instructions on this chip).  S_p: the plane sums from the matrix
-// pipe, b = 128 * (column sum of the weights), so that the true plane sums are T_p = S_p + b and the result is
-// sum_p T_p 2^(8p) mod q.  Planes are first paired in 32-bit integers (|T_p| < 2^22 for up to 32768 operands, so
-// T_p + 2^8 T_(p+1) < 2^31), the pairs combined into lo + 2^32 hi with |lo| < 2^47 and |hi| < 2^38 -- every product
-// by a power of two and every sum below 2^53 is exact in a double --, 2^32 hi reduced on its own (its quotient by q
-// is below 2^21, and x - k q is an integer below 2^52 that the fused multiply-add returns exactly), and lo added
-// before the final reduction to (-q/2, q/2] and the shift into [0, q).
+// pipe; the true plane sums are T_p = S_p + b with b = 128 * (column sum of the weights), and the result is
+// sum_p T_p 2^(8p) mod q = (sum_p S_p 2^(8p) + B) mod q with B = b * sum_p 2^(8p) mod q, which the host supplies
+// per output and limb as a double in [0, q).  |S_p| <= 2^22 for up to 32768 operands, so planes are first paired
+// in 32-bit integers (S_p + 2^8 S_(p+1) < 2^31) and the pairs combined into lo + 2^32 hi with |lo| < 2^48 and
+// |hi| < 2^38.1 -- every product by a power of two and every sum below 2^53 is exact in a double.  One reduction:
+// k = rint((lo + B + 2^32 hi) / q) from two rounded products (off by far less than one half except within 2^-30 of
+// a tie), then 2^32 hi - k q, an integer below 2^52 in magnitude that the fused multiply-add returns exactly, plus
+// lo + B: a representative within (1/2 + 2^-30) q of zero, shifted into [0, q).
 template <int PLANES>
-__device__ __forceinline__ u64 recombine_fp(const int (&S)[PLANES], int b, double q, double q_inv) {
-    const int b257 = b * 257;
-    const int c01 = S[0] + S[1] * 256 + b257, c23 = S[2] + S[3] * 256 + b257;
-    const double lo = fma((double)c23, 65536.0, (double)c01);
+__device__ __forceinline__ u64 recombine_fp(const int (&S)[PLANES], double B, double q, double q_inv) {
+    const int c01 = S[0] + (S[1] << 8), c23 = S[2] + (S[3] << 8);
+    const double lb = fma((double)c23, 65536.0, (double)c01) + B;
     double hi;
     if (PLANES == 7) {
-        const int c45 = S[4] + S[5] * 256 + b257, c6 = S[6] + b;
-        hi = fma((double)c6, 65536.0, (double)c45);
+        const int c45 = S[4] + (S[5] << 8);
+        hi = fma((double)S[6], 65536.0, (double)c45);
     } else {
-        hi = (double)(S[4] + b);
+        hi = (double)S[4];
     }
     const double x = hi * 4294967296.0;
-    const double r = fma(-rint(x * q_inv), q, x);
-    const double s = lo + r;
-    double u = fma(-rint(s * q_inv), q, s);
+    const double k = rint(fma(lb, q_inv, x * q_inv));
+    double u = fma(-k, q, x) + lb;
     u = u < 0.0 ? u + q : u;
     // an integer in [0, 2^52) plus 2^52 has that integer as its mantissa
     return (u64)__double_as_longlong(u + 4503599627370496.0) & 0xFFFFFFFFFFFFFull;
@@ -244,16 +244,17 @@ template <int PLANES>
 struct AmLayout {
     static constexpr int bring_off = 0;                                  // [AM_RING][AM_BSLOT]
     static constexpr int aring_off = bring_off + AM_RING * AM_BSLOT;     // [4 waves][AM_RING][AM_ASLOT]
-    static constexpr int bias_off = aring_off + 4 * AM_RING * AM_ASLOT;  // [2][256] offset terms of an item's outputs
-    static constexpr int total = bias_off + 2 * AM_TILE_M * 4;
+    static constexpr int bias_off = aring_off + 4 * AM_RING * AM_ASLOT;  // [2][256] offset terms of an item's outputs (int32 or double)
+    static constexpr int total = bias_off + 2 * AM_TILE_M * 8;
 };
 
 // xp: plane tiles of the slice, [word tile][nk][PLANES][1024]; the slice covers coefficient tiles c0 .. c0+cw-1
 // of all 2*l1 limb rows (n_tiles_n = 2*l1*cw word tiles); nk = n_kpad / 32, a multiple of AM_RING.
-// FP_EPI: every active prime is below 2^50, so the planes are recombined in double precision (recombine_fp); else
-// in 64-bit integers.
+// FP_EPI: every active prime is below 2^50, so the planes are recombined in double precision (recombine_fp) and bias
+// points to doubles [l1][n_tiles_m * 256], the offset term of every output reduced modulo each limb's prime; else the
+// planes are recombined in 64-bit integers and bias points to int32 [n_tiles_m * 256], 128 * column sum of the weights.
 template <int PLANES, bool FP_EPI>
-__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int c0, int cw, int n_kpad, const v4i *wfrag, const int32_t *bias,
+__global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, int c0, int cw, int n_kpad, const v4i *wfrag, const void *bias,
                                                                 int m, AmPrimes pr, int N, int l1, u64 *out, int limb_stride_out,
                                                                 int n_tiles_n, int n_tiles_m, int workers_per_xcd, int m_group) {
     HIP_DYNAMIC_SHARED(char, smem)
@@ -318,11 +319,20 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
     };
 
     // offset terms of an item's 256 outputs -> one of two LDS buffers (64 per wave); issued one item ahead
-    const u32 bias_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::bias_off + wv * 256));
+    constexpr int BIAS_BYTES = FP_EPI ? 8 : 4;
+    const u32 bias_lds = (u32)__builtin_amdgcn_readfirstlane((int)(smem0 + LY::bias_off + wv * 64 * BIAS_BYTES));
     auto issue_bias = [&](int item, int buf) {
         int mt, nt;
         decode(item, mt, nt);
-        dma_load4(bias + mt * AM_TILE_M + wv * 64 + lane, bias_lds + (u32)buf * (AM_TILE_M * 4));
+        if (FP_EPI) {
+            // the wave's 64 doubles of the item's limb, as two copies of 4 bytes per lane (256 contiguous bytes each)
+            const int pl = nt / cw, limb = pl - (pl / l1) * l1;
+            const char *src = (const char *)((const double *)bias + (size_t)limb * n_tiles_m * AM_TILE_M + mt * AM_TILE_M + wv * 64) + lane * 4;
+            dma_load4(src, bias_lds + (u32)buf * (AM_TILE_M * 8));
+            dma_load4(src + 256, bias_lds + (u32)buf * (AM_TILE_M * 8) + 256);
+        } else {
+            dma_load4((const int32_t *)bias + mt * AM_TILE_M + wv * 64 + lane, bias_lds + (u32)buf * (AM_TILE_M * 4));
+        }
     };
 
     int item = next_valid(worker);
@@ -361,7 +371,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
         const int i0 = m_tile * AM_TILE_M + wv * 64;
         // offset terms of this item's outputs: copied one item ahead into two buffers used alternately (the
         // other one may still be read by a wave that has not finished the previous item's recombination)
-        const int *bl = (const int *)(smem + LY::bias_off) + (it & 1) * AM_TILE_M;
+        const char *bl = smem + LY::bias_off + (it & 1) * AM_TILE_M * BIAS_BYTES;
 
         v16i acc[PLANES][2];
 #pragma unroll
@@ -431,16 +441,20 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
 #pragma unroll
             for (int c = 0; c < 4; c++) {
                 const int ib = i0 + mb * 32 + 8 * c + 4 * g;  // rows ib .. ib+3
-                const v4i b4 = *(const v4i *)(bl + (ib - m_tile * AM_TILE_M));
                 u64 res[4];
+                if (FP_EPI) {
+                    const double *b4 = (const double *)bl + (ib - m_tile * AM_TILE_M);
 #pragma unroll
-                for (int e = 0; e < 4; e++) {
-                    if (FP_EPI) {
+                    for (int e = 0; e < 4; e++) {
                         int S[PLANES];
 #pragma unroll
                         for (int p = 0; p < PLANES; p++) S[p] = acc[p][mb][4 * c + e];
                         res[e] = recombine_fp<PLANES>(S, b4[e], qd, q_inv);
-                    } else {
+                    }
+                } else {
+                    const v4i b4 = *(const v4i *)((const int *)bl + (ib - m_tile * AM_TILE_M));
+#pragma unroll
+                    for (int e = 0; e < 4; e++) {
                         int64_t t = (int64_t)((u64)(int64_t)b4[e] * ones);
 #pragma unroll
                         for (int p = 0; p < PLANES; p++) t += (int64_t)((u64)(int64_t)acc[p][mb][4 * c + e] << (8 * p));
@@ -465,7 +479,7 @@ __global__ __launch_bounds__(AM_THREADS) void k_accumulate_mfma(const char *xp, 
 
 template <int P, bool FP_EPI>
 static void am_launch(ensi_ctx *ctx, unsigned grid, hipStream_t st, const u64 *xbase, u32 xstride, int n_v, int n_kpad, const v4i *wfrag,
-                      const int32_t *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_m, int workers,
+                      const void *bias, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, int n_tiles_m, int workers,
                       int m_group, char *xp, int slice_ctiles, const double *d_rescale) {
     bool &attr_set = ctx->am_attr_set[(P == 5 ? 0 : 1) + (FP_EPI ? 0 : 2)];
     if (!attr_set) {
@@ -507,7 +521,7 @@ static int am_slice_ctiles(int ctiles, int l1, int n_kpad, int planes) {
 // d_rescale != nullptr: the operands are read at l1 + 1 limbs and the scalar-multiply + rescale step is applied while
 // their planes are built (constants as for k_rescale_fp at l1 + 1 limbs); out is at l1 limbs.
 int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
-                           int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
+                           const double *d_bias_fp, int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
                            hipStream_t st) {
     const int ctiles = ctx->N / AM_TILE_N;
     const int n_tiles_m = (m + AM_TILE_M - 1) / AM_TILE_M;
@@ -534,10 +548,10 @@ int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int 
         }
         ctx->ws_xp_words = xp_words;
     }
-    bool fp_epi = true;  // the double-precision recombination is exact while every active prime is below 2^50
+    bool fp_epi = d_bias_fp != nullptr;  // the double-precision recombination is exact while every active prime is below 2^50
     for (int i = 0; i < l1; i++) fp_epi = fp_epi && ctx->primes[i] < ((u64)1 << 50);
 #define AM_LAUNCH(PL, FP)                                                                                                              \
-    am_launch<PL, FP>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, \
+    am_launch<PL, FP>(ctx, grid, st, xbase, (u32)xstride, n_v, n_kpad, wf, (FP) ? (const void *)d_bias_fp : (const void *)d_bias, m, l1, limb_stride_in, out, limb_stride_out, n_tiles_m, \
                       workers, m_group, (char *)ctx->ws_xp, slice_ctiles, d_rescale)
     if (P == 5) {
         if (fp_epi) AM_LAUNCH(5, true);

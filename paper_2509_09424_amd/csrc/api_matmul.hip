@@ -29,6 +29,7 @@ void free_plan(MatmulPlan *p) {
     if (p->d_masks) (void)hipFree(p->d_masks);
     if (p->d_wt) (void)hipFree(p->d_wt);
     if (p->d_bias) (void)hipFree(p->d_bias);
+    if (p->d_bias_fp) (void)hipFree(p->d_bias_fp);
     delete p;
 }
 
@@ -112,12 +113,27 @@ static int build_plan(ensi_ctx *ctx, const int8_t *W, int s, int d, int m, int p
     }
     if (mfma_ok)
         for (int i = 0; i < m; i++) bias[i] *= 128;  // every byte is fed to the matrix pipe as u - 128
-    hipError_t e1 = upload(&p->d_masks, masks), e2 = hipSuccess, e3 = hipSuccess;
+    hipError_t e1 = upload(&p->d_masks, masks), e2 = hipSuccess, e3 = hipSuccess, e4 = hipSuccess;
     if (mfma_ok) {
         e2 = upload(&p->d_wt, wt);
         e3 = upload(&p->d_bias, bias);
+        if (qbits <= 50) {
+            // the recombination in double precision adds the offset term already reduced: b * sum_p 256^p mod q_limb
+            std::vector<double> bias_fp((size_t)l1 * p->m_pad, 0.0);
+            __int128 ones = 0;
+            for (int pl = 0; pl < p->planes; pl++) ones |= (__int128)1 << (8 * pl);
+            for (int limb = 0; limb < l1; limb++) {
+                const __int128 q = (__int128)ctx->primes[limb];
+                for (int i = 0; i < m; i++) {
+                    __int128 r = ((__int128)bias[i] * ones) % q;
+                    if (r < 0) r += q;
+                    bias_fp[(size_t)limb * p->m_pad + i] = (double)(u64)r;
+                }
+            }
+            e4 = upload(&p->d_bias_fp, bias_fp);
+        }
     }
-    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) {
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess || e4 != hipSuccess) {
         free_plan(p);
         ENSI_FAIL(ctx, ENSI_E_NOMEM, "uploading the matmul plan failed");
     }
@@ -310,7 +326,7 @@ static int matmul_run(ensi_ctx *ctx, const ensi_gk *gk, const ensi_ct *in, Matmu
     // ---- Alg. 1: signed sums
     const bool use_mfma = plan->planes > 0 && ctx->accumulate_mode != 1;
     if (use_mfma) {
-        if ((rc = launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1, in->limbs_alloc,
+        if ((rc = launch_accumulate_mfma(ctx, xbase, in_ct, n_v, plan->n_kpad, plan->d_wt, plan->d_bias, plan->d_bias_fp, plan->planes, m, l1, in->limbs_alloc,
                                          out->d, out->limbs_alloc, nullptr, st)))
             return rc;
     } else
@@ -400,7 +416,7 @@ static int rescale_matmul_run(ensi_ctx *ctx, ensi_ct *in, double kappa, MatmulPl
     const double *d_fconsts;
     const double kr = rescale_constant(ctx, l1_in, kappa);
     if ((rc = upload_rescale_consts(ctx, l1_in, kr, kappa < 0, st, &d_consts, &d_fconsts, &fp))) return rc;
-    if ((rc = launch_accumulate_mfma(ctx, in->d, (size_t)2 * in->limbs_alloc * N, d, plan->n_kpad, plan->d_wt, plan->d_bias, plan->planes, m, l1,
+    if ((rc = launch_accumulate_mfma(ctx, in->d, (size_t)2 * in->limbs_alloc * N, d, plan->n_kpad, plan->d_wt, plan->d_bias, plan->d_bias_fp, plan->planes, m, l1,
                                      in->limbs_alloc, out->d, out->limbs_alloc, d_fconsts, st)))
         return rc;
     in->limbs = l1;

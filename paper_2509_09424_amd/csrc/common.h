@@ -150,6 +150,7 @@ struct MatmulPlan {
     u32 *d_masks = nullptr;      // [tiles32][n_v][2] (+1 bits, -1 bits)
     int8_t *d_wt = nullptr;      // [m_pad][n_kpad] weights, operand index fastest
     int32_t *d_bias = nullptr;   // [m_pad] 128 * column sum of the weights
+    double *d_bias_fp = nullptr; // [l1][m_pad] that offset times sum_p 256^p, reduced modulo each limb's prime (all primes below 2^50), else null
 };
 
 struct KernelTimer {
@@ -322,6 +323,7 @@ void launch_rescale(ensi_ctx *ctx, u64 *ct, int n_ct, int l1, int limb_stride, c
 // multiple of 256.  Grows ctx->ws_xp (byte planes of a slice of the operand words); returns an ENSI_E_* code.
 // d_rescale != nullptr: operands are read at l1 + 1 limbs and multiplied/rescaled on the fly (fp64 constants [5][l1+1]).
 int launch_accumulate_mfma(ensi_ctx *ctx, const u64 *xbase, size_t xstride, int n_v, int n_kpad, const int8_t *d_wt, const int32_t *d_bias,
+                           const double *d_bias_fp,
                            int planes, int m, int l1, int limb_stride_in, u64 *out, int limb_stride_out, const double *d_rescale,
                            hipStream_t st);
 // sustained int8 matrix-instruction rate over the whole chip, measured for about `seconds`
