@@ -60,8 +60,8 @@ def to_oracle_cts(arr, scale):
 
 
 def note(msg):
-    """Progress line of a long test: straight to the terminal (past pytest's capture) and, where the folder
-    exists, appended to gpurun_out/progress.log."""
+    """Progress line of a long test: straight to the terminal (past pytest's capture) and, when the environment
+    names a file in ENSI_PROGRESS_LOG, appended to it."""
     import os
     import sys
     import time
@@ -70,11 +70,13 @@ def note(msg):
         os.write(sys.__stderr__.fileno() if sys.__stderr__ is not None else 2, line.encode())
     except OSError:
         pass
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    out = os.path.join(root, "gpurun_out")
-    if os.path.isdir(out):
-        with open(os.path.join(out, "progress.log"), "a") as f:
-            f.write(line)
+    path = os.environ.get("ENSI_PROGRESS_LOG")
+    if path:
+        try:
+            with open(path, "a") as f:
+                f.write(line)
+        except OSError:
+            pass
 
 
 def oracle_columns(o, o_sk, o_cts, s, jobs, error_of_step, seed_a, block=32, tell=None):
