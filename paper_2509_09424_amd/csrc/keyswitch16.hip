@@ -222,6 +222,7 @@ template <bool FP>
 __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
                                                                  u64 *u, LimbList limbs, int members) {
     __shared__ u64 lds[(FP ? 1 : 2) * (4096 + 256)];
+    __shared__ ulonglong2 tw1[FP ? 16 * 16 : 1];
     const int tid = threadIdx.x, rho = tid >> 4, j16 = tid & 15;
     const int rot = blockIdx.y, e = limbs.e[blockIdx.z];
     const int l1 = kc.l1, ext = l1 + kc.K, ext_full = kc.L + kc.K, beta = kc.beta;
@@ -280,17 +281,29 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
             }
         }
         }
+        // Inverse row pass of both sums.  Its twiddles are fetched once for the two polynomials: the 15 pairs of the
+        // second step (per row) into LDS, the 15 pairs of the first step (per thread) into registers.
         double *l = (double *)lds;
         double v[16];
+        row_table_to_lds(tw1, tw, tw + KS_N, 256u + (u32)(r0 + rho), rho, j16);
+        TwRegs tw2;
+        tw2.load(tw, tw + KS_N, (256u + (u32)(r0 + rho)) * 16u + j16);
+        const ulonglong2 *tab = tw1 + rho * 16;
 #pragma unroll
         for (int poly = 0; poly < 2; poly++) {
             if (poly) __syncthreads();
 #pragma unroll
             for (int i = 0; i < 16; i++) l[rpad(tid + 256 * i)] = ar.mid(poly ? a1[i] : a0[i]);
-            __syncthreads();
+            __syncthreads();  // (also makes tw1 visible)
 #pragma unroll
             for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + 16 * j16 + i)];
-            rows_inv_regs(ar, v, tw, tw + KS_N, lds, rho, j16, (u32)(r0 + rho));
+            gs4_tab(ar, v, tw2);
+#pragma unroll
+            for (int i = 0; i < 16; i++) l[rpad(rho * 256 + 16 * j16 + i)] = ar.mid(v[i]);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = l[rpad(rho * 256 + j16 + 16 * i)];
+            gs4_tab(ar, v, tab);
             u64 *o = uo + (size_t)poly * ext * KS_N + rho * 256 + j16;
 #pragma unroll
             for (int i = 0; i < 16; i++) o[16 * i] = as_u64(ar.mid(v[i]));
