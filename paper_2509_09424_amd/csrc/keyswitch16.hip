@@ -222,7 +222,7 @@ template <bool FP>
 __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
                                                                  u64 *u, LimbList limbs, int members) {
     __shared__ u64 lds[(FP ? 1 : 2) * (4096 + 256)];
-    __shared__ ulonglong2 tw1[FP ? 16 * 16 : 1];
+    __shared__ ulonglong2 tw1[16 * 16];
     const int tid = threadIdx.x, rho = tid >> 4, j16 = tid & 15;
     const int rot = blockIdx.y, e = limbs.e[blockIdx.z];
     const int l1 = kc.l1, ext = l1 + kc.K, ext_full = kc.L + kc.K, beta = kc.beta;
@@ -362,6 +362,10 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
                 lds1[rpad(tid + 256 * (h + i))] = t1[i];
             }
         }
+        row_table_to_lds(tw1, tw, tw + KS_N, 256u + (u32)(r0 + rho), rho, j16);
+        TwRegs tw2;
+        tw2.load(tw, tw + KS_N, (256u + (u32)(r0 + rho)) * 16u + j16);
+        const ulonglong2 *tab = tw1 + rho * 16;
         __syncthreads();
         u64 v[16];
 #pragma unroll 1
@@ -369,7 +373,13 @@ __global__ __launch_bounds__(KS_THREADS, FP ? 3 : 2) void k_ks16_inner_irows(Ks1
             u64 *lp = poly ? lds1 : lds;
 #pragma unroll
             for (int i = 0; i < 16; i++) v[i] = lp[rpad(rho * 256 + 16 * j16 + i)];
-            rows_inv_regs(ar, v, tw, tw + KS_N, lp, rho, j16, (u32)(r0 + rho));
+            gs4_tab(ar, v, tw2);
+#pragma unroll
+            for (int i = 0; i < 16; i++) lp[rpad(rho * 256 + 16 * j16 + i)] = v[i];
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 16; i++) v[i] = lp[rpad(rho * 256 + j16 + 16 * i)];
+            gs4_tab(ar, v, tab);
             u64 *o = uo + (size_t)poly * ext * KS_N + rho * 256 + j16;
 #pragma unroll
             for (int i = 0; i < 16; i++) o[16 * i] = ar.store_inv(v[i]);
@@ -436,6 +446,7 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_special(Ks16Const kc,
 __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, const RotDesc *desc, const PrimeConst *pcs, const u64 *tw_all,
                                                                 const u64 *u, const u64 *ysp, int limb_stride_out, int members) {
     __shared__ u64 lds[4096];
+    __shared__ ulonglong2 ctab[COL_TAB_PAIRS];
     const int tid = threadIdx.x, c = tid & 15, jj = tid >> 4;
     const int limb = blockIdx.x, poly = blockIdx.y >> 4, rot = blockIdx.z;
     const int l1 = kc.l1, K = kc.K, ext = l1 + K;
@@ -449,9 +460,11 @@ __global__ __launch_bounds__(KS_THREADS) void k_ks16_icols_down(Ks16Const kc, co
     ArithFp ar;
     ar.init(pc);
     double v[16];
+    col_tables_to_lds(ctab, tw, tw + KS_N, tid);
 #pragma unroll
     for (int i = 0; i < 16; i++) v[i] = as_f64(src[(size_t)(16 * jj + i) * 256]);
-    cols_inv_regs(ar, v, tw, tw + KS_N, lds, c, jj);
+    __syncthreads();
+    cols_inv_regs_t(ar, v, ctab, lds, c, jj);
     const double *dq = kc.down_q + (size_t)limb * (2 + 4 * K);
     const double sc = dq[0], sc_p = dq[1];
 #pragma unroll

@@ -216,6 +216,46 @@ __device__ __forceinline__ void cols_inv_regs(const A &ar, typename A::T *v, con
     gs4(ar, v, tw, tws, 1u);
 }
 
+// The same two passes with their twiddles in LDS.  A column tile uses 15 pairs that are the same for every thread
+// (first forward step, base index 1) and 15 pairs per thread row jj (base index 16 + jj); read straight from the
+// table in memory they are 60 loads per thread for 16 values.  col_tables_to_lds puts them into tab (COL_TAB_PAIRS
+// entries: slot 0 = base 1, slot 1 + jj = base 16 + jj, 16 entries per slot of which 15 are used); the caller
+// synchronises between the fill and the first use.
+#define COL_TAB_PAIRS (17 * 16)
+__device__ __forceinline__ void col_tables_to_lds(ulonglong2 *tab, const u64 *tw, const u64 *tws, int tid) {
+    for (int t = tid; t < COL_TAB_PAIRS; t += 256) {
+        const int slot = t >> 4, ent = t & 15;
+        if (ent < 15) {
+            const int k = 31 - __clz(ent + 1), g = ent + 1 - (1 << k);
+            const u32 mbase = slot == 0 ? 1u : 16u + (u32)(slot - 1);
+            const u32 idx = (mbase << k) + g;
+            tab[t] = make_ulonglong2(tw[idx], tws[idx]);
+        }
+    }
+}
+template <class A>
+__device__ __forceinline__ void cols_fwd_regs_t(const A &ar, typename A::T *v, const ulonglong2 *tab, void *lds, int c, int jj) {
+    typename A::T *l = (typename A::T *)lds;
+    ct4_tab(ar, v, tab);
+#pragma unroll
+    for (int i = 0; i < 16; i++) l[(jj + 16 * i) * 16 + c] = ar.mid(v[i]);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = l[(16 * jj + i) * 16 + c];
+    ct4_tab(ar, v, tab + 16 * (1 + jj));
+}
+template <class A>
+__device__ __forceinline__ void cols_inv_regs_t(const A &ar, typename A::T *v, const ulonglong2 *tab, void *lds, int c, int jj) {
+    typename A::T *l = (typename A::T *)lds;
+    gs4_tab(ar, v, tab + 16 * (1 + jj));
+#pragma unroll
+    for (int i = 0; i < 16; i++) l[(16 * jj + i) * 16 + c] = ar.mid(v[i]);
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; i++) v[i] = l[(jj + 16 * i) * 16 + c];
+    gs4_tab(ar, v, tab);
+}
+
 // Row pass, thread (rho = tid / 16, j = tid % 16) of a 256-thread block working on 16 whole
 // rows r0 .. r0+15 (r = r0 + rho); lds holds 4096 + 256 words (one pad word per 16).
 //   forward: on entry v[i] = element j + 16 i of row rho, on exit v[i] = element 16 j + i.
